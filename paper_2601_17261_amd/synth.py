@@ -1,0 +1,120 @@
+"""Seeded synthetic inputs shaped like the paper's workloads.
+
+This module only *makes inputs* (weights, activations, targets) and holds none
+of the method's arithmetic; both the CPU oracle's tests and the HIP path's
+tests draw their inputs from here, so the two sides see identical numbers.
+
+The paper fine-tunes Qwen3 / Pangu models on public NLP datasets
+(App. B.1-B.2); neither weights nor data are used here.  What is kept is the
+layer shapes and the spectral character the paper reports for activations
+(Sec. 3.2, Fig. 1c: fast singular-value decay, a few dominant directions).
+
+All functions return float32 numpy arrays whose values are exactly
+representable in the stated storage type (fp32, or bf16 after rounding).
+"""
+import numpy as np
+import torch
+
+QWEN3_0P6B_LAYER = [("q", 1024, 2048), ("k", 1024, 1024), ("v", 1024, 1024), ("o", 2048, 1024),
+                    ("gate", 1024, 3072), ("up", 1024, 3072), ("down", 3072, 1024)]
+QWEN3_8B_LAYER = [("q", 4096, 4096), ("k", 4096, 1024), ("v", 4096, 1024), ("o", 4096, 4096),
+                  ("gate", 4096, 12288), ("up", 4096, 12288), ("down", 12288, 4096)]
+QWEN3_4B_LAYER = [("q", 2560, 4096), ("k", 2560, 1024), ("v", 2560, 1024), ("o", 4096, 2560),
+                  ("gate", 2560, 9728), ("up", 2560, 9728), ("down", 9728, 2560)]
+
+
+def to_bf16_values(a):
+    """Round a float array to bfloat16 (nearest even) and return it as float32."""
+    t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32))
+    return t.to(torch.bfloat16).to(torch.float32).numpy()
+
+
+def _store(a, storage):
+    a = np.asarray(a, dtype=np.float32)
+    return to_bf16_values(a) if storage == "bf16" else a
+
+
+def weights(rng, d_out, d_in, std=0.02, storage="f32"):
+    return _store(rng.standard_normal((d_out, d_in)) * std, storage)
+
+
+def shifted_target(rng, X, W, rank=4, std=0.05, storage="f32"):
+    """MSE target Y* = X W*^T with W* = W + rank-`rank` shift whose entries have std `std`."""
+    d_out, d_in = W.shape
+    P = rng.standard_normal((d_out, rank))
+    Q = rng.standard_normal((d_in, rank))
+    Wstar = W.astype(np.float64) + (std / np.sqrt(rank)) * (P @ Q.T)
+    Y = X.astype(np.float64) @ Wstar.T
+    return _store(Y, storage)
+
+
+def x_lowrank_plus_noise(rng, n, d, rank=16, s_hi=10.0, s_lo=0.1, noise=0.01, storage="f32"):
+    """Planted spectrum: U diag(S) V^T + noise, S log-spaced s_hi..s_lo (the small fp32 config)."""
+    U, _ = np.linalg.qr(rng.standard_normal((n, rank)))
+    V, _ = np.linalg.qr(rng.standard_normal((d, rank)))
+    S = np.logspace(np.log10(s_hi), np.log10(s_lo), rank)
+    X = (U * S[None, :]) @ V.T + noise * rng.standard_normal((n, d))
+    return _store(X, storage)
+
+
+def x_rmsnorm_gaussian(rng, n, d, storage="bf16"):
+    """iid N(0,1) rows scaled to unit RMS per token (input of a projection after RMSNorm)."""
+    X = rng.standard_normal((n, d))
+    X /= np.sqrt(np.mean(X * X, axis=1, keepdims=True))
+    return _store(X, storage)
+
+
+def x_powerlaw_outliers(rng, n, d, n_outliers=5, outlier_scale=20.0, storage="bf16"):
+    """Power-law activation spectrum (singular values ~ 1/i) in a random rotation,
+    a few outlier channels scaled up, global unit RMS.  Used for the Qwen3-8B/4B
+    shaped layers."""
+    Zm = rng.standard_normal((n, d)) / np.sqrt(n)
+    Zm *= (1.0 / np.arange(1, d + 1))[None, :]
+    V, _ = np.linalg.qr(rng.standard_normal((d, d)))
+    X = Zm @ V.T
+    ch = rng.choice(d, size=min(n_outliers, d), replace=False)
+    X[:, ch] *= outlier_scale
+    X /= np.sqrt(np.mean(X * X))
+    return _store(X, storage)
+
+
+def single_layer_problem(seed, n, d_in, d_out, kind="lowrank", storage="f32", target_storage="f32"):
+    """(W, X, Y*) for one projection with an MSE loss to a shifted-weights target."""
+    rng = np.random.default_rng(seed)
+    W = weights(rng, d_out, d_in, storage=storage)
+    if kind == "lowrank":
+        X = x_lowrank_plus_noise(rng, n, d_in, rank=min(16, d_in, n), storage=storage)
+    elif kind == "rmsnorm":
+        X = x_rmsnorm_gaussian(rng, n, d_in, storage=storage)
+    elif kind == "powerlaw":
+        X = x_powerlaw_outliers(rng, n, d_in, storage=storage)
+    else:
+        raise ValueError(kind)
+    Ystar = shifted_target(rng, X, W, storage=target_storage)
+    return W, X, Ystar
+
+
+# ----------------------------------------------------------------------------
+# full-size inputs generated on the device (outside any timed region)
+# ----------------------------------------------------------------------------
+def device_powerlaw_problem(seed, n, d_in, d_out, device="cuda", n_outliers=5, outlier_scale=20.0):
+    """bf16 (W, X) and fp32 Y* on the device for a Qwen3-shaped projection; same recipe
+    as x_powerlaw_outliers / shifted_target, drawn from torch's seeded generator."""
+    gen = torch.Generator(device=device)
+    gen.manual_seed(int(seed))
+    f32 = dict(device=device, dtype=torch.float32, generator=gen)
+    W = (torch.randn(d_out, d_in, **f32) * 0.02).to(torch.bfloat16)
+    Zm = torch.randn(n, d_in, **f32) / float(np.sqrt(n))
+    Zm *= (1.0 / torch.arange(1, d_in + 1, device=device, dtype=torch.float32))[None, :]
+    V, _ = torch.linalg.qr(torch.randn(d_in, d_in, **f32))
+    X = Zm @ V.T
+    del Zm, V
+    ch = torch.randperm(d_in, device=device, generator=gen)[:n_outliers]
+    X[:, ch] *= outlier_scale
+    X /= X.square().mean().sqrt()
+    X = X.to(torch.bfloat16)
+    P = torch.randn(d_out, 4, **f32)
+    Q = torch.randn(d_in, 4, **f32)
+    Wstar = W.float() + (0.05 / 2.0) * (P @ Q.T)
+    Ystar = X.float() @ Wstar.T
+    return W, X, Ystar
