@@ -1,0 +1,131 @@
+/*
+ * agzo.h - C ABI of the MI355X (gfx950) AGZO hot-path library.
+ *
+ * One AGZO step for a linear layer (paper Sec. 4.1, Alg. 1, Alg. 2):
+ *   sketch the mini-batch activations, orthonormalise to a rank-r basis B,
+ *   regenerate the seeded Gaussian factor G, evaluate the loss at
+ *   W + eps*G*B^T and W - eps*G*B^T without touching W, form the two-point
+ *   scalar g, and apply W -= lr*g*G*B^T in place.
+ *
+ * Conventions
+ *   - Every tensor pointer is DEVICE memory owned by the caller; the library
+ *     borrows it until the work enqueued by the call has finished.  Pointers
+ *     named *_dev are device scalars/arrays too.  The only host pointers are
+ *     the small descriptor structs and the ctx.
+ *   - All matrices are row-major.  W is [d_out][d_in] (y = W h, batched
+ *     Y = X W^T, Sec. 3.1), X is [n_tokens][d_in] (one token per row: the
+ *     transpose of the paper's H), Y is [n_tokens][d_out], the basis B, the
+ *     sketches S and the start/iterate Q are [d_in][r] fp32 with leading
+ *     dimension r, the projection P is [n_tokens][r] fp32.
+ *   - Leading dimensions (ldw, ldx, ldy, ldt) are in elements; for bf16
+ *     operands ldw, ldx and d_in must be multiples of 8 (16-byte rows).
+ *   - Calls only enqueue work on the ctx stream (no host synchronisation)
+ *     unless stated.  Calls on one ctx must not overlap from several threads.
+ *   - Return value: 0 on success, a negative agzo_status otherwise; the text
+ *     of the last error is available from agzo_last_error().
+ */
+#ifndef AGZO_H
+#define AGZO_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct agzo_ctx agzo_ctx;
+
+typedef enum {
+    AGZO_OK = 0,
+    AGZO_EINVAL = -1,   /* null pointer, r < 1, r > 64, r > min(n_tokens, d_in), bad dtype, bad alignment */
+    AGZO_ENOMEM = -2,   /* workspace allocation failed */
+    AGZO_ENUMERIC = -3, /* Cholesky pivot <= 0: the sketch is rank deficient (reported by agzo_check) */
+    AGZO_EHIP = -4      /* HIP runtime error */
+} agzo_status;
+
+typedef enum { AGZO_F32 = 0, AGZO_BF16 = 1 } agzo_dtype;
+typedef enum { AGZO_LOSS_NONE = 0, AGZO_LOSS_MSE = 1, AGZO_LOSS_CE = 2 } agzo_loss_kind;
+typedef enum {
+    AGZO_SKETCH_NONE = 0,
+    AGZO_SKETCH_RANGE = 1, /* S = X^T Omega, Omega [n_tokens][r] Gaussian from (seed, tag 1): Alg. 1, first product */
+    AGZO_SKETCH_POWER = 2  /* S = X^T (X Q) for a given Q [d_in][r]: Alg. 1, power step */
+} agzo_sketch;
+
+/* Philox stream tags: which Gaussian matrix a (seed, tag, row, col) element belongs to. */
+enum { AGZO_TAG_G = 0, AGZO_TAG_OMEGA = 1, AGZO_TAG_Q0 = 2, AGZO_TAG_DENSE = 3 };
+
+/* agzo_step / agzo_basis flags */
+enum {
+    AGZO_ONE_SIDED = 1,    /* g = (L+ - L0)/eps, the literal form of Eq. 10 / Alg. 2; default is (L+ - L-)/(2 eps) */
+    AGZO_NAIVE_INPLACE = 2,/* comparator: perturb W in place, plain forward, undo (Alg. 2's literal schedule) */
+    AGZO_INIT_FEATURE = 4  /* start Alg. 1 from a Gaussian Q0 [d_in][r] (tag 2) instead of a token-space Omega */
+};
+
+typedef struct {
+    int64_t n_tokens;  /* N = batch x sequence (the paper's m) */
+    int64_t d_in;
+    int64_t d_out;
+    int32_t r;         /* rank of the activation basis, 1..64 */
+    int32_t dtype;     /* agzo_dtype of W and X (both the same) */
+    int32_t y_dtype;   /* agzo_dtype of Y when stored: F32, or BF16 for bf16 layers */
+    int32_t reserved;
+    int64_t ldw, ldx, ldy;
+} agzo_layer;
+
+typedef struct {
+    int32_t kind;         /* agzo_loss_kind */
+    int32_t target_dtype; /* MSE: AGZO_F32 or AGZO_BF16 target values; ignored for CE */
+    const void* target;   /* MSE: Y* [n_tokens][d_out], ld = ldt.  CE: int32 ids [n_tokens], < 0 = ignored row */
+    int64_t ldt;
+} agzo_loss_spec;
+
+/* Create a context that enqueues on hip_stream (a hipStream_t, borrowed; NULL = default stream)
+ * of the current device.  The ctx owns a workspace that grows on demand (growth synchronises). */
+int agzo_create(agzo_ctx** out, void* hip_stream);
+void agzo_destroy(agzo_ctx* ctx);
+const char* agzo_last_error(const agzo_ctx* ctx);
+/* Synchronise the stream and report a deferred numeric failure (AGZO_ENUMERIC) if any; clears it. */
+int agzo_check(agzo_ctx* ctx);
+
+/* Generator (Alg. 2 "generate R from seed"; this build: Philox4x32-10 + Box-Muller).
+ * words: uint32 [rows][cols], word (row, col) = word col%4 of Philox(counter (row, col/4, tag, 0),
+ * key (seed lo, seed hi)).  normal: fp32 [rows][cols] from the same words, u = ((x>>9)+0.5)*2^-23,
+ * (z0,z1) = sqrt(-2 ln u0) (cos, sin)(2 pi u1), (z2,z3) likewise. */
+int agzo_philox_words(agzo_ctx* ctx, uint32_t* dst, int64_t rows, int32_t cols, uint64_t seed, uint32_t tag);
+int agzo_fill_normal(agzo_ctx* ctx, float* dst, int64_t rows, int32_t cols, uint64_t seed, uint32_t tag);
+
+/* Base forward (f0 of Sec. 4.1) with sketch emission (Alg. 1 products):
+ *   Y = X W^T (stored if Y != NULL), loss -> *loss_dev (if loss && loss_dev),
+ *   S = X^T Omega (RANGE) or X^T (X Q) (POWER) -> S [d_in][r].
+ * W may be NULL together with Y == NULL and no loss: sketch only. */
+int agzo_layer_forward_sketch(agzo_ctx* ctx, const agzo_layer* L, const void* W, const void* X, void* Y,
+                              int32_t mode, const float* Q, uint64_t seed, float* S,
+                              const agzo_loss_spec* loss, double* loss_dev);
+
+/* Thin QR with positive diagonal of a tall fp32 matrix S [d_in][r] -> Q [d_in][r]
+ * (the "qr" steps of Alg. 1; CholeskyQR2 with fp64 Gram and Cholesky). */
+int agzo_qr(agzo_ctx* ctx, const float* S, int64_t d_in, int32_t r, float* Q);
+
+/* Alg. 1 SubspaceExtract: B = orthonormal basis after K power steps.  S0, if not NULL, is the
+ * first sketch already produced by agzo_layer_forward_sketch(RANGE) with the same seed. */
+int agzo_basis(agzo_ctx* ctx, const agzo_layer* L, const void* X, int32_t K, uint64_t seed,
+               const float* S0, int32_t flags, float* B);
+
+/* Perturbed forward (f+ / f- of Sec. 4.1, Eq. 7): Y = X W^T + eps_signed (X B) G^T with G [d_out][r]
+ * regenerated from (seed, tag 0); W is not modified.  Loss as above. */
+int agzo_perturbed_forward(agzo_ctx* ctx, const agzo_layer* L, const void* W, const void* X,
+                           const float* B, uint64_t seed, float eps_signed, void* Y,
+                           const agzo_loss_spec* loss, double* loss_dev);
+
+/* In-place rank-r sweep (Alg. 2, restore/update line): W -= lr * g * G B^T, g = *g_dev (1 if NULL). */
+int agzo_update(agzo_ctx* ctx, const agzo_layer* L, void* W, const float* B, uint64_t seed,
+                float lr, const double* g_dev);
+
+/* One whole AGZO step for one layer (Alg. 2).  out_dev[4] = {L0, L+, L-, g} (device doubles). */
+int agzo_step(agzo_ctx* ctx, const agzo_layer* L, void* W, const void* X, const agzo_loss_spec* loss,
+              int32_t K, float eps, float lr, uint64_t seed, int32_t flags, double* out_dev);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AGZO_H */

@@ -1,0 +1,184 @@
+"""Thin ctypes binding of libagzo.so: argument marshalling only.
+
+Function names and argument order are those of include/agzo.h.  Tensors are
+torch tensors on the GPU (torch is used for device memory and streams only);
+nothing is computed here, and there is no fallback: if the HIP library is not
+built, importing the entry points raises.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libagzo.so")
+
+F32, BF16 = 0, 1
+LOSS_NONE, LOSS_MSE, LOSS_CE = 0, 1, 2
+SKETCH_NONE, SKETCH_RANGE, SKETCH_POWER = 0, 1, 2
+TAG_G, TAG_OMEGA, TAG_Q0, TAG_DENSE = 0, 1, 2, 3
+ONE_SIDED, NAIVE_INPLACE, INIT_FEATURE = 1, 2, 4
+OK, EINVAL, ENOMEM, ENUMERIC, EHIP = 0, -1, -2, -3, -4
+
+EXPORTS = ["agzo_create", "agzo_destroy", "agzo_last_error", "agzo_check", "agzo_philox_words", "agzo_fill_normal",
+           "agzo_layer_forward_sketch", "agzo_qr", "agzo_basis", "agzo_perturbed_forward", "agzo_update", "agzo_step"]
+
+
+class AgzoLayer(ctypes.Structure):
+    _fields_ = [("n_tokens", ctypes.c_int64), ("d_in", ctypes.c_int64), ("d_out", ctypes.c_int64),
+                ("r", ctypes.c_int32), ("dtype", ctypes.c_int32), ("y_dtype", ctypes.c_int32),
+                ("reserved", ctypes.c_int32), ("ldw", ctypes.c_int64), ("ldx", ctypes.c_int64),
+                ("ldy", ctypes.c_int64)]
+
+
+class AgzoLossSpec(ctypes.Structure):
+    _fields_ = [("kind", ctypes.c_int32), ("target_dtype", ctypes.c_int32), ("target", ctypes.c_void_p),
+                ("ldt", ctypes.c_int64)]
+
+
+class AgzoError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__("agzo error %d: %s" % (code, msg))
+        self.code = code
+
+
+_lib = None
+
+
+def load():
+    """Load the built library (raises if it has not been built)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError("libagzo.so is not built: run `python -m paper_2601_17261_amd.build` "
+                          "(there is no CPU fallback for the HIP path)")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32, i64, u32, u64, f32 = (ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_uint32,
+                                   ctypes.c_uint64, ctypes.c_float)
+    lp, sp = ctypes.POINTER(AgzoLayer), ctypes.POINTER(AgzoLossSpec)
+    lib.agzo_create.argtypes = [ctypes.POINTER(vp), vp]
+    lib.agzo_destroy.argtypes = [vp]
+    lib.agzo_destroy.restype = None
+    lib.agzo_last_error.argtypes = [vp]
+    lib.agzo_last_error.restype = ctypes.c_char_p
+    lib.agzo_check.argtypes = [vp]
+    lib.agzo_philox_words.argtypes = [vp, vp, i64, i32, u64, u32]
+    lib.agzo_fill_normal.argtypes = [vp, vp, i64, i32, u64, u32]
+    lib.agzo_layer_forward_sketch.argtypes = [vp, lp, vp, vp, vp, i32, vp, u64, vp, sp, vp]
+    lib.agzo_qr.argtypes = [vp, vp, i64, i32, vp]
+    lib.agzo_basis.argtypes = [vp, lp, vp, i32, u64, vp, i32, vp]
+    lib.agzo_perturbed_forward.argtypes = [vp, lp, vp, vp, vp, u64, f32, vp, sp, vp]
+    lib.agzo_update.argtypes = [vp, lp, vp, vp, u64, f32, vp]
+    lib.agzo_step.argtypes = [vp, lp, vp, vp, sp, i32, f32, f32, u64, i32, vp]
+    for name in EXPORTS:
+        if name not in ("agzo_destroy", "agzo_last_error"):
+            getattr(lib, name).restype = ctypes.c_int
+    _lib = lib
+    return lib
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _dt(t):
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError("unsupported dtype %s" % t.dtype)
+
+
+def make_layer(W=None, X=None, r=1, Y=None, d_out=None):
+    """Descriptor for row-major 2-D tensors W [d_out][d_in], X [n][d_in], optional Y [n][d_out]."""
+    L = AgzoLayer()
+    L.n_tokens, L.d_in = X.shape
+    L.d_out = W.shape[0] if W is not None else (d_out or 0)
+    L.r = r
+    L.dtype = _dt(X)
+    L.y_dtype = _dt(Y) if Y is not None else F32
+    L.ldx = X.stride(0)
+    L.ldw = W.stride(0) if W is not None else L.d_in
+    L.ldy = Y.stride(0) if Y is not None else L.d_out
+    return L
+
+
+def make_loss(target=None, kind=LOSS_MSE):
+    s = AgzoLossSpec()
+    if target is None:
+        s.kind = LOSS_NONE
+        return s
+    s.kind = kind
+    s.target = target.data_ptr()
+    if kind == LOSS_MSE:
+        s.target_dtype = _dt(target)
+        s.ldt = target.stride(0)
+    return s
+
+
+class Context:
+    """Owns an agzo_ctx bound to a torch stream (default: the current one)."""
+
+    def __init__(self, stream=None):
+        self.lib = load()
+        if not torch.cuda.is_available():
+            raise RuntimeError("the AGZO HIP path needs a GPU")
+        self.stream = stream if stream is not None else torch.cuda.current_stream()
+        h = ctypes.c_void_p()
+        rc = self.lib.agzo_create(ctypes.byref(h), ctypes.c_void_p(self.stream.cuda_stream))
+        if rc != 0:
+            raise AgzoError(rc, "agzo_create failed")
+        self.h = h
+
+    def close(self):
+        if getattr(self, "h", None):
+            self.lib.agzo_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _rc(self, rc):
+        if rc != 0:
+            raise AgzoError(rc, self.lib.agzo_last_error(self.h).decode())
+
+    # --- one method per C entry point, same name without the prefix -------------------------
+    def check(self):
+        self._rc(self.lib.agzo_check(self.h))
+
+    def philox_words(self, dst, seed, tag):
+        rows, cols = dst.shape
+        self._rc(self.lib.agzo_philox_words(self.h, _ptr(dst), rows, cols, seed, tag))
+
+    def fill_normal(self, dst, seed, tag):
+        rows, cols = dst.shape
+        self._rc(self.lib.agzo_fill_normal(self.h, _ptr(dst), rows, cols, seed, tag))
+
+    def layer_forward_sketch(self, L, W, X, Y, mode, Q, seed, S, loss, loss_dev):
+        self._rc(self.lib.agzo_layer_forward_sketch(self.h, ctypes.byref(L), _ptr(W), _ptr(X), _ptr(Y), mode,
+                                                    _ptr(Q), seed, _ptr(S),
+                                                    ctypes.byref(loss) if loss is not None else None,
+                                                    _ptr(loss_dev)))
+
+    def qr(self, S, Q):
+        d, r = S.shape
+        self._rc(self.lib.agzo_qr(self.h, _ptr(S), d, r, _ptr(Q)))
+
+    def basis(self, L, X, K, seed, S0, flags, B):
+        self._rc(self.lib.agzo_basis(self.h, ctypes.byref(L), _ptr(X), K, seed, _ptr(S0), flags, _ptr(B)))
+
+    def perturbed_forward(self, L, W, X, B, seed, eps_signed, Y, loss, loss_dev):
+        self._rc(self.lib.agzo_perturbed_forward(self.h, ctypes.byref(L), _ptr(W), _ptr(X), _ptr(B), seed,
+                                                 eps_signed, _ptr(Y),
+                                                 ctypes.byref(loss) if loss is not None else None, _ptr(loss_dev)))
+
+    def update(self, L, W, B, seed, lr, g_dev):
+        self._rc(self.lib.agzo_update(self.h, ctypes.byref(L), _ptr(W), _ptr(B), seed, lr, _ptr(g_dev)))
+
+    def step(self, L, W, X, loss, K, eps, lr, seed, flags, out_dev):
+        self._rc(self.lib.agzo_step(self.h, ctypes.byref(L), _ptr(W), _ptr(X), ctypes.byref(loss), K, eps, lr,
+                                    seed, flags, _ptr(out_dev)))

@@ -1,0 +1,414 @@
+// C ABI of libagzo: argument checks, workspace carving and the stream-ordered sequence of kernel
+// launches that makes up one AGZO step (Alg. 2) for a linear layer.  No arithmetic lives here.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+
+#include "agzo_internal.h"
+
+using namespace agzo;
+
+struct agzo_ctx {
+    hipStream_t stream;
+    char err[512];
+    char* ws;
+    size_t ws_bytes;
+    int* flag;   // device int: deferred numeric failure
+};
+
+namespace {
+
+int fail(agzo_ctx* c, int code, const char* fmt, ...) {
+    if (c) {
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(c->err, sizeof(c->err), fmt, ap);
+        va_end(ap);
+    }
+    return code;
+}
+
+#define HIPCHK(expr)                                                                              \
+    do {                                                                                          \
+        hipError_t e__ = (expr);                                                                  \
+        if (e__ != hipSuccess) return fail(ctx, AGZO_EHIP, "%s: %s", #expr, hipGetErrorString(e__)); \
+    } while (0)
+#define TRY(expr)              \
+    do {                       \
+        int rc__ = (expr);     \
+        if (rc__ != 0) return rc__; \
+    } while (0)
+
+inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
+inline int round16(int r) { return (r + 15) / 16 * 16; }
+inline int64_t round32(int64_t n) { return (n + 31) / 32 * 32; }
+
+// carve-out of the ctx workspace for one layer; everything a step can need at the same time
+struct Plan {
+    size_t off_S, off_Q, off_B, off_pack, off_T, off_TpackT, off_xtt, off_qr, off_part, off_Ybuf, total;
+    int rp, nsplit;
+    int64_t m_pad;
+    int n_part;
+};
+
+Plan make_plan(const agzo_layer& L, bool need_ybuf) {
+    Plan p;
+    const bool bf = (L.dtype == AGZO_BF16);
+    p.rp = round16(L.r);
+    p.m_pad = round32(L.n_tokens);
+    p.nsplit = bf ? xtt_num_splits(L.n_tokens, L.d_in) : 1;
+    const int n_gemm = bf ? gemm_bf16_num_workgroups(L.n_tokens, L.d_out) : epilogue_f32_num_workgroups(L.n_tokens, L.d_out);
+    p.n_part = n_gemm;
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o += align_up(bytes); return at; };
+    p.off_S = take((size_t)L.d_in * L.r * 4);
+    p.off_Q = take((size_t)L.d_in * L.r * 4);
+    p.off_B = take((size_t)L.d_in * L.r * 4);
+    p.off_pack = take(bf ? (size_t)3 * p.rp * L.d_in * 2 : 0);
+    p.off_T = take((size_t)L.n_tokens * L.r * 4);
+    p.off_TpackT = take(bf ? (size_t)3 * p.rp * p.m_pad * 2 : 0);
+    p.off_xtt = take(bf ? (size_t)p.nsplit * L.d_in * p.rp * 4 : 0);
+    p.off_qr = take(qr_workspace_bytes(L.d_in, L.r));
+    p.off_part = take((size_t)n_gemm * 8);
+    p.off_Ybuf = take(need_ybuf ? (size_t)L.n_tokens * L.d_out * 4 : 0);
+    p.total = o;
+    return p;
+}
+
+int reserve(agzo_ctx* ctx, size_t bytes) {
+    if (bytes <= ctx->ws_bytes) return 0;
+    HIPCHK(hipStreamSynchronize(ctx->stream));
+    if (ctx->ws) HIPCHK(hipFree(ctx->ws));
+    ctx->ws = nullptr;
+    ctx->ws_bytes = 0;
+    void* p = nullptr;
+    hipError_t e = hipMalloc(&p, bytes);
+    if (e != hipSuccess) return fail(ctx, AGZO_ENOMEM, "workspace of %zu bytes: %s", bytes, hipGetErrorString(e));
+    ctx->ws = static_cast<char*>(p);
+    ctx->ws_bytes = bytes;
+    return 0;
+}
+
+int check_layer(agzo_ctx* ctx, const agzo_layer* L, bool need_w) {
+    if (!ctx) return AGZO_EINVAL;
+    if (!L) return fail(ctx, AGZO_EINVAL, "layer descriptor is NULL");
+    if (L->n_tokens < 1 || L->d_in < 1 || (need_w && L->d_out < 1))
+        return fail(ctx, AGZO_EINVAL, "empty layer: n_tokens=%lld d_in=%lld d_out=%lld", (long long)L->n_tokens,
+                    (long long)L->d_in, (long long)L->d_out);
+    if (L->n_tokens > (1LL << 24) || L->d_in > (1LL << 24) || L->d_out > (1LL << 24))
+        return fail(ctx, AGZO_EINVAL, "dimension above 2^24");
+    if (L->r < 1 || L->r > kMaxRank) return fail(ctx, AGZO_EINVAL, "r=%d outside 1..%d", L->r, kMaxRank);
+    if (L->r > L->n_tokens || L->r > L->d_in) return fail(ctx, AGZO_EINVAL, "r=%d exceeds min(n_tokens, d_in)", L->r);
+    if (L->dtype != AGZO_F32 && L->dtype != AGZO_BF16) return fail(ctx, AGZO_EINVAL, "dtype %d", L->dtype);
+    if (L->ldx < L->d_in || (need_w && L->ldw < L->d_in)) return fail(ctx, AGZO_EINVAL, "leading dimension below d_in");
+    if (L->dtype == AGZO_BF16) {
+        if (L->d_in % 8 || L->ldx % 8 || (need_w && L->ldw % 8))
+            return fail(ctx, AGZO_EINVAL, "bf16 layers need d_in, ldx, ldw multiples of 8");
+    }
+    return 0;
+}
+
+int check_y(agzo_ctx* ctx, const agzo_layer* L, const void* Y) {
+    if (!Y) return 0;
+    if (L->ldy < L->d_out) return fail(ctx, AGZO_EINVAL, "ldy below d_out");
+    if (L->y_dtype == AGZO_F32) return 0;
+    if (L->y_dtype == AGZO_BF16 && L->dtype == AGZO_BF16) return 0;
+    return fail(ctx, AGZO_EINVAL, "y_dtype %d not supported for layer dtype %d", L->y_dtype, L->dtype);
+}
+
+int check_loss(agzo_ctx* ctx, const agzo_layer* L, const agzo_loss_spec* loss, const double* loss_dev) {
+    if (!loss || loss->kind == AGZO_LOSS_NONE) return 0;
+    if (loss->kind != AGZO_LOSS_MSE) return fail(ctx, AGZO_EINVAL, "loss kind %d not supported", loss->kind);
+    if (!loss->target || !loss_dev) return fail(ctx, AGZO_EINVAL, "loss needs a target and an output scalar");
+    if (loss->ldt < L->d_out) return fail(ctx, AGZO_EINVAL, "ldt below d_out");
+    if (loss->target_dtype != AGZO_F32 && loss->target_dtype != AGZO_BF16)
+        return fail(ctx, AGZO_EINVAL, "target dtype %d", loss->target_dtype);
+    return 0;
+}
+
+// ---- internal building blocks; all take a ready workspace plan --------------------------------
+inline float* wsf(agzo_ctx* c, size_t off) { return reinterpret_cast<float*>(c->ws + off); }
+inline bf16_t* wsh(agzo_ctx* c, size_t off) { return reinterpret_cast<bf16_t*>(c->ws + off); }
+
+// S = X^T Omega  (Alg. 1: Y <- H Omega)
+int op_sketch_range(agzo_ctx* ctx, const agzo_layer& L, const Plan& p, const void* X, uint64_t seed, float* S) {
+    hipStream_t st = ctx->stream;
+    if (L.dtype == AGZO_BF16) {
+        HIPCHK(launch_fill_normal_packT(wsh(ctx, p.off_TpackT), L.n_tokens, p.m_pad, L.r, p.rp, seed, AGZO_TAG_OMEGA, st));
+        HIPCHK(launch_xtt_bf16(static_cast<const bf16_t*>(X), L.ldx, L.n_tokens, L.d_in, wsh(ctx, p.off_TpackT), p.m_pad,
+                               p.rp, wsf(ctx, p.off_xtt), p.nsplit, st));
+        HIPCHK(launch_reduce_splits(wsf(ctx, p.off_xtt), p.nsplit, L.d_in, p.rp, L.r, S, st));
+    } else {
+        float* om = wsf(ctx, p.off_T);
+        HIPCHK(launch_fill_normal(om, L.n_tokens, L.r, seed, AGZO_TAG_OMEGA, st));
+        HIPCHK(launch_gemm_f32(static_cast<const float*>(X), 1, L.ldx, om, L.r, 1, S, L.r, L.d_in, L.r, L.n_tokens, st));
+    }
+    return 0;
+}
+
+// S = X^T (X Q)  (Alg. 1: Y <- H (H^T Q))
+int op_sketch_power(agzo_ctx* ctx, const agzo_layer& L, const Plan& p, const void* X, const float* Q, float* S) {
+    hipStream_t st = ctx->stream;
+    if (L.dtype == AGZO_BF16) {
+        HIPCHK(launch_pack_planes(Q, L.d_in, L.r, p.rp, wsh(ctx, p.off_pack), st));
+        HIPCHK(launch_xq_bf16(static_cast<const bf16_t*>(X), L.ldx, L.n_tokens, L.d_in, wsh(ctx, p.off_pack), L.r, p.rp,
+                              nullptr, wsh(ctx, p.off_TpackT), p.m_pad, st));
+        HIPCHK(launch_xtt_bf16(static_cast<const bf16_t*>(X), L.ldx, L.n_tokens, L.d_in, wsh(ctx, p.off_TpackT), p.m_pad,
+                               p.rp, wsf(ctx, p.off_xtt), p.nsplit, st));
+        HIPCHK(launch_reduce_splits(wsf(ctx, p.off_xtt), p.nsplit, L.d_in, p.rp, L.r, S, st));
+    } else {
+        const float* Xf = static_cast<const float*>(X);
+        float* T = wsf(ctx, p.off_T);
+        HIPCHK(launch_gemm_f32(Xf, L.ldx, 1, Q, L.r, 1, T, L.r, L.n_tokens, L.r, L.d_in, st));
+        HIPCHK(launch_gemm_f32(Xf, 1, L.ldx, T, L.r, 1, S, L.r, L.d_in, L.r, L.n_tokens, st));
+    }
+    return 0;
+}
+
+int op_qr(agzo_ctx* ctx, const Plan& p, const float* S, int64_t d, int r, float* Q) {
+    HIPCHK(launch_qr(S, d, r, Q, ctx->ws + p.off_qr, ctx->flag, ctx->stream));
+    return 0;
+}
+
+// P = X B  (N x r)
+int op_project(agzo_ctx* ctx, const agzo_layer& L, const Plan& p, const void* X, const float* B, float* P) {
+    hipStream_t st = ctx->stream;
+    if (L.dtype == AGZO_BF16) {
+        HIPCHK(launch_pack_planes(B, L.d_in, L.r, p.rp, wsh(ctx, p.off_pack), st));
+        HIPCHK(launch_xq_bf16(static_cast<const bf16_t*>(X), L.ldx, L.n_tokens, L.d_in, wsh(ctx, p.off_pack), L.r, p.rp, P,
+                              nullptr, p.m_pad, st));
+    } else {
+        HIPCHK(launch_gemm_f32(static_cast<const float*>(X), L.ldx, 1, B, L.r, 1, P, L.r, L.n_tokens, L.r, L.d_in, st));
+    }
+    return 0;
+}
+
+// Y = X W^T (+ eps (P) G^T), loss
+int op_forward(agzo_ctx* ctx, const agzo_layer& L, const Plan& p, const void* W, const void* X, const float* P,
+               float eps_signed, uint64_t seed, void* Y, const agzo_loss_spec* loss, double* loss_dev) {
+    hipStream_t st = ctx->stream;
+    GemmLossArgs la;
+    const bool has_loss = loss && loss->kind != AGZO_LOSS_NONE;
+    la.kind = has_loss ? loss->kind : AGZO_LOSS_NONE;
+    la.target_dtype = has_loss ? loss->target_dtype : AGZO_F32;
+    la.target = has_loss ? loss->target : nullptr;
+    la.ldt = has_loss ? loss->ldt : 0;
+    la.partials = reinterpret_cast<double*>(ctx->ws + p.off_part);
+    if (L.dtype == AGZO_BF16) {
+        GemmBf16Args a;
+        a.X = static_cast<const bf16_t*>(X); a.ldx = L.ldx;
+        a.W = static_cast<const bf16_t*>(W); a.ldw = L.ldw;
+        a.M = L.n_tokens; a.N = L.d_out; a.K = L.d_in;
+        a.Y = Y; a.y_dtype = L.y_dtype; a.ldy = L.ldy;
+        a.P = P; a.r = L.r; a.eps_signed = eps_signed; a.seed = seed;
+        a.loss = la;
+        HIPCHK(launch_gemm_bf16(a, st));
+    } else {
+        float* Yf = Y ? static_cast<float*>(Y) : wsf(ctx, p.off_Ybuf);
+        const int64_t ldy = Y ? L.ldy : L.d_out;
+        HIPCHK(launch_gemm_f32(static_cast<const float*>(X), L.ldx, 1, static_cast<const float*>(W), 1, L.ldw, Yf, ldy,
+                               L.n_tokens, L.d_out, L.d_in, st));
+        HIPCHK(launch_epilogue_f32(Yf, ldy, L.n_tokens, L.d_out, P, L.r, eps_signed, seed, la, st));
+    }
+    if (has_loss)
+        HIPCHK(launch_finish_loss(la.partials, p.n_part, 1.0 / ((double)L.n_tokens * (double)L.d_out), loss_dev, st));
+    return 0;
+}
+
+int op_basis(agzo_ctx* ctx, const agzo_layer& L, const Plan& p, const void* X, int K, uint64_t seed, const float* S0,
+             int flags, float* B) {
+    float* S = wsf(ctx, p.off_S);
+    float* Q = wsf(ctx, p.off_Q);
+    const float* cur = S0;
+    if (flags & AGZO_INIT_FEATURE) {
+        HIPCHK(launch_fill_normal(Q, L.d_in, L.r, seed, AGZO_TAG_Q0, ctx->stream));
+        TRY(op_sketch_power(ctx, L, p, X, Q, S));
+        cur = S;
+    } else if (!cur) {
+        TRY(op_sketch_range(ctx, L, p, X, seed, S));
+        cur = S;
+    }
+    for (int k = 0; k < K; ++k) {
+        TRY(op_qr(ctx, p, cur, L.d_in, L.r, Q));
+        TRY(op_sketch_power(ctx, L, p, X, Q, S));
+        cur = S;
+    }
+    TRY(op_qr(ctx, p, cur, L.d_in, L.r, B));
+    return 0;
+}
+
+}  // namespace
+
+extern "C" {
+
+int agzo_create(agzo_ctx** out, void* hip_stream) {
+    if (!out) return AGZO_EINVAL;
+    agzo_ctx* ctx = new (std::nothrow) agzo_ctx;
+    if (!ctx) return AGZO_ENOMEM;
+    ctx->stream = static_cast<hipStream_t>(hip_stream);
+    ctx->err[0] = 0;
+    ctx->ws = nullptr;
+    ctx->ws_bytes = 0;
+    ctx->flag = nullptr;
+    hipError_t e = hipMalloc(reinterpret_cast<void**>(&ctx->flag), 256);
+    if (e == hipSuccess) e = hipMemset(ctx->flag, 0, 256);
+    if (e != hipSuccess) {
+        delete ctx;
+        return AGZO_EHIP;
+    }
+    *out = ctx;
+    return AGZO_OK;
+}
+
+void agzo_destroy(agzo_ctx* ctx) {
+    if (!ctx) return;
+    (void)hipStreamSynchronize(ctx->stream);
+    if (ctx->ws) (void)hipFree(ctx->ws);
+    if (ctx->flag) (void)hipFree(ctx->flag);
+    delete ctx;
+}
+
+const char* agzo_last_error(const agzo_ctx* ctx) { return ctx ? ctx->err : "null context"; }
+
+int agzo_check(agzo_ctx* ctx) {
+    if (!ctx) return AGZO_EINVAL;
+    HIPCHK(hipStreamSynchronize(ctx->stream));
+    int h = 0;
+    HIPCHK(hipMemcpy(&h, ctx->flag, sizeof(int), hipMemcpyDeviceToHost));
+    if (h) {
+        HIPCHK(hipMemset(ctx->flag, 0, sizeof(int)));
+        return fail(ctx, AGZO_ENUMERIC, "Cholesky pivot <= 0: the sketch is rank deficient");
+    }
+    return AGZO_OK;
+}
+
+int agzo_philox_words(agzo_ctx* ctx, uint32_t* dst, int64_t rows, int32_t cols, uint64_t seed, uint32_t tag) {
+    if (!ctx) return AGZO_EINVAL;
+    if (rows < 0 || cols < 0 || rows > 0xFFFFFFFFLL) return fail(ctx, AGZO_EINVAL, "bad shape");
+    if (!dst && rows * cols > 0) return fail(ctx, AGZO_EINVAL, "dst is NULL");
+    HIPCHK(launch_philox_words(dst, rows, cols, seed, tag, ctx->stream));
+    return AGZO_OK;
+}
+
+int agzo_fill_normal(agzo_ctx* ctx, float* dst, int64_t rows, int32_t cols, uint64_t seed, uint32_t tag) {
+    if (!ctx) return AGZO_EINVAL;
+    if (rows < 0 || cols < 0 || rows > 0xFFFFFFFFLL) return fail(ctx, AGZO_EINVAL, "bad shape");
+    if (!dst && rows * cols > 0) return fail(ctx, AGZO_EINVAL, "dst is NULL");
+    HIPCHK(launch_fill_normal(dst, rows, cols, seed, tag, ctx->stream));
+    return AGZO_OK;
+}
+
+int agzo_layer_forward_sketch(agzo_ctx* ctx, const agzo_layer* L, const void* W, const void* X, void* Y, int32_t mode,
+                              const float* Q, uint64_t seed, float* S, const agzo_loss_spec* loss, double* loss_dev) {
+    const bool gemm = (W != nullptr);
+    TRY(check_layer(ctx, L, gemm));
+    if (!X) return fail(ctx, AGZO_EINVAL, "X is NULL");
+    if (!gemm && (Y || (loss && loss->kind != AGZO_LOSS_NONE))) return fail(ctx, AGZO_EINVAL, "Y or loss without W");
+    if (mode != AGZO_SKETCH_NONE && mode != AGZO_SKETCH_RANGE && mode != AGZO_SKETCH_POWER)
+        return fail(ctx, AGZO_EINVAL, "sketch mode %d", mode);
+    if (mode != AGZO_SKETCH_NONE && !S) return fail(ctx, AGZO_EINVAL, "S is NULL");
+    if (mode == AGZO_SKETCH_POWER && !Q) return fail(ctx, AGZO_EINVAL, "power sketch needs Q");
+    if (gemm) {
+        TRY(check_y(ctx, L, Y));
+        TRY(check_loss(ctx, L, loss, loss_dev));
+    }
+    const Plan p = make_plan(*L, gemm && L->dtype == AGZO_F32 && !Y);
+    TRY(reserve(ctx, p.total));
+    if (gemm) TRY(op_forward(ctx, *L, p, W, X, nullptr, 0.f, seed, Y, loss, loss_dev));
+    if (mode == AGZO_SKETCH_RANGE) TRY(op_sketch_range(ctx, *L, p, X, seed, S));
+    if (mode == AGZO_SKETCH_POWER) TRY(op_sketch_power(ctx, *L, p, X, Q, S));
+    return AGZO_OK;
+}
+
+int agzo_qr(agzo_ctx* ctx, const float* S, int64_t d_in, int32_t r, float* Q) {
+    if (!ctx) return AGZO_EINVAL;
+    if (!S || !Q) return fail(ctx, AGZO_EINVAL, "S or Q is NULL");
+    if (r < 1 || r > kMaxRank || d_in < r) return fail(ctx, AGZO_EINVAL, "need 1 <= r <= min(64, d_in)");
+    Plan p;
+    memset(&p, 0, sizeof(p));
+    p.off_qr = 0;
+    TRY(reserve(ctx, qr_workspace_bytes(d_in, r)));
+    return op_qr(ctx, p, S, d_in, r, Q);
+}
+
+int agzo_basis(agzo_ctx* ctx, const agzo_layer* L, const void* X, int32_t K, uint64_t seed, const float* S0,
+               int32_t flags, float* B) {
+    TRY(check_layer(ctx, L, false));
+    if (!X || !B) return fail(ctx, AGZO_EINVAL, "X or B is NULL");
+    if (K < 0 || K > 64) return fail(ctx, AGZO_EINVAL, "K=%d outside 0..64", K);
+    const Plan p = make_plan(*L, false);
+    TRY(reserve(ctx, p.total));
+    return op_basis(ctx, *L, p, X, K, seed, S0, flags, B);
+}
+
+int agzo_perturbed_forward(agzo_ctx* ctx, const agzo_layer* L, const void* W, const void* X, const float* B,
+                           uint64_t seed, float eps_signed, void* Y, const agzo_loss_spec* loss, double* loss_dev) {
+    TRY(check_layer(ctx, L, true));
+    if (!W || !X || !B) return fail(ctx, AGZO_EINVAL, "W, X or B is NULL");
+    TRY(check_y(ctx, L, Y));
+    TRY(check_loss(ctx, L, loss, loss_dev));
+    const Plan p = make_plan(*L, L->dtype == AGZO_F32 && !Y);
+    TRY(reserve(ctx, p.total));
+    float* P = wsf(ctx, p.off_T);
+    TRY(op_project(ctx, *L, p, X, B, P));
+    return op_forward(ctx, *L, p, W, X, P, eps_signed, seed, Y, loss, loss_dev);
+}
+
+int agzo_update(agzo_ctx* ctx, const agzo_layer* L, void* W, const float* B, uint64_t seed, float lr,
+                const double* g_dev) {
+    if (!ctx) return AGZO_EINVAL;
+    if (!L) return fail(ctx, AGZO_EINVAL, "layer descriptor is NULL");
+    if (!W || !B) return fail(ctx, AGZO_EINVAL, "W or B is NULL");
+    if (L->d_in < 1 || L->d_out < 1 || L->r < 1 || L->r > kMaxRank || L->r > L->d_in || L->ldw < L->d_in)
+        return fail(ctx, AGZO_EINVAL, "bad layer shape");
+    if (L->dtype != AGZO_F32 && L->dtype != AGZO_BF16) return fail(ctx, AGZO_EINVAL, "dtype %d", L->dtype);
+    if (L->dtype == AGZO_BF16 && (L->ldw % 8 || (reinterpret_cast<uintptr_t>(W) & 15)))
+        return fail(ctx, AGZO_EINVAL, "bf16 W needs 16-byte aligned rows");
+    HIPCHK(launch_update(W, L->dtype, L->ldw, L->d_out, L->d_in, B, L->r, seed, lr, g_dev, ctx->stream));
+    return AGZO_OK;
+}
+
+int agzo_step(agzo_ctx* ctx, const agzo_layer* L, void* W, const void* X, const agzo_loss_spec* loss, int32_t K,
+              float eps, float lr, uint64_t seed, int32_t flags, double* out_dev) {
+    TRY(check_layer(ctx, L, true));
+    if (!W || !X || !out_dev) return fail(ctx, AGZO_EINVAL, "W, X or out_dev is NULL");
+    if (!loss || loss->kind == AGZO_LOSS_NONE) return fail(ctx, AGZO_EINVAL, "a step needs a loss");
+    TRY(check_loss(ctx, L, loss, out_dev));
+    if (K < 0 || K > 64) return fail(ctx, AGZO_EINVAL, "K=%d outside 0..64", K);
+    if (!(eps > 0.f)) return fail(ctx, AGZO_EINVAL, "eps must be positive");
+    if (L->dtype == AGZO_BF16 && (reinterpret_cast<uintptr_t>(W) & 15)) return fail(ctx, AGZO_EINVAL, "W misaligned");
+    const Plan p = make_plan(*L, L->dtype == AGZO_F32);
+    TRY(reserve(ctx, p.total));
+    hipStream_t st = ctx->stream;
+    float* B = wsf(ctx, p.off_B);
+    const bool one_sided = (flags & AGZO_ONE_SIDED) != 0;
+
+    // 1. base forward f0 and subspace extraction from the same activations (Alg. 2, part 1)
+    TRY(op_forward(ctx, *L, p, W, X, nullptr, 0.f, seed, nullptr, loss, out_dev + 0));
+    TRY(op_basis(ctx, *L, p, X, K, seed, nullptr, flags & AGZO_INIT_FEATURE, B));
+    // 2. perturbed evaluations (Alg. 2, parts 2-3)
+    if (flags & AGZO_NAIVE_INPLACE) {
+        HIPCHK(launch_update(W, L->dtype, L->ldw, L->d_out, L->d_in, B, L->r, seed, -eps, nullptr, st));
+        TRY(op_forward(ctx, *L, p, W, X, nullptr, 0.f, seed, nullptr, loss, out_dev + 1));
+        if (!one_sided) {
+            HIPCHK(launch_update(W, L->dtype, L->ldw, L->d_out, L->d_in, B, L->r, seed, 2.f * eps, nullptr, st));
+            TRY(op_forward(ctx, *L, p, W, X, nullptr, 0.f, seed, nullptr, loss, out_dev + 2));
+            HIPCHK(launch_update(W, L->dtype, L->ldw, L->d_out, L->d_in, B, L->r, seed, -eps, nullptr, st));
+        } else {
+            HIPCHK(launch_update(W, L->dtype, L->ldw, L->d_out, L->d_in, B, L->r, seed, eps, nullptr, st));
+        }
+    } else {
+        float* P = wsf(ctx, p.off_T);
+        TRY(op_project(ctx, *L, p, X, B, P));
+        TRY(op_forward(ctx, *L, p, W, X, P, +eps, seed, nullptr, loss, out_dev + 1));
+        if (!one_sided) TRY(op_forward(ctx, *L, p, W, X, P, -eps, seed, nullptr, loss, out_dev + 2));
+    }
+    // 3. scalar g and the rank-r update
+    HIPCHK(launch_two_point(out_dev, eps, one_sided ? 1 : 0, st));
+    HIPCHK(launch_update(W, L->dtype, L->ldw, L->d_out, L->d_in, B, L->r, seed, lr, out_dev + 3, st));
+    return AGZO_OK;
+}
+
+}  // extern "C"

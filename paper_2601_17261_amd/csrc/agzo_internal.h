@@ -1,0 +1,142 @@
+// Internal declarations shared by the HIP sources of libagzo (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "agzo.h"
+
+namespace agzo {
+
+constexpr int kMaxRank = 64;
+
+// ---------------------------------------------------------------------------
+// bf16 helpers (bit-level; bf16 = upper half of an fp32)
+// ---------------------------------------------------------------------------
+typedef uint16_t bf16_t;
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
+
+// round to nearest, ties to even (inputs are finite)
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+    uint32_t u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+
+// f = hi + mid + lo with each part a bf16: 24 significant bits in total, so the
+// three-term sum reproduces an fp32 value exactly (up to the bf16 exponent range).
+__device__ __forceinline__ void split3_bf16(float f, bf16_t& hi, bf16_t& mid, bf16_t& lo) {
+    hi = f32_to_bf16(f);
+    float r1 = f - bf16_to_f32(hi);
+    mid = f32_to_bf16(r1);
+    float r2 = r1 - bf16_to_f32(mid);
+    lo = f32_to_bf16(r2);
+}
+
+// ---------------------------------------------------------------------------
+// Philox4x32-10 (Salmon et al., SC'11) and the Box-Muller map used for every
+// Gaussian matrix of the method (Alg. 2: generated from a seed, never stored).
+// counter = (row, col/4, tag, 0), key = (seed lo, seed hi).
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ uint4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                               uint32_t k0, uint32_t k1) {
+    constexpr uint32_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u, W0 = 0x9E3779B9u, W1 = 0xBB67AE85u;
+#pragma unroll
+    for (int i = 0; i < 10; ++i) {
+        uint32_t hi0 = __umulhi(M0, c0), lo0 = M0 * c0;
+        uint32_t hi1 = __umulhi(M1, c2), lo1 = M1 * c2;
+        uint32_t n0 = hi1 ^ c1 ^ k0, n2 = hi0 ^ c3 ^ k1;
+        c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
+        k0 += W0; k1 += W1;
+    }
+    return make_uint4(c0, c1, c2, c3);
+}
+
+__device__ __forceinline__ float philox_uniform(uint32_t x) {
+    // 23 random bits plus a half: exact in fp32, strictly inside (0, 1)
+    return ((float)(x >> 9) + 0.5f) * 1.1920928955078125e-07f;  // 2^-23
+}
+
+__device__ __forceinline__ void box_muller(uint32_t xa, uint32_t xb, float& z0, float& z1) {
+    float rad = sqrtf(-2.0f * logf(philox_uniform(xa)));
+    float s, c;
+    sincospif(2.0f * philox_uniform(xb), &s, &c);
+    z0 = rad * c;
+    z1 = rad * s;
+}
+
+// four normals for columns 4*quad .. 4*quad+3 of `row`
+__device__ __forceinline__ float4 philox_normal4(uint32_t seed_lo, uint32_t seed_hi, uint32_t tag,
+                                                 uint32_t row, uint32_t quad) {
+    uint4 x = philox4x32_10(row, quad, tag, 0u, seed_lo, seed_hi);
+    float4 z;
+    box_muller(x.x, x.y, z.x, z.y);
+    box_muller(x.z, x.w, z.z, z.w);
+    return z;
+}
+
+// ---------------------------------------------------------------------------
+// host-side launch functions (one per source file); all enqueue on `st`
+// ---------------------------------------------------------------------------
+struct GemmLossArgs {
+    int kind;             // agzo_loss_kind
+    int target_dtype;     // agzo_dtype
+    const void* target;
+    int64_t ldt;
+    double* partials;     // [n_workgroups] (MSE) scratch
+};
+
+// philox.hip
+hipError_t launch_philox_words(uint32_t* dst, int64_t rows, int cols, uint64_t seed, uint32_t tag, hipStream_t st);
+hipError_t launch_fill_normal(float* dst, int64_t rows, int cols, uint64_t seed, uint32_t tag, hipStream_t st);
+// bf16 [3][rp][n_pad] hi/mid/lo planes of Omega^T (rows of Omega are tokens)
+hipError_t launch_fill_normal_packT(bf16_t* dst, int64_t n, int64_t n_pad, int r, int rp, uint64_t seed,
+                                    uint32_t tag, hipStream_t st);
+
+// gemm_bf16.hip : Y = X W^T (+ P' G^T), MFMA, fused loss partials
+struct GemmBf16Args {
+    const bf16_t* X; int64_t ldx;
+    const bf16_t* W; int64_t ldw;
+    int64_t M, N, K;            // tokens, d_out, d_in
+    void* Y; int y_dtype; int64_t ldy;
+    const float* P; int r;      // projection X B [M][r] (NULL: no rank-r term)
+    float eps_signed; uint64_t seed;
+    GemmLossArgs loss;
+};
+int gemm_bf16_num_workgroups(int64_t M, int64_t N);
+hipError_t launch_gemm_bf16(const GemmBf16Args& a, hipStream_t st);
+
+// gemm_f32.hip : generic strided fp32 GEMM with fp64 accumulation, and the fp32 epilogue
+hipError_t launch_gemm_f32(const float* A, int64_t sam, int64_t sak, const float* B, int64_t sbk, int64_t sbn,
+                           float* C, int64_t ldc, int64_t M, int64_t N, int64_t K, hipStream_t st);
+int epilogue_f32_num_workgroups(int64_t M, int64_t N);
+// Y[t][j] += eps_signed * sum_k P[t][k] G[j][k] (if P), then loss partials (if loss.kind)
+hipError_t launch_epilogue_f32(float* Y, int64_t ldy, int64_t M, int64_t N, const float* P, int r,
+                               float eps_signed, uint64_t seed, const GemmLossArgs& loss, hipStream_t st);
+
+// skinny.hip : bf16 tall-skinny products
+// T = X Qp, Qp given as bf16 planes [3][rp][d_in]; writes T fp32 [M][r] (nullable) and
+// T^T planes bf16 [3][rp][m_pad] (nullable)
+hipError_t launch_xq_bf16(const bf16_t* X, int64_t ldx, int64_t M, int64_t K, const bf16_t* Qpack, int r, int rp,
+                          float* T, bf16_t* TpackT, int64_t m_pad, hipStream_t st);
+int xtt_num_splits(int64_t M, int64_t K);
+// partial[s][d][rp] = sum over token range s of X[t][d] * T[t][k]
+hipError_t launch_xtt_bf16(const bf16_t* X, int64_t ldx, int64_t M, int64_t K, const bf16_t* TpackT, int64_t m_pad,
+                           int rp, float* partial, int nsplit, hipStream_t st);
+hipError_t launch_reduce_splits(const float* partial, int nsplit, int64_t d, int rp, int r, float* S, hipStream_t st);
+// Q fp32 [d][r] -> bf16 planes [3][rp][d]
+hipError_t launch_pack_planes(const float* Q, int64_t d, int r, int rp, bf16_t* pack, hipStream_t st);
+
+// qr.hip : CholeskyQR2
+size_t qr_workspace_bytes(int64_t d, int r);
+hipError_t launch_qr(const float* S, int64_t d, int r, float* Q, void* workspace, int* numeric_flag, hipStream_t st);
+
+// update.hip : W -= lr * g * G B^T in place
+hipError_t launch_update(void* W, int dtype, int64_t ldw, int64_t d_out, int64_t d_in, const float* B, int r,
+                         uint64_t seed, float lr, const double* g_dev, hipStream_t st);
+
+// loss.hip
+hipError_t launch_finish_loss(const double* partials, int n, double scale, double* out, hipStream_t st);
+hipError_t launch_two_point(double* out4, float eps, int one_sided, hipStream_t st);
+
+}  // namespace agzo

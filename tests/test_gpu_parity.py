@@ -1,0 +1,314 @@
+"""GPU parity: every entry point of the C ABI against the fp64 CPU oracle, element by element,
+on identical seeded inputs.  Sizes span several tiles plus ragged tails.
+
+Bars (the benchmark spec): Philox words bit-exact; fp32-storage path <= 1e-4 relative (Frobenius);
+bf16-storage path <= 2e-2 relative on outputs and updated W.  The kernels are in fact far
+tighter than that, so each test also asserts a bound derived from the arithmetic:
+  * fp32 path: products accumulate in fp64, results rounded once to fp32 -> ~1e-6;
+  * bf16 path: bf16 x bf16 products are exact in fp32, fp32 accumulation over d_in terms
+    -> ~sqrt(d_in) * 2^-24 ~ 1e-5 on Y; small fp32 factors enter as three bf16 planes (24 bits).
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import agzo as oagzo
+from oracle import philox as ophilox
+from paper_2601_17261_amd import binding, synth
+
+pytestmark = pytest.mark.gpu
+
+EPS = float(np.float32(1e-3))
+LR = float(np.float32(1e-2))
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    c = binding.Context()
+    yield c
+    c.close()
+
+
+def rel(a, b):
+    a = np.asarray(a, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300))
+
+
+def dev(a, storage="f32"):
+    t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+    return t.to(torch.bfloat16) if storage == "bf16" else t
+
+
+def host(t):
+    return t.detach().float().cpu().numpy().astype(np.float64)
+
+
+def problem(seed, n, d_in, d_out, kind, storage):
+    W, X, T = synth.single_layer_problem(seed, n, d_in, d_out, kind=kind, storage=storage)
+    return W, X, T, dev(W, storage), dev(X, storage), dev(T)
+
+
+# ---------------------------------------------------------------------------------------------
+# generator
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("rows,cols", [(1, 1), (7, 3), (300, 16), (1025, 5), (4096, 64)])
+def test_philox_words_bit_exact(ctx, rows, cols):
+    for seed, tag in ((0, 0), (0x0123456789ABCDEF, 1), (2 ** 64 - 1, 3)):
+        dst = torch.empty(rows, cols, dtype=torch.int32, device="cuda")
+        ctx.philox_words(dst, seed, tag)
+        got = dst.cpu().numpy().view(np.uint32)
+        np.testing.assert_array_equal(got, ophilox.philox_words(seed, tag, rows, cols))
+
+
+@pytest.mark.parametrize("rows,cols", [(5, 1), (333, 7), (2048, 16), (12288, 64)])
+def test_fill_normal_matches_oracle(ctx, rows, cols):
+    dst = torch.empty(rows, cols, dtype=torch.float32, device="cuda")
+    ctx.fill_normal(dst, 1234567, binding.TAG_G)
+    got = host(dst)
+    want = ophilox.normal(1234567, ophilox.TAG_G, rows, cols).astype(np.float64)
+    assert np.abs(got - want).max() < 2e-6           # fp32 log / sincos vs fp64, |z| < 5.8
+    assert rel(got, want) < 1e-6
+
+
+def test_generator_empty_is_ok(ctx):
+    dst = torch.empty(0, 4, dtype=torch.float32, device="cuda")
+    ctx.fill_normal(dst, 1, 0)
+    ctx.check()
+
+
+# ---------------------------------------------------------------------------------------------
+# QR
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("d,r,cond", [(64, 1, 1.0), (300, 4, 1e2), (1000, 16, 1e4), (4100, 33, 1e3), (777, 64, 1e2)])
+def test_qr_matches_oracle(ctx, d, r, cond):
+    rng = np.random.default_rng(d + r)
+    Y = rng.standard_normal((d, r)) @ np.diag(np.logspace(0, -np.log10(cond), r)) @ rng.standard_normal((r, r))
+    Y = Y.astype(np.float32)
+    Q = torch.empty(d, r, dtype=torch.float32, device="cuda")
+    ctx.qr(dev(Y), Q)
+    ctx.check()
+    want, _ = oagzo.qr_pos(Y.astype(np.float64))
+    got = host(Q)
+    assert np.linalg.norm(got.T @ got - np.eye(r)) < 1e-5
+    assert rel(got, want) < 1e-5
+
+
+def test_qr_rank_deficient_reports_numeric_error(ctx):
+    Y = np.ones((128, 3), dtype=np.float32)
+    Y[:, 1] = 0.0                      # an exactly zero column: pivot 0
+    Q = torch.empty(128, 3, dtype=torch.float32, device="cuda")
+    ctx.qr(dev(Y), Q)
+    with pytest.raises(binding.AgzoError) as e:
+        ctx.check()
+    assert e.value.code == binding.ENUMERIC
+    ctx.check()                        # flag is cleared by the failed check
+
+
+# ---------------------------------------------------------------------------------------------
+# per-entry-point parity, both storage types
+# ---------------------------------------------------------------------------------------------
+CASES = [
+    # storage, n, d_in, d_out, r, kind, tolerance on Y / S / B
+    ("f32", 300, 100, 70, 4, "lowrank", 2e-6),
+    ("f32", 512, 256, 256, 4, "lowrank", 2e-6),
+    ("f32", 130, 65, 33, 1, "lowrank", 2e-6),
+    ("bf16", 300, 200, 264, 8, "lowrank", 2e-5),
+    ("bf16", 600, 1024, 520, 16, "rmsnorm", 2e-5),
+    ("bf16", 257, 72, 40, 1, "lowrank", 2e-5),
+    ("bf16", 515, 136, 300, 24, "powerlaw", 2e-5),
+]
+
+
+@pytest.mark.parametrize("storage,n,d_in,d_out,r,kind,tol", CASES)
+def test_forward_sketch_basis_perturbed_update(ctx, storage, n, d_in, d_out, r, kind, tol):
+    seed = 4242 + n
+    W, X, T, Wd, Xd, Td = problem(n + d_in, n, d_in, d_out, kind, storage)
+    W64, X64 = W.astype(np.float64), X.astype(np.float64)
+    L = binding.make_layer(Wd, Xd, r)
+    loss = binding.make_loss(Td)
+    scal = torch.zeros(4, dtype=torch.float64, device="cuda")
+
+    # base forward + range sketch
+    Y = torch.empty(n, d_out, dtype=torch.float32, device="cuda")
+    S = torch.empty(d_in, r, dtype=torch.float32, device="cuda")
+    Ly = binding.make_layer(Wd, Xd, r, Y=Y)
+    ctx.layer_forward_sketch(Ly, Wd, Xd, Y, binding.SKETCH_RANGE, None, seed, S, loss, scal[0:1])
+    Y0 = oagzo.forward(X64, W64)
+    S0 = oagzo.range_sketch(X64, r, seed)
+    assert rel(host(Y), Y0) < tol
+    assert rel(host(S), S0) < tol
+    assert abs(scal[0].item() - oagzo.mse_loss(Y0, T)) < 1e-5 * oagzo.mse_loss(Y0, T)
+
+    # power sketch from a given Q
+    ext = oagzo.subspace_extract(X64, r, 3, seed)
+    Q1 = ext["Q"][0].astype(np.float32)
+    ctx.layer_forward_sketch(L, None, Xd, None, binding.SKETCH_POWER, dev(Q1), seed, S, None, None)
+    assert rel(host(S), oagzo.power_sketch(X64, Q1.astype(np.float64))) < tol
+
+    # basis, with and without a precomputed first sketch
+    B = torch.empty(d_in, r, dtype=torch.float32, device="cuda")
+    ctx.basis(L, Xd, 3, seed, None, 0, B)
+    ctx.check()
+    Bg = host(B)
+    Bo = ext["B"]
+    assert np.linalg.norm(Bg.T @ Bg - np.eye(r)) < 1e-5
+    gap = np.linalg.norm(Bg @ Bg.T - Bo @ Bo.T) / np.sqrt(r)
+    assert gap < 2e-3, gap
+    B2 = torch.empty_like(B)
+    ctx.basis(L, Xd, 3, seed, dev(S0.astype(np.float32)), 0, B2)
+    assert rel(host(B2), Bg) < 1e-4
+
+    # perturbed forward with the oracle's basis (isolates this entry point)
+    Bo32 = Bo.astype(np.float32)
+    Z, G = oagzo.perturbation(Bo32.astype(np.float64), seed, d_out)
+    for sign in (+1.0, -1.0):
+        ctx.perturbed_forward(Ly, Wd, Xd, dev(Bo32), seed, sign * EPS, Y, loss, scal[1:2])
+        Yp = oagzo.forward(X64, W64 + sign * EPS * Z)
+        assert rel(host(Y), Yp) < tol
+        # the perturbation itself, not just the output it rides on
+        assert rel(host(Y) - Y0, Yp - Y0) < 5e-3
+        Lp = oagzo.mse_loss(Yp, T)
+        assert abs(scal[1].item() - Lp) < 1e-5 * Lp
+
+    # update (g given on the device)
+    g = -0.731
+    gd = torch.tensor([g], dtype=torch.float64, device="cuda")
+    Wu = Wd.clone()
+    ctx.update(L, Wu, dev(Bo32), seed, LR, gd)
+    want = oagzo.round_storage(W64 - LR * g * Z, storage)
+    assert rel(host(Wu), want) < (1e-6 if storage == "f32" else 2e-3)
+    assert rel(host(Wu) - W64, want - W64) < (1e-4 if storage == "f32" else 0.2)
+    if storage == "bf16":
+        # rounding decisions taken in fp32 instead of fp64: at most isolated one-ulp flips
+        ulp = np.abs(want) * 2.0 ** -7
+        assert (np.abs(host(Wu) - want) <= ulp + 1e-30).all()
+        assert np.mean(host(Wu) != want) < 2e-3
+    ctx.check()
+
+
+@pytest.mark.parametrize("storage,n,d_in,d_out,r,kind", [
+    ("f32", 512, 256, 256, 4, "lowrank"),
+    ("bf16", 515, 136, 300, 8, "lowrank"),
+    ("bf16", 600, 1024, 520, 16, "rmsnorm"),
+])
+@pytest.mark.parametrize("flags", [0, binding.ONE_SIDED, binding.INIT_FEATURE])
+def test_step_matches_oracle(ctx, storage, n, d_in, d_out, r, kind, flags):
+    seed = 99
+    W, X, T, Wd, Xd, Td = problem(7 + n, n, d_in, d_out, kind, storage)
+    L = binding.make_layer(Wd, Xd, r)
+    out = torch.zeros(4, dtype=torch.float64, device="cuda")
+    ctx.step(L, Wd, Xd, binding.make_loss(Td), 3, EPS, LR, seed, flags, out)
+    ctx.check()
+    o = oagzo.agzo_step(W, X, T, r, 3, EPS, LR, seed, storage=storage, one_sided=bool(flags & binding.ONE_SIDED),
+                        init="feature" if flags & binding.INIT_FEATURE else "token")
+    got = out.cpu().numpy()
+    assert abs(got[0] - o["L0"]) < 1e-5 * o["L0"]
+    assert abs(got[1] - o["Lp"]) < 1e-5 * o["Lp"]
+    if not flags & binding.ONE_SIDED:
+        assert abs(got[2] - o["Lm"]) < 1e-5 * o["Lm"]
+    gtol = 2e-3 if storage == "f32" else 2e-2
+    assert abs(got[3] - o["g"]) < gtol * abs(o["g"]) + 1e-9, (got[3], o["g"])
+    assert rel(host(Wd), o["W_new"]) < (1e-4 if storage == "f32" else 2e-2)
+    assert rel(host(Wd), o["W_new"]) < (1e-6 if storage == "f32" else 3e-3)
+
+
+def test_config1_trajectory_20_steps(ctx):
+    """The small fp32 workload in full: 256x256 layer, 512 tokens, r=4, K=3, 20 steps."""
+    W, X, T, Wd, Xd, Td = problem(0, 512, 256, 256, "lowrank", "f32")
+    L = binding.make_layer(Wd, Xd, 4)
+    loss = binding.make_loss(Td)
+    out = torch.zeros(20, 4, dtype=torch.float64, device="cuda")
+    Wo = W.astype(np.float64)
+    ref = []
+    for step in range(20):
+        ctx.step(L, Wd, Xd, loss, 3, EPS, LR, 1000 * step, 0, out[step])
+        o = oagzo.agzo_step(Wo, X, T, 4, 3, EPS, LR, 1000 * step, storage="f32")
+        Wo = o["W_new"]
+        ref.append((o["L0"], o["Lp"], o["Lm"], o["g"]))
+    ctx.check()
+    got = out.cpu().numpy()
+    ref = np.array(ref)
+    assert np.abs(got[:, :3] / ref[:, :3] - 1).max() < 1e-5
+    assert np.abs(got[:, 3] - ref[:, 3]).max() < 2e-3 * np.abs(ref[:, 3]).max()
+    assert rel(host(Wd), Wo) < 1e-4
+    assert rel(host(Wd) - W, Wo - W) < 1e-2          # the accumulated update itself
+    assert ref[-1, 0] < ref[0, 0]                       # and the 20 steps did descend
+
+
+def test_naive_inplace_comparator_has_its_own_oracle(ctx):
+    for storage, tolW in (("f32", 1e-6), ("bf16", 3e-3)):
+        W, X, T, Wd, Xd, Td = problem(5, 300, 136, 264, "lowrank", storage)
+        r, seed = 8, 31
+        L = binding.make_layer(Wd, Xd, r)
+        B = torch.empty(136, r, dtype=torch.float32, device="cuda")
+        ctx.basis(L, Xd, 3, seed, None, 0, B)
+        out = torch.zeros(4, dtype=torch.float64, device="cuda")
+        ctx.step(L, Wd, Xd, binding.make_loss(Td), 3, EPS, LR, seed, binding.NAIVE_INPLACE, out)
+        ctx.check()
+        o = oagzo.agzo_step_inplace(W, X, T, host(B), EPS, LR, seed, storage=storage)
+        got = out.cpu().numpy()
+        assert abs(got[0] - o["L0"]) < 1e-5 * o["L0"]
+        assert abs(got[1] - o["Lp"]) < 1e-4 * o["Lp"]
+        assert abs(got[2] - o["Lm"]) < 1e-4 * o["Lm"]
+        assert rel(host(Wd), o["W_new"]) < tolW
+
+
+def test_step_is_deterministic(ctx):
+    W, X, T, Wd, Xd, Td = problem(3, 600, 1024, 520, "rmsnorm", "bf16")
+    L = binding.make_layer(Wd, Xd, 16)
+    res = []
+    for _ in range(2):
+        Wc = Wd.clone()
+        out = torch.zeros(4, dtype=torch.float64, device="cuda")
+        ctx.step(L, Wc, Xd, binding.make_loss(Td), 3, EPS, LR, 5, 0, out)
+        res.append((Wc.cpu(), out.cpu()))
+    assert torch.equal(res[0][0], res[1][0]) and torch.equal(res[0][1], res[1][1])
+
+
+def test_qwen3_0p6b_layer_set_one_step(ctx):
+    """Config 2 at full size: the seven projections of a Qwen3-0.6B layer, N = 8 x 256, r = 8."""
+    n, r = 2048, 8
+    rng = np.random.default_rng(2)
+    inputs = {}
+    for name, d_in, d_out in synth.QWEN3_0P6B_LAYER:
+        key = {"q": "attn", "k": "attn", "v": "attn", "gate": "mlp", "up": "mlp"}.get(name, name)
+        if key not in inputs:
+            inputs[key] = synth.x_rmsnorm_gaussian(rng, n, d_in, storage="bf16")
+        X = inputs[key]
+        W = synth.weights(rng, d_out, d_in, storage="bf16")
+        T = synth.shifted_target(rng, X, W)
+        Wd, Xd, Td = dev(W, "bf16"), dev(X, "bf16"), dev(T)
+        L = binding.make_layer(Wd, Xd, r)
+        out = torch.zeros(4, dtype=torch.float64, device="cuda")
+        seed = 1000 + len(name)
+        ctx.step(L, Wd, Xd, binding.make_loss(Td), 3, EPS, LR, seed, 0, out)
+        ctx.check()
+        o = oagzo.agzo_step(W, X, T, r, 3, EPS, LR, seed, storage="bf16")
+        got = out.cpu().numpy()
+        assert abs(got[0] - o["L0"]) < 1e-5 * o["L0"], name
+        assert abs(got[3] - o["g"]) < 2e-2 * abs(o["g"]) + 1e-9, (name, got[3], o["g"])
+        assert rel(host(Wd), o["W_new"]) < 3e-3, name
+
+
+# ---------------------------------------------------------------------------------------------
+# argument checking
+# ---------------------------------------------------------------------------------------------
+def test_invalid_arguments_are_rejected(ctx):
+    W, X, T, Wd, Xd, Td = problem(1, 64, 32, 16, "lowrank", "bf16")
+    out = torch.zeros(4, dtype=torch.float64, device="cuda")
+    loss = binding.make_loss(Td)
+    for r in (0, 65, 33):
+        with pytest.raises(binding.AgzoError) as e:
+            ctx.step(binding.make_layer(Wd, Xd, r), Wd, Xd, loss, 3, EPS, LR, 1, 0, out)
+        assert e.value.code == binding.EINVAL
+    L = binding.make_layer(Wd, Xd, 4)
+    with pytest.raises(binding.AgzoError):
+        ctx.step(L, None, Xd, loss, 3, EPS, LR, 1, 0, out)
+    with pytest.raises(binding.AgzoError):
+        ctx.step(L, Wd, Xd, loss, 3, 0.0, LR, 1, 0, out)
+    Lbad = binding.make_layer(Wd, Xd, 4)
+    Lbad.ldx = 36                       # not a multiple of 8 for bf16
+    with pytest.raises(binding.AgzoError):
+        ctx.step(Lbad, Wd, Xd, loss, 3, EPS, LR, 1, 0, out)
+    np.testing.assert_array_equal(Wd.float().cpu().numpy(), W)     # nothing was touched
