@@ -1,0 +1,165 @@
+#!/usr/bin/env python3
+"""Benchmark of the AGZO per-step hot path on one MI355X.
+
+Workload: the seven projections of one Qwen3-8B-shaped decoder layer (bf16 weights and
+activations, N = 16 x 1024 tokens, r = 16, K = 3 power steps, MSE loss), synthetic inputs with a
+power-law activation spectrum plus outlier channels.  One *step* = one full AGZO step (base forward
+with subspace extraction, two perturbed forwards, two-point scalar, in-place rank-r update) for each
+of the seven projections.  Inputs are resident in HBM before the timed region starts.
+
+Prints one JSON line: steps/s for the layer set, the roofline of the dominant kernel (the forward
+GEMM, timed live with HIP events on the library's stream), the update kernel's HBM figure, and the
+CPU oracle timed on this host as a baseline.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+from paper_2601_17261_amd import binding, synth  # noqa: E402
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
+
+
+def build_layer_set(n_tokens, shapes, seed):
+    """One (W, X, Y*) triple per projection; projections that read the same activations share X."""
+    groups = {"q": "attn", "k": "attn", "v": "attn", "gate": "mlp", "up": "mlp"}
+    xs, out = {}, []
+    for idx, (name, d_in, d_out) in enumerate(shapes):
+        key = groups.get(name, name)
+        if key not in xs:
+            xs[key] = synth.device_powerlaw_x(seed + 100 + idx, n_tokens, d_in)
+        X = xs[key]
+        W, T = synth.device_weights_and_target(seed + idx, X, d_out)
+        out.append((name, d_in, d_out, W, X, T))
+    torch.cuda.synchronize()
+    return out
+
+
+def cpu_baseline(n_tokens, r, K, eps, lr, layer_flops):
+    """The oracle, as it stands, on this host: one full step of the k projection (4096 -> 1024) at the
+    benchmark's token count, scaled to the seven-projection layer set by forward-flop ratio."""
+    from oracle import agzo as oagzo
+    d_in, d_out = 4096, 1024
+    rng = np.random.default_rng(0)
+    W = synth.weights(rng, d_out, d_in, storage="bf16")
+    X = synth.to_bf16_values(rng.standard_normal((n_tokens, d_in)).astype(np.float32))
+    T = (X @ W.T).astype(np.float32)
+    try:
+        import threadpoolctl
+        cores = max(i["num_threads"] for i in threadpoolctl.threadpool_info()) if threadpoolctl.threadpool_info() else 1
+    except Exception:
+        cores = os.cpu_count() or 1
+    t0 = time.perf_counter()
+    oagzo.agzo_step(W, X, T, r, K, eps, lr, seed=1, storage="bf16")
+    dt = time.perf_counter() - t0
+    ratio = layer_flops / (2.0 * n_tokens * d_in * d_out)
+    return {"value": 1.0 / (dt * ratio), "unit": "steps/s", "cores": int(cores), "kind": "oracle",
+            "sample": "one oracle step of the k projection (4096->1024, N=%d, r=%d, K=%d) took %.2f s; "
+                      "scaled by the layer set's forward-flop ratio %.1f" % (n_tokens, r, K, dt, ratio)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--tokens", type=int, default=16384)
+    ap.add_argument("--rank", type=int, default=16)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--naive", action="store_true", help="time the perturb-in-place / undo comparator instead")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives are part of it); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(2)
+
+    N, r, K = args.tokens, args.rank, 3
+    eps, lr = float(np.float32(1e-3)), float(np.float32(1e-4))
+    shapes = synth.QWEN3_8B_LAYER
+    layers = build_layer_set(N, shapes, seed=0)
+    ctx = binding.Context()
+    descs = []
+    for name, d_in, d_out, W, X, T in layers:
+        descs.append((binding.make_layer(W, X, r), W, X, binding.make_loss(T)))
+    out = torch.zeros(len(layers), 4, dtype=torch.float64, device="cuda")
+    flags = binding.NAIVE_INPLACE if args.naive else 0
+
+    def one_step(step):
+        for li, (L, W, X, loss) in enumerate(descs):
+            ctx.step(L, W, X, loss, K, eps, lr, 1000 * step + li, flags, out[li])
+
+    for s in range(args.warmup):
+        one_step(s)
+    ctx.check()
+    torch.cuda.synchronize()
+    ctx.profile_enable(True)
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        one_step(args.warmup + s)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    n_gemm, ms_gemm = ctx.profile_read(binding.PROF_GEMM)
+    n_upd, ms_upd = ctx.profile_read(binding.PROF_UPDATE)
+    n_xq, ms_xq = ctx.profile_read(binding.PROF_XQ)
+    n_xtt, ms_xtt = ctx.profile_read(binding.PROF_XTT)
+    n_qr, ms_qr = ctx.profile_read(binding.PROF_QR)
+    ctx.profile_enable(False)
+    ctx.check()
+    losses = out.cpu().numpy()
+    if not np.isfinite(losses).all():
+        print("bench.py: non-finite loss in the timed region", file=sys.stderr)
+        sys.exit(1)
+
+    # algorithmic work per launch, averaged over the launches of the timed region
+    fwd_flops = sum(2.0 * N * d_in * d_out for _, d_in, d_out in shapes)        # one forward of the layer set
+    rank_flops = sum(2.0 * N * r * (d_in + d_out) for _, d_in, d_out in shapes)   # rank-r term (perturbed only)
+    gemm_per_step = 3 if not args.naive else 3
+    algo_flops_per_launch = (gemm_per_step * fwd_flops + (0 if args.naive else 2 * rank_flops)) / (gemm_per_step * len(shapes))
+    gemm_avg_ms = ms_gemm / max(n_gemm, 1)
+    gemm_tflops = algo_flops_per_launch / (gemm_avg_ms * 1e-3) / 1e12
+    upd_bytes_per_launch = sum(2.0 * 2 * d_in * d_out + 4.0 * d_in * r for _, d_in, d_out in shapes) / len(shapes)
+    upd_avg_ms = ms_upd / max(n_upd, 1)
+    upd_gbs = upd_bytes_per_launch / (upd_avg_ms * 1e-3) / 1e9
+
+    traffic = None
+    tfile = os.path.join(ROOT, "profiles", "gemm_bf16_qwen3_8b_traffic.txt")
+    if os.path.exists(tfile):
+        for line in open(tfile):
+            if line.startswith("traffic_bytes_per_launch"):
+                traffic = float(line.split()[1])
+
+    res = {
+        "metric": "AGZO steps/sec per layer set (Qwen3-8B layer projections)",
+        "value": args.steps / dt, "unit": "steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": 1e3 * dt / args.steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "qwen3-8b layer projections (q,k,v,o,gate,up,down), N=%d tokens, r=%d, K=%d, "
+                               "bf16 weights/activations, MSE loss, %s" % (N, r, K, "naive in-place comparator" if args.naive else "factored perturbed forward"),
+                   "tokens": N, "rank": r, "power_steps": K, "eps": eps, "lr": lr},
+        "roofline": {"bound": "mfma", "kernel": "gemm_bf16_kernel", "achieved": gemm_tflops, "peak": PEAK_BF16_TFLOPS,
+                     "unit": "TFLOP/s", "frac": gemm_tflops / PEAK_BF16_TFLOPS, "traffic": traffic,
+                     "launches": n_gemm, "avg_ms": gemm_avg_ms},
+        "roofline_update": {"bound": "hbm", "kernel": "update_kernel", "achieved": upd_gbs, "peak": PEAK_HBM_GBS,
+                            "unit": "GB/s", "frac": upd_gbs / PEAK_HBM_GBS, "launches": n_upd, "avg_ms": upd_avg_ms},
+        "stage_ms_per_step": {"gemm": ms_gemm / args.steps, "update": ms_upd / args.steps, "xq": ms_xq / args.steps,
+                              "xtt": ms_xtt / args.steps, "qr": ms_qr / args.steps},
+    }
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(N, r, K, eps, lr, fwd_flops)
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

@@ -87,6 +87,14 @@ const char* agzo_last_error(const agzo_ctx* ctx);
 /* Synchronise the stream and report a deferred numeric failure (AGZO_ENUMERIC) if any; clears it. */
 int agzo_check(agzo_ctx* ctx);
 
+/* Measurement hooks (no counterpart in the paper): when enabled, each launch of a kernel class is
+ * bracketed by HIP events recorded on the ctx stream; agzo_profile_read synchronises and returns the
+ * number of launches since agzo_profile_enable and the sum of their durations in milliseconds. */
+enum { AGZO_PROF_GEMM = 0, AGZO_PROF_UPDATE = 1, AGZO_PROF_XQ = 2, AGZO_PROF_XTT = 3, AGZO_PROF_QR = 4,
+       AGZO_PROF_FILL = 5, AGZO_PROF_KINDS = 6 };
+int agzo_profile_enable(agzo_ctx* ctx, int32_t on);
+int agzo_profile_read(agzo_ctx* ctx, int32_t kind, int64_t* launches, double* total_ms);
+
 /* Generator (Alg. 2 "generate R from seed"; this build: Philox4x32-10 + Box-Muller).
  * words: uint32 [rows][cols], word (row, col) = word col%4 of Philox(counter (row, col/4, tag, 0),
  * key (seed lo, seed hi)).  normal: fp32 [rows][cols] from the same words, u = ((x>>9)+0.5)*2^-23,

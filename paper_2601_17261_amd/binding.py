@@ -20,7 +20,10 @@ TAG_G, TAG_OMEGA, TAG_Q0, TAG_DENSE = 0, 1, 2, 3
 ONE_SIDED, NAIVE_INPLACE, INIT_FEATURE = 1, 2, 4
 OK, EINVAL, ENOMEM, ENUMERIC, EHIP = 0, -1, -2, -3, -4
 
-EXPORTS = ["agzo_create", "agzo_destroy", "agzo_last_error", "agzo_check", "agzo_philox_words", "agzo_fill_normal",
+PROF_GEMM, PROF_UPDATE, PROF_XQ, PROF_XTT, PROF_QR, PROF_FILL = range(6)
+
+EXPORTS = ["agzo_create", "agzo_destroy", "agzo_last_error", "agzo_check", "agzo_profile_enable",
+           "agzo_profile_read", "agzo_philox_words", "agzo_fill_normal",
            "agzo_layer_forward_sketch", "agzo_qr", "agzo_basis", "agzo_perturbed_forward", "agzo_update", "agzo_step"]
 
 
@@ -63,6 +66,8 @@ def load():
     lib.agzo_last_error.argtypes = [vp]
     lib.agzo_last_error.restype = ctypes.c_char_p
     lib.agzo_check.argtypes = [vp]
+    lib.agzo_profile_enable.argtypes = [vp, i32]
+    lib.agzo_profile_read.argtypes = [vp, i32, ctypes.POINTER(i64), ctypes.POINTER(ctypes.c_double)]
     lib.agzo_philox_words.argtypes = [vp, vp, i64, i32, u64, u32]
     lib.agzo_fill_normal.argtypes = [vp, vp, i64, i32, u64, u32]
     lib.agzo_layer_forward_sketch.argtypes = [vp, lp, vp, vp, vp, i32, vp, u64, vp, sp, vp]
@@ -149,6 +154,14 @@ class Context:
     # --- one method per C entry point, same name without the prefix -------------------------
     def check(self):
         self._rc(self.lib.agzo_check(self.h))
+
+    def profile_enable(self, on):
+        self._rc(self.lib.agzo_profile_enable(self.h, 1 if on else 0))
+
+    def profile_read(self, kind):
+        n, ms = ctypes.c_int64(0), ctypes.c_double(0.0)
+        self._rc(self.lib.agzo_profile_read(self.h, kind, ctypes.byref(n), ctypes.byref(ms)))
+        return n.value, ms.value
 
     def philox_words(self, dst, seed, tag):
         rows, cols = dst.shape

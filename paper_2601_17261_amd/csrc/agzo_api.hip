@@ -5,10 +5,16 @@
 #include <string.h>
 
 #include <new>
+#include <vector>
 
 #include "agzo_internal.h"
 
 using namespace agzo;
+
+struct ProfClass {
+    std::vector<hipEvent_t> start, stop;
+    size_t used = 0;
+};
 
 struct agzo_ctx {
     hipStream_t stream;
@@ -16,6 +22,8 @@ struct agzo_ctx {
     char* ws;
     size_t ws_bytes;
     int* flag;   // device int: deferred numeric failure
+    bool prof;
+    ProfClass pc[AGZO_PROF_KINDS];
 };
 
 namespace {
@@ -40,6 +48,29 @@ int fail(agzo_ctx* c, int code, const char* fmt, ...) {
         int rc__ = (expr);     \
         if (rc__ != 0) return rc__; \
     } while (0)
+
+// Optional timing of one kernel class with HIP events recorded on the ctx stream around each launch.
+struct ProfScope {
+    agzo_ctx* c;
+    int kind;
+    hipEvent_t stop = nullptr;
+    ProfScope(agzo_ctx* ctx, int k) : c(ctx), kind(k) {
+        if (!c->prof) return;
+        ProfClass& pc = c->pc[kind];
+        if (pc.used == pc.start.size()) {
+            hipEvent_t a, b;
+            if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) return;
+            pc.start.push_back(a);
+            pc.stop.push_back(b);
+        }
+        (void)hipEventRecord(pc.start[pc.used], c->stream);
+        stop = pc.stop[pc.used];
+        pc.used++;
+    }
+    ~ProfScope() {
+        if (stop) (void)hipEventRecord(stop, c->stream);
+    }
+};
 
 inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 inline int round16(int r) { return (r + 15) / 16 * 16; }
@@ -136,9 +167,15 @@ inline bf16_t* wsh(agzo_ctx* c, size_t off) { return reinterpret_cast<bf16_t*>(c
 int op_sketch_range(agzo_ctx* ctx, const agzo_layer& L, const Plan& p, const void* X, uint64_t seed, float* S) {
     hipStream_t st = ctx->stream;
     if (L.dtype == AGZO_BF16) {
-        HIPCHK(launch_fill_normal_packT(wsh(ctx, p.off_TpackT), L.n_tokens, p.m_pad, L.r, p.rp, seed, AGZO_TAG_OMEGA, st));
-        HIPCHK(launch_xtt_bf16(static_cast<const bf16_t*>(X), L.ldx, L.n_tokens, L.d_in, wsh(ctx, p.off_TpackT), p.m_pad,
-                               p.rp, wsf(ctx, p.off_xtt), p.nsplit, st));
+        {
+            ProfScope ps(ctx, AGZO_PROF_FILL);
+            HIPCHK(launch_fill_normal_packT(wsh(ctx, p.off_TpackT), L.n_tokens, p.m_pad, L.r, p.rp, seed, AGZO_TAG_OMEGA, st));
+        }
+        {
+            ProfScope ps(ctx, AGZO_PROF_XTT);
+            HIPCHK(launch_xtt_bf16(static_cast<const bf16_t*>(X), L.ldx, L.n_tokens, L.d_in, wsh(ctx, p.off_TpackT),
+                                   p.m_pad, p.rp, wsf(ctx, p.off_xtt), p.nsplit, st));
+        }
         HIPCHK(launch_reduce_splits(wsf(ctx, p.off_xtt), p.nsplit, L.d_in, p.rp, L.r, S, st));
     } else {
         float* om = wsf(ctx, p.off_T);
@@ -153,10 +190,16 @@ int op_sketch_power(agzo_ctx* ctx, const agzo_layer& L, const Plan& p, const voi
     hipStream_t st = ctx->stream;
     if (L.dtype == AGZO_BF16) {
         HIPCHK(launch_pack_planes(Q, L.d_in, L.r, p.rp, wsh(ctx, p.off_pack), st));
-        HIPCHK(launch_xq_bf16(static_cast<const bf16_t*>(X), L.ldx, L.n_tokens, L.d_in, wsh(ctx, p.off_pack), L.r, p.rp,
-                              nullptr, wsh(ctx, p.off_TpackT), p.m_pad, st));
-        HIPCHK(launch_xtt_bf16(static_cast<const bf16_t*>(X), L.ldx, L.n_tokens, L.d_in, wsh(ctx, p.off_TpackT), p.m_pad,
-                               p.rp, wsf(ctx, p.off_xtt), p.nsplit, st));
+        {
+            ProfScope ps(ctx, AGZO_PROF_XQ);
+            HIPCHK(launch_xq_bf16(static_cast<const bf16_t*>(X), L.ldx, L.n_tokens, L.d_in, wsh(ctx, p.off_pack), L.r,
+                                  p.rp, nullptr, wsh(ctx, p.off_TpackT), p.m_pad, st));
+        }
+        {
+            ProfScope ps(ctx, AGZO_PROF_XTT);
+            HIPCHK(launch_xtt_bf16(static_cast<const bf16_t*>(X), L.ldx, L.n_tokens, L.d_in, wsh(ctx, p.off_TpackT),
+                                   p.m_pad, p.rp, wsf(ctx, p.off_xtt), p.nsplit, st));
+        }
         HIPCHK(launch_reduce_splits(wsf(ctx, p.off_xtt), p.nsplit, L.d_in, p.rp, L.r, S, st));
     } else {
         const float* Xf = static_cast<const float*>(X);
@@ -168,6 +211,7 @@ int op_sketch_power(agzo_ctx* ctx, const agzo_layer& L, const Plan& p, const voi
 }
 
 int op_qr(agzo_ctx* ctx, const Plan& p, const float* S, int64_t d, int r, float* Q) {
+    ProfScope ps(ctx, AGZO_PROF_QR);
     HIPCHK(launch_qr(S, d, r, Q, ctx->ws + p.off_qr, ctx->flag, ctx->stream));
     return 0;
 }
@@ -177,8 +221,11 @@ int op_project(agzo_ctx* ctx, const agzo_layer& L, const Plan& p, const void* X,
     hipStream_t st = ctx->stream;
     if (L.dtype == AGZO_BF16) {
         HIPCHK(launch_pack_planes(B, L.d_in, L.r, p.rp, wsh(ctx, p.off_pack), st));
-        HIPCHK(launch_xq_bf16(static_cast<const bf16_t*>(X), L.ldx, L.n_tokens, L.d_in, wsh(ctx, p.off_pack), L.r, p.rp, P,
-                              nullptr, p.m_pad, st));
+        {
+            ProfScope ps(ctx, AGZO_PROF_XQ);
+            HIPCHK(launch_xq_bf16(static_cast<const bf16_t*>(X), L.ldx, L.n_tokens, L.d_in, wsh(ctx, p.off_pack), L.r,
+                                  p.rp, P, nullptr, p.m_pad, st));
+        }
     } else {
         HIPCHK(launch_gemm_f32(static_cast<const float*>(X), L.ldx, 1, B, L.r, 1, P, L.r, L.n_tokens, L.r, L.d_in, st));
     }
@@ -204,6 +251,7 @@ int op_forward(agzo_ctx* ctx, const agzo_layer& L, const Plan& p, const void* W,
         a.Y = Y; a.y_dtype = L.y_dtype; a.ldy = L.ldy;
         a.P = P; a.r = L.r; a.eps_signed = eps_signed; a.seed = seed;
         a.loss = la;
+        ProfScope ps(ctx, AGZO_PROF_GEMM);
         HIPCHK(launch_gemm_bf16(a, st));
     } else {
         float* Yf = Y ? static_cast<float*>(Y) : wsf(ctx, p.off_Ybuf);
@@ -214,6 +262,13 @@ int op_forward(agzo_ctx* ctx, const agzo_layer& L, const Plan& p, const void* W,
     }
     if (has_loss)
         HIPCHK(launch_finish_loss(la.partials, p.n_part, 1.0 / ((double)L.n_tokens * (double)L.d_out), loss_dev, st));
+    return 0;
+}
+
+int op_update(agzo_ctx* ctx, const agzo_layer& L, void* W, const float* B, uint64_t seed, float lr,
+              const double* g_dev) {
+    ProfScope ps(ctx, AGZO_PROF_UPDATE);
+    HIPCHK(launch_update(W, L.dtype, L.ldw, L.d_out, L.d_in, B, L.r, seed, lr, g_dev, ctx->stream));
     return 0;
 }
 
@@ -252,6 +307,7 @@ int agzo_create(agzo_ctx** out, void* hip_stream) {
     ctx->ws = nullptr;
     ctx->ws_bytes = 0;
     ctx->flag = nullptr;
+    ctx->prof = false;
     hipError_t e = hipMalloc(reinterpret_cast<void**>(&ctx->flag), 256);
     if (e == hipSuccess) e = hipMemset(ctx->flag, 0, 256);
     if (e != hipSuccess) {
@@ -267,6 +323,10 @@ void agzo_destroy(agzo_ctx* ctx) {
     (void)hipStreamSynchronize(ctx->stream);
     if (ctx->ws) (void)hipFree(ctx->ws);
     if (ctx->flag) (void)hipFree(ctx->flag);
+    for (auto& pc : ctx->pc) {
+        for (hipEvent_t e : pc.start) (void)hipEventDestroy(e);
+        for (hipEvent_t e : pc.stop) (void)hipEventDestroy(e);
+    }
     delete ctx;
 }
 
@@ -281,6 +341,30 @@ int agzo_check(agzo_ctx* ctx) {
         HIPCHK(hipMemset(ctx->flag, 0, sizeof(int)));
         return fail(ctx, AGZO_ENUMERIC, "Cholesky pivot <= 0: the sketch is rank deficient");
     }
+    return AGZO_OK;
+}
+
+int agzo_profile_enable(agzo_ctx* ctx, int32_t on) {
+    if (!ctx) return AGZO_EINVAL;
+    HIPCHK(hipStreamSynchronize(ctx->stream));
+    ctx->prof = (on != 0);
+    for (auto& pc : ctx->pc) pc.used = 0;
+    return AGZO_OK;
+}
+
+int agzo_profile_read(agzo_ctx* ctx, int32_t kind, int64_t* launches, double* total_ms) {
+    if (!ctx) return AGZO_EINVAL;
+    if (kind < 0 || kind >= AGZO_PROF_KINDS || !launches || !total_ms) return fail(ctx, AGZO_EINVAL, "bad profile query");
+    HIPCHK(hipStreamSynchronize(ctx->stream));
+    ProfClass& pc = ctx->pc[kind];
+    double sum = 0.0;
+    for (size_t i = 0; i < pc.used; ++i) {
+        float ms = 0.f;
+        HIPCHK(hipEventElapsedTime(&ms, pc.start[i], pc.stop[i]));
+        sum += ms;
+    }
+    *launches = (int64_t)pc.used;
+    *total_ms = sum;
     return AGZO_OK;
 }
 
@@ -366,7 +450,7 @@ int agzo_update(agzo_ctx* ctx, const agzo_layer* L, void* W, const float* B, uin
     if (L->dtype != AGZO_F32 && L->dtype != AGZO_BF16) return fail(ctx, AGZO_EINVAL, "dtype %d", L->dtype);
     if (L->dtype == AGZO_BF16 && (L->ldw % 8 || (reinterpret_cast<uintptr_t>(W) & 15)))
         return fail(ctx, AGZO_EINVAL, "bf16 W needs 16-byte aligned rows");
-    HIPCHK(launch_update(W, L->dtype, L->ldw, L->d_out, L->d_in, B, L->r, seed, lr, g_dev, ctx->stream));
+    TRY(op_update(ctx, *L, W, B, seed, lr, g_dev));
     return AGZO_OK;
 }
 
@@ -390,14 +474,14 @@ int agzo_step(agzo_ctx* ctx, const agzo_layer* L, void* W, const void* X, const 
     TRY(op_basis(ctx, *L, p, X, K, seed, nullptr, flags & AGZO_INIT_FEATURE, B));
     // 2. perturbed evaluations (Alg. 2, parts 2-3)
     if (flags & AGZO_NAIVE_INPLACE) {
-        HIPCHK(launch_update(W, L->dtype, L->ldw, L->d_out, L->d_in, B, L->r, seed, -eps, nullptr, st));
+        TRY(op_update(ctx, *L, W, B, seed, -eps, nullptr));
         TRY(op_forward(ctx, *L, p, W, X, nullptr, 0.f, seed, nullptr, loss, out_dev + 1));
         if (!one_sided) {
-            HIPCHK(launch_update(W, L->dtype, L->ldw, L->d_out, L->d_in, B, L->r, seed, 2.f * eps, nullptr, st));
+            TRY(op_update(ctx, *L, W, B, seed, 2.f * eps, nullptr));
             TRY(op_forward(ctx, *L, p, W, X, nullptr, 0.f, seed, nullptr, loss, out_dev + 2));
-            HIPCHK(launch_update(W, L->dtype, L->ldw, L->d_out, L->d_in, B, L->r, seed, -eps, nullptr, st));
+            TRY(op_update(ctx, *L, W, B, seed, -eps, nullptr));
         } else {
-            HIPCHK(launch_update(W, L->dtype, L->ldw, L->d_out, L->d_in, B, L->r, seed, eps, nullptr, st));
+            TRY(op_update(ctx, *L, W, B, seed, eps, nullptr));
         }
     } else {
         float* P = wsf(ctx, p.off_T);
@@ -407,7 +491,7 @@ int agzo_step(agzo_ctx* ctx, const agzo_layer* L, void* W, const void* X, const 
     }
     // 3. scalar g and the rank-r update
     HIPCHK(launch_two_point(out_dev, eps, one_sided ? 1 : 0, st));
-    HIPCHK(launch_update(W, L->dtype, L->ldw, L->d_out, L->d_in, B, L->r, seed, lr, out_dev + 3, st));
+    TRY(op_update(ctx, *L, W, B, seed, lr, out_dev + 3));
     return AGZO_OK;
 }
 

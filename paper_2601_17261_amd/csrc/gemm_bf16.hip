@@ -2,12 +2,16 @@
 //     Y = X W^T  (+ eps * (X B) G^T, the factored form of Eq. 7)   with fp32 accumulation,
 // and the loss of Sec. 4.1 (f0, f+, f-) reduced from the fp32 accumulators in the epilogue.
 //
-// Tiling: one workgroup (256 threads = 4 wave64) owns a 256 x 256 tile of Y; each wave owns a
-// 128 x 128 quadrant as 4 x 4 blocks of v_mfma_f32_32x32x16_bf16.  X and W are both K-contiguous
-// (an "NT" product), staged through LDS in 64-wide K slices, double buffered.
-// The rank-r term is accumulated by the same MFMA loop as a few extra K slices appended after
-// the d_in slices: A-operand = eps * P split in bf16 hi/lo, B-operand = G regenerated from the
+// Tiling: one workgroup owns a 256 (tokens) x 256 (outputs) tile of Y.  X and W are both
+// K-contiguous (an "NT" product) and are staged through LDS in 64-wide K slices, double buffered.
+// MFMA roles (v_mfma_f32_32x32x16_bf16): A-operand = W rows, B-operand = X rows, so a lane owns one
+// token and 16 output columns per 32x32 block; the W rows of a block are permuted on their way
+// into LDS so that those 16 columns are consecutive and the epilogue moves 16-byte vectors.
+// The rank-r term is accumulated by the same MFMA loop as a few extra K slices appended after the
+// d_in slices: one operand is eps * P split in bf16 hi/lo, the other is G regenerated from the
 // Philox seed and split likewise, so both signs share bit-identical X W^T accumulators.
+#include <stdlib.h>
+
 #include "agzo_internal.h"
 
 namespace agzo {
@@ -15,59 +19,53 @@ namespace agzo {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-constexpr int BM = 256, BN = 256, BK = 64;
+constexpr int BT = 256;                        // tile edge (tokens and outputs)
+constexpr int BK = 64;
 constexpr int CHUNKS = BK / 8;                 // 16-byte chunks per tile row
-constexpr int TILE_BYTES = BM * BK * 2;        // one operand tile: 32 KiB
+constexpr int TILE_BYTES = BT * BK * 2;        // one operand tile: 32 KiB
 
 int gemm_bf16_num_workgroups(int64_t M, int64_t N) {
-    return (int)(((M + BM - 1) / BM) * ((N + BN - 1) / BN));
+    return (int)(((M + BT - 1) / BT) * ((N + BT - 1) / BT));
 }
 
 // byte offset of 16-byte chunk `c` of row `row` inside a [256][64] bf16 tile; the XOR spreads the
-// rows of one MFMA operand read over all LDS banks.
+// 16 rows touched by one pass of a ds_read_b128 over all LDS banks.
 __device__ __forceinline__ int lds_off(int row, int c) { return row * (BK * 2) + ((c ^ ((row >> 1) & 7)) << 4); }
+
+// LDS row m' of a 32-row block holds W row perm(m'): MFMA output register e of lane half h is
+// row 8*(e/4) + 4*h + e%4 of the block, which this makes output column 16*h + e.
+__device__ __forceinline__ int w_perm(int m) { return ((m >> 2) & 1) * 16 + ((m >> 3) & 3) * 4 + (m & 3); }
 
 struct GemmParams {
     const bf16_t* X; int64_t ldx;
     const bf16_t* W; int64_t ldw;
-    int64_t M, N, K;
+    int64_t M, N, K;            // tokens, outputs, d_in
     void* Y; int y_dtype; int64_t ldy;
     const float* P; int r; int rp;
     float eps_signed; uint32_t s_lo, s_hi;
     int loss_kind; int target_dtype; const void* target; int64_t ldt; double* partials;
     int tiles_m, tiles_n;
+    int vec_ok;                 // 16-byte epilogue accesses are legal
 };
 
-__device__ __forceinline__ void compute_tile(const char* As, const char* Bs, int wm, int wn, int lane,
-                                             floatx16 (&acc)[4][4]) {
-    const int lr = lane & 31, lh = lane >> 5;
-#pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) {
-        bf16x8 a[4], b[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-            a[i] = *reinterpret_cast<const bf16x8*>(As + lds_off(wm * 128 + i * 32 + lr, kk * 2 + lh));
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-            b[j] = *reinterpret_cast<const bf16x8*>(Bs + lds_off(wn * 128 + j * 32 + lr, kk * 2 + lh));
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
-    }
-}
-
-__global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams p) {
+// WA x WB waves: WA splits the 256 outputs, WB splits the 256 tokens
+template <int WA, int WB>
+__global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
+    constexpr int NT = 64 * WA * WB;
+    constexpr int BA = BT / WA / 32;           // 32-row blocks of W per wave
+    constexpr int BB = BT / WB / 32;           // 32-row blocks of X per wave
+    constexpr int LPT = BT * CHUNKS / NT;      // 16-byte chunks per thread per operand tile
     extern __shared__ __align__(16) char smem[];
-    auto As = [&](int buf) -> char* { return smem + buf * (2 * TILE_BYTES); };
-    auto Bs = [&](int buf) -> char* { return smem + buf * (2 * TILE_BYTES) + TILE_BYTES; };
+    auto Xs = [&](int buf) -> char* { return smem + buf * (2 * TILE_BYTES); };
+    auto Ws = [&](int buf) -> char* { return smem + buf * (2 * TILE_BYTES) + TILE_BYTES; };
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wa = wave / WB, wb = wave % WB;
+    const int lr = lane & 31, lh = lane >> 5;
 
-    // workgroup -> tile: consecutive ids of one XCD (ids are dealt round-robin over the 8 XCDs)
-    // walk down a column of tiles, so an XCD's L2 keeps a W tile and streams X tiles under it.
+    // workgroup -> tile.  Ids are dealt round-robin over the 8 XCDs; give each XCD a contiguous
+    // run of tiles, walked in groups of 8 token-tiles per output-tile so that its L2 keeps a W tile
+    // and a band of X tiles.
     int64_t wg = blockIdx.x;
     const int64_t nwg = (int64_t)p.tiles_m * p.tiles_n;
     {
@@ -81,40 +79,69 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams p) {
     const int64_t in_group = wg - group * GROUP_M * p.tiles_n;
     const int64_t tm = first_m + in_group % gsz;
     const int64_t tn = in_group / gsz;
-    const int64_t m0 = tm * BM, n0 = tn * BN;
+    const int64_t m0 = tm * BT, n0 = tn * BT;
 
-    floatx16 acc[4][4];
+    floatx16 acc[BA][BB];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < BA; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < BB; ++j)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    // global -> LDS staging: thread owns chunk (tid % 8) of rows tid/8 + 32*i
+    // global -> LDS staging: thread owns chunk (tid % 8) of tile rows tid/8 + (NT/8)*i
     const int lc = tid & 7;
     const int lrow = tid >> 3;
-    uint4 ra[8], rb[8];
+    uint4 rx[LPT], rw[LPT];
+    const bf16_t* xp[LPT];
+    const bf16_t* wp[LPT];
+#pragma unroll
+    for (int i = 0; i < LPT; ++i) {
+        const int row = lrow + (NT / 8) * i;
+        const int64_t gm = min(m0 + row, p.M - 1);
+        const int64_t gn = min(n0 + (row & ~31) + w_perm(row & 31), p.N - 1);
+        xp[i] = p.X + gm * p.ldx + lc * 8;
+        wp[i] = p.W + gn * p.ldw + lc * 8;
+    }
     const int64_t nk = (p.K + BK - 1) / BK;
 
     auto gload = [&](int64_t kt) {
-        const int64_t kcol = kt * BK + lc * 8;
-        const bool kin = kcol < p.K;
+        const int64_t k0 = kt * BK;
+        const bool kin = k0 + lc * 8 < p.K;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int row = lrow + 32 * i;
-            int64_t gm = min(m0 + row, p.M - 1);
-            int64_t gn = min(n0 + row, p.N - 1);
-            ra[i] = kin ? *reinterpret_cast<const uint4*>(p.X + gm * p.ldx + kcol) : make_uint4(0, 0, 0, 0);
-            rb[i] = kin ? *reinterpret_cast<const uint4*>(p.W + gn * p.ldw + kcol) : make_uint4(0, 0, 0, 0);
+        for (int i = 0; i < LPT; ++i) {
+            rx[i] = kin ? *reinterpret_cast<const uint4*>(xp[i] + k0) : make_uint4(0, 0, 0, 0);
+            rw[i] = kin ? *reinterpret_cast<const uint4*>(wp[i] + k0) : make_uint4(0, 0, 0, 0);
         }
     };
     auto lstore = [&](int buf) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int row = lrow + 32 * i;
-            *reinterpret_cast<uint4*>(As(buf) + lds_off(row, lc)) = ra[i];
-            *reinterpret_cast<uint4*>(Bs(buf) + lds_off(row, lc)) = rb[i];
+        for (int i = 0; i < LPT; ++i) {
+            const int row = lrow + (NT / 8) * i;
+            *reinterpret_cast<uint4*>(Xs(buf) + lds_off(row, lc)) = rx[i];
+            *reinterpret_cast<uint4*>(Ws(buf) + lds_off(row, lc)) = rw[i];
+        }
+    };
+    auto compute = [&](const char* xs, const char* ws) {
+        bf16x8 a[2][BA], b[2][BB];
+        auto frag = [&](int kk, int s) {
+#pragma unroll
+            for (int i = 0; i < BA; ++i)
+                a[s][i] = *reinterpret_cast<const bf16x8*>(ws + lds_off(wa * (BT / WA) + i * 32 + lr, kk * 2 + lh));
+#pragma unroll
+            for (int j = 0; j < BB; ++j)
+                b[s][j] = *reinterpret_cast<const bf16x8*>(xs + lds_off(wb * (BT / WB) + j * 32 + lr, kk * 2 + lh));
+        };
+        frag(0, 0);
+#pragma unroll
+        for (int kk = 0; kk < BK / 16; ++kk) {
+            const int s = kk & 1;
+            if (kk + 1 < BK / 16) frag(kk + 1, s ^ 1);
+#pragma unroll
+            for (int i = 0; i < BA; ++i)
+#pragma unroll
+                for (int j = 0; j < BB; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[s][i], b[s][j], acc[i][j], 0, 0, 0);
         }
     };
 
@@ -124,12 +151,12 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams p) {
     for (int64_t kt = 0; kt < nk; ++kt) {
         const int cur = (int)(kt & 1);
         if (kt + 1 < nk) gload(kt + 1);
-        compute_tile(As(cur), Bs(cur), wm, wn, lane, acc);
+        compute(Xs(cur), Ws(cur));
         if (kt + 1 < nk) lstore(cur ^ 1);
         __syncthreads();
     }
 
-    // ---- rank-r term: extra K slices [Ph|Ph|Pl] x [Gh|Gl|Gh] --------------------------------
+    // ---- rank-r term: extra K slices, X side [Ph|Ph|Pl], W side [Gh|Gl|Gh] ---------------------
     if (p.P != nullptr) {
         const int rp = p.rp;                  // r rounded up to 16
         const int kext = 3 * rp;              // columns of the extended operands
@@ -137,22 +164,23 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams p) {
         const int kchunks = rp / 8;           // 8-column chunks of P' and G per row
         for (int et = 0; et < next; ++et) {
             // chunks of this slice that lie beyond the extended width are zero
-            for (int e = tid; e < BM * CHUNKS; e += 256) {
+            for (int e = tid; e < BT * CHUNKS; e += NT) {
                 const int row = e >> 3, c = e & 7;
                 if (et * BK + c * 8 >= kext) {
-                    *reinterpret_cast<uint4*>(As(0) + lds_off(row, c)) = make_uint4(0, 0, 0, 0);
-                    *reinterpret_cast<uint4*>(Bs(0) + lds_off(row, c)) = make_uint4(0, 0, 0, 0);
+                    *reinterpret_cast<uint4*>(Xs(0) + lds_off(row, c)) = make_uint4(0, 0, 0, 0);
+                    *reinterpret_cast<uint4*>(Ws(0) + lds_off(row, c)) = make_uint4(0, 0, 0, 0);
                 }
             }
-            // one item = 8 consecutive k of one tile row: P' (for X row m0+row) and G (for W row n0+row),
-            // written to each of the three segments that falls into this slice
-            for (int e = tid; e < BM * kchunks; e += 256) {
+            // one item = 8 consecutive k of one tile row: P' for the token of X-tile row `row`, G for
+            // the output held by W-tile row `row`; written to each segment that falls into this slice
+            for (int e = tid; e < BT * kchunks; e += NT) {
                 const int row = e / kchunks, k0 = (e - row * kchunks) * 8;
                 bool need = false;
 #pragma unroll
                 for (int seg = 0; seg < 3; ++seg) need |= ((seg * rp + k0) / BK == et);
                 if (!need) continue;
-                const int64_t gm = m0 + row, gn = n0 + row;
+                const int64_t gm = m0 + row;
+                const int64_t gn = n0 + (row & ~31) + w_perm(row & 31);
                 float pv[8], gv[8];
 #pragma unroll
                 for (int i = 0; i < 8; ++i)
@@ -188,41 +216,86 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams p) {
                     const int c = (col0 - et * BK) >> 3;
                     const uint32_t* av = (seg == 2) ? pl : ph;   // [Ph | Ph | Pl]
                     const uint32_t* bv = (seg == 1) ? gl : gh;   // [Gh | Gl | Gh]
-                    *reinterpret_cast<uint4*>(As(0) + lds_off(row, c)) = make_uint4(av[0], av[1], av[2], av[3]);
-                    *reinterpret_cast<uint4*>(Bs(0) + lds_off(row, c)) = make_uint4(bv[0], bv[1], bv[2], bv[3]);
+                    *reinterpret_cast<uint4*>(Xs(0) + lds_off(row, c)) = make_uint4(av[0], av[1], av[2], av[3]);
+                    *reinterpret_cast<uint4*>(Ws(0) + lds_off(row, c)) = make_uint4(bv[0], bv[1], bv[2], bv[3]);
                 }
             }
             __syncthreads();
-            compute_tile(As(0), Bs(0), wm, wn, lane, acc);
+            compute(Xs(0), Ws(0));
             __syncthreads();
         }
     }
 
-    // ---- epilogue: optional store, loss partial ---------------------------------------------
-    const int lr = lane & 31, lh = lane >> 5;
+    // ---- epilogue: lane = one token, 16 consecutive outputs per block ---------------------------
     double part = 0.0;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int64_t col = n0 + wn * 128 + j * 32 + lr;
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int64_t row = m0 + wm * 128 + i * 32 + (e >> 2) * 8 + lh * 4 + (e & 3);
-                if (row < p.M && col < p.N) {
-                    const float y = acc[i][j][e];
-                    if (p.Y != nullptr) {
-                        if (p.y_dtype == AGZO_BF16)
-                            reinterpret_cast<bf16_t*>(p.Y)[row * p.ldy + col] = f32_to_bf16(y);
-                        else
-                            reinterpret_cast<float*>(p.Y)[row * p.ldy + col] = y;
+    const bool y_f32 = (p.Y != nullptr) && p.y_dtype != AGZO_BF16;
+    const bool y_bf16 = (p.Y != nullptr) && p.y_dtype == AGZO_BF16;
+    const bool l_f32 = p.loss_kind == AGZO_LOSS_MSE && p.target_dtype != AGZO_BF16;
+    const bool l_bf16 = p.loss_kind == AGZO_LOSS_MSE && p.target_dtype == AGZO_BF16;
+#pragma clang loop unroll(full)
+    for (int j = 0; j < BB; ++j) {
+        const int64_t row = m0 + wb * (BT / WB) + j * 32 + lr;
+#pragma clang loop unroll(full)
+        for (int i = 0; i < BA; ++i) {
+            const int64_t col0 = n0 + wa * (BT / WA) + i * 32 + lh * 16;
+            const floatx16 v = acc[i][j];
+            if (row >= p.M || col0 >= p.N) continue;
+            if (p.vec_ok && col0 + 16 <= p.N) {
+                if (y_f32) {
+                    float4* dst = reinterpret_cast<float4*>(reinterpret_cast<float*>(p.Y) + row * p.ldy + col0);
+#pragma clang loop unroll(full)
+                    for (int q = 0; q < 4; ++q) dst[q] = make_float4(v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]);
+                }
+                if (y_bf16) {
+                    uint4* dst = reinterpret_cast<uint4*>(reinterpret_cast<bf16_t*>(p.Y) + row * p.ldy + col0);
+                    uint32_t w[8];
+#pragma clang loop unroll(full)
+                    for (int q = 0; q < 8; ++q)
+                        w[q] = (uint32_t)f32_to_bf16(v[2 * q]) | ((uint32_t)f32_to_bf16(v[2 * q + 1]) << 16);
+                    dst[0] = make_uint4(w[0], w[1], w[2], w[3]);
+                    dst[1] = make_uint4(w[4], w[5], w[6], w[7]);
+                }
+                if (l_f32) {
+                    const float4* src = reinterpret_cast<const float4*>(reinterpret_cast<const float*>(p.target) + row * p.ldt + col0);
+#pragma clang loop unroll(full)
+                    for (int q = 0; q < 4; ++q) {
+                        const float4 t = src[q];
+                        const double d0 = (double)v[4 * q] - (double)t.x, d1 = (double)v[4 * q + 1] - (double)t.y;
+                        const double d2 = (double)v[4 * q + 2] - (double)t.z, d3 = (double)v[4 * q + 3] - (double)t.w;
+                        part = fma(d0, d0, part); part = fma(d1, d1, part);
+                        part = fma(d2, d2, part); part = fma(d3, d3, part);
                     }
-                    if (p.loss_kind == AGZO_LOSS_MSE) {
-                        const float tv = (p.target_dtype == AGZO_BF16)
-                                             ? bf16_to_f32(reinterpret_cast<const bf16_t*>(p.target)[row * p.ldt + col])
-                                             : reinterpret_cast<const float*>(p.target)[row * p.ldt + col];
-                        const double d = (double)y - (double)tv;
-                        part = fma(d, d, part);
+                }
+                if (l_bf16) {
+                    const uint4* src = reinterpret_cast<const uint4*>(reinterpret_cast<const bf16_t*>(p.target) + row * p.ldt + col0);
+#pragma clang loop unroll(full)
+                    for (int q = 0; q < 2; ++q) {
+                        const uint4 t = src[q];
+                        const uint32_t tw[4] = {t.x, t.y, t.z, t.w};
+#pragma clang loop unroll(full)
+                        for (int u = 0; u < 4; ++u) {
+                            const double d0 = (double)v[8 * q + 2 * u] - (double)__uint_as_float(tw[u] << 16);
+                            const double d1 = (double)v[8 * q + 2 * u + 1] - (double)__uint_as_float(tw[u] & 0xFFFF0000u);
+                            part = fma(d0, d0, part); part = fma(d1, d1, part);
+                        }
+                    }
+                }
+            } else {
+#pragma clang loop unroll(full)
+                for (int e = 0; e < 16; ++e) {
+                    const int64_t col = col0 + e;
+                    if (col < p.N) {
+                        const float y = v[e];
+                        if (y_f32) reinterpret_cast<float*>(p.Y)[row * p.ldy + col] = y;
+                        if (y_bf16) reinterpret_cast<bf16_t*>(p.Y)[row * p.ldy + col] = f32_to_bf16(y);
+                        if (l_f32) {
+                            const double dd = (double)y - (double)reinterpret_cast<const float*>(p.target)[row * p.ldt + col];
+                            part = fma(dd, dd, part);
+                        }
+                        if (l_bf16) {
+                            const double dd = (double)y - (double)bf16_to_f32(reinterpret_cast<const bf16_t*>(p.target)[row * p.ldt + col]);
+                            part = fma(dd, dd, part);
+                        }
                     }
                 }
             }
@@ -232,12 +305,27 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams p) {
         double* red = reinterpret_cast<double*>(smem);
         red[tid] = part;
         __syncthreads();
-        for (int s = 128; s > 0; s >>= 1) {
+        for (int s = NT / 2; s > 0; s >>= 1) {
             if (tid < s) red[tid] += red[tid + s];
             __syncthreads();
         }
         if (tid == 0) p.partials[tm * p.tiles_n + tn] = red[0];
     }
+}
+
+template <int WA, int WB>
+static hipError_t launch_variant(const GemmParams& p, hipStream_t st) {
+    static bool attr_set = false;
+    const int smem = 4 * TILE_BYTES;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_bf16_kernel<WA, WB>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    dim3 grid((unsigned)((int64_t)p.tiles_m * p.tiles_n));
+    hipLaunchKernelGGL((gemm_bf16_kernel<WA, WB>), grid, dim3(64 * WA * WB), smem, st, p);
+    return hipGetLastError();
 }
 
 hipError_t launch_gemm_bf16(const GemmBf16Args& a, hipStream_t st) {
@@ -250,19 +338,23 @@ hipError_t launch_gemm_bf16(const GemmBf16Args& a, hipStream_t st) {
     p.eps_signed = a.eps_signed; p.s_lo = (uint32_t)a.seed; p.s_hi = (uint32_t)(a.seed >> 32);
     p.loss_kind = a.loss.kind; p.target_dtype = a.loss.target_dtype; p.target = a.loss.target;
     p.ldt = a.loss.ldt; p.partials = a.loss.partials;
-    p.tiles_m = (int)((a.M + BM - 1) / BM);
-    p.tiles_n = (int)((a.N + BN - 1) / BN);
-    static bool attr_set = false;
-    const int smem = 4 * TILE_BYTES;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_bf16_kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-        if (e != hipSuccess) return e;
-        attr_set = true;
+    p.tiles_m = (int)((a.M + BT - 1) / BT);
+    p.tiles_n = (int)((a.N + BT - 1) / BT);
+    bool vec = true;
+    if (a.Y) vec = vec && (a.ldy % 8 == 0) && ((reinterpret_cast<uintptr_t>(a.Y) & 15) == 0);
+    if (a.loss.kind == AGZO_LOSS_MSE)
+        vec = vec && (a.loss.ldt % 8 == 0) && ((reinterpret_cast<uintptr_t>(a.loss.target) & 15) == 0);
+    p.vec_ok = vec ? 1 : 0;
+    static int variant = -1;
+    if (variant < 0) {
+        const char* v = getenv("AGZO_GEMM_VARIANT");
+        variant = v ? atoi(v) : 0;
     }
-    dim3 grid((unsigned)((int64_t)p.tiles_m * p.tiles_n));
-    hipLaunchKernelGGL(gemm_bf16_kernel, grid, dim3(256), smem, st, p);
-    return hipGetLastError();
+    switch (variant) {
+        case 1: return launch_variant<4, 2>(p, st);
+        case 2: return launch_variant<2, 4>(p, st);
+        default: return launch_variant<2, 2>(p, st);
+    }
 }
 
 }  // namespace agzo

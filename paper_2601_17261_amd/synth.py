@@ -97,13 +97,12 @@ def single_layer_problem(seed, n, d_in, d_out, kind="lowrank", storage="f32", ta
 # ----------------------------------------------------------------------------
 # full-size inputs generated on the device (outside any timed region)
 # ----------------------------------------------------------------------------
-def device_powerlaw_problem(seed, n, d_in, d_out, device="cuda", n_outliers=5, outlier_scale=20.0):
-    """bf16 (W, X) and fp32 Y* on the device for a Qwen3-shaped projection; same recipe
-    as x_powerlaw_outliers / shifted_target, drawn from torch's seeded generator."""
+def device_powerlaw_x(seed, n, d_in, device="cuda", n_outliers=5, outlier_scale=20.0):
+    """bf16 activations on the device, same recipe as x_powerlaw_outliers, drawn from torch's
+    seeded generator."""
     gen = torch.Generator(device=device)
     gen.manual_seed(int(seed))
     f32 = dict(device=device, dtype=torch.float32, generator=gen)
-    W = (torch.randn(d_out, d_in, **f32) * 0.02).to(torch.bfloat16)
     Zm = torch.randn(n, d_in, **f32) / float(np.sqrt(n))
     Zm *= (1.0 / torch.arange(1, d_in + 1, device=device, dtype=torch.float32))[None, :]
     V, _ = torch.linalg.qr(torch.randn(d_in, d_in, **f32))
@@ -112,9 +111,18 @@ def device_powerlaw_problem(seed, n, d_in, d_out, device="cuda", n_outliers=5, o
     ch = torch.randperm(d_in, device=device, generator=gen)[:n_outliers]
     X[:, ch] *= outlier_scale
     X /= X.square().mean().sqrt()
-    X = X.to(torch.bfloat16)
+    return X.to(torch.bfloat16)
+
+
+def device_weights_and_target(seed, X, d_out, device="cuda"):
+    """bf16 W ~ N(0, 0.02^2) and the fp32 MSE target Y* = X W*^T, W* = W + rank-4 shift (entry std 0.05)."""
+    gen = torch.Generator(device=device)
+    gen.manual_seed(int(seed))
+    f32 = dict(device=device, dtype=torch.float32, generator=gen)
+    d_in = X.shape[1]
+    W = (torch.randn(d_out, d_in, **f32) * 0.02).to(torch.bfloat16)
     P = torch.randn(d_out, 4, **f32)
     Q = torch.randn(d_in, 4, **f32)
     Wstar = W.float() + (0.05 / 2.0) * (P @ Q.T)
     Ystar = X.float() @ Wstar.T
-    return W, X, Ystar
+    return W, Ystar
