@@ -54,7 +54,6 @@ __global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
     constexpr int NT = 64 * WA * WB;
     constexpr int BA = BT / WA / 32;           // 32-row blocks of W per wave
     constexpr int BB = BT / WB / 32;           // 32-row blocks of X per wave
-    constexpr int LPT = BT * CHUNKS / NT;      // 16-byte chunks per thread per operand tile
     extern __shared__ __align__(16) char smem[];
     auto Xs = [&](int buf) -> char* { return smem + buf * (2 * TILE_BYTES); };
     auto Ws = [&](int buf) -> char* { return smem + buf * (2 * TILE_BYTES) + TILE_BYTES; };
@@ -89,142 +88,179 @@ __global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    // global -> LDS staging: thread owns chunk (tid % 8) of tile rows tid/8 + (NT/8)*i
-    const int lc = tid & 7;
-    const int lrow = tid >> 3;
-    uint4 rx[LPT], rw[LPT];
-    const bf16_t* xp[LPT];
-    const bf16_t* wp[LPT];
+    // ---- operand staging ------------------------------------------------------------------------
+    // Whole 64-wide K slices travel global -> LDS without passing through registers
+    // (global_load_lds_dwordx4: lane l of a wave writes its 16 bytes at LDS base + 16*l, so one
+    // instruction fills 8 consecutive tile rows).  The bank swizzle is applied on the global side by
+    // choosing which 16-byte chunk of its row a lane fetches.  Slices that are not plain copies of
+    // memory (the ragged end of d_in, the rank-r extension) are written by the threads themselves.
+    constexpr int GP = 32 / (WA * WB);          // 8-row groups per wave per operand
+    static_assert(GP == 4 || GP == 8, "loads are spread over the four MFMA sub-steps");
+    uint32_t xo[GP], wo[GP];                    // element offsets from the tile's first row
+    const bf16_t* xbase = p.X + m0 * p.ldx;
+    const bf16_t* wbase = p.W + n0 * p.ldw;
 #pragma unroll
-    for (int i = 0; i < LPT; ++i) {
-        const int row = lrow + (NT / 8) * i;
-        const int64_t gm = min(m0 + row, p.M - 1);
-        const int64_t gn = min(n0 + (row & ~31) + w_perm(row & 31), p.N - 1);
-        xp[i] = p.X + gm * p.ldx + lc * 8;
-        wp[i] = p.W + gn * p.ldw + lc * 8;
+    for (int t = 0; t < GP; ++t) {
+        const int row = 8 * (wave + WA * WB * t) + (lane >> 3);
+        const int c = (lane & 7) ^ ((row >> 1) & 7);
+        const int64_t gm = min((int64_t)row, p.M - 1 - m0);
+        const int64_t gn = min((int64_t)((row & ~31) + w_perm(row & 31)), p.N - 1 - n0);
+        xo[t] = (uint32_t)(gm * p.ldx + c * 8);
+        wo[t] = (uint32_t)(gn * p.ldw + c * 8);
     }
-    const int64_t nk = (p.K + BK - 1) / BK;
+    const int nfull = (int)(p.K / BK);
+    const int ntail = (p.K % BK) ? 1 : 0;
+    const int rp = p.rp;                        // r rounded up to 16
+    const int kext = 3 * rp;                    // width of the extended operands [Ph|Ph|Pl] x [Gh|Gl|Gh]
+    const int next = (p.P != nullptr) ? (kext + BK - 1) / BK : 0;
+    const int total = nfull + ntail + next;
 
-    auto gload = [&](int64_t kt) {
-        const int64_t k0 = kt * BK;
-        const bool kin = k0 + lc * 8 < p.K;
-#pragma unroll
-        for (int i = 0; i < LPT; ++i) {
-            rx[i] = kin ? *reinterpret_cast<const uint4*>(xp[i] + k0) : make_uint4(0, 0, 0, 0);
-            rw[i] = kin ? *reinterpret_cast<const uint4*>(wp[i] + k0) : make_uint4(0, 0, 0, 0);
+    // ragged last slice of d_in: chunks past d_in are zero
+    auto fill_tail = [&](int buf) {
+        for (int e = tid; e < BT * CHUNKS; e += NT) {
+            const int row = e >> 3, c = e & 7;
+            const int64_t kcol = (int64_t)nfull * BK + c * 8;
+            uint4 vx = make_uint4(0, 0, 0, 0), vw = vx;
+            if (kcol < p.K) {
+                const int64_t gm = min((int64_t)row, p.M - 1 - m0);
+                const int64_t gn = min((int64_t)((row & ~31) + w_perm(row & 31)), p.N - 1 - n0);
+                vx = *reinterpret_cast<const uint4*>(xbase + gm * p.ldx + kcol);
+                vw = *reinterpret_cast<const uint4*>(wbase + gn * p.ldw + kcol);
+            }
+            *reinterpret_cast<uint4*>(Xs(buf) + lds_off(row, c)) = vx;
+            *reinterpret_cast<uint4*>(Ws(buf) + lds_off(row, c)) = vw;
         }
     };
-    auto lstore = [&](int buf) {
+    // slice `et` of the rank-r extension: X side eps*P as [hi|hi|lo], W side G as [hi|lo|hi]
+    auto fill_ext = [&](int buf, int et) {
+        const int kchunks = rp / 8;             // 8-column chunks of P' and G per row
+        for (int e = tid; e < BT * CHUNKS; e += NT) {
+            const int row = e >> 3, c = e & 7;
+            if (et * BK + c * 8 >= kext) {      // beyond the extended width: zero
+                *reinterpret_cast<uint4*>(Xs(buf) + lds_off(row, c)) = make_uint4(0, 0, 0, 0);
+                *reinterpret_cast<uint4*>(Ws(buf) + lds_off(row, c)) = make_uint4(0, 0, 0, 0);
+            }
+        }
+        // one item = 8 consecutive k of one tile row: P' for the token of X-tile row `row`, G for the
+        // output held by W-tile row `row`; written to each segment that falls into this slice
+        for (int e = tid; e < BT * kchunks; e += NT) {
+            const int row = e / kchunks, k0 = (e - row * kchunks) * 8;
+            bool need = false;
 #pragma unroll
-        for (int i = 0; i < LPT; ++i) {
-            const int row = lrow + (NT / 8) * i;
-            *reinterpret_cast<uint4*>(Xs(buf) + lds_off(row, lc)) = rx[i];
-            *reinterpret_cast<uint4*>(Ws(buf) + lds_off(row, lc)) = rw[i];
+            for (int seg = 0; seg < 3; ++seg) need |= ((seg * rp + k0) / BK == et);
+            if (!need) continue;
+            const int64_t gm = m0 + row;
+            const int64_t gn = n0 + (row & ~31) + w_perm(row & 31);
+            float pv[8], gv[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                pv[i] = (gm < p.M && k0 + i < p.r) ? p.eps_signed * p.P[gm * p.r + k0 + i] : 0.f;
+            {
+                float4 z0 = make_float4(0.f, 0.f, 0.f, 0.f), z1 = z0;
+                if (gn < p.N) {
+                    if (k0 < p.r) z0 = philox_normal4(p.s_lo, p.s_hi, AGZO_TAG_G, (uint32_t)gn, (uint32_t)(k0 >> 2));
+                    if (k0 + 4 < p.r)
+                        z1 = philox_normal4(p.s_lo, p.s_hi, AGZO_TAG_G, (uint32_t)gn, (uint32_t)((k0 >> 2) + 1));
+                }
+                const float t[8] = {z0.x, z0.y, z0.z, z0.w, z1.x, z1.y, z1.z, z1.w};
+#pragma unroll
+                for (int i = 0; i < 8; ++i) gv[i] = (k0 + i < p.r) ? t[i] : 0.f;
+            }
+            uint32_t ph[4] = {0, 0, 0, 0}, pl[4] = {0, 0, 0, 0}, gh[4] = {0, 0, 0, 0}, gl[4] = {0, 0, 0, 0};
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const bf16_t a_hi = f32_to_bf16(pv[i]);
+                const bf16_t a_lo = f32_to_bf16(pv[i] - bf16_to_f32(a_hi));
+                const bf16_t b_hi = f32_to_bf16(gv[i]);
+                const bf16_t b_lo = f32_to_bf16(gv[i] - bf16_to_f32(b_hi));
+                const int sh = (i & 1) * 16;
+                ph[i >> 1] |= ((uint32_t)a_hi) << sh;
+                pl[i >> 1] |= ((uint32_t)a_lo) << sh;
+                gh[i >> 1] |= ((uint32_t)b_hi) << sh;
+                gl[i >> 1] |= ((uint32_t)b_lo) << sh;
+            }
+#pragma unroll
+            for (int seg = 0; seg < 3; ++seg) {
+                const int col0 = seg * rp + k0;
+                if (col0 / BK != et) continue;
+                const int c = (col0 - et * BK) >> 3;
+                const uint32_t* av = (seg == 2) ? pl : ph;   // [Ph | Ph | Pl]
+                const uint32_t* bv = (seg == 1) ? gl : gh;   // [Gh | Gl | Gh]
+                *reinterpret_cast<uint4*>(Xs(buf) + lds_off(row, c)) = make_uint4(av[0], av[1], av[2], av[3]);
+                *reinterpret_cast<uint4*>(Ws(buf) + lds_off(row, c)) = make_uint4(bv[0], bv[1], bv[2], bv[3]);
+            }
         }
     };
-    auto compute = [&](const char* xs, const char* ws) {
+    auto fill_manual = [&](int it, int buf) {
+        if (it < nfull + ntail) fill_tail(buf); else fill_ext(buf, it - nfull - ntail);
+    };
+    typedef const __attribute__((address_space(1))) void* gptr_t;
+    typedef __attribute__((address_space(3))) void* lptr_t;
+
+    // first slice
+    if (nfull > 0) {
+#pragma unroll
+        for (int t = 0; t < GP; ++t) {
+            const int g = wave + WA * WB * t;
+            __builtin_amdgcn_global_load_lds((gptr_t)(xbase + xo[t]), (lptr_t)(Xs(0) + g * 1024), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((gptr_t)(wbase + wo[t]), (lptr_t)(Ws(0) + g * 1024), 16, 0, 0);
+        }
+    } else {
+        fill_manual(0, 0);
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);         // vmcnt(0): the LDS-direct loads have landed
+    __syncthreads();
+
+    // main loop: slice `it` is multiplied from buffer it&1 while slice it+1 is brought into the other;
+    // the direct loads of the next slice are issued a few at a time between the MFMA sub-steps so
+    // that their LDS writes do not arrive in one burst
+    for (int it = 0; it < total; ++it) {
+        const int cur = it & 1;
+        const bool dma_next = it + 1 < nfull;
+        if (!dma_next && it + 1 < total) fill_manual(it + 1, cur ^ 1);
+        const char* xs = Xs(cur);
+        const char* ws = Ws(cur);
+        char* nxs = Xs(cur ^ 1);
+        char* nws = Ws(cur ^ 1);
+        const bf16_t* xk = xbase + (int64_t)(it + 1) * BK;
+        const bf16_t* wk = wbase + (int64_t)(it + 1) * BK;
         bf16x8 a[2][BA], b[2][BB];
-        auto frag = [&](int kk, int s) {
 #pragma unroll
-            for (int i = 0; i < BA; ++i)
-                a[s][i] = *reinterpret_cast<const bf16x8*>(ws + lds_off(wa * (BT / WA) + i * 32 + lr, kk * 2 + lh));
+        for (int i = 0; i < BA; ++i)
+            a[0][i] = *reinterpret_cast<const bf16x8*>(ws + lds_off(wa * (BT / WA) + i * 32 + lr, lh));
 #pragma unroll
-            for (int j = 0; j < BB; ++j)
-                b[s][j] = *reinterpret_cast<const bf16x8*>(xs + lds_off(wb * (BT / WB) + j * 32 + lr, kk * 2 + lh));
-        };
-        frag(0, 0);
+        for (int j = 0; j < BB; ++j)
+            b[0][j] = *reinterpret_cast<const bf16x8*>(xs + lds_off(wb * (BT / WB) + j * 32 + lr, lh));
 #pragma unroll
         for (int kk = 0; kk < BK / 16; ++kk) {
             const int s = kk & 1;
-            if (kk + 1 < BK / 16) frag(kk + 1, s ^ 1);
+            if (kk + 1 < BK / 16) {
+#pragma unroll
+                for (int i = 0; i < BA; ++i)
+                    a[s ^ 1][i] = *reinterpret_cast<const bf16x8*>(ws + lds_off(wa * (BT / WA) + i * 32 + lr, (kk + 1) * 2 + lh));
+#pragma unroll
+                for (int j = 0; j < BB; ++j)
+                    b[s ^ 1][j] = *reinterpret_cast<const bf16x8*>(xs + lds_off(wb * (BT / WB) + j * 32 + lr, (kk + 1) * 2 + lh));
+            }
+            if (dma_next) {
+#pragma unroll
+                for (int t = 0; t < GP; ++t) {
+                    if ((t * 4) / GP != kk) continue;
+                    const int g = wave + WA * WB * t;
+                    __builtin_amdgcn_global_load_lds((gptr_t)(xk + xo[t]), (lptr_t)(nxs + g * 1024), 16, 0, 0);
+                    __builtin_amdgcn_global_load_lds((gptr_t)(wk + wo[t]), (lptr_t)(nws + g * 1024), 16, 0, 0);
+                }
+            }
 #pragma unroll
             for (int i = 0; i < BA; ++i)
 #pragma unroll
                 for (int j = 0; j < BB; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[s][i], b[s][j], acc[i][j], 0, 0, 0);
         }
-    };
-
-    gload(0);
-    lstore(0);
-    __syncthreads();
-    for (int64_t kt = 0; kt < nk; ++kt) {
-        const int cur = (int)(kt & 1);
-        if (kt + 1 < nk) gload(kt + 1);
-        compute(Xs(cur), Ws(cur));
-        if (kt + 1 < nk) lstore(cur ^ 1);
+        __builtin_amdgcn_s_waitcnt(0x0F70);
         __syncthreads();
     }
 
-    // ---- rank-r term: extra K slices, X side [Ph|Ph|Pl], W side [Gh|Gl|Gh] ---------------------
-    if (p.P != nullptr) {
-        const int rp = p.rp;                  // r rounded up to 16
-        const int kext = 3 * rp;              // columns of the extended operands
-        const int next = (kext + BK - 1) / BK;
-        const int kchunks = rp / 8;           // 8-column chunks of P' and G per row
-        for (int et = 0; et < next; ++et) {
-            // chunks of this slice that lie beyond the extended width are zero
-            for (int e = tid; e < BT * CHUNKS; e += NT) {
-                const int row = e >> 3, c = e & 7;
-                if (et * BK + c * 8 >= kext) {
-                    *reinterpret_cast<uint4*>(Xs(0) + lds_off(row, c)) = make_uint4(0, 0, 0, 0);
-                    *reinterpret_cast<uint4*>(Ws(0) + lds_off(row, c)) = make_uint4(0, 0, 0, 0);
-                }
-            }
-            // one item = 8 consecutive k of one tile row: P' for the token of X-tile row `row`, G for
-            // the output held by W-tile row `row`; written to each segment that falls into this slice
-            for (int e = tid; e < BT * kchunks; e += NT) {
-                const int row = e / kchunks, k0 = (e - row * kchunks) * 8;
-                bool need = false;
-#pragma unroll
-                for (int seg = 0; seg < 3; ++seg) need |= ((seg * rp + k0) / BK == et);
-                if (!need) continue;
-                const int64_t gm = m0 + row;
-                const int64_t gn = n0 + (row & ~31) + w_perm(row & 31);
-                float pv[8], gv[8];
-#pragma unroll
-                for (int i = 0; i < 8; ++i)
-                    pv[i] = (gm < p.M && k0 + i < p.r) ? p.eps_signed * p.P[gm * p.r + k0 + i] : 0.f;
-                {
-                    float4 z0 = make_float4(0.f, 0.f, 0.f, 0.f), z1 = z0;
-                    if (gn < p.N) {
-                        if (k0 < p.r) z0 = philox_normal4(p.s_lo, p.s_hi, AGZO_TAG_G, (uint32_t)gn, (uint32_t)(k0 >> 2));
-                        if (k0 + 4 < p.r)
-                            z1 = philox_normal4(p.s_lo, p.s_hi, AGZO_TAG_G, (uint32_t)gn, (uint32_t)((k0 >> 2) + 1));
-                    }
-                    const float t[8] = {z0.x, z0.y, z0.z, z0.w, z1.x, z1.y, z1.z, z1.w};
-#pragma unroll
-                    for (int i = 0; i < 8; ++i) gv[i] = (k0 + i < p.r) ? t[i] : 0.f;
-                }
-                uint32_t ph[4] = {0, 0, 0, 0}, pl[4] = {0, 0, 0, 0}, gh[4] = {0, 0, 0, 0}, gl[4] = {0, 0, 0, 0};
-#pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    const bf16_t a_hi = f32_to_bf16(pv[i]);
-                    const bf16_t a_lo = f32_to_bf16(pv[i] - bf16_to_f32(a_hi));
-                    const bf16_t b_hi = f32_to_bf16(gv[i]);
-                    const bf16_t b_lo = f32_to_bf16(gv[i] - bf16_to_f32(b_hi));
-                    const int sh = (i & 1) * 16;
-                    ph[i >> 1] |= ((uint32_t)a_hi) << sh;
-                    pl[i >> 1] |= ((uint32_t)a_lo) << sh;
-                    gh[i >> 1] |= ((uint32_t)b_hi) << sh;
-                    gl[i >> 1] |= ((uint32_t)b_lo) << sh;
-                }
-#pragma unroll
-                for (int seg = 0; seg < 3; ++seg) {
-                    const int col0 = seg * rp + k0;
-                    if (col0 / BK != et) continue;
-                    const int c = (col0 - et * BK) >> 3;
-                    const uint32_t* av = (seg == 2) ? pl : ph;   // [Ph | Ph | Pl]
-                    const uint32_t* bv = (seg == 1) ? gl : gh;   // [Gh | Gl | Gh]
-                    *reinterpret_cast<uint4*>(Xs(0) + lds_off(row, c)) = make_uint4(av[0], av[1], av[2], av[3]);
-                    *reinterpret_cast<uint4*>(Ws(0) + lds_off(row, c)) = make_uint4(bv[0], bv[1], bv[2], bv[3]);
-                }
-            }
-            __syncthreads();
-            compute(Xs(0), Ws(0));
-            __syncthreads();
-        }
-    }
 
     // ---- epilogue: lane = one token, 16 consecutive outputs per block ---------------------------
     double part = 0.0;
@@ -352,8 +388,8 @@ hipError_t launch_gemm_bf16(const GemmBf16Args& a, hipStream_t st) {
     }
     switch (variant) {
         case 1: return launch_variant<4, 2>(p, st);
-        case 2: return launch_variant<2, 4>(p, st);
-        default: return launch_variant<2, 2>(p, st);
+        case 2: return launch_variant<2, 2>(p, st);
+        default: return launch_variant<2, 4>(p, st);
     }
 }
 
