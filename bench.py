@@ -76,6 +76,8 @@ def main():
     ap.add_argument("--rank", type=int, default=16)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--naive", action="store_true", help="time the perturb-in-place / undo comparator instead")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (known traffic) so counter runs can be scaled")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives are part of it); use --gpus 1",
@@ -100,6 +102,12 @@ def main():
         for li, (L, W, X, loss) in enumerate(descs):
             ctx.step(L, W, X, loss, K, eps, lr, 1000 * step + li, flags, out[li])
 
+    if args.calibrate_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)            # 1 GiB read + 1 GiB written by one elementwise kernel
+        torch.cuda.synchronize()
+        del src, dst
     for s in range(args.warmup):
         one_step(s)
     ctx.check()

@@ -103,11 +103,22 @@ def device_powerlaw_x(seed, n, d_in, device="cuda", n_outliers=5, outlier_scale=
     gen = torch.Generator(device=device)
     gen.manual_seed(int(seed))
     f32 = dict(device=device, dtype=torch.float32, generator=gen)
-    Zm = torch.randn(n, d_in, **f32) / float(np.sqrt(n))
-    Zm *= (1.0 / torch.arange(1, d_in + 1, device=device, dtype=torch.float32))[None, :]
-    V, _ = torch.linalg.qr(torch.randn(d_in, d_in, **f32))
-    X = Zm @ V.T
-    del Zm, V
+    X = torch.randn(n, d_in, **f32) / float(np.sqrt(n))
+    X *= (1.0 / torch.arange(1, d_in + 1, device=device, dtype=torch.float32))[None, :]
+    # random rotation of feature space as a butterfly network: each stage permutes the channels at
+    # random and rotates consecutive pairs by random angles (exactly orthogonal, O(n d) per stage,
+    # plain elementwise kernels); 2 log2(d) stages mix every channel into every other.
+    for _ in range(2 * int(np.ceil(np.log2(max(d_in, 2))))):
+        perm = torch.randperm(d_in, device=device, generator=gen)
+        X = X[:, perm]
+        half = d_in // 2
+        ang = torch.rand(half, **f32) * (2.0 * np.pi)
+        c, s = torch.cos(ang)[None, :], torch.sin(ang)[None, :]
+        a, b = X[:, 0:2 * half:2], X[:, 1:2 * half:2]
+        ra, rb = c * a - s * b, s * a + c * b
+        X[:, 0:2 * half:2] = ra
+        X[:, 1:2 * half:2] = rb
+        del a, b, ra, rb
     ch = torch.randperm(d_in, device=device, generator=gen)[:n_outliers]
     X[:, ch] *= outlier_scale
     X /= X.square().mean().sqrt()
