@@ -22,6 +22,7 @@ struct agzo_ctx {
     char* ws;
     size_t ws_bytes;
     int* flag;   // device int: deferred numeric failure
+    unsigned int* counter;   // device ticket counter of the QR's last-block reduction (zero between launches)
     bool prof;
     ProfClass pc[AGZO_PROF_KINDS];
 };
@@ -163,20 +164,21 @@ int check_loss(agzo_ctx* ctx, const agzo_layer* L, const agzo_loss_spec* loss, c
 inline float* wsf(agzo_ctx* c, size_t off) { return reinterpret_cast<float*>(c->ws + off); }
 inline bf16_t* wsh(agzo_ctx* c, size_t off) { return reinterpret_cast<bf16_t*>(c->ws + off); }
 
-// S = X^T Omega  (Alg. 1: Y <- H Omega)
-int op_sketch_range(agzo_ctx* ctx, const agzo_layer& L, const Plan& p, const void* X, uint64_t seed, float* S) {
+// ---- sketches.  On the bf16 path a sketch first exists as per-token-range partials in the workspace
+// (`splits`); they are summed either by the QR that consumes them or, when the caller wants S itself,
+// by reduce_splits.  On the fp32 path S is produced directly.
+
+// Omega^T planes -> splits (bf16) / S (fp32):  S = X^T Omega  (Alg. 1: Y <- H Omega)
+int sketch_range(agzo_ctx* ctx, const agzo_layer& L, const Plan& p, const void* X, uint64_t seed, float* S) {
     hipStream_t st = ctx->stream;
     if (L.dtype == AGZO_BF16) {
         {
             ProfScope ps(ctx, AGZO_PROF_FILL);
             HIPCHK(launch_fill_normal_packT(wsh(ctx, p.off_TpackT), L.n_tokens, p.m_pad, L.r, p.rp, seed, AGZO_TAG_OMEGA, st));
         }
-        {
-            ProfScope ps(ctx, AGZO_PROF_XTT);
-            HIPCHK(launch_xtt_bf16(static_cast<const bf16_t*>(X), L.ldx, L.n_tokens, L.d_in, wsh(ctx, p.off_TpackT),
-                                   p.m_pad, p.rp, wsf(ctx, p.off_xtt), p.nsplit, st));
-        }
-        HIPCHK(launch_reduce_splits(wsf(ctx, p.off_xtt), p.nsplit, L.d_in, p.rp, L.r, S, st));
+        ProfScope ps(ctx, AGZO_PROF_XTT);
+        HIPCHK(launch_xtt_bf16(static_cast<const bf16_t*>(X), L.ldx, L.n_tokens, L.d_in, wsh(ctx, p.off_TpackT),
+                               p.m_pad, p.rp, wsf(ctx, p.off_xtt), p.nsplit, st));
     } else {
         float* om = wsf(ctx, p.off_T);
         HIPCHK(launch_fill_normal(om, L.n_tokens, L.r, seed, AGZO_TAG_OMEGA, st));
@@ -185,22 +187,18 @@ int op_sketch_range(agzo_ctx* ctx, const agzo_layer& L, const Plan& p, const voi
     return 0;
 }
 
-// S = X^T (X Q)  (Alg. 1: Y <- H (H^T Q))
-int op_sketch_power(agzo_ctx* ctx, const agzo_layer& L, const Plan& p, const void* X, const float* Q, float* S) {
+// S = X^T (X Q)  (Alg. 1: Y <- H (H^T Q)).  bf16: Q must already sit in the workspace as planes.
+int sketch_power(agzo_ctx* ctx, const agzo_layer& L, const Plan& p, const void* X, const float* Q, float* S) {
     hipStream_t st = ctx->stream;
     if (L.dtype == AGZO_BF16) {
-        HIPCHK(launch_pack_planes(Q, L.d_in, L.r, p.rp, wsh(ctx, p.off_pack), st));
         {
             ProfScope ps(ctx, AGZO_PROF_XQ);
             HIPCHK(launch_xq_bf16(static_cast<const bf16_t*>(X), L.ldx, L.n_tokens, L.d_in, wsh(ctx, p.off_pack), L.r,
                                   p.rp, nullptr, wsh(ctx, p.off_TpackT), p.m_pad, st));
         }
-        {
-            ProfScope ps(ctx, AGZO_PROF_XTT);
-            HIPCHK(launch_xtt_bf16(static_cast<const bf16_t*>(X), L.ldx, L.n_tokens, L.d_in, wsh(ctx, p.off_TpackT),
-                                   p.m_pad, p.rp, wsf(ctx, p.off_xtt), p.nsplit, st));
-        }
-        HIPCHK(launch_reduce_splits(wsf(ctx, p.off_xtt), p.nsplit, L.d_in, p.rp, L.r, S, st));
+        ProfScope ps(ctx, AGZO_PROF_XTT);
+        HIPCHK(launch_xtt_bf16(static_cast<const bf16_t*>(X), L.ldx, L.n_tokens, L.d_in, wsh(ctx, p.off_TpackT),
+                               p.m_pad, p.rp, wsf(ctx, p.off_xtt), p.nsplit, st));
     } else {
         const float* Xf = static_cast<const float*>(X);
         float* T = wsf(ctx, p.off_T);
@@ -210,22 +208,36 @@ int op_sketch_power(agzo_ctx* ctx, const agzo_layer& L, const Plan& p, const voi
     return 0;
 }
 
-int op_qr(agzo_ctx* ctx, const Plan& p, const float* S, int64_t d, int r, float* Q) {
-    ProfScope ps(ctx, AGZO_PROF_QR);
-    HIPCHK(launch_qr(S, d, r, Q, ctx->ws + p.off_qr, ctx->flag, ctx->stream));
+int reduce_to_S(agzo_ctx* ctx, const agzo_layer& L, const Plan& p, float* S) {
+    if (L.dtype == AGZO_BF16)
+        HIPCHK(launch_reduce_splits(wsf(ctx, p.off_xtt), p.nsplit, L.d_in, p.rp, L.r, S, ctx->stream));
     return 0;
 }
 
-// P = X B  (N x r)
-int op_project(agzo_ctx* ctx, const agzo_layer& L, const Plan& p, const void* X, const float* B, float* P) {
+// Q = qr(S) for an explicit S; planes (nullable) also receive Q as bf16 planes
+int op_qr(agzo_ctx* ctx, size_t off_qr, const float* S, int64_t d, int r, int rp, float* Q, bf16_t* planes) {
+    ProfScope ps(ctx, AGZO_PROF_QR);
+    HIPCHK(launch_qr(S, nullptr, 0, rp, nullptr, d, r, Q, planes, ctx->ws + off_qr, ctx->counter, ctx->flag, ctx->stream));
+    return 0;
+}
+
+// Q = qr(sum of the pending splits); the summed sketch is left in the workspace S
+int op_qr_from_splits(agzo_ctx* ctx, const agzo_layer& L, const Plan& p, float* Q, bf16_t* planes) {
+    ProfScope ps(ctx, AGZO_PROF_QR);
+    HIPCHK(launch_qr(nullptr, wsf(ctx, p.off_xtt), p.nsplit, p.rp, wsf(ctx, p.off_S), L.d_in, L.r, Q, planes,
+                     ctx->ws + p.off_qr, ctx->counter, ctx->flag, ctx->stream));
+    return 0;
+}
+
+// P = X B  (N x r).  planes_ready: B already sits in the workspace as planes (left there by the last QR)
+int op_project(agzo_ctx* ctx, const agzo_layer& L, const Plan& p, const void* X, const float* B, float* P,
+               bool planes_ready) {
     hipStream_t st = ctx->stream;
     if (L.dtype == AGZO_BF16) {
-        HIPCHK(launch_pack_planes(B, L.d_in, L.r, p.rp, wsh(ctx, p.off_pack), st));
-        {
-            ProfScope ps(ctx, AGZO_PROF_XQ);
-            HIPCHK(launch_xq_bf16(static_cast<const bf16_t*>(X), L.ldx, L.n_tokens, L.d_in, wsh(ctx, p.off_pack), L.r,
-                                  p.rp, P, nullptr, p.m_pad, st));
-        }
+        if (!planes_ready) HIPCHK(launch_pack_planes(B, L.d_in, L.r, p.rp, wsh(ctx, p.off_pack), st));
+        ProfScope ps(ctx, AGZO_PROF_XQ);
+        HIPCHK(launch_xq_bf16(static_cast<const bf16_t*>(X), L.ldx, L.n_tokens, L.d_in, wsh(ctx, p.off_pack), L.r, p.rp,
+                              P, nullptr, p.m_pad, st));
     } else {
         HIPCHK(launch_gemm_f32(static_cast<const float*>(X), L.ldx, 1, B, L.r, 1, P, L.r, L.n_tokens, L.r, L.d_in, st));
     }
@@ -272,25 +284,34 @@ int op_update(agzo_ctx* ctx, const agzo_layer& L, void* W, const float* B, uint6
     return 0;
 }
 
+// Alg. 1.  On return (bf16) the workspace planes hold B.
 int op_basis(agzo_ctx* ctx, const agzo_layer& L, const Plan& p, const void* X, int K, uint64_t seed, const float* S0,
              int flags, float* B) {
+    const bool bf = (L.dtype == AGZO_BF16);
     float* S = wsf(ctx, p.off_S);
     float* Q = wsf(ctx, p.off_Q);
-    const float* cur = S0;
+    bf16_t* planes = bf ? wsh(ctx, p.off_pack) : nullptr;
+    const float* given = S0;      // an explicit first sketch, if any
     if (flags & AGZO_INIT_FEATURE) {
         HIPCHK(launch_fill_normal(Q, L.d_in, L.r, seed, AGZO_TAG_Q0, ctx->stream));
-        TRY(op_sketch_power(ctx, L, p, X, Q, S));
-        cur = S;
-    } else if (!cur) {
-        TRY(op_sketch_range(ctx, L, p, X, seed, S));
-        cur = S;
+        if (bf) HIPCHK(launch_pack_planes(Q, L.d_in, L.r, p.rp, planes, ctx->stream));
+        TRY(sketch_power(ctx, L, p, X, Q, S));
+        given = nullptr;
+    } else if (!given) {
+        TRY(sketch_range(ctx, L, p, X, seed, S));
     }
-    for (int k = 0; k < K; ++k) {
-        TRY(op_qr(ctx, p, cur, L.d_in, L.r, Q));
-        TRY(op_sketch_power(ctx, L, p, X, Q, S));
-        cur = S;
+    for (int k = 0; k <= K; ++k) {
+        float* out = (k == K) ? B : Q;
+        if (given) {
+            TRY(op_qr(ctx, p.off_qr, given, L.d_in, L.r, p.rp, out, planes));
+            given = nullptr;
+        } else if (bf) {
+            TRY(op_qr_from_splits(ctx, L, p, out, planes));
+        } else {
+            TRY(op_qr(ctx, p.off_qr, S, L.d_in, L.r, p.rp, out, nullptr));
+        }
+        if (k < K) TRY(sketch_power(ctx, L, p, X, Q, S));
     }
-    TRY(op_qr(ctx, p, cur, L.d_in, L.r, B));
     return 0;
 }
 
@@ -310,6 +331,7 @@ int agzo_create(agzo_ctx** out, void* hip_stream) {
     ctx->prof = false;
     hipError_t e = hipMalloc(reinterpret_cast<void**>(&ctx->flag), 256);
     if (e == hipSuccess) e = hipMemset(ctx->flag, 0, 256);
+    ctx->counter = reinterpret_cast<unsigned int*>(ctx->flag) + 16;
     if (e != hipSuccess) {
         delete ctx;
         return AGZO_EHIP;
@@ -401,8 +423,16 @@ int agzo_layer_forward_sketch(agzo_ctx* ctx, const agzo_layer* L, const void* W,
     const Plan p = make_plan(*L, gemm && L->dtype == AGZO_F32 && !Y);
     TRY(reserve(ctx, p.total));
     if (gemm) TRY(op_forward(ctx, *L, p, W, X, nullptr, 0.f, seed, Y, loss, loss_dev));
-    if (mode == AGZO_SKETCH_RANGE) TRY(op_sketch_range(ctx, *L, p, X, seed, S));
-    if (mode == AGZO_SKETCH_POWER) TRY(op_sketch_power(ctx, *L, p, X, Q, S));
+    if (mode == AGZO_SKETCH_RANGE) {
+        TRY(sketch_range(ctx, *L, p, X, seed, S));
+        TRY(reduce_to_S(ctx, *L, p, S));
+    }
+    if (mode == AGZO_SKETCH_POWER) {
+        if (L->dtype == AGZO_BF16)
+            HIPCHK(launch_pack_planes(Q, L->d_in, L->r, p.rp, wsh(ctx, p.off_pack), ctx->stream));
+        TRY(sketch_power(ctx, *L, p, X, Q, S));
+        TRY(reduce_to_S(ctx, *L, p, S));
+    }
     return AGZO_OK;
 }
 
@@ -410,11 +440,8 @@ int agzo_qr(agzo_ctx* ctx, const float* S, int64_t d_in, int32_t r, float* Q) {
     if (!ctx) return AGZO_EINVAL;
     if (!S || !Q) return fail(ctx, AGZO_EINVAL, "S or Q is NULL");
     if (r < 1 || r > kMaxRank || d_in < r) return fail(ctx, AGZO_EINVAL, "need 1 <= r <= min(64, d_in)");
-    Plan p;
-    memset(&p, 0, sizeof(p));
-    p.off_qr = 0;
     TRY(reserve(ctx, qr_workspace_bytes(d_in, r)));
-    return op_qr(ctx, p, S, d_in, r, Q);
+    return op_qr(ctx, 0, S, d_in, r, round16(r), Q, nullptr);
 }
 
 int agzo_basis(agzo_ctx* ctx, const agzo_layer* L, const void* X, int32_t K, uint64_t seed, const float* S0,
@@ -436,7 +463,7 @@ int agzo_perturbed_forward(agzo_ctx* ctx, const agzo_layer* L, const void* W, co
     const Plan p = make_plan(*L, L->dtype == AGZO_F32 && !Y);
     TRY(reserve(ctx, p.total));
     float* P = wsf(ctx, p.off_T);
-    TRY(op_project(ctx, *L, p, X, B, P));
+    TRY(op_project(ctx, *L, p, X, B, P, false));
     return op_forward(ctx, *L, p, W, X, P, eps_signed, seed, Y, loss, loss_dev);
 }
 
@@ -485,7 +512,7 @@ int agzo_step(agzo_ctx* ctx, const agzo_layer* L, void* W, const void* X, const 
         }
     } else {
         float* P = wsf(ctx, p.off_T);
-        TRY(op_project(ctx, *L, p, X, B, P));
+        TRY(op_project(ctx, *L, p, X, B, P, true));
         TRY(op_forward(ctx, *L, p, W, X, P, +eps, seed, nullptr, loss, out_dev + 1));
         if (!one_sided) TRY(op_forward(ctx, *L, p, W, X, P, -eps, seed, nullptr, loss, out_dev + 2));
     }

@@ -129,7 +129,10 @@ hipError_t launch_pack_planes(const float* Q, int64_t d, int r, int rp, bf16_t* 
 
 // qr.hip : CholeskyQR2
 size_t qr_workspace_bytes(int64_t d, int r);
-hipError_t launch_qr(const float* S, int64_t d, int r, float* Q, void* workspace, int* numeric_flag, hipStream_t st);
+// S explicit, or splits [nsplit][d][rp] (then their fp32 sum is also stored to S_out); Q fp32 out;
+// planes (nullable) bf16 [3][rp][d]; counter: zero-initialised device word used as a ticket
+hipError_t launch_qr(const float* S, const float* splits, int nsplit, int rp, float* S_out, int64_t d, int r, float* Q,
+                     bf16_t* planes, void* workspace, unsigned int* counter, int* numeric_flag, hipStream_t st);
 
 // update.hip : W -= lr * g * G B^T in place
 hipError_t launch_update(void* W, int dtype, int64_t ldw, int64_t d_out, int64_t d_in, const float* B, int r,

@@ -214,10 +214,21 @@ __global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
     // main loop: slice `it` is multiplied from buffer it&1 while slice it+1 is brought into the other;
     // the direct loads of the next slice are issued a few at a time between the MFMA sub-steps so
     // that their LDS writes do not arrive in one burst
+    // Target prefetch: during four of the last slices every thread touches one 128-byte line of the
+    // tile's target values with a 4-byte LDS-direct load into a scratch slot, so that the epilogue's
+    // reads find the tile in L2.  These loads are issued after the slice's operand loads and are the
+    // only ones allowed to stay in flight across the slice's closing wait.
+    const bool pf_on = (p.loss_kind == AGZO_LOSS_MSE) && total >= 6;
+    const int pf_first = total - 6;
+    char* sink = smem + 4 * TILE_BYTES + wave * 256;
+    const int t_shift = (p.target_dtype == AGZO_BF16) ? 1 : 2;       // log2(bytes per target element)
+    const int lines_per_row = (BT << t_shift) >> 7;                    // 128-byte lines per tile row
     for (int it = 0; it < total; ++it) {
         const int cur = it & 1;
         const bool dma_next = it + 1 < nfull;
         if (!dma_next && it + 1 < total) fill_manual(it + 1, cur ^ 1);
+        const int pj = it - pf_first;                                  // 0..3 while prefetching
+        const bool pf_now = pf_on && pj >= 0 && pj < 4 && (pj * NT < BT * lines_per_row);
         const char* xs = Xs(cur);
         const char* ws = Ws(cur);
         char* nxs = Xs(cur ^ 1);
@@ -257,7 +268,16 @@ __global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
                 for (int j = 0; j < BB; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[s][i], b[s][j], acc[i][j], 0, 0, 0);
         }
-        __builtin_amdgcn_s_waitcnt(0x0F70);
+        if (pf_now) {
+            const int line = pj * NT + tid;
+            const int64_t prow = min((int64_t)(line / lines_per_row), p.M - 1 - m0);
+            const int64_t pcol = min((int64_t)((line % lines_per_row) << (7 - t_shift)), p.N - 1 - n0);
+            const char* tp = reinterpret_cast<const char*>(p.target) + (((m0 + prow) * p.ldt + n0 + pcol) << t_shift);
+            __builtin_amdgcn_global_load_lds((gptr_t)tp, (lptr_t)sink, 4, 0, 0);
+            __builtin_amdgcn_s_waitcnt(0x0F71);     // vmcnt(1): everything but the prefetch just issued
+        } else {
+            __builtin_amdgcn_s_waitcnt(0x0F70);
+        }
         __syncthreads();
     }
 
@@ -352,7 +372,7 @@ __global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
 template <int WA, int WB>
 static hipError_t launch_variant(const GemmParams& p, hipStream_t st) {
     static bool attr_set = false;
-    const int smem = 4 * TILE_BYTES;
+    const int smem = 4 * TILE_BYTES + 256 * WA * WB;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_bf16_kernel<WA, WB>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, smem);
