@@ -98,9 +98,9 @@ def main():
     out = torch.zeros(len(layers), 4, dtype=torch.float64, device="cuda")
     flags = binding.NAIVE_INPLACE if args.naive else 0
 
-    def one_step(step):
+    def one_step(step, fl=None):
         for li, (L, W, X, loss) in enumerate(descs):
-            ctx.step(L, W, X, loss, K, eps, lr, 1000 * step + li, flags, out[li])
+            ctx.step(L, W, X, loss, K, eps, lr, 1000 * step + li, flags if fl is None else fl, out[li])
 
     if args.calibrate_copy:
         src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
@@ -164,6 +164,26 @@ def main():
         "stage_ms_per_step": {"gemm": ms_gemm / args.steps, "update": ms_upd / args.steps, "xq": ms_xq / args.steps,
                               "xtt": ms_xtt / args.steps, "qr": ms_qr / args.steps},
     }
+    if not args.naive:
+        # the same steps with f0, f+ and f- evaluated from one pass over X and W (AGZO_SHARED_FORWARD):
+        # identical results up to rounding, one GEMM main loop per projection instead of three
+        for s in range(args.warmup):
+            one_step(10_000 + s, binding.SHARED_FORWARD)
+        torch.cuda.synchronize()
+        ctx.profile_enable(True)
+        t1 = time.perf_counter()
+        for s in range(args.steps):
+            one_step(20_000 + s, binding.SHARED_FORWARD)
+        torch.cuda.synchronize()
+        dt1 = time.perf_counter() - t1
+        n_g1, ms_g1 = ctx.profile_read(binding.PROF_GEMM)
+        ctx.profile_enable(False)
+        ctx.check()
+        flops1 = (fwd_flops + 2 * rank_flops) / len(shapes)
+        res["shared_forward"] = {"value": args.steps / dt1, "unit": "steps/s", "ms_per_step": 1e3 * dt1 / args.steps,
+                                 "gemm_launches": n_g1, "gemm_avg_ms": ms_g1 / max(n_g1, 1),
+                                 "gemm_tflops": flops1 / (ms_g1 / max(n_g1, 1) * 1e-3) / 1e12,
+                                 "note": "f0, f+, f- from one pass over X and W per projection (single-layer problems only)"}
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(N, r, K, eps, lr, fwd_flops)
     print(json.dumps(res))

@@ -58,7 +58,9 @@ enum { AGZO_TAG_G = 0, AGZO_TAG_OMEGA = 1, AGZO_TAG_Q0 = 2, AGZO_TAG_DENSE = 3 }
 enum {
     AGZO_ONE_SIDED = 1,    /* g = (L+ - L0)/eps, the literal form of Eq. 10 / Alg. 2; default is (L+ - L-)/(2 eps) */
     AGZO_NAIVE_INPLACE = 2,/* comparator: perturb W in place, plain forward, undo (Alg. 2's literal schedule) */
-    AGZO_INIT_FEATURE = 4  /* start Alg. 1 from a Gaussian Q0 [d_in][r] (tag 2) instead of a token-space Omega */
+    AGZO_INIT_FEATURE = 4, /* start Alg. 1 from a Gaussian Q0 [d_in][r] (tag 2) instead of a token-space Omega */
+    AGZO_SHARED_FORWARD = 8/* single layer only: f0, f+ and f- are evaluated from one pass over X and W
+                              (Y+- = X W^T +- eps (X B) G^T share the product X W^T); extraction runs first */
 };
 
 typedef struct {

@@ -17,7 +17,7 @@ F32, BF16 = 0, 1
 LOSS_NONE, LOSS_MSE, LOSS_CE = 0, 1, 2
 SKETCH_NONE, SKETCH_RANGE, SKETCH_POWER = 0, 1, 2
 TAG_G, TAG_OMEGA, TAG_Q0, TAG_DENSE = 0, 1, 2, 3
-ONE_SIDED, NAIVE_INPLACE, INIT_FEATURE = 1, 2, 4
+ONE_SIDED, NAIVE_INPLACE, INIT_FEATURE, SHARED_FORWARD = 1, 2, 4, 8
 OK, EINVAL, ENOMEM, ENUMERIC, EHIP = 0, -1, -2, -3, -4
 
 PROF_GEMM, PROF_UPDATE, PROF_XQ, PROF_XTT, PROF_QR, PROF_FILL = range(6)

@@ -22,7 +22,6 @@ struct agzo_ctx {
     char* ws;
     size_t ws_bytes;
     int* flag;   // device int: deferred numeric failure
-    unsigned int* counter;   // device ticket counter of the QR's last-block reduction (zero between launches)
     bool prof;
     ProfClass pc[AGZO_PROF_KINDS];
 };
@@ -103,7 +102,7 @@ Plan make_plan(const agzo_layer& L, bool need_ybuf) {
     p.off_TpackT = take(bf ? (size_t)3 * p.rp * p.m_pad * 2 : 0);
     p.off_xtt = take(bf ? (size_t)p.nsplit * L.d_in * p.rp * 4 : 0);
     p.off_qr = take(qr_workspace_bytes(L.d_in, L.r));
-    p.off_part = take((size_t)n_gemm * 8);
+    p.off_part = take((size_t)n_gemm * 8 * 3);
     p.off_Ybuf = take(need_ybuf ? (size_t)L.n_tokens * L.d_out * 4 : 0);
     p.total = o;
     return p;
@@ -217,7 +216,7 @@ int reduce_to_S(agzo_ctx* ctx, const agzo_layer& L, const Plan& p, float* S) {
 // Q = qr(S) for an explicit S; planes (nullable) also receive Q as bf16 planes
 int op_qr(agzo_ctx* ctx, size_t off_qr, const float* S, int64_t d, int r, int rp, float* Q, bf16_t* planes) {
     ProfScope ps(ctx, AGZO_PROF_QR);
-    HIPCHK(launch_qr(S, nullptr, 0, rp, nullptr, d, r, Q, planes, ctx->ws + off_qr, ctx->counter, ctx->flag, ctx->stream));
+    HIPCHK(launch_qr(S, nullptr, 0, rp, nullptr, d, r, Q, planes, ctx->ws + off_qr, ctx->flag, ctx->stream));
     return 0;
 }
 
@@ -225,7 +224,7 @@ int op_qr(agzo_ctx* ctx, size_t off_qr, const float* S, int64_t d, int r, int rp
 int op_qr_from_splits(agzo_ctx* ctx, const agzo_layer& L, const Plan& p, float* Q, bf16_t* planes) {
     ProfScope ps(ctx, AGZO_PROF_QR);
     HIPCHK(launch_qr(nullptr, wsf(ctx, p.off_xtt), p.nsplit, p.rp, wsf(ctx, p.off_S), L.d_in, L.r, Q, planes,
-                     ctx->ws + p.off_qr, ctx->counter, ctx->flag, ctx->stream));
+                     ctx->ws + p.off_qr, ctx->flag, ctx->stream));
     return 0;
 }
 
@@ -245,8 +244,10 @@ int op_project(agzo_ctx* ctx, const agzo_layer& L, const Plan& p, const void* X,
 }
 
 // Y = X W^T (+ eps (P) G^T), loss
+// shared = true: one pass over X and W evaluates the loss at W, W + eps Z, W - eps Z -> loss_dev[0..2]
 int op_forward(agzo_ctx* ctx, const agzo_layer& L, const Plan& p, const void* W, const void* X, const float* P,
-               float eps_signed, uint64_t seed, void* Y, const agzo_loss_spec* loss, double* loss_dev) {
+               float eps_signed, uint64_t seed, void* Y, const agzo_loss_spec* loss, double* loss_dev,
+               bool shared = false) {
     hipStream_t st = ctx->stream;
     GemmLossArgs la;
     const bool has_loss = loss && loss->kind != AGZO_LOSS_NONE;
@@ -263,6 +264,7 @@ int op_forward(agzo_ctx* ctx, const agzo_layer& L, const Plan& p, const void* W,
         a.Y = Y; a.y_dtype = L.y_dtype; a.ldy = L.ldy;
         a.P = P; a.r = L.r; a.eps_signed = eps_signed; a.seed = seed;
         a.loss = la;
+        a.shared = shared;
         ProfScope ps(ctx, AGZO_PROF_GEMM);
         HIPCHK(launch_gemm_bf16(a, st));
     } else {
@@ -270,10 +272,21 @@ int op_forward(agzo_ctx* ctx, const agzo_layer& L, const Plan& p, const void* W,
         const int64_t ldy = Y ? L.ldy : L.d_out;
         HIPCHK(launch_gemm_f32(static_cast<const float*>(X), L.ldx, 1, static_cast<const float*>(W), 1, L.ldw, Yf, ldy,
                                L.n_tokens, L.d_out, L.d_in, st));
-        HIPCHK(launch_epilogue_f32(Yf, ldy, L.n_tokens, L.d_out, P, L.r, eps_signed, seed, la, st));
+        if (shared) {
+            // Y0 -> f0; Y0 + eps D -> f+; then - 2 eps D -> f-   (all in the stored fp32 Y buffer)
+            GemmLossArgs l1 = la, l2 = la;
+            l1.partials = la.partials + p.n_part;
+            l2.partials = la.partials + 2 * p.n_part;
+            HIPCHK(launch_epilogue_f32(Yf, ldy, L.n_tokens, L.d_out, nullptr, L.r, 0.f, seed, la, st));
+            HIPCHK(launch_epilogue_f32(Yf, ldy, L.n_tokens, L.d_out, P, L.r, eps_signed, seed, l1, st));
+            HIPCHK(launch_epilogue_f32(Yf, ldy, L.n_tokens, L.d_out, P, L.r, -2.f * eps_signed, seed, l2, st));
+        } else {
+            HIPCHK(launch_epilogue_f32(Yf, ldy, L.n_tokens, L.d_out, P, L.r, eps_signed, seed, la, st));
+        }
     }
     if (has_loss)
-        HIPCHK(launch_finish_loss(la.partials, p.n_part, 1.0 / ((double)L.n_tokens * (double)L.d_out), loss_dev, st));
+        HIPCHK(launch_finish_loss(la.partials, p.n_part, 1.0 / ((double)L.n_tokens * (double)L.d_out), loss_dev,
+                                  shared ? 3 : 1, st));
     return 0;
 }
 
@@ -331,7 +344,6 @@ int agzo_create(agzo_ctx** out, void* hip_stream) {
     ctx->prof = false;
     hipError_t e = hipMalloc(reinterpret_cast<void**>(&ctx->flag), 256);
     if (e == hipSuccess) e = hipMemset(ctx->flag, 0, 256);
-    ctx->counter = reinterpret_cast<unsigned int*>(ctx->flag) + 16;
     if (e != hipSuccess) {
         delete ctx;
         return AGZO_EHIP;
@@ -496,6 +508,17 @@ int agzo_step(agzo_ctx* ctx, const agzo_layer* L, void* W, const void* X, const 
     float* B = wsf(ctx, p.off_B);
     const bool one_sided = (flags & AGZO_ONE_SIDED) != 0;
 
+    if ((flags & AGZO_SHARED_FORWARD) && !(flags & AGZO_NAIVE_INPLACE)) {
+        // extraction first, then f0, f+ and f- from one pass over X and W (valid for a single layer:
+        // all three evaluations read the same activations)
+        TRY(op_basis(ctx, *L, p, X, K, seed, nullptr, flags & AGZO_INIT_FEATURE, B));
+        float* P = wsf(ctx, p.off_T);
+        TRY(op_project(ctx, *L, p, X, B, P, true));
+        TRY(op_forward(ctx, *L, p, W, X, P, eps, seed, nullptr, loss, out_dev, true));
+        HIPCHK(launch_two_point(out_dev, eps, one_sided ? 1 : 0, st));
+        TRY(op_update(ctx, *L, W, B, seed, lr, out_dev + 3));
+        return AGZO_OK;
+    }
     // 1. base forward f0 and subspace extraction from the same activations (Alg. 2, part 1)
     TRY(op_forward(ctx, *L, p, W, X, nullptr, 0.f, seed, nullptr, loss, out_dev + 0));
     TRY(op_basis(ctx, *L, p, X, K, seed, nullptr, flags & AGZO_INIT_FEATURE, B));

@@ -102,6 +102,9 @@ struct GemmBf16Args {
     const float* P; int r;      // projection X B [M][r] (NULL: no rank-r term)
     float eps_signed; uint64_t seed;
     GemmLossArgs loss;
+    // shared = true: one pass evaluates the loss at W, W + eps Z and W - eps Z (eps = eps_signed > 0);
+    // the loss partials are then [3][n_workgroups] and Y must be NULL
+    bool shared = false;
 };
 int gemm_bf16_num_workgroups(int64_t M, int64_t N);
 hipError_t launch_gemm_bf16(const GemmBf16Args& a, hipStream_t st);
@@ -130,16 +133,17 @@ hipError_t launch_pack_planes(const float* Q, int64_t d, int r, int rp, bf16_t* 
 // qr.hip : CholeskyQR2
 size_t qr_workspace_bytes(int64_t d, int r);
 // S explicit, or splits [nsplit][d][rp] (then their fp32 sum is also stored to S_out); Q fp32 out;
-// planes (nullable) bf16 [3][rp][d]; counter: zero-initialised device word used as a ticket
+// planes (nullable) bf16 [3][rp][d]
 hipError_t launch_qr(const float* S, const float* splits, int nsplit, int rp, float* S_out, int64_t d, int r, float* Q,
-                     bf16_t* planes, void* workspace, unsigned int* counter, int* numeric_flag, hipStream_t st);
+                     bf16_t* planes, void* workspace, int* numeric_flag, hipStream_t st);
 
 // update.hip : W -= lr * g * G B^T in place
 hipError_t launch_update(void* W, int dtype, int64_t ldw, int64_t d_out, int64_t d_in, const float* B, int r,
                          uint64_t seed, float lr, const double* g_dev, hipStream_t st);
 
 // loss.hip
-hipError_t launch_finish_loss(const double* partials, int n, double scale, double* out, hipStream_t st);
+// out[b] = scale * sum(partials[b*n .. b*n+n)), b < nout
+hipError_t launch_finish_loss(const double* partials, int n, double scale, double* out, int nout, hipStream_t st);
 hipError_t launch_two_point(double* out4, float eps, int one_sided, hipStream_t st);
 
 }  // namespace agzo

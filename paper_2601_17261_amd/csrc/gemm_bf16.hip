@@ -10,8 +10,6 @@
 // The rank-r term is accumulated by the same MFMA loop as a few extra K slices appended after the
 // d_in slices: one operand is eps * P split in bf16 hi/lo, the other is G regenerated from the
 // Philox seed and split likewise, so both signs share bit-identical X W^T accumulators.
-#include <stdlib.h>
-
 #include "agzo_internal.h"
 
 namespace agzo {
@@ -46,10 +44,11 @@ struct GemmParams {
     int loss_kind; int target_dtype; const void* target; int64_t ldt; double* partials;
     int tiles_m, tiles_n;
     int vec_ok;                 // 16-byte epilogue accesses are legal
+    int shared;                 // one pass evaluates f0, f+ and f- (three loss partials per tile)
 };
 
 // WA x WB waves: WA splits the 256 outputs, WB splits the 256 tokens
-template <int WA, int WB>
+template <int WA, int WB, bool SHARED>
 __global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
     constexpr int NT = 64 * WA * WB;
     constexpr int BA = BT / WA / 32;           // 32-row blocks of W per wave
@@ -113,7 +112,9 @@ __global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
     const int rp = p.rp;                        // r rounded up to 16
     const int kext = 3 * rp;                    // width of the extended operands [Ph|Ph|Pl] x [Gh|Gl|Gh]
     const int next = (p.P != nullptr) ? (kext + BK - 1) / BK : 0;
-    const int total = nfull + ntail + next;
+    const int nd = nfull + ntail;               // slices of d_in
+    // shared mode: the extension runs twice, with +eps (accumulators become Y+) and then with -2 eps (Y-)
+    const int total = nd + (SHARED ? 2 * next : next);
 
     // ragged last slice of d_in: chunks past d_in are zero
     auto fill_tail = [&](int buf) {
@@ -132,7 +133,7 @@ __global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
         }
     };
     // slice `et` of the rank-r extension: X side eps*P as [hi|hi|lo], W side G as [hi|lo|hi]
-    auto fill_ext = [&](int buf, int et) {
+    auto fill_ext = [&](int buf, int et, float coef) {
         const int kchunks = rp / 8;             // 8-column chunks of P' and G per row
         for (int e = tid; e < BT * CHUNKS; e += NT) {
             const int row = e >> 3, c = e & 7;
@@ -154,7 +155,7 @@ __global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
             float pv[8], gv[8];
 #pragma unroll
             for (int i = 0; i < 8; ++i)
-                pv[i] = (gm < p.M && k0 + i < p.r) ? p.eps_signed * p.P[gm * p.r + k0 + i] : 0.f;
+                pv[i] = (gm < p.M && k0 + i < p.r) ? coef * p.P[gm * p.r + k0 + i] : 0.f;
             {
                 float4 z0 = make_float4(0.f, 0.f, 0.f, 0.f), z1 = z0;
                 if (gn < p.N) {
@@ -192,7 +193,13 @@ __global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
         }
     };
     auto fill_manual = [&](int it, int buf) {
-        if (it < nfull + ntail) fill_tail(buf); else fill_ext(buf, it - nfull - ntail);
+        if (it < nd) {
+            fill_tail(buf);
+        } else {
+            const int e = it - nd;
+            if (SHARED && e >= next) fill_ext(buf, e - next, -2.f * p.eps_signed);
+            else fill_ext(buf, e, p.eps_signed);
+        }
     };
     typedef const __attribute__((address_space(1))) void* gptr_t;
     typedef __attribute__((address_space(3))) void* lptr_t;
@@ -213,17 +220,24 @@ __global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
 
     // main loop: slice `it` is multiplied from buffer it&1 while slice it+1 is brought into the other;
     // the direct loads of the next slice are issued a few at a time between the MFMA sub-steps so
-    // that their LDS writes do not arrive in one burst
-    // Target prefetch: during four of the last slices every thread touches one 128-byte line of the
-    // tile's target values with a 4-byte LDS-direct load into a scratch slot, so that the epilogue's
-    // reads find the tile in L2.  These loads are issued after the slice's operand loads and are the
-    // only ones allowed to stay in flight across the slice's closing wait.
-    const bool pf_on = (p.loss_kind == AGZO_LOSS_MSE) && total >= 6;
-    const int pf_first = total - 6;
+    // that their LDS writes do not arrive in one burst.
+    // Target prefetch: during four of the slices before the first loss evaluation every thread touches
+    // one 128-byte line of the tile's target values with a 4-byte LDS-direct load into a scratch slot,
+    // so that the epilogue's reads find the tile in L2.  These loads are issued after the slice's
+    // operand loads and are the only ones allowed to stay in flight across the slice's closing wait.
+    const int first_epi = SHARED ? nd - 1 : total - 1;
+    const bool pf_on = (p.loss_kind == AGZO_LOSS_MSE) && first_epi >= 5;
+    const int pf_first = first_epi - 5;
     char* sink = smem + 4 * TILE_BYTES + wave * 256;
+    double* red = reinterpret_cast<double*>(smem + 4 * TILE_BYTES + 256 * WA * WB);
     const int t_shift = (p.target_dtype == AGZO_BF16) ? 1 : 2;       // log2(bytes per target element)
     const int lines_per_row = (BT << t_shift) >> 7;                    // 128-byte lines per tile row
-    for (int it = 0; it < total; ++it) {
+    const bool y_f32 = (p.Y != nullptr) && p.y_dtype != AGZO_BF16;
+    const bool y_bf16 = (p.Y != nullptr) && p.y_dtype == AGZO_BF16;
+    const bool l_f32 = p.loss_kind == AGZO_LOSS_MSE && p.target_dtype != AGZO_BF16;
+    const bool l_bf16 = p.loss_kind == AGZO_LOSS_MSE && p.target_dtype == AGZO_BF16;
+    auto run_slices = [&](int it_begin, int it_end) __attribute__((always_inline)) {
+    for (int it = it_begin; it < it_end; ++it) {
         const int cur = it & 1;
         const bool dma_next = it + 1 < nfull;
         if (!dma_next && it + 1 < total) fill_manual(it + 1, cur ^ 1);
@@ -280,107 +294,132 @@ __global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
         }
         __syncthreads();
     }
-
-
-    // ---- epilogue: lane = one token, 16 consecutive outputs per block ---------------------------
-    double part = 0.0;
-    const bool y_f32 = (p.Y != nullptr) && p.y_dtype != AGZO_BF16;
-    const bool y_bf16 = (p.Y != nullptr) && p.y_dtype == AGZO_BF16;
-    const bool l_f32 = p.loss_kind == AGZO_LOSS_MSE && p.target_dtype != AGZO_BF16;
-    const bool l_bf16 = p.loss_kind == AGZO_LOSS_MSE && p.target_dtype == AGZO_BF16;
+    };
+    // ---- evaluation point: the accumulators hold Y0 (shared mode, after the d_in slices), or Y with
+    // the rank-r term of the current sign.  Lane = one token, 16 consecutive outputs per block.
+    auto evaluate = [&](int phase) __attribute__((always_inline)) {
+        double part = 0.0;
+        // shared mode: the first evaluation turns the accumulators into the residual Y0 - Y*, so the
+        // target is read once and the two perturbed evaluations are sums of squares of registers
+        const bool resid = SHARED && phase > 0;
 #pragma clang loop unroll(full)
-    for (int j = 0; j < BB; ++j) {
-        const int64_t row = m0 + wb * (BT / WB) + j * 32 + lr;
+        for (int j = 0; j < BB; ++j) {
+            const int64_t row = m0 + wb * (BT / WB) + j * 32 + lr;
 #pragma clang loop unroll(full)
-        for (int i = 0; i < BA; ++i) {
-            const int64_t col0 = n0 + wa * (BT / WA) + i * 32 + lh * 16;
-            const floatx16 v = acc[i][j];
-            if (row >= p.M || col0 >= p.N) continue;
-            if (p.vec_ok && col0 + 16 <= p.N) {
-                if (y_f32) {
-                    float4* dst = reinterpret_cast<float4*>(reinterpret_cast<float*>(p.Y) + row * p.ldy + col0);
+            for (int i = 0; i < BA; ++i) {
+                const int64_t col0 = n0 + wa * (BT / WA) + i * 32 + lh * 16;
+                floatx16 v = acc[i][j];
+                if (row >= p.M || col0 >= p.N) continue;
+                if (resid) {
 #pragma clang loop unroll(full)
-                    for (int q = 0; q < 4; ++q) dst[q] = make_float4(v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]);
+                    for (int e = 0; e < 16; ++e)
+                        if (col0 + e < p.N) part = fma((double)v[e], (double)v[e], part);
+                    continue;
                 }
-                if (y_bf16) {
-                    uint4* dst = reinterpret_cast<uint4*>(reinterpret_cast<bf16_t*>(p.Y) + row * p.ldy + col0);
-                    uint32_t w[8];
+                if (p.vec_ok && col0 + 16 <= p.N) {
+                    if (y_f32) {
+                        float4* dst = reinterpret_cast<float4*>(reinterpret_cast<float*>(p.Y) + row * p.ldy + col0);
 #pragma clang loop unroll(full)
-                    for (int q = 0; q < 8; ++q)
-                        w[q] = (uint32_t)f32_to_bf16(v[2 * q]) | ((uint32_t)f32_to_bf16(v[2 * q + 1]) << 16);
-                    dst[0] = make_uint4(w[0], w[1], w[2], w[3]);
-                    dst[1] = make_uint4(w[4], w[5], w[6], w[7]);
-                }
-                if (l_f32) {
-                    const float4* src = reinterpret_cast<const float4*>(reinterpret_cast<const float*>(p.target) + row * p.ldt + col0);
-#pragma clang loop unroll(full)
-                    for (int q = 0; q < 4; ++q) {
-                        const float4 t = src[q];
-                        const double d0 = (double)v[4 * q] - (double)t.x, d1 = (double)v[4 * q + 1] - (double)t.y;
-                        const double d2 = (double)v[4 * q + 2] - (double)t.z, d3 = (double)v[4 * q + 3] - (double)t.w;
-                        part = fma(d0, d0, part); part = fma(d1, d1, part);
-                        part = fma(d2, d2, part); part = fma(d3, d3, part);
+                        for (int q = 0; q < 4; ++q) dst[q] = make_float4(v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]);
                     }
-                }
-                if (l_bf16) {
-                    const uint4* src = reinterpret_cast<const uint4*>(reinterpret_cast<const bf16_t*>(p.target) + row * p.ldt + col0);
+                    if (y_bf16) {
+                        uint4* dst = reinterpret_cast<uint4*>(reinterpret_cast<bf16_t*>(p.Y) + row * p.ldy + col0);
+                        uint32_t w[8];
 #pragma clang loop unroll(full)
-                    for (int q = 0; q < 2; ++q) {
-                        const uint4 t = src[q];
-                        const uint32_t tw[4] = {t.x, t.y, t.z, t.w};
+                        for (int q = 0; q < 8; ++q)
+                            w[q] = (uint32_t)f32_to_bf16(v[2 * q]) | ((uint32_t)f32_to_bf16(v[2 * q + 1]) << 16);
+                        dst[0] = make_uint4(w[0], w[1], w[2], w[3]);
+                        dst[1] = make_uint4(w[4], w[5], w[6], w[7]);
+                    }
+                    if (l_f32) {
+                        const float4* src = reinterpret_cast<const float4*>(reinterpret_cast<const float*>(p.target) + row * p.ldt + col0);
 #pragma clang loop unroll(full)
-                        for (int u = 0; u < 4; ++u) {
-                            const double d0 = (double)v[8 * q + 2 * u] - (double)__uint_as_float(tw[u] << 16);
-                            const double d1 = (double)v[8 * q + 2 * u + 1] - (double)__uint_as_float(tw[u] & 0xFFFF0000u);
-                            part = fma(d0, d0, part); part = fma(d1, d1, part);
+                        for (int q = 0; q < 4; ++q) {
+                            const float4 t = src[q];
+                            const float tv[4] = {t.x, t.y, t.z, t.w};
+#pragma clang loop unroll(full)
+                            for (int u = 0; u < 4; ++u) {
+                                const double dd = (double)v[4 * q + u] - (double)tv[u];
+                                part = fma(dd, dd, part);
+                                if (SHARED) v[4 * q + u] = v[4 * q + u] - tv[u];
+                            }
+                        }
+                    }
+                    if (l_bf16) {
+                        const uint4* src = reinterpret_cast<const uint4*>(reinterpret_cast<const bf16_t*>(p.target) + row * p.ldt + col0);
+#pragma clang loop unroll(full)
+                        for (int q = 0; q < 2; ++q) {
+                            const uint4 t = src[q];
+                            const uint32_t tw[4] = {t.x, t.y, t.z, t.w};
+#pragma clang loop unroll(full)
+                            for (int u = 0; u < 4; ++u) {
+                                const float t0 = __uint_as_float(tw[u] << 16), t1 = __uint_as_float(tw[u] & 0xFFFF0000u);
+                                const double d0 = (double)v[8 * q + 2 * u] - (double)t0;
+                                const double d1 = (double)v[8 * q + 2 * u + 1] - (double)t1;
+                                part = fma(d0, d0, part); part = fma(d1, d1, part);
+                                if (SHARED) { v[8 * q + 2 * u] -= t0; v[8 * q + 2 * u + 1] -= t1; }
+                            }
+                        }
+                    }
+                } else {
+#pragma clang loop unroll(full)
+                    for (int e = 0; e < 16; ++e) {
+                        const int64_t col = col0 + e;
+                        if (col < p.N) {
+                            const float y = v[e];
+                            if (y_f32) reinterpret_cast<float*>(p.Y)[row * p.ldy + col] = y;
+                            if (y_bf16) reinterpret_cast<bf16_t*>(p.Y)[row * p.ldy + col] = f32_to_bf16(y);
+                            float tv = 0.f;
+                            if (l_f32) tv = reinterpret_cast<const float*>(p.target)[row * p.ldt + col];
+                            if (l_bf16) tv = bf16_to_f32(reinterpret_cast<const bf16_t*>(p.target)[row * p.ldt + col]);
+                            if (l_f32 || l_bf16) {
+                                const double dd = (double)y - (double)tv;
+                                part = fma(dd, dd, part);
+                                if (SHARED) v[e] = y - tv;
+                            }
                         }
                     }
                 }
-            } else {
-#pragma clang loop unroll(full)
-                for (int e = 0; e < 16; ++e) {
-                    const int64_t col = col0 + e;
-                    if (col < p.N) {
-                        const float y = v[e];
-                        if (y_f32) reinterpret_cast<float*>(p.Y)[row * p.ldy + col] = y;
-                        if (y_bf16) reinterpret_cast<bf16_t*>(p.Y)[row * p.ldy + col] = f32_to_bf16(y);
-                        if (l_f32) {
-                            const double dd = (double)y - (double)reinterpret_cast<const float*>(p.target)[row * p.ldt + col];
-                            part = fma(dd, dd, part);
-                        }
-                        if (l_bf16) {
-                            const double dd = (double)y - (double)bf16_to_f32(reinterpret_cast<const bf16_t*>(p.target)[row * p.ldt + col]);
-                            part = fma(dd, dd, part);
-                        }
-                    }
-                }
+                if (SHARED) acc[i][j] = v;
             }
         }
-    }
-    if (p.loss_kind == AGZO_LOSS_MSE) {
-        double* red = reinterpret_cast<double*>(smem);
-        red[tid] = part;
-        __syncthreads();
-        for (int s = NT / 2; s > 0; s >>= 1) {
-            if (tid < s) red[tid] += red[tid + s];
+        if (p.loss_kind == AGZO_LOSS_MSE) {
+            red[tid] = part;
+            __syncthreads();
+            for (int s = NT / 2; s > 0; s >>= 1) {
+                if (tid < s) red[tid] += red[tid + s];
+                __syncthreads();
+            }
+            if (tid == 0) p.partials[(int64_t)phase * p.tiles_m * p.tiles_n + tm * p.tiles_n + tn] = red[0];
             __syncthreads();
         }
-        if (tid == 0) p.partials[tm * p.tiles_n + tn] = red[0];
+    };
+    if (SHARED && next > 0) {
+        run_slices(0, nd);
+        evaluate(0);
+        run_slices(nd, nd + next);
+        evaluate(1);
+        run_slices(nd + next, total);
+        evaluate(2);
+    } else {
+        run_slices(0, total);
+        evaluate(0);
     }
 }
 
-template <int WA, int WB>
+
+template <int WA, int WB, bool SHARED>
 static hipError_t launch_variant(const GemmParams& p, hipStream_t st) {
     static bool attr_set = false;
-    const int smem = 4 * TILE_BYTES + 256 * WA * WB;
+    const int smem = 4 * TILE_BYTES + 256 * WA * WB + 64 * WA * WB * (int)sizeof(double);
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_bf16_kernel<WA, WB>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_bf16_kernel<WA, WB, SHARED>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, smem);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     dim3 grid((unsigned)((int64_t)p.tiles_m * p.tiles_n));
-    hipLaunchKernelGGL((gemm_bf16_kernel<WA, WB>), grid, dim3(64 * WA * WB), smem, st, p);
+    hipLaunchKernelGGL((gemm_bf16_kernel<WA, WB, SHARED>), grid, dim3(64 * WA * WB), smem, st, p);
     return hipGetLastError();
 }
 
@@ -401,16 +440,9 @@ hipError_t launch_gemm_bf16(const GemmBf16Args& a, hipStream_t st) {
     if (a.loss.kind == AGZO_LOSS_MSE)
         vec = vec && (a.loss.ldt % 8 == 0) && ((reinterpret_cast<uintptr_t>(a.loss.target) & 15) == 0);
     p.vec_ok = vec ? 1 : 0;
-    static int variant = -1;
-    if (variant < 0) {
-        const char* v = getenv("AGZO_GEMM_VARIANT");
-        variant = v ? atoi(v) : 0;
-    }
-    switch (variant) {
-        case 1: return launch_variant<4, 2>(p, st);
-        case 2: return launch_variant<2, 2>(p, st);
-        default: return launch_variant<2, 4>(p, st);
-    }
+    p.shared = a.shared ? 1 : 0;
+    if (p.shared) return launch_variant<2, 4, true>(p, st);
+    return launch_variant<2, 4, false>(p, st);
 }
 
 }  // namespace agzo

@@ -10,6 +10,7 @@ __global__ __launch_bounds__(256) void finish_loss_kernel(const double* __restri
     __shared__ double red[256];
     const int tid = threadIdx.x;
     double s = 0.0;
+    partials += (int64_t)blockIdx.x * n;
     for (int i = tid; i < n; i += 256) s += partials[i];
     red[tid] = s;
     __syncthreads();
@@ -17,7 +18,7 @@ __global__ __launch_bounds__(256) void finish_loss_kernel(const double* __restri
         if (tid < k) red[tid] += red[tid + k];
         __syncthreads();
     }
-    if (tid == 0) *out = red[0] * scale;
+    if (tid == 0) out[blockIdx.x] = red[0] * scale;
 }
 
 // out4 = {L0, L+, L-, g}
@@ -33,8 +34,8 @@ __global__ void two_point_kernel(double* __restrict__ out4, float eps, int one_s
     }
 }
 
-hipError_t launch_finish_loss(const double* partials, int n, double scale, double* out, hipStream_t st) {
-    hipLaunchKernelGGL(finish_loss_kernel, dim3(1), dim3(256), 0, st, partials, n, scale, out);
+hipError_t launch_finish_loss(const double* partials, int n, double scale, double* out, int nout, hipStream_t st) {
+    hipLaunchKernelGGL(finish_loss_kernel, dim3(nout), dim3(256), 0, st, partials, n, scale, out);
     return hipGetLastError();
 }
 

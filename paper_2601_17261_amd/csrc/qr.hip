@@ -3,13 +3,14 @@
 // diagonal, which is the unique thin-QR factorisation of a full-rank Y.  A non-positive pivot
 // (rank-deficient sketch) raises a device flag instead of producing NaNs.
 //
-// Three launches per QR:
-//   1. gram_chol      : Gram partials of Y per 128-row block (v_mfma_f64_16x16x4_f64); the block that
-//                       finishes last sums them in block order and one wave factors the r x r matrix
-//                       in registers (lane = column, rows broadcast with v_readlane)  -> R1
-//   2. apply_gram_chol: Q1 = Y R1^-1 by forward substitution, one thread per row (fp64, stored), then
-//                       Gram partials of Q1 and the last block's factorisation       -> R2
-//   3. apply_final    : Q = Q1 R2^-1 (fp32), optionally also as three bf16 planes [3][rp][d]
+// Three launches per QR, coherence between them by kernel boundaries only (no device-scope fences):
+//   1. gram        : Gram partials of Y per 128-row block (v_mfma_f64_16x16x4_f64)
+//   2. apply_gram  : every block sums the partials in block order and one of its waves factors the
+//                    r x r matrix in registers (lane = column, rows broadcast with v_readlane) -> R1;
+//                    Q1 = Y R1^-1 by forward substitution, one thread per row (fp64, stored), then
+//                    the Gram partials of Q1
+//   3. apply_final : the same reduction and factorisation -> R2; Q = Q1 R2^-1 (fp32), optionally
+//                    also as three bf16 planes [3][rp][d]
 // When the input arrives as per-token-range partial sketches, launch 1 sums them (fp64, fixed order)
 // on the way in and stores the fp32 sketch, so no separate reduction kernel is needed.
 #include "agzo_internal.h"
@@ -24,9 +25,8 @@ static inline int64_t qr_blocks(int64_t d) { return (d + QR_ROWS - 1) / QR_ROWS;
 
 size_t qr_workspace_bytes(int64_t d, int r) {
     const int rp = (r + 15) / 16 * 16;
-    // [Q1 fp64 d*r][gram partials nblk*rp*rp fp64][R1, R2: rp*rp fp64 each]
-    return (size_t)d * r * sizeof(double) + (size_t)qr_blocks(d) * rp * rp * sizeof(double) +
-           (size_t)2 * rp * rp * sizeof(double);
+    // [Q1 fp64 d*r][gram partials of Y and of Q1: nblk*rp*rp fp64 each]
+    return (size_t)d * r * sizeof(double) + (size_t)2 * qr_blocks(d) * rp * rp * sizeof(double);
 }
 
 __device__ __forceinline__ double readlane_f64(double v, int lane) {
@@ -52,7 +52,10 @@ __device__ int chol_wave(double* G, int r) {
         double piv = readlane_f64(col[j], j);
         if (j >= r) piv = 1.0;
         if (!(piv > 0.0)) { bad = 1; piv = 1.0; }
-        const double inv = 1.0 / sqrt(piv);
+        // 1/sqrt(piv): hardware estimate refined by two Newton steps (full fp64 accuracy, no divide)
+        double inv = __builtin_amdgcn_rsq(piv);
+        inv = inv * fma(-0.5 * piv * inv, inv, 1.5);
+        inv = inv * fma(-0.5 * piv * inv, inv, 1.5);
         const double rowj = col[j] * inv;                 // lane c: R[j][c]
         col[j] = (lane == j) ? inv : rowj;                // keep 1/R[j][j] on the diagonal
 #pragma unroll
@@ -75,11 +78,8 @@ __device__ int chol_dispatch(double* G, int r, int rp) {
 }
 
 // Gram partial of the block's rows (fp64 in LDS: Ys[row][ld], zero padded to a multiple of 4 rows and rp
-// columns) with the fp64 matrix cores, written to `partial`; the last block to arrive reduces all
-// partials in block order, factors, and stores the factor to Rout.  Gs: [rp][rp] LDS work matrix.
-__device__ void gram_then_last_block_chol(const double* Ys, int ld, double* Gs, int rows_pad, int r, int rp, double* partial,
-                                          int nblk, double* Rout, unsigned int* counter, int* flag) {
-    __shared__ int is_last;
+// columns) with the fp64 matrix cores, written to partial[blockIdx.x][rp][rp].
+__device__ void gram_partial(const double* Ys, int ld, int rows_pad, int rp, double* partial) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int nb = rp / 16;
     // block pair (bi, bj) of the Gram matrix per wave, round robin; operand lane layout of the 16x16x4
@@ -97,17 +97,13 @@ __device__ void gram_then_last_block_chol(const double* Ys, int ld, double* Gs, 
         for (int i = 0; i < 4; ++i)
             partial[((int64_t)blockIdx.x * rp + bi * 16 + 4 * i + (lane >> 4)) * rp + bj * 16 + (lane & 15)] = acc[i];
     }
-    __threadfence();                       // partials visible device-wide before the ticket is taken
-    __syncthreads();
-    if (tid == 0) {
-        const unsigned int ticket = atomicAdd(counter, 1u);
-        is_last = (ticket == (unsigned int)(nblk - 1));
-    }
-    __syncthreads();
-    if (!is_last) return;
-    __threadfence();                       // see every other block's partials
+}
+
+// Every block: Gs <- sum over blocks of partial (block order, sixteen loads in flight), then wave 0
+// factors it in place (upper factor, reciprocal diagonal).  Block 0 reports a bad pivot.
+__device__ void reduce_and_factor(const double* partial, int nblk, double* Gs, int r, int rp, int* flag) {
+    const int tid = threadIdx.x;
     for (int e = tid; e < rp * rp; e += blockDim.x) {
-        // sixteen independent running sums so that the loads overlap; the order is fixed all the same
         double a16[16];
 #pragma unroll
         for (int u = 0; u < 16; ++u) a16[u] = 0.0;
@@ -123,38 +119,47 @@ __device__ void gram_then_last_block_chol(const double* Ys, int ld, double* Gs, 
         Gs[e] = a16[0];
     }
     __syncthreads();
-    if (wave == 0) {
+    if (tid < 64) {
         const int bad = chol_dispatch(Gs, r, rp);
-        if (lane == 0) {
-            if (bad) *flag = 1;
-            *counter = 0u;                 // ready for the next launch on this stream
-        }
+        if (bad && tid == 0 && blockIdx.x == 0) *flag = 1;
     }
     __syncthreads();
-    for (int e = tid; e < rp * rp; e += blockDim.x) Rout[e] = Gs[e];
 }
 
-// row <- row R^-1 for upper-triangular R held in LDS with reciprocal diagonal (forward substitution)
-// q is the thread's own row in LDS (rows are an odd number of doubles apart: no bank conflicts)
+// row <- row R^-1 for upper-triangular R held in LDS with reciprocal diagonal (forward substitution);
+// the row stays in registers, R is read with broadcast loads
+template <int RP, typename Tin>
+__device__ __forceinline__ void solve_row_t(const Tin* y, const double* Rl, int r, double* q_out) {
+    double q[RP];
+#pragma unroll
+    for (int c = 0; c < RP; ++c) {
+        double s = (c < r) ? (double)y[c] : 0.0;
+#pragma unroll
+        for (int k = 0; k < c; ++k) s = fma(-q[k], Rl[k * RP + c], s);
+        q[c] = s * Rl[c * RP + c];
+    }
+#pragma unroll
+    for (int c = 0; c < RP; ++c) q_out[c] = q[c];
+}
+
 template <typename Tin>
 __device__ __forceinline__ void solve_row(const Tin* y, const double* Rl, int r, int rp, double* q) {
-    for (int c = 0; c < r; ++c) {
-        double s = (double)y[c];
-        for (int k = 0; k < c; ++k) s = fma(-q[k], Rl[k * rp + c], s);
-        q[c] = s * Rl[c * rp + c];
+    switch (rp) {
+        case 16: solve_row_t<16>(y, Rl, r, q); break;
+        case 32: solve_row_t<32>(y, Rl, r, q); break;
+        case 48: solve_row_t<48>(y, Rl, r, q); break;
+        default: solve_row_t<64>(y, Rl, r, q); break;
     }
 }
 
 // launch 1.  Input: S fp32 [d][r], or (splits != nullptr) partial sketches [nsplit][d][rp] whose sum is
 // stored to S_out as fp32 and used (in its rounded form) for the factorisation.
-__global__ __launch_bounds__(256) void qr_gram_chol_kernel(const float* __restrict__ S, const float* __restrict__ splits,
-                                                           int nsplit, float* __restrict__ S_out, int64_t d, int r,
-                                                           int rp, double* __restrict__ partial, int nblk,
-                                                           double* __restrict__ R1, unsigned int* counter, int* flag) {
+__global__ __launch_bounds__(256) void qr_gram_kernel(const float* __restrict__ S, const float* __restrict__ splits,
+                                                      int nsplit, float* __restrict__ S_out, int64_t d, int r, int rp,
+                                                      double* __restrict__ partial) {
     extern __shared__ __align__(16) double qr_smem[];
     const int ld = rp + 1;
     double* Ys = qr_smem;                 // [QR_ROWS][ld]
-    double* Gs = qr_smem + QR_ROWS * ld;  // [rp][rp]
     const int tid = threadIdx.x;
     const int64_t i0 = (int64_t)blockIdx.x * QR_ROWS;
     const int rows = (int)min((int64_t)QR_ROWS, d - i0);
@@ -202,15 +207,14 @@ __global__ __launch_bounds__(256) void qr_gram_chol_kernel(const float* __restri
         }
     }
     __syncthreads();
-    gram_then_last_block_chol(Ys, ld, Gs, rows_pad, r, rp, partial, nblk, R1, counter, flag);
+    gram_partial(Ys, ld, rows_pad, rp, partial);
 }
 
-// launch 2: Q1 = S R1^-1 for the block's rows (fp64, stored), then the Gram of Q1 as in launch 1.
-__global__ __launch_bounds__(256) void qr_apply_gram_chol_kernel(const float* __restrict__ S, int64_t d, int r, int rp,
-                                                                 const double* __restrict__ R1, double* __restrict__ Q1,
-                                                                 double* __restrict__ partial, int nblk,
-                                                                 double* __restrict__ R2, unsigned int* counter,
-                                                                 int* flag) {
+// launch 2: R1 from the partials, Q1 = S R1^-1 for the block's rows (fp64, stored), Gram partials of Q1.
+__global__ __launch_bounds__(256) void qr_apply_gram_kernel(const float* __restrict__ S, int64_t d, int r, int rp,
+                                                            const double* __restrict__ partial1, int nblk,
+                                                            double* __restrict__ Q1, double* __restrict__ partial2,
+                                                            int* flag) {
     extern __shared__ __align__(16) double qr_smem[];
     const int ld = rp + 1;
     double* Ys = qr_smem;
@@ -219,22 +223,22 @@ __global__ __launch_bounds__(256) void qr_apply_gram_chol_kernel(const float* __
     const int64_t i0 = (int64_t)blockIdx.x * QR_ROWS;
     const int rows = (int)min((int64_t)QR_ROWS, d - i0);
     const int rows_pad = (rows + 3) & ~3;
-    for (int e = tid; e < rp * rp; e += 256) Gs[e] = R1[e];
     for (int e = tid; e < rows_pad * ld; e += 256) Ys[e] = 0.0;
-    __syncthreads();
+    reduce_and_factor(partial1, nblk, Gs, r, rp, flag);
     if (tid < rows) {
         double* q = Ys + tid * ld;
         solve_row(S + (i0 + tid) * r, Gs, r, rp, q);
         for (int c = 0; c < r; ++c) Q1[(i0 + tid) * r + c] = q[c];
     }
     __syncthreads();
-    gram_then_last_block_chol(Ys, ld, Gs, rows_pad, r, rp, partial, nblk, R2, counter, flag);
+    gram_partial(Ys, ld, rows_pad, rp, partial2);
 }
 
 // launch 3: Q = Q1 R2^-1, rounded to fp32; planes (nullable) receive the hi/mid/lo bf16 parts [3][rp][d]
 __global__ __launch_bounds__(256) void qr_apply_final_kernel(const double* __restrict__ Q1, int64_t d, int r, int rp,
-                                                             const double* __restrict__ R2, float* __restrict__ Q,
-                                                             bf16_t* __restrict__ planes) {
+                                                             const double* __restrict__ partial2, int nblk,
+                                                             float* __restrict__ Q, bf16_t* __restrict__ planes,
+                                                             int* flag) {
     extern __shared__ __align__(16) double qr_smem[];
     const int ld = rp + 1;
     double* Gs = qr_smem;                 // [rp][rp]
@@ -242,8 +246,7 @@ __global__ __launch_bounds__(256) void qr_apply_final_kernel(const double* __res
     const int tid = threadIdx.x;
     const int64_t i0 = (int64_t)blockIdx.x * QR_ROWS;
     const int rows = (int)min((int64_t)QR_ROWS, d - i0);
-    for (int e = tid; e < rp * rp; e += 256) Gs[e] = R2[e];
-    __syncthreads();
+    reduce_and_factor(partial2, nblk, Gs, r, rp, flag);
     if (tid < rows) {
         double* q = Qs + tid * ld;
         solve_row(Q1 + (i0 + tid) * r, Gs, r, rp, q);
@@ -265,23 +268,21 @@ __global__ __launch_bounds__(256) void qr_apply_final_kernel(const double* __res
 }
 
 hipError_t launch_qr(const float* S, const float* splits, int nsplit, int rp, float* S_out, int64_t d, int r, float* Q,
-                     bf16_t* planes, void* workspace, unsigned int* counter, int* numeric_flag, hipStream_t st) {
+                     bf16_t* planes, void* workspace, int* numeric_flag, hipStream_t st) {
     if (d == 0) return hipSuccess;
     const int nblk = (int)qr_blocks(d);
     double* Q1 = reinterpret_cast<double*>(workspace);
-    double* partial = Q1 + d * r;
-    double* R1 = partial + (size_t)nblk * rp * rp;
-    double* R2 = R1 + rp * rp;
+    double* partial1 = Q1 + d * r;
+    double* partial2 = partial1 + (size_t)nblk * rp * rp;
     dim3 grid((unsigned)nblk), block(256);
     const size_t sm_full = ((size_t)QR_ROWS * (rp + 1) + (size_t)rp * rp) * sizeof(double);
-    const size_t sm_apply = sm_full;
     static bool attr_set = false;
     if (!attr_set) {
         const int big = (QR_ROWS * (kMaxRank + 1) + kMaxRank * kMaxRank) * (int)sizeof(double);
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(qr_gram_chol_kernel),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(qr_gram_kernel),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, big);
         if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(qr_apply_gram_chol_kernel),
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(qr_apply_gram_kernel),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, big);
         if (e == hipSuccess)
             e = hipFuncSetAttribute(reinterpret_cast<const void*>(qr_apply_final_kernel),
@@ -290,11 +291,11 @@ hipError_t launch_qr(const float* S, const float* splits, int nsplit, int rp, fl
         attr_set = true;
     }
     const float* Sin = splits ? S_out : S;
-    hipLaunchKernelGGL(qr_gram_chol_kernel, grid, block, sm_full, st, S, splits, nsplit, S_out, d, r, rp, partial, nblk, R1,
-                       counter, numeric_flag);
-    hipLaunchKernelGGL(qr_apply_gram_chol_kernel, grid, block, sm_full, st, Sin, d, r, rp, R1, Q1, partial, nblk, R2,
-                       counter, numeric_flag);
-    hipLaunchKernelGGL(qr_apply_final_kernel, grid, block, sm_apply, st, Q1, d, r, rp, R2, Q, planes);
+    hipLaunchKernelGGL(qr_gram_kernel, grid, block, sm_full, st, S, splits, nsplit, S_out, d, r, rp, partial1);
+    hipLaunchKernelGGL(qr_apply_gram_kernel, grid, block, sm_full, st, Sin, d, r, rp, partial1, nblk, Q1, partial2,
+                       numeric_flag);
+    hipLaunchKernelGGL(qr_apply_final_kernel, grid, block, sm_full, st, Q1, d, r, rp, partial2, nblk, Q, planes,
+                       numeric_flag);
     return hipGetLastError();
 }
 

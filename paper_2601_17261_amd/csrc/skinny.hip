@@ -116,11 +116,11 @@ constexpr int XTT_STEP = 32;
 
 int xtt_num_splits(int64_t M, int64_t K) {
     const int64_t panels = (K + XTT_PANEL - 1) / XTT_PANEL;
-    int64_t want = (1024 + panels - 1) / panels;
+    int64_t want = (256 + panels - 1) / panels;   // about one workgroup per CU; few splits keep the partials small
     const int64_t max_splits = (M + 4 * XTT_STEP - 1) / (4 * XTT_STEP);
     if (want > max_splits) want = max_splits;
     if (want < 1) want = 1;
-    if (want > 64) want = 64;
+    if (want > 16) want = 16;
     return (int)want;
 }
 

@@ -192,7 +192,8 @@ def test_forward_sketch_basis_perturbed_update(ctx, storage, n, d_in, d_out, r, 
     ("bf16", 515, 136, 300, 8, "lowrank"),
     ("bf16", 600, 1024, 520, 16, "rmsnorm"),
 ])
-@pytest.mark.parametrize("flags", [0, binding.ONE_SIDED, binding.INIT_FEATURE])
+@pytest.mark.parametrize("flags", [0, binding.ONE_SIDED, binding.INIT_FEATURE, binding.SHARED_FORWARD,
+                                   binding.SHARED_FORWARD | binding.ONE_SIDED])
 def test_step_matches_oracle(ctx, storage, n, d_in, d_out, r, kind, flags):
     seed = 99
     W, X, T, Wd, Xd, Td = problem(7 + n, n, d_in, d_out, kind, storage)
