@@ -77,7 +77,8 @@ typedef struct {
 typedef struct {
     int32_t kind;         /* agzo_loss_kind */
     int32_t target_dtype; /* MSE: AGZO_F32 or AGZO_BF16 target values; ignored for CE */
-    const void* target;   /* MSE: Y* [n_tokens][d_out], ld = ldt.  CE: int32 ids [n_tokens], < 0 = ignored row */
+    const void* target;   /* MSE: Y* [n_tokens][d_out], ld = ldt.  CE: int32 ids [n_tokens] in [0, d_out), < 0 = ignored row
+                             (loss = mean over the other rows of -log softmax(Y[row])[id], natural log) */
     int64_t ldt;
 } agzo_loss_spec;
 

@@ -116,6 +116,8 @@ def make_loss(target=None, kind=LOSS_MSE):
         return s
     s.kind = kind
     s.target = target.data_ptr()
+    if kind == LOSS_CE and target.dtype != torch.int32:
+        raise TypeError("cross-entropy targets must be int32 ids")
     if kind == LOSS_MSE:
         s.target_dtype = _dt(target)
         s.ldt = target.stride(0)

@@ -78,13 +78,13 @@ inline int64_t round32(int64_t n) { return (n + 31) / 32 * 32; }
 
 // carve-out of the ctx workspace for one layer; everything a step can need at the same time
 struct Plan {
-    size_t off_S, off_Q, off_B, off_pack, off_T, off_TpackT, off_xtt, off_qr, off_part, off_Ybuf, total;
+    size_t off_S, off_Q, off_B, off_pack, off_T, off_TpackT, off_xtt, off_qr, off_part, off_Ybuf, off_ce_ms, off_ce_tl, total;
     int rp, nsplit;
     int64_t m_pad;
     int n_part;
 };
 
-Plan make_plan(const agzo_layer& L, bool need_ybuf) {
+Plan make_plan(const agzo_layer& L, bool need_ybuf, bool ce = false) {
     Plan p;
     const bool bf = (L.dtype == AGZO_BF16);
     p.rp = round16(L.r);
@@ -102,7 +102,14 @@ Plan make_plan(const agzo_layer& L, bool need_ybuf) {
     p.off_TpackT = take(bf ? (size_t)3 * p.rp * p.m_pad * 2 : 0);
     p.off_xtt = take(bf ? (size_t)p.nsplit * L.d_in * p.rp * 4 : 0);
     p.off_qr = take(qr_workspace_bytes(L.d_in, L.r));
-    p.off_part = take((size_t)n_gemm * 8 * 3);
+    {
+        size_t part = (size_t)n_gemm * 3;                                          // MSE: one double per tile and phase
+        const size_t ce_part = (size_t)2 * L.n_tokens + 6 * ((L.n_tokens + 255) / 256);   // CE: (sum, count) pairs
+        if (ce && ce_part > part) part = ce_part;
+        p.off_part = take(part * 8);
+    }
+    p.off_ce_ms = take((ce && bf) ? (size_t)3 * gemm_bf16_ce_chunks(L.d_out) * L.n_tokens * 8 : 0);
+    p.off_ce_tl = take((ce && bf) ? (size_t)3 * L.n_tokens * 4 : 0);
     p.off_Ybuf = take(need_ybuf ? (size_t)L.n_tokens * L.d_out * 4 : 0);
     p.total = o;
     return p;
@@ -151,8 +158,10 @@ int check_y(agzo_ctx* ctx, const agzo_layer* L, const void* Y) {
 
 int check_loss(agzo_ctx* ctx, const agzo_layer* L, const agzo_loss_spec* loss, const double* loss_dev) {
     if (!loss || loss->kind == AGZO_LOSS_NONE) return 0;
-    if (loss->kind != AGZO_LOSS_MSE) return fail(ctx, AGZO_EINVAL, "loss kind %d not supported", loss->kind);
+    if (loss->kind != AGZO_LOSS_MSE && loss->kind != AGZO_LOSS_CE)
+        return fail(ctx, AGZO_EINVAL, "loss kind %d not supported", loss->kind);
     if (!loss->target || !loss_dev) return fail(ctx, AGZO_EINVAL, "loss needs a target and an output scalar");
+    if (loss->kind == AGZO_LOSS_CE) return 0;
     if (loss->ldt < L->d_out) return fail(ctx, AGZO_EINVAL, "ldt below d_out");
     if (loss->target_dtype != AGZO_F32 && loss->target_dtype != AGZO_BF16)
         return fail(ctx, AGZO_EINVAL, "target dtype %d", loss->target_dtype);
@@ -256,6 +265,12 @@ int op_forward(agzo_ctx* ctx, const agzo_layer& L, const Plan& p, const void* W,
     la.target = has_loss ? loss->target : nullptr;
     la.ldt = has_loss ? loss->ldt : 0;
     la.partials = reinterpret_cast<double*>(ctx->ws + p.off_part);
+    const bool ce = has_loss && loss->kind == AGZO_LOSS_CE;
+    const int32_t* ids = ce ? static_cast<const int32_t*>(loss->target) : nullptr;
+    if (ce && L.dtype == AGZO_BF16) {
+        la.ce_ms = ctx->ws + p.off_ce_ms;
+        la.ce_tl = wsf(ctx, p.off_ce_tl);
+    }
     if (L.dtype == AGZO_BF16) {
         GemmBf16Args a;
         a.X = static_cast<const bf16_t*>(X); a.ldx = L.ldx;
@@ -265,8 +280,13 @@ int op_forward(agzo_ctx* ctx, const agzo_layer& L, const Plan& p, const void* W,
         a.P = P; a.r = L.r; a.eps_signed = eps_signed; a.seed = seed;
         a.loss = la;
         a.shared = shared;
-        ProfScope ps(ctx, AGZO_PROF_GEMM);
-        HIPCHK(launch_gemm_bf16(a, st));
+        {
+            ProfScope ps(ctx, AGZO_PROF_GEMM);
+            HIPCHK(launch_gemm_bf16(a, st));
+        }
+        if (ce)
+            HIPCHK(launch_ce_combine(la.ce_ms, la.ce_tl, ids, L.n_tokens, gemm_bf16_ce_chunks(L.d_out), shared ? 3 : 1,
+                                     la.partials, loss_dev, st));
     } else {
         float* Yf = Y ? static_cast<float*>(Y) : wsf(ctx, p.off_Ybuf);
         const int64_t ldy = Y ? L.ldy : L.d_out;
@@ -278,13 +298,17 @@ int op_forward(agzo_ctx* ctx, const agzo_layer& L, const Plan& p, const void* W,
             l1.partials = la.partials + p.n_part;
             l2.partials = la.partials + 2 * p.n_part;
             HIPCHK(launch_epilogue_f32(Yf, ldy, L.n_tokens, L.d_out, nullptr, L.r, 0.f, seed, la, st));
+            if (ce) HIPCHK(launch_ce_rows_f32(Yf, ldy, L.n_tokens, L.d_out, ids, la.partials, loss_dev + 0, st));
             HIPCHK(launch_epilogue_f32(Yf, ldy, L.n_tokens, L.d_out, P, L.r, eps_signed, seed, l1, st));
+            if (ce) HIPCHK(launch_ce_rows_f32(Yf, ldy, L.n_tokens, L.d_out, ids, la.partials, loss_dev + 1, st));
             HIPCHK(launch_epilogue_f32(Yf, ldy, L.n_tokens, L.d_out, P, L.r, -2.f * eps_signed, seed, l2, st));
+            if (ce) HIPCHK(launch_ce_rows_f32(Yf, ldy, L.n_tokens, L.d_out, ids, la.partials, loss_dev + 2, st));
         } else {
             HIPCHK(launch_epilogue_f32(Yf, ldy, L.n_tokens, L.d_out, P, L.r, eps_signed, seed, la, st));
+            if (ce) HIPCHK(launch_ce_rows_f32(Yf, ldy, L.n_tokens, L.d_out, ids, la.partials, loss_dev, st));
         }
     }
-    if (has_loss)
+    if (has_loss && !ce)
         HIPCHK(launch_finish_loss(la.partials, p.n_part, 1.0 / ((double)L.n_tokens * (double)L.d_out), loss_dev,
                                   shared ? 3 : 1, st));
     return 0;
@@ -432,7 +456,7 @@ int agzo_layer_forward_sketch(agzo_ctx* ctx, const agzo_layer* L, const void* W,
         TRY(check_y(ctx, L, Y));
         TRY(check_loss(ctx, L, loss, loss_dev));
     }
-    const Plan p = make_plan(*L, gemm && L->dtype == AGZO_F32 && !Y);
+    const Plan p = make_plan(*L, gemm && L->dtype == AGZO_F32 && !Y, loss && loss->kind == AGZO_LOSS_CE);
     TRY(reserve(ctx, p.total));
     if (gemm) TRY(op_forward(ctx, *L, p, W, X, nullptr, 0.f, seed, Y, loss, loss_dev));
     if (mode == AGZO_SKETCH_RANGE) {
@@ -472,7 +496,7 @@ int agzo_perturbed_forward(agzo_ctx* ctx, const agzo_layer* L, const void* W, co
     if (!W || !X || !B) return fail(ctx, AGZO_EINVAL, "W, X or B is NULL");
     TRY(check_y(ctx, L, Y));
     TRY(check_loss(ctx, L, loss, loss_dev));
-    const Plan p = make_plan(*L, L->dtype == AGZO_F32 && !Y);
+    const Plan p = make_plan(*L, L->dtype == AGZO_F32 && !Y, loss && loss->kind == AGZO_LOSS_CE);
     TRY(reserve(ctx, p.total));
     float* P = wsf(ctx, p.off_T);
     TRY(op_project(ctx, *L, p, X, B, P, false));
@@ -502,7 +526,7 @@ int agzo_step(agzo_ctx* ctx, const agzo_layer* L, void* W, const void* X, const 
     if (K < 0 || K > 64) return fail(ctx, AGZO_EINVAL, "K=%d outside 0..64", K);
     if (!(eps > 0.f)) return fail(ctx, AGZO_EINVAL, "eps must be positive");
     if (L->dtype == AGZO_BF16 && (reinterpret_cast<uintptr_t>(W) & 15)) return fail(ctx, AGZO_EINVAL, "W misaligned");
-    const Plan p = make_plan(*L, L->dtype == AGZO_F32);
+    const Plan p = make_plan(*L, L->dtype == AGZO_F32, loss->kind == AGZO_LOSS_CE);
     TRY(reserve(ctx, p.total));
     hipStream_t st = ctx->stream;
     float* B = wsf(ctx, p.off_B);

@@ -84,6 +84,9 @@ struct GemmLossArgs {
     const void* target;
     int64_t ldt;
     double* partials;     // [n_workgroups] (MSE) scratch
+    // cross-entropy scratch: (max, sum exp) per (phase, column chunk, token) and target logit per (phase, token)
+    void* ce_ms = nullptr;
+    float* ce_tl = nullptr;
 };
 
 // philox.hip
@@ -142,6 +145,14 @@ hipError_t launch_update(void* W, int dtype, int64_t ldw, int64_t d_out, int64_t
                          uint64_t seed, float lr, const double* g_dev, hipStream_t st);
 
 // loss.hip
+// cross-entropy from the GEMM's per-chunk softmax statistics: out[ph] = mean over rows with target >= 0 of
+// log(sum exp) - logit[target];  ms: float2 [nphase][nchunk][M], tl: float [nphase][M]
+int gemm_bf16_ce_chunks(int64_t N);
+hipError_t launch_ce_combine(const void* ms, const float* tl, const int32_t* target, int64_t M, int nchunk, int nphase,
+                             double* scratch, double* out, hipStream_t st);
+// cross-entropy of stored fp32 logits Y [M][N] (fp32-storage path): out[0] as above
+hipError_t launch_ce_rows_f32(const float* Y, int64_t ldy, int64_t M, int64_t N, const int32_t* target, double* scratch,
+                              double* out, hipStream_t st);
 // out[b] = scale * sum(partials[b*n .. b*n+n)), b < nout
 hipError_t launch_finish_loss(const double* partials, int n, double scale, double* out, int nout, hipStream_t st);
 hipError_t launch_two_point(double* out4, float eps, int one_sided, hipStream_t st);

@@ -22,6 +22,8 @@ constexpr int BK = 64;
 constexpr int CHUNKS = BK / 8;                 // 16-byte chunks per tile row
 constexpr int TILE_BYTES = BT * BK * 2;        // one operand tile: 32 KiB
 
+int gemm_bf16_ce_chunks(int64_t N) { return (int)((N + BT - 1) / BT) * 2; }   // 128-column chunks (2 per tile)
+
 int gemm_bf16_num_workgroups(int64_t M, int64_t N) {
     return (int)(((M + BT - 1) / BT) * ((N + BT - 1) / BT));
 }
@@ -45,10 +47,12 @@ struct GemmParams {
     int tiles_m, tiles_n;
     int vec_ok;                 // 16-byte epilogue accesses are legal
     int shared;                 // one pass evaluates f0, f+ and f- (three loss partials per tile)
+    // cross-entropy: per (128-column chunk, token) running max and sum of exponentials, and the target's logit
+    const int32_t* ce_target; float2* ce_ms; float* ce_tl;
 };
 
 // WA x WB waves: WA splits the 256 outputs, WB splits the 256 tokens
-template <int WA, int WB, bool SHARED>
+template <int WA, int WB, bool SHARED, bool CE>
 __global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
     constexpr int NT = 64 * WA * WB;
     constexpr int BA = BT / WA / 32;           // 32-row blocks of W per wave
@@ -226,7 +230,7 @@ __global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
     // so that the epilogue's reads find the tile in L2.  These loads are issued after the slice's
     // operand loads and are the only ones allowed to stay in flight across the slice's closing wait.
     const int first_epi = SHARED ? nd - 1 : total - 1;
-    const bool pf_on = (p.loss_kind == AGZO_LOSS_MSE) && first_epi >= 5;
+    const bool pf_on = !CE && (p.loss_kind == AGZO_LOSS_MSE) && first_epi >= 5;
     const int pf_first = first_epi - 5;
     char* sink = smem + 4 * TILE_BYTES + wave * 256;
     double* red = reinterpret_cast<double*>(smem + 4 * TILE_BYTES + 256 * WA * WB);
@@ -234,8 +238,8 @@ __global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
     const int lines_per_row = (BT << t_shift) >> 7;                    // 128-byte lines per tile row
     const bool y_f32 = (p.Y != nullptr) && p.y_dtype != AGZO_BF16;
     const bool y_bf16 = (p.Y != nullptr) && p.y_dtype == AGZO_BF16;
-    const bool l_f32 = p.loss_kind == AGZO_LOSS_MSE && p.target_dtype != AGZO_BF16;
-    const bool l_bf16 = p.loss_kind == AGZO_LOSS_MSE && p.target_dtype == AGZO_BF16;
+    const bool l_f32 = !CE && p.loss_kind == AGZO_LOSS_MSE && p.target_dtype != AGZO_BF16;
+    const bool l_bf16 = !CE && p.loss_kind == AGZO_LOSS_MSE && p.target_dtype == AGZO_BF16;
     auto run_slices = [&](int it_begin, int it_end) __attribute__((always_inline)) {
     for (int it = it_begin; it < it_end; ++it) {
         const int cur = it & 1;
@@ -301,7 +305,7 @@ __global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
         double part = 0.0;
         // shared mode: the first evaluation turns the accumulators into the residual Y0 - Y*, so the
         // target is read once and the two perturbed evaluations are sums of squares of registers
-        const bool resid = SHARED && phase > 0;
+        const bool resid = !CE && SHARED && phase > 0 && p.loss_kind == AGZO_LOSS_MSE;
 #pragma clang loop unroll(full)
         for (int j = 0; j < BB; ++j) {
             const int64_t row = m0 + wb * (BT / WB) + j * 32 + lr;
@@ -383,7 +387,46 @@ __global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
                 if (SHARED) acc[i][j] = v;
             }
         }
-        if (p.loss_kind == AGZO_LOSS_MSE) {
+        if (CE) {
+            // a lane holds 16 of the 32 logits of each of its BA blocks for BB tokens; its partner lane
+            // (lane ^ 32) holds the other 16.  Online softmax over the wave's columns, per token.
+#pragma clang loop unroll(full)
+            for (int j = 0; j < BB; ++j) {
+                const int64_t row = m0 + wb * (BT / WB) + j * 32 + lr;
+                const int tgt = (row < p.M) ? p.ce_target[row] : -1;
+                float mx = -INFINITY, tl = 0.f;
+                bool has_tl = false;
+#pragma clang loop unroll(full)
+                for (int i = 0; i < BA; ++i) {
+                    const int64_t col0 = n0 + wa * (BT / WA) + i * 32 + lh * 16;
+#pragma clang loop unroll(full)
+                    for (int e = 0; e < 16; ++e) {
+                        const float y = acc[i][j][e];
+                        if (col0 + e < p.N) {
+                            mx = fmaxf(mx, y);
+                            if ((int64_t)tgt == col0 + e) { tl = y; has_tl = true; }
+                        }
+                    }
+                }
+                mx = fmaxf(mx, __shfl_xor(mx, 32));
+                float sm = 0.f;
+#pragma clang loop unroll(full)
+                for (int i = 0; i < BA; ++i) {
+                    const int64_t col0 = n0 + wa * (BT / WA) + i * 32 + lh * 16;
+#pragma clang loop unroll(full)
+                    for (int e = 0; e < 16; ++e)
+                        if (col0 + e < p.N) sm += expf(acc[i][j][e] - mx);
+                }
+                sm += __shfl_xor(sm, 32);
+                if (row < p.M) {
+                    const int64_t chunk = tn * WA + wa;
+                    const int64_t nchunk = (int64_t)p.tiles_n * WA;
+                    if (lh == 0) p.ce_ms[((int64_t)phase * nchunk + chunk) * p.M + row] = make_float2(mx, sm);
+                    if (has_tl) p.ce_tl[(int64_t)phase * p.M + row] = tl;
+                }
+            }
+        }
+        if (!CE && p.loss_kind == AGZO_LOSS_MSE) {
             red[tid] = part;
             __syncthreads();
             for (int s = NT / 2; s > 0; s >>= 1) {
@@ -408,18 +451,18 @@ __global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
 }
 
 
-template <int WA, int WB, bool SHARED>
+template <int WA, int WB, bool SHARED, bool CE>
 static hipError_t launch_variant(const GemmParams& p, hipStream_t st) {
     static bool attr_set = false;
     const int smem = 4 * TILE_BYTES + 256 * WA * WB + 64 * WA * WB * (int)sizeof(double);
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_bf16_kernel<WA, WB, SHARED>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_bf16_kernel<WA, WB, SHARED, CE>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, smem);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     dim3 grid((unsigned)((int64_t)p.tiles_m * p.tiles_n));
-    hipLaunchKernelGGL((gemm_bf16_kernel<WA, WB, SHARED>), grid, dim3(64 * WA * WB), smem, st, p);
+    hipLaunchKernelGGL((gemm_bf16_kernel<WA, WB, SHARED, CE>), grid, dim3(64 * WA * WB), smem, st, p);
     return hipGetLastError();
 }
 
@@ -441,8 +484,12 @@ hipError_t launch_gemm_bf16(const GemmBf16Args& a, hipStream_t st) {
         vec = vec && (a.loss.ldt % 8 == 0) && ((reinterpret_cast<uintptr_t>(a.loss.target) & 15) == 0);
     p.vec_ok = vec ? 1 : 0;
     p.shared = a.shared ? 1 : 0;
-    if (p.shared) return launch_variant<2, 4, true>(p, st);
-    return launch_variant<2, 4, false>(p, st);
+    p.ce_target = reinterpret_cast<const int32_t*>(a.loss.target);
+    p.ce_ms = reinterpret_cast<float2*>(a.loss.ce_ms);
+    p.ce_tl = a.loss.ce_tl;
+    const bool ce = (p.loss_kind == AGZO_LOSS_CE);
+    if (p.shared) return ce ? launch_variant<2, 4, true, true>(p, st) : launch_variant<2, 4, true, false>(p, st);
+    return ce ? launch_variant<2, 4, false, true>(p, st) : launch_variant<2, 4, false, false>(p, st);
 }
 
 }  // namespace agzo

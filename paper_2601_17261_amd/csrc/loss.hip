@@ -34,6 +34,110 @@ __global__ void two_point_kernel(double* __restrict__ out4, float eps, int one_s
     }
 }
 
+// ---- cross-entropy -----------------------------------------------------------------------------
+// one thread per token: merge the chunk statistics, loss_t = log(sum exp) - logit[target]; block sums
+// of (loss, count) go to scratch[2*block], the last stage divides.
+__global__ __launch_bounds__(256) void ce_combine_kernel(const float2* __restrict__ ms, const float* __restrict__ tl,
+                                                         const int32_t* __restrict__ target, int64_t M, int nchunk,
+                                                         double* __restrict__ scratch) {
+    __shared__ double rs[256], rc[256];
+    const int tid = threadIdx.x;
+    const int ph = blockIdx.y;
+    const int64_t t = (int64_t)blockIdx.x * 256 + tid;
+    double loss = 0.0, cnt = 0.0;
+    if (t < M && target[t] >= 0) {
+        const float2* m = ms + (int64_t)ph * nchunk * M + t;
+        float mx = -INFINITY;
+        for (int c = 0; c < nchunk; ++c) mx = fmaxf(mx, m[(int64_t)c * M].x);
+        double s = 0.0;
+        for (int c = 0; c < nchunk; ++c) {
+            const float2 v = m[(int64_t)c * M];
+            s += (double)v.y * exp((double)v.x - (double)mx);
+        }
+        loss = log(s) + (double)mx - (double)tl[(int64_t)ph * M + t];
+        cnt = 1.0;
+    }
+    rs[tid] = loss; rc[tid] = cnt;
+    __syncthreads();
+    for (int k = 128; k > 0; k >>= 1) {
+        if (tid < k) { rs[tid] += rs[tid + k]; rc[tid] += rc[tid + k]; }
+        __syncthreads();
+    }
+    if (tid == 0) {
+        scratch[((int64_t)ph * gridDim.x + blockIdx.x) * 2] = rs[0];
+        scratch[((int64_t)ph * gridDim.x + blockIdx.x) * 2 + 1] = rc[0];
+    }
+}
+
+__global__ __launch_bounds__(256) void ce_finish_kernel(const double* __restrict__ scratch, int nblk, double* __restrict__ out) {
+    __shared__ double rs[256], rc[256];
+    const int tid = threadIdx.x, ph = blockIdx.x;
+    double s = 0.0, c = 0.0;
+    for (int i = tid; i < nblk; i += 256) {
+        s += scratch[((int64_t)ph * nblk + i) * 2];
+        c += scratch[((int64_t)ph * nblk + i) * 2 + 1];
+    }
+    rs[tid] = s; rc[tid] = c;
+    __syncthreads();
+    for (int k = 128; k > 0; k >>= 1) {
+        if (tid < k) { rs[tid] += rs[tid + k]; rc[tid] += rc[tid + k]; }
+        __syncthreads();
+    }
+    if (tid == 0) out[ph] = rc[0] > 0.0 ? rs[0] / rc[0] : 0.0;
+}
+
+hipError_t launch_ce_combine(const void* ms, const float* tl, const int32_t* target, int64_t M, int nchunk, int nphase,
+                             double* scratch, double* out, hipStream_t st) {
+    const int nblk = (int)((M + 255) / 256);
+    hipLaunchKernelGGL(ce_combine_kernel, dim3(nblk, nphase), dim3(256), 0, st, reinterpret_cast<const float2*>(ms), tl,
+                       target, M, nchunk, scratch);
+    hipLaunchKernelGGL(ce_finish_kernel, dim3(nphase), dim3(256), 0, st, scratch, nblk, out);
+    return hipGetLastError();
+}
+
+// fp32-storage path: one workgroup per token row of stored logits, fp64 statistics
+__global__ __launch_bounds__(256) void ce_rows_f32_kernel(const float* __restrict__ Y, int64_t ldy, int64_t M, int64_t N,
+                                                          const int32_t* __restrict__ target, double* __restrict__ scratch) {
+    __shared__ double red[256];
+    const int tid = threadIdx.x;
+    const int64_t t = blockIdx.x;
+    const int tgt = target[t];
+    if (tgt < 0) {
+        if (tid == 0) { scratch[t * 2] = 0.0; scratch[t * 2 + 1] = 0.0; }
+        return;
+    }
+    const float* y = Y + t * ldy;
+    double mx = -INFINITY;
+    for (int64_t j = tid; j < N; j += 256) mx = fmax(mx, (double)y[j]);
+    red[tid] = mx;
+    __syncthreads();
+    for (int k = 128; k > 0; k >>= 1) {
+        if (tid < k) red[tid] = fmax(red[tid], red[tid + k]);
+        __syncthreads();
+    }
+    mx = red[0];
+    __syncthreads();
+    double s = 0.0;
+    for (int64_t j = tid; j < N; j += 256) s += exp((double)y[j] - mx);
+    red[tid] = s;
+    __syncthreads();
+    for (int k = 128; k > 0; k >>= 1) {
+        if (tid < k) red[tid] += red[tid + k];
+        __syncthreads();
+    }
+    if (tid == 0) {
+        scratch[t * 2] = log(red[0]) + mx - (double)y[tgt];
+        scratch[t * 2 + 1] = 1.0;
+    }
+}
+
+hipError_t launch_ce_rows_f32(const float* Y, int64_t ldy, int64_t M, int64_t N, const int32_t* target, double* scratch,
+                              double* out, hipStream_t st) {
+    hipLaunchKernelGGL(ce_rows_f32_kernel, dim3((unsigned)M), dim3(256), 0, st, Y, ldy, M, N, target, scratch);
+    hipLaunchKernelGGL(ce_finish_kernel, dim3(1), dim3(256), 0, st, scratch, (int)M, out);
+    return hipGetLastError();
+}
+
 hipError_t launch_finish_loss(const double* partials, int n, double scale, double* out, int nout, hipStream_t st) {
     hipLaunchKernelGGL(finish_loss_kernel, dim3(nout), dim3(256), 0, st, partials, n, scale, out);
     return hipGetLastError();

@@ -214,6 +214,39 @@ def test_step_matches_oracle(ctx, storage, n, d_in, d_out, r, kind, flags):
     assert rel(host(Wd), o["W_new"]) < (1e-6 if storage == "f32" else 3e-3)
 
 
+@pytest.mark.parametrize("storage,n,d_in,d_out,r", [("f32", 200, 96, 130, 4), ("bf16", 515, 136, 300, 8),
+                                                      ("bf16", 512, 256, 1000, 16)])
+@pytest.mark.parametrize("flags", [0, binding.SHARED_FORWARD])
+def test_cross_entropy_step_matches_oracle(ctx, storage, n, d_in, d_out, r, flags):
+    """Token cross-entropy on the layer's outputs as logits (LM-head shape: d_out = vocabulary), with
+    ignored rows (target -1)."""
+    W, X, _ = synth.single_layer_problem(21 + n, n, d_in, d_out, kind="lowrank", storage=storage)
+    W = (W * 5.0).astype(np.float32)                       # logits with some spread
+    if storage == "bf16":
+        W = synth.to_bf16_values(W)
+    rng = np.random.default_rng(n)
+    ids = rng.integers(0, d_out, size=n).astype(np.int32)
+    ids[rng.choice(n, size=n // 7, replace=False)] = -1
+    Wd, Xd, Td = dev(W, storage), dev(X, storage), torch.from_numpy(ids).cuda()
+    L = binding.make_layer(Wd, Xd, r)
+    loss = binding.make_loss(Td, kind=binding.LOSS_CE)
+    # forward entry point on its own
+    sc = torch.zeros(1, dtype=torch.float64, device="cuda")
+    ctx.layer_forward_sketch(L, Wd, Xd, None, binding.SKETCH_NONE, None, 1, None, loss, sc)
+    L0 = oagzo.ce_loss(oagzo.forward(X, W), ids)
+    assert abs(sc.item() - L0) < 2e-6 * L0
+    out = torch.zeros(4, dtype=torch.float64, device="cuda")
+    ctx.step(L, Wd, Xd, loss, 3, EPS, LR, 17, flags, out)
+    ctx.check()
+    o = oagzo.agzo_step(W, X, ids, r, 3, EPS, LR, 17, loss="ce", storage=storage)
+    got = out.cpu().numpy()
+    assert abs(got[0] - o["L0"]) < 2e-6 * o["L0"]
+    assert abs(got[1] - o["Lp"]) < 2e-6 * o["Lp"]
+    assert abs(got[2] - o["Lm"]) < 2e-6 * o["Lm"]
+    assert abs(got[3] - o["g"]) < 2e-2 * abs(o["g"]) + 1e-7, (got[3], o["g"])
+    assert rel(host(Wd), o["W_new"]) < (1e-6 if storage == "f32" else 3e-3)
+
+
 def test_config1_trajectory_20_steps(ctx):
     """The small fp32 workload in full: 256x256 layer, 512 tokens, r=4, K=3, 20 steps."""
     W, X, T, Wd, Xd, Td = problem(0, 512, 256, 256, "lowrank", "f32")
