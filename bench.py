@@ -67,6 +67,59 @@ def cpu_baseline(n_tokens, r, K, eps, lr, layer_flops):
                       "scaled by the layer set's forward-flop ratio %.1f" % (n_tokens, r, K, dt, ratio)}
 
 
+def sweep(args):
+    """Qwen3-4B shapes, r in {1,4,16,64} x N in {512,4096,16384,65536}: per kernel the achieved rate, the
+    algorithmic intensity and which roofline (HBM or MFMA) bounds it.  Prints one text table."""
+    ctx = binding.Context()
+    eps = float(np.float32(1e-3))
+    projs = [p for p in synth.QWEN3_4B_LAYER if p[0] in ("q", "k", "gate", "down")]
+    print("# kernel rates on Qwen3-4B-shaped projections, bf16; bound = larger of flops/2500 TFLOP/s and bytes/8000 GB/s")
+    print("# %-5s %6s %3s | %-9s %9s %9s %8s %7s %6s" % ("proj", "N", "r", "kernel", "us", "TFLOP/s", "GB/s", "flop/B", "bound"))
+    for N in (512, 4096, 16384, 65536):
+        xs = {}
+        for name, d_in, d_out in projs:
+            if d_in not in xs:
+                xs[d_in] = synth.device_powerlaw_x(7 + d_in, N, d_in)
+            X = xs[d_in]
+            W, T = synth.device_weights_and_target(3 + d_out, X, d_out)
+            loss = binding.make_loss(T)
+            sc = torch.zeros(4, dtype=torch.float64, device="cuda")
+            for r in (1, 4, 16, 64):
+                if r > min(N, d_in):
+                    continue
+                L = binding.make_layer(W, X, r)
+                B = torch.empty(d_in, r, device="cuda")
+                ctx.basis(L, X, 1, 5, None, 0, B)
+                ctx.check()
+
+                def timed(kind, fn, reps=5):
+                    fn()
+                    ctx.profile_enable(True)
+                    for _ in range(reps):
+                        fn()
+                    n, ms = ctx.profile_read(kind)
+                    ctx.profile_enable(False)
+                    return 1e3 * ms / max(n, 1)       # us per launch of that kernel class
+
+                rows = []
+                us = timed(binding.PROF_GEMM, lambda: ctx.perturbed_forward(L, W, X, B, 5, eps, None, loss, sc[1:2]))
+                rows.append(("pfwd+loss", us, 2.0 * N * d_in * d_out + 2.0 * N * r * (d_in + d_out),
+                             2.0 * N * d_in + 2.0 * d_in * d_out + 4.0 * N * d_out))
+                us = timed(binding.PROF_XQ, lambda: ctx.layer_forward_sketch(L, None, X, None, 2, B, 5, B.clone(), None, None))
+                rows.append(("xq", us, 2.0 * N * d_in * r, 2.0 * N * d_in))
+                us = timed(binding.PROF_XTT, lambda: ctx.layer_forward_sketch(L, None, X, None, 1, None, 5, B.clone(), None, None))
+                rows.append(("xtt", us, 2.0 * N * d_in * r, 2.0 * N * d_in))
+                us = timed(binding.PROF_UPDATE, lambda: ctx.update(L, W, B, 5, 1e-9, None))
+                rows.append(("update", us, 2.0 * r * d_in * d_out, 4.0 * d_in * d_out))
+                for kname, us, fl, by in rows:
+                    bound = "mfma" if fl / 2.5e15 > by / 8e12 else "hbm"
+                    print("  %-5s %6d %3d | %-9s %9.1f %9.1f %8.0f %7.1f %6s" %
+                          (name, N, r, kname, us, fl / us / 1e6, by / us / 1e3, fl / by, bound), flush=True)
+            del W, T
+        del xs
+        torch.cuda.empty_cache()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -78,6 +131,7 @@ def main():
     ap.add_argument("--naive", action="store_true", help="time the perturb-in-place / undo comparator instead")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (known traffic) so counter runs can be scaled")
+    ap.add_argument("--sweep", action="store_true", help="rank x tokens sweep on Qwen3-4B shapes (text table)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives are part of it); use --gpus 1",
@@ -87,6 +141,9 @@ def main():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         sys.exit(2)
 
+    if args.sweep:
+        sweep(args)
+        return
     N, r, K = args.tokens, args.rank, 3
     eps, lr = float(np.float32(1e-3)), float(np.float32(1e-4))
     shapes = synth.QWEN3_8B_LAYER

@@ -180,9 +180,11 @@ def test_forward_sketch_basis_perturbed_update(ctx, storage, n, d_in, d_out, r, 
     assert rel(host(Wu), want) < (1e-6 if storage == "f32" else 2e-3)
     assert rel(host(Wu) - W64, want - W64) < (1e-4 if storage == "f32" else 0.2)
     if storage == "bf16":
-        # rounding decisions taken in fp32 instead of fp64: at most isolated one-ulp flips
+        # rounding decisions taken in fp32 instead of fp64: at most isolated one-ulp flips, plus the
+        # increment's own error (bf16 hi/lo operands on the matrix cores: 2^-16 relative) where the
+        # increment nearly cancels the weight
         ulp = np.abs(want) * 2.0 ** -7
-        assert (np.abs(host(Wu) - want) <= ulp + 1e-30).all()
+        assert (np.abs(host(Wu) - want) <= ulp + 2.0 ** -15 * np.abs(want - W64) + 1e-30).all()
         assert np.mean(host(Wu) != want) < 2e-3
     ctx.check()
 
