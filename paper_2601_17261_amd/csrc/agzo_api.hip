@@ -78,7 +78,7 @@ inline int64_t round32(int64_t n) { return (n + 31) / 32 * 32; }
 
 // carve-out of the ctx workspace for one layer; everything a step can need at the same time
 struct Plan {
-    size_t off_S, off_Q, off_B, off_pack, off_T, off_TpackT, off_xtt, off_qr, off_part, off_Ybuf, off_ce_ms, off_ce_tl, total;
+    size_t off_S, off_Q, off_B, off_pack, off_T, off_TpackT, off_xtt, off_qr, off_part, off_Ybuf, off_ce_ms, off_ce_tl, off_upd, total;
     int rp, nsplit;
     int64_t m_pad;
     int n_part;
@@ -110,6 +110,7 @@ Plan make_plan(const agzo_layer& L, bool need_ybuf, bool ce = false) {
     }
     p.off_ce_ms = take((ce && bf) ? (size_t)3 * gemm_bf16_ce_chunks(L.d_out) * L.n_tokens * 8 : 0);
     p.off_ce_tl = take((ce && bf) ? (size_t)3 * L.n_tokens * 4 : 0);
+    p.off_upd = take(update_workspace_bytes(L.dtype, L.d_out, L.d_in, L.r));
     p.off_Ybuf = take(need_ybuf ? (size_t)L.n_tokens * L.d_out * 4 : 0);
     p.total = o;
     return p;
@@ -314,10 +315,10 @@ int op_forward(agzo_ctx* ctx, const agzo_layer& L, const Plan& p, const void* W,
     return 0;
 }
 
-int op_update(agzo_ctx* ctx, const agzo_layer& L, void* W, const float* B, uint64_t seed, float lr,
+int op_update(agzo_ctx* ctx, const agzo_layer& L, size_t off_upd, void* W, const float* B, uint64_t seed, float lr,
               const double* g_dev) {
     ProfScope ps(ctx, AGZO_PROF_UPDATE);
-    HIPCHK(launch_update(W, L.dtype, L.ldw, L.d_out, L.d_in, B, L.r, seed, lr, g_dev, ctx->stream));
+    HIPCHK(launch_update(W, L.dtype, L.ldw, L.d_out, L.d_in, B, L.r, seed, lr, g_dev, ctx->ws + off_upd, ctx->stream));
     return 0;
 }
 
@@ -511,9 +512,10 @@ int agzo_update(agzo_ctx* ctx, const agzo_layer* L, void* W, const float* B, uin
     if (L->d_in < 1 || L->d_out < 1 || L->r < 1 || L->r > kMaxRank || L->r > L->d_in || L->ldw < L->d_in)
         return fail(ctx, AGZO_EINVAL, "bad layer shape");
     if (L->dtype != AGZO_F32 && L->dtype != AGZO_BF16) return fail(ctx, AGZO_EINVAL, "dtype %d", L->dtype);
-    if (L->dtype == AGZO_BF16 && (L->ldw % 8 || (reinterpret_cast<uintptr_t>(W) & 15)))
-        return fail(ctx, AGZO_EINVAL, "bf16 W needs 16-byte aligned rows");
-    TRY(op_update(ctx, *L, W, B, seed, lr, g_dev));
+    if (L->dtype == AGZO_BF16 && (L->d_in % 8 || L->ldw % 8 || (reinterpret_cast<uintptr_t>(W) & 15)))
+        return fail(ctx, AGZO_EINVAL, "bf16 W needs d_in and ldw multiples of 8 and 16-byte aligned rows");
+    TRY(reserve(ctx, update_workspace_bytes(L->dtype, L->d_out, L->d_in, L->r)));
+    TRY(op_update(ctx, *L, 0, W, B, seed, lr, g_dev));
     return AGZO_OK;
 }
 
@@ -540,7 +542,7 @@ int agzo_step(agzo_ctx* ctx, const agzo_layer* L, void* W, const void* X, const 
         TRY(op_project(ctx, *L, p, X, B, P, true));
         TRY(op_forward(ctx, *L, p, W, X, P, eps, seed, nullptr, loss, out_dev, true));
         HIPCHK(launch_two_point(out_dev, eps, one_sided ? 1 : 0, st));
-        TRY(op_update(ctx, *L, W, B, seed, lr, out_dev + 3));
+        TRY(op_update(ctx, *L, p.off_upd, W, B, seed, lr, out_dev + 3));
         return AGZO_OK;
     }
     // 1. base forward f0 and subspace extraction from the same activations (Alg. 2, part 1)
@@ -548,14 +550,14 @@ int agzo_step(agzo_ctx* ctx, const agzo_layer* L, void* W, const void* X, const 
     TRY(op_basis(ctx, *L, p, X, K, seed, nullptr, flags & AGZO_INIT_FEATURE, B));
     // 2. perturbed evaluations (Alg. 2, parts 2-3)
     if (flags & AGZO_NAIVE_INPLACE) {
-        TRY(op_update(ctx, *L, W, B, seed, -eps, nullptr));
+        TRY(op_update(ctx, *L, p.off_upd, W, B, seed, -eps, nullptr));
         TRY(op_forward(ctx, *L, p, W, X, nullptr, 0.f, seed, nullptr, loss, out_dev + 1));
         if (!one_sided) {
-            TRY(op_update(ctx, *L, W, B, seed, 2.f * eps, nullptr));
+            TRY(op_update(ctx, *L, p.off_upd, W, B, seed, 2.f * eps, nullptr));
             TRY(op_forward(ctx, *L, p, W, X, nullptr, 0.f, seed, nullptr, loss, out_dev + 2));
-            TRY(op_update(ctx, *L, W, B, seed, -eps, nullptr));
+            TRY(op_update(ctx, *L, p.off_upd, W, B, seed, -eps, nullptr));
         } else {
-            TRY(op_update(ctx, *L, W, B, seed, eps, nullptr));
+            TRY(op_update(ctx, *L, p.off_upd, W, B, seed, eps, nullptr));
         }
     } else {
         float* P = wsf(ctx, p.off_T);
@@ -565,7 +567,7 @@ int agzo_step(agzo_ctx* ctx, const agzo_layer* L, void* W, const void* X, const 
     }
     // 3. scalar g and the rank-r update
     HIPCHK(launch_two_point(out_dev, eps, one_sided ? 1 : 0, st));
-    TRY(op_update(ctx, *L, W, B, seed, lr, out_dev + 3));
+    TRY(op_update(ctx, *L, p.off_upd, W, B, seed, lr, out_dev + 3));
     return AGZO_OK;
 }
 

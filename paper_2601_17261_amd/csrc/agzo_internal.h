@@ -16,11 +16,19 @@ typedef uint16_t bf16_t;
 
 __device__ __forceinline__ float bf16_to_f32(bf16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
 
-// round to nearest, ties to even (inputs are finite)
+// round to nearest, ties to even (v_cvt_pk_bf16_f32)
 __device__ __forceinline__ bf16_t f32_to_bf16(float f) {
-    uint32_t u = __float_as_uint(f);
-    u += 0x7FFFu + ((u >> 16) & 1u);
-    return (bf16_t)(u >> 16);
+    const __bf16 b = (__bf16)f;
+    return __builtin_bit_cast(bf16_t, b);
+}
+
+// two values rounded and packed: a in the low half, b in the high half
+__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    const f32x2 v = {a, b};
+    const bf16x2 h = __builtin_convertvector(v, bf16x2);
+    return __builtin_bit_cast(uint32_t, h);
 }
 
 // f = hi + mid + lo with each part a bf16: 24 significant bits in total, so the
@@ -141,8 +149,10 @@ hipError_t launch_qr(const float* S, const float* splits, int nsplit, int rp, fl
                      bf16_t* planes, void* workspace, int* numeric_flag, hipStream_t st);
 
 // update.hip : W -= lr * g * G B^T in place
+// workspace: update_workspace_bytes() bytes of device scratch (may be NULL when that is 0)
+size_t update_workspace_bytes(int dtype, int64_t d_out, int64_t d_in, int r);
 hipError_t launch_update(void* W, int dtype, int64_t ldw, int64_t d_out, int64_t d_in, const float* B, int r,
-                         uint64_t seed, float lr, const double* g_dev, hipStream_t st);
+                         uint64_t seed, float lr, const double* g_dev, void* workspace, hipStream_t st);
 
 // loss.hip
 // cross-entropy from the GEMM's per-chunk softmax statistics: out[ph] = mean over rows with target >= 0 of

@@ -1,8 +1,8 @@
 // In-place rank-r sweep of Alg. 2 (restore / update line, Eq. 10):
 //     W[i][j] -= lr * g * sum_k G[i][k] * B[j][k]
-// W is read and written exactly once (HBM-bound); G is regenerated from the Philox seed per tile
-// and never stored; B (d_in x r fp32) is small and stays in L2.  fp32 arithmetic, one rounding
-// to the storage type on the store.
+// W is read and written exactly once (HBM-bound); G is regenerated from the Philox seed (the d_out x d_in
+// direction Z = G B^T never exists in memory); B (d_in x r fp32) is small and stays in L2.  fp32
+// accumulation, one rounding to the storage type on the store.
 #include "agzo_internal.h"
 
 namespace agzo {
@@ -12,8 +12,8 @@ constexpr int UP_TJ = 256;   // cols (d_in) per tile
 constexpr int UP_TR = 8;     // rows per thread
 
 // KC = number of k handled per register chunk; nchunk chunks cover r (zero padded)
-template <int KC, bool BF16>
-__global__ __launch_bounds__(256) void update_kernel(void* __restrict__ Wv, int64_t ldw, int64_t d_out, int64_t d_in,
+template <int KC>
+__global__ __launch_bounds__(256) void update_kernel(float* __restrict__ Wf, int64_t ldw, int64_t d_out, int64_t d_in,
                                                      const float* __restrict__ B, int r, int nchunk, uint32_t s_lo,
                                                      uint32_t s_hi, float lr, const double* __restrict__ g_dev) {
     extern __shared__ __align__(16) float up_smem[];
@@ -80,44 +80,32 @@ __global__ __launch_bounds__(256) void update_kernel(void* __restrict__ Wv, int6
     for (int s = 0; s < UP_TR; ++s) {
         const int64_t i = i0 + ty + 8 * s;
         if (i >= d_out) continue;
-        if (BF16) {
-            bf16_t* w = reinterpret_cast<bf16_t*>(Wv) + i * ldw + jc;
-            if (full) {
-                uint4 raw = *reinterpret_cast<const uint4*>(w);
-                uint32_t* pw = reinterpret_cast<uint32_t*>(&raw);
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const float w0 = __uint_as_float(pw[q] << 16), w1 = __uint_as_float(pw[q] & 0xFFFF0000u);
-                    const bf16_t o0 = f32_to_bf16(fmaf(coef, acc[s][2 * q], w0));
-                    const bf16_t o1 = f32_to_bf16(fmaf(coef, acc[s][2 * q + 1], w1));
-                    pw[q] = (uint32_t)o0 | ((uint32_t)o1 << 16);
-                }
-                *reinterpret_cast<uint4*>(w) = raw;
-            } else {
-                for (int c = 0; c < 8 && jc + c < d_in; ++c) w[c] = f32_to_bf16(fmaf(coef, acc[s][c], bf16_to_f32(w[c])));
-            }
+        float* w = Wf + i * ldw + jc;
+        if (full && ((reinterpret_cast<uintptr_t>(w) & 15) == 0)) {
+            float4 a = *reinterpret_cast<const float4*>(w), c4 = *reinterpret_cast<const float4*>(w + 4);
+            a.x = fmaf(coef, acc[s][0], a.x); a.y = fmaf(coef, acc[s][1], a.y);
+            a.z = fmaf(coef, acc[s][2], a.z); a.w = fmaf(coef, acc[s][3], a.w);
+            c4.x = fmaf(coef, acc[s][4], c4.x); c4.y = fmaf(coef, acc[s][5], c4.y);
+            c4.z = fmaf(coef, acc[s][6], c4.z); c4.w = fmaf(coef, acc[s][7], c4.w);
+            *reinterpret_cast<float4*>(w) = a;
+            *reinterpret_cast<float4*>(w + 4) = c4;
         } else {
-            float* w = reinterpret_cast<float*>(Wv) + i * ldw + jc;
-            if (full && ((reinterpret_cast<uintptr_t>(w) & 15) == 0)) {
-                float4 a = *reinterpret_cast<const float4*>(w), c4 = *reinterpret_cast<const float4*>(w + 4);
-                a.x = fmaf(coef, acc[s][0], a.x); a.y = fmaf(coef, acc[s][1], a.y);
-                a.z = fmaf(coef, acc[s][2], a.z); a.w = fmaf(coef, acc[s][3], a.w);
-                c4.x = fmaf(coef, acc[s][4], c4.x); c4.y = fmaf(coef, acc[s][5], c4.y);
-                c4.z = fmaf(coef, acc[s][6], c4.z); c4.w = fmaf(coef, acc[s][7], c4.w);
-                *reinterpret_cast<float4*>(w) = a;
-                *reinterpret_cast<float4*>(w + 4) = c4;
-            } else {
-                for (int c = 0; c < 8 && jc + c < d_in; ++c) w[c] = fmaf(coef, acc[s][c], w[c]);
-            }
+            for (int c = 0; c < 8 && jc + c < d_in; ++c) w[c] = fmaf(coef, acc[s][c], w[c]);
         }
     }
 }
 
 // ---------------------------------------------------------------------------
-// r > 8: the outer product G B^T runs on the matrix cores (v_mfma_f32_32x32x16_bf16, K = r padded to 16).
-// Roles: A-operand rows = basis rows (columns j of W, permuted so that a lane ends up with 16 consecutive
-// j), B-operand rows = G rows (rows i of W).  G and B are split hi + lo in bf16 and the products hi*hi,
-// hi*lo, lo*hi are accumulated: relative error 2^-16 of the increment.  A wave owns 32 rows x 256 columns.
+// bf16 storage: the outer product G B^T runs on the matrix cores (v_mfma_f32_32x32x16_bf16,
+// K = r padded to 16).  A small preparation kernel writes both factors once, already split hi + lo in
+// bf16 and already in the register order the matrix instruction wants (coef = -lr g folded into G), so
+// the sweep itself holds no generator and no conversions of the factors: it is a read-add-write of W.
+// Products hi*hi, hi*lo, lo*hi are accumulated: relative error 2^-16 of the increment.
+//
+// Roles: A-operand rows = rows i of W (G), B-operand columns = columns j of W (basis rows), interleaved
+// over eight instructions (column c of instruction m is j = 8 c + m), so that a lane ends up with eight
+// consecutive columns of one row (16 bytes) and a half-wave with 512 contiguous bytes.
+// A wave owns 32 rows x 256 columns; the four waves of a workgroup share the basis fragments in LDS.
 // ---------------------------------------------------------------------------
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
@@ -126,164 +114,204 @@ union FragU {
     bf16x8 v;
 };
 
-__device__ __forceinline__ int upd_perm(int m) { return ((m >> 2) & 1) * 16 + ((m >> 3) & 3) * 4 + (m & 3); }
-
 // eight fp32 values -> hi and lo bf16 fragments
 __device__ __forceinline__ void split_frag(const float (&f)[8], FragU& hi, FragU& lo) {
-    uint32_t h[4] = {0, 0, 0, 0}, l[4] = {0, 0, 0, 0};
+    uint32_t h[4], l[4];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const bf16_t a = f32_to_bf16(f[i]);
-        const bf16_t b = f32_to_bf16(f[i] - bf16_to_f32(a));
-        h[i >> 1] |= ((uint32_t)a) << ((i & 1) * 16);
-        l[i >> 1] |= ((uint32_t)b) << ((i & 1) * 16);
+    for (int i = 0; i < 4; ++i) {
+        h[i] = pack_bf16x2(f[2 * i], f[2 * i + 1]);
+        const float r0 = f[2 * i] - __uint_as_float(h[i] << 16);
+        const float r1 = f[2 * i + 1] - __uint_as_float(h[i] & 0xFFFF0000u);
+        l[i] = pack_bf16x2(r0, r1);
     }
     hi.u = make_uint4(h[0], h[1], h[2], h[3]);
     lo.u = make_uint4(l[0], l[1], l[2], l[3]);
 }
 
-constexpr int UM_ROWS = 32;            // rows of W per workgroup
-constexpr int UM_COLS_PER_WAVE = 256;  // columns per wave (8 blocks of 32)
+constexpr int UM_ROWS = 32;     // rows of W per wave
+constexpr int UM_COLS = 256;    // columns of W per workgroup
 
-template <int NK, bool BF16>   // NK = rp / 16
-__global__ __launch_bounds__(256) void update_mfma_kernel(void* __restrict__ Wv, int64_t ldw, int64_t d_out, int64_t d_in,
-                                                          const float* __restrict__ B, int r, uint32_t s_lo,
-                                                          uint32_t s_hi, float lr, const double* __restrict__ g_dev) {
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int lr_ = lane & 31, lh = lane >> 5;
-    const int64_t i0 = (int64_t)blockIdx.y * UM_ROWS;
-    const int64_t jw = ((int64_t)blockIdx.x * 4 + wave) * UM_COLS_PER_WAVE;
-    if (jw >= d_in) return;
-    const float coef = -lr * (g_dev ? (float)(*g_dev) : 1.0f);
-    const int64_t i = i0 + lr_;
-
-    // G fragments of this lane's row: k = 16*kc + 8*lh .. +7
-    FragU gh[NK], gl[NK];
-#pragma unroll
-    for (int kc = 0; kc < NK; ++kc) {
-        const int k0 = 16 * kc + 8 * lh;
-        float g[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        if (i < d_out) {
-            if (k0 < r) {
-                const float4 z = philox_normal4(s_lo, s_hi, AGZO_TAG_G, (uint32_t)i, (uint32_t)(k0 >> 2));
-                g[0] = z.x; g[1] = z.y; g[2] = z.z; g[3] = z.w;
-            }
+// fragment stores (uint4 units):
+//   Gf [row block ib][kc][plane][lane]        lane = (i % 32) + 32 * lh,      k = 16 kc + 8 lh + 0..7
+//   Bf [col block jb][kc][plane][m][lane]     lane = c + 32 * lh, j = 256 jb + 8 c + m, same k
+__global__ __launch_bounds__(256) void update_prep_kernel(uint4* __restrict__ Gf, uint4* __restrict__ Bf,
+                                                          int64_t n_g, int64_t n_b, int nk, int64_t d_out,
+                                                          int64_t d_in, const float* __restrict__ B, int r,
+                                                          uint32_t s_lo, uint32_t s_hi, float lr,
+                                                          const double* __restrict__ g_dev) {
+    const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    float f[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    FragU hi, lo;
+    if (t < n_g) {
+        const int lane = (int)(t & 63), kc = (int)((t >> 6) % nk);
+        const int64_t ib = (t >> 6) / nk;
+        const int64_t i = ib * UM_ROWS + (lane & 31);
+        const int k0 = 16 * kc + 8 * (lane >> 5);
+        if (i < d_out && k0 < r) {
+            const float coef = -lr * (g_dev ? (float)(*g_dev) : 1.0f);
+            const float4 z0 = philox_normal4(s_lo, s_hi, AGZO_TAG_G, (uint32_t)i, (uint32_t)(k0 >> 2));
+            f[0] = z0.x; f[1] = z0.y; f[2] = z0.z; f[3] = z0.w;
             if (k0 + 4 < r) {
-                const float4 z = philox_normal4(s_lo, s_hi, AGZO_TAG_G, (uint32_t)i, (uint32_t)((k0 >> 2) + 1));
-                g[4] = z.x; g[5] = z.y; g[6] = z.z; g[7] = z.w;
+                const float4 z1 = philox_normal4(s_lo, s_hi, AGZO_TAG_G, (uint32_t)i, (uint32_t)((k0 >> 2) + 1));
+                f[4] = z1.x; f[5] = z1.y; f[6] = z1.z; f[7] = z1.w;
             }
+#pragma unroll
+            for (int q = 0; q < 8; ++q) f[q] = (k0 + q < r) ? coef * f[q] : 0.f;
+        }
+        split_frag(f, hi, lo);
+        uint4* dst = Gf + ((ib * nk + kc) * 2) * 64 + lane;
+        dst[0] = hi.u;
+        dst[64] = lo.u;
+    } else if (t < n_g + n_b) {
+        const int64_t u = t - n_g;
+        const int lane = (int)(u & 63), m = (int)((u >> 6) & 7), kc = (int)((u >> 9) % nk);
+        const int64_t jb = (u >> 9) / nk;
+        const int64_t j = jb * UM_COLS + 8 * (lane & 31) + m;
+        const int k0 = 16 * kc + 8 * (lane >> 5);
+        if (j < d_in) {
 #pragma unroll
             for (int q = 0; q < 8; ++q)
-                if (k0 + q >= r) g[q] = 0.f;
+                if (k0 + q < r) f[q] = B[j * r + k0 + q];
         }
-        split_frag(g, gh[kc], gl[kc]);
+        split_frag(f, hi, lo);
+        uint4* dst = Bf + (((jb * nk + kc) * 2) * 8 + m) * 64 + lane;
+        dst[0] = hi.u;
+        dst[8 * 64] = lo.u;
     }
+}
 
-    for (int jb = 0; jb < UM_COLS_PER_WAVE / 32; ++jb) {
-        const int64_t j0 = jw + jb * 32;
-        if (j0 >= d_in) break;
-        floatx16 z;
+template <int NK>   // NK = rp / 16
+__global__ __launch_bounds__(256, 2) void update_mfma_kernel(bf16_t* __restrict__ W, int64_t ldw, int64_t d_out,
+                                                             int64_t d_in, const uint4* __restrict__ Gf,
+                                                             const uint4* __restrict__ Bf, int row_iters) {
+    extern __shared__ __align__(16) uint4 um_smem[];   // [NK][2][8][64]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int c = lane & 31, lh = lane >> 5;
+    const int64_t jb = blockIdx.x;
+    {
+        const uint4* src = Bf + jb * (NK * 2 * 8 * 64);
 #pragma unroll
-        for (int e = 0; e < 16; ++e) z[e] = 0.f;
-        const int64_t jrow = j0 + upd_perm(lr_);     // basis row this lane feeds as A-operand row lr_
+        for (int e = 0; e < NK * 4; ++e) um_smem[e * 256 + tid] = src[e * 256 + tid];
+    }
+    __syncthreads();
+    const int64_t jc = jb * UM_COLS + 8 * c;     // this lane's eight consecutive columns
+    const bool col_ok = jc < d_in;               // d_in is a multiple of 8: the piece is all in or all out
+
+    for (int it = 0; it < row_iters; ++it) {
+        const int64_t ib = ((int64_t)blockIdx.y * row_iters + it) * 4 + wave;
+        const int64_t i0 = ib * UM_ROWS;
+        if (i0 >= d_out) break;                  // wave-uniform
+        // this lane's rows: i0 + 8 (e / 4) + 4 lh + e % 4
+        uint4 wv[16];
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const int64_t i = i0 + 8 * (e >> 2) + 4 * lh + (e & 3);
+            wv[e] = make_uint4(0, 0, 0, 0);
+            if (col_ok && i < d_out) wv[e] = *reinterpret_cast<const uint4*>(W + i * ldw + jc);
+        }
+        floatx16 z[8];
+#pragma unroll
+        for (int m = 0; m < 8; ++m)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) z[m][e] = 0.f;
 #pragma unroll
         for (int kc = 0; kc < NK; ++kc) {
-            const int k0 = 16 * kc + 8 * lh;
-            float b[8];
+            FragU gh, gl;
+            gh.u = Gf[((ib * NK + kc) * 2) * 64 + lane];
+            gl.u = Gf[((ib * NK + kc) * 2 + 1) * 64 + lane];
 #pragma unroll
-            for (int q = 0; q < 8; ++q) b[q] = (jrow < d_in && k0 + q < r) ? B[jrow * r + k0 + q] : 0.f;
-            FragU bh, bl;
-            split_frag(b, bh, bl);
-            z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bh.v, gh[kc].v, z, 0, 0, 0);
-            z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bh.v, gl[kc].v, z, 0, 0, 0);
-            z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bl.v, gh[kc].v, z, 0, 0, 0);
-        }
-        if (i >= d_out) continue;
-        const int64_t jc = j0 + 16 * lh;             // this lane's 16 consecutive columns of row i
-        if (BF16) {
-            bf16_t* w = reinterpret_cast<bf16_t*>(Wv) + i * ldw + jc;
-#pragma unroll
-            for (int hq = 0; hq < 2; ++hq) {
-                if (jc + 8 * hq >= d_in) continue;   // d_in is a multiple of 8: an 8-column piece is all in or all out
-                uint4 raw = *reinterpret_cast<const uint4*>(w + 8 * hq);
-                uint32_t* pw = reinterpret_cast<uint32_t*>(&raw);
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const float w0 = __uint_as_float(pw[q] << 16), w1 = __uint_as_float(pw[q] & 0xFFFF0000u);
-                    const bf16_t o0 = f32_to_bf16(fmaf(coef, z[8 * hq + 2 * q], w0));
-                    const bf16_t o1 = f32_to_bf16(fmaf(coef, z[8 * hq + 2 * q + 1], w1));
-                    pw[q] = (uint32_t)o0 | ((uint32_t)o1 << 16);
-                }
-                *reinterpret_cast<uint4*>(w + 8 * hq) = raw;
+            for (int m = 0; m < 8; ++m) {
+                FragU bh, bl;
+                bh.u = um_smem[((kc * 2) * 8 + m) * 64 + lane];
+                bl.u = um_smem[((kc * 2 + 1) * 8 + m) * 64 + lane];
+                z[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gh.v, bh.v, z[m], 0, 0, 0);
+                z[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gh.v, bl.v, z[m], 0, 0, 0);
+                z[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gl.v, bh.v, z[m], 0, 0, 0);
             }
-        } else {
-            float* w = reinterpret_cast<float*>(Wv) + i * ldw + jc;
+        }
 #pragma unroll
-            for (int e = 0; e < 16; ++e)
-                if (jc + e < d_in) w[e] = fmaf(coef, z[e], w[e]);
+        for (int e = 0; e < 16; ++e) {
+            const int64_t i = i0 + 8 * (e >> 2) + 4 * lh + (e & 3);
+            if (!(col_ok && i < d_out)) continue;
+            uint32_t* pw = reinterpret_cast<uint32_t*>(&wv[e]);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float w0 = __uint_as_float(pw[q] << 16), w1 = __uint_as_float(pw[q] & 0xFFFF0000u);
+                pw[q] = pack_bf16x2(w0 + z[2 * q][e], w1 + z[2 * q + 1][e]);
+            }
+            *reinterpret_cast<uint4*>(W + i * ldw + jc) = wv[e];
         }
     }
 }
 
+size_t update_workspace_bytes(int dtype, int64_t d_out, int64_t d_in, int r) {
+    if (dtype != AGZO_BF16) return 0;
+    const int64_t nk = (r + 15) / 16;
+    const int64_t nib = (d_out + UM_ROWS - 1) / UM_ROWS, njb = (d_in + UM_COLS - 1) / UM_COLS;
+    return (size_t)(nib * nk * 2 * 64 + njb * nk * 2 * 8 * 64) * sizeof(uint4);
+}
+
 template <int NK>
-static hipError_t launch_mfma(void* W, int dtype, int64_t ldw, int64_t d_out, int64_t d_in, const float* B, int r,
-                              uint64_t seed, float lr, const double* g_dev, hipStream_t st) {
-    dim3 grid((unsigned)((d_in + 4 * UM_COLS_PER_WAVE - 1) / (4 * UM_COLS_PER_WAVE)), (unsigned)((d_out + UM_ROWS - 1) / UM_ROWS));
-    if (dtype == AGZO_BF16)
-        hipLaunchKernelGGL((update_mfma_kernel<NK, true>), grid, dim3(256), 0, st, W, ldw, d_out, d_in, B, r, (uint32_t)seed,
-                           (uint32_t)(seed >> 32), lr, g_dev);
-    else
-        hipLaunchKernelGGL((update_mfma_kernel<NK, false>), grid, dim3(256), 0, st, W, ldw, d_out, d_in, B, r,
-                           (uint32_t)seed, (uint32_t)(seed >> 32), lr, g_dev);
+static hipError_t launch_mfma(bf16_t* W, int64_t ldw, int64_t d_out, int64_t d_in, const uint4* Gf, const uint4* Bf,
+                              hipStream_t st) {
+    const int64_t njb = (d_in + UM_COLS - 1) / UM_COLS;
+    const int64_t ngroups = (d_out + 4 * UM_ROWS - 1) / (4 * UM_ROWS);
+    // more rows per workgroup (fewer reloads of the basis fragments) once the grid still covers the chip a few times
+    int row_iters = 1;
+    while (row_iters < 4 && njb * (ngroups / (2 * row_iters)) >= 2048) row_iters *= 2;
+    dim3 grid((unsigned)njb, (unsigned)((ngroups + row_iters - 1) / row_iters));
+    const size_t smem = (size_t)NK * 2 * 8 * 64 * sizeof(uint4);
+    hipLaunchKernelGGL((update_mfma_kernel<NK>), grid, dim3(256), smem, st, W, ldw, d_out, d_in, Gf, Bf, row_iters);
     return hipGetLastError();
 }
 
 template <int KC>
-static hipError_t launch_kc(void* W, int dtype, int64_t ldw, int64_t d_out, int64_t d_in, const float* B, int r,
-                            int nchunk, uint64_t seed, float lr, const double* g_dev, hipStream_t st) {
+static hipError_t launch_kc(float* W, int64_t ldw, int64_t d_out, int64_t d_in, const float* B, int r, int nchunk,
+                            uint64_t seed, float lr, const double* g_dev, hipStream_t st) {
     dim3 grid((unsigned)((d_in + UP_TJ - 1) / UP_TJ), (unsigned)((d_out + UP_TI - 1) / UP_TI));
     const int rp = KC * nchunk;
     const size_t smem = (size_t)(UP_TI + UP_TJ) * rp * sizeof(float);
-    if (dtype == AGZO_BF16) {
-        static bool set = false;
-        if (!set) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(update_kernel<KC, true>),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize,
-                                               (UP_TI + UP_TJ) * kMaxRank * (int)sizeof(float));
-            if (e != hipSuccess) return e;
-            set = true;
-        }
-        hipLaunchKernelGGL((update_kernel<KC, true>), grid, dim3(256), smem, st, W, ldw, d_out, d_in, B, r, nchunk,
-                           (uint32_t)seed, (uint32_t)(seed >> 32), lr, g_dev);
-    } else {
-        static bool set = false;
-        if (!set) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(update_kernel<KC, false>),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize,
-                                               (UP_TI + UP_TJ) * kMaxRank * (int)sizeof(float));
-            if (e != hipSuccess) return e;
-            set = true;
-        }
-        hipLaunchKernelGGL((update_kernel<KC, false>), grid, dim3(256), smem, st, W, ldw, d_out, d_in, B, r, nchunk,
-                           (uint32_t)seed, (uint32_t)(seed >> 32), lr, g_dev);
+    static bool set = false;
+    if (!set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(update_kernel<KC>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           (UP_TI + UP_TJ) * kMaxRank * (int)sizeof(float));
+        if (e != hipSuccess) return e;
+        set = true;
     }
+    hipLaunchKernelGGL((update_kernel<KC>), grid, dim3(256), smem, st, W, ldw, d_out, d_in, B, r, nchunk, (uint32_t)seed,
+                       (uint32_t)(seed >> 32), lr, g_dev);
     return hipGetLastError();
 }
 
 hipError_t launch_update(void* W, int dtype, int64_t ldw, int64_t d_out, int64_t d_in, const float* B, int r,
-                         uint64_t seed, float lr, const double* g_dev, hipStream_t st) {
+                         uint64_t seed, float lr, const double* g_dev, void* workspace, hipStream_t st) {
     if (d_out == 0 || d_in == 0) return hipSuccess;
-    if (r <= 1) return launch_kc<1>(W, dtype, ldw, d_out, d_in, B, r, 1, seed, lr, g_dev, st);
-    if (r <= 2) return launch_kc<2>(W, dtype, ldw, d_out, d_in, B, r, 1, seed, lr, g_dev, st);
-    if (r <= 4) return launch_kc<4>(W, dtype, ldw, d_out, d_in, B, r, 1, seed, lr, g_dev, st);
-    if (r <= 8) return launch_kc<8>(W, dtype, ldw, d_out, d_in, B, r, 1, seed, lr, g_dev, st);
     // fp32 storage keeps exact fp32 products (VALU); bf16 storage takes the matrix-core outer product
-    if (dtype != AGZO_BF16) return launch_kc<16>(W, dtype, ldw, d_out, d_in, B, r, (r + 15) / 16, seed, lr, g_dev, st);
-    switch ((r + 15) / 16) {
-        case 1: return launch_mfma<1>(W, dtype, ldw, d_out, d_in, B, r, seed, lr, g_dev, st);
-        case 2: return launch_mfma<2>(W, dtype, ldw, d_out, d_in, B, r, seed, lr, g_dev, st);
-        case 3: return launch_mfma<3>(W, dtype, ldw, d_out, d_in, B, r, seed, lr, g_dev, st);
-        default: return launch_mfma<4>(W, dtype, ldw, d_out, d_in, B, r, seed, lr, g_dev, st);
+    if (dtype != AGZO_BF16) {
+        float* Wf = static_cast<float*>(W);
+        if (r <= 1) return launch_kc<1>(Wf, ldw, d_out, d_in, B, r, 1, seed, lr, g_dev, st);
+        if (r <= 2) return launch_kc<2>(Wf, ldw, d_out, d_in, B, r, 1, seed, lr, g_dev, st);
+        if (r <= 4) return launch_kc<4>(Wf, ldw, d_out, d_in, B, r, 1, seed, lr, g_dev, st);
+        if (r <= 8) return launch_kc<8>(Wf, ldw, d_out, d_in, B, r, 1, seed, lr, g_dev, st);
+        return launch_kc<16>(Wf, ldw, d_out, d_in, B, r, (r + 15) / 16, seed, lr, g_dev, st);
+    }
+    if (!workspace) return hipErrorInvalidValue;
+    const int nk = (r + 15) / 16;
+    const int64_t nib = (d_out + UM_ROWS - 1) / UM_ROWS, njb = (d_in + UM_COLS - 1) / UM_COLS;
+    const int64_t n_g = nib * nk * 64, n_b = njb * nk * 8 * 64;
+    uint4* Gf = static_cast<uint4*>(workspace);
+    uint4* Bf = Gf + nib * nk * 2 * 64;
+    hipLaunchKernelGGL(update_prep_kernel, dim3((unsigned)((n_g + n_b + 255) / 256)), dim3(256), 0, st, Gf, Bf, n_g, n_b,
+                       nk, d_out, d_in, B, r, (uint32_t)seed, (uint32_t)(seed >> 32), lr, g_dev);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    bf16_t* Wb = static_cast<bf16_t*>(W);
+    switch (nk) {
+        case 1: return launch_mfma<1>(Wb, ldw, d_out, d_in, Gf, Bf, st);
+        case 2: return launch_mfma<2>(Wb, ldw, d_out, d_in, Gf, Bf, st);
+        case 3: return launch_mfma<3>(Wb, ldw, d_out, d_in, Gf, Bf, st);
+        default: return launch_mfma<4>(Wb, ldw, d_out, d_in, Gf, Bf, st);
     }
 }
 
