@@ -16,6 +16,7 @@ namespace agzo {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+template <int V> struct IC { static constexpr int value = V; };
 
 constexpr int BT = 256;                        // tile edge (tokens and outputs)
 constexpr int BK = 64;
@@ -61,7 +62,8 @@ __global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
     auto Xs = [&](int buf) -> char* { return smem + buf * (2 * TILE_BYTES); };
     auto Ws = [&](int buf) -> char* { return smem + buf * (2 * TILE_BYTES) + TILE_BYTES; };
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform by construction: keeps LDS bases scalar
     const int wa = wave / WB, wb = wave % WB;
     const int lr = lane & 31, lh = lane >> 5;
 
@@ -93,23 +95,25 @@ __global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
 
     // ---- operand staging ------------------------------------------------------------------------
     // Whole 64-wide K slices travel global -> LDS without passing through registers
-    // (global_load_lds_dwordx4: lane l of a wave writes its 16 bytes at LDS base + 16*l, so one
+    // (buffer_load_dwordx4 ... lds: lane l of a wave writes its 16 bytes at LDS base + 16*l, so one
     // instruction fills 8 consecutive tile rows).  The bank swizzle is applied on the global side by
     // choosing which 16-byte chunk of its row a lane fetches.  Slices that are not plain copies of
     // memory (the ragged end of d_in, the rank-r extension) are written by the threads themselves.
-    constexpr int GP = 32 / (WA * WB);          // 8-row groups per wave per operand
-    static_assert(GP == 4 || GP == 8, "loads are spread over the four MFMA sub-steps");
-    uint32_t xo[GP], wo[GP];                    // element offsets from the tile's first row
+    static_assert(WA == 2 && WB == 2 && BA == 4 && BB == 4, "the issue schedule below is written for 2 x 2 waves");
+    constexpr int GP = 8;                       // 8-row groups per wave per operand
     const bf16_t* xbase = p.X + m0 * p.ldx;
     const bf16_t* wbase = p.W + n0 * p.ldw;
+    const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(xbase), 0, -1, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(wbase), 0, -1, 0x00020000);
+    int xo[GP], wo[GP];                         // byte offsets from the tile's first row
 #pragma unroll
     for (int t = 0; t < GP; ++t) {
-        const int row = 8 * (wave + WA * WB * t) + (lane >> 3);
+        const int row = 8 * (wave + 4 * t) + (lane >> 3);
         const int c = (lane & 7) ^ ((row >> 1) & 7);
         const int64_t gm = min((int64_t)row, p.M - 1 - m0);
         const int64_t gn = min((int64_t)((row & ~31) + w_perm(row & 31)), p.N - 1 - n0);
-        xo[t] = (uint32_t)(gm * p.ldx + c * 8);
-        wo[t] = (uint32_t)(gn * p.ldw + c * 8);
+        xo[t] = (int)((gm * p.ldx + c * 8) * 2);
+        wo[t] = (int)((gn * p.ldw + c * 8) * 2);
     }
     const int nfull = (int)(p.K / BK);
     const int ntail = (p.K % BK) ? 1 : 0;
@@ -171,18 +175,13 @@ __global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
 #pragma unroll
                 for (int i = 0; i < 8; ++i) gv[i] = (k0 + i < p.r) ? t[i] : 0.f;
             }
-            uint32_t ph[4] = {0, 0, 0, 0}, pl[4] = {0, 0, 0, 0}, gh[4] = {0, 0, 0, 0}, gl[4] = {0, 0, 0, 0};
+            uint32_t ph[4], pl[4], gh[4], gl[4];
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const bf16_t a_hi = f32_to_bf16(pv[i]);
-                const bf16_t a_lo = f32_to_bf16(pv[i] - bf16_to_f32(a_hi));
-                const bf16_t b_hi = f32_to_bf16(gv[i]);
-                const bf16_t b_lo = f32_to_bf16(gv[i] - bf16_to_f32(b_hi));
-                const int sh = (i & 1) * 16;
-                ph[i >> 1] |= ((uint32_t)a_hi) << sh;
-                pl[i >> 1] |= ((uint32_t)a_lo) << sh;
-                gh[i >> 1] |= ((uint32_t)b_hi) << sh;
-                gl[i >> 1] |= ((uint32_t)b_lo) << sh;
+            for (int i = 0; i < 4; ++i) {
+                ph[i] = pack_bf16x2(pv[2 * i], pv[2 * i + 1]);
+                pl[i] = pack_bf16x2(pv[2 * i] - __uint_as_float(ph[i] << 16), pv[2 * i + 1] - __uint_as_float(ph[i] & 0xFFFF0000u));
+                gh[i] = pack_bf16x2(gv[2 * i], gv[2 * i + 1]);
+                gl[i] = pack_bf16x2(gv[2 * i] - __uint_as_float(gh[i] << 16), gv[2 * i + 1] - __uint_as_float(gh[i] & 0xFFFF0000u));
             }
 #pragma unroll
             for (int seg = 0; seg < 3; ++seg) {
@@ -205,99 +204,157 @@ __global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
             else fill_ext(buf, e, p.eps_signed);
         }
     };
-    typedef const __attribute__((address_space(1))) void* gptr_t;
     typedef __attribute__((address_space(3))) void* lptr_t;
 
-    // first slice
-    if (nfull > 0) {
-#pragma unroll
-        for (int t = 0; t < GP; ++t) {
-            const int g = wave + WA * WB * t;
-            __builtin_amdgcn_global_load_lds((gptr_t)(xbase + xo[t]), (lptr_t)(Xs(0) + g * 1024), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds((gptr_t)(wbase + wo[t]), (lptr_t)(Ws(0) + g * 1024), 16, 0, 0);
-        }
-    } else {
-        fill_manual(0, 0);
-    }
-    __builtin_amdgcn_s_waitcnt(0x0F70);         // vmcnt(0): the LDS-direct loads have landed
-    __syncthreads();
-
-    // main loop: slice `it` is multiplied from buffer it&1 while slice it+1 is brought into the other;
-    // the direct loads of the next slice are issued a few at a time between the MFMA sub-steps so
-    // that their LDS writes do not arrive in one burst.
-    // Target prefetch: during four of the slices before the first loss evaluation every thread touches
-    // one 128-byte line of the tile's target values with a 4-byte LDS-direct load into a scratch slot,
-    // so that the epilogue's reads find the tile in L2.  These loads are issued after the slice's
-    // operand loads and are the only ones allowed to stay in flight across the slice's closing wait.
-    const int first_epi = SHARED ? nd - 1 : total - 1;
-    const bool pf_on = !CE && (p.loss_kind == AGZO_LOSS_MSE) && first_epi >= 5;
-    const int pf_first = first_epi - 5;
     char* sink = smem + 4 * TILE_BYTES + wave * 256;
     double* red = reinterpret_cast<double*>(smem + 4 * TILE_BYTES + 256 * WA * WB);
     const int t_shift = (p.target_dtype == AGZO_BF16) ? 1 : 2;       // log2(bytes per target element)
-    const int lines_per_row = (BT << t_shift) >> 7;                    // 128-byte lines per tile row
     const bool y_f32 = (p.Y != nullptr) && p.y_dtype != AGZO_BF16;
     const bool y_bf16 = (p.Y != nullptr) && p.y_dtype == AGZO_BF16;
     const bool l_f32 = !CE && p.loss_kind == AGZO_LOSS_MSE && p.target_dtype != AGZO_BF16;
     const bool l_bf16 = !CE && p.loss_kind == AGZO_LOSS_MSE && p.target_dtype == AGZO_BF16;
-    auto run_slices = [&](int it_begin, int it_end) __attribute__((always_inline)) {
-    for (int it = it_begin; it < it_end; ++it) {
-        const int cur = it & 1;
-        const bool dma_next = it + 1 < nfull;
-        if (!dma_next && it + 1 < total) fill_manual(it + 1, cur ^ 1);
-        const int pj = it - pf_first;                                  // 0..3 while prefetching
-        const bool pf_now = pf_on && pj >= 0 && pj < 4 && (pj * NT < BT * lines_per_row);
-        const char* xs = Xs(cur);
-        const char* ws = Ws(cur);
-        char* nxs = Xs(cur ^ 1);
-        char* nws = Ws(cur ^ 1);
-        const bf16_t* xk = xbase + (int64_t)(it + 1) * BK;
-        const bf16_t* wk = wbase + (int64_t)(it + 1) * BK;
-        bf16x8 a[2][BA], b[2][BB];
+
+    // ---- multiply ---------------------------------------------------------------------------------
+    // per-lane LDS byte offsets of this wave's fragments for the four 16-wide sub-steps of a slice; block i of an
+    // operand is 32 rows = 4096 bytes further (the swizzle term (row >> 1) & 7 is the same for all blocks)
+    int aoff[4], boff[4];
 #pragma unroll
-        for (int i = 0; i < BA; ++i)
-            a[0][i] = *reinterpret_cast<const bf16x8*>(ws + lds_off(wa * (BT / WA) + i * 32 + lr, lh));
-#pragma unroll
-        for (int j = 0; j < BB; ++j)
-            b[0][j] = *reinterpret_cast<const bf16x8*>(xs + lds_off(wb * (BT / WB) + j * 32 + lr, lh));
-#pragma unroll
-        for (int kk = 0; kk < BK / 16; ++kk) {
-            const int s = kk & 1;
-            if (kk + 1 < BK / 16) {
-#pragma unroll
-                for (int i = 0; i < BA; ++i)
-                    a[s ^ 1][i] = *reinterpret_cast<const bf16x8*>(ws + lds_off(wa * (BT / WA) + i * 32 + lr, (kk + 1) * 2 + lh));
-#pragma unroll
-                for (int j = 0; j < BB; ++j)
-                    b[s ^ 1][j] = *reinterpret_cast<const bf16x8*>(xs + lds_off(wb * (BT / WB) + j * 32 + lr, (kk + 1) * 2 + lh));
-            }
-            if (dma_next) {
-#pragma unroll
-                for (int t = 0; t < GP; ++t) {
-                    if ((t * 4) / GP != kk) continue;
-                    const int g = wave + WA * WB * t;
-                    __builtin_amdgcn_global_load_lds((gptr_t)(xk + xo[t]), (lptr_t)(nxs + g * 1024), 16, 0, 0);
-                    __builtin_amdgcn_global_load_lds((gptr_t)(wk + wo[t]), (lptr_t)(nws + g * 1024), 16, 0, 0);
-                }
-            }
-#pragma unroll
-            for (int i = 0; i < BA; ++i)
-#pragma unroll
-                for (int j = 0; j < BB; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[s][i], b[s][j], acc[i][j], 0, 0, 0);
-        }
-        if (pf_now) {
-            const int line = pj * NT + tid;
-            const int64_t prow = min((int64_t)(line / lines_per_row), p.M - 1 - m0);
-            const int64_t pcol = min((int64_t)((line % lines_per_row) << (7 - t_shift)), p.N - 1 - n0);
-            const char* tp = reinterpret_cast<const char*>(p.target) + (((m0 + prow) * p.ldt + n0 + pcol) << t_shift);
-            __builtin_amdgcn_global_load_lds((gptr_t)tp, (lptr_t)sink, 4, 0, 0);
-            __builtin_amdgcn_s_waitcnt(0x0F71);     // vmcnt(1): everything but the prefetch just issued
-        } else {
-            __builtin_amdgcn_s_waitcnt(0x0F70);
-        }
-        __syncthreads();
+    for (int kk = 0; kk < 4; ++kk) {
+        aoff[kk] = TILE_BYTES + lds_off(wa * 128 + lr, kk * 2 + lh);
+        boff[kk] = lds_off(wb * 128 + lr, kk * 2 + lh);
     }
+    bf16x8 a[2][BA], b[2][BB];
+    auto frag1 = [&](int buf, int kk, int s, int q) __attribute__((always_inline)) {
+        const char* base = smem + buf * (2 * TILE_BYTES);
+        if (q < 4) a[s][q] = *reinterpret_cast<const bf16x8*>(base + aoff[kk] + q * 4096);
+        else b[s][q - 4] = *reinterpret_cast<const bf16x8*>(base + boff[kk] + (q - 4) * 4096);
+    };
+    auto mfma1 = [&](int s, int idx) __attribute__((always_inline)) {
+        const int i = idx >> 2, j = idx & 3;
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[s][i], b[s][j], acc[i][j], 0, 0, 0);
+    };
+    // direct load q (0..15) of slice kt into buffer buf: even q = X row group q/2, odd q = W row group q/2
+    auto dma1 = [&](int kt, int buf, int q) __attribute__((always_inline)) {
+        const int t = q >> 1;
+        char* dst = smem + buf * (2 * TILE_BYTES) + wave * 1024 + t * 4096 + ((q & 1) ? TILE_BYTES : 0);
+        if (q & 1) __builtin_amdgcn_raw_ptr_buffer_load_lds(rw, (lptr_t)dst, 16, wo[t], kt * (BK * 2), 0, 0);
+        else __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (lptr_t)dst, 16, xo[t], kt * (BK * 2), 0, 0);
+    };
+    // Target prefetch: while the last PF_SLICES plain slices are multiplied every thread touches PF_PER lines of the
+    // tile's target values per slice with 4-byte LDS-direct loads into a scratch slot, so that the epilogue's reads
+    // find the tile in L2.  These loads are issued after the slice's operand loads and may stay in flight across the
+    // slice's closing wait.
+    constexpr int PF_SLICES = 4, PF_PER = 2;
+    const int lines_per_row = (BT << t_shift) >> 7;                    // 128-byte lines per tile row
+    auto touch = [&](int pj, int u) __attribute__((always_inline)) {
+        const int line = (pj * PF_PER + u) * NT + tid;
+        const int64_t prow = min((int64_t)(line / lines_per_row), p.M - 1 - m0);
+        const int64_t pcol = min((int64_t)((line % lines_per_row) << (7 - t_shift)), p.N - 1 - n0);
+        const char* tp = reinterpret_cast<const char*>(p.target) + (((m0 + prow) * p.ldt + n0 + pcol) << t_shift);
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)tp, (lptr_t)sink, 4, 0, 0);
+    };
+    // One block = the 16 MFMAs of sub-step S_CUR in a fixed issue order (a scheduling barrier after every group keeps
+    // the compiler from regrouping): even slots carry one fragment read each (for the next block), odd slots carry
+    // the direct loads D0..D1-1 of slice lkt, spread evenly, or the target touches of this slice.
+    auto block = [&](auto S_CUR, int rbuf, auto RKK, auto RS, int lkt, int lbuf, auto D0, auto D1, auto NTOUCH, int pj)
+                     __attribute__((always_inline)) {
+        constexpr int s_cur = decltype(S_CUR)::value, rkk = decltype(RKK)::value, rs = decltype(RS)::value;
+        constexpr int d0 = decltype(D0)::value, d1 = decltype(D1)::value, n = d1 - d0, ntouch = decltype(NTOUCH)::value;
+#pragma unroll
+        for (int q = 0; q < 16; ++q) {
+            mfma1(s_cur, q);
+            const int o = q >> 1;
+            if (!(q & 1)) frag1(rbuf, rkk, rs, o);
+            else if (((o + 1) * n) / 8 > (o * n) / 8) dma1(lkt, lbuf, d0 + (o * n) / 8);
+            else if (ntouch > 0 && o < ntouch) touch(pj, o);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    // the 16 direct loads of a slice ride on four consecutive blocks: the last block of the slice before the previous
+    // one's (N3), then the first three blocks of the previous slice (N0, N1, none in the block before the wait)
+    constexpr int N3 = 6, N0 = 6, N1 = 4;
+    static_assert(N3 + N0 + N1 == 16, "loads per slice");
+    // plain slices kt0 .. kt1-1 of the steady state; on entry fragment set 0 holds sub-step 0 of slice kt0 and the
+    // first N3 loads of slice kt0+1 are in flight; the same holds for kt1 on exit
+    auto steady = [&](int kt0, int kt1, auto PF, int pj0) __attribute__((always_inline)) {
+        constexpr int pf = decltype(PF)::value;
+        for (int kt = kt0; kt < kt1; ++kt) {
+            const int cur = kt & 1;
+            block(IC<0>{}, cur, IC<1>{}, IC<1>{}, kt + 1, cur ^ 1, IC<N3>{}, IC<N3 + N0>{}, IC<0>{}, 0);
+            block(IC<1>{}, cur, IC<2>{}, IC<0>{}, kt + 1, cur ^ 1, IC<N3 + N0>{}, IC<16>{}, IC<0>{}, 0);
+            block(IC<0>{}, cur, IC<3>{}, IC<1>{}, 0, 0, IC<0>{}, IC<0>{}, IC<pf ? PF_PER : 0>{}, pj0 + (kt - kt0));
+            // every operand load has landed (the touches just issued may stay in flight); all waves are done reading
+            // the buffer that the next loads overwrite
+            if (pf) __builtin_amdgcn_s_waitcnt(0x0072);      // vmcnt(PF_PER) lgkmcnt(0)
+            else __builtin_amdgcn_s_waitcnt(0x0070);         // vmcnt(0) lgkmcnt(0)
+            __builtin_amdgcn_s_barrier();
+            __builtin_amdgcn_sched_barrier(0);
+            // past the last plain slice the loads re-fetch it into the buffer nobody reads any more
+            block(IC<1>{}, cur ^ 1, IC<0>{}, IC<0>{}, min(kt + 2, nfull - 1), cur, IC<0>{}, IC<N3>{}, IC<0>{}, 0);
+        }
+    };
+    // a slice whose operands are complete in buffer `buf`, fragment set 0 not yet read
+    auto multiply_plain = [&](int buf) __attribute__((always_inline)) {
+#pragma unroll
+        for (int q = 0; q < 8; ++q) frag1(buf, 0, 0, q);
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            if (kk + 1 < 4) {
+#pragma unroll
+                for (int q = 0; q < 8; ++q) frag1(buf, kk + 1, (kk + 1) & 1, q);
+            }
+#pragma unroll
+            for (int q = 0; q < 16; ++q) mfma1(kk & 1, q);
+        }
+    };
+    static_assert(PF_PER == 2, "the closing wait of a prefetching slice is written for two touches");
+    const bool pf_on = !CE && (p.loss_kind == AGZO_LOSS_MSE) && nd == nfull && nfull >= PF_SLICES + 2 &&
+                       (PF_SLICES * PF_PER * NT >= BT * lines_per_row);
+    // slices [it_begin, it_end): the plain ones (all inside the first call) run the pipeline above; the others are
+    // filled by the threads and multiplied one at a time
+    auto run_slices = [&](int it_begin, int it_end) __attribute__((always_inline)) {
+        int it = it_begin;
+        if (it == 0 && nfull > 0) {
+#pragma unroll
+            for (int q = 0; q < 16; ++q) dma1(0, 0, q);
+            if (nfull > 1) {
+#pragma unroll
+                for (int q = 0; q < N3; ++q) dma1(1, 1, q);
+                __builtin_amdgcn_s_waitcnt(0x0F76);          // vmcnt(N3): slice 0 has landed
+            } else {
+                __builtin_amdgcn_s_waitcnt(0x0F70);
+            }
+            __syncthreads();
+            if (nfull > 1) {
+#pragma unroll
+                for (int q = 0; q < 8; ++q) frag1(0, 0, 0, q);
+                const int split = pf_on ? nfull - 1 - PF_SLICES : nfull - 1;
+                steady(0, split, IC<0>{}, 0);
+                if (pf_on) steady(split, nfull - 1, IC<1>{}, 0);
+                __builtin_amdgcn_s_waitcnt(0x0F70);          // the re-fetches and touches
+                // last plain slice: sub-step 0 is already in fragment set 0
+                const int cur = (nfull - 1) & 1;
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk) {
+                    if (kk + 1 < 4) {
+#pragma unroll
+                        for (int q = 0; q < 8; ++q) frag1(cur, kk + 1, (kk + 1) & 1, q);
+                    }
+#pragma unroll
+                    for (int q = 0; q < 16; ++q) mfma1(kk & 1, q);
+                }
+            } else {
+                multiply_plain(0);
+            }
+            __syncthreads();
+            it = nfull;
+        }
+        for (; it < it_end; ++it) {
+            fill_manual(it, 0);
+            __syncthreads();
+            multiply_plain(0);
+            __syncthreads();
+        }
     };
     // ---- evaluation point: the accumulators hold Y0 (shared mode, after the d_in slices), or Y with
     // the rank-r term of the current sign.  Lane = one token, 16 consecutive outputs per block.
@@ -488,8 +545,8 @@ hipError_t launch_gemm_bf16(const GemmBf16Args& a, hipStream_t st) {
     p.ce_ms = reinterpret_cast<float2*>(a.loss.ce_ms);
     p.ce_tl = a.loss.ce_tl;
     const bool ce = (p.loss_kind == AGZO_LOSS_CE);
-    if (p.shared) return ce ? launch_variant<2, 4, true, true>(p, st) : launch_variant<2, 4, true, false>(p, st);
-    return ce ? launch_variant<2, 4, false, true>(p, st) : launch_variant<2, 4, false, false>(p, st);
+    if (p.shared) return ce ? launch_variant<2, 2, true, true>(p, st) : launch_variant<2, 2, true, false>(p, st);
+    return ce ? launch_variant<2, 2, false, true>(p, st) : launch_variant<2, 2, false, false>(p, st);
 }
 
 }  // namespace agzo
