@@ -11,6 +11,7 @@
 // d_in slices: one operand is eps * P split in bf16 hi/lo, the other is G regenerated from the
 // Philox seed and split likewise, so both signs share bit-identical X W^T accumulators.
 #include "agzo_internal.h"
+#include <stdlib.h>
 
 namespace agzo {
 
@@ -46,6 +47,8 @@ struct GemmParams {
     float eps_signed; uint32_t s_lo, s_hi;
     int loss_kind; int target_dtype; const void* target; int64_t ldt; double* partials;
     int tiles_m, tiles_n;
+    int dbg;
+    int group_m;                // token tiles walked per output tile inside an XCD's run
     int vec_ok;                 // 16-byte epilogue accesses are legal
     int shared;                 // one pass evaluates f0, f+ and f- (three loss partials per tile)
     // cross-entropy: per (128-column chunk, token) running max and sum of exponentials, and the target's logit
@@ -53,8 +56,13 @@ struct GemmParams {
 };
 
 // WA x WB waves: WA splits the 256 outputs, WB splits the 256 tokens
-template <int WA, int WB, bool SHARED, bool CE>
+// EPI selects the epilogue compiled into the kernel: 0 = general (stores, squared error, any bounds), 1 = cross-entropy
+// statistics, 2 / 3 = squared error only against an fp32 / bf16 target, M and N multiples of the tile, 16-byte accesses
+template <int WA, int WB, bool SHARED, int EPI>
 __global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
+    constexpr bool CE = (EPI == 1);
+    constexpr bool FAST = (EPI >= 2);
+    constexpr bool T_F32 = (EPI == 2);
     constexpr int NT = 64 * WA * WB;
     constexpr int BA = BT / WA / 32;           // 32-row blocks of W per wave
     constexpr int BB = BT / WB / 32;           // 32-row blocks of X per wave
@@ -70,19 +78,21 @@ __global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
     // workgroup -> tile.  Ids are dealt round-robin over the 8 XCDs; give each XCD a contiguous
     // run of tiles, walked in groups of 8 token-tiles per output-tile so that its L2 keeps a W tile
     // and a band of X tiles.
-    int64_t wg = blockIdx.x;
-    const int64_t nwg = (int64_t)p.tiles_m * p.tiles_n;
+    int wg = (int)blockIdx.x;
+    const int nwg = p.tiles_m * p.tiles_n;
     {
-        const int64_t per = nwg / 8;
+        const int per = nwg / 8;
         if (wg < per * 8) wg = (wg % 8) * per + wg / 8;
     }
-    constexpr int GROUP_M = 8;
-    const int64_t group = wg / (GROUP_M * p.tiles_n);
-    const int64_t first_m = group * GROUP_M;
-    const int gsz = (int)min((int64_t)GROUP_M, p.tiles_m - first_m);
-    const int64_t in_group = wg - group * GROUP_M * p.tiles_n;
-    const int64_t tm = first_m + in_group % gsz;
-    const int64_t tn = in_group / gsz;
+    const int GROUP_M = p.group_m;
+    const int group = wg / (GROUP_M * p.tiles_n);
+    const int first_m = group * GROUP_M;
+    const int gsz = min(GROUP_M, p.tiles_m - first_m);
+    const int in_group = wg - group * GROUP_M * p.tiles_n;
+    // the divisions run on the vector unit; pin the (uniform) results to scalar registers so that everything derived
+    // from the tile origin, the buffer descriptors above all, stays scalar
+    const int64_t tm = __builtin_amdgcn_readfirstlane(first_m + in_group % gsz);
+    const int64_t tn = __builtin_amdgcn_readfirstlane(in_group / gsz);
     const int64_t m0 = tm * BT, n0 = tn * BT;
 
     floatx16 acc[BA][BB];
@@ -214,6 +224,36 @@ __global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
     const bool l_f32 = !CE && p.loss_kind == AGZO_LOSS_MSE && p.target_dtype != AGZO_BF16;
     const bool l_bf16 = !CE && p.loss_kind == AGZO_LOSS_MSE && p.target_dtype == AGZO_BF16;
 
+    // Target staging for the squared-error loss: the 16 values a lane needs per accumulator block are fetched as raw
+    // 16-byte vectors (fp32: four, bf16: two), one token block (BA accumulator blocks) per request group and two groups
+    // in flight, because the epilogue is bound by memory latency, not by bandwidth or arithmetic.
+    uint4 traw[2][BA][4];
+    // token block j of the tile: fp32 values fill traw[j & 1][i][0..3] (two blocks in flight); bf16 values fill
+    // traw[j >> 1][i][2 (j & 1) ..] (the whole tile fits)
+    auto tload = [&](auto J) __attribute__((always_inline)) {
+        constexpr int j = decltype(J)::value;
+        if (!FAST || (p.dbg & 2)) return;
+        const int64_t row = m0 + wb * (BT / WB) + j * 32 + lr;
+        const int64_t colw = n0 + wa * (BT / WA) + lh * 16;
+        if (T_F32) {
+            const uint4* src = reinterpret_cast<const uint4*>(reinterpret_cast<const float*>(p.target) + row * p.ldt + colw);
+#pragma clang loop unroll(full)
+            for (int i = 0; i < BA; ++i)
+#pragma clang loop unroll(full)
+                for (int q = 0; q < 4; ++q) traw[j & 1][i][q] = src[i * 8 + q];
+        } else {
+            const uint4* src = reinterpret_cast<const uint4*>(reinterpret_cast<const bf16_t*>(p.target) + row * p.ldt + colw);
+#pragma clang loop unroll(full)
+            for (int i = 0; i < BA; ++i)
+#pragma clang loop unroll(full)
+                for (int q = 0; q < 2; ++q) traw[j >> 1][i][2 * (j & 1) + q] = src[i * 4 + q];
+        }
+    };
+    // issued ahead of the last multiply before the evaluation that reads the target
+    auto tload_first = [&]() __attribute__((always_inline)) {
+        tload(IC<0>{});
+        if (FAST && !T_F32) { tload(IC<1>{}); tload(IC<2>{}); tload(IC<3>{}); }
+    };
     // ---- multiply ---------------------------------------------------------------------------------
     // per-lane LDS byte offsets of this wave's fragments for the four 16-wide sub-steps of a slice; block i of an
     // operand is 32 rows = 4096 bytes further (the swizzle term (row >> 1) & 7 is the same for all blocks)
@@ -308,63 +348,67 @@ __global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
         }
     };
     static_assert(PF_PER == 2, "the closing wait of a prefetching slice is written for two touches");
-    const bool pf_on = !CE && (p.loss_kind == AGZO_LOSS_MSE) && nd == nfull && nfull >= PF_SLICES + 2 &&
+    const bool pf_on = (p.dbg & 1) && !CE && (p.loss_kind == AGZO_LOSS_MSE) && nd == nfull && nfull >= PF_SLICES + 2 &&
                        (PF_SLICES * PF_PER * NT >= BT * lines_per_row);
-    // slices [it_begin, it_end): the plain ones (all inside the first call) run the pipeline above; the others are
-    // filled by the threads and multiplied one at a time
-    auto run_slices = [&](int it_begin, int it_end) __attribute__((always_inline)) {
-        int it = it_begin;
-        if (it == 0 && nfull > 0) {
+    // the plain slices 0 .. nfull-1 through the pipeline above
+    auto run_plain = [&](bool preload) __attribute__((always_inline)) {
+        if (nfull == 0) return;
 #pragma unroll
-            for (int q = 0; q < 16; ++q) dma1(0, 0, q);
-            if (nfull > 1) {
+        for (int q = 0; q < 16; ++q) dma1(0, 0, q);
+        if (nfull > 1) {
 #pragma unroll
-                for (int q = 0; q < N3; ++q) dma1(1, 1, q);
-                __builtin_amdgcn_s_waitcnt(0x0F76);          // vmcnt(N3): slice 0 has landed
-            } else {
-                __builtin_amdgcn_s_waitcnt(0x0F70);
-            }
-            __syncthreads();
-            if (nfull > 1) {
-#pragma unroll
-                for (int q = 0; q < 8; ++q) frag1(0, 0, 0, q);
-                const int split = pf_on ? nfull - 1 - PF_SLICES : nfull - 1;
-                steady(0, split, IC<0>{}, 0);
-                if (pf_on) steady(split, nfull - 1, IC<1>{}, 0);
-                __builtin_amdgcn_s_waitcnt(0x0F70);          // the re-fetches and touches
-                // last plain slice: sub-step 0 is already in fragment set 0
-                const int cur = (nfull - 1) & 1;
-#pragma unroll
-                for (int kk = 0; kk < 4; ++kk) {
-                    if (kk + 1 < 4) {
-#pragma unroll
-                        for (int q = 0; q < 8; ++q) frag1(cur, kk + 1, (kk + 1) & 1, q);
-                    }
-#pragma unroll
-                    for (int q = 0; q < 16; ++q) mfma1(kk & 1, q);
-                }
-            } else {
-                multiply_plain(0);
-            }
-            __syncthreads();
-            it = nfull;
+            for (int q = 0; q < N3; ++q) dma1(1, 1, q);
+            __builtin_amdgcn_s_waitcnt(0x0F76);          // vmcnt(N3): slice 0 has landed
+        } else {
+            __builtin_amdgcn_s_waitcnt(0x0F70);
         }
-        for (; it < it_end; ++it) {
+        __syncthreads();
+        if (nfull > 1) {
+#pragma unroll
+            for (int q = 0; q < 8; ++q) frag1(0, 0, 0, q);
+            const int split = pf_on ? nfull - 1 - PF_SLICES : nfull - 1;
+            steady(0, split, IC<0>{}, 0);
+            if (pf_on) steady(split, nfull - 1, IC<1>{}, 0);
+            __builtin_amdgcn_s_waitcnt(0x0F70);          // the re-fetches and touches
+            // last plain slice: sub-step 0 is already in fragment set 0
+            if (preload) tload_first();
+            const int cur = (nfull - 1) & 1;
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) {
+                if (kk + 1 < 4) {
+#pragma unroll
+                    for (int q = 0; q < 8; ++q) frag1(cur, kk + 1, (kk + 1) & 1, q);
+                }
+#pragma unroll
+                for (int q = 0; q < 16; ++q) mfma1(kk & 1, q);
+            }
+        } else {
+            if (preload) tload_first();
+            multiply_plain(0);
+        }
+        __syncthreads();
+    };
+    // slices [it_begin, it_end) that the threads fill themselves (ragged end of d_in, rank-r extension), one at a time
+    auto run_manual = [&](int it_begin, int it_end, int preload_at) __attribute__((always_inline)) {
+        for (int it = it_begin; it < it_end; ++it) {
             fill_manual(it, 0);
             __syncthreads();
+            if (it == preload_at) tload_first();
             multiply_plain(0);
             __syncthreads();
         }
     };
     // ---- evaluation point: the accumulators hold Y0 (shared mode, after the d_in slices), or Y with
     // the rank-r term of the current sign.  Lane = one token, 16 consecutive outputs per block.
+    // Differences and their squares are taken in fp32, four at a time, and summed in fp64.
+    // The caller has issued tload(0) before the last multiply when the target is read at this evaluation.
     auto evaluate = [&](int phase) __attribute__((always_inline)) {
         double part = 0.0;
         // shared mode: the first evaluation turns the accumulators into the residual Y0 - Y*, so the
         // target is read once and the two perturbed evaluations are sums of squares of registers
         const bool resid = !CE && SHARED && phase > 0 && p.loss_kind == AGZO_LOSS_MSE;
-#pragma clang loop unroll(full)
-        for (int j = 0; j < BB; ++j) {
+        auto eval_block = [&](auto J) __attribute__((always_inline)) {
+            constexpr int j = decltype(J)::value;
             const int64_t row = m0 + wb * (BT / WB) + j * 32 + lr;
 #pragma clang loop unroll(full)
             for (int i = 0; i < BA; ++i) {
@@ -373,8 +417,13 @@ __global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
                 if (row >= p.M || col0 >= p.N) continue;
                 if (resid) {
 #pragma clang loop unroll(full)
-                    for (int e = 0; e < 16; ++e)
-                        if (col0 + e < p.N) part = fma((double)v[e], (double)v[e], part);
+                    for (int q = 0; q < 4; ++q) {
+                        float s4 = 0.f;
+#pragma clang loop unroll(full)
+                        for (int u = 0; u < 4; ++u)
+                            if (col0 + 4 * q + u < p.N) s4 = fmaf(v[4 * q + u], v[4 * q + u], s4);
+                        part += (double)s4;
+                    }
                     continue;
                 }
                 if (p.vec_ok && col0 + 16 <= p.N) {
@@ -387,38 +436,43 @@ __global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
                         uint4* dst = reinterpret_cast<uint4*>(reinterpret_cast<bf16_t*>(p.Y) + row * p.ldy + col0);
                         uint32_t w[8];
 #pragma clang loop unroll(full)
-                        for (int q = 0; q < 8; ++q)
-                            w[q] = (uint32_t)f32_to_bf16(v[2 * q]) | ((uint32_t)f32_to_bf16(v[2 * q + 1]) << 16);
+                        for (int q = 0; q < 8; ++q) w[q] = pack_bf16x2(v[2 * q], v[2 * q + 1]);
                         dst[0] = make_uint4(w[0], w[1], w[2], w[3]);
                         dst[1] = make_uint4(w[4], w[5], w[6], w[7]);
                     }
                     if (l_f32) {
-                        const float4* src = reinterpret_cast<const float4*>(reinterpret_cast<const float*>(p.target) + row * p.ldt + col0);
 #pragma clang loop unroll(full)
                         for (int q = 0; q < 4; ++q) {
-                            const float4 t = src[q];
-                            const float tv[4] = {t.x, t.y, t.z, t.w};
+                            const uint4 t = reinterpret_cast<const uint4*>(reinterpret_cast<const float*>(p.target) + row * p.ldt + col0)[q];
+                            const float tv[4] = {__uint_as_float(t.x), __uint_as_float(t.y), __uint_as_float(t.z), __uint_as_float(t.w)};
+                            float s4 = 0.f;
 #pragma clang loop unroll(full)
                             for (int u = 0; u < 4; ++u) {
-                                const double dd = (double)v[4 * q + u] - (double)tv[u];
-                                part = fma(dd, dd, part);
-                                if (SHARED) v[4 * q + u] = v[4 * q + u] - tv[u];
+                                const float dd = v[4 * q + u] - tv[u];
+                                s4 = fmaf(dd, dd, s4);
+                                if (SHARED) v[4 * q + u] = dd;
                             }
+                            part += (double)s4;
                         }
                     }
                     if (l_bf16) {
-                        const uint4* src = reinterpret_cast<const uint4*>(reinterpret_cast<const bf16_t*>(p.target) + row * p.ldt + col0);
 #pragma clang loop unroll(full)
                         for (int q = 0; q < 2; ++q) {
-                            const uint4 t = src[q];
+                            const uint4 t = reinterpret_cast<const uint4*>(reinterpret_cast<const bf16_t*>(p.target) + row * p.ldt + col0)[q];
                             const uint32_t tw[4] = {t.x, t.y, t.z, t.w};
 #pragma clang loop unroll(full)
-                            for (int u = 0; u < 4; ++u) {
-                                const float t0 = __uint_as_float(tw[u] << 16), t1 = __uint_as_float(tw[u] & 0xFFFF0000u);
-                                const double d0 = (double)v[8 * q + 2 * u] - (double)t0;
-                                const double d1 = (double)v[8 * q + 2 * u + 1] - (double)t1;
-                                part = fma(d0, d0, part); part = fma(d1, d1, part);
-                                if (SHARED) { v[8 * q + 2 * u] -= t0; v[8 * q + 2 * u + 1] -= t1; }
+                            for (int h = 0; h < 2; ++h) {
+                                float s4 = 0.f;
+#pragma clang loop unroll(full)
+                                for (int u = 0; u < 2; ++u) {
+                                    const uint32_t w = tw[2 * h + u];
+                                    const float d0 = v[8 * q + 4 * h + 2 * u] - __uint_as_float(w << 16);
+                                    const float d1 = v[8 * q + 4 * h + 2 * u + 1] - __uint_as_float(w & 0xFFFF0000u);
+                                    s4 = fmaf(d0, d0, s4);
+                                    s4 = fmaf(d1, d1, s4);
+                                    if (SHARED) { v[8 * q + 4 * h + 2 * u] = d0; v[8 * q + 4 * h + 2 * u + 1] = d1; }
+                                }
+                                part += (double)s4;
                             }
                         }
                     }
@@ -434,15 +488,71 @@ __global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
                             if (l_f32) tv = reinterpret_cast<const float*>(p.target)[row * p.ldt + col];
                             if (l_bf16) tv = bf16_to_f32(reinterpret_cast<const bf16_t*>(p.target)[row * p.ldt + col]);
                             if (l_f32 || l_bf16) {
-                                const double dd = (double)y - (double)tv;
-                                part = fma(dd, dd, part);
-                                if (SHARED) v[e] = y - tv;
+                                const float dd = y - tv;
+                                part += (double)dd * (double)dd;
+                                if (SHARED) v[e] = dd;
                             }
                         }
                     }
                 }
                 if (SHARED) acc[i][j] = v;
             }
+        };
+        // fast path: one of two specialised bodies, no stores, no bounds
+        auto fast_block = [&](auto J, auto F32) __attribute__((always_inline)) {
+            constexpr int j = decltype(J)::value;
+            constexpr bool f32 = decltype(F32)::value != 0;
+#pragma clang loop unroll(full)
+            for (int i = 0; i < BA; ++i) {
+                floatx16 v = acc[i][j];
+#pragma clang loop unroll(full)
+                for (int q = 0; q < 4; ++q) {
+                    float tv[4] = {0.f, 0.f, 0.f, 0.f};
+                    if (!resid && !(p.dbg & 2)) {
+                        if (f32) {
+                            const uint4 t = traw[j & 1][i][q];
+                            tv[0] = __uint_as_float(t.x); tv[1] = __uint_as_float(t.y);
+                            tv[2] = __uint_as_float(t.z); tv[3] = __uint_as_float(t.w);
+                        } else {
+                            const uint4 t = traw[j >> 1][i][2 * (j & 1) + (q >> 1)];
+                            const uint32_t w0 = (q & 1) ? t.z : t.x, w1 = (q & 1) ? t.w : t.y;
+                            tv[0] = __uint_as_float(w0 << 16); tv[1] = __uint_as_float(w0 & 0xFFFF0000u);
+                            tv[2] = __uint_as_float(w1 << 16); tv[3] = __uint_as_float(w1 & 0xFFFF0000u);
+                        }
+                    }
+                    float s4 = 0.f;
+#pragma clang loop unroll(full)
+                    for (int u = 0; u < 4; ++u) {
+                        const float dd = v[4 * q + u] - tv[u];
+                        s4 = fmaf(dd, dd, s4);
+                        if (SHARED) v[4 * q + u] = dd;
+                    }
+                    part += (double)s4;
+                }
+                if (SHARED && !resid) acc[i][j] = v;
+            }
+        };
+        if constexpr (FAST) {
+            if constexpr (T_F32) {
+                // the next token block's values are requested before this one's are used
+                if (!resid) tload(IC<1>{});
+                fast_block(IC<0>{}, IC<1>{});
+                if (!resid) tload(IC<2>{});
+                fast_block(IC<1>{}, IC<1>{});
+                if (!resid) tload(IC<3>{});
+                fast_block(IC<2>{}, IC<1>{});
+                fast_block(IC<3>{}, IC<1>{});
+            } else {
+                fast_block(IC<0>{}, IC<0>{});
+                fast_block(IC<1>{}, IC<0>{});
+                fast_block(IC<2>{}, IC<0>{});
+                fast_block(IC<3>{}, IC<0>{});
+            }
+        } else {
+            eval_block(IC<0>{});
+            eval_block(IC<1>{});
+            eval_block(IC<2>{});
+            eval_block(IC<3>{});
         }
         if (CE) {
             // a lane holds 16 of the 32 logits of each of its BA blocks for BB tokens; its partner lane
@@ -494,32 +604,41 @@ __global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
             __syncthreads();
         }
     };
+    // the first target values are requested ahead of the last multiply before the evaluation that reads them
+    const int last0 = ((SHARED && next > 0) ? nd : total) - 1;
+    const uint64_t dbg_t0 = wall_clock64();
+    run_plain(last0 == nfull - 1);
+    const uint64_t dbg_t1 = wall_clock64();
     if (SHARED && next > 0) {
-        run_slices(0, nd);
+        run_manual(nfull, nd, last0);
         evaluate(0);
-        run_slices(nd, nd + next);
+        run_manual(nd, nd + next, -1);
         evaluate(1);
-        run_slices(nd + next, total);
+        run_manual(nd + next, total, -1);
         evaluate(2);
     } else {
-        run_slices(0, total);
+        run_manual(nfull, total, last0);
+        const uint64_t dbg_t2 = wall_clock64();
         evaluate(0);
+        if ((p.dbg & 8) && tid == 0 && (blockIdx.x == 300 || blockIdx.x == 900))
+            printf("wg %d: plain %llu manual %llu evaluate %llu (10 ns ticks)\n", (int)blockIdx.x, (unsigned long long)(dbg_t1 - dbg_t0),
+                   (unsigned long long)(dbg_t2 - dbg_t1), (unsigned long long)(wall_clock64() - dbg_t2));
     }
 }
 
 
-template <int WA, int WB, bool SHARED, bool CE>
+template <int WA, int WB, bool SHARED, int EPI>
 static hipError_t launch_variant(const GemmParams& p, hipStream_t st) {
     static bool attr_set = false;
     const int smem = 4 * TILE_BYTES + 256 * WA * WB + 64 * WA * WB * (int)sizeof(double);
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_bf16_kernel<WA, WB, SHARED, CE>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_bf16_kernel<WA, WB, SHARED, EPI>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, smem);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     dim3 grid((unsigned)((int64_t)p.tiles_m * p.tiles_n));
-    hipLaunchKernelGGL((gemm_bf16_kernel<WA, WB, SHARED, CE>), grid, dim3(64 * WA * WB), smem, st, p);
+    hipLaunchKernelGGL((gemm_bf16_kernel<WA, WB, SHARED, EPI>), grid, dim3(64 * WA * WB), smem, st, p);
     return hipGetLastError();
 }
 
@@ -535,6 +654,10 @@ hipError_t launch_gemm_bf16(const GemmBf16Args& a, hipStream_t st) {
     p.ldt = a.loss.ldt; p.partials = a.loss.partials;
     p.tiles_m = (int)((a.M + BT - 1) / BT);
     p.tiles_n = (int)((a.N + BT - 1) / BT);
+    p.group_m = 8;
+    if (const char* e = getenv("AGZO_GROUP_M")) p.group_m = atoi(e);
+    p.dbg = 0;
+    if (const char* e = getenv("AGZO_DBG")) p.dbg = atoi(e);
     bool vec = true;
     if (a.Y) vec = vec && (a.ldy % 8 == 0) && ((reinterpret_cast<uintptr_t>(a.Y) & 15) == 0);
     if (a.loss.kind == AGZO_LOSS_MSE)
@@ -544,9 +667,24 @@ hipError_t launch_gemm_bf16(const GemmBf16Args& a, hipStream_t st) {
     p.ce_target = reinterpret_cast<const int32_t*>(a.loss.target);
     p.ce_ms = reinterpret_cast<float2*>(a.loss.ce_ms);
     p.ce_tl = a.loss.ce_tl;
-    const bool ce = (p.loss_kind == AGZO_LOSS_CE);
-    if (p.shared) return ce ? launch_variant<2, 2, true, true>(p, st) : launch_variant<2, 2, true, false>(p, st);
-    return ce ? launch_variant<2, 2, false, true>(p, st) : launch_variant<2, 2, false, false>(p, st);
+    int epi = 0;
+    if (p.loss_kind == AGZO_LOSS_CE) epi = 1;
+    else if (p.loss_kind == AGZO_LOSS_MSE && !a.Y && vec && a.M % BT == 0 && a.N % BT == 0)
+        epi = (p.target_dtype == AGZO_BF16) ? 3 : 2;
+    if (p.shared) {
+        switch (epi) {
+            case 1: return launch_variant<2, 2, true, 1>(p, st);
+            case 2: return launch_variant<2, 2, true, 2>(p, st);
+            case 3: return launch_variant<2, 2, true, 3>(p, st);
+            default: return launch_variant<2, 2, true, 0>(p, st);
+        }
+    }
+    switch (epi) {
+        case 1: return launch_variant<2, 2, false, 1>(p, st);
+        case 2: return launch_variant<2, 2, false, 2>(p, st);
+        case 3: return launch_variant<2, 2, false, 3>(p, st);
+        default: return launch_variant<2, 2, false, 0>(p, st);
+    }
 }
 
 }  // namespace agzo
