@@ -277,8 +277,15 @@ __global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
     auto dma1 = [&](int kt, int buf, int q) __attribute__((always_inline)) {
         const int t = q >> 1;
         char* dst = smem + buf * (2 * TILE_BYTES) + wave * 1024 + t * 4096 + ((q & 1) ? TILE_BYTES : 0);
-        if (q & 1) __builtin_amdgcn_raw_ptr_buffer_load_lds(rw, (lptr_t)dst, 16, wo[t], kt * (BK * 2), 0, 0);
-        else __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (lptr_t)dst, 16, xo[t], kt * (BK * 2), 0, 0);
+        if constexpr (SHARED) {
+            // per-lane 64-bit addresses: this variant is short of scalar registers, and a buffer descriptor that the
+            // register allocator moves into vector registers would be re-broadcast lane by lane at every load
+            const char* src = reinterpret_cast<const char*>((q & 1) ? wbase : xbase) + ((q & 1) ? wo[t] : xo[t]) + kt * (BK * 2);
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src, (lptr_t)dst, 16, 0, 0);
+        } else {
+            if (q & 1) __builtin_amdgcn_raw_ptr_buffer_load_lds(rw, (lptr_t)dst, 16, wo[t], kt * (BK * 2), 0, 0);
+            else __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (lptr_t)dst, 16, xo[t], kt * (BK * 2), 0, 0);
+        }
     };
     // Target prefetch: while the last PF_SLICES plain slices are multiplied every thread touches PF_PER lines of the
     // tile's target values per slice with 4-byte LDS-direct loads into a scratch slot, so that the epilogue's reads
@@ -610,12 +617,13 @@ __global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
     run_plain(last0 == nfull - 1);
     const uint64_t dbg_t1 = wall_clock64();
     if (SHARED && next > 0) {
-        run_manual(nfull, nd, last0);
-        evaluate(0);
-        run_manual(nd, nd + next, -1);
-        evaluate(1);
-        run_manual(nd + next, total, -1);
-        evaluate(2);
+        // one copy of the fill / multiply / evaluate code, walked three times: Y0, Y+ (extension with +eps), Y- (-2 eps)
+        for (int ph = 0; ph < 3; ++ph) {
+            const int it0 = (ph == 0) ? nfull : nd + (ph - 1) * next;
+            const int it1 = nd + ph * next;
+            run_manual(it0, it1, (ph == 0) ? last0 : -1);
+            evaluate(ph);
+        }
     } else {
         run_manual(nfull, total, last0);
         const uint64_t dbg_t2 = wall_clock64();
