@@ -224,17 +224,18 @@ int reduce_to_S(agzo_ctx* ctx, const agzo_layer& L, const Plan& p, float* S) {
 }
 
 // Q = qr(S) for an explicit S; planes (nullable) also receive Q as bf16 planes
-int op_qr(agzo_ctx* ctx, size_t off_qr, const float* S, int64_t d, int r, int rp, float* Q, bf16_t* planes) {
+int op_qr(agzo_ctx* ctx, size_t off_qr, const float* S, int64_t d, int r, int rp, float* Q, bf16_t* planes,
+          bool refine = true) {
     ProfScope ps(ctx, AGZO_PROF_QR);
-    HIPCHK(launch_qr(S, nullptr, 0, rp, nullptr, d, r, Q, planes, ctx->ws + off_qr, ctx->flag, ctx->stream));
+    HIPCHK(launch_qr(S, nullptr, 0, rp, nullptr, d, r, Q, planes, ctx->ws + off_qr, ctx->flag, refine, ctx->stream));
     return 0;
 }
 
 // Q = qr(sum of the pending splits); the summed sketch is left in the workspace S
-int op_qr_from_splits(agzo_ctx* ctx, const agzo_layer& L, const Plan& p, float* Q, bf16_t* planes) {
+int op_qr_from_splits(agzo_ctx* ctx, const agzo_layer& L, const Plan& p, float* Q, bf16_t* planes, bool refine) {
     ProfScope ps(ctx, AGZO_PROF_QR);
     HIPCHK(launch_qr(nullptr, wsf(ctx, p.off_xtt), p.nsplit, p.rp, wsf(ctx, p.off_S), L.d_in, L.r, Q, planes,
-                     ctx->ws + p.off_qr, ctx->flag, ctx->stream));
+                     ctx->ws + p.off_qr, ctx->flag, refine, ctx->stream));
     return 0;
 }
 
@@ -340,13 +341,16 @@ int op_basis(agzo_ctx* ctx, const agzo_layer& L, const Plan& p, const void* X, i
     }
     for (int k = 0; k <= K; ++k) {
         float* out = (k == K) ? B : Q;
+        // iterates that are sketched again need a well-conditioned basis of the same span, not full orthonormality:
+        // one Cholesky pass (same final QR factor, see qr.hip); the returned basis gets both passes
+        const bool refine = (k == K);
         if (given) {
-            TRY(op_qr(ctx, p.off_qr, given, L.d_in, L.r, p.rp, out, planes));
+            TRY(op_qr(ctx, p.off_qr, given, L.d_in, L.r, p.rp, out, planes, refine));
             given = nullptr;
         } else if (bf) {
-            TRY(op_qr_from_splits(ctx, L, p, out, planes));
+            TRY(op_qr_from_splits(ctx, L, p, out, planes, refine));
         } else {
-            TRY(op_qr(ctx, p.off_qr, S, L.d_in, L.r, p.rp, out, nullptr));
+            TRY(op_qr(ctx, p.off_qr, S, L.d_in, L.r, p.rp, out, nullptr, refine));
         }
         if (k < K) TRY(sketch_power(ctx, L, p, X, Q, S));
     }

@@ -144,9 +144,9 @@ hipError_t launch_pack_planes(const float* Q, int64_t d, int r, int rp, bf16_t* 
 // qr.hip : CholeskyQR2
 size_t qr_workspace_bytes(int64_t d, int r);
 // S explicit, or splits [nsplit][d][rp] (then their fp32 sum is also stored to S_out); Q fp32 out;
-// planes (nullable) bf16 [3][rp][d]
+// planes (nullable) bf16 [3][rp][d]; refine = false: single Cholesky pass (for iterates that are sketched again)
 hipError_t launch_qr(const float* S, const float* splits, int nsplit, int rp, float* S_out, int64_t d, int r, float* Q,
-                     bf16_t* planes, void* workspace, int* numeric_flag, hipStream_t st);
+                     bf16_t* planes, void* workspace, int* numeric_flag, bool refine, hipStream_t st);
 
 // update.hip : W -= lr * g * G B^T in place
 // workspace: update_workspace_bytes() bytes of device scratch (may be NULL when that is 0)

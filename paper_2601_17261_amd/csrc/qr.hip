@@ -11,6 +11,9 @@
 //                    the Gram partials of Q1
 //   3. apply_final : the same reduction and factorisation -> R2; Q = Q1 R2^-1 (fp32), optionally
 //                    also as three bf16 planes [3][rp][d]
+// The orthonormalisations between power steps run a single pass (launches 1 and 3 only, launch 3 applying R1 to Y):
+// Q1 = Q R2 with R2 upper triangular and positive on the diagonal, so the next sketch X^T X Q1 = (X^T X Q) R2 has
+// the same thin-QR Q factor; the second pass only matters for the orthonormality of the basis that is returned.
 // When the input arrives as per-token-range partial sketches, launch 1 sums them (fp64, fixed order)
 // on the way in and stores the fp32 sketch, so no separate reduction kernel is needed.
 #include "agzo_internal.h"
@@ -234,8 +237,10 @@ __global__ __launch_bounds__(256) void qr_apply_gram_kernel(const float* __restr
     gram_partial(Ys, ld, rows_pad, rp, partial2);
 }
 
-// launch 3: Q = Q1 R2^-1, rounded to fp32; planes (nullable) receive the hi/mid/lo bf16 parts [3][rp][d]
-__global__ __launch_bounds__(256) void qr_apply_final_kernel(const double* __restrict__ Q1, int64_t d, int r, int rp,
+// launch 3: Q = Q1 R2^-1, rounded to fp32; planes (nullable) receive the hi/mid/lo bf16 parts [3][rp][d].
+// With Tin = float the same kernel closes a single-pass factorisation: Q = Y R1^-1 straight from launch 1's partials.
+template <typename Tin>
+__global__ __launch_bounds__(256) void qr_apply_final_kernel(const Tin* __restrict__ Q1, int64_t d, int r, int rp,
                                                              const double* __restrict__ partial2, int nblk,
                                                              float* __restrict__ Q, bf16_t* __restrict__ planes,
                                                              int* flag) {
@@ -268,7 +273,7 @@ __global__ __launch_bounds__(256) void qr_apply_final_kernel(const double* __res
 }
 
 hipError_t launch_qr(const float* S, const float* splits, int nsplit, int rp, float* S_out, int64_t d, int r, float* Q,
-                     bf16_t* planes, void* workspace, int* numeric_flag, hipStream_t st) {
+                     bf16_t* planes, void* workspace, int* numeric_flag, bool refine, hipStream_t st) {
     if (d == 0) return hipSuccess;
     const int nblk = (int)qr_blocks(d);
     double* Q1 = reinterpret_cast<double*>(workspace);
@@ -285,16 +290,24 @@ hipError_t launch_qr(const float* S, const float* splits, int nsplit, int rp, fl
             e = hipFuncSetAttribute(reinterpret_cast<const void*>(qr_apply_gram_kernel),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, big);
         if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(qr_apply_final_kernel),
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(qr_apply_final_kernel<double>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, big);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(qr_apply_final_kernel<float>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, big);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     const float* Sin = splits ? S_out : S;
     hipLaunchKernelGGL(qr_gram_kernel, grid, block, sm_full, st, S, splits, nsplit, S_out, d, r, rp, partial1);
+    if (!refine) {
+        hipLaunchKernelGGL(qr_apply_final_kernel<float>, grid, block, sm_full, st, Sin, d, r, rp, partial1, nblk, Q, planes,
+                           numeric_flag);
+        return hipGetLastError();
+    }
     hipLaunchKernelGGL(qr_apply_gram_kernel, grid, block, sm_full, st, Sin, d, r, rp, partial1, nblk, Q1, partial2,
                        numeric_flag);
-    hipLaunchKernelGGL(qr_apply_final_kernel, grid, block, sm_full, st, Q1, d, r, rp, partial2, nblk, Q, planes,
+    hipLaunchKernelGGL(qr_apply_final_kernel<double>, grid, block, sm_full, st, Q1, d, r, rp, partial2, nblk, Q, planes,
                        numeric_flag);
     return hipGetLastError();
 }
