@@ -17,76 +17,160 @@ union Frag {
 };
 
 // ---------------------------------------------------------------------------
-// xq: workgroup = 32 tokens, its 4 waves split d_in; partial tiles are summed through LDS.
-// MFMA roles: A = X tile (rows = tokens, K = d_in), B = Q planes (K = d_in, cols = k).
+// xq: workgroup = 64 tokens, wave = 16 of them over the whole of d_in, so no cross-wave reduction.
+// MFMA roles: A = X tile (rows = tokens, K = d_in), B = Q planes (K = d_in, cols = k); the three planes
+// accumulate into the same registers.  X and the plane rows travel global -> LDS directly in 64-wide
+// slices (one 128-byte line per row and slice, XOR-swizzled chunks) through a ring of XQ_STAGES slots,
+// so that enough bytes are in flight per CU to cover the memory latency with four waves.
 // ---------------------------------------------------------------------------
-constexpr int XQ_TOK = 32;
+constexpr int XQ_TOK = 64;
+constexpr int XQ_BK = 64;
+
+__device__ __forceinline__ int xq_lds_off(int row, int c) { return row * 128 + ((c ^ ((row >> 1) & 7)) << 4); }
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+    static_assert(N >= 0 && N < 64, "vmcnt range");
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+}
+// wait until at most n loads of this wave are outstanding (n is wave-uniform)
+__device__ __forceinline__ void wait_vmcnt_dyn(int n) {
+    switch (n) {
+        case 0: wait_vmcnt<0>(); break;   case 3: wait_vmcnt<3>(); break;   case 4: wait_vmcnt<4>(); break;
+        case 5: wait_vmcnt<5>(); break;   case 6: wait_vmcnt<6>(); break;   case 7: wait_vmcnt<7>(); break;
+        case 8: wait_vmcnt<8>(); break;   case 9: wait_vmcnt<9>(); break;   case 10: wait_vmcnt<10>(); break;
+        case 12: wait_vmcnt<12>(); break; case 14: wait_vmcnt<14>(); break; case 15: wait_vmcnt<15>(); break;
+        case 16: wait_vmcnt<16>(); break; case 18: wait_vmcnt<18>(); break; case 20: wait_vmcnt<20>(); break;
+        case 21: wait_vmcnt<21>(); break; case 24: wait_vmcnt<24>(); break; case 28: wait_vmcnt<28>(); break;
+        default: wait_vmcnt<0>(); break;
+    }
+}
 
 template <int NB>
 __global__ __launch_bounds__(256) void xq_bf16_kernel(const bf16_t* __restrict__ X, int64_t ldx, int64_t M, int64_t K,
                                                       const bf16_t* __restrict__ Qpack, int r, float* __restrict__ T,
                                                       bf16_t* __restrict__ TpackT, int64_t m_pad) {
     constexpr int RP = NB * 16;
-    __shared__ float red[4][XQ_TOK][RP + 1];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    constexpr int QROWS = 3 * RP;                          // plane rows: (plane, k)
+    constexpr int NGROUP = XQ_TOK / 8 + QROWS / 8;         // 8-row groups per slice: X first, then the planes
+    constexpr int SLOT = (XQ_TOK + QROWS) * 128;           // bytes per ring slot
+    constexpr int STAGES = (NB == 1) ? 8 : (NB == 2) ? 6 : 4;
+    extern __shared__ __align__(16) char xq_smem[];
+    typedef __attribute__((address_space(3))) void* lptr_t;
+    typedef const __attribute__((address_space(1))) void* gptr_t;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lm = lane & 15, lg = lane >> 4;
     const int64_t t0 = (int64_t)blockIdx.x * XQ_TOK;
 
-    floatx4 acc[2][NB];
+    floatx4 acc[NB];
 #pragma unroll
-    for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb) acc[mt][nb] = floatx4{0.f, 0.f, 0.f, 0.f};
+    for (int nb = 0; nb < NB; ++nb) acc[nb] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-    const int64_t ksteps = (K + 31) / 32;
-    const int64_t per = (ksteps + 3) / 4;
-    const int64_t s_begin = wave * per, s_end = min(s_begin + per, ksteps);
-    const bf16_t* xrow[2];
+    // this wave's row groups g = wave, wave + 4, ...: per-lane source pointers (row of the group, swizzled chunk)
+    constexpr int MAXG = (NGROUP + 3) / 4;
+    const int ng = (NGROUP - wave + 3) / 4;                // groups of this wave
+    const bf16_t* src[MAXG];
 #pragma unroll
-    for (int mt = 0; mt < 2; ++mt) xrow[mt] = X + min(t0 + mt * 16 + lm, M - 1) * ldx;
-
-#pragma unroll 2
-    for (int64_t s = s_begin; s < s_end; ++s) {
-        const int64_t d = s * 32 + lg * 8;
-        const bool in = d < K;
-        Frag a[2];
+    for (int i = 0; i < MAXG; ++i) {
+        const int g = min(wave + 4 * i, NGROUP - 1);
+        const int row = 8 * g + (lane >> 3);
+        const int c = (lane & 7) ^ ((row >> 1) & 7);
+        if (row < XQ_TOK) src[i] = X + min(t0 + row, M - 1) * ldx + c * 8;
+        else src[i] = Qpack + (int64_t)(row - XQ_TOK) * K + c * 8;
+    }
+    const int nfull = (int)(K / XQ_BK);
+    const bool tail = (K % XQ_BK) != 0;
+    auto issue = [&](int kt, int slot) __attribute__((always_inline)) {
+        char* base = xq_smem + slot * SLOT + wave * 1024;
 #pragma unroll
-        for (int mt = 0; mt < 2; ++mt)
-            a[mt].u = in ? *reinterpret_cast<const uint4*>(xrow[mt] + d) : make_uint4(0, 0, 0, 0);
+        for (int i = 0; i < MAXG; ++i)
+            if (i < ng)
+                __builtin_amdgcn_global_load_lds((gptr_t)(src[i] + (int64_t)kt * XQ_BK), (lptr_t)(base + i * 4096), 16, 0, 0);
+    };
+    auto multiply = [&](int slot) __attribute__((always_inline)) {
+        const char* xs = xq_smem + slot * SLOT;
+        const char* qs = xs + XQ_TOK * 128;
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {
+        for (int sub = 0; sub < 2; ++sub) {
+            Frag a;
+            a.u = *reinterpret_cast<const uint4*>(xs + xq_lds_off(wave * 16 + lm, sub * 4 + lg));
 #pragma unroll
-            for (int pl = 0; pl < 3; ++pl) {
-                Frag b;
-                b.u = in ? *reinterpret_cast<const uint4*>(Qpack + ((int64_t)(pl * RP + nb * 16 + lm)) * K + d)
-                         : make_uint4(0, 0, 0, 0);
+            for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-                for (int mt = 0; mt < 2; ++mt)
-                    acc[mt][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[mt].v, b.v, acc[mt][nb], 0, 0, 0);
-            }
+                for (int pl = 0; pl < 3; ++pl) {
+                    Frag b;
+                    b.u = *reinterpret_cast<const uint4*>(qs + xq_lds_off(pl * RP + nb * 16 + lm, sub * 4 + lg));
+                    acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, b.v, acc[nb], 0, 0, 0);
+                }
         }
+    };
+    // ring: slices kt .. kt + STAGES - 2 in flight while slice kt is multiplied
+#pragma unroll
+    for (int s = 0; s < STAGES - 1; ++s)
+        if (s < nfull) issue(s, s);
+    int slot = 0;
+    for (int kt = 0; kt < nfull; ++kt) {
+        // this wave's loads of slice kt have landed when at most (younger slices in flight) * ng are outstanding
+        const int younger = min(STAGES - 2, nfull - 1 - kt);
+        wait_vmcnt_dyn(younger * ng);
+        __syncthreads();                                   // everybody's loads of slice kt; slot of slice kt-1 is free
+        if (kt + STAGES - 1 < nfull) issue(kt + STAGES - 1, (slot + STAGES - 1) % STAGES);
+        multiply(slot);
+        slot = (slot + 1 == STAGES) ? 0 : slot + 1;
+    }
+    if (tail) {
+        // ragged end of d_in: the threads copy it themselves, zero past d_in
+        __syncthreads();
+        char* base = xq_smem;                              // slot 0 (all loads have landed and were consumed)
+        for (int e = tid; e < (XQ_TOK + QROWS) * 8; e += 256) {
+            const int row = e >> 3, c = e & 7;
+            const int64_t kcol = (int64_t)nfull * XQ_BK + c * 8;
+            uint4 v = make_uint4(0, 0, 0, 0);
+            if (kcol < K) {
+                const bf16_t* p = (row < XQ_TOK) ? X + min(t0 + row, M - 1) * ldx + kcol
+                                                 : Qpack + (int64_t)(row - XQ_TOK) * K + kcol;
+                v = *reinterpret_cast<const uint4*>(p);
+            }
+            *reinterpret_cast<uint4*>(base + xq_lds_off(row, c)) = v;
+        }
+        __syncthreads();
+        multiply(0);
     }
     // D layout: row (token) = 4*(lane/16) + e, col (k) = lane%16
 #pragma unroll
-    for (int mt = 0; mt < 2; ++mt)
+    for (int nb = 0; nb < NB; ++nb) {
+        const int k = nb * 16 + lm;
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-            for (int e = 0; e < 4; ++e) red[wave][mt * 16 + lg * 4 + e][nb * 16 + lm] = acc[mt][nb][e];
-    __syncthreads();
-    for (int idx = tid; idx < XQ_TOK * RP; idx += 256) {
-        const int tt = idx % XQ_TOK, k = idx / XQ_TOK;
-        const int64_t t = t0 + tt;
-        const float v = (red[0][tt][k] + red[1][tt][k]) + (red[2][tt][k] + red[3][tt][k]);
-        if (t < M && k < r && T != nullptr) T[t * r + k] = v;
-        if (TpackT != nullptr && t < m_pad) {
-            bf16_t hi, mid, lo;
-            split3_bf16((t < M && k < r) ? v : 0.f, hi, mid, lo);
-            TpackT[((int64_t)0 * RP + k) * m_pad + t] = hi;
-            TpackT[((int64_t)1 * RP + k) * m_pad + t] = mid;
-            TpackT[((int64_t)2 * RP + k) * m_pad + t] = lo;
+        for (int e = 0; e < 4; ++e) {
+            const int64_t t = t0 + wave * 16 + lg * 4 + e;
+            const float v = (t < M && k < r) ? acc[nb][e] : 0.f;
+            if (t < M && k < r && T != nullptr) T[t * r + k] = v;
+            if (TpackT != nullptr && t < m_pad) {
+                bf16_t hi, mid, lo;
+                split3_bf16(v, hi, mid, lo);
+                TpackT[((int64_t)0 * RP + k) * m_pad + t] = hi;
+                TpackT[((int64_t)1 * RP + k) * m_pad + t] = mid;
+                TpackT[((int64_t)2 * RP + k) * m_pad + t] = lo;
+            }
         }
     }
+}
+
+template <int NB>
+static hipError_t launch_xq_nb(dim3 grid, hipStream_t st, const bf16_t* X, int64_t ldx, int64_t M, int64_t K,
+                               const bf16_t* Qpack, int r, float* T, bf16_t* TpackT, int64_t m_pad) {
+    constexpr int stages = (NB == 1) ? 8 : (NB == 2) ? 6 : 4;
+    const int smem = stages * (XQ_TOK + 3 * NB * 16) * 128;
+    static bool set = false;
+    if (!set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(xq_bf16_kernel<NB>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+        if (e != hipSuccess) return e;
+        set = true;
+    }
+    hipLaunchKernelGGL(xq_bf16_kernel<NB>, grid, dim3(256), smem, st, X, ldx, M, K, Qpack, r, T, TpackT, m_pad);
+    return hipGetLastError();
 }
 
 hipError_t launch_xq_bf16(const bf16_t* X, int64_t ldx, int64_t M, int64_t K, const bf16_t* Qpack, int r, int rp,
@@ -96,13 +180,12 @@ hipError_t launch_xq_bf16(const bf16_t* X, int64_t ldx, int64_t M, int64_t K, co
     const int64_t rows = TpackT ? m_pad : M;
     dim3 grid((unsigned)((rows + XQ_TOK - 1) / XQ_TOK));
     switch (rp / 16) {
-        case 1: hipLaunchKernelGGL(xq_bf16_kernel<1>, grid, dim3(256), 0, st, X, ldx, M, K, Qpack, r, T, TpackT, m_pad); break;
-        case 2: hipLaunchKernelGGL(xq_bf16_kernel<2>, grid, dim3(256), 0, st, X, ldx, M, K, Qpack, r, T, TpackT, m_pad); break;
-        case 3: hipLaunchKernelGGL(xq_bf16_kernel<3>, grid, dim3(256), 0, st, X, ldx, M, K, Qpack, r, T, TpackT, m_pad); break;
-        case 4: hipLaunchKernelGGL(xq_bf16_kernel<4>, grid, dim3(256), 0, st, X, ldx, M, K, Qpack, r, T, TpackT, m_pad); break;
+        case 1: return launch_xq_nb<1>(grid, st, X, ldx, M, K, Qpack, r, T, TpackT, m_pad);
+        case 2: return launch_xq_nb<2>(grid, st, X, ldx, M, K, Qpack, r, T, TpackT, m_pad);
+        case 3: return launch_xq_nb<3>(grid, st, X, ldx, M, K, Qpack, r, T, TpackT, m_pad);
+        case 4: return launch_xq_nb<4>(grid, st, X, ldx, M, K, Qpack, r, T, TpackT, m_pad);
         default: return hipErrorInvalidValue;
     }
-    return hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------
