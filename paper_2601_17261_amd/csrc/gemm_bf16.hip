@@ -2,16 +2,22 @@
 //     Y = X W^T  (+ eps * (X B) G^T, the factored form of Eq. 7)   with fp32 accumulation,
 // and the loss of Sec. 4.1 (f0, f+, f-) reduced from the fp32 accumulators in the epilogue.
 //
-// Tiling: one workgroup owns a 256 (tokens) x 256 (outputs) tile of Y.  X and W are both
-// K-contiguous (an "NT" product) and are staged through LDS in 64-wide K slices, double buffered.
-// MFMA roles (v_mfma_f32_32x32x16_bf16): A-operand = W rows, B-operand = X rows, so a lane owns one
-// token and 16 output columns per 32x32 block; the W rows of a block are permuted on their way
-// into LDS so that those 16 columns are consecutive and the epilogue moves 16-byte vectors.
-// The rank-r term is accumulated by the same MFMA loop as a few extra K slices appended after the
-// d_in slices: one operand is eps * P split in bf16 hi/lo, the other is G regenerated from the
-// Philox seed and split likewise, so both signs share bit-identical X W^T accumulators.
+// Tiling: one workgroup (4 waves, one per SIMD) owns a 256 (tokens) x 256 (outputs) tile of Y, one wave a
+// 128 x 128 quarter: 16 accumulator blocks = 256 registers, which the compiler keeps in the accumulation half of
+// the register file, leaving the other 256 for operands and the epilogue.  The large wave tile is what keeps the
+// LDS traffic per MFMA low enough (8 fragment reads per 16 MFMAs).
+// X and W are both K-contiguous (an "NT" product) and are staged through LDS in 64-wide K slices, double
+// buffered, with direct global -> LDS loads.  MFMA roles (v_mfma_f32_32x32x16_bf16): A-operand = W rows,
+// B-operand = X rows, so a lane owns one token and 16 output columns per 32x32 block; the W rows of a block are
+// permuted on their way into LDS so that those 16 columns are consecutive and the epilogue moves 16-byte vectors.
+// With one wave per SIMD nothing hides an issue stall, so the steady state is written in issue order: every MFMA
+// is followed by at most one fragment read or one direct load, the 16 loads of the next slice are spread over
+// three of the four 16-MFMA blocks, and the slice's barrier sits before its last block, whose MFMAs then cover
+// the LDS latency of the next slice's first fragments.
+// The rank-r term is accumulated by the same MFMA blocks as a few extra K slices appended after the d_in slices:
+// one operand is eps * P split in bf16 hi/lo, the other is G regenerated from the Philox seed and split
+// likewise, so both signs share bit-identical X W^T accumulators.
 #include "agzo_internal.h"
-#include <stdlib.h>
 
 namespace agzo {
 
@@ -47,7 +53,6 @@ struct GemmParams {
     float eps_signed; uint32_t s_lo, s_hi;
     int loss_kind; int target_dtype; const void* target; int64_t ldt; double* partials;
     int tiles_m, tiles_n;
-    int dbg;
     int group_m;                // token tiles walked per output tile inside an XCD's run
     int vec_ok;                 // 16-byte epilogue accesses are legal
     int shared;                 // one pass evaluates f0, f+ and f- (three loss partials per tile)
@@ -216,9 +221,7 @@ __global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
     };
     typedef __attribute__((address_space(3))) void* lptr_t;
 
-    char* sink = smem + 4 * TILE_BYTES + wave * 256;
-    double* red = reinterpret_cast<double*>(smem + 4 * TILE_BYTES + 256 * WA * WB);
-    const int t_shift = (p.target_dtype == AGZO_BF16) ? 1 : 2;       // log2(bytes per target element)
+    double* red = reinterpret_cast<double*>(smem + 4 * TILE_BYTES);
     const bool y_f32 = (p.Y != nullptr) && p.y_dtype != AGZO_BF16;
     const bool y_bf16 = (p.Y != nullptr) && p.y_dtype == AGZO_BF16;
     const bool l_f32 = !CE && p.loss_kind == AGZO_LOSS_MSE && p.target_dtype != AGZO_BF16;
@@ -232,7 +235,7 @@ __global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
     // traw[j >> 1][i][2 (j & 1) ..] (the whole tile fits)
     auto tload = [&](auto J) __attribute__((always_inline)) {
         constexpr int j = decltype(J)::value;
-        if (!FAST || (p.dbg & 2)) return;
+        if (!FAST) return;
         const int64_t row = m0 + wb * (BT / WB) + j * 32 + lr;
         const int64_t colw = n0 + wa * (BT / WA) + lh * 16;
         if (T_F32) {
@@ -287,33 +290,18 @@ __global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
             else __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (lptr_t)dst, 16, xo[t], kt * (BK * 2), 0, 0);
         }
     };
-    // Target prefetch: while the last PF_SLICES plain slices are multiplied every thread touches PF_PER lines of the
-    // tile's target values per slice with 4-byte LDS-direct loads into a scratch slot, so that the epilogue's reads
-    // find the tile in L2.  These loads are issued after the slice's operand loads and may stay in flight across the
-    // slice's closing wait.
-    constexpr int PF_SLICES = 4, PF_PER = 2;
-    const int lines_per_row = (BT << t_shift) >> 7;                    // 128-byte lines per tile row
-    auto touch = [&](int pj, int u) __attribute__((always_inline)) {
-        const int line = (pj * PF_PER + u) * NT + tid;
-        const int64_t prow = min((int64_t)(line / lines_per_row), p.M - 1 - m0);
-        const int64_t pcol = min((int64_t)((line % lines_per_row) << (7 - t_shift)), p.N - 1 - n0);
-        const char* tp = reinterpret_cast<const char*>(p.target) + (((m0 + prow) * p.ldt + n0 + pcol) << t_shift);
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)tp, (lptr_t)sink, 4, 0, 0);
-    };
     // One block = the 16 MFMAs of sub-step S_CUR in a fixed issue order (a scheduling barrier after every group keeps
     // the compiler from regrouping): even slots carry one fragment read each (for the next block), odd slots carry
-    // the direct loads D0..D1-1 of slice lkt, spread evenly, or the target touches of this slice.
-    auto block = [&](auto S_CUR, int rbuf, auto RKK, auto RS, int lkt, int lbuf, auto D0, auto D1, auto NTOUCH, int pj)
-                     __attribute__((always_inline)) {
+    // the direct loads D0..D1-1 of slice lkt, spread evenly.
+    auto block = [&](auto S_CUR, int rbuf, auto RKK, auto RS, int lkt, int lbuf, auto D0, auto D1) __attribute__((always_inline)) {
         constexpr int s_cur = decltype(S_CUR)::value, rkk = decltype(RKK)::value, rs = decltype(RS)::value;
-        constexpr int d0 = decltype(D0)::value, d1 = decltype(D1)::value, n = d1 - d0, ntouch = decltype(NTOUCH)::value;
+        constexpr int d0 = decltype(D0)::value, d1 = decltype(D1)::value, n = d1 - d0;
 #pragma unroll
         for (int q = 0; q < 16; ++q) {
             mfma1(s_cur, q);
             const int o = q >> 1;
             if (!(q & 1)) frag1(rbuf, rkk, rs, o);
             else if (((o + 1) * n) / 8 > (o * n) / 8) dma1(lkt, lbuf, d0 + (o * n) / 8);
-            else if (ntouch > 0 && o < ntouch) touch(pj, o);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
@@ -323,21 +311,19 @@ __global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
     static_assert(N3 + N0 + N1 == 16, "loads per slice");
     // plain slices kt0 .. kt1-1 of the steady state; on entry fragment set 0 holds sub-step 0 of slice kt0 and the
     // first N3 loads of slice kt0+1 are in flight; the same holds for kt1 on exit
-    auto steady = [&](int kt0, int kt1, auto PF, int pj0) __attribute__((always_inline)) {
-        constexpr int pf = decltype(PF)::value;
+    auto steady = [&](int kt0, int kt1) __attribute__((always_inline)) {
         for (int kt = kt0; kt < kt1; ++kt) {
             const int cur = kt & 1;
-            block(IC<0>{}, cur, IC<1>{}, IC<1>{}, kt + 1, cur ^ 1, IC<N3>{}, IC<N3 + N0>{}, IC<0>{}, 0);
-            block(IC<1>{}, cur, IC<2>{}, IC<0>{}, kt + 1, cur ^ 1, IC<N3 + N0>{}, IC<16>{}, IC<0>{}, 0);
-            block(IC<0>{}, cur, IC<3>{}, IC<1>{}, 0, 0, IC<0>{}, IC<0>{}, IC<pf ? PF_PER : 0>{}, pj0 + (kt - kt0));
-            // every operand load has landed (the touches just issued may stay in flight); all waves are done reading
-            // the buffer that the next loads overwrite
-            if (pf) __builtin_amdgcn_s_waitcnt(0x0072);      // vmcnt(PF_PER) lgkmcnt(0)
-            else __builtin_amdgcn_s_waitcnt(0x0070);         // vmcnt(0) lgkmcnt(0)
+            block(IC<0>{}, cur, IC<1>{}, IC<1>{}, kt + 1, cur ^ 1, IC<N3>{}, IC<N3 + N0>{});
+            block(IC<1>{}, cur, IC<2>{}, IC<0>{}, kt + 1, cur ^ 1, IC<N3 + N0>{}, IC<16>{});
+            block(IC<0>{}, cur, IC<3>{}, IC<1>{}, 0, 0, IC<0>{}, IC<0>{});
+            // every operand load of the next slice has landed; all waves are done reading the buffer that the next
+            // loads overwrite
+            __builtin_amdgcn_s_waitcnt(0x0070);              // vmcnt(0) lgkmcnt(0)
             __builtin_amdgcn_s_barrier();
             __builtin_amdgcn_sched_barrier(0);
             // past the last plain slice the loads re-fetch it into the buffer nobody reads any more
-            block(IC<1>{}, cur ^ 1, IC<0>{}, IC<0>{}, min(kt + 2, nfull - 1), cur, IC<0>{}, IC<N3>{}, IC<0>{}, 0);
+            block(IC<1>{}, cur ^ 1, IC<0>{}, IC<0>{}, min(kt + 2, nfull - 1), cur, IC<0>{}, IC<N3>{});
         }
     };
     // a slice whose operands are complete in buffer `buf`, fragment set 0 not yet read
@@ -354,9 +340,6 @@ __global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
             for (int q = 0; q < 16; ++q) mfma1(kk & 1, q);
         }
     };
-    static_assert(PF_PER == 2, "the closing wait of a prefetching slice is written for two touches");
-    const bool pf_on = (p.dbg & 1) && !CE && (p.loss_kind == AGZO_LOSS_MSE) && nd == nfull && nfull >= PF_SLICES + 2 &&
-                       (PF_SLICES * PF_PER * NT >= BT * lines_per_row);
     // the plain slices 0 .. nfull-1 through the pipeline above
     auto run_plain = [&](bool preload) __attribute__((always_inline)) {
         if (nfull == 0) return;
@@ -373,10 +356,8 @@ __global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
         if (nfull > 1) {
 #pragma unroll
             for (int q = 0; q < 8; ++q) frag1(0, 0, 0, q);
-            const int split = pf_on ? nfull - 1 - PF_SLICES : nfull - 1;
-            steady(0, split, IC<0>{}, 0);
-            if (pf_on) steady(split, nfull - 1, IC<1>{}, 0);
-            __builtin_amdgcn_s_waitcnt(0x0F70);          // the re-fetches and touches
+            steady(0, nfull - 1);
+            __builtin_amdgcn_s_waitcnt(0x0F70);          // the re-fetches
             // last plain slice: sub-step 0 is already in fragment set 0
             if (preload) tload_first();
             const int cur = (nfull - 1) & 1;
@@ -515,7 +496,7 @@ __global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
 #pragma clang loop unroll(full)
                 for (int q = 0; q < 4; ++q) {
                     float tv[4] = {0.f, 0.f, 0.f, 0.f};
-                    if (!resid && !(p.dbg & 2)) {
+                    if (!resid) {
                         if (f32) {
                             const uint4 t = traw[j & 1][i][q];
                             tv[0] = __uint_as_float(t.x); tv[1] = __uint_as_float(t.y);
@@ -613,9 +594,7 @@ __global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
     };
     // the first target values are requested ahead of the last multiply before the evaluation that reads them
     const int last0 = ((SHARED && next > 0) ? nd : total) - 1;
-    const uint64_t dbg_t0 = wall_clock64();
     run_plain(last0 == nfull - 1);
-    const uint64_t dbg_t1 = wall_clock64();
     if (SHARED && next > 0) {
         // one copy of the fill / multiply / evaluate code, walked three times: Y0, Y+ (extension with +eps), Y- (-2 eps)
         for (int ph = 0; ph < 3; ++ph) {
@@ -626,11 +605,7 @@ __global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
         }
     } else {
         run_manual(nfull, total, last0);
-        const uint64_t dbg_t2 = wall_clock64();
         evaluate(0);
-        if ((p.dbg & 8) && tid == 0 && (blockIdx.x == 300 || blockIdx.x == 900))
-            printf("wg %d: plain %llu manual %llu evaluate %llu (10 ns ticks)\n", (int)blockIdx.x, (unsigned long long)(dbg_t1 - dbg_t0),
-                   (unsigned long long)(dbg_t2 - dbg_t1), (unsigned long long)(wall_clock64() - dbg_t2));
     }
 }
 
@@ -638,7 +613,7 @@ __global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
 template <int WA, int WB, bool SHARED, int EPI>
 static hipError_t launch_variant(const GemmParams& p, hipStream_t st) {
     static bool attr_set = false;
-    const int smem = 4 * TILE_BYTES + 256 * WA * WB + 64 * WA * WB * (int)sizeof(double);
+    const int smem = 4 * TILE_BYTES + 64 * WA * WB * (int)sizeof(double);
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_bf16_kernel<WA, WB, SHARED, EPI>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, smem);
@@ -662,10 +637,9 @@ hipError_t launch_gemm_bf16(const GemmBf16Args& a, hipStream_t st) {
     p.ldt = a.loss.ldt; p.partials = a.loss.partials;
     p.tiles_m = (int)((a.M + BT - 1) / BT);
     p.tiles_n = (int)((a.N + BT - 1) / BT);
-    p.group_m = 8;
-    if (const char* e = getenv("AGZO_GROUP_M")) p.group_m = atoi(e);
-    p.dbg = 0;
-    if (const char* e = getenv("AGZO_DBG")) p.dbg = atoi(e);
+    // a band of group_m token tiles per XCD run stays hot while the output tiles sweep past; a deep d_in makes the
+    // band too large for the last-level cache, so it is halved there (measured on the 12288-wide down projection)
+    p.group_m = (a.K >= 8192) ? 4 : 8;
     bool vec = true;
     if (a.Y) vec = vec && (a.ldy % 8 == 0) && ((reinterpret_cast<uintptr_t>(a.Y) & 15) == 0);
     if (a.loss.kind == AGZO_LOSS_MSE)

@@ -117,6 +117,8 @@ CASES = [
     ("bf16", 600, 1024, 520, 16, "rmsnorm", 2e-5),
     ("bf16", 257, 72, 40, 1, "lowrank", 2e-5),
     ("bf16", 515, 136, 300, 24, "powerlaw", 2e-5),
+    ("bf16", 700, 320, 264, 40, "powerlaw", 2e-5),      # three 16-column blocks in every rank-r kernel
+    ("bf16", 450, 192, 520, 64, "rmsnorm", 2e-5),       # the largest rank
 ]
 
 
@@ -289,6 +291,33 @@ def test_naive_inplace_comparator_has_its_own_oracle(ctx):
         assert abs(got[1] - o["Lp"]) < 1e-4 * o["Lp"]
         assert abs(got[2] - o["Lm"]) < 1e-4 * o["Lm"]
         assert rel(host(Wd), o["W_new"]) < tolW
+
+
+@pytest.mark.parametrize("target_dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("flags", [0, binding.SHARED_FORWARD])
+def test_tile_aligned_shapes_take_the_specialised_loss_epilogues(ctx, target_dtype, flags):
+    """Tokens and outputs multiples of the 256 x 256 tile: the squared-error kernels without bounds checks,
+    against an fp32 and a bf16 target."""
+    n, d_in, d_out, r = 512, 320, 768, 16
+    W, X, T, Wd, Xd, Td = problem(61, n, d_in, d_out, "powerlaw", "bf16")
+    if target_dtype == "bf16":
+        T = synth.to_bf16_values(T)
+        Td = dev(T, "bf16")
+    L = binding.make_layer(Wd, Xd, r)
+    sc = torch.zeros(1, dtype=torch.float64, device="cuda")
+    ctx.layer_forward_sketch(L, Wd, Xd, None, binding.SKETCH_NONE, None, 1, None, binding.make_loss(Td), sc)
+    L0 = oagzo.mse_loss(oagzo.forward(X.astype(np.float64), W.astype(np.float64)), T)
+    assert abs(sc.item() - L0) < 1e-5 * L0
+    out = torch.zeros(4, dtype=torch.float64, device="cuda")
+    ctx.step(L, Wd, Xd, binding.make_loss(Td), 2, EPS, LR, 17, flags, out)
+    ctx.check()
+    o = oagzo.agzo_step(W, X, T, r, 2, EPS, LR, 17, storage="bf16")
+    got = out.cpu().numpy()
+    assert abs(got[0] - o["L0"]) < 1e-5 * o["L0"]
+    assert abs(got[1] - o["Lp"]) < 1e-5 * o["Lp"]
+    assert abs(got[2] - o["Lm"]) < 1e-5 * o["Lm"]
+    assert abs(got[3] - o["g"]) < 2e-2 * abs(o["g"]) + 1e-9, (got[3], o["g"])
+    assert rel(host(Wd), o["W_new"]) < 3e-3
 
 
 def test_step_is_deterministic(ctx):
