@@ -5,8 +5,8 @@
 //
 // Three launches per QR, coherence between them by kernel boundaries only (no device-scope fences):
 //   1. gram        : Gram partials of Y per 128-row block (v_mfma_f64_16x16x4_f64)
-//   2. apply_gram  : every block sums the partials in block order and one of its waves factors the
-//                    r x r matrix in registers (lane = column, rows broadcast with v_readlane) -> R1;
+//   2. apply_gram  : every block sums the partials in block order and factors the r x r matrix in LDS
+//                    (right-looking, the whole workgroup on the trailing update) -> R1;
 //                    Q1 = Y R1^-1 by forward substitution, one thread per row (fp64, stored), then
 //                    the Gram partials of Q1
 //   3. apply_final : the same reduction and factorisation -> R2; Q = Q1 R2^-1 (fp32), optionally
@@ -32,52 +32,36 @@ size_t qr_workspace_bytes(int64_t d, int r) {
     return (size_t)d * r * sizeof(double) + (size_t)2 * qr_blocks(d) * rp * rp * sizeof(double);
 }
 
-__device__ __forceinline__ double readlane_f64(double v, int lane) {
-    const uint64_t u = __double_as_longlong(v);
-    const uint32_t lo = __builtin_amdgcn_readlane((int)(uint32_t)u, lane);
-    const uint32_t hi = __builtin_amdgcn_readlane((int)(uint32_t)(u >> 32), lane);
-    return __longlong_as_double(((uint64_t)hi << 32) | lo);
-}
-
-// One wave factors G (RP x RP, row-major fp64 in LDS, leading dimension RP) = R^T R in registers:
-// lane c owns column c.  On exit G's upper triangle holds R, its diagonal 1 / R[j][j] (what the
-// substitution needs).  Padding columns (>= r) carry a unit diagonal.  Returns nonzero on a bad pivot.
-template <int RP>
-__device__ int chol_wave(double* G, int r) {
-    const int lane = threadIdx.x & 63;
-    const int c = lane < RP ? lane : RP - 1;
-    double col[RP];
-#pragma unroll
-    for (int a = 0; a < RP; ++a) col[a] = G[a * RP + c];
+// The workgroup factors G (rp x rp, row-major fp64 in LDS) = R^T R in place, right-looking, two barriers per column:
+// on exit G's upper triangle holds R and its diagonal 1 / R[j][j] (what the substitution needs).  Padding columns
+// (>= r) carry a unit diagonal.  Returns nonzero on a non-positive pivot (the same value in every thread).
+__device__ int chol_block(double* G, int r, int rp) {
+    __shared__ double dinv[kMaxRank];
+    const int tid = threadIdx.x, nt = blockDim.x;
     int bad = 0;
-#pragma unroll
-    for (int j = 0; j < RP; ++j) {
-        double piv = readlane_f64(col[j], j);
+    for (int j = 0; j < rp; ++j) {
+        __syncthreads();                                  // the trailing update of the previous column is complete
+        double piv = G[j * rp + j];
         if (j >= r) piv = 1.0;
         if (!(piv > 0.0)) { bad = 1; piv = 1.0; }
         // 1/sqrt(piv): hardware estimate refined by two Newton steps (full fp64 accuracy, no divide)
         double inv = __builtin_amdgcn_rsq(piv);
         inv = inv * fma(-0.5 * piv * inv, inv, 1.5);
         inv = inv * fma(-0.5 * piv * inv, inv, 1.5);
-        const double rowj = col[j] * inv;                 // lane c: R[j][c]
-        col[j] = (lane == j) ? inv : rowj;                // keep 1/R[j][j] on the diagonal
-#pragma unroll
-        for (int a = j + 1; a < RP; ++a) col[a] = fma(-readlane_f64(rowj, a), rowj, col[a]);
+        if (tid == j) dinv[j] = inv;
+        if (tid > j && tid < rp) G[j * rp + tid] *= inv;  // row j of R (the pivot itself stays in place until the end)
+        __syncthreads();
+        // trailing update of the upper triangle: G[a][c] -= R[j][a] R[j][c], j < a <= c
+        const int m = rp - j - 1;
+        for (int e = tid; e < m * m; e += nt) {
+            const int a = j + 1 + e / m, c = j + 1 + e % m;
+            if (c >= a) G[a * rp + c] = fma(-G[j * rp + a], G[j * rp + c], G[a * rp + c]);
+        }
     }
-    if (lane < RP) {
-#pragma unroll
-        for (int a = 0; a < RP; ++a) G[a * RP + lane] = col[a];
-    }
+    __syncthreads();
+    if (tid < rp) G[tid * rp + tid] = dinv[tid];
+    __syncthreads();
     return bad;
-}
-
-__device__ int chol_dispatch(double* G, int r, int rp) {
-    switch (rp) {
-        case 16: return chol_wave<16>(G, r);
-        case 32: return chol_wave<32>(G, r);
-        case 48: return chol_wave<48>(G, r);
-        default: return chol_wave<64>(G, r);
-    }
 }
 
 // Gram partial of the block's rows (fp64 in LDS: Ys[row][ld], zero padded to a multiple of 4 rows and rp
@@ -102,31 +86,24 @@ __device__ void gram_partial(const double* Ys, int ld, int rows_pad, int rp, dou
     }
 }
 
-// Every block: Gs <- sum over blocks of partial (block order, sixteen loads in flight), then wave 0
-// factors it in place (upper factor, reciprocal diagonal).  Block 0 reports a bad pivot.
+// Every block: Gs <- sum over blocks of partial (block order, up to 32 loads in flight), then the workgroup factors
+// it in place (upper factor, reciprocal diagonal).  Block 0 reports a bad pivot.
 __device__ void reduce_and_factor(const double* partial, int nblk, double* Gs, int r, int rp, int* flag) {
     const int tid = threadIdx.x;
     for (int e = tid; e < rp * rp; e += blockDim.x) {
-        double a16[16];
+        double sum = 0.0;
+        for (int b0 = 0; b0 < nblk; b0 += 32) {
+            double v[32];
 #pragma unroll
-        for (int u = 0; u < 16; ++u) a16[u] = 0.0;
-        for (int b0 = 0; b0 < nblk; b0 += 16) {
+            for (int u = 0; u < 32; ++u) v[u] = (b0 + u < nblk) ? partial[(int64_t)(b0 + u) * rp * rp + e] : 0.0;
 #pragma unroll
-            for (int u = 0; u < 16; ++u)
-                if (b0 + u < nblk) a16[u] += partial[(int64_t)(b0 + u) * rp * rp + e];
+            for (int u = 0; u < 32; ++u) sum += v[u];
         }
-#pragma unroll
-        for (int s = 8; s > 0; s >>= 1)
-#pragma unroll
-            for (int u = 0; u < s; ++u) a16[u] += a16[u + s];
-        Gs[e] = a16[0];
+        Gs[e] = sum;
     }
     __syncthreads();
-    if (tid < 64) {
-        const int bad = chol_dispatch(Gs, r, rp);
-        if (bad && tid == 0 && blockIdx.x == 0) *flag = 1;
-    }
-    __syncthreads();
+    const int bad = chol_block(Gs, r, rp);
+    if (bad && tid == 0 && blockIdx.x == 0) *flag = 1;
 }
 
 // row <- row R^-1 for upper-triangular R held in LDS with reciprocal diagonal (forward substitution);
@@ -168,38 +145,35 @@ __global__ __launch_bounds__(256) void qr_gram_kernel(const float* __restrict__ 
     const int rows = (int)min((int64_t)QR_ROWS, d - i0);
     const int rows_pad = (rows + 3) & ~3;
     if (splits != nullptr) {
-        // sum of the partial sketches: 8 elements per thread and 4 splits per round, 32 loads in flight
-        for (int base = 0; base < rows_pad * rp; base += 256 * 8) {
-            double acc[8];
+        // sum of the partial sketches: a block's rows are one contiguous run of rows * rp floats in every split, so the
+        // loads are plain 16-byte vectors, all splits of a vector in flight together (fp64 sum in split order)
+        const int nvec = rows * rp / 4;
+        const float* base = splits + i0 * rp;
+        for (int v = tid; v < rows_pad * rp / 4; v += 256) {
+            double acc[4] = {0.0, 0.0, 0.0, 0.0};
+            if (v < nvec) {
+                for (int sp0 = 0; sp0 < nsplit; sp0 += 16) {
+                    float4 x[16];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) acc[u] = 0.0;
-            for (int sp0 = 0; sp0 < nsplit; sp0 += 4) {
-                float v[4][8];
+                    for (int u = 0; u < 16; ++u)
+                        x[u] = (sp0 + u < nsplit) ? reinterpret_cast<const float4*>(base + (int64_t)(sp0 + u) * d * rp)[v]
+                                                  : make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
-                for (int s4 = 0; s4 < 4; ++s4)
-#pragma unroll
-                    for (int u = 0; u < 8; ++u) {
-                        const int e = base + u * 256 + tid;
-                        const int i = e / rp, k = e % rp;
-                        const bool ok = (e < rows_pad * rp) && (i < rows) && (sp0 + s4 < nsplit);
-                        v[s4][u] = ok ? splits[((int64_t)(sp0 + s4) * d + i0 + i) * rp + k] : 0.f;
+                    for (int u = 0; u < 16; ++u) {
+                        acc[0] += (double)x[u].x; acc[1] += (double)x[u].y;
+                        acc[2] += (double)x[u].z; acc[3] += (double)x[u].w;
                     }
-#pragma unroll
-                for (int s4 = 0; s4 < 4; ++s4)
-#pragma unroll
-                    for (int u = 0; u < 8; ++u) acc[u] += (double)v[s4][u];
-            }
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int e = base + u * 256 + tid;
-                if (e >= rows_pad * rp) continue;
-                const int i = e / rp, k = e % rp;
-                float f = 0.f;
-                if (i < rows && k < r) {
-                    f = (float)acc[u];
-                    S_out[(i0 + i) * r + k] = f;
                 }
-                Ys[i * ld + k] = (double)f;
+            }
+            const int i = (v * 4) / rp, k0 = (v * 4) % rp;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                float f = 0.f;
+                if (v < nvec && k0 + c < r) {
+                    f = (float)acc[c];
+                    S_out[(i0 + i) * r + k0 + c] = f;
+                }
+                Ys[i * ld + k0 + c] = (double)f;
             }
         }
     } else {
