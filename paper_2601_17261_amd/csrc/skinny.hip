@@ -88,22 +88,49 @@ __global__ __launch_bounds__(256) void xq_bf16_kernel(const bf16_t* __restrict__
             if (i < ng)
                 __builtin_amdgcn_global_load_lds((gptr_t)(src[i] + (int64_t)kt * XQ_BK), (lptr_t)(base + i * 4096), 16, 0, 0);
     };
-    auto multiply = [&](int slot) __attribute__((always_inline)) {
+    // Fragment reads go through inline assembly: for a plain LDS load the compiler, which cannot tell the ring's slots
+    // apart, first waits for every direct load in flight (vmcnt(0)) and so collapses the ring to one slice.  The
+    // waits that are needed are the explicit ones around the barrier and the lgkmcnt below.
+    auto lds_read16 = [&](const char* ptr) __attribute__((always_inline)) {
+        typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+        u32x4 v;
+        const uint32_t addr = (uint32_t)(uintptr_t)(lptr_t)ptr;
+        asm volatile("ds_read_b128 %0, %1" : "=v"(v) : "v"(addr));
+        return v;
+    };
+    auto multiply = [&](int slot, bool dma) __attribute__((always_inline)) {
         const char* xs = xq_smem + slot * SLOT;
         const char* qs = xs + XQ_TOK * 128;
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub) {
-            Frag a;
-            a.u = *reinterpret_cast<const uint4*>(xs + xq_lds_off(wave * 16 + lm, sub * 4 + lg));
+            typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+            u32x4 a, b[NB][3];
+            a = lds_read16(xs + xq_lds_off(wave * 16 + lm, sub * 4 + lg));
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-                for (int pl = 0; pl < 3; ++pl) {
-                    Frag b;
-                    b.u = *reinterpret_cast<const uint4*>(qs + xq_lds_off(pl * RP + nb * 16 + lm, sub * 4 + lg));
-                    acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, b.v, acc[nb], 0, 0, 0);
-                }
+                for (int pl = 0; pl < 3; ++pl) b[nb][pl] = lds_read16(qs + xq_lds_off(pl * RP + nb * 16 + lm, sub * 4 + lg));
+            // the wait names every loaded register as an in/out operand, so nothing that uses them can move above it
+            if constexpr (NB == 1)
+                asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(a), "+v"(b[0][0]), "+v"(b[0][1]), "+v"(b[0][2]) :: "memory");
+            else if constexpr (NB == 2)
+                asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(a), "+v"(b[0][0]), "+v"(b[0][1]), "+v"(b[0][2]), "+v"(b[1][0]),
+                             "+v"(b[1][1]), "+v"(b[1][2]) :: "memory");
+            else if constexpr (NB == 3)
+                asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(a), "+v"(b[0][0]), "+v"(b[0][1]), "+v"(b[0][2]), "+v"(b[1][0]),
+                             "+v"(b[1][1]), "+v"(b[1][2]), "+v"(b[2][0]), "+v"(b[2][1]), "+v"(b[2][2]) :: "memory");
+            else
+                asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(a), "+v"(b[0][0]), "+v"(b[0][1]), "+v"(b[0][2]), "+v"(b[1][0]),
+                             "+v"(b[1][1]), "+v"(b[1][2]), "+v"(b[2][0]), "+v"(b[2][1]), "+v"(b[2][2]), "+v"(b[3][0]),
+                             "+v"(b[3][1]), "+v"(b[3][2]) :: "memory");
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                for (int pl = 0; pl < 3; ++pl)
+                    acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b[nb][pl]),
+                                                                      acc[nb], 0, 0, 0);
         }
+        (void)dma;
     };
     // ring: slices kt .. kt + STAGES - 2 in flight while slice kt is multiplied
 #pragma unroll
@@ -114,9 +141,14 @@ __global__ __launch_bounds__(256) void xq_bf16_kernel(const bf16_t* __restrict__
         // this wave's loads of slice kt have landed when at most (younger slices in flight) * ng are outstanding
         const int younger = min(STAGES - 2, nfull - 1 - kt);
         wait_vmcnt_dyn(younger * ng);
-        __syncthreads();                                   // everybody's loads of slice kt; slot of slice kt-1 is free
+        // everybody's loads of slice kt have landed; the slot of slice kt-1 is free.  A bare barrier: __syncthreads()
+        // would first wait for every load in flight and collapse the ring to one slice.
+        __builtin_amdgcn_s_waitcnt(0xC07F);                // lgkmcnt(0)
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
         if (kt + STAGES - 1 < nfull) issue(kt + STAGES - 1, (slot + STAGES - 1) % STAGES);
-        multiply(slot);
+        multiply(slot, true);
         slot = (slot + 1 == STAGES) ? 0 : slot + 1;
     }
     if (tail) {
@@ -135,7 +167,7 @@ __global__ __launch_bounds__(256) void xq_bf16_kernel(const bf16_t* __restrict__
             *reinterpret_cast<uint4*>(base + xq_lds_off(row, c)) = v;
         }
         __syncthreads();
-        multiply(0);
+        multiply(0, false);
     }
     // D layout: row (token) = 4*(lane/16) + e, col (k) = lane%16
 #pragma unroll
