@@ -216,7 +216,7 @@ def main():
         "roofline": {"bound": "mfma", "kernel": "gemm_bf16_kernel", "achieved": gemm_tflops, "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": gemm_tflops / PEAK_BF16_TFLOPS, "traffic": traffic,
                      "launches": n_gemm, "avg_ms": gemm_avg_ms},
-        "roofline_update": {"bound": "hbm", "kernel": "update_kernel", "achieved": upd_gbs, "peak": PEAK_HBM_GBS,
+        "roofline_update": {"bound": "hbm", "kernel": "update_prep_kernel + update_mfma_kernel", "achieved": upd_gbs, "peak": PEAK_HBM_GBS,
                             "unit": "GB/s", "frac": upd_gbs / PEAK_HBM_GBS, "launches": n_upd, "avg_ms": upd_avg_ms},
         "stage_ms_per_step": {"gemm": ms_gemm / args.steps, "update": ms_upd / args.steps, "xq": ms_xq / args.steps,
                               "xtt": ms_xtt / args.steps, "qr": ms_qr / args.steps},
@@ -241,6 +241,33 @@ def main():
                                  "gemm_launches": n_g1, "gemm_avg_ms": ms_g1 / max(n_g1, 1),
                                  "gemm_tflops": flops1 / (ms_g1 / max(n_g1, 1) * 1e-3) / 1e12,
                                  "note": "f0, f+, f- from one pass over X and W per projection (single-layer problems only)"}
+        # the forward GEMM alone (no loss, no store): what the multiply loop reaches without the target traffic
+        for li, (L, W, X, loss) in enumerate(descs):
+            ctx.layer_forward_sketch(L, W, X, None, binding.SKETCH_NONE, None, 1, None, None, None)
+        torch.cuda.synchronize()
+        ctx.profile_enable(True)
+        for _ in range(3):
+            for li, (L, W, X, loss) in enumerate(descs):
+                ctx.layer_forward_sketch(L, W, X, None, binding.SKETCH_NONE, None, 1, None, None, None)
+        torch.cuda.synchronize()
+        n_g2, ms_g2 = ctx.profile_read(binding.PROF_GEMM)
+        ctx.profile_enable(False)
+        res["forward_only"] = {"gemm_launches": n_g2, "gemm_avg_ms": ms_g2 / max(n_g2, 1),
+                               "gemm_tflops": fwd_flops / len(shapes) / (ms_g2 / max(n_g2, 1) * 1e-3) / 1e12,
+                               "note": "same kernel without the fused loss (no target read)"}
+        # the paper's literal schedule as a comparator: perturb W in place, plain forward, undo (Alg. 2)
+        nsteps = max(2, args.steps // 2)
+        one_step(30_000, binding.NAIVE_INPLACE)
+        torch.cuda.synchronize()
+        t2 = time.perf_counter()
+        for s in range(nsteps):
+            one_step(30_001 + s, binding.NAIVE_INPLACE)
+        torch.cuda.synchronize()
+        dt2 = time.perf_counter() - t2
+        ctx.check()
+        res["naive_inplace"] = {"value": nsteps / dt2, "unit": "steps/s", "ms_per_step": 1e3 * dt2 / nsteps, "steps": nsteps,
+                                "note": "perturb-in-place / undo comparator (4 extra sweeps of W per step; in bf16 a different "
+                                        "computation: the perturbation is rounded into the weights)"}
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(N, r, K, eps, lr, fwd_flops)
     print(json.dumps(res))

@@ -78,7 +78,7 @@ inline int64_t round32(int64_t n) { return (n + 31) / 32 * 32; }
 
 // carve-out of the ctx workspace for one layer; everything a step can need at the same time
 struct Plan {
-    size_t off_S, off_Q, off_B, off_pack, off_T, off_TpackT, off_xtt, off_qr, off_part, off_Ybuf, off_ce_ms, off_ce_tl, off_upd, total;
+    size_t off_S, off_Q, off_B, off_pack, off_T, off_TpackT, off_xtt, off_qr, off_part, off_Ybuf, off_ce_ms, off_ce_tl, off_upd, off_ext, total;
     int rp, nsplit;
     int64_t m_pad;
     int n_part;
@@ -111,6 +111,7 @@ Plan make_plan(const agzo_layer& L, bool need_ybuf, bool ce = false) {
     p.off_ce_ms = take((ce && bf) ? (size_t)3 * gemm_bf16_ce_chunks(L.d_out) * L.n_tokens * 8 : 0);
     p.off_ce_tl = take((ce && bf) ? (size_t)3 * L.n_tokens * 4 : 0);
     p.off_upd = take(update_workspace_bytes(L.dtype, L.d_out, L.d_in, L.r));
+    p.off_ext = take(bf ? gemm_bf16_ext_bytes(L.n_tokens, L.d_out, L.r) : 0);
     p.off_Ybuf = take(need_ybuf ? (size_t)L.n_tokens * L.d_out * 4 : 0);
     p.total = o;
     return p;
@@ -282,6 +283,7 @@ int op_forward(agzo_ctx* ctx, const agzo_layer& L, const Plan& p, const void* W,
         a.P = P; a.r = L.r; a.eps_signed = eps_signed; a.seed = seed;
         a.loss = la;
         a.shared = shared;
+        a.ext_ws = (P && !shared) ? ctx->ws + p.off_ext : nullptr;
         {
             ProfScope ps(ctx, AGZO_PROF_GEMM);
             HIPCHK(launch_gemm_bf16(a, st));

@@ -116,8 +116,12 @@ struct GemmBf16Args {
     // shared = true: one pass evaluates the loss at W, W + eps Z and W - eps Z (eps = eps_signed > 0);
     // the loss partials are then [3][n_workgroups] and Y must be NULL
     bool shared = false;
+    // gemm_bf16_ext_bytes() bytes of device scratch for the rank-r extension operands of a perturbed forward
+    // (NULL: every tile builds them itself)
+    void* ext_ws = nullptr;
 };
 int gemm_bf16_num_workgroups(int64_t M, int64_t N);
+size_t gemm_bf16_ext_bytes(int64_t M, int64_t N, int r);
 hipError_t launch_gemm_bf16(const GemmBf16Args& a, hipStream_t st);
 
 // gemm_f32.hip : generic strided fp32 GEMM with fp64 accumulation, and the fp32 epilogue

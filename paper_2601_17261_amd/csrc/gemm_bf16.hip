@@ -50,6 +50,9 @@ struct GemmParams {
     int64_t M, N, K;            // tokens, outputs, d_in
     void* Y; int y_dtype; int64_t ldy;
     const float* P; int r; int rp;
+    // rank-r extension operands prepared ahead of the launch (NULL: the workgroups build them per tile):
+    // Xext [M][ext_ld] = [Ph | Ph | Pl | 0], Wext [N][ext_ld] = [Gh | Gl | Gh | 0] with the signed eps folded into G
+    const bf16_t* Xext; const bf16_t* Wext; int ext_ld;
     float eps_signed; uint32_t s_lo, s_hi;
     int loss_kind; int target_dtype; const void* target; int64_t ldt; double* partials;
     int tiles_m, tiles_n;
@@ -118,17 +121,38 @@ __global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
     constexpr int GP = 8;                       // 8-row groups per wave per operand
     const bf16_t* xbase = p.X + m0 * p.ldx;
     const bf16_t* wbase = p.W + n0 * p.ldw;
-    const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(xbase), 0, -1, 0x00020000);
-    const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(wbase), 0, -1, 0x00020000);
-    int xo[GP], wo[GP];                         // byte offsets from the tile's first row
+    // Buffer descriptors with the tile's own byte range: rows past the end of the matrix are out of range for the
+    // descriptor, so their loads fetch nothing (zeros) and no address has to be clamped; such rows only feed outputs
+    // that the epilogue masks.  That makes the offset of row group t a scalar multiple of t: one vector offset per
+    // operand instead of one per group.
+    auto tile_rsrc = [&](const bf16_t* base, int64_t rows_left, int64_t ld, int64_t width) {
+        // (a descriptor with a real range costs about 6 % of the load rate on this chip, so only the tiles that
+        // hang over the edge get one)
+        int64_t bytes = ((rows_left - 1) * ld + width) * 2;
+        if (bytes > 0xFFFFFFFFll || rows_left >= BT) bytes = 0xFFFFFFFFll;
+        return __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(base), 0, (int)(uint32_t)bytes, 0x00020000);
+    };
+    const __amdgpu_buffer_rsrc_t rx = tile_rsrc(xbase, p.M - m0, p.ldx, p.K);
+    const __amdgpu_buffer_rsrc_t rw = tile_rsrc(wbase, p.N - n0, p.ldw, p.K);
+    const __amdgpu_buffer_rsrc_t rx2 = tile_rsrc(p.Xext ? p.Xext + m0 * p.ext_ld : xbase, p.M - m0, p.Xext ? p.ext_ld : p.ldx, p.Xext ? p.ext_ld : p.K);
+    const __amdgpu_buffer_rsrc_t rw2 = tile_rsrc(p.Wext ? p.Wext + n0 * p.ext_ld : wbase, p.N - n0, p.Wext ? p.ext_ld : p.ldw, p.Wext ? p.ext_ld : p.K);
+    const int row0 = 8 * wave + (lane >> 3);                 // row of group t = row0 + 32 t (X), 32 t + w_perm(row0) (W)
+    const int chunk0 = (lane & 7) ^ ((row0 >> 1) & 7);       // (row >> 1) & 7 does not depend on t
+    const int vx = (int)(((int64_t)row0 * p.ldx + chunk0 * 8) * 2), vw = (int)(((int64_t)w_perm(row0) * p.ldw + chunk0 * 8) * 2);
+    const int vx2 = (row0 * p.ext_ld + chunk0 * 8) * 2, vw2 = (w_perm(row0) * p.ext_ld + chunk0 * 8) * 2;
+    const int gsx = (int)(64 * p.ldx), gsw = (int)(64 * p.ldw), gs2 = 64 * p.ext_ld;   // bytes between row groups
+    // the shared-forward variant addresses per lane (see dma1) and keeps clamped per-group offsets
+    int xo[SHARED ? GP : 1], wo[SHARED ? GP : 1];
+    if constexpr (SHARED) {
 #pragma unroll
-    for (int t = 0; t < GP; ++t) {
-        const int row = 8 * (wave + 4 * t) + (lane >> 3);
-        const int c = (lane & 7) ^ ((row >> 1) & 7);
-        const int64_t gm = min((int64_t)row, p.M - 1 - m0);
-        const int64_t gn = min((int64_t)((row & ~31) + w_perm(row & 31)), p.N - 1 - n0);
-        xo[t] = (int)((gm * p.ldx + c * 8) * 2);
-        wo[t] = (int)((gn * p.ldw + c * 8) * 2);
+        for (int t = 0; t < GP; ++t) {
+            const int row = 8 * (wave + 4 * t) + (lane >> 3);
+            const int c = (lane & 7) ^ ((row >> 1) & 7);
+            const int64_t gm = min((int64_t)row, p.M - 1 - m0);
+            const int64_t gn = min((int64_t)((row & ~31) + w_perm(row & 31)), p.N - 1 - n0);
+            xo[t] = (int)((gm * p.ldx + c * 8) * 2);
+            wo[t] = (int)((gn * p.ldw + c * 8) * 2);
+        }
     }
     const int nfull = (int)(p.K / BK);
     const int ntail = (p.K % BK) ? 1 : 0;
@@ -136,6 +160,9 @@ __global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
     const int kext = 3 * rp;                    // width of the extended operands [Ph|Ph|Pl] x [Gh|Gl|Gh]
     const int next = (p.P != nullptr) ? (kext + BK - 1) / BK : 0;
     const int nd = nfull + ntail;               // slices of d_in
+    // extension slices that come as ready-made operands ride the load pipeline right behind the plain slices
+    const bool ext_dma = !SHARED && p.Xext != nullptr;
+    const int npipe = nfull + (ext_dma ? next : 0);
     // shared mode: the extension runs twice, with +eps (accumulators become Y+) and then with -2 eps (Y-)
     const int total = nd + (SHARED ? 2 * next : next);
 
@@ -276,8 +303,23 @@ __global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
         const int i = idx >> 2, j = idx & 3;
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[s][i], b[s][j], acc[i][j], 0, 0, 0);
     };
-    // direct load q (0..15) of slice kt into buffer buf: even q = X row group q/2, odd q = W row group q/2
-    auto dma1 = [&](int kt, int buf, int q) __attribute__((always_inline)) {
+    // Where a pipelined slice comes from: a plain 64-wide slice of X and W, or a slice of the ready-made extension
+    // operands.  Chosen once per slice with scalar selects into one of two sets of variables (set 0: the slice loaded
+    // by an iteration's first blocks, set 1: the one after it), so that the load sites themselves stay free of
+    // branches, which would cut the fixed-order blocks below into pieces and put the accumulators through joins.
+    __amdgpu_buffer_rsrc_t src_rsx[2] = {rx, rx}, src_rsw[2] = {rw, rw};
+    int src_vx[2] = {vx, vx}, src_vw[2] = {vw, vw}, src_so[2] = {0, 0}, src_gx[2] = {gsx, gsx}, src_gw[2] = {gsw, gsw};
+    auto select_slice = [&](auto SET, int kt) __attribute__((always_inline)) {
+        constexpr int set = decltype(SET)::value;
+        const bool e = kt >= nfull;
+        src_rsx[set] = e ? rx2 : rx;   src_rsw[set] = e ? rw2 : rw;
+        src_vx[set] = e ? vx2 : vx;    src_vw[set] = e ? vw2 : vw;
+        src_so[set] = (e ? kt - nfull : kt) * (BK * 2);
+        src_gx[set] = e ? gs2 : gsx;   src_gw[set] = e ? gs2 : gsw;
+    };
+    // direct load q (0..15) of the slice selected into SET, into buffer buf: even q = X row group q/2, odd q = W row group
+    auto dma1 = [&](auto SET, int kt, int buf, int q) __attribute__((always_inline)) {
+        constexpr int set = decltype(SET)::value;
         const int t = q >> 1;
         char* dst = smem + buf * (2 * TILE_BYTES) + wave * 1024 + t * 4096 + ((q & 1) ? TILE_BYTES : 0);
         if constexpr (SHARED) {
@@ -286,14 +328,14 @@ __global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
             const char* src = reinterpret_cast<const char*>((q & 1) ? wbase : xbase) + ((q & 1) ? wo[t] : xo[t]) + kt * (BK * 2);
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src, (lptr_t)dst, 16, 0, 0);
         } else {
-            if (q & 1) __builtin_amdgcn_raw_ptr_buffer_load_lds(rw, (lptr_t)dst, 16, wo[t], kt * (BK * 2), 0, 0);
-            else __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (lptr_t)dst, 16, xo[t], kt * (BK * 2), 0, 0);
+            if (q & 1) __builtin_amdgcn_raw_ptr_buffer_load_lds(src_rsw[set], (lptr_t)dst, 16, src_vw[set] + t * src_gw[set], src_so[set], 0, 0);
+            else __builtin_amdgcn_raw_ptr_buffer_load_lds(src_rsx[set], (lptr_t)dst, 16, src_vx[set] + t * src_gx[set], src_so[set], 0, 0);
         }
     };
     // One block = the 16 MFMAs of sub-step S_CUR in a fixed issue order (a scheduling barrier after every group keeps
     // the compiler from regrouping): even slots carry one fragment read each (for the next block), odd slots carry
     // the direct loads D0..D1-1 of slice lkt, spread evenly.
-    auto block = [&](auto S_CUR, int rbuf, auto RKK, auto RS, int lkt, int lbuf, auto D0, auto D1) __attribute__((always_inline)) {
+    auto block = [&](auto S_CUR, int rbuf, auto RKK, auto RS, auto SET, int lkt, int lbuf, auto D0, auto D1) __attribute__((always_inline)) {
         constexpr int s_cur = decltype(S_CUR)::value, rkk = decltype(RKK)::value, rs = decltype(RS)::value;
         constexpr int d0 = decltype(D0)::value, d1 = decltype(D1)::value, n = d1 - d0;
 #pragma unroll
@@ -301,7 +343,7 @@ __global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
             mfma1(s_cur, q);
             const int o = q >> 1;
             if (!(q & 1)) frag1(rbuf, rkk, rs, o);
-            else if (((o + 1) * n) / 8 > (o * n) / 8) dma1(lkt, lbuf, d0 + (o * n) / 8);
+            else if (((o + 1) * n) / 8 > (o * n) / 8) dma1(SET, lkt, lbuf, d0 + (o * n) / 8);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
@@ -314,16 +356,19 @@ __global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
     auto steady = [&](int kt0, int kt1) __attribute__((always_inline)) {
         for (int kt = kt0; kt < kt1; ++kt) {
             const int cur = kt & 1;
-            block(IC<0>{}, cur, IC<1>{}, IC<1>{}, kt + 1, cur ^ 1, IC<N3>{}, IC<N3 + N0>{});
-            block(IC<1>{}, cur, IC<2>{}, IC<0>{}, kt + 1, cur ^ 1, IC<N3 + N0>{}, IC<16>{});
-            block(IC<0>{}, cur, IC<3>{}, IC<1>{}, 0, 0, IC<0>{}, IC<0>{});
+            select_slice(IC<0>{}, kt + 1);
+            block(IC<0>{}, cur, IC<1>{}, IC<1>{}, IC<0>{}, kt + 1, cur ^ 1, IC<N3>{}, IC<N3 + N0>{});
+            block(IC<1>{}, cur, IC<2>{}, IC<0>{}, IC<0>{}, kt + 1, cur ^ 1, IC<N3 + N0>{}, IC<16>{});
+            block(IC<0>{}, cur, IC<3>{}, IC<1>{}, IC<0>{}, 0, 0, IC<0>{}, IC<0>{});
             // every operand load of the next slice has landed; all waves are done reading the buffer that the next
             // loads overwrite
             __builtin_amdgcn_s_waitcnt(0x0070);              // vmcnt(0) lgkmcnt(0)
             __builtin_amdgcn_s_barrier();
             __builtin_amdgcn_sched_barrier(0);
-            // past the last plain slice the loads re-fetch it into the buffer nobody reads any more
-            block(IC<1>{}, cur ^ 1, IC<0>{}, IC<0>{}, min(kt + 2, nfull - 1), cur, IC<0>{}, IC<N3>{});
+            // past the last pipelined slice the loads re-fetch it into the buffer nobody reads any more
+            const int k2 = min(kt + 2, npipe - 1);
+            select_slice(IC<1>{}, k2);
+            block(IC<1>{}, cur ^ 1, IC<0>{}, IC<0>{}, IC<1>{}, k2, cur, IC<0>{}, IC<N3>{});
         }
     };
     // a slice whose operands are complete in buffer `buf`, fragment set 0 not yet read
@@ -340,27 +385,29 @@ __global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
             for (int q = 0; q < 16; ++q) mfma1(kk & 1, q);
         }
     };
-    // the plain slices 0 .. nfull-1 through the pipeline above
+    // the plain slices 0 .. nfull-1 (and ready-made extension slices) through the pipeline above
     auto run_plain = [&](bool preload) __attribute__((always_inline)) {
-        if (nfull == 0) return;
+        if (npipe == 0) return;
+        select_slice(IC<0>{}, 0);
 #pragma unroll
-        for (int q = 0; q < 16; ++q) dma1(0, 0, q);
-        if (nfull > 1) {
+        for (int q = 0; q < 16; ++q) dma1(IC<0>{}, 0, 0, q);
+        if (npipe > 1) {
+            select_slice(IC<1>{}, 1);
 #pragma unroll
-            for (int q = 0; q < N3; ++q) dma1(1, 1, q);
+            for (int q = 0; q < N3; ++q) dma1(IC<1>{}, 1, 1, q);
             __builtin_amdgcn_s_waitcnt(0x0F76);          // vmcnt(N3): slice 0 has landed
         } else {
             __builtin_amdgcn_s_waitcnt(0x0F70);
         }
         __syncthreads();
-        if (nfull > 1) {
+        if (npipe > 1) {
 #pragma unroll
             for (int q = 0; q < 8; ++q) frag1(0, 0, 0, q);
-            steady(0, nfull - 1);
+            steady(0, npipe - 1);
             __builtin_amdgcn_s_waitcnt(0x0F70);          // the re-fetches
             // last plain slice: sub-step 0 is already in fragment set 0
             if (preload) tload_first();
-            const int cur = (nfull - 1) & 1;
+            const int cur = (npipe - 1) & 1;
 #pragma unroll
             for (int kk = 0; kk < 4; ++kk) {
                 if (kk + 1 < 4) {
@@ -593,9 +640,9 @@ __global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
         }
     };
     // the first target values are requested ahead of the last multiply before the evaluation that reads them
-    const int last0 = ((SHARED && next > 0) ? nd : total) - 1;
-    run_plain(last0 == nfull - 1);
     if (SHARED && next > 0) {
+        const int last0 = nd - 1;
+        run_plain(last0 == nfull - 1);
         // one copy of the fill / multiply / evaluate code, walked three times: Y0, Y+ (extension with +eps), Y- (-2 eps)
         for (int ph = 0; ph < 3; ++ph) {
             const int it0 = (ph == 0) ? nfull : nd + (ph - 1) * next;
@@ -603,12 +650,71 @@ __global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
             run_manual(it0, it1, (ph == 0) ? last0 : -1);
             evaluate(ph);
         }
+    } else if (ext_dma) {
+        // pipelined: plain slices, then the ready-made extension slices; the ragged end of d_in (if any) last
+        run_plain(ntail == 0);
+        run_manual(nfull, nd, nd - 1);
+        evaluate(0);
     } else {
+        const int last0 = total - 1;
+        run_plain(last0 == nfull - 1);
         run_manual(nfull, total, last0);
         evaluate(0);
     }
 }
 
+
+
+// Extension operands for one perturbed forward, written once instead of once per tile: eight columns per thread.
+// Rows 0..M-1 are the X side ([Ph | Ph | Pl | 0], P = X B split hi + lo in bf16), rows M..M+N-1 the W side
+// ([Gh | Gl | Gh | 0], G regenerated from the Philox seed, times the signed eps).
+__global__ __launch_bounds__(256) void gemm_ext_prep_kernel(bf16_t* __restrict__ Xext, bf16_t* __restrict__ Wext, int64_t M,
+                                                            int64_t N, int ext_ld, const float* __restrict__ P, int r, int rp,
+                                                            float coef, uint32_t s_lo, uint32_t s_hi) {
+    const int chunks = ext_ld / 8;
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (M + N) * chunks) return;
+    const int64_t row = idx / chunks;
+    const int col0 = (int)(idx % chunks) * 8;
+    const int seg = col0 / rp, k0 = col0 % rp;
+    uint32_t hi[4] = {0, 0, 0, 0}, lo[4] = {0, 0, 0, 0};
+    if (seg < 3) {
+        float v[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        if (row < M) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                if (k0 + i < r) v[i] = P[row * r + k0 + i];
+        } else {
+            const int64_t j = row - M;
+            if (k0 < r) {
+                const float4 z = philox_normal4(s_lo, s_hi, AGZO_TAG_G, (uint32_t)j, (uint32_t)(k0 >> 2));
+                v[0] = z.x; v[1] = z.y; v[2] = z.z; v[3] = z.w;
+            }
+            if (k0 + 4 < r) {
+                const float4 z = philox_normal4(s_lo, s_hi, AGZO_TAG_G, (uint32_t)j, (uint32_t)((k0 >> 2) + 1));
+                v[4] = z.x; v[5] = z.y; v[6] = z.z; v[7] = z.w;
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) v[i] = (k0 + i < r) ? coef * v[i] : 0.f;
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            hi[i] = pack_bf16x2(v[2 * i], v[2 * i + 1]);
+            lo[i] = pack_bf16x2(v[2 * i] - __uint_as_float(hi[i] << 16), v[2 * i + 1] - __uint_as_float(hi[i] & 0xFFFF0000u));
+        }
+    }
+    // X side: [hi | hi | lo]; W side: [hi | lo | hi]
+    const bool use_lo = (row < M) ? (seg == 2) : (seg == 1);
+    const uint4 out = use_lo ? make_uint4(lo[0], lo[1], lo[2], lo[3]) : make_uint4(hi[0], hi[1], hi[2], hi[3]);
+    bf16_t* dst = (row < M) ? Xext + row * ext_ld + col0 : Wext + (row - M) * ext_ld + col0;
+    *reinterpret_cast<uint4*>(dst) = out;
+}
+
+size_t gemm_bf16_ext_bytes(int64_t M, int64_t N, int r) {
+    const int rp = (r + 15) / 16 * 16;
+    const int ext_ld = (3 * rp + BK - 1) / BK * BK;
+    return (size_t)(M + N) * ext_ld * sizeof(bf16_t);
+}
 
 template <int WA, int WB, bool SHARED, int EPI>
 static hipError_t launch_variant(const GemmParams& p, hipStream_t st) {
@@ -646,6 +752,18 @@ hipError_t launch_gemm_bf16(const GemmBf16Args& a, hipStream_t st) {
         vec = vec && (a.loss.ldt % 8 == 0) && ((reinterpret_cast<uintptr_t>(a.loss.target) & 15) == 0);
     p.vec_ok = vec ? 1 : 0;
     p.shared = a.shared ? 1 : 0;
+    p.Xext = nullptr; p.Wext = nullptr; p.ext_ld = 0;
+    if (a.P && !a.shared && a.ext_ws) {
+        p.ext_ld = (3 * p.rp + BK - 1) / BK * BK;
+        bf16_t* xe = static_cast<bf16_t*>(a.ext_ws);
+        bf16_t* we = xe + a.M * p.ext_ld;
+        const int64_t items = (a.M + a.N) * (p.ext_ld / 8);
+        hipLaunchKernelGGL(gemm_ext_prep_kernel, dim3((unsigned)((items + 255) / 256)), dim3(256), 0, st, xe, we, a.M, a.N, p.ext_ld,
+                           a.P, a.r, p.rp, a.eps_signed, p.s_lo, p.s_hi);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        p.Xext = xe; p.Wext = we;
+    }
     p.ce_target = reinterpret_cast<const int32_t*>(a.loss.target);
     p.ce_ms = reinterpret_cast<float2*>(a.loss.ce_ms);
     p.ce_tl = a.loss.ce_tl;
