@@ -259,7 +259,7 @@ int op_project(agzo_ctx* ctx, const agzo_layer& L, const Plan& p, const void* X,
 // shared = true: one pass over X and W evaluates the loss at W, W + eps Z, W - eps Z -> loss_dev[0..2]
 int op_forward(agzo_ctx* ctx, const agzo_layer& L, const Plan& p, const void* W, const void* X, const float* P,
                float eps_signed, uint64_t seed, void* Y, const agzo_loss_spec* loss, double* loss_dev,
-               bool shared = false) {
+               bool shared = false, int part_slot = 0, bool defer_finish = false) {
     hipStream_t st = ctx->stream;
     GemmLossArgs la;
     const bool has_loss = loss && loss->kind != AGZO_LOSS_NONE;
@@ -267,7 +267,8 @@ int op_forward(agzo_ctx* ctx, const agzo_layer& L, const Plan& p, const void* W,
     la.target_dtype = has_loss ? loss->target_dtype : AGZO_F32;
     la.target = has_loss ? loss->target : nullptr;
     la.ldt = has_loss ? loss->ldt : 0;
-    la.partials = reinterpret_cast<double*>(ctx->ws + p.off_part);
+    // a step keeps the tile partials of its forwards side by side (slot = 0, 1, 2) and finishes them in one launch
+    la.partials = reinterpret_cast<double*>(ctx->ws + p.off_part) + (size_t)part_slot * p.n_part;
     const bool ce = has_loss && loss->kind == AGZO_LOSS_CE;
     const int32_t* ids = ce ? static_cast<const int32_t*>(loss->target) : nullptr;
     if (ce && L.dtype == AGZO_BF16) {
@@ -312,7 +313,7 @@ int op_forward(agzo_ctx* ctx, const agzo_layer& L, const Plan& p, const void* W,
             if (ce) HIPCHK(launch_ce_rows_f32(Yf, ldy, L.n_tokens, L.d_out, ids, la.partials, loss_dev, st));
         }
     }
-    if (has_loss && !ce)
+    if (has_loss && !ce && !defer_finish)
         HIPCHK(launch_finish_loss(la.partials, p.n_part, 1.0 / ((double)L.n_tokens * (double)L.d_out), loss_dev,
                                   shared ? 3 : 1, st));
     return 0;
@@ -539,6 +540,18 @@ int agzo_step(agzo_ctx* ctx, const agzo_layer* L, void* W, const void* X, const 
     hipStream_t st = ctx->stream;
     float* B = wsf(ctx, p.off_B);
     const bool one_sided = (flags & AGZO_ONE_SIDED) != 0;
+    // squared error: the forwards leave their tile partials side by side and one launch reduces them and forms g;
+    // cross-entropy finishes each loss on its own and only g is left to do
+    const bool mse = loss->kind == AGZO_LOSS_MSE;
+    auto finish = [&](int nphase) -> int {
+        if (mse)
+            HIPCHK(launch_finish_two_point(reinterpret_cast<const double*>(ctx->ws + p.off_part), p.n_part,
+                                           1.0 / ((double)L->n_tokens * (double)L->d_out), nphase, out_dev, eps,
+                                           one_sided ? 1 : 0, st));
+        else
+            HIPCHK(launch_two_point(out_dev, eps, one_sided ? 1 : 0, st));
+        return 0;
+    };
 
     if ((flags & AGZO_SHARED_FORWARD) && !(flags & AGZO_NAIVE_INPLACE)) {
         // extraction first, then f0, f+ and f- from one pass over X and W (valid for a single layer:
@@ -546,21 +559,21 @@ int agzo_step(agzo_ctx* ctx, const agzo_layer* L, void* W, const void* X, const 
         TRY(op_basis(ctx, *L, p, X, K, seed, nullptr, flags & AGZO_INIT_FEATURE, B));
         float* P = wsf(ctx, p.off_T);
         TRY(op_project(ctx, *L, p, X, B, P, true));
-        TRY(op_forward(ctx, *L, p, W, X, P, eps, seed, nullptr, loss, out_dev, true));
-        HIPCHK(launch_two_point(out_dev, eps, one_sided ? 1 : 0, st));
+        TRY(op_forward(ctx, *L, p, W, X, P, eps, seed, nullptr, loss, out_dev, true, 0, mse));
+        TRY(finish(3));
         TRY(op_update(ctx, *L, p.off_upd, W, B, seed, lr, out_dev + 3));
         return AGZO_OK;
     }
     // 1. base forward f0 and subspace extraction from the same activations (Alg. 2, part 1)
-    TRY(op_forward(ctx, *L, p, W, X, nullptr, 0.f, seed, nullptr, loss, out_dev + 0));
+    TRY(op_forward(ctx, *L, p, W, X, nullptr, 0.f, seed, nullptr, loss, out_dev + 0, false, 0, mse));
     TRY(op_basis(ctx, *L, p, X, K, seed, nullptr, flags & AGZO_INIT_FEATURE, B));
     // 2. perturbed evaluations (Alg. 2, parts 2-3)
     if (flags & AGZO_NAIVE_INPLACE) {
         TRY(op_update(ctx, *L, p.off_upd, W, B, seed, -eps, nullptr));
-        TRY(op_forward(ctx, *L, p, W, X, nullptr, 0.f, seed, nullptr, loss, out_dev + 1));
+        TRY(op_forward(ctx, *L, p, W, X, nullptr, 0.f, seed, nullptr, loss, out_dev + 1, false, 1, mse));
         if (!one_sided) {
             TRY(op_update(ctx, *L, p.off_upd, W, B, seed, 2.f * eps, nullptr));
-            TRY(op_forward(ctx, *L, p, W, X, nullptr, 0.f, seed, nullptr, loss, out_dev + 2));
+            TRY(op_forward(ctx, *L, p, W, X, nullptr, 0.f, seed, nullptr, loss, out_dev + 2, false, 2, mse));
             TRY(op_update(ctx, *L, p.off_upd, W, B, seed, -eps, nullptr));
         } else {
             TRY(op_update(ctx, *L, p.off_upd, W, B, seed, eps, nullptr));
@@ -568,11 +581,11 @@ int agzo_step(agzo_ctx* ctx, const agzo_layer* L, void* W, const void* X, const 
     } else {
         float* P = wsf(ctx, p.off_T);
         TRY(op_project(ctx, *L, p, X, B, P, true));
-        TRY(op_forward(ctx, *L, p, W, X, P, +eps, seed, nullptr, loss, out_dev + 1));
-        if (!one_sided) TRY(op_forward(ctx, *L, p, W, X, P, -eps, seed, nullptr, loss, out_dev + 2));
+        TRY(op_forward(ctx, *L, p, W, X, P, +eps, seed, nullptr, loss, out_dev + 1, false, 1, mse));
+        if (!one_sided) TRY(op_forward(ctx, *L, p, W, X, P, -eps, seed, nullptr, loss, out_dev + 2, false, 2, mse));
     }
     // 3. scalar g and the rank-r update
-    HIPCHK(launch_two_point(out_dev, eps, one_sided ? 1 : 0, st));
+    TRY(finish(one_sided ? 2 : 3));
     TRY(op_update(ctx, *L, p.off_upd, W, B, seed, lr, out_dev + 3));
     return AGZO_OK;
 }

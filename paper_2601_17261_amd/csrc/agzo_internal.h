@@ -170,5 +170,8 @@ hipError_t launch_ce_rows_f32(const float* Y, int64_t ldy, int64_t M, int64_t N,
 // out[b] = scale * sum(partials[b*n .. b*n+n)), b < nout
 hipError_t launch_finish_loss(const double* partials, int n, double scale, double* out, int nout, hipStream_t st);
 hipError_t launch_two_point(double* out4, float eps, int one_sided, hipStream_t st);
+// both in one launch: partials [nphase][n] (phase 0 = f0, 1 = f+, 2 = f-; nphase = 2 for the one-sided form) -> out4
+hipError_t launch_finish_two_point(const double* partials, int n, double scale, int nphase, double* out4, float eps,
+                                   int one_sided, hipStream_t st);
 
 }  // namespace agzo

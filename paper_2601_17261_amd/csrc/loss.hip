@@ -34,6 +34,41 @@ __global__ void two_point_kernel(double* __restrict__ out4, float eps, int one_s
     }
 }
 
+// finish_loss for nphase (2 or 3) consecutive partial arrays and two_point in one launch: out4 = {L0, L+, L-, g}.
+// Same summation order per loss as finish_loss_kernel.
+__global__ __launch_bounds__(256) void finish_two_point_kernel(const double* __restrict__ partials, int n, double scale,
+                                                               int nphase, double* __restrict__ out4, float eps,
+                                                               int one_sided) {
+    __shared__ double red[256];
+    __shared__ double loss[3];
+    const int tid = threadIdx.x;
+    for (int ph = 0; ph < nphase; ++ph) {
+        double s = 0.0;
+        const double* p = partials + (int64_t)ph * n;
+        for (int i = tid; i < n; i += 256) s += p[i];
+        red[tid] = s;
+        __syncthreads();
+        for (int k = 128; k > 0; k >>= 1) {
+            if (tid < k) red[tid] += red[tid + k];
+            __syncthreads();
+        }
+        if (tid == 0) loss[ph] = red[0] * scale;
+        __syncthreads();
+    }
+    if (tid == 0) {
+        const double e = (double)eps;
+        out4[0] = loss[0];
+        out4[1] = loss[1];
+        if (one_sided) {
+            out4[2] = 0.0;   // L- is not evaluated in the one-sided form
+            out4[3] = (loss[1] - loss[0]) / e;
+        } else {
+            out4[2] = loss[2];
+            out4[3] = (loss[1] - loss[2]) / (2.0 * e);
+        }
+    }
+}
+
 // ---- cross-entropy -----------------------------------------------------------------------------
 // one thread per token: merge the chunk statistics, loss_t = log(sum exp) - logit[target]; block sums
 // of (loss, count) go to scratch[2*block], the last stage divides.
@@ -140,6 +175,12 @@ hipError_t launch_ce_rows_f32(const float* Y, int64_t ldy, int64_t M, int64_t N,
 
 hipError_t launch_finish_loss(const double* partials, int n, double scale, double* out, int nout, hipStream_t st) {
     hipLaunchKernelGGL(finish_loss_kernel, dim3(nout), dim3(256), 0, st, partials, n, scale, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_finish_two_point(const double* partials, int n, double scale, int nphase, double* out4, float eps,
+                                   int one_sided, hipStream_t st) {
+    hipLaunchKernelGGL(finish_two_point_kernel, dim3(1), dim3(256), 0, st, partials, n, scale, nphase, out4, eps, one_sided);
     return hipGetLastError();
 }
 
