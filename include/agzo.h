@@ -90,12 +90,14 @@ const char* agzo_last_error(const agzo_ctx* ctx);
 /* Synchronise the stream and report a deferred numeric failure (AGZO_ENUMERIC) if any; clears it. */
 int agzo_check(agzo_ctx* ctx);
 
-/* Measurement hooks (no counterpart in the paper): when enabled, each launch of a kernel class is
- * bracketed by HIP events recorded on the ctx stream; agzo_profile_read synchronises and returns the
- * number of launches since agzo_profile_enable and the sum of their durations in milliseconds. */
+/* Measurement hooks (no counterpart in the paper): each launch of a selected kernel class is bracketed
+ * by HIP events recorded on the ctx stream; agzo_profile_read synchronises and returns the number of
+ * launches since agzo_profile_enable and the sum of their durations in milliseconds.
+ * mask: bit (1 << AGZO_PROF_x) selects class x, AGZO_PROF_ALL all of them, 0 switches timing off.  The events
+ * cost a few microseconds of stream time each, so a timed region should select only what it reports. */
 enum { AGZO_PROF_GEMM = 0, AGZO_PROF_UPDATE = 1, AGZO_PROF_XQ = 2, AGZO_PROF_XTT = 3, AGZO_PROF_QR = 4,
-       AGZO_PROF_FILL = 5, AGZO_PROF_KINDS = 6 };
-int agzo_profile_enable(agzo_ctx* ctx, int32_t on);
+       AGZO_PROF_FILL = 5, AGZO_PROF_KINDS = 6, AGZO_PROF_ALL = 63 };
+int agzo_profile_enable(agzo_ctx* ctx, int32_t mask);
 int agzo_profile_read(agzo_ctx* ctx, int32_t kind, int64_t* launches, double* total_ms);
 
 /* Generator (Alg. 2 "generate R from seed"; this build: Philox4x32-10 + Box-Muller).

@@ -21,6 +21,7 @@ ONE_SIDED, NAIVE_INPLACE, INIT_FEATURE, SHARED_FORWARD = 1, 2, 4, 8
 OK, EINVAL, ENOMEM, ENUMERIC, EHIP = 0, -1, -2, -3, -4
 
 PROF_GEMM, PROF_UPDATE, PROF_XQ, PROF_XTT, PROF_QR, PROF_FILL = range(6)
+PROF_ALL = 63
 
 EXPORTS = ["agzo_create", "agzo_destroy", "agzo_last_error", "agzo_check", "agzo_profile_enable",
            "agzo_profile_read", "agzo_philox_words", "agzo_fill_normal",
@@ -158,7 +159,9 @@ class Context:
         self._rc(self.lib.agzo_check(self.h))
 
     def profile_enable(self, on):
-        self._rc(self.lib.agzo_profile_enable(self.h, 1 if on else 0))
+        """on: False / True (all kernel classes) or a mask of (1 << PROF_x) bits."""
+        mask = (PROF_ALL if on else 0) if isinstance(on, bool) else int(on)
+        self._rc(self.lib.agzo_profile_enable(self.h, mask))
 
     def profile_read(self, kind):
         n, ms = ctypes.c_int64(0), ctypes.c_double(0.0)

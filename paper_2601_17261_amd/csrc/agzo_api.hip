@@ -22,7 +22,7 @@ struct agzo_ctx {
     char* ws;
     size_t ws_bytes;
     int* flag;   // device int: deferred numeric failure
-    bool prof;
+    uint32_t prof;      // mask of timed kernel classes (bit = AGZO_PROF_* value)
     ProfClass pc[AGZO_PROF_KINDS];
 };
 
@@ -55,7 +55,7 @@ struct ProfScope {
     int kind;
     hipEvent_t stop = nullptr;
     ProfScope(agzo_ctx* ctx, int k) : c(ctx), kind(k) {
-        if (!c->prof) return;
+        if (!((c->prof >> kind) & 1u)) return;
         ProfClass& pc = c->pc[kind];
         if (pc.used == pc.start.size()) {
             hipEvent_t a, b;
@@ -373,7 +373,7 @@ int agzo_create(agzo_ctx** out, void* hip_stream) {
     ctx->ws = nullptr;
     ctx->ws_bytes = 0;
     ctx->flag = nullptr;
-    ctx->prof = false;
+    ctx->prof = 0;
     hipError_t e = hipMalloc(reinterpret_cast<void**>(&ctx->flag), 256);
     if (e == hipSuccess) e = hipMemset(ctx->flag, 0, 256);
     if (e != hipSuccess) {
@@ -410,10 +410,10 @@ int agzo_check(agzo_ctx* ctx) {
     return AGZO_OK;
 }
 
-int agzo_profile_enable(agzo_ctx* ctx, int32_t on) {
+int agzo_profile_enable(agzo_ctx* ctx, int32_t mask) {
     if (!ctx) return AGZO_EINVAL;
     HIPCHK(hipStreamSynchronize(ctx->stream));
-    ctx->prof = (on != 0);
+    ctx->prof = (uint32_t)mask & ((1u << AGZO_PROF_KINDS) - 1u);
     for (auto& pc : ctx->pc) pc.used = 0;
     return AGZO_OK;
 }
