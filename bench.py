@@ -179,6 +179,7 @@ def main():
     dt = time.perf_counter() - t0
     n_gemm, ms_gemm = ctx.profile_read(binding.PROF_GEMM)
     n_upd, ms_upd = ctx.profile_read(binding.PROF_UPDATE)
+    n_clk, gemm_ghz = ctx.profile_clock()
     ctx.profile_enable(False)
     # stage breakdown: two more steps with every kernel class timed (not part of `value`)
     nstage = 2
@@ -226,7 +227,9 @@ def main():
                    "tokens": N, "rank": r, "power_steps": K, "eps": eps, "lr": lr},
         "roofline": {"bound": "mfma", "kernel": "gemm_bf16_kernel", "achieved": gemm_tflops, "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": gemm_tflops / PEAK_BF16_TFLOPS, "traffic": traffic,
-                     "launches": n_gemm, "avg_ms": gemm_avg_ms},
+                     "launches": n_gemm, "avg_ms": gemm_avg_ms,
+                     "shader_clock_ghz": gemm_ghz, "clock_note": "mean shader clock over the first workgroup of each of "
+                     "these launches (in-kernel cycle counter / constant-rate counter); the peak assumes 2.4 GHz"},
         "roofline_update": {"bound": "hbm", "kernel": "update_prep_kernel + update_mfma_kernel", "achieved": upd_gbs, "peak": PEAK_HBM_GBS,
                             "unit": "GB/s", "frac": upd_gbs / PEAK_HBM_GBS, "launches": n_upd, "avg_ms": upd_avg_ms},
         "stage_ms_per_step": {"gemm": st_gemm, "update": st_upd, "xq": ms_xq, "xtt": ms_xtt, "qr": ms_qr,
@@ -279,6 +282,19 @@ def main():
         res["naive_inplace"] = {"value": nsteps / dt2, "unit": "steps/s", "ms_per_step": 1e3 * dt2 / nsteps, "steps": nsteps,
                                 "note": "perturb-in-place / undo comparator (4 extra sweeps of W per step; in bf16 a different "
                                         "computation: the perturbation is rounded into the weights)"}
+    # yardstick for the MFMA fraction: a register-only MFMA loop (no LDS, no memory traffic) on this device, with
+    # operand bits that never toggle (zeros) and with N(0,1) bf16 operands like the workload's
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(7)
+    probes = {}
+    for name, ops in (("zero_operands", torch.zeros(16384, dtype=torch.bfloat16, device="cuda")),
+                      ("randn_operands", torch.randn(16384, device="cuda", generator=gen).to(torch.bfloat16))):
+        for _ in range(6):                      # a few launches so that the clock settles (about 6 ms each)
+            tf, ghz = ctx.probe_mfma(ops, 8, 3000)
+        probes[name] = {"tflops": tf, "clock_ghz": ghz}
+    res["roofline"]["sustained_mfma"] = dict(probes, note="register-only v_mfma_f32_32x32x16_bf16 loop, 4 waves per CU, "
+                                             "issued back to back: the rate this device holds under its power limit")
+    res["roofline"]["frac_of_sustained"] = gemm_tflops / probes["randn_operands"]["tflops"]
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(N, r, K, eps, lr, fwd_flops)
     print(json.dumps(res))

@@ -99,6 +99,20 @@ enum { AGZO_PROF_GEMM = 0, AGZO_PROF_UPDATE = 1, AGZO_PROF_XQ = 2, AGZO_PROF_XTT
        AGZO_PROF_FILL = 5, AGZO_PROF_KINDS = 6, AGZO_PROF_ALL = 63 };
 int agzo_profile_enable(agzo_ctx* ctx, int32_t mask);
 int agzo_profile_read(agzo_ctx* ctx, int32_t kind, int64_t* launches, double* total_ms);
+/* Shader clock during the GEMM class (no counterpart in the paper): while AGZO_PROF_GEMM is selected, the first
+ * workgroup of every bf16 GEMM launch (up to 8192 launches per agzo_profile_enable) records the GPU's shader-clock
+ * counter and its constant-rate counter at entry and exit.  Synchronises; *launches = records taken, *mean_ghz =
+ * sum of shader cycles / sum of elapsed time over them (0 if none).  Both outputs are host pointers. */
+int agzo_profile_clock(agzo_ctx* ctx, int64_t* launches, double* mean_ghz);
+/* Device probe (no counterpart in the paper; a yardstick for the measured MFMA roofline fraction): one workgroup of
+ * four waves per compute unit runs `iters` iterations of 8 groups of 16 v_mfma_f32_32x32x16_bf16 on register
+ * operands only (no LDS, no memory traffic inside the loop); `duty` (1..8) of every 8 groups are issued, the rest
+ * replaced by a sleep of similar length.  operands: device, 32 KiB of bf16 bit patterns, read as 8 x 256 16-byte
+ * vectors (vector i*256 + t feeds lane t: i < 4 A fragments, i >= 4 B fragments); how often these bits toggle decides
+ * the power drawn and with it the clock the device holds.  Synchronous: enqueues on the ctx stream, waits, and
+ * returns the matrix rate over workgroup 0's lifetime in *tflops and the mean shader clock in *clock_ghz (host
+ * pointers).  Errors: AGZO_EINVAL for NULL pointers or duty / iters out of range (iters <= 2^20). */
+int agzo_probe_mfma(agzo_ctx* ctx, const void* operands, int32_t duty, int32_t iters, double* tflops, double* clock_ghz);
 
 /* Generator (Alg. 2 "generate R from seed"; this build: Philox4x32-10 + Box-Muller).
  * words: uint32 [rows][cols], word (row, col) = word col%4 of Philox(counter (row, col/4, tag, 0),

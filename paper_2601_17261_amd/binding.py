@@ -24,7 +24,7 @@ PROF_GEMM, PROF_UPDATE, PROF_XQ, PROF_XTT, PROF_QR, PROF_FILL = range(6)
 PROF_ALL = 63
 
 EXPORTS = ["agzo_create", "agzo_destroy", "agzo_last_error", "agzo_check", "agzo_profile_enable",
-           "agzo_profile_read", "agzo_philox_words", "agzo_fill_normal",
+           "agzo_profile_read", "agzo_profile_clock", "agzo_probe_mfma", "agzo_philox_words", "agzo_fill_normal",
            "agzo_layer_forward_sketch", "agzo_qr", "agzo_basis", "agzo_perturbed_forward", "agzo_update", "agzo_step"]
 
 
@@ -69,6 +69,8 @@ def load():
     lib.agzo_check.argtypes = [vp]
     lib.agzo_profile_enable.argtypes = [vp, i32]
     lib.agzo_profile_read.argtypes = [vp, i32, ctypes.POINTER(i64), ctypes.POINTER(ctypes.c_double)]
+    lib.agzo_profile_clock.argtypes = [vp, ctypes.POINTER(i64), ctypes.POINTER(ctypes.c_double)]
+    lib.agzo_probe_mfma.argtypes = [vp, vp, i32, i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
     lib.agzo_philox_words.argtypes = [vp, vp, i64, i32, u64, u32]
     lib.agzo_fill_normal.argtypes = [vp, vp, i64, i32, u64, u32]
     lib.agzo_layer_forward_sketch.argtypes = [vp, lp, vp, vp, vp, i32, vp, u64, vp, sp, vp]
@@ -167,6 +169,19 @@ class Context:
         n, ms = ctypes.c_int64(0), ctypes.c_double(0.0)
         self._rc(self.lib.agzo_profile_read(self.h, kind, ctypes.byref(n), ctypes.byref(ms)))
         return n.value, ms.value
+
+    def profile_clock(self):
+        n, ghz = ctypes.c_int64(0), ctypes.c_double(0.0)
+        self._rc(self.lib.agzo_profile_clock(self.h, ctypes.byref(n), ctypes.byref(ghz)))
+        return n.value, ghz.value
+
+    def probe_mfma(self, operands, duty, iters):
+        """operands: 32 KiB device tensor of bf16 bit patterns.  Returns (TFLOP/s, shader clock in GHz)."""
+        if operands.numel() * operands.element_size() < 32768 or not operands.is_contiguous():
+            raise ValueError("operands must be a contiguous device tensor of at least 32 KiB")
+        tf, ghz = ctypes.c_double(0.0), ctypes.c_double(0.0)
+        self._rc(self.lib.agzo_probe_mfma(self.h, _ptr(operands), duty, iters, ctypes.byref(tf), ctypes.byref(ghz)))
+        return tf.value, ghz.value
 
     def philox_words(self, dst, seed, tag):
         rows, cols = dst.shape

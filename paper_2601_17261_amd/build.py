@@ -10,7 +10,7 @@ CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(ROOT, "_build")
 LIB = os.path.join(PKG, "libagzo.so")
 SOURCES = ["philox.hip", "gemm_f32.hip", "gemm_bf16.hip", "skinny.hip", "qr.hip", "update.hip", "loss.hip",
-           "agzo_api.hip"]
+           "probe.hip", "agzo_api.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # packed-fp32 VALU forms are switched off for every device compile (some forms have misbehaved
 # on the test machines); the host pass does not know the feature and says so, harmlessly.

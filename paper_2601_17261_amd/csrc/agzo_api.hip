@@ -24,7 +24,12 @@ struct agzo_ctx {
     int* flag;   // device int: deferred numeric failure
     uint32_t prof;      // mask of timed kernel classes (bit = AGZO_PROF_* value)
     ProfClass pc[AGZO_PROF_KINDS];
+    // clock telemetry: kClkSlots records of four 64-bit words (one per timed GEMM launch), then the probe's record
+    unsigned long long* clk;
+    size_t clk_used;
 };
+constexpr size_t kClkSlots = 8192;
+constexpr size_t kClkBytes = (kClkSlots + 1) * 32 + 1024;
 
 namespace {
 
@@ -285,6 +290,7 @@ int op_forward(agzo_ctx* ctx, const agzo_layer& L, const Plan& p, const void* W,
         a.loss = la;
         a.shared = shared;
         a.ext_ws = (P && !shared) ? ctx->ws + p.off_ext : nullptr;
+        if (((ctx->prof >> AGZO_PROF_GEMM) & 1u) && ctx->clk_used < kClkSlots) a.clk = ctx->clk + 4 * ctx->clk_used++;
         {
             ProfScope ps(ctx, AGZO_PROF_GEMM);
             HIPCHK(launch_gemm_bf16(a, st));
@@ -374,9 +380,15 @@ int agzo_create(agzo_ctx** out, void* hip_stream) {
     ctx->ws_bytes = 0;
     ctx->flag = nullptr;
     ctx->prof = 0;
+    ctx->clk = nullptr;
+    ctx->clk_used = 0;
     hipError_t e = hipMalloc(reinterpret_cast<void**>(&ctx->flag), 256);
     if (e == hipSuccess) e = hipMemset(ctx->flag, 0, 256);
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&ctx->clk), kClkBytes);
+    if (e == hipSuccess) e = hipMemset(ctx->clk, 0, kClkBytes);
     if (e != hipSuccess) {
+        if (ctx->flag) (void)hipFree(ctx->flag);
+        if (ctx->clk) (void)hipFree(ctx->clk);
         delete ctx;
         return AGZO_EHIP;
     }
@@ -389,6 +401,7 @@ void agzo_destroy(agzo_ctx* ctx) {
     (void)hipStreamSynchronize(ctx->stream);
     if (ctx->ws) (void)hipFree(ctx->ws);
     if (ctx->flag) (void)hipFree(ctx->flag);
+    if (ctx->clk) (void)hipFree(ctx->clk);
     for (auto& pc : ctx->pc) {
         for (hipEvent_t e : pc.start) (void)hipEventDestroy(e);
         for (hipEvent_t e : pc.stop) (void)hipEventDestroy(e);
@@ -415,6 +428,60 @@ int agzo_profile_enable(agzo_ctx* ctx, int32_t mask) {
     HIPCHK(hipStreamSynchronize(ctx->stream));
     ctx->prof = (uint32_t)mask & ((1u << AGZO_PROF_KINDS) - 1u);
     for (auto& pc : ctx->pc) pc.used = 0;
+    ctx->clk_used = 0;
+    return AGZO_OK;
+}
+
+namespace {
+// rate of the constant counter that wall_clock64() reads, in Hz
+int wall_rate(agzo_ctx* ctx, double* hz) {
+    int dev = 0, khz = 0;
+    HIPCHK(hipGetDevice(&dev));
+    HIPCHK(hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev));
+    if (khz <= 0) return fail(ctx, AGZO_EHIP, "device reports no wall clock rate");
+    *hz = 1e3 * khz;
+    return 0;
+}
+}  // namespace
+
+int agzo_profile_clock(agzo_ctx* ctx, int64_t* launches, double* mean_ghz) {
+    if (!ctx) return AGZO_EINVAL;
+    if (!launches || !mean_ghz) return fail(ctx, AGZO_EINVAL, "bad clock query");
+    HIPCHK(hipStreamSynchronize(ctx->stream));
+    double hz = 0.0;
+    TRY(wall_rate(ctx, &hz));
+    std::vector<unsigned long long> h(4 * ctx->clk_used);
+    if (ctx->clk_used) HIPCHK(hipMemcpy(h.data(), ctx->clk, h.size() * 8, hipMemcpyDeviceToHost));
+    double cycles = 0.0, ticks = 0.0;
+    for (size_t i = 0; i < ctx->clk_used; ++i) {
+        cycles += (double)(h[4 * i + 2] - h[4 * i]);
+        ticks += (double)(h[4 * i + 3] - h[4 * i + 1]);
+    }
+    *launches = (int64_t)ctx->clk_used;
+    *mean_ghz = (ticks > 0.0) ? cycles / ticks * hz * 1e-9 : 0.0;
+    return AGZO_OK;
+}
+
+int agzo_probe_mfma(agzo_ctx* ctx, const void* operands, int32_t duty, int32_t iters, double* tflops, double* clock_ghz) {
+    if (!ctx) return AGZO_EINVAL;
+    if (!operands || !tflops || !clock_ghz) return fail(ctx, AGZO_EINVAL, "NULL argument");
+    if (duty < 1 || duty > 8 || iters < 1 || iters > (1 << 20)) return fail(ctx, AGZO_EINVAL, "need 1 <= duty <= 8 and 1 <= iters <= 2^20");
+    double hz = 0.0;
+    TRY(wall_rate(ctx, &hz));
+    int dev = 0, cus = 0;
+    HIPCHK(hipGetDevice(&dev));
+    HIPCHK(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+    unsigned long long* rec = ctx->clk + 4 * kClkSlots;
+    HIPCHK(launch_probe_mfma(operands, duty, iters, rec, ctx->stream));
+    HIPCHK(hipStreamSynchronize(ctx->stream));
+    unsigned long long h[4];
+    HIPCHK(hipMemcpy(h, rec, sizeof(h), hipMemcpyDeviceToHost));
+    const double seconds = (double)(h[3] - h[1]) / hz;
+    if (seconds <= 0.0) return fail(ctx, AGZO_EHIP, "probe returned no time");
+    // 16 MFMAs of 32x32x16 per issued group, 4 waves per workgroup, one workgroup per CU
+    const double flops = 2.0 * 32 * 32 * 16 * 16.0 * duty * (double)iters * 4.0 * cus;
+    *tflops = flops / seconds * 1e-12;
+    *clock_ghz = (double)(h[2] - h[0]) / seconds * 1e-9;
     return AGZO_OK;
 }
 

@@ -119,6 +119,9 @@ struct GemmBf16Args {
     // gemm_bf16_ext_bytes() bytes of device scratch for the rank-r extension operands of a perturbed forward
     // (NULL: every tile builds them itself)
     void* ext_ws = nullptr;
+    // telemetry (NULL: none): four 64-bit device words that workgroup 0 fills with the shader-clock counter and the
+    // constant-rate counter at kernel entry and exit
+    unsigned long long* clk = nullptr;
 };
 int gemm_bf16_num_workgroups(int64_t M, int64_t N);
 size_t gemm_bf16_ext_bytes(int64_t M, int64_t N, int r);
@@ -173,5 +176,9 @@ hipError_t launch_two_point(double* out4, float eps, int one_sided, hipStream_t 
 // both in one launch: partials [nphase][n] (phase 0 = f0, 1 = f+, 2 = f-; nphase = 2 for the one-sided form) -> out4
 hipError_t launch_finish_two_point(const double* partials, int n, double scale, int nphase, double* out4, float eps,
                                    int one_sided, hipStream_t st);
+
+// probe.hip : register-only MFMA loop for measuring the sustained matrix rate and shader clock of the device;
+// clk4: four 64-bit words for the counters plus 1 KiB that the kernel may (never does) write behind them
+hipError_t launch_probe_mfma(const void* operands, int duty, int iters, unsigned long long* clk4, hipStream_t st);
 
 }  // namespace agzo

@@ -61,6 +61,8 @@ struct GemmParams {
     int shared;                 // one pass evaluates f0, f+ and f- (three loss partials per tile)
     // cross-entropy: per (128-column chunk, token) running max and sum of exponentials, and the target's logit
     const int32_t* ce_target; float2* ce_ms; float* ce_tl;
+    // optional telemetry: workgroup 0 leaves {shader clock, constant-rate clock} at entry and at exit
+    unsigned long long* clk;
 };
 
 // WA x WB waves: WA splits the 256 outputs, WB splits the 256 tokens
@@ -79,6 +81,7 @@ __global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
     auto Ws = [&](int buf) -> char* { return smem + buf * (2 * TILE_BYTES) + TILE_BYTES; };
 
     const int tid = threadIdx.x, lane = tid & 63;
+    if (p.clk && blockIdx.x == 0 && tid == 0) { p.clk[0] = __builtin_readcyclecounter(); p.clk[1] = wall_clock64(); }
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform by construction: keeps LDS bases scalar
     const int wa = wave / WB, wb = wave % WB;
     const int lr = lane & 31, lh = lane >> 5;
@@ -661,6 +664,7 @@ __global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
         run_manual(nfull, total, last0);
         evaluate(0);
     }
+    if (p.clk && blockIdx.x == 0 && tid == 0) { p.clk[2] = __builtin_readcyclecounter(); p.clk[3] = wall_clock64(); }
 }
 
 
@@ -767,6 +771,7 @@ hipError_t launch_gemm_bf16(const GemmBf16Args& a, hipStream_t st) {
     p.ce_target = reinterpret_cast<const int32_t*>(a.loss.target);
     p.ce_ms = reinterpret_cast<float2*>(a.loss.ce_ms);
     p.ce_tl = a.loss.ce_tl;
+    p.clk = a.clk;
     int epi = 0;
     if (p.loss_kind == AGZO_LOSS_CE) epi = 1;
     else if (p.loss_kind == AGZO_LOSS_MSE && !a.Y && vec && a.M % BT == 0 && a.N % BT == 0)

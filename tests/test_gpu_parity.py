@@ -378,3 +378,39 @@ def test_invalid_arguments_are_rejected(ctx):
     with pytest.raises(binding.AgzoError):
         ctx.step(Lbad, Wd, Xd, loss, 3, EPS, LR, 1, 0, out)
     np.testing.assert_array_equal(Wd.float().cpu().numpy(), W)     # nothing was touched
+
+
+# ---------------------------------------------------------------------------------------------
+# measurement hooks: they report through the C ABI and leave the results untouched
+# ---------------------------------------------------------------------------------------------
+def test_clock_telemetry_and_mfma_probe(ctx):
+    W, X, T, Wd, Xd, Td = problem(5, 300, 200, 136, "lowrank", "bf16")
+    L = binding.make_layer(Wd, Xd, 4)
+    loss = binding.make_loss(Td)
+    out = torch.zeros(2, 4, dtype=torch.float64, device="cuda")
+    W0, W1 = Wd.clone(), Wd.clone()
+    ctx.step(L, W0, Xd, loss, 2, EPS, LR, 9, 0, out[0])
+    ctx.profile_enable(1 << binding.PROF_GEMM)
+    ctx.step(L, W1, Xd, loss, 2, EPS, LR, 9, 0, out[1])
+    n_ev, _ = ctx.profile_read(binding.PROF_GEMM)
+    n_clk, ghz = ctx.profile_clock()
+    ctx.profile_enable(False)
+    ctx.check()
+    assert n_ev == 3 and n_clk == 3                  # f0, f+, f-
+    assert 0.3 < ghz < 3.0
+    assert torch.equal(out[0], out[1]) and torch.equal(W0, W1)      # telemetry changes no result
+    assert ctx.profile_clock() == (0, 0.0)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(3)
+    ops = torch.randn(16384, device="cuda", generator=g).to(torch.bfloat16)
+    tf, clk = ctx.probe_mfma(ops, 8, 200)
+    # rate and clock are tied together: 4 SIMDs per CU, one 32x32x16 MFMA (32768 flop) per 32 cycles each
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    assert 0.3 < clk < 3.0
+    assert tf == pytest.approx(cus * 4 * 1024 * clk * 1e-3, rel=0.05)
+    tf4, clk4 = ctx.probe_mfma(ops, 4, 200)
+    assert tf4 < 0.7 * tf * clk4 / clk
+    for duty, iters in ((0, 10), (9, 10), (8, 0)):
+        with pytest.raises(binding.AgzoError) as e:
+            ctx.probe_mfma(ops, duty, iters)
+        assert e.value.code == binding.EINVAL
