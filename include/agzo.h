@@ -144,6 +144,12 @@ int agzo_perturbed_forward(agzo_ctx* ctx, const agzo_layer* L, const void* W, co
                            const float* B, uint64_t seed, float eps_signed, void* Y,
                            const agzo_loss_spec* loss, double* loss_dev);
 
+/* Projected-gradient scalar (Eq. 10, Alg. 2): out4_dev = {L0, L+, L-, g} (device doubles); reads the losses and writes
+ * g = (L+ - L-) / (2 eps), or with AGZO_ONE_SIDED the paper's literal g = (L+ - L0) / eps (L- is then set to 0).
+ * For schedules that the caller composes from the calls above (several layers sharing one global g): every layer's
+ * agzo_update can take out4_dev + 3 as its g_dev.  Errors: AGZO_EINVAL for NULL or eps <= 0. */
+int agzo_two_point(agzo_ctx* ctx, double* out4_dev, float eps, int32_t flags);
+
 /* In-place rank-r sweep (Alg. 2, restore/update line): W -= lr * g * G B^T, g = *g_dev (1 if NULL). */
 int agzo_update(agzo_ctx* ctx, const agzo_layer* L, void* W, const float* B, uint64_t seed,
                 float lr, const double* g_dev);

@@ -25,7 +25,8 @@ PROF_ALL = 63
 
 EXPORTS = ["agzo_create", "agzo_destroy", "agzo_last_error", "agzo_check", "agzo_profile_enable",
            "agzo_profile_read", "agzo_profile_clock", "agzo_probe_mfma", "agzo_philox_words", "agzo_fill_normal",
-           "agzo_layer_forward_sketch", "agzo_qr", "agzo_basis", "agzo_perturbed_forward", "agzo_update", "agzo_step"]
+           "agzo_layer_forward_sketch", "agzo_qr", "agzo_basis", "agzo_perturbed_forward", "agzo_two_point", "agzo_update",
+           "agzo_step"]
 
 
 class AgzoLayer(ctypes.Structure):
@@ -77,6 +78,7 @@ def load():
     lib.agzo_qr.argtypes = [vp, vp, i64, i32, vp]
     lib.agzo_basis.argtypes = [vp, lp, vp, i32, u64, vp, i32, vp]
     lib.agzo_perturbed_forward.argtypes = [vp, lp, vp, vp, vp, u64, f32, vp, sp, vp]
+    lib.agzo_two_point.argtypes = [vp, vp, f32, i32]
     lib.agzo_update.argtypes = [vp, lp, vp, vp, u64, f32, vp]
     lib.agzo_step.argtypes = [vp, lp, vp, vp, sp, i32, f32, f32, u64, i32, vp]
     for name in EXPORTS:
@@ -208,6 +210,11 @@ class Context:
         self._rc(self.lib.agzo_perturbed_forward(self.h, ctypes.byref(L), _ptr(W), _ptr(X), _ptr(B), seed,
                                                  eps_signed, _ptr(Y),
                                                  ctypes.byref(loss) if loss is not None else None, _ptr(loss_dev)))
+
+    def two_point(self, out4_dev, eps, flags=0):
+        if out4_dev.dtype != torch.float64 or out4_dev.numel() < 4 or not out4_dev.is_contiguous():
+            raise TypeError("out4_dev must be 4 contiguous float64 values on the device")
+        self._rc(self.lib.agzo_two_point(self.h, _ptr(out4_dev), eps, flags))
 
     def update(self, L, W, B, seed, lr, g_dev):
         self._rc(self.lib.agzo_update(self.h, ctypes.byref(L), _ptr(W), _ptr(B), seed, lr, _ptr(g_dev)))

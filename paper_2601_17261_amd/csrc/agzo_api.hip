@@ -593,6 +593,14 @@ int agzo_update(agzo_ctx* ctx, const agzo_layer* L, void* W, const float* B, uin
     return AGZO_OK;
 }
 
+int agzo_two_point(agzo_ctx* ctx, double* out4_dev, float eps, int32_t flags) {
+    if (!ctx) return AGZO_EINVAL;
+    if (!out4_dev) return fail(ctx, AGZO_EINVAL, "out4_dev is NULL");
+    if (!(eps > 0.f)) return fail(ctx, AGZO_EINVAL, "eps must be positive");
+    HIPCHK(launch_two_point(out4_dev, eps, (flags & AGZO_ONE_SIDED) ? 1 : 0, ctx->stream));
+    return AGZO_OK;
+}
+
 int agzo_step(agzo_ctx* ctx, const agzo_layer* L, void* W, const void* X, const agzo_loss_spec* loss, int32_t K,
               float eps, float lr, uint64_t seed, int32_t flags, double* out_dev) {
     TRY(check_layer(ctx, L, true));

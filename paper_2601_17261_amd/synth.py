@@ -137,3 +137,24 @@ def device_weights_and_target(seed, X, d_out, device="cuda"):
     Wstar = W.float() + (0.05 / 2.0) * (P @ Q.T)
     Ystar = X.float() @ Wstar.T
     return W, Ystar
+
+
+def mlp_stack_problem(seed, n_blocks, hidden, inter, vocab, n_seq, seq_len, emb_rank=16):
+    """Weights and token ids of a gated-MLP stack (the reduced form of the MLP-stack workload): bf16-exact values.
+
+    params: "E" [vocab][hidden] (a rank-`emb_rank` part plus noise, so that activations have a few dominant
+    directions), ("gate", b) / ("up", b) [inter][hidden], ("down", b) [hidden][inter], ("head", 0) [vocab][hidden],
+    all ~ N(0, 0.02^2) except E (unit-RMS rows on average); ids uniform over the vocabulary."""
+    rng = np.random.default_rng(seed)
+    A = rng.standard_normal((vocab, emb_rank))
+    C = rng.standard_normal((emb_rank, hidden))
+    E = (A * np.logspace(0.0, -1.0, emb_rank)[None, :]) @ C + 0.3 * rng.standard_normal((vocab, hidden))
+    E /= np.sqrt(np.mean(E * E))
+    params = {"n_blocks": n_blocks, "E": to_bf16_values(E)}
+    for b in range(n_blocks):
+        params[("gate", b)] = weights(rng, inter, hidden, storage="bf16")
+        params[("up", b)] = weights(rng, inter, hidden, storage="bf16")
+        params[("down", b)] = weights(rng, hidden, inter, storage="bf16")
+    params[("head", 0)] = weights(rng, vocab, hidden, storage="bf16")
+    ids = rng.integers(0, vocab, size=(n_seq, seq_len), dtype=np.int64)
+    return params, ids
