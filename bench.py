@@ -282,6 +282,22 @@ def main():
         res["naive_inplace"] = {"value": nsteps / dt2, "unit": "steps/s", "ms_per_step": 1e3 * dt2 / nsteps, "steps": nsteps,
                                 "note": "perturb-in-place / undo comparator (4 extra sweeps of W per step; in bf16 a different "
                                         "computation: the perturbation is rounded into the weights)"}
+    # the standalone generator fill (the form in which the Gaussian factor is checked bit for bit): 2^28 normals
+    gbuf = torch.empty(1 << 24, 16, dtype=torch.float32, device="cuda")
+    ctx.fill_normal(gbuf, 1, binding.TAG_G)
+    torch.cuda.synchronize()
+    ctx.profile_enable(1 << binding.PROF_FILL)
+    for i in range(5):
+        ctx.fill_normal(gbuf, 2 + i, binding.TAG_G)
+    n_fill, ms_fill = ctx.profile_read(binding.PROF_FILL)
+    ctx.profile_enable(False)
+    fill_gbs = gbuf.numel() * 4.0 / (ms_fill / max(n_fill, 1) * 1e-3) / 1e9
+    res["roofline_generator"] = {"bound": "hbm", "kernel": "fill_normal_kernel", "achieved": fill_gbs, "peak": PEAK_HBM_GBS,
+                                 "unit": "GB/s", "frac": fill_gbs / PEAK_HBM_GBS, "launches": n_fill,
+                                 "normals_per_s": fill_gbs * 1e9 / 4.0,
+                                 "note": "4 bytes written per value; about 60 VALU issue slots per value (Philox4x32-10 "
+                                         "+ Box-Muller), so the ALU bound is of the same order as the write bound"}
+    del gbuf
     # yardstick for the MFMA fraction: a register-only MFMA loop (no LDS, no memory traffic) on this device, with
     # operand bits that never toggle (zeros) and with N(0,1) bf16 operands like the workload's
     gen = torch.Generator(device="cuda")

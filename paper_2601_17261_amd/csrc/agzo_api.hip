@@ -513,6 +513,7 @@ int agzo_fill_normal(agzo_ctx* ctx, float* dst, int64_t rows, int32_t cols, uint
     if (!ctx) return AGZO_EINVAL;
     if (rows < 0 || cols < 0 || rows > 0xFFFFFFFFLL) return fail(ctx, AGZO_EINVAL, "bad shape");
     if (!dst && rows * cols > 0) return fail(ctx, AGZO_EINVAL, "dst is NULL");
+    ProfScope ps(ctx, AGZO_PROF_FILL);
     HIPCHK(launch_fill_normal(dst, rows, cols, seed, tag, ctx->stream));
     return AGZO_OK;
 }
