@@ -297,7 +297,21 @@ def main():
                                  "normals_per_s": fill_gbs * 1e9 / 4.0,
                                  "note": "4 bytes written per value; about 60 VALU issue slots per value (Philox4x32-10 "
                                          "+ Box-Muller), so the ALU bound is of the same order as the write bound"}
-    del gbuf
+    # the dense Gaussian sweep of Eq. 7's other branch on a bf16 block of the same size (read + write 2 bytes each)
+    theta = gbuf.view(torch.bfloat16)[:, :16]
+    theta.zero_()
+    ctx.dense_perturb(theta, 1, 1e-3)
+    torch.cuda.synchronize()
+    ctx.profile_enable(1 << binding.PROF_FILL)
+    for i in range(5):
+        ctx.dense_perturb(theta, 2 + i, 1e-3)
+    n_dn, ms_dn = ctx.profile_read(binding.PROF_FILL)
+    ctx.profile_enable(False)
+    dn_rate = theta.numel() / (ms_dn / max(n_dn, 1) * 1e-3)
+    res["roofline_generator"]["dense_sweep_bf16"] = {"kernel": "dense_axpy_kernel", "achieved": 4.0 * dn_rate / 1e9, "unit": "GB/s",
+                                                     "frac": 4.0 * dn_rate / 1e9 / PEAK_HBM_GBS, "normals_per_s": dn_rate,
+                                                     "launches": n_dn}
+    del gbuf, theta
     # yardstick for the MFMA fraction: a register-only MFMA loop (no LDS, no memory traffic) on this device, with
     # operand bits that never toggle (zeros) and with N(0,1) bf16 operands like the workload's
     gen = torch.Generator(device="cuda")

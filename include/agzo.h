@@ -154,6 +154,17 @@ int agzo_two_point(agzo_ctx* ctx, double* out4_dev, float eps, int32_t flags);
 int agzo_update(agzo_ctx* ctx, const agzo_layer* L, void* W, const float* B, uint64_t seed,
                 float lr, const double* g_dev);
 
+/* Dense Gaussian sweep for parameters that are not linear-layer weights (Eq. 7, second branch; Alg. 2: the perturb,
+ * restore and update lines for such parameters): theta[i][j] += coef * z(i, j) in place, z the N(0,1) value
+ * (seed, tag 3, row i, column j) of the generator above, coef = scale * *g_dev (scale alone if g_dev is NULL).
+ * theta: device, [rows][cols] with row stride ld elements, dtype AGZO_F32 or AGZO_BF16 (fp32 arithmetic, one rounding
+ * to the storage type; bf16 to nearest even).  A vector of n parameters is rows = 1, cols = n or any other fixed
+ * factorisation: the perturbation, its reversal and the update must use the same one.  Perturb with scale = +eps,
+ * go to the other side with -2 eps, restore with +eps, update with scale = -lr and g_dev = the scalar of
+ * agzo_two_point.  Errors: AGZO_EINVAL for NULL theta, negative sizes, ld < cols, rows or cols/4 >= 2^32, bad dtype. */
+int agzo_dense_perturb(agzo_ctx* ctx, void* theta, int32_t dtype, int64_t rows, int64_t cols, int64_t ld, uint64_t seed,
+                       float scale, const double* g_dev);
+
 /* One whole AGZO step for one layer (Alg. 2).  out_dev[4] = {L0, L+, L-, g} (device doubles). */
 int agzo_step(agzo_ctx* ctx, const agzo_layer* L, void* W, const void* X, const agzo_loss_spec* loss,
               int32_t K, float eps, float lr, uint64_t seed, int32_t flags, double* out_dev);

@@ -117,6 +117,21 @@ def perturbation(B, seed, d_out):
     return G @ B.T, G
 
 
+def dense_perturbation(seed, rows, cols):
+    """R for a parameter block that is not a linear-layer weight (Eq. 7, second branch):
+    iid N(0,1) of the block's own shape, regenerated from the seed (stream TAG_DENSE)."""
+    return philox.normal(seed, philox.TAG_DENSE, rows, cols).astype(np.float64)
+
+
+def dense_apply(theta, seed, coef, storage):
+    """theta + coef R rounded to the storage type: one in-place sweep of Alg. 2 (perturb with
+    +eps, restore with -eps, update with -lr g) for such a block.  A 1-D block is one row."""
+    t = np.asarray(theta, dtype=np.float64)
+    t2 = t.reshape(1, -1) if t.ndim == 1 else t
+    out = round_storage(t2 + coef * dense_perturbation(seed, t2.shape[0], t2.shape[1]), storage)
+    return out.reshape(t.shape)
+
+
 def forward(X, W):
     """Y = X W^T (y = W h per token)."""
     return np.asarray(X, dtype=np.float64) @ np.asarray(W, dtype=np.float64).T

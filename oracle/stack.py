@@ -12,8 +12,11 @@ Model (a synthetic stand-in with the structure of a gated-MLP language model):
   h = E[ids]                                   embedding rows, frozen
   per block:  n = rmsnorm(h);  h = h + W_down (silu(W_gate n) * (W_up n))
   logits = W_head rmsnorm(h);  loss = token cross-entropy (oracle.agzo.ce_loss)
-rmsnorm has no gain: x / sqrt(mean(x^2) + 1e-6).  Nothing but the linear layers
-is trained, so Alg. 2's dense-Gaussian branch for other parameters is not used.
+rmsnorm(x) = gain * x / sqrt(mean(x^2) + 1e-6).  The gains (one vector per block and
+one before the head; fp32 values, all ones if params holds none) are the parameters
+that are not linear-layer weights: they take Alg. 2's other branch, a dense Gaussian
+perturbation R of their own shape (Eq. 7), with the same eps, the same global g and
+the update gain <- gain - lr g R.  The embedding is frozen.
 
 Activation storage: `act` names the type every stored tensor is rounded to
 ("bf16", "f32", or None for no rounding).  The rounding points are the stored
@@ -31,9 +34,10 @@ def _store(a, act):
     return np.asarray(a, dtype=np.float64) if act is None else agzo.round_storage(a, act)
 
 
-def rmsnorm(x):
+def rmsnorm(x, gain=None):
     x = np.asarray(x, dtype=np.float64)
-    return x / np.sqrt(np.mean(x * x, axis=1, keepdims=True) + 1e-6)
+    y = x / np.sqrt(np.mean(x * x, axis=1, keepdims=True) + 1e-6)
+    return y if gain is None else y * np.asarray(gain, dtype=np.float64)[None, :]
 
 
 def silu(a):
@@ -47,6 +51,12 @@ def layer_names(n_blocks):
     for b in range(n_blocks):
         names += [("gate", b), ("up", b), ("down", b)]
     return names + [("head", 0)]
+
+
+def gain_names(params):
+    """The gain vectors present in params, in the order they are met."""
+    names = [("norm", b) for b in range(params["n_blocks"])] + [("norm_f", 0)]
+    return [nm for nm in names if nm in params]
 
 
 def shifted_targets(ids):
@@ -69,16 +79,22 @@ def forward(params, ids, act="bf16", delta=None, record=None):
             record[name] = x
         return x @ W.T
 
+    def gain(name):
+        if name not in params:
+            return None
+        gv = np.asarray(params[name], dtype=np.float64)
+        return gv + delta[name] if delta is not None and name in delta else gv
+
     ids = np.asarray(ids)
     h = np.asarray(params["E"], dtype=np.float64)[ids.reshape(-1)]
     for b in range(params["n_blocks"]):
-        n = _store(rmsnorm(h), act)
+        n = _store(rmsnorm(h, gain(("norm", b))), act)
         a = _store(lin(("gate", b), n), act)
         u = _store(lin(("up", b), n), act)
         m = _store(silu(a) * u, act)
         d = _store(lin(("down", b), m), act)
         h = _store(h + d, act)
-    n = _store(rmsnorm(h), act)
+    n = _store(rmsnorm(h, gain(("norm_f", 0))), act)
     logits = lin(("head", 0), n)
     return agzo.ce_loss(logits, shifted_targets(ids))
 
@@ -94,8 +110,15 @@ def agzo_stack_step(params, ids, r, K, eps, lr, seeds, act="bf16", storage="bf16
     for nm in names:
         B[nm] = agzo.subspace_extract(inputs[nm], r, K, seeds[nm])["B"]
         Z[nm], G[nm] = agzo.perturbation(B[nm], seeds[nm], np.asarray(params[nm]).shape[0])
-    Lp = forward(params, ids, act, {nm: eps * Z[nm] for nm in names})
-    Lm = 0.0 if one_sided else forward(params, ids, act, {nm: -eps * Z[nm] for nm in names})
+    # parameters that are not linear-layer weights: dense Gaussian of their own shape, kept in fp32
+    gains = gain_names(params)
+    for nm in gains:
+        Z[nm] = agzo.dense_perturbation(seeds[nm], 1, np.asarray(params[nm]).shape[0])[0]
+    every = names + gains
+    Lp = forward(params, ids, act, {nm: eps * Z[nm] for nm in every})
+    Lm = 0.0 if one_sided else forward(params, ids, act, {nm: -eps * Z[nm] for nm in every})
     g = (Lp - L0) / eps if one_sided else (Lp - Lm) / (2.0 * eps)
     W_new = {nm: agzo.round_storage(np.asarray(params[nm], dtype=np.float64) - lr * g * Z[nm], storage) for nm in names}
+    for nm in gains:
+        W_new[nm] = agzo.round_storage(np.asarray(params[nm], dtype=np.float64) - lr * g * Z[nm], "f32")
     return {"L0": L0, "Lp": Lp, "Lm": Lm, "g": g, "B": B, "G": G, "Z": Z, "W_new": W_new, "inputs": inputs}

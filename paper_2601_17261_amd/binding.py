@@ -25,7 +25,7 @@ PROF_ALL = 63
 
 EXPORTS = ["agzo_create", "agzo_destroy", "agzo_last_error", "agzo_check", "agzo_profile_enable",
            "agzo_profile_read", "agzo_profile_clock", "agzo_probe_mfma", "agzo_philox_words", "agzo_fill_normal",
-           "agzo_layer_forward_sketch", "agzo_qr", "agzo_basis", "agzo_perturbed_forward", "agzo_two_point", "agzo_update",
+           "agzo_layer_forward_sketch", "agzo_qr", "agzo_basis", "agzo_perturbed_forward", "agzo_two_point", "agzo_dense_perturb", "agzo_update",
            "agzo_step"]
 
 
@@ -79,6 +79,7 @@ def load():
     lib.agzo_basis.argtypes = [vp, lp, vp, i32, u64, vp, i32, vp]
     lib.agzo_perturbed_forward.argtypes = [vp, lp, vp, vp, vp, u64, f32, vp, sp, vp]
     lib.agzo_two_point.argtypes = [vp, vp, f32, i32]
+    lib.agzo_dense_perturb.argtypes = [vp, vp, i32, i64, i64, i64, u64, f32, vp]
     lib.agzo_update.argtypes = [vp, lp, vp, vp, u64, f32, vp]
     lib.agzo_step.argtypes = [vp, lp, vp, vp, sp, i32, f32, f32, u64, i32, vp]
     for name in EXPORTS:
@@ -215,6 +216,17 @@ class Context:
         if out4_dev.dtype != torch.float64 or out4_dev.numel() < 4 or not out4_dev.is_contiguous():
             raise TypeError("out4_dev must be 4 contiguous float64 values on the device")
         self._rc(self.lib.agzo_two_point(self.h, _ptr(out4_dev), eps, flags))
+
+    def dense_perturb(self, theta, seed, scale, g_dev=None):
+        """theta: 1-D (taken as one row) or 2-D device tensor, fp32 or bf16, unit stride along the last axis."""
+        if theta.dim() == 1:
+            rows, cols, ld = 1, theta.shape[0], theta.shape[0]
+        else:
+            rows, cols = theta.shape
+            ld = theta.stride(0)
+        if theta.numel() and theta.stride(-1) != 1:
+            raise ValueError("theta must have unit stride along its last axis")
+        self._rc(self.lib.agzo_dense_perturb(self.h, _ptr(theta), _dt(theta), rows, cols, ld, seed, scale, _ptr(g_dev)))
 
     def update(self, L, W, B, seed, lr, g_dev):
         self._rc(self.lib.agzo_update(self.h, ctypes.byref(L), _ptr(W), _ptr(B), seed, lr, _ptr(g_dev)))

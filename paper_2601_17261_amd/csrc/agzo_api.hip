@@ -594,6 +594,18 @@ int agzo_update(agzo_ctx* ctx, const agzo_layer* L, void* W, const float* B, uin
     return AGZO_OK;
 }
 
+int agzo_dense_perturb(agzo_ctx* ctx, void* theta, int32_t dtype, int64_t rows, int64_t cols, int64_t ld, uint64_t seed,
+                       float scale, const double* g_dev) {
+    if (!ctx) return AGZO_EINVAL;
+    if (rows < 0 || cols < 0 || ld < cols) return fail(ctx, AGZO_EINVAL, "bad shape %lld x %lld, ld %lld", (long long)rows, (long long)cols, (long long)ld);
+    if (dtype != AGZO_F32 && dtype != AGZO_BF16) return fail(ctx, AGZO_EINVAL, "dtype %d", dtype);
+    if (rows > 0xFFFFFFFFLL || (cols + 3) / 4 > 0xFFFFFFFFLL) return fail(ctx, AGZO_EINVAL, "rows and cols/4 must fit 32-bit counters");
+    if (!theta && rows * cols > 0) return fail(ctx, AGZO_EINVAL, "theta is NULL");
+    ProfScope ps(ctx, AGZO_PROF_FILL);
+    HIPCHK(launch_dense_axpy(theta, dtype, rows, cols, ld, seed, scale, g_dev, ctx->stream));
+    return AGZO_OK;
+}
+
 int agzo_two_point(agzo_ctx* ctx, double* out4_dev, float eps, int32_t flags) {
     if (!ctx) return AGZO_EINVAL;
     if (!out4_dev) return fail(ctx, AGZO_EINVAL, "out4_dev is NULL");

@@ -177,6 +177,10 @@ hipError_t launch_two_point(double* out4, float eps, int one_sided, hipStream_t 
 hipError_t launch_finish_two_point(const double* partials, int n, double scale, int nphase, double* out4, float eps,
                                    int one_sided, hipStream_t st);
 
+// update.hip : theta[i][j] += scale * (*g_dev or 1) * z(i, j), z = Philox normal of stream AGZO_TAG_DENSE (rows < 2^32)
+hipError_t launch_dense_axpy(void* theta, int dtype, int64_t rows, int64_t cols, int64_t ld, uint64_t seed, float scale,
+                             const double* g_dev, hipStream_t st);
+
 // probe.hip : register-only MFMA loop for measuring the sustained matrix rate and shader clock of the device;
 // clk4: four 64-bit words for the counters plus 1 KiB that the kernel may (never does) write behind them
 hipError_t launch_probe_mfma(const void* operands, int duty, int iters, unsigned long long* clk4, hipStream_t st);

@@ -315,4 +315,62 @@ hipError_t launch_update(void* W, int dtype, int64_t ldw, int64_t d_out, int64_t
     }
 }
 
+
+// Dense Gaussian sweep (Eq. 7, the branch for parameters that are not linear-layer weights; Alg. 2 perturb / restore /
+// update lines): theta[i][j] += coef * z(i, j), z from Philox stream AGZO_TAG_DENSE, coef = scale * (*g_dev or 1).
+// One thread = one Philox call = four consecutive columns of a row.  The generator (about 110 instructions per
+// value) bounds this kernel, not the 4 - 8 bytes per value it moves.
+template <typename T>
+__global__ __launch_bounds__(256) void dense_axpy_kernel(T* __restrict__ theta, int64_t rows, int64_t cols, int64_t ld,
+                                                         int64_t nquad, uint32_t s_lo, uint32_t s_hi, float scale,
+                                                         const double* __restrict__ g_dev, int vec_ok) {
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= rows * nquad) return;
+    const int64_t row = idx / nquad;
+    const int64_t quad = idx - row * nquad;
+    const float coef = g_dev ? (float)((double)scale * *g_dev) : scale;
+    const float4 z4 = philox_normal4(s_lo, s_hi, AGZO_TAG_DENSE, (uint32_t)row, (uint32_t)quad);
+    const float z[4] = {z4.x, z4.y, z4.z, z4.w};
+    T* p = theta + row * ld + quad * 4;
+    if (vec_ok) {
+        if constexpr (sizeof(T) == 4) {
+            float4 v = *reinterpret_cast<float4*>(p);
+            v.x = fmaf(coef, z[0], v.x); v.y = fmaf(coef, z[1], v.y);
+            v.z = fmaf(coef, z[2], v.z); v.w = fmaf(coef, z[3], v.w);
+            *reinterpret_cast<float4*>(p) = v;
+        } else {
+            const uint2 w = *reinterpret_cast<uint2*>(p);
+            const float a0 = fmaf(coef, z[0], __uint_as_float(w.x << 16)), a1 = fmaf(coef, z[1], __uint_as_float(w.x & 0xFFFF0000u));
+            const float a2 = fmaf(coef, z[2], __uint_as_float(w.y << 16)), a3 = fmaf(coef, z[3], __uint_as_float(w.y & 0xFFFF0000u));
+            *reinterpret_cast<uint2*>(p) = make_uint2(pack_bf16x2(a0, a1), pack_bf16x2(a2, a3));
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            if (quad * 4 + i >= cols) break;
+            if constexpr (sizeof(T) == 4) p[i] = fmaf(coef, z[i], p[i]);
+            else p[i] = f32_to_bf16(fmaf(coef, z[i], bf16_to_f32(p[i])));
+        }
+    }
+}
+
+hipError_t launch_dense_axpy(void* theta, int dtype, int64_t rows, int64_t cols, int64_t ld, uint64_t seed, float scale,
+                             const double* g_dev, hipStream_t st) {
+    if (rows == 0 || cols == 0) return hipSuccess;
+    const int64_t nquad = (cols + 3) / 4;
+    const int64_t items = rows * nquad;
+    const dim3 grid((unsigned)((items + 255) / 256));
+    const uintptr_t addr = reinterpret_cast<uintptr_t>(theta);
+    if (dtype == AGZO_BF16) {
+        const int vec = (cols % 4 == 0) && (ld % 4 == 0) && (addr % 8 == 0);
+        hipLaunchKernelGGL(dense_axpy_kernel<bf16_t>, grid, dim3(256), 0, st, static_cast<bf16_t*>(theta), rows, cols, ld, nquad,
+                           (uint32_t)seed, (uint32_t)(seed >> 32), scale, g_dev, vec);
+    } else {
+        const int vec = (cols % 4 == 0) && (ld % 4 == 0) && (addr % 16 == 0);
+        hipLaunchKernelGGL(dense_axpy_kernel<float>, grid, dim3(256), 0, st, static_cast<float*>(theta), rows, cols, ld, nquad,
+                           (uint32_t)seed, (uint32_t)(seed >> 32), scale, g_dev, vec);
+    }
+    return hipGetLastError();
+}
+
 }  // namespace agzo

@@ -139,12 +139,13 @@ def device_weights_and_target(seed, X, d_out, device="cuda"):
     return W, Ystar
 
 
-def mlp_stack_problem(seed, n_blocks, hidden, inter, vocab, n_seq, seq_len, emb_rank=16):
+def mlp_stack_problem(seed, n_blocks, hidden, inter, vocab, n_seq, seq_len, emb_rank=16, gains=False):
     """Weights and token ids of a gated-MLP stack (the reduced form of the MLP-stack workload): bf16-exact values.
 
     params: "E" [vocab][hidden] (a rank-`emb_rank` part plus noise, so that activations have a few dominant
     directions), ("gate", b) / ("up", b) [inter][hidden], ("down", b) [hidden][inter], ("head", 0) [vocab][hidden],
-    all ~ N(0, 0.02^2) except E (unit-RMS rows on average); ids uniform over the vocabulary."""
+    all ~ N(0, 0.02^2) except E (unit-RMS rows on average); ids uniform over the vocabulary.  gains=True adds
+    the normalisation gains ("norm", b) and ("norm_f", 0), fp32 vectors of 1 + N(0, 0.1^2)."""
     rng = np.random.default_rng(seed)
     A = rng.standard_normal((vocab, emb_rank))
     C = rng.standard_normal((emb_rank, hidden))
@@ -157,4 +158,7 @@ def mlp_stack_problem(seed, n_blocks, hidden, inter, vocab, n_seq, seq_len, emb_
         params[("down", b)] = weights(rng, hidden, inter, storage="bf16")
     params[("head", 0)] = weights(rng, vocab, hidden, storage="bf16")
     ids = rng.integers(0, vocab, size=(n_seq, seq_len), dtype=np.int64)
+    if gains:       # drawn last, so that the other tensors do not depend on the flag
+        for nm in [("norm", b) for b in range(n_blocks)] + [("norm_f", 0)]:
+            params[nm] = (1.0 + 0.1 * rng.standard_normal(hidden)).astype(np.float32)
     return params, ids

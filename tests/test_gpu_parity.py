@@ -414,3 +414,57 @@ def test_clock_telemetry_and_mfma_probe(ctx):
         with pytest.raises(binding.AgzoError) as e:
             ctx.probe_mfma(ops, duty, iters)
         assert e.value.code == binding.EINVAL
+
+
+# ---------------------------------------------------------------------------------------------
+# dense Gaussian sweep (Eq. 7, parameters that are not linear-layer weights)
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("storage,shape", [("f32", (1, 2048)), ("f32", (33, 130)), ("f32", (5, 7)),
+                                           ("bf16", (1, 4096)), ("bf16", (257, 72)), ("bf16", (64, 1023))])
+def test_dense_perturb_matches_oracle(ctx, storage, shape):
+    rng = np.random.default_rng(shape[1])
+    th = synth.weights(rng, shape[0], shape[1], std=1.0, storage=storage)
+    seed, eps, lr = 99 + shape[0], float(np.float32(1e-2)), float(np.float32(0.5))
+    g = torch.tensor([-0.37], dtype=torch.float64, device="cuda")
+    d = dev(th, storage)
+    ulp_bits = 7 if storage == "bf16" else 23
+
+    def check(got, want, incr):
+        # one rounding to the storage type (fp32 arithmetic here, fp64 in the oracle: a value near a rounding
+        # boundary may come out one ulp apart) plus the fp32 generator's own error (2e-6 absolute per normal)
+        ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(want), 1e-30))) - ulp_bits)
+        assert (np.abs(host(got) - want) <= ulp * 1.0001 + 3e-6 * abs(incr)).all()
+        # (in fp32 the generator's own error is a sizeable part of an ulp, so only bf16 results are mostly identical)
+        if storage == "bf16":
+            assert (host(got) != want).mean() < 0.02
+
+    def sweep(t, scale, g_dev=None, g_val=1.0):
+        # compared sweep by sweep from this side's own state, so that a one-ulp difference is not carried along
+        before = host(t)
+        ctx.dense_perturb(t, seed, scale, g_dev)
+        want = oagzo.dense_apply(before, seed, scale * g_val, storage)
+        check(t, want, scale * g_val)
+        return want
+
+    p1 = sweep(d, eps)                     # perturb (Alg. 2)
+    sweep(d, -2 * eps)                     # to the other side
+    sweep(d, eps)                          # restore
+    back = host(d)
+    assert np.abs(back - th).max() <= 4 * 2.0 ** -ulp_bits * np.abs(th).max()
+    sweep(d, -lr, g, -0.37)                # update with the device scalar
+    assert np.abs(host(d) - back).max() > 0.1
+    # a 1-D tensor is one row of the same stream
+    if shape[0] == 1:
+        d1 = dev(th, storage).reshape(-1)
+        ctx.dense_perturb(d1, seed, eps)
+        check(d1.reshape(1, -1), p1, eps)
+    # strided rows: only the addressed columns change
+    big = torch.zeros(shape[0], shape[1] + 5, dtype=d.dtype, device="cuda")
+    view = big[:, :shape[1]]
+    ctx.dense_perturb(view, seed, 1.0)
+    assert (big[:, shape[1]:] == 0).all()
+    check(view, oagzo.dense_apply(np.zeros(shape), seed, 1.0, storage), 1.0)
+    with pytest.raises(binding.AgzoError) as e:
+        ctx._rc(ctx.lib.agzo_dense_perturb(ctx.h, None, 0, 4, 4, 2, 1, 1.0, None))
+    assert e.value.code == binding.EINVAL
+    ctx.check()

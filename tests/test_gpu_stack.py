@@ -3,7 +3,8 @@ hidden 2048, intermediate 6144, vocabulary 32000; token cross-entropy; r = 16, K
 over seven chained linear layers with one global g (Alg. 2), composed from the per-layer C-ABI calls.
 
 Every linear-layer operation (base forward, subspace extraction, factored perturbed forward, fused
-cross-entropy, the scalar g, the rank-r update) is a library call; what sits between the layers
+cross-entropy, the scalar g, the rank-r update) is a library call, and so are the in-place dense Gaussian sweeps of
+the normalisation gains (the parameters that are not linear-layer weights); what sits between the layers
 (embedding lookup, RMS normalisation, SiLU gate, residual sum: not steps of the method) is a few torch ops
 here, fp32 arithmetic rounded to bf16 where the oracle rounds.  In the perturbed passes every layer reads
 activations that already carry the perturbations of the layers before it, so the three passes share
@@ -39,6 +40,7 @@ class GpuStack:
         self.W = {nm: torch.from_numpy(params[nm]).to("cuda", self.dt) for nm in self.names}
         self.ids = torch.from_numpy(ids.reshape(-1)).cuda()
         self.tgt = torch.from_numpy(ostack.shifted_targets(ids).astype(np.int32)).cuda()
+        self.gains = {nm: torch.from_numpy(params[nm]).cuda() for nm in ostack.gain_names(params)}      # fp32
         self.B = {}
         self.L = {}
 
@@ -57,32 +59,46 @@ class GpuStack:
             self.ctx.perturbed_forward(L, W, x, self.B[nm], seeds[nm], sign * eps, Y, loss, loss_dev)
         return Y
 
-    def rms(self, h):
+    def rms(self, h, name):
         x = h.double()
-        return (x * torch.rsqrt(x.pow(2).mean(dim=1, keepdim=True) + 1e-6)).to(self.dt)
+        y = x * torch.rsqrt(x.pow(2).mean(dim=1, keepdim=True) + 1e-6)
+        if name in self.gains:
+            y = y * self.gains[name].double()[None, :]
+        return y.to(self.dt)
 
     def run_pass(self, sign, eps, seeds, loss_dev):
         # the glue is evaluated in fp64 and rounded once to the storage type, like the oracle's, so that the
         # comparison is about the library's layers
         h = self.E[self.ids]
         for b in range(self.nb):
-            n = self.rms(h)
+            n = self.rms(h, ("norm", b))
             a = self.linear(("gate", b), n, sign, eps, seeds)
             u = self.linear(("up", b), n, sign, eps, seeds)
             m = (torch.nn.functional.silu(a.double()) * u.double()).to(self.dt)
             d = self.linear(("down", b), m, sign, eps, seeds)
             h = (h.double() + d.double()).to(self.dt)
-        self.linear(("head", 0), self.rms(h), sign, eps, seeds, loss_dev)
+        self.linear(("head", 0), self.rms(h, ("norm_f", 0)), sign, eps, seeds, loss_dev)
 
     def step(self, eps, lr, seeds, flags=0):
         out = torch.zeros(4, dtype=torch.float64, device="cuda")
+        def sweep_gains(scale, g_dev=None):
+            # Alg. 2 for parameters that are not linear-layer weights: perturbed in place, restored, updated
+            for nm, gv in self.gains.items():
+                self.ctx.dense_perturb(gv, seeds[nm], scale, g_dev)
+
         self.run_pass(0, eps, seeds, out[0:1])
+        sweep_gains(+eps)
         self.run_pass(+1, eps, seeds, out[1:2])
-        if not (flags & binding.ONE_SIDED):
+        if flags & binding.ONE_SIDED:
+            sweep_gains(-eps)
+        else:
+            sweep_gains(-2.0 * eps)
             self.run_pass(-1, eps, seeds, out[2:3])
+            sweep_gains(+eps)
         self.ctx.two_point(out, eps, flags)
         for nm in self.names:
             self.ctx.update(self.L[nm], self.W[nm], self.B[nm], seeds[nm], lr, out[3:4])
+        sweep_gains(-lr, out[3:4])
         self.ctx.check()
         return out.cpu().numpy()
 
@@ -96,7 +112,7 @@ def ctx():
 
 @pytest.fixture(scope="module")
 def reduced_stack():
-    return synth.mlp_stack_problem(31, n_blocks=2, hidden=2048, inter=6144, vocab=32000, n_seq=2, seq_len=128)
+    return synth.mlp_stack_problem(31, n_blocks=2, hidden=2048, inter=6144, vocab=32000, n_seq=2, seq_len=128, gains=True)
 
 
 # g is a difference of two ~10-sized losses.  With bf16 storage every stored activation is a rounding point, and where
@@ -118,7 +134,7 @@ def test_reduced_mlp_stack_step_matches_oracle(ctx, reduced_stack, storage, eps,
     eps = float(np.float32(eps))
     params, ids = reduced_stack
     names = ostack.layer_names(2)
-    seeds = {nm: 7000 + i for i, nm in enumerate(names)}
+    seeds = {nm: 7000 + i for i, nm in enumerate(names + ostack.gain_names(params))}
     one_sided = bool(flags & binding.ONE_SIDED)
     o = ostack.agzo_stack_step(params, ids, R, K, eps, LR, seeds, act=storage, storage=storage, one_sided=one_sided)
     g_stack = GpuStack(ctx, params, ids, storage)
@@ -135,6 +151,13 @@ def test_reduced_mlp_stack_step_matches_oracle(ctx, reduced_stack, storage, eps,
         assert abs(got[2] - o["Lm"]) < tol_l * o["Lm"]
     floor_g = floor_l * o["L0"] / (eps if one_sided else 2.0 * eps) * 2.0 ** 0.5
     assert abs(got[3] - o["g"]) < tol_g * abs(o["g"]) + floor_g, (got[3], o["g"], floor_g)
+    # the gains moved along their dense directions by the same g (fp32, perturbed and restored in place)
+    for nm in ostack.gain_names(params):
+        got_gain = g_stack.gains[nm].double().cpu().numpy()
+        want_gain = params[nm].astype(np.float64) - LR * got[3] * o["Z"][nm]
+        assert np.abs(got_gain - want_gain).max() < 1e-6, nm
+        assert np.abs(got_gain - params[nm]).max() > 1e-5, nm
+        assert rel(got_gain - params[nm], o["W_new"][nm] - params[nm]) < tol_g + floor_g / abs(o["g"]), nm
     # the update: every layer moved along its own direction by the one global g
     for nm in names:
         Wg = g_stack.W[nm].double().cpu().numpy()

@@ -226,3 +226,51 @@ def test_bf16_storage_and_inplace_schedule():
     c = agzo.agzo_step_inplace(W64, X64, T, out["B"], 1e-3, 1e-2, 5, storage="bf16")
     np.testing.assert_array_equal(c["Wp"], agzo.round_bf16(W64 + 1e-3 * out["Z"]))
     assert c["L0"] == out["L0"]
+
+
+# --- Eq. 7, second branch: dense Gaussian perturbation of other parameters ---------------------
+def test_dense_branch_moments_and_stream_separation():
+    R = agzo.dense_perturbation(9, 512, 512)
+    n = R.size
+    assert abs(R.mean()) < 4.0 / math.sqrt(n)
+    assert abs(R.var() - 1.0) < 4.0 * math.sqrt(2.0 / n)
+    assert abs((R ** 4).mean() - 3.0) < 4.0 * math.sqrt(96.0 / n)
+    G = agzo.gaussian_factor(9, 512, 512)             # same seed, the linear branch's stream
+    assert abs((R * G).mean()) < 4.0 / math.sqrt(n)   # the two streams are uncorrelated
+    assert not np.array_equal(R[:4, :4], agzo.dense_perturbation(10, 4, 4))
+    # a block's values do not depend on how many rows or columns are asked for
+    np.testing.assert_array_equal(R[:7, :9], agzo.dense_perturbation(9, 7, 9))
+
+
+def test_dense_sweeps_compose_and_restore():
+    rng = np.random.default_rng(3)
+    th = rng.standard_normal((6, 10)).astype(np.float32).astype(np.float64)
+    eps = 1e-3
+    R = agzo.dense_perturbation(21, 6, 10)
+    plus = agzo.dense_apply(th, 21, eps, "f32")
+    np.testing.assert_allclose(plus, th + eps * R, rtol=0, atol=2.0 ** -23 * np.abs(th).max())
+    back = agzo.dense_apply(agzo.dense_apply(plus, 21, -2 * eps, "f32"), 21, eps, "f32")
+    assert np.abs(back - th).max() <= 2.0 ** -22 * np.abs(th).max()          # restored up to fp32 rounding
+    # a 1-D block is one row of the same stream
+    v = agzo.dense_apply(th[0], 21, 0.5, "f32")
+    np.testing.assert_array_equal(v, agzo.dense_apply(th[:1], 21, 0.5, "f32")[0])
+    # bf16 storage: a perturbation below half an ulp is swallowed, one well above it is not
+    w = synth.to_bf16_values(np.full((4, 8), 0.02, dtype=np.float32)).astype(np.float64)
+    np.testing.assert_array_equal(agzo.dense_apply(w, 5, 1e-7, "bf16"), w)
+    assert (agzo.dense_apply(w, 5, 1e-2, "bf16") != w).mean() > 0.9
+
+
+def test_dense_two_point_estimator_mean_is_the_gradient():
+    # f(theta) = 0.5 |theta - a|^2: the central difference along R is exactly <grad, R>, and E[<grad, R> R] = grad
+    rng = np.random.default_rng(8)
+    th, a = rng.standard_normal((2, 5)), rng.standard_normal((2, 5))
+    f = lambda t: 0.5 * float(((t - a) ** 2).sum())
+    eps, n = 1e-3, 6000
+    acc = np.zeros_like(th)
+    for s in range(n):
+        R = agzo.dense_perturbation(1000 + s, 2, 5)
+        g = (f(th + eps * R) - f(th - eps * R)) / (2 * eps)
+        assert abs(g - float(((th - a) * R).sum())) < 1e-9
+        acc += g * R
+    err = np.linalg.norm(acc / n - (th - a)) / np.linalg.norm(th - a)
+    assert err < 4.0 * math.sqrt((th.size + 1.0) / n)

@@ -20,12 +20,13 @@ from paper_2601_17261_amd import synth
 R, K = 4, 2
 
 
-def small():
-    return synth.mlp_stack_problem(11, n_blocks=2, hidden=48, inter=80, vocab=67, n_seq=3, seq_len=17)
+def small(gains=False):
+    return synth.mlp_stack_problem(11, n_blocks=2, hidden=48, inter=80, vocab=67, n_seq=3, seq_len=17, gains=gains)
 
 
 def seeds_for(params, step=0):
-    return {nm: 1000 * step + i for i, nm in enumerate(ostack.layer_names(params["n_blocks"]))}
+    every = ostack.layer_names(params["n_blocks"]) + ostack.gain_names(params)
+    return {nm: 1000 * step + i for i, nm in enumerate(every)}
 
 
 def torch_loss(params, ids, weights):
@@ -33,10 +34,10 @@ def torch_loss(params, ids, weights):
     ids_t = torch.from_numpy(ids.reshape(-1))
     h = torch.from_numpy(params["E"].astype(np.float64))[ids_t]
     for b in range(params["n_blocks"]):
-        n = F.rms_norm(h, (h.shape[1],), eps=1e-6)
+        n = F.rms_norm(h, (h.shape[1],), weight=weights.get(("norm", b)), eps=1e-6)
         m = F.silu(F.linear(n, weights[("gate", b)])) * F.linear(n, weights[("up", b)])
         h = h + F.linear(m, weights[("down", b)])
-    logits = F.linear(F.rms_norm(h, (h.shape[1],), eps=1e-6), weights[("head", 0)])
+    logits = F.linear(F.rms_norm(h, (h.shape[1],), weight=weights.get(("norm_f", 0)), eps=1e-6), weights[("head", 0)])
     tgt = torch.from_numpy(ostack.shifted_targets(ids))
     return F.cross_entropy(logits, tgt, ignore_index=-1)
 
@@ -67,6 +68,31 @@ def test_g_is_the_directional_derivative_along_the_joint_perturbation():
     o1 = ostack.agzo_stack_step(params, ids, R, K, 1e-4, 0.0, seeds, act=None, storage="f32", one_sided=True)
     assert abs(o1["g"] - want) < 5e-2 * abs(want) and o1["Lm"] == 0.0
     assert abs(o1["g"] - want) > abs(o["g"] - want)          # the one-sided form carries the O(eps) term
+
+
+def test_gains_take_the_dense_branch_with_the_same_global_g():
+    params, ids = small(gains=True)
+    every = ostack.layer_names(2) + ostack.gain_names(params)
+    assert len(ostack.gain_names(params)) == 3
+    seeds = seeds_for(params)
+    w = {nm: torch.from_numpy(params[nm].astype(np.float64)).requires_grad_(True) for nm in every}
+    loss = torch_loss(params, ids, w)
+    assert abs(ostack.forward(params, ids, act=None) - loss.item()) < 1e-12 * loss.item()
+    loss.backward()
+    lr = 0.01
+    o = ostack.agzo_stack_step(params, ids, R, K, 1e-4, lr, seeds, act=None, storage="f32")
+    want = sum(float((w[nm].grad.numpy() * o["Z"][nm]).sum()) for nm in every)
+    assert abs(o["g"] - want) < 1e-5 * abs(want)
+    gain_part = sum(float((w[nm].grad.numpy() * o["Z"][nm]).sum()) for nm in ostack.gain_names(params))
+    assert abs(gain_part) > 1e-3 * abs(want)                   # the gains' share of the derivative is not negligible
+    for nm in ostack.gain_names(params):
+        Rg = oagzo.dense_perturbation(seeds[nm], 1, 48)[0]     # a dense direction of the gain's own shape
+        np.testing.assert_array_equal(o["Z"][nm], Rg)
+        np.testing.assert_allclose(o["W_new"][nm], params[nm] - lr * o["g"] * Rg, rtol=0, atol=1e-7)
+    # without gains in params the model is the gain-free one
+    p0, _ = small(gains=False)
+    for nm in ostack.layer_names(2):
+        np.testing.assert_array_equal(p0[nm], params[nm])
 
 
 def test_bases_come_from_each_layers_own_unperturbed_input():
