@@ -83,7 +83,7 @@ inline int64_t round32(int64_t n) { return (n + 31) / 32 * 32; }
 
 // carve-out of the ctx workspace for one layer; everything a step can need at the same time
 struct Plan {
-    size_t off_S, off_Q, off_B, off_pack, off_T, off_TpackT, off_xtt, off_qr, off_part, off_Ybuf, off_ce_ms, off_ce_tl, off_upd, off_ext, total;
+    size_t off_S, off_Q, off_B, off_pack, off_T, off_TpackT, off_xtt, off_qr, off_part, off_Ybuf, off_ce_ms, off_ce_tl, off_upd, off_ext, off_xqpart, total;
     int rp, nsplit;
     int64_t m_pad;
     int n_part;
@@ -117,6 +117,7 @@ Plan make_plan(const agzo_layer& L, bool need_ybuf, bool ce = false) {
     p.off_ce_tl = take((ce && bf) ? (size_t)3 * L.n_tokens * 4 : 0);
     p.off_upd = take(update_workspace_bytes(L.dtype, L.d_out, L.d_in, L.r));
     p.off_ext = take(bf ? gemm_bf16_ext_bytes(L.n_tokens, L.d_out, L.r) : 0);
+    p.off_xqpart = take(bf ? xq_part_bytes(L.n_tokens, L.d_in, p.rp) : 0);
     p.off_Ybuf = take(need_ybuf ? (size_t)L.n_tokens * L.d_out * 4 : 0);
     p.total = o;
     return p;
@@ -209,7 +210,7 @@ int sketch_power(agzo_ctx* ctx, const agzo_layer& L, const Plan& p, const void* 
         {
             ProfScope ps(ctx, AGZO_PROF_XQ);
             HIPCHK(launch_xq_bf16(static_cast<const bf16_t*>(X), L.ldx, L.n_tokens, L.d_in, wsh(ctx, p.off_pack), L.r,
-                                  p.rp, nullptr, wsh(ctx, p.off_TpackT), p.m_pad, st));
+                                  p.rp, nullptr, wsh(ctx, p.off_TpackT), p.m_pad, wsf(ctx, p.off_xqpart), st));
         }
         ProfScope ps(ctx, AGZO_PROF_XTT);
         HIPCHK(launch_xtt_bf16(static_cast<const bf16_t*>(X), L.ldx, L.n_tokens, L.d_in, wsh(ctx, p.off_TpackT),
@@ -253,7 +254,7 @@ int op_project(agzo_ctx* ctx, const agzo_layer& L, const Plan& p, const void* X,
         if (!planes_ready) HIPCHK(launch_pack_planes(B, L.d_in, L.r, p.rp, wsh(ctx, p.off_pack), st));
         ProfScope ps(ctx, AGZO_PROF_XQ);
         HIPCHK(launch_xq_bf16(static_cast<const bf16_t*>(X), L.ldx, L.n_tokens, L.d_in, wsh(ctx, p.off_pack), L.r, p.rp,
-                              P, nullptr, p.m_pad, st));
+                              P, nullptr, p.m_pad, wsf(ctx, p.off_xqpart), st));
     } else {
         HIPCHK(launch_gemm_f32(static_cast<const float*>(X), L.ldx, 1, B, L.r, 1, P, L.r, L.n_tokens, L.r, L.d_in, st));
     }

@@ -138,8 +138,10 @@ hipError_t launch_epilogue_f32(float* Y, int64_t ldy, int64_t M, int64_t N, cons
 // skinny.hip : bf16 tall-skinny products
 // T = X Qp, Qp given as bf16 planes [3][rp][d_in]; writes T fp32 [M][r] (nullable) and
 // T^T planes bf16 [3][rp][m_pad] (nullable)
+// part: xq_part_bytes() bytes of scratch for the split over d_in that small token counts take (NULL: never split)
+size_t xq_part_bytes(int64_t M, int64_t K, int rp);
 hipError_t launch_xq_bf16(const bf16_t* X, int64_t ldx, int64_t M, int64_t K, const bf16_t* Qpack, int r, int rp,
-                          float* T, bf16_t* TpackT, int64_t m_pad, hipStream_t st);
+                          float* T, bf16_t* TpackT, int64_t m_pad, float* part, hipStream_t st);
 int xtt_num_splits(int64_t M, int64_t K);
 // partial[s][d][rp] = sum over token range s of X[t][d] * T[t][k]
 hipError_t launch_xtt_bf16(const bf16_t* X, int64_t ldx, int64_t M, int64_t K, const bf16_t* TpackT, int64_t m_pad,

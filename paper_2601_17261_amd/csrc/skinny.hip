@@ -49,7 +49,7 @@ __device__ __forceinline__ void wait_vmcnt_dyn(int n) {
 template <int NB>
 __global__ __launch_bounds__(256) void xq_bf16_kernel(const bf16_t* __restrict__ X, int64_t ldx, int64_t M, int64_t K,
                                                       const bf16_t* __restrict__ Qpack, int r, float* __restrict__ T,
-                                                      bf16_t* __restrict__ TpackT, int64_t m_pad) {
+                                                      bf16_t* __restrict__ TpackT, int64_t m_pad, float* __restrict__ part) {
     constexpr int RP = NB * 16;
     constexpr int QROWS = 3 * RP;                          // plane rows: (plane, k)
     constexpr int NGROUP = XQ_TOK / 8 + QROWS / 8;         // 8-row groups per slice: X first, then the planes
@@ -79,14 +79,19 @@ __global__ __launch_bounds__(256) void xq_bf16_kernel(const bf16_t* __restrict__
         if (row < XQ_TOK) src[i] = X + min(t0 + row, M - 1) * ldx + c * 8;
         else src[i] = Qpack + (int64_t)(row - XQ_TOK) * K + c * 8;
     }
-    const int nfull = (int)(K / XQ_BK);
-    const bool tail = (K % XQ_BK) != 0;
+    // few tokens: gridDim.y workgroups share a token block, each taking a contiguous run of d_in slices, and leave
+    // partial sums in `part` for xq_finish_kernel (a single workgroup per block would walk d_in alone, bound by latency)
+    const int nsplit = (int)gridDim.y, split = (int)blockIdx.y;
+    const int nfull_all = (int)(K / XQ_BK);
+    const int kbeg = (int)((int64_t)nfull_all * split / nsplit);
+    const int nfull = (int)((int64_t)nfull_all * (split + 1) / nsplit) - kbeg;      // this workgroup's slices
+    const bool tail = (K % XQ_BK) != 0 && split == nsplit - 1;
     auto issue = [&](int kt, int slot) __attribute__((always_inline)) {
         char* base = xq_smem + slot * SLOT + wave * 1024;
 #pragma unroll
         for (int i = 0; i < MAXG; ++i)
             if (i < ng)
-                __builtin_amdgcn_global_load_lds((gptr_t)(src[i] + (int64_t)kt * XQ_BK), (lptr_t)(base + i * 4096), 16, 0, 0);
+                __builtin_amdgcn_global_load_lds((gptr_t)(src[i] + (int64_t)(kbeg + kt) * XQ_BK), (lptr_t)(base + i * 4096), 16, 0, 0);
     };
     // Fragment reads go through inline assembly: for a plain LDS load the compiler, which cannot tell the ring's slots
     // apart, first waits for every direct load in flight (vmcnt(0)) and so collapses the ring to one slice.  The
@@ -157,7 +162,7 @@ __global__ __launch_bounds__(256) void xq_bf16_kernel(const bf16_t* __restrict__
         char* base = xq_smem;                              // slot 0 (all loads have landed and were consumed)
         for (int e = tid; e < (XQ_TOK + QROWS) * 8; e += 256) {
             const int row = e >> 3, c = e & 7;
-            const int64_t kcol = (int64_t)nfull * XQ_BK + c * 8;
+            const int64_t kcol = (int64_t)nfull_all * XQ_BK + c * 8;
             uint4 v = make_uint4(0, 0, 0, 0);
             if (kcol < K) {
                 const bf16_t* p = (row < XQ_TOK) ? X + min(t0 + row, M - 1) * ldx + kcol
@@ -170,6 +175,16 @@ __global__ __launch_bounds__(256) void xq_bf16_kernel(const bf16_t* __restrict__
         multiply(0, false);
     }
     // D layout: row (token) = 4*(lane/16) + e, col (k) = lane%16
+    if (part != nullptr) {
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int64_t t = t0 + wave * 16 + lg * 4 + e;
+                if (t < m_pad) part[((int64_t)split * m_pad + t) * RP + nb * 16 + lm] = acc[nb][e];
+            }
+        return;
+    }
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
         const int k = nb * 16 + lm;
@@ -189,9 +204,47 @@ __global__ __launch_bounds__(256) void xq_bf16_kernel(const bf16_t* __restrict__
     }
 }
 
+// sums the d_in splits of xq in fixed order and writes what the unsplit kernel's epilogue writes; one thread per (t, k)
+__global__ __launch_bounds__(256) void xq_finish_kernel(const float* __restrict__ part, int nsplit, int64_t rows, int64_t M,
+                                                        int64_t m_pad, int r, int rp, float* __restrict__ T,
+                                                        bf16_t* __restrict__ TpackT) {
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= rows * rp) return;
+    const int64_t t = idx / rp;
+    const int k = (int)(idx - t * rp);
+    float v = 0.f;
+    if (t < M && k < r)
+        for (int s = 0; s < nsplit; ++s) v += part[((int64_t)s * m_pad + t) * rp + k];
+    if (t < M && k < r && T != nullptr) T[t * r + k] = v;
+    if (TpackT != nullptr && t < m_pad) {
+        bf16_t hi, mid, lo;
+        split3_bf16(v, hi, mid, lo);
+        TpackT[((int64_t)0 * rp + k) * m_pad + t] = hi;
+        TpackT[((int64_t)1 * rp + k) * m_pad + t] = mid;
+        TpackT[((int64_t)2 * rp + k) * m_pad + t] = lo;
+    }
+}
+
+// number of d_in splits for M tokens (1 = the token blocks alone fill the chip, or d_in is too short to share)
+static int xq_splits(int64_t rows, int64_t K) {
+    const int64_t blocks = (rows + XQ_TOK - 1) / XQ_TOK;
+    const int64_t slices = K / XQ_BK;
+    if (blocks >= 128 || slices < 16) return 1;
+    int64_t want = 256 / blocks;
+    if (want > slices / 8) want = slices / 8;      // at least eight slices each: the depth of the load ring
+    if (want > 16) want = 16;
+    return (int)(want < 1 ? 1 : want);
+}
+
+size_t xq_part_bytes(int64_t M, int64_t K, int rp) {
+    const int64_t m_pad = (M + 31) / 32 * 32;
+    const int ns = xq_splits(m_pad, K);
+    return ns > 1 ? (size_t)ns * m_pad * rp * sizeof(float) : 0;
+}
+
 template <int NB>
 static hipError_t launch_xq_nb(dim3 grid, hipStream_t st, const bf16_t* X, int64_t ldx, int64_t M, int64_t K,
-                               const bf16_t* Qpack, int r, float* T, bf16_t* TpackT, int64_t m_pad) {
+                               const bf16_t* Qpack, int r, float* T, bf16_t* TpackT, int64_t m_pad, float* part) {
     constexpr int stages = (NB == 1) ? 8 : (NB == 2) ? 6 : 4;
     const int smem = stages * (XQ_TOK + 3 * NB * 16) * 128;
     static bool set = false;
@@ -201,23 +254,31 @@ static hipError_t launch_xq_nb(dim3 grid, hipStream_t st, const bf16_t* X, int64
         if (e != hipSuccess) return e;
         set = true;
     }
-    hipLaunchKernelGGL(xq_bf16_kernel<NB>, grid, dim3(256), smem, st, X, ldx, M, K, Qpack, r, T, TpackT, m_pad);
+    hipLaunchKernelGGL(xq_bf16_kernel<NB>, grid, dim3(256), smem, st, X, ldx, M, K, Qpack, r, T, TpackT, m_pad, part);
     return hipGetLastError();
 }
 
 hipError_t launch_xq_bf16(const bf16_t* X, int64_t ldx, int64_t M, int64_t K, const bf16_t* Qpack, int r, int rp,
-                          float* T, bf16_t* TpackT, int64_t m_pad, hipStream_t st) {
+                          float* T, bf16_t* TpackT, int64_t m_pad, float* part, hipStream_t st) {
     if (M == 0) return hipSuccess;
     // cover the padded token range too so that the planes' tail is zeroed
     const int64_t rows = TpackT ? m_pad : M;
-    dim3 grid((unsigned)((rows + XQ_TOK - 1) / XQ_TOK));
+    // the split is sized for the padded range, which is what the workspace was sized for
+    const int ns = part ? xq_splits(m_pad, K) : 1;
+    dim3 grid((unsigned)((rows + XQ_TOK - 1) / XQ_TOK), (unsigned)ns);
+    float* p = ns > 1 ? part : nullptr;
+    hipError_t e;
     switch (rp / 16) {
-        case 1: return launch_xq_nb<1>(grid, st, X, ldx, M, K, Qpack, r, T, TpackT, m_pad);
-        case 2: return launch_xq_nb<2>(grid, st, X, ldx, M, K, Qpack, r, T, TpackT, m_pad);
-        case 3: return launch_xq_nb<3>(grid, st, X, ldx, M, K, Qpack, r, T, TpackT, m_pad);
-        case 4: return launch_xq_nb<4>(grid, st, X, ldx, M, K, Qpack, r, T, TpackT, m_pad);
+        case 1: e = launch_xq_nb<1>(grid, st, X, ldx, M, K, Qpack, r, T, TpackT, m_pad, p); break;
+        case 2: e = launch_xq_nb<2>(grid, st, X, ldx, M, K, Qpack, r, T, TpackT, m_pad, p); break;
+        case 3: e = launch_xq_nb<3>(grid, st, X, ldx, M, K, Qpack, r, T, TpackT, m_pad, p); break;
+        case 4: e = launch_xq_nb<4>(grid, st, X, ldx, M, K, Qpack, r, T, TpackT, m_pad, p); break;
         default: return hipErrorInvalidValue;
     }
+    if (e != hipSuccess || ns == 1) return e;
+    const int64_t items = rows * rp;
+    hipLaunchKernelGGL(xq_finish_kernel, dim3((unsigned)((items + 255) / 256)), dim3(256), 0, st, p, ns, rows, M, m_pad, r, rp, T, TpackT);
+    return hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------

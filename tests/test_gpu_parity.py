@@ -119,6 +119,8 @@ CASES = [
     ("bf16", 515, 136, 300, 24, "powerlaw", 2e-5),
     ("bf16", 700, 320, 264, 40, "powerlaw", 2e-5),      # three 16-column blocks in every rank-r kernel
     ("bf16", 450, 192, 520, 64, "rmsnorm", 2e-5),       # the largest rank
+    ("bf16", 200, 4136, 72, 16, "rmsnorm", 2e-5),       # few tokens, deep d_in with a ragged end: X Q splits d_in 8 ways
+    ("bf16", 1100, 2048, 136, 40, "powerlaw", 2e-5),    # 18 token blocks x 4 splits, three 16-column blocks
 ]
 
 
