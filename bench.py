@@ -144,6 +144,9 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (known traffic) so counter runs can be scaled")
     ap.add_argument("--sweep", action="store_true", help="rank x tokens sweep on Qwen3-4B shapes (text table)")
+    ap.add_argument("--workload", choices=["qwen3-8b", "qwen3-0.6b"], default="qwen3-8b",
+                    help="layer set: qwen3-8b is the benchmark configuration; qwen3-0.6b (use --tokens 2048 --rank 8) is the "
+                         "small launch-bound one")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives are part of it); use --gpus 1",
@@ -158,7 +161,7 @@ def main():
         return
     N, r, K = args.tokens, args.rank, 3
     eps, lr = float(np.float32(1e-3)), float(np.float32(1e-4))
-    shapes = synth.QWEN3_8B_LAYER
+    shapes = synth.QWEN3_8B_LAYER if args.workload == "qwen3-8b" else synth.QWEN3_0P6B_LAYER
     layers = build_layer_set(N, shapes, seed=0)
     ctx = binding.Context()
     descs = []
@@ -234,8 +237,8 @@ def main():
         "value": args.steps / dt, "unit": "steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": 1e3 * dt / args.steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "qwen3-8b layer projections (q,k,v,o,gate,up,down), N=%d tokens, r=%d, K=%d, "
-                               "bf16 weights/activations, MSE loss, %s" % (N, r, K, "naive in-place comparator" if args.naive else "factored perturbed forward"),
+        "config": {"workload": args.workload + " layer projections (q,k,v,o,gate,up,down), N=%d tokens, r=%d, K=%d, "
+                               "bf16 weights/activations/targets, MSE loss, %s" % (N, r, K, "naive in-place comparator" if args.naive else "factored perturbed forward"),
                    "tokens": N, "rank": r, "power_steps": K, "eps": eps, "lr": lr},
         "roofline": {"bound": "mfma", "kernel": "gemm_bf16_kernel", "achieved": gemm_tflops, "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": gemm_tflops / PEAK_BF16_TFLOPS, "traffic": traffic,

@@ -282,10 +282,11 @@ __global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
                 for (int q = 0; q < 2; ++q) traw[j >> 1][i][2 * (j & 1) + q] = src[i * 4 + q];
         }
     };
-    // issued ahead of the last multiply before the evaluation that reads the target
+    // issued ahead of the last multiply before the evaluation that reads the target: 64 registers' worth (one fp32
+    // token block, two bf16 ones); more would not fit beside the multiply's fragments and spill
     auto tload_first = [&]() __attribute__((always_inline)) {
         tload(IC<0>{});
-        if (FAST && !T_F32) { tload(IC<1>{}); tload(IC<2>{}); tload(IC<3>{}); }
+        if (FAST && !T_F32) tload(IC<1>{});
     };
     // ---- multiply ---------------------------------------------------------------------------------
     // per-lane LDS byte offsets of this wave's fragments for the four 16-wide sub-steps of a slice; block i of an
@@ -581,6 +582,7 @@ __global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
                 fast_block(IC<2>{}, IC<1>{});
                 fast_block(IC<3>{}, IC<1>{});
             } else {
+                if (!resid) { tload(IC<2>{}); tload(IC<3>{}); }
                 fast_block(IC<0>{}, IC<0>{});
                 fast_block(IC<1>{}, IC<0>{});
                 fast_block(IC<2>{}, IC<0>{});

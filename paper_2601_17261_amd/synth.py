@@ -125,8 +125,9 @@ def device_powerlaw_x(seed, n, d_in, device="cuda", n_outliers=5, outlier_scale=
     return X.to(torch.bfloat16)
 
 
-def device_weights_and_target(seed, X, d_out, device="cuda"):
-    """bf16 W ~ N(0, 0.02^2) and the fp32 MSE target Y* = X W*^T, W* = W + rank-4 shift (entry std 0.05)."""
+def device_weights_and_target(seed, X, d_out, device="cuda", target_dtype=torch.bfloat16):
+    """bf16 W ~ N(0, 0.02^2) and the MSE target Y* = X W*^T, W* = W + rank-4 shift (entry std 0.05), stored in
+    `target_dtype` (bf16 like every other tensor of the bf16 configurations, or fp32)."""
     gen = torch.Generator(device=device)
     gen.manual_seed(int(seed))
     f32 = dict(device=device, dtype=torch.float32, generator=gen)
@@ -136,7 +137,7 @@ def device_weights_and_target(seed, X, d_out, device="cuda"):
     Q = torch.randn(d_in, 4, **f32)
     Wstar = W.float() + (0.05 / 2.0) * (P @ Q.T)
     Ystar = X.float() @ Wstar.T
-    return W, Ystar
+    return W, Ystar.to(target_dtype)
 
 
 def mlp_stack_problem(seed, n_blocks, hidden, inter, vocab, n_seq, seq_len, emb_rank=16, gains=False):
