@@ -5,14 +5,23 @@
 
 namespace agzo {
 
+// this thread's share of sum(p[0..n)) for a 256-thread workgroup: four independent strided sums keep four loads in
+// flight (the finishing kernels are one workgroup each, bound by latency); the order is fixed
+__device__ __forceinline__ double strided_sum4(const double* __restrict__ p, int n, int tid) {
+    double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+    int i = tid;
+    for (; i + 768 < n; i += 1024) {
+        s0 += p[i]; s1 += p[i + 256]; s2 += p[i + 512]; s3 += p[i + 768];
+    }
+    for (; i < n; i += 256) s0 += p[i];
+    return (s0 + s1) + (s2 + s3);
+}
+
 __global__ __launch_bounds__(256) void finish_loss_kernel(const double* __restrict__ partials, int n, double scale,
                                                           double* __restrict__ out) {
     __shared__ double red[256];
     const int tid = threadIdx.x;
-    double s = 0.0;
-    partials += (int64_t)blockIdx.x * n;
-    for (int i = tid; i < n; i += 256) s += partials[i];
-    red[tid] = s;
+    red[tid] = strided_sum4(partials + (int64_t)blockIdx.x * n, n, tid);
     __syncthreads();
     for (int k = 128; k > 0; k >>= 1) {
         if (tid < k) red[tid] += red[tid + k];
@@ -43,10 +52,7 @@ __global__ __launch_bounds__(256) void finish_two_point_kernel(const double* __r
     __shared__ double loss[3];
     const int tid = threadIdx.x;
     for (int ph = 0; ph < nphase; ++ph) {
-        double s = 0.0;
-        const double* p = partials + (int64_t)ph * n;
-        for (int i = tid; i < n; i += 256) s += p[i];
-        red[tid] = s;
+        red[tid] = strided_sum4(partials + (int64_t)ph * n, n, tid);
         __syncthreads();
         for (int k = 128; k > 0; k >>= 1) {
             if (tid < k) red[tid] += red[tid + k];
