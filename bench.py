@@ -116,7 +116,7 @@ def sweep(args):
                 rows = []
                 us = timed(binding.PROF_GEMM, lambda: ctx.perturbed_forward(L, W, X, B, 5, eps, None, loss, sc[1:2]))
                 rows.append(("pfwd+loss", us, 2.0 * N * d_in * d_out + 2.0 * N * r * (d_in + d_out),
-                             2.0 * N * d_in + 2.0 * d_in * d_out + 4.0 * N * d_out))
+                             2.0 * N * d_in + 2.0 * d_in * d_out + T.element_size() * float(N) * d_out))
                 us = timed(binding.PROF_XQ, lambda: ctx.layer_forward_sketch(L, None, X, None, 2, B, 5, B.clone(), None, None))
                 rows.append(("xq", us, 2.0 * N * d_in * r, 2.0 * N * d_in))
                 us = timed(binding.PROF_XTT, lambda: ctx.layer_forward_sketch(L, None, X, None, 1, None, 5, B.clone(), None, None))

@@ -42,9 +42,10 @@ def x4096():
     return synth.device_powerlaw_x(101, N, 4096)
 
 
-@pytest.mark.parametrize("name,d_out,target_dtype", [("k", 1024, torch.bfloat16), ("k", 1024, torch.float32),
-                                                     ("q", 4096, torch.bfloat16)])
-def test_full_step_against_full_oracle(ctx, x4096, name, d_out, target_dtype):
+@pytest.mark.parametrize("name,d_out,target_dtype,R", [("k", 1024, torch.bfloat16, 16), ("k", 1024, torch.float32, 16),
+                                                       ("q", 4096, torch.bfloat16, 16),
+                                                       ("k", 1024, torch.bfloat16, 64)])      # the largest rank
+def test_full_step_against_full_oracle(ctx, x4096, name, d_out, target_dtype, R):
     X = x4096
     W, T = synth.device_weights_and_target(7 + d_out, X, d_out, target_dtype=target_dtype)
     W0 = host(W)

@@ -470,3 +470,37 @@ def test_dense_perturb_matches_oracle(ctx, storage, shape):
         ctx._rc(ctx.lib.agzo_dense_perturb(ctx.h, None, 0, 4, 4, 2, 1, 1.0, None))
     assert e.value.code == binding.EINVAL
     ctx.check()
+
+
+# ---------------------------------------------------------------------------------------------
+# degenerate shapes: a single token, rank equal to the token count or to d_in, no power steps
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("storage,n,d_in,d_out,r", [("bf16", 1, 8, 1, 1), ("bf16", 8, 8, 8, 8), ("bf16", 16, 64, 264, 16),
+                                                     ("bf16", 40, 16, 3, 16), ("f32", 1, 1, 1, 1), ("f32", 2, 3, 1, 2),
+                                                     ("f32", 5, 4, 7, 4)])
+@pytest.mark.parametrize("K", [0, 2])
+def test_degenerate_shapes_step(ctx, storage, n, d_in, d_out, r, K):
+    seed = 17
+    rng = np.random.default_rng(100 * n + d_in)
+    X = synth.x_rmsnorm_gaussian(rng, n, d_in, storage=storage)
+    W = synth.weights(rng, d_out, d_in, std=0.3, storage=storage)
+    T = rng.standard_normal((n, d_out)).astype(np.float32)
+    Wd, Xd, Td = dev(W, storage), dev(X, storage), dev(T)
+    L = binding.make_layer(Wd, Xd, r)
+    out = torch.zeros(4, dtype=torch.float64, device="cuda")
+    lr = float(np.float32(1e-2))
+    ctx.step(L, Wd, Xd, binding.make_loss(Td), K, EPS, lr, seed, 0, out)
+    ctx.check()
+    o = oagzo.agzo_step(W, X, T, r, K, EPS, lr, seed, storage=storage)
+    got = out.cpu().numpy()
+    for i, k in enumerate(("L0", "Lp", "Lm")):
+        assert abs(got[i] - o[k]) < 1e-5 * o[k] + 1e-12, (k, got[i], o[k])
+    gtol = 2e-3 if storage == "f32" else 2e-2
+    # g is a difference of losses: next to the relative bound stands the losses' own rounding, amplified by 1 / (2 eps)
+    assert abs(got[3] - o["g"]) < gtol * abs(o["g"]) + (1e-7 if storage == "f32" else 2e-6) * o["L0"] / EPS, (got[3], o["g"])
+    ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(o["W_new"]), 1e-30))) - (23 if storage == "f32" else 7))
+    incr = lr * abs(o["g"]) * np.abs(o["Z"])
+    assert (np.abs(host(Wd) - o["W_new"]) <= ulp * 1.0001 + (gtol + 1e-3) * incr + 1e-7).all()
+    if r == d_in:
+        # the basis spans the whole input space: the perturbation is then a full d_out x d_in Gaussian in disguise
+        np.testing.assert_allclose(o["B"] @ o["B"].T, np.eye(d_in), atol=1e-10)
