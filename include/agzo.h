@@ -54,6 +54,8 @@ typedef enum {
 /* Philox stream tags: which Gaussian matrix a (seed, tag, row, col) element belongs to. */
 enum { AGZO_TAG_G = 0, AGZO_TAG_OMEGA = 1, AGZO_TAG_Q0 = 2, AGZO_TAG_DENSE = 3 };
 
+enum { AGZO_TILING_AUTO = 0, AGZO_TILING_LARGE = 1 };
+
 /* agzo_step / agzo_basis flags */
 enum {
     AGZO_ONE_SIDED = 1,    /* g = (L+ - L0)/eps, the literal form of Eq. 10 / Alg. 2; default is (L+ - L-)/(2 eps) */
@@ -70,7 +72,8 @@ typedef struct {
     int32_t r;         /* rank of the activation basis, 1..64 */
     int32_t dtype;     /* agzo_dtype of W and X (both the same) */
     int32_t y_dtype;   /* agzo_dtype of Y when stored: F32, or BF16 for bf16 layers */
-    int32_t reserved;
+    int32_t tiling;      /* 0 = the library picks the forward GEMM's tiling from the shape; AGZO_TILING_LARGE = always the
+                          * 256 x 256 tiles (tests and measurements; results are the same to rounding order) */
     int64_t ldw, ldx, ldy;
 } agzo_layer;
 

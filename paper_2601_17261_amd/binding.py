@@ -20,6 +20,7 @@ TAG_G, TAG_OMEGA, TAG_Q0, TAG_DENSE = 0, 1, 2, 3
 ONE_SIDED, NAIVE_INPLACE, INIT_FEATURE, SHARED_FORWARD = 1, 2, 4, 8
 OK, EINVAL, ENOMEM, ENUMERIC, EHIP = 0, -1, -2, -3, -4
 
+TILING_AUTO, TILING_LARGE = 0, 1
 PROF_GEMM, PROF_UPDATE, PROF_XQ, PROF_XTT, PROF_QR, PROF_FILL = range(6)
 PROF_ALL = 63
 
@@ -32,7 +33,7 @@ EXPORTS = ["agzo_create", "agzo_destroy", "agzo_last_error", "agzo_check", "agzo
 class AgzoLayer(ctypes.Structure):
     _fields_ = [("n_tokens", ctypes.c_int64), ("d_in", ctypes.c_int64), ("d_out", ctypes.c_int64),
                 ("r", ctypes.c_int32), ("dtype", ctypes.c_int32), ("y_dtype", ctypes.c_int32),
-                ("reserved", ctypes.c_int32), ("ldw", ctypes.c_int64), ("ldx", ctypes.c_int64),
+                ("tiling", ctypes.c_int32), ("ldw", ctypes.c_int64), ("ldx", ctypes.c_int64),
                 ("ldy", ctypes.c_int64)]
 
 

@@ -9,7 +9,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(ROOT, "_build")
 LIB = os.path.join(PKG, "libagzo.so")
-SOURCES = ["philox.hip", "gemm_f32.hip", "gemm_bf16.hip", "skinny.hip", "qr.hip", "update.hip", "loss.hip",
+SOURCES = ["philox.hip", "gemm_f32.hip", "gemm_bf16.hip", "gemm_bf16_small.hip", "skinny.hip", "qr.hip", "update.hip", "loss.hip",
            "probe.hip", "agzo_api.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # packed-fp32 VALU forms are switched off for every device compile (some forms have misbehaved
@@ -22,7 +22,8 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wno-unused-com
 def _compile(src, force):
     obj = os.path.join(OBJ, src.replace(".hip", ".o"))
     srcp = os.path.join(CSRC, src)
-    deps = [srcp, os.path.join(CSRC, "agzo_internal.h"), os.path.join(ROOT, "include", "agzo.h")]
+    deps = [srcp, os.path.join(CSRC, "agzo_internal.h"), os.path.join(CSRC, "gemm_bf16_common.h"),
+            os.path.join(ROOT, "include", "agzo.h")]
     if not force and os.path.exists(obj) and all(os.path.getmtime(obj) > os.path.getmtime(d) for d in deps):
         return obj, ""
     cmd = [HIPCC] + FLAGS + ["-c", srcp, "-o", obj]

@@ -89,13 +89,13 @@ struct Plan {
     int n_part;
 };
 
-Plan make_plan(const agzo_layer& L, bool need_ybuf, bool ce = false) {
+Plan make_plan(const agzo_layer& L, bool need_ybuf, bool ce = false, bool shared = false) {
     Plan p;
     const bool bf = (L.dtype == AGZO_BF16);
     p.rp = round16(L.r);
     p.m_pad = round32(L.n_tokens);
     p.nsplit = bf ? xtt_num_splits(L.n_tokens, L.d_in) : 1;
-    const int n_gemm = bf ? gemm_bf16_num_workgroups(L.n_tokens, L.d_out) : epilogue_f32_num_workgroups(L.n_tokens, L.d_out);
+    const int n_gemm = bf ? gemm_bf16_num_workgroups(L.n_tokens, L.d_out, !ce && !shared && L.tiling != AGZO_TILING_LARGE) : epilogue_f32_num_workgroups(L.n_tokens, L.d_out);
     p.n_part = n_gemm;
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o += align_up(bytes); return at; };
@@ -148,6 +148,7 @@ int check_layer(agzo_ctx* ctx, const agzo_layer* L, bool need_w) {
     if (L->r < 1 || L->r > kMaxRank) return fail(ctx, AGZO_EINVAL, "r=%d outside 1..%d", L->r, kMaxRank);
     if (L->r > L->n_tokens || L->r > L->d_in) return fail(ctx, AGZO_EINVAL, "r=%d exceeds min(n_tokens, d_in)", L->r);
     if (L->dtype != AGZO_F32 && L->dtype != AGZO_BF16) return fail(ctx, AGZO_EINVAL, "dtype %d", L->dtype);
+    if (L->tiling != AGZO_TILING_AUTO && L->tiling != AGZO_TILING_LARGE) return fail(ctx, AGZO_EINVAL, "tiling %d", L->tiling);
     if (L->ldx < L->d_in || (need_w && L->ldw < L->d_in)) return fail(ctx, AGZO_EINVAL, "leading dimension below d_in");
     if (L->dtype == AGZO_BF16) {
         if (L->d_in % 8 || L->ldx % 8 || (need_w && L->ldw % 8))
@@ -290,6 +291,7 @@ int op_forward(agzo_ctx* ctx, const agzo_layer& L, const Plan& p, const void* W,
         a.P = P; a.r = L.r; a.eps_signed = eps_signed; a.seed = seed;
         a.loss = la;
         a.shared = shared;
+        a.large_tiles = (L.tiling == AGZO_TILING_LARGE);
         a.ext_ws = (P && !shared) ? ctx->ws + p.off_ext : nullptr;
         if (((ctx->prof >> AGZO_PROF_GEMM) & 1u) && ctx->clk_used < kClkSlots) a.clk = ctx->clk + 4 * ctx->clk_used++;
         {
@@ -588,6 +590,7 @@ int agzo_update(agzo_ctx* ctx, const agzo_layer* L, void* W, const float* B, uin
     if (L->d_in < 1 || L->d_out < 1 || L->r < 1 || L->r > kMaxRank || L->r > L->d_in || L->ldw < L->d_in)
         return fail(ctx, AGZO_EINVAL, "bad layer shape");
     if (L->dtype != AGZO_F32 && L->dtype != AGZO_BF16) return fail(ctx, AGZO_EINVAL, "dtype %d", L->dtype);
+    if (L->tiling != AGZO_TILING_AUTO && L->tiling != AGZO_TILING_LARGE) return fail(ctx, AGZO_EINVAL, "tiling %d", L->tiling);
     if (L->dtype == AGZO_BF16 && (L->d_in % 8 || L->ldw % 8 || (reinterpret_cast<uintptr_t>(W) & 15)))
         return fail(ctx, AGZO_EINVAL, "bf16 W needs d_in and ldw multiples of 8 and 16-byte aligned rows");
     TRY(reserve(ctx, update_workspace_bytes(L->dtype, L->d_out, L->d_in, L->r)));
@@ -624,7 +627,8 @@ int agzo_step(agzo_ctx* ctx, const agzo_layer* L, void* W, const void* X, const 
     if (K < 0 || K > 64) return fail(ctx, AGZO_EINVAL, "K=%d outside 0..64", K);
     if (!(eps > 0.f)) return fail(ctx, AGZO_EINVAL, "eps must be positive");
     if (L->dtype == AGZO_BF16 && (reinterpret_cast<uintptr_t>(W) & 15)) return fail(ctx, AGZO_EINVAL, "W misaligned");
-    const Plan p = make_plan(*L, L->dtype == AGZO_F32, loss->kind == AGZO_LOSS_CE);
+    const Plan p = make_plan(*L, L->dtype == AGZO_F32, loss->kind == AGZO_LOSS_CE,
+                             (flags & AGZO_SHARED_FORWARD) && !(flags & AGZO_NAIVE_INPLACE));
     TRY(reserve(ctx, p.total));
     hipStream_t st = ctx->stream;
     float* B = wsf(ctx, p.off_B);

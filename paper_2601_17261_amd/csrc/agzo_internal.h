@@ -116,6 +116,9 @@ struct GemmBf16Args {
     // shared = true: one pass evaluates the loss at W, W + eps Z and W - eps Z (eps = eps_signed > 0);
     // the loss partials are then [3][n_workgroups] and Y must be NULL
     bool shared = false;
+    // true: always the 256 x 256 tiling (default: shapes with few such tiles take the 128 x 128 one when the call is
+    // one it supports); must agree with the small_ok given to gemm_bf16_num_workgroups when the workspace was sized
+    bool large_tiles = false;
     // gemm_bf16_ext_bytes() bytes of device scratch for the rank-r extension operands of a perturbed forward
     // (NULL: every tile builds them itself)
     void* ext_ws = nullptr;
@@ -123,7 +126,9 @@ struct GemmBf16Args {
     // constant-rate counter at kernel entry and exit
     unsigned long long* clk = nullptr;
 };
-int gemm_bf16_num_workgroups(int64_t M, int64_t N);
+// number of loss partials a launch writes; small_ok: the call is one the 128 x 128 tiling supports (no shared-forward
+// mode, no cross-entropy), which is then used for shapes with few 256 x 256 tiles
+int gemm_bf16_num_workgroups(int64_t M, int64_t N, bool small_ok);
 size_t gemm_bf16_ext_bytes(int64_t M, int64_t N, int r);
 hipError_t launch_gemm_bf16(const GemmBf16Args& a, hipStream_t st);
 

@@ -17,53 +17,22 @@
 // The rank-r term is accumulated by the same MFMA blocks as a few extra K slices appended after the d_in slices:
 // one operand is eps * P split in bf16 hi/lo, the other is G regenerated from the Philox seed and split
 // likewise, so both signs share bit-identical X W^T accumulators.
-#include "agzo_internal.h"
+#include "gemm_bf16_common.h"
 
 namespace agzo {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float floatx16 __attribute__((ext_vector_type(16)));
-template <int V> struct IC { static constexpr int value = V; };
-
-constexpr int BT = 256;                        // tile edge (tokens and outputs)
-constexpr int BK = 64;
-constexpr int CHUNKS = BK / 8;                 // 16-byte chunks per tile row
-constexpr int TILE_BYTES = BT * BK * 2;        // one operand tile: 32 KiB
+// true: the shape gives so few 256 x 256 tiles that most compute units would idle; the 128 x 128 tiling is used when
+// the call is one it supports (no shared-forward mode, no cross-entropy)
+static bool small_shape(int64_t M, int64_t N) {
+    return ((M + BT - 1) / BT) * ((N + BT - 1) / BT) < 160;
+}
 
 int gemm_bf16_ce_chunks(int64_t N) { return (int)((N + BT - 1) / BT) * 2; }   // 128-column chunks (2 per tile)
 
-int gemm_bf16_num_workgroups(int64_t M, int64_t N) {
+int gemm_bf16_num_workgroups(int64_t M, int64_t N, bool small_ok) {
+    if (small_ok && small_shape(M, N)) return (int)(((M + BT_SMALL - 1) / BT_SMALL) * ((N + BT_SMALL - 1) / BT_SMALL));
     return (int)(((M + BT - 1) / BT) * ((N + BT - 1) / BT));
 }
-
-// byte offset of 16-byte chunk `c` of row `row` inside a [256][64] bf16 tile; the XOR spreads the
-// 16 rows touched by one pass of a ds_read_b128 over all LDS banks.
-__device__ __forceinline__ int lds_off(int row, int c) { return row * (BK * 2) + ((c ^ ((row >> 1) & 7)) << 4); }
-
-// LDS row m' of a 32-row block holds W row perm(m'): MFMA output register e of lane half h is
-// row 8*(e/4) + 4*h + e%4 of the block, which this makes output column 16*h + e.
-__device__ __forceinline__ int w_perm(int m) { return ((m >> 2) & 1) * 16 + ((m >> 3) & 3) * 4 + (m & 3); }
-
-struct GemmParams {
-    const bf16_t* X; int64_t ldx;
-    const bf16_t* W; int64_t ldw;
-    int64_t M, N, K;            // tokens, outputs, d_in
-    void* Y; int y_dtype; int64_t ldy;
-    const float* P; int r; int rp;
-    // rank-r extension operands prepared ahead of the launch (NULL: the workgroups build them per tile):
-    // Xext [M][ext_ld] = [Ph | Ph | Pl | 0], Wext [N][ext_ld] = [Gh | Gl | Gh | 0] with the signed eps folded into G
-    const bf16_t* Xext; const bf16_t* Wext; int ext_ld;
-    float eps_signed; uint32_t s_lo, s_hi;
-    int loss_kind; int target_dtype; const void* target; int64_t ldt; double* partials;
-    int tiles_m, tiles_n;
-    int group_m;                // token tiles walked per output tile inside an XCD's run
-    int vec_ok;                 // 16-byte epilogue accesses are legal
-    int shared;                 // one pass evaluates f0, f+ and f- (three loss partials per tile)
-    // cross-entropy: per (128-column chunk, token) running max and sum of exponentials, and the target's logit
-    const int32_t* ce_target; float2* ce_ms; float* ce_tl;
-    // optional telemetry: workgroup 0 leaves {shader clock, constant-rate clock} at entry and at exit
-    unsigned long long* clk;
-};
 
 // WA x WB waves: WA splits the 256 outputs, WB splits the 256 tokens
 // EPI selects the epilogue compiled into the kernel: 0 = general (stores, squared error, any bounds), 1 = cross-entropy
@@ -774,6 +743,13 @@ hipError_t launch_gemm_bf16(const GemmBf16Args& a, hipStream_t st) {
     p.ce_ms = reinterpret_cast<float2*>(a.loss.ce_ms);
     p.ce_tl = a.loss.ce_tl;
     p.clk = a.clk;
+    if (small_shape(a.M, a.N) && !a.large_tiles && !a.shared && p.loss_kind != AGZO_LOSS_CE) {
+        // the workspace was sized for this tiling's partials (gemm_bf16_num_workgroups with small_ok)
+        if (a.P && !p.Xext) return hipErrorInvalidValue;      // the small tiling takes the rank-r term as operands only
+        p.tiles_m = (int)((a.M + BT_SMALL - 1) / BT_SMALL);
+        p.tiles_n = (int)((a.N + BT_SMALL - 1) / BT_SMALL);
+        return launch_gemm_bf16_small(p, st);
+    }
     int epi = 0;
     if (p.loss_kind == AGZO_LOSS_CE) epi = 1;
     else if (p.loss_kind == AGZO_LOSS_MSE && !a.Y && vec && a.M % BT == 0 && a.N % BT == 0)

@@ -124,12 +124,20 @@ CASES = [
 ]
 
 
+# the bf16 forward GEMM has two tilings; these shapes would all take the small one, so each also runs with the large
+TILINGS = [binding.TILING_AUTO, binding.TILING_LARGE]
+
+
+@pytest.mark.parametrize("tiling", TILINGS)
 @pytest.mark.parametrize("storage,n,d_in,d_out,r,kind,tol", CASES)
-def test_forward_sketch_basis_perturbed_update(ctx, storage, n, d_in, d_out, r, kind, tol):
+def test_forward_sketch_basis_perturbed_update(ctx, storage, n, d_in, d_out, r, kind, tol, tiling):
+    if storage == "f32" and tiling != binding.TILING_AUTO:
+        pytest.skip("the fp32-storage path has one tiling")
     seed = 4242 + n
     W, X, T, Wd, Xd, Td = problem(n + d_in, n, d_in, d_out, kind, storage)
     W64, X64 = W.astype(np.float64), X.astype(np.float64)
     L = binding.make_layer(Wd, Xd, r)
+    L.tiling = tiling
     loss = binding.make_loss(Td)
     scal = torch.zeros(4, dtype=torch.float64, device="cuda")
 
@@ -201,10 +209,14 @@ def test_forward_sketch_basis_perturbed_update(ctx, storage, n, d_in, d_out, r, 
 ])
 @pytest.mark.parametrize("flags", [0, binding.ONE_SIDED, binding.INIT_FEATURE, binding.SHARED_FORWARD,
                                    binding.SHARED_FORWARD | binding.ONE_SIDED])
-def test_step_matches_oracle(ctx, storage, n, d_in, d_out, r, kind, flags):
+@pytest.mark.parametrize("tiling", TILINGS)
+def test_step_matches_oracle(ctx, storage, n, d_in, d_out, r, kind, flags, tiling):
+    if tiling != binding.TILING_AUTO and (storage == "f32" or flags & binding.SHARED_FORWARD):
+        pytest.skip("one tiling only")
     seed = 99
     W, X, T, Wd, Xd, Td = problem(7 + n, n, d_in, d_out, kind, storage)
     L = binding.make_layer(Wd, Xd, r)
+    L.tiling = tiling
     out = torch.zeros(4, dtype=torch.float64, device="cuda")
     ctx.step(L, Wd, Xd, binding.make_loss(Td), 3, EPS, LR, seed, flags, out)
     ctx.check()
@@ -306,6 +318,7 @@ def test_tile_aligned_shapes_take_the_specialised_loss_epilogues(ctx, target_dty
         T = synth.to_bf16_values(T)
         Td = dev(T, "bf16")
     L = binding.make_layer(Wd, Xd, r)
+    L.tiling = binding.TILING_LARGE                # this shape alone would take the small tiling
     sc = torch.zeros(1, dtype=torch.float64, device="cuda")
     ctx.layer_forward_sketch(L, Wd, Xd, None, binding.SKETCH_NONE, None, 1, None, binding.make_loss(Td), sc)
     L0 = oagzo.mse_loss(oagzo.forward(X.astype(np.float64), W.astype(np.float64)), T)
@@ -478,8 +491,11 @@ def test_dense_perturb_matches_oracle(ctx, storage, shape):
 @pytest.mark.parametrize("storage,n,d_in,d_out,r", [("bf16", 1, 8, 1, 1), ("bf16", 8, 8, 8, 8), ("bf16", 16, 64, 264, 16),
                                                      ("bf16", 40, 16, 3, 16), ("f32", 1, 1, 1, 1), ("f32", 2, 3, 1, 2),
                                                      ("f32", 5, 4, 7, 4)])
+@pytest.mark.parametrize("tiling", TILINGS)
 @pytest.mark.parametrize("K", [0, 2])
-def test_degenerate_shapes_step(ctx, storage, n, d_in, d_out, r, K):
+def test_degenerate_shapes_step(ctx, storage, n, d_in, d_out, r, K, tiling):
+    if storage == "f32" and tiling != binding.TILING_AUTO:
+        pytest.skip("the fp32-storage path has one tiling")
     seed = 17
     rng = np.random.default_rng(100 * n + d_in)
     X = synth.x_rmsnorm_gaussian(rng, n, d_in, storage=storage)
@@ -487,6 +503,7 @@ def test_degenerate_shapes_step(ctx, storage, n, d_in, d_out, r, K):
     T = rng.standard_normal((n, d_out)).astype(np.float32)
     Wd, Xd, Td = dev(W, storage), dev(X, storage), dev(T)
     L = binding.make_layer(Wd, Xd, r)
+    L.tiling = tiling
     out = torch.zeros(4, dtype=torch.float64, device="cuda")
     lr = float(np.float32(1e-2))
     ctx.step(L, Wd, Xd, binding.make_loss(Td), K, EPS, lr, seed, 0, out)
