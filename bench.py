@@ -327,6 +327,39 @@ def main():
                                                      "frac": 4.0 * dn_rate / 1e9 / PEAK_HBM_GBS, "normals_per_s": dn_rate,
                                                      "launches": n_dn}
     del gbuf, theta
+    if args.workload == "qwen3-8b" and not args.naive:
+        # the small, launch-bound configuration next to the headline one: Qwen3-0.6B layer set, N = 2048, r = 8
+        del layers, descs
+        torch.cuda.empty_cache()
+        s_layers = build_layer_set(2048, synth.QWEN3_0P6B_LAYER, seed=50)
+        s_descs = [(binding.make_layer(W, X, 8), W, X, binding.make_loss(T)) for _, _, _, W, X, T in s_layers]
+        s_out = torch.zeros(len(s_layers), 4, dtype=torch.float64, device="cuda")
+
+        def small_step(step):
+            for li, (L, W, X, loss) in enumerate(s_descs):
+                ctx.step(L, W, X, loss, K, eps, lr, 1000 * step + li, 0, s_out[li])
+
+        for s_ in range(5):
+            small_step(s_)
+        torch.cuda.synchronize()
+        n_small = 50
+        t3 = time.perf_counter()
+        for s_ in range(n_small):
+            small_step(10 + s_)
+        torch.cuda.synchronize()
+        dt3 = time.perf_counter() - t3
+        ctx.profile_enable(True)
+        for s_ in range(2):
+            small_step(100 + s_)
+        torch.cuda.synchronize()
+        st = {k: ctx.profile_read(v)[1] / 2 for k, v in (("gemm", binding.PROF_GEMM), ("update", binding.PROF_UPDATE),
+                                                        ("xq", binding.PROF_XQ), ("xtt", binding.PROF_XTT), ("qr", binding.PROF_QR))}
+        ctx.profile_enable(False)
+        ctx.check()
+        res["qwen3_0p6b_layer_set"] = {"value": n_small / dt3, "unit": "steps/s", "ms_per_step": 1e3 * dt3 / n_small,
+                                       "tokens": 2048, "rank": 8, "steps": n_small, "stage_ms_per_step": st,
+                                       "note": "launch- and latency-bound: 7 projections of 1-3 M parameters each"}
+        del s_layers, s_descs
     # yardstick for the MFMA fraction: a register-only MFMA loop (no LDS, no memory traffic) on this device, with
     # operand bits that never toggle (zeros) and with N(0,1) bf16 operands like the workload's
     gen = torch.Generator(device="cuda")
