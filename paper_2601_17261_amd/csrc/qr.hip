@@ -39,10 +39,10 @@ __device__ int chol_block(double* G, int r, int rp) {
     __shared__ double dinv[kMaxRank];
     const int tid = threadIdx.x, nt = blockDim.x;
     int bad = 0;
-    for (int j = 0; j < rp; ++j) {
+    if (tid >= r && tid < rp) dinv[tid] = 1.0;            // padding columns: zero rows and columns, unit diagonal
+    for (int j = 0; j < r; ++j) {                         // (they need no elimination step)
         __syncthreads();                                  // the trailing update of the previous column is complete
         double piv = G[j * rp + j];
-        if (j >= r) piv = 1.0;
         if (!(piv > 0.0)) { bad = 1; piv = 1.0; }
         // 1/sqrt(piv): hardware estimate refined by two Newton steps (full fp64 accuracy, no divide)
         double inv = __builtin_amdgcn_rsq(piv);
@@ -69,8 +69,26 @@ __device__ int chol_block(double* G, int r, int rp) {
 __device__ void gram_partial(const double* Ys, int ld, int rows_pad, int rp, double* partial) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int nb = rp / 16;
-    // block pair (bi, bj) of the Gram matrix per wave, round robin; operand lane layout of the 16x16x4
-    // fp64 MFMA: lane l supplies element (l % 16, k = l / 16) of both A (rows = Gram row) and B
+    // operand lane layout of the 16x16x4 fp64 MFMA: lane l supplies element (l % 16, k = l / 16) of both A (rows =
+    // Gram row) and B; D (measured on gfx950): register i of lane l is row 4*i + l/16, column l % 16
+    if (nb == 1) {
+        // a single 16 x 16 block: the four waves split the rows (a lone wave would walk all of them through a chain
+        // of dependent MFMAs) and their sums are added in wave order
+        __shared__ double quarter[4][256];
+        const int chunk = ((rows_pad / 4 + 3) / 4) * 4;               // rows per wave, a multiple of 4
+        const int k_begin = min(wave * chunk, rows_pad), k_end = min(k_begin + chunk, rows_pad);
+        doublex4 acc = {0.0, 0.0, 0.0, 0.0};
+        for (int k0 = k_begin; k0 < k_end; k0 += 4) {
+            const double a = Ys[(k0 + (lane >> 4)) * ld + (lane & 15)];
+            acc = __builtin_amdgcn_mfma_f64_16x16x4f64(a, a, acc, 0, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) quarter[wave][(4 * i + (lane >> 4)) * 16 + (lane & 15)] = acc[i];
+        __syncthreads();
+        partial[(int64_t)blockIdx.x * 256 + tid] = (quarter[0][tid] + quarter[1][tid]) + (quarter[2][tid] + quarter[3][tid]);
+        return;
+    }
+    // block pair (bi, bj) of the Gram matrix per wave, round robin
     for (int blk = wave; blk < nb * nb; blk += 4) {
         const int bi = blk / nb, bj = blk % nb;
         doublex4 acc = {0.0, 0.0, 0.0, 0.0};
@@ -79,7 +97,6 @@ __device__ void gram_partial(const double* Ys, int ld, int rows_pad, int rp, dou
             const double b = Ys[(k0 + (lane >> 4)) * ld + bj * 16 + (lane & 15)];
             acc = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, acc, 0, 0, 0);
         }
-        // D (measured on gfx950): register i of lane l is row 4*i + l/16, column l % 16
 #pragma unroll
         for (int i = 0; i < 4; ++i)
             partial[((int64_t)blockIdx.x * rp + bi * 16 + 4 * i + (lane >> 4)) * rp + bj * 16 + (lane & 15)] = acc[i];
