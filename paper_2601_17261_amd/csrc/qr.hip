@@ -123,30 +123,28 @@ __device__ void reduce_and_factor(const double* partial, int nblk, double* Gs, i
     if (bad && tid == 0 && blockIdx.x == 0) *flag = 1;
 }
 
+// the block's input row of this thread, requested before the reduction and factorisation so that its memory latency
+// runs under them (RP is a compile-time bound, so the row lives in registers)
+template <int RP, typename Tin>
+__device__ __forceinline__ void load_row_t(const Tin* y, int r, bool active, Tin (&v)[RP]) {
+#pragma unroll
+    for (int c = 0; c < RP; ++c) v[c] = (active && c < r) ? y[c] : (Tin)0;
+}
+
 // row <- row R^-1 for upper-triangular R held in LDS with reciprocal diagonal (forward substitution);
 // the row stays in registers, R is read with broadcast loads
 template <int RP, typename Tin>
-__device__ __forceinline__ void solve_row_t(const Tin* y, const double* Rl, int r, double* q_out) {
+__device__ __forceinline__ void solve_row_t(const Tin (&y)[RP], const double* Rl, double* q_out) {
     double q[RP];
 #pragma unroll
     for (int c = 0; c < RP; ++c) {
-        double s = (c < r) ? (double)y[c] : 0.0;
+        double s = (double)y[c];
 #pragma unroll
         for (int k = 0; k < c; ++k) s = fma(-q[k], Rl[k * RP + c], s);
         q[c] = s * Rl[c * RP + c];
     }
 #pragma unroll
     for (int c = 0; c < RP; ++c) q_out[c] = q[c];
-}
-
-template <typename Tin>
-__device__ __forceinline__ void solve_row(const Tin* y, const double* Rl, int r, int rp, double* q) {
-    switch (rp) {
-        case 16: solve_row_t<16>(y, Rl, r, q); break;
-        case 32: solve_row_t<32>(y, Rl, r, q); break;
-        case 48: solve_row_t<48>(y, Rl, r, q); break;
-        default: solve_row_t<64>(y, Rl, r, q); break;
-    }
 }
 
 // launch 1.  Input: S fp32 [d][r], or (splits != nullptr) partial sketches [nsplit][d][rp] whose sum is
@@ -164,24 +162,9 @@ __global__ __launch_bounds__(256) void qr_gram_kernel(const float* __restrict__ 
     if (splits != nullptr) {
         // sum of the partial sketches: a block's rows are one contiguous run of rows * rp floats in every split, so the
         // loads are plain 16-byte vectors, all splits of a vector in flight together (fp64 sum in split order)
-        const int nvec = rows * rp / 4;
+        const int nvec = rows * rp / 4, total_vec = rows_pad * rp / 4;
         const float* base = splits + i0 * rp;
-        for (int v = tid; v < rows_pad * rp / 4; v += 256) {
-            double acc[4] = {0.0, 0.0, 0.0, 0.0};
-            if (v < nvec) {
-                for (int sp0 = 0; sp0 < nsplit; sp0 += 16) {
-                    float4 x[16];
-#pragma unroll
-                    for (int u = 0; u < 16; ++u)
-                        x[u] = (sp0 + u < nsplit) ? reinterpret_cast<const float4*>(base + (int64_t)(sp0 + u) * d * rp)[v]
-                                                  : make_float4(0.f, 0.f, 0.f, 0.f);
-#pragma unroll
-                    for (int u = 0; u < 16; ++u) {
-                        acc[0] += (double)x[u].x; acc[1] += (double)x[u].y;
-                        acc[2] += (double)x[u].z; acc[3] += (double)x[u].w;
-                    }
-                }
-            }
+        auto finish = [&](int v, const double (&acc)[4]) {
             const int i = (v * 4) / rp, k0 = (v * 4) % rp;
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
@@ -192,6 +175,30 @@ __global__ __launch_bounds__(256) void qr_gram_kernel(const float* __restrict__ 
                 }
                 Ys[i * ld + k0 + c] = (double)f;
             }
+        };
+        // two vectors per thread and pass, so that at rp = 16 a thread has all its loads in flight at once (the kernel
+        // is bound by the latency of these loads: the partials were written by the other XCDs)
+        for (int v0 = tid; v0 < total_vec; v0 += 512) {
+            const int v1 = v0 + 256;
+            double acc0[4] = {0.0, 0.0, 0.0, 0.0}, acc1[4] = {0.0, 0.0, 0.0, 0.0};
+            for (int sp0 = 0; sp0 < nsplit; sp0 += 16) {
+                float4 x0[16], x1[16];
+#pragma unroll
+                for (int u = 0; u < 16; ++u) {
+                    const float4* src = reinterpret_cast<const float4*>(base + (int64_t)(sp0 + u) * d * rp);
+                    x0[u] = (v0 < nvec && sp0 + u < nsplit) ? src[v0] : make_float4(0.f, 0.f, 0.f, 0.f);
+                    x1[u] = (v1 < nvec && sp0 + u < nsplit) ? src[v1] : make_float4(0.f, 0.f, 0.f, 0.f);
+                }
+#pragma unroll
+                for (int u = 0; u < 16; ++u) {
+                    acc0[0] += (double)x0[u].x; acc0[1] += (double)x0[u].y;
+                    acc0[2] += (double)x0[u].z; acc0[3] += (double)x0[u].w;
+                    acc1[0] += (double)x1[u].x; acc1[1] += (double)x1[u].y;
+                    acc1[2] += (double)x1[u].z; acc1[3] += (double)x1[u].w;
+                }
+            }
+            finish(v0, acc0);
+            if (v1 < total_vec) finish(v1, acc1);
         }
     } else {
         for (int e = tid; e < rows_pad * rp; e += 256) {
@@ -205,11 +212,13 @@ __global__ __launch_bounds__(256) void qr_gram_kernel(const float* __restrict__ 
 }
 
 // launch 2: R1 from the partials, Q1 = S R1^-1 for the block's rows (fp64, stored), Gram partials of Q1.
-__global__ __launch_bounds__(256) void qr_apply_gram_kernel(const float* __restrict__ S, int64_t d, int r, int rp,
+template <int RP>
+__global__ __launch_bounds__(256) void qr_apply_gram_kernel(const float* __restrict__ S, int64_t d, int r,
                                                             const double* __restrict__ partial1, int nblk,
                                                             double* __restrict__ Q1, double* __restrict__ partial2,
                                                             int* flag) {
     extern __shared__ __align__(16) double qr_smem[];
+    constexpr int rp = RP;
     const int ld = rp + 1;
     double* Ys = qr_smem;
     double* Gs = qr_smem + QR_ROWS * ld;
@@ -217,11 +226,13 @@ __global__ __launch_bounds__(256) void qr_apply_gram_kernel(const float* __restr
     const int64_t i0 = (int64_t)blockIdx.x * QR_ROWS;
     const int rows = (int)min((int64_t)QR_ROWS, d - i0);
     const int rows_pad = (rows + 3) & ~3;
+    float y[RP];
+    load_row_t<RP>(S + (i0 + min(tid, rows - 1)) * r, r, tid < rows, y);
     for (int e = tid; e < rows_pad * ld; e += 256) Ys[e] = 0.0;
     reduce_and_factor(partial1, nblk, Gs, r, rp, flag);
     if (tid < rows) {
         double* q = Ys + tid * ld;
-        solve_row(S + (i0 + tid) * r, Gs, r, rp, q);
+        solve_row_t<RP>(y, Gs, q);
         for (int c = 0; c < r; ++c) Q1[(i0 + tid) * r + c] = q[c];
     }
     __syncthreads();
@@ -230,22 +241,25 @@ __global__ __launch_bounds__(256) void qr_apply_gram_kernel(const float* __restr
 
 // launch 3: Q = Q1 R2^-1, rounded to fp32; planes (nullable) receive the hi/mid/lo bf16 parts [3][rp][d].
 // With Tin = float the same kernel closes a single-pass factorisation: Q = Y R1^-1 straight from launch 1's partials.
-template <typename Tin>
-__global__ __launch_bounds__(256) void qr_apply_final_kernel(const Tin* __restrict__ Q1, int64_t d, int r, int rp,
+template <int RP, typename Tin>
+__global__ __launch_bounds__(256) void qr_apply_final_kernel(const Tin* __restrict__ Q1, int64_t d, int r,
                                                              const double* __restrict__ partial2, int nblk,
                                                              float* __restrict__ Q, bf16_t* __restrict__ planes,
                                                              int* flag) {
     extern __shared__ __align__(16) double qr_smem[];
+    constexpr int rp = RP;
     const int ld = rp + 1;
     double* Gs = qr_smem;                 // [rp][rp]
     double* Qs = qr_smem + rp * rp;       // [QR_ROWS][ld]
     const int tid = threadIdx.x;
     const int64_t i0 = (int64_t)blockIdx.x * QR_ROWS;
     const int rows = (int)min((int64_t)QR_ROWS, d - i0);
+    Tin y[RP];
+    load_row_t<RP>(Q1 + (i0 + min(tid, rows - 1)) * r, r, tid < rows, y);
     reduce_and_factor(partial2, nblk, Gs, r, rp, flag);
     if (tid < rows) {
         double* q = Qs + tid * ld;
-        solve_row(Q1 + (i0 + tid) * r, Gs, r, rp, q);
+        solve_row_t<RP>(y, Gs, q);
         for (int c = 0; c < r; ++c) Q[(i0 + tid) * r + c] = (float)q[c];
         for (int c = r; c < rp; ++c) q[c] = 0.0;
     }
@@ -263,6 +277,34 @@ __global__ __launch_bounds__(256) void qr_apply_final_kernel(const Tin* __restri
     }
 }
 
+// the launches after the first, for one padded rank (the rows' registers are sized by it)
+template <int RP>
+static hipError_t launch_apply(dim3 grid, size_t smem, hipStream_t st, const float* Sin, int64_t d, int r, const double* partial1,
+                               double* partial2, int nblk, double* Q1, float* Q, bf16_t* planes, int* numeric_flag, bool refine) {
+    static bool attr_set = false;
+    if (!attr_set) {
+        const int big = (QR_ROWS * (kMaxRank + 1) + kMaxRank * kMaxRank) * (int)sizeof(double);
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(qr_apply_gram_kernel<RP>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, big);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(qr_apply_final_kernel<RP, double>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, big);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(qr_apply_final_kernel<RP, float>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, big);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const dim3 block(256);
+    if (!refine) {
+        hipLaunchKernelGGL((qr_apply_final_kernel<RP, float>), grid, block, smem, st, Sin, d, r, partial1, nblk, Q, planes, numeric_flag);
+        return hipGetLastError();
+    }
+    hipLaunchKernelGGL(qr_apply_gram_kernel<RP>, grid, block, smem, st, Sin, d, r, partial1, nblk, Q1, partial2, numeric_flag);
+    hipLaunchKernelGGL((qr_apply_final_kernel<RP, double>), grid, block, smem, st, Q1, d, r, partial2, nblk, Q, planes, numeric_flag);
+    return hipGetLastError();
+}
+
 hipError_t launch_qr(const float* S, const float* splits, int nsplit, int rp, float* S_out, int64_t d, int r, float* Q,
                      bf16_t* planes, void* workspace, int* numeric_flag, bool refine, hipStream_t st) {
     if (d == 0) return hipSuccess;
@@ -272,35 +314,23 @@ hipError_t launch_qr(const float* S, const float* splits, int nsplit, int rp, fl
     double* partial2 = partial1 + (size_t)nblk * rp * rp;
     dim3 grid((unsigned)nblk), block(256);
     const size_t sm_full = ((size_t)QR_ROWS * (rp + 1) + (size_t)rp * rp) * sizeof(double);
+    const float* Sin = splits ? S_out : S;
     static bool attr_set = false;
     if (!attr_set) {
         const int big = (QR_ROWS * (kMaxRank + 1) + kMaxRank * kMaxRank) * (int)sizeof(double);
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(qr_gram_kernel),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, big);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(qr_apply_gram_kernel),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, big);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(qr_apply_final_kernel<double>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, big);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(qr_apply_final_kernel<float>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, big);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    const float* Sin = splits ? S_out : S;
     hipLaunchKernelGGL(qr_gram_kernel, grid, block, sm_full, st, S, splits, nsplit, S_out, d, r, rp, partial1);
-    if (!refine) {
-        hipLaunchKernelGGL(qr_apply_final_kernel<float>, grid, block, sm_full, st, Sin, d, r, rp, partial1, nblk, Q, planes,
-                           numeric_flag);
-        return hipGetLastError();
+    switch (rp) {
+        case 16: return launch_apply<16>(grid, sm_full, st, Sin, d, r, partial1, partial2, nblk, Q1, Q, planes, numeric_flag, refine);
+        case 32: return launch_apply<32>(grid, sm_full, st, Sin, d, r, partial1, partial2, nblk, Q1, Q, planes, numeric_flag, refine);
+        case 48: return launch_apply<48>(grid, sm_full, st, Sin, d, r, partial1, partial2, nblk, Q1, Q, planes, numeric_flag, refine);
+        case 64: return launch_apply<64>(grid, sm_full, st, Sin, d, r, partial1, partial2, nblk, Q1, Q, planes, numeric_flag, refine);
+        default: return hipErrorInvalidValue;
     }
-    hipLaunchKernelGGL(qr_apply_gram_kernel, grid, block, sm_full, st, Sin, d, r, rp, partial1, nblk, Q1, partial2,
-                       numeric_flag);
-    hipLaunchKernelGGL(qr_apply_final_kernel<double>, grid, block, sm_full, st, Q1, d, r, rp, partial2, nblk, Q, planes,
-                       numeric_flag);
-    return hipGetLastError();
 }
 
 }  // namespace agzo
