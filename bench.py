@@ -194,7 +194,10 @@ def main():
     dt = time.perf_counter() - t0
     n_gemm, ms_gemm = ctx.profile_read(binding.PROF_GEMM)
     n_upd, ms_upd = ctx.profile_read(binding.PROF_UPDATE)
-    n_clk, gemm_ghz = ctx.profile_clock()
+    try:
+        n_clk, gemm_ghz = ctx.profile_clock()
+    except binding.AgzoError:                    # telemetry only: never a reason to lose the measurement
+        n_clk, gemm_ghz = 0, None
     ctx.profile_enable(False)
     # stage breakdown: two more steps with every kernel class timed (not part of `value`)
     nstage = 2
@@ -396,14 +399,17 @@ def main():
     gen = torch.Generator(device="cuda")
     gen.manual_seed(7)
     probes = {}
-    for name, ops in (("zero_operands", torch.zeros(16384, dtype=torch.bfloat16, device="cuda")),
-                      ("randn_operands", torch.randn(16384, device="cuda", generator=gen).to(torch.bfloat16))):
-        for _ in range(6):                      # a few launches so that the clock settles (about 6 ms each)
-            tf, ghz = ctx.probe_mfma(ops, 8, 3000)
-        probes[name] = {"tflops": tf, "clock_ghz": ghz}
-    res["roofline"]["sustained_mfma"] = dict(probes, note="register-only v_mfma_f32_32x32x16_bf16 loop, 4 waves per CU, "
-                                             "issued back to back: the rate this device holds under its power limit")
-    res["roofline"]["frac_of_sustained"] = gemm_tflops / probes["randn_operands"]["tflops"]
+    try:
+        for name, ops in (("zero_operands", torch.zeros(16384, dtype=torch.bfloat16, device="cuda")),
+                          ("randn_operands", torch.randn(16384, device="cuda", generator=gen).to(torch.bfloat16))):
+            for _ in range(6):                      # a few launches so that the clock settles (about 6 ms each)
+                tf, ghz = ctx.probe_mfma(ops, 8, 3000)
+            probes[name] = {"tflops": tf, "clock_ghz": ghz}
+        res["roofline"]["sustained_mfma"] = dict(probes, note="register-only v_mfma_f32_32x32x16_bf16 loop, 4 waves per CU, "
+                                                 "issued back to back: the rate this device holds under its power limit")
+        res["roofline"]["frac_of_sustained"] = gemm_tflops / probes["randn_operands"]["tflops"]
+    except binding.AgzoError as e:                  # a yardstick, not part of the measurement
+        res["roofline"]["sustained_mfma"] = {"error": str(e)}
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(N, r, K, eps, lr, shapes)
     print(json.dumps(res))

@@ -121,3 +121,35 @@ def test_wide_projections_sampled(ctx, x4096, name, d_in, d_out):
     wrows = np.sort(rng.choice(d_out, size=64, replace=False))
     want = oagzo.round_bf16(W0[wrows] - LR * got[3] * Zg[wrows])
     assert rel(host(W)[wrows], want) < 3e-3
+
+
+def test_bench_line_has_the_contract_fields():
+    """bench.py in its default shape (fewer steps, no CPU baseline): one JSON line with the fields the harness reads,
+    a roofline whose fraction is achieved / peak, and a finite positive throughput."""
+    import json
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    res = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--steps", "2", "--warmup", "1", "--no-cpu-baseline"],
+                         capture_output=True, text=True, timeout=600, cwd=root)
+    assert res.returncode == 0, res.stderr[-2000:]
+    lines = [l for l in res.stdout.splitlines() if l.startswith("{")]
+    assert len(lines) == 1
+    d = json.loads(lines[0])
+    for k in ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step", "higher_is_better", "scaling",
+              "vs_baseline", "dtype", "data", "config", "roofline"):
+        assert k in d, k
+    assert d["n_gpus"] == 1 and d["steps"] == 2 and d["warmup"] == 1 and d["higher_is_better"] is True
+    assert d["vs_baseline"] is None and d["data"] == "synthetic" and d["dtype"] == "bf16"
+    assert "workload" in d["config"] and "model" not in d["config"]
+    assert np.isfinite(d["value"]) and d["value"] > 0
+    assert abs(d["value"] * d["ms_per_step"] - 1e3) < 1e-6 * 1e3
+    rf = d["roofline"]
+    for k in ("bound", "achieved", "peak", "unit", "frac", "traffic"):
+        assert k in rf, k
+    assert rf["bound"] == "mfma" and rf["unit"] == "TFLOP/s" and rf["peak"] == 2500.0
+    assert abs(rf["frac"] - rf["achieved"] / rf["peak"]) < 1e-12
+    res2 = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                          timeout=120, cwd=root)
+    assert res2.returncode != 0 and "one GPU" in res2.stderr
