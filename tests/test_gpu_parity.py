@@ -347,8 +347,10 @@ def test_step_is_deterministic(ctx):
     assert torch.equal(res[0][0], res[1][0]) and torch.equal(res[0][1], res[1][1])
 
 
-def test_qwen3_0p6b_layer_set_one_step(ctx):
-    """Config 2 at full size: the seven projections of a Qwen3-0.6B layer, N = 8 x 256, r = 8."""
+@pytest.mark.parametrize("tiling", TILINGS)
+def test_qwen3_0p6b_layer_set_one_step(ctx, tiling):
+    """Config 2 at full size: the seven projections of a Qwen3-0.6B layer, N = 8 x 256, r = 8 (every shape here takes
+    the small GEMM tiling by itself; the second run forces the large one)."""
     n, r = 2048, 8
     rng = np.random.default_rng(2)
     inputs = {}
@@ -361,6 +363,7 @@ def test_qwen3_0p6b_layer_set_one_step(ctx):
         T = synth.shifted_target(rng, X, W)
         Wd, Xd, Td = dev(W, "bf16"), dev(X, "bf16"), dev(T)
         L = binding.make_layer(Wd, Xd, r)
+        L.tiling = tiling
         out = torch.zeros(4, dtype=torch.float64, device="cuda")
         seed = 1000 + len(name)
         ctx.step(L, Wd, Xd, binding.make_loss(Td), 3, EPS, LR, seed, 0, out)
