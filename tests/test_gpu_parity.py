@@ -395,6 +395,21 @@ def test_invalid_arguments_are_rejected(ctx):
     Lbad.ldx = 36                       # not a multiple of 8 for bf16
     with pytest.raises(binding.AgzoError):
         ctx.step(Lbad, Wd, Xd, loss, 3, EPS, LR, 1, 0, out)
+    # empty layers and dimensions beyond the documented maximum are refused, not launched
+    for field, value in (("n_tokens", 0), ("d_in", 0), ("d_out", 0), ("n_tokens", (1 << 24) + 1), ("d_out", (1 << 24) + 1)):
+        Le = binding.make_layer(Wd, Xd, 4)
+        setattr(Le, field, value)
+        with pytest.raises(binding.AgzoError) as e:
+            ctx.step(Le, Wd, Xd, loss, 3, EPS, LR, 1, 0, out)
+        assert e.value.code == binding.EINVAL, field
+    Lt = binding.make_layer(Wd, Xd, 4)
+    Lt.tiling = 7
+    with pytest.raises(binding.AgzoError):
+        ctx.step(Lt, Wd, Xd, loss, 3, EPS, LR, 1, 0, out)
+    # empty blocks are fine where the call has nothing to do
+    ctx.dense_perturb(torch.empty(0, 8, dtype=torch.float32, device="cuda"), 1, 1.0)
+    ctx.dense_perturb(torch.empty(0, dtype=torch.bfloat16, device="cuda"), 1, 1.0)
+    ctx.check()
     np.testing.assert_array_equal(Wd.float().cpu().numpy(), W)     # nothing was touched
 
 
