@@ -153,3 +153,37 @@ def test_bench_line_has_the_contract_fields():
     res2 = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
                           timeout=120, cwd=root)
     assert res2.returncode != 0 and "one GPU" in res2.stderr
+
+
+@pytest.mark.parametrize("flags", [0, binding.SHARED_FORWARD])
+def test_lm_head_cross_entropy_at_full_size(ctx, flags):
+    """The output projection of the MLP-stack workload at its full size: 16 x 512 tokens, hidden 2048, vocabulary
+    32000, token cross-entropy with the last position of every sequence ignored (32 x 125 GEMM tiles, the logits are
+    never stored).  The oracle's three forwards are a teraflop each in fp64, which the host does in seconds."""
+    n_seq, seq, hidden, vocab = 16, 512, 2048, 32000
+    n = n_seq * seq
+    rng = np.random.default_rng(77)
+    X = synth.x_rmsnorm_gaussian(rng, n, hidden, storage="bf16")
+    W = synth.weights(rng, vocab, hidden, storage="bf16")
+    ids = rng.integers(0, vocab, size=(n_seq, seq))
+    tgt = np.full((n_seq, seq), -1, dtype=np.int32)
+    tgt[:, :-1] = ids[:, 1:]
+    tgt = tgt.reshape(-1)
+    Wd = torch.from_numpy(W).to("cuda", torch.bfloat16)
+    Xd = torch.from_numpy(X).to("cuda", torch.bfloat16)
+    Td = torch.from_numpy(tgt).cuda()
+    out = torch.zeros(4, dtype=torch.float64, device="cuda")
+    seed, lr = 2024, float(np.float32(1e-2))
+    ctx.step(binding.make_layer(Wd, Xd, R), Wd, Xd, binding.make_loss(Td, kind=binding.LOSS_CE), K, EPS, lr, seed, flags, out)
+    ctx.check()
+    got = out.cpu().numpy()
+    o = oagzo.agzo_step(W, X, tgt, R, K, EPS, lr, seed, loss="ce", storage="bf16")
+    assert (tgt >= 0).sum() == n_seq * (seq - 1)
+    assert abs(got[0] - o["L0"]) < 2e-6 * o["L0"]
+    assert abs(got[1] - o["Lp"]) < 2e-6 * o["Lp"]
+    assert abs(got[2] - o["Lm"]) < 2e-6 * o["Lm"]
+    assert abs(got[3] - o["g"]) < 2e-2 * abs(o["g"]) + 1e-9, (got[3], o["g"])
+    Wn = host(Wd)
+    assert rel(Wn, o["W_new"]) < 3e-3
+    assert np.mean(Wn != o["W_new"]) < 2e-2
+    assert np.mean(Wn != W) > 0.01                       # the step moved the weights
