@@ -572,26 +572,32 @@ __global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
                 const int tgt = (row < p.M) ? p.ce_target[row] : -1;
                 float mx = -INFINITY, tl = 0.f;
                 bool has_tl = false;
+                // per block: how many of the lane's 16 columns exist, and which of them (if any) is the target
+                int ncol[BA], trel[BA];
 #pragma clang loop unroll(full)
                 for (int i = 0; i < BA; ++i) {
                     const int64_t col0 = n0 + wa * (BT / WA) + i * 32 + lh * 16;
+                    ncol[i] = (int)max((int64_t)0, min((int64_t)16, p.N - col0));
+                    trel[i] = (tgt >= 0) ? (int)((int64_t)tgt - col0) : -1;
+                }
+#pragma clang loop unroll(full)
+                for (int i = 0; i < BA; ++i) {
 #pragma clang loop unroll(full)
                     for (int e = 0; e < 16; ++e) {
                         const float y = acc[i][j][e];
-                        if (col0 + e < p.N) {
-                            mx = fmaxf(mx, y);
-                            if ((int64_t)tgt == col0 + e) { tl = y; has_tl = true; }
-                        }
+                        if (e < ncol[i]) mx = fmaxf(mx, y);
+                        if (e == trel[i]) { tl = y; has_tl = true; }
                     }
                 }
                 mx = fmaxf(mx, __shfl_xor(mx, 32));
+                // exp(y - mx) as 2^((y - mx) log2 e) on the hardware exponential: the difference is exact enough in
+                // fp32 (one rounding), the terms that matter have small exponents, and the far tail underflows to 0
                 float sm = 0.f;
 #pragma clang loop unroll(full)
                 for (int i = 0; i < BA; ++i) {
-                    const int64_t col0 = n0 + wa * (BT / WA) + i * 32 + lh * 16;
 #pragma clang loop unroll(full)
                     for (int e = 0; e < 16; ++e)
-                        if (col0 + e < p.N) sm += expf(acc[i][j][e] - mx);
+                        if (e < ncol[i]) sm += __builtin_amdgcn_exp2f((acc[i][j][e] - mx) * 1.44269504088896341f);
                 }
                 sm += __shfl_xor(sm, 32);
                 if (row < p.M) {
