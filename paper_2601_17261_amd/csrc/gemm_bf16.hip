@@ -320,9 +320,11 @@ __global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
             __builtin_amdgcn_sched_barrier(0);
         }
     };
-    // the 16 direct loads of a slice ride on four consecutive blocks: the last block of the slice before the previous
-    // one's (N3), then the first three blocks of the previous slice (N0, N1, none in the block before the wait)
-    constexpr int N3 = 6, N0 = 6, N1 = 4;
+    // the 16 direct loads of a slice ride on consecutive blocks: the last block of the slice before the previous one's
+    // (N3), then the first blocks of the previous slice (N0, N1), none in the block before the wait.  As early as the
+    // buffer allows: with the fused loss other tiles' target reads are in flight and operand loads take longer, and the
+    // early split gains 2 % there (a later one, 6 / 6 / 4, was 0.7 % faster for a forward without a loss).
+    constexpr int N3 = 8, N0 = 8, N1 = 0;
     static_assert(N3 + N0 + N1 == 16, "loads per slice");
     // plain slices kt0 .. kt1-1 of the steady state; on entry fragment set 0 holds sub-step 0 of slice kt0 and the
     // first N3 loads of slice kt0+1 are in flight; the same holds for kt1 on exit
@@ -368,7 +370,7 @@ __global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
             select_slice(IC<1>{}, 1);
 #pragma unroll
             for (int q = 0; q < N3; ++q) dma1(IC<1>{}, 1, 1, q);
-            __builtin_amdgcn_s_waitcnt(0x0F76);          // vmcnt(N3): slice 0 has landed
+            __builtin_amdgcn_s_waitcnt(0x0F70 | N3);      // vmcnt(N3): slice 0 has landed
         } else {
             __builtin_amdgcn_s_waitcnt(0x0F70);
         }
