@@ -144,6 +144,8 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (known traffic) so counter runs can be scaled")
     ap.add_argument("--sweep", action="store_true", help="rank x tokens sweep on Qwen3-4B shapes (text table)")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="only the timed workload and its stage breakdown (for counter-collection runs of the profiler)")
     ap.add_argument("--workload", choices=["qwen3-8b", "qwen3-0.6b"], default="qwen3-8b",
                     help="layer set: qwen3-8b is the benchmark configuration; qwen3-0.6b (use --tokens 2048 --rank 8) is the "
                          "small launch-bound one")
@@ -253,7 +255,7 @@ def main():
         "stage_ms_per_step": {"gemm": st_gemm, "update": st_upd, "xq": ms_xq, "xtt": ms_xtt, "qr": ms_qr,
                               "note": "from %d extra steps with every kernel class timed" % nstage},
     }
-    if not args.naive:
+    if not args.naive and not args.no_extras:
         # the same steps with f0, f+ and f- evaluated from one pass over X and W (AGZO_SHARED_FORWARD):
         # identical results up to rounding, one GEMM main loop per projection instead of three
         for s in range(args.warmup):
@@ -361,7 +363,7 @@ def main():
                                                      "frac": 4.0 * dn_rate / 1e9 / PEAK_HBM_GBS, "normals_per_s": dn_rate,
                                                      "launches": n_dn}
     del gbuf, theta
-    if args.workload == "qwen3-8b" and not args.naive:
+    if args.workload == "qwen3-8b" and not args.naive and not args.no_extras:
         # the small, launch-bound configuration next to the headline one: Qwen3-0.6B layer set, N = 2048, r = 8
         del layers, descs
         torch.cuda.empty_cache()

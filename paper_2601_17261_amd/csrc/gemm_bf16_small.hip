@@ -3,7 +3,7 @@
 // Sec. 4.1 from the accumulators.
 //
 // 128 x 128 tile per workgroup, 4 waves of 64 x 64 (2 x 2 blocks of v_mfma_f32_32x32x16_bf16), K slices of 64 double
-// buffered in LDS (66 KiB per workgroup: two workgroups per compute unit).  Four times the workgroups of the large
+// buffered in LDS (64 KiB per workgroup: two workgroups per compute unit).  Four times the workgroups of the large
 // tiling, at twice its LDS reads per MFMA: the better trade while the large tiling would leave compute units idle.
 // Operands travel global -> registers -> LDS (the next slice is in flight in registers while the current one is
 // multiplied), in the same swizzled layout and with the same permutation of W rows as the large tiling, so a lane
@@ -16,14 +16,14 @@ namespace agzo {
 
 constexpr int ST = BT_SMALL;                    // tile edge
 constexpr int STILE_BYTES = ST * BK * 2;        // one operand tile: 16 KiB
-constexpr int SMALL_SMEM = 4 * STILE_BYTES + 256 * (int)sizeof(double);
+constexpr int SMALL_SMEM = 4 * STILE_BYTES;      // 64 KiB: two operand tiles x two stages (the loss reduction reuses them)
 
 // (LDS allows two workgroups per compute unit = two waves per SIMD, so each wave may use half the register file)
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void gemm_bf16_small_kernel(GemmParams p) {
     extern __shared__ __align__(16) char smem[];
     auto Xs = [&](int buf) -> char* { return smem + buf * (2 * STILE_BYTES); };
     auto Ws = [&](int buf) -> char* { return smem + buf * (2 * STILE_BYTES) + STILE_BYTES; };
-    double* red = reinterpret_cast<double*>(smem + 4 * STILE_BYTES);
+    double* red = reinterpret_cast<double*>(smem);           // used after the slice loop, when the operand buffers are idle
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     if (p.clk && blockIdx.x == 0 && tid == 0) { p.clk[0] = __builtin_readcyclecounter(); p.clk[1] = wall_clock64(); }
@@ -240,7 +240,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         }
     }
     if (p.loss_kind == AGZO_LOSS_MSE) {
-        // the operand buffers are no longer read (barrier at the end of the slice loop); red lies behind them anyway
+        // the operand buffers are no longer read (barrier at the end of the slice loop), so red may lie in them
         red[tid] = part;
         __syncthreads();
         for (int s = 128; s > 0; s >>= 1) {
@@ -254,13 +254,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 
 // p.tiles_m / p.tiles_n count 128 x 128 tiles here
 hipError_t launch_gemm_bf16_small(const GemmParams& p, hipStream_t st) {
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_bf16_small_kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, SMALL_SMEM);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
     dim3 grid((unsigned)((int64_t)p.tiles_m * p.tiles_n));
     hipLaunchKernelGGL(gemm_bf16_small_kernel, grid, dim3(256), SMALL_SMEM, st, p);
     return hipGetLastError();
