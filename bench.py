@@ -255,6 +255,23 @@ def main():
         "stage_ms_per_step": {"gemm": st_gemm, "update": st_upd, "xq": ms_xq, "xtt": ms_xtt, "qr": ms_qr,
                               "note": "from %d extra steps with every kernel class timed" % nstage},
     }
+    if not args.no_extras:
+        # the update sweep per projection shape (the average above includes the small k/v matrices, which a launch
+        # of a few microseconds cannot fill): prep + sweep, bytes = W read + written + the basis
+        by_shape = {}
+        Bu = {}
+        for (name, d_in, d_out, W, X, T), (L, _, _, _) in zip(layers, descs):
+            if d_in not in Bu:
+                Bu[d_in] = torch.empty(d_in, r, dtype=torch.float32, device="cuda").normal_()
+            ctx.update(L, W, Bu[d_in], 7, 1e-9, None)
+            ctx.profile_enable(1 << binding.PROF_UPDATE)
+            for _ in range(5):
+                ctx.update(L, W, Bu[d_in], 7, 1e-9, None)
+            n_u, ms_u = ctx.profile_read(binding.PROF_UPDATE)
+            ctx.profile_enable(False)
+            gbs = (4.0 * d_in * d_out + 4.0 * d_in * r) / (ms_u / max(n_u, 1) * 1e-3) / 1e9
+            by_shape["%s %dx%d" % (name, d_out, d_in)] = {"us": 1e3 * ms_u / max(n_u, 1), "GB/s": gbs, "frac": gbs / PEAK_HBM_GBS}
+        res["roofline_update"]["by_shape"] = by_shape
     if not args.naive and not args.no_extras:
         # the same steps with f0, f+ and f- evaluated from one pass over X and W (AGZO_SHARED_FORWARD):
         # identical results up to rounding, one GEMM main loop per projection instead of three
