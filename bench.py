@@ -5,7 +5,8 @@ Workload: the seven projections of one Qwen3-8B-shaped decoder layer (bf16 weigh
 activations, N = 16 x 1024 tokens, r = 16, K = 3 power steps, MSE loss), synthetic inputs with a
 power-law activation spectrum plus outlier channels.  One *step* = one full AGZO step (base forward
 with subspace extraction, two perturbed forwards, two-point scalar, in-place rank-r update) for each
-of the seven projections.  Inputs are resident in HBM before the timed region starts.
+of the seven projections; as in Alg. 2 the updates follow once every scalar is known, in one batched
+call for the seven matrices.  Inputs are resident in HBM before the timed region starts.
 
 Prints one JSON line: steps/s for the layer set, the roofline of the dominant kernel (the forward
 GEMM, timed live with HIP events on the library's stream), the update kernel's HBM figure, and the
@@ -172,9 +173,21 @@ def main():
     out = torch.zeros(len(layers), 4, dtype=torch.float64, device="cuda")
     flags = binding.NAIVE_INPLACE if args.naive else 0
 
+    # Alg. 2 at the level of the layer set: every projection runs its step up to its scalar g, then all the
+    # updates go out together (one preparation launch and one sweep for the seven matrices)
+    def step_fn(descs_, out_, r_):
+        bases = [torch.empty(W.shape[1], r_, dtype=torch.float32, device="cuda") for _, W, _, _ in descs_]
+
+        def run(step, fl):
+            for li, (L, W, X, loss) in enumerate(descs_):
+                ctx.step_no_update(L, W, X, loss, K, eps, 1000 * step + li, fl, out_[li], bases[li])
+            ctx.update_many([(W, bases[li], 1000 * step + li, lr, out_[li, 3:4]) for li, (_, W, _, _) in enumerate(descs_)])
+        return run
+
+    run_step = step_fn(descs, out, r)
+
     def one_step(step, fl=None):
-        for li, (L, W, X, loss) in enumerate(descs):
-            ctx.step(L, W, X, loss, K, eps, lr, 1000 * step + li, flags if fl is None else fl, out[li])
+        run_step(step, flags if fl is None else fl)
 
     if args.calibrate_copy:
         src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
@@ -226,7 +239,10 @@ def main():
     algo_flops_per_launch = (gemm_per_step * fwd_flops + (0 if args.naive else 2 * rank_flops)) / (gemm_per_step * len(shapes))
     gemm_avg_ms = ms_gemm / max(n_gemm, 1)
     gemm_tflops = algo_flops_per_launch / (gemm_avg_ms * 1e-3) / 1e12
-    upd_bytes_per_launch = sum(2.0 * 2 * d_in * d_out + 4.0 * d_in * r for _, d_in, d_out in shapes) / len(shapes)
+    # update: bytes of the timed region / its launches (one batched launch pair per step; the in-place comparator adds
+    # three single-matrix sweeps per projection and step: perturb, to the other side, restore)
+    upd_bytes_per_step = sum(2.0 * 2 * d_in * d_out + 4.0 * d_in * r for _, d_in, d_out in shapes) * (4 if args.naive else 1)
+    upd_bytes_per_launch = upd_bytes_per_step * args.steps / max(n_upd, 1)
     upd_avg_ms = ms_upd / max(n_upd, 1)
     upd_gbs = upd_bytes_per_launch / (upd_avg_ms * 1e-3) / 1e9
 
@@ -250,14 +266,14 @@ def main():
                      "launches": n_gemm, "avg_ms": gemm_avg_ms,
                      "shader_clock_ghz": gemm_ghz, "clock_note": "mean shader clock over the first workgroup of each of "
                      "these launches (in-kernel cycle counter / constant-rate counter); the peak assumes 2.4 GHz"},
-        "roofline_update": {"bound": "hbm", "kernel": "update_prep_kernel + update_mfma_kernel", "achieved": upd_gbs, "peak": PEAK_HBM_GBS,
+        "roofline_update": {"bound": "hbm", "kernel": "update_prep_many_kernel + update_mfma_many_kernel (the layer set's matrices in one launch pair)", "achieved": upd_gbs, "peak": PEAK_HBM_GBS,
                             "unit": "GB/s", "frac": upd_gbs / PEAK_HBM_GBS, "launches": n_upd, "avg_ms": upd_avg_ms},
         "stage_ms_per_step": {"gemm": st_gemm, "update": st_upd, "xq": ms_xq, "xtt": ms_xtt, "qr": ms_qr,
                               "note": "from %d extra steps with every kernel class timed" % nstage},
     }
     if not args.no_extras:
-        # the update sweep per projection shape (the average above includes the small k/v matrices, which a launch
-        # of a few microseconds cannot fill): prep + sweep, bytes = W read + written + the basis
+        # the single-matrix update (agzo_update) per projection shape: prep + sweep, bytes = W read + written + the basis;
+        # the small k/v matrices cannot fill launches of their own, which is what the batched call above avoids
         by_shape = {}
         Bu = {}
         for (name, d_in, d_out, W, X, T), (L, _, _, _) in zip(layers, descs):
@@ -323,7 +339,7 @@ def main():
                 ctx.perturbed_forward(L, W, X, Bs[key], seed, eps, None, loss, out[li, 1:2])
                 ctx.perturbed_forward(L, W, X, Bs[key], seed, -eps, None, loss, out[li, 2:3])
                 ctx.two_point(out[li], eps)
-                ctx.update(L, W, Bs[key], seed, lr, out[li, 3:4])
+            ctx.update_many([(W, Bs[X.data_ptr()], 1000 * step + li, lr, out[li, 3:4]) for li, (_, W, X, _) in enumerate(descs)])
 
         composed_step(40_000)
         torch.cuda.synchronize()
@@ -388,9 +404,10 @@ def main():
         s_descs = [(binding.make_layer(W, X, 8), W, X, binding.make_loss(T)) for _, _, _, W, X, T in s_layers]
         s_out = torch.zeros(len(s_layers), 4, dtype=torch.float64, device="cuda")
 
+        small_run = step_fn(s_descs, s_out, 8)
+
         def small_step(step):
-            for li, (L, W, X, loss) in enumerate(s_descs):
-                ctx.step(L, W, X, loss, K, eps, lr, 1000 * step + li, 0, s_out[li])
+            small_run(step, 0)
 
         for s_ in range(5):
             small_step(s_)

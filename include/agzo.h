@@ -157,6 +157,27 @@ int agzo_two_point(agzo_ctx* ctx, double* out4_dev, float eps, int32_t flags);
 int agzo_update(agzo_ctx* ctx, const agzo_layer* L, void* W, const float* B, uint64_t seed,
                 float lr, const double* g_dev);
 
+/* The same sweep for n matrices at once (Alg. 2: every layer is updated after the one scalar g is known, so the
+ * updates of a model arrive together).  items: host array, read during the call only; per item the arguments of
+ * agzo_update: W device [d_out][ldw] of `dtype`, B device fp32 [d_in][r], g_dev device scalar or NULL (= 1), seed of
+ * that layer's Gaussian factor, lr; reserved must be 0.  bf16 matrices whose ranks round up to the same multiple of 16
+ * share one preparation launch and one sweep per 16 matrices (small matrices no longer pay two launches each); fp32
+ * matrices are swept one by one.  Every matrix ends bit-identical to what agzo_update gives it.  The matrices must
+ * not overlap.  n = 0 is a no-op.  Errors: AGZO_EINVAL for n < 0, NULL items, or an item agzo_update would reject
+ * (nothing is enqueued then). */
+typedef struct {
+    void* W;
+    const float* B;
+    const double* g_dev;
+    int64_t d_out, d_in, ldw;
+    int32_t r;
+    int32_t dtype;     /* agzo_dtype of W */
+    uint64_t seed;
+    float lr;
+    int32_t reserved;
+} agzo_update_item;
+int agzo_update_many(agzo_ctx* ctx, const agzo_update_item* items, int32_t n);
+
 /* Dense Gaussian sweep for parameters that are not linear-layer weights (Eq. 7, second branch; Alg. 2: the perturb,
  * restore and update lines for such parameters): theta[i][j] += coef * z(i, j) in place, z the N(0,1) value
  * (seed, tag 3, row i, column j) of the generator above, coef = scale * *g_dev (scale alone if g_dev is NULL).
@@ -171,6 +192,13 @@ int agzo_dense_perturb(agzo_ctx* ctx, void* theta, int32_t dtype, int64_t rows, 
 /* One whole AGZO step for one layer (Alg. 2).  out_dev[4] = {L0, L+, L-, g} (device doubles). */
 int agzo_step(agzo_ctx* ctx, const agzo_layer* L, void* W, const void* X, const agzo_loss_spec* loss,
               int32_t K, float eps, float lr, uint64_t seed, int32_t flags, double* out_dev);
+
+/* The same step without its last line (Alg. 2 up to and including g): out_dev as above, the basis goes to
+ * B_out (device fp32 [d_in][r], required) and W is left unchanged, for callers that update several layers together
+ * with agzo_update_many (g_dev = out_dev + 3, or a scalar of their own).  Flags as for agzo_step; with
+ * AGZO_NAIVE_INPLACE W is perturbed and restored inside the call.  Errors as agzo_step, AGZO_EINVAL for NULL B_out. */
+int agzo_step_no_update(agzo_ctx* ctx, const agzo_layer* L, void* W, const void* X, const agzo_loss_spec* loss,
+                        int32_t K, float eps, uint64_t seed, int32_t flags, double* out_dev, float* B_out);
 
 #ifdef __cplusplus
 }

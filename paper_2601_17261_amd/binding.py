@@ -27,7 +27,7 @@ PROF_ALL = 63
 EXPORTS = ["agzo_create", "agzo_destroy", "agzo_last_error", "agzo_check", "agzo_profile_enable",
            "agzo_profile_read", "agzo_profile_clock", "agzo_probe_mfma", "agzo_philox_words", "agzo_fill_normal",
            "agzo_layer_forward_sketch", "agzo_qr", "agzo_basis", "agzo_perturbed_forward", "agzo_two_point", "agzo_dense_perturb", "agzo_update",
-           "agzo_step"]
+           "agzo_update_many", "agzo_step", "agzo_step_no_update"]
 
 
 class AgzoLayer(ctypes.Structure):
@@ -40,6 +40,13 @@ class AgzoLayer(ctypes.Structure):
 class AgzoLossSpec(ctypes.Structure):
     _fields_ = [("kind", ctypes.c_int32), ("target_dtype", ctypes.c_int32), ("target", ctypes.c_void_p),
                 ("ldt", ctypes.c_int64)]
+
+
+class AgzoUpdateItem(ctypes.Structure):
+    _fields_ = [("W", ctypes.c_void_p), ("B", ctypes.c_void_p), ("g_dev", ctypes.c_void_p),
+                ("d_out", ctypes.c_int64), ("d_in", ctypes.c_int64), ("ldw", ctypes.c_int64),
+                ("r", ctypes.c_int32), ("dtype", ctypes.c_int32), ("seed", ctypes.c_uint64),
+                ("lr", ctypes.c_float), ("reserved", ctypes.c_int32)]
 
 
 class AgzoError(RuntimeError):
@@ -82,7 +89,9 @@ def load():
     lib.agzo_two_point.argtypes = [vp, vp, f32, i32]
     lib.agzo_dense_perturb.argtypes = [vp, vp, i32, i64, i64, i64, u64, f32, vp]
     lib.agzo_update.argtypes = [vp, lp, vp, vp, u64, f32, vp]
+    lib.agzo_update_many.argtypes = [vp, ctypes.POINTER(AgzoUpdateItem), i32]
     lib.agzo_step.argtypes = [vp, lp, vp, vp, sp, i32, f32, f32, u64, i32, vp]
+    lib.agzo_step_no_update.argtypes = [vp, lp, vp, vp, sp, i32, f32, u64, i32, vp, vp]
     for name in EXPORTS:
         if name not in ("agzo_destroy", "agzo_last_error"):
             getattr(lib, name).restype = ctypes.c_int
@@ -231,6 +240,22 @@ class Context:
 
     def update(self, L, W, B, seed, lr, g_dev):
         self._rc(self.lib.agzo_update(self.h, ctypes.byref(L), _ptr(W), _ptr(B), seed, lr, _ptr(g_dev)))
+
+    def update_many(self, items):
+        """items: sequence of (W, B, seed, lr, g_dev) with W a 2-D device tensor (unit stride along d_in), B [d_in][r]."""
+        arr = (AgzoUpdateItem * max(len(items), 1))()
+        for it, (W, B, seed, lr, g_dev) in zip(arr, items):
+            it.W, it.B, it.g_dev = W.data_ptr(), B.data_ptr(), (0 if g_dev is None else g_dev.data_ptr())
+            it.d_out, it.d_in, it.ldw = W.shape[0], W.shape[1], W.stride(0)
+            it.r, it.dtype, it.seed, it.lr, it.reserved = B.shape[1], _dt(W), seed, lr, 0
+        self.update_many_raw(arr, len(items))
+
+    def update_many_raw(self, arr, n):
+        self._rc(self.lib.agzo_update_many(self.h, arr, n))
+
+    def step_no_update(self, L, W, X, loss, K, eps, seed, flags, out_dev, B_out):
+        self._rc(self.lib.agzo_step_no_update(self.h, ctypes.byref(L), _ptr(W), _ptr(X), ctypes.byref(loss), K, eps,
+                                              seed, flags, _ptr(out_dev), _ptr(B_out)))
 
     def step(self, L, W, X, loss, K, eps, lr, seed, flags, out_dev):
         self._rc(self.lib.agzo_step(self.h, ctypes.byref(L), _ptr(W), _ptr(X), ctypes.byref(loss), K, eps, lr,

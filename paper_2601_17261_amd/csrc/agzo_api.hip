@@ -328,6 +328,17 @@ int op_forward(agzo_ctx* ctx, const agzo_layer& L, const Plan& p, const void* W,
     return 0;
 }
 
+int check_update(agzo_ctx* ctx, const void* W, const float* B, int dtype, int64_t d_out, int64_t d_in, int64_t ldw, int r) {
+    if (!W || !B) return fail(ctx, AGZO_EINVAL, "W or B is NULL");
+    if (d_in < 1 || d_out < 1 || r < 1 || r > kMaxRank || r > d_in || ldw < d_in)
+        return fail(ctx, AGZO_EINVAL, "bad layer shape");
+    if (dtype != AGZO_F32 && dtype != AGZO_BF16) return fail(ctx, AGZO_EINVAL, "dtype %d", dtype);
+    if (dtype == AGZO_BF16 && (d_in % 8 || ldw % 8 || (reinterpret_cast<uintptr_t>(W) & 15)))
+        return fail(ctx, AGZO_EINVAL, "bf16 W needs d_in and ldw multiples of 8 and 16-byte aligned rows");
+    if (dtype == AGZO_BF16 && ldw >= (1LL << 28)) return fail(ctx, AGZO_EINVAL, "bf16 W: ldw must be below 2^28");
+    return 0;
+}
+
 int op_update(agzo_ctx* ctx, const agzo_layer& L, size_t off_upd, void* W, const float* B, uint64_t seed, float lr,
               const double* g_dev) {
     ProfScope ps(ctx, AGZO_PROF_UPDATE);
@@ -586,15 +597,53 @@ int agzo_update(agzo_ctx* ctx, const agzo_layer* L, void* W, const float* B, uin
                 const double* g_dev) {
     if (!ctx) return AGZO_EINVAL;
     if (!L) return fail(ctx, AGZO_EINVAL, "layer descriptor is NULL");
-    if (!W || !B) return fail(ctx, AGZO_EINVAL, "W or B is NULL");
-    if (L->d_in < 1 || L->d_out < 1 || L->r < 1 || L->r > kMaxRank || L->r > L->d_in || L->ldw < L->d_in)
-        return fail(ctx, AGZO_EINVAL, "bad layer shape");
-    if (L->dtype != AGZO_F32 && L->dtype != AGZO_BF16) return fail(ctx, AGZO_EINVAL, "dtype %d", L->dtype);
     if (L->tiling != AGZO_TILING_AUTO && L->tiling != AGZO_TILING_LARGE) return fail(ctx, AGZO_EINVAL, "tiling %d", L->tiling);
-    if (L->dtype == AGZO_BF16 && (L->d_in % 8 || L->ldw % 8 || (reinterpret_cast<uintptr_t>(W) & 15)))
-        return fail(ctx, AGZO_EINVAL, "bf16 W needs d_in and ldw multiples of 8 and 16-byte aligned rows");
+    TRY(check_update(ctx, W, B, L->dtype, L->d_out, L->d_in, L->ldw, L->r));
     TRY(reserve(ctx, update_workspace_bytes(L->dtype, L->d_out, L->d_in, L->r)));
     TRY(op_update(ctx, *L, 0, W, B, seed, lr, g_dev));
+    return AGZO_OK;
+}
+
+int agzo_update_many(agzo_ctx* ctx, const agzo_update_item* items, int32_t n) {
+    if (!ctx) return AGZO_EINVAL;
+    if (n < 0 || (n > 0 && !items)) return fail(ctx, AGZO_EINVAL, "bad item list");
+    size_t need = 0;
+    for (int m = 0; m < n; ++m) {
+        const agzo_update_item& u = items[m];
+        if (u.reserved != 0) return fail(ctx, AGZO_EINVAL, "item %d: reserved field must be 0", m);
+        TRY(check_update(ctx, u.W, u.B, u.dtype, u.d_out, u.d_in, u.ldw, u.r));
+        need += update_workspace_bytes(u.dtype, u.d_out, u.d_in, u.r);
+    }
+    TRY(reserve(ctx, need));
+    // fp32 matrices one by one (no workspace); bf16 matrices by padded rank, update_many_max() to a pair of launches
+    size_t off = 0;
+    for (int nk = 0; nk <= (kMaxRank + 15) / 16; ++nk) {
+        std::vector<UpdateDesc> group;
+        size_t group_bytes = 0;
+        auto flush = [&]() -> int {
+            if (group.empty()) return 0;
+            ProfScope ps(ctx, AGZO_PROF_UPDATE);
+            HIPCHK(launch_update_many(group.data(), (int)group.size(), nk, ctx->ws + off, ctx->stream));
+            off += group_bytes;
+            group.clear();
+            group_bytes = 0;
+            return 0;
+        };
+        for (int m = 0; m < n; ++m) {
+            const agzo_update_item& u = items[m];
+            if (nk == 0) {
+                if (u.dtype != AGZO_F32) continue;
+                ProfScope ps(ctx, AGZO_PROF_UPDATE);
+                HIPCHK(launch_update(u.W, u.dtype, u.ldw, u.d_out, u.d_in, u.B, u.r, u.seed, u.lr, u.g_dev, nullptr, ctx->stream));
+                continue;
+            }
+            if (u.dtype != AGZO_BF16 || (u.r + 15) / 16 != nk) continue;
+            group.push_back(UpdateDesc{u.W, u.B, u.g_dev, u.ldw, u.d_out, u.d_in, u.seed, u.lr, u.r});
+            group_bytes += update_workspace_bytes(u.dtype, u.d_out, u.d_in, u.r);
+            if ((int)group.size() == update_many_max()) TRY(flush());
+        }
+        TRY(flush());
+    }
     return AGZO_OK;
 }
 
@@ -618,8 +667,10 @@ int agzo_two_point(agzo_ctx* ctx, double* out4_dev, float eps, int32_t flags) {
     return AGZO_OK;
 }
 
-int agzo_step(agzo_ctx* ctx, const agzo_layer* L, void* W, const void* X, const agzo_loss_spec* loss, int32_t K,
-              float eps, float lr, uint64_t seed, int32_t flags, double* out_dev) {
+// Alg. 2 for one layer.  B_out == NULL: the basis stays in the workspace and the update runs at the end;
+// otherwise the basis goes to B_out and W is left as it was (the caller updates once g is final).
+static int step_impl(agzo_ctx* ctx, const agzo_layer* L, void* W, const void* X, const agzo_loss_spec* loss, int32_t K,
+                     float eps, float lr, uint64_t seed, int32_t flags, double* out_dev, float* B_out) {
     TRY(check_layer(ctx, L, true));
     if (!W || !X || !out_dev) return fail(ctx, AGZO_EINVAL, "W, X or out_dev is NULL");
     if (!loss || loss->kind == AGZO_LOSS_NONE) return fail(ctx, AGZO_EINVAL, "a step needs a loss");
@@ -631,7 +682,7 @@ int agzo_step(agzo_ctx* ctx, const agzo_layer* L, void* W, const void* X, const 
                              (flags & AGZO_SHARED_FORWARD) && !(flags & AGZO_NAIVE_INPLACE));
     TRY(reserve(ctx, p.total));
     hipStream_t st = ctx->stream;
-    float* B = wsf(ctx, p.off_B);
+    float* B = B_out ? B_out : wsf(ctx, p.off_B);
     const bool one_sided = (flags & AGZO_ONE_SIDED) != 0;
     // squared error: the forwards leave their tile partials side by side and one launch reduces them and forms g;
     // cross-entropy finishes each loss on its own and only g is left to do
@@ -654,7 +705,7 @@ int agzo_step(agzo_ctx* ctx, const agzo_layer* L, void* W, const void* X, const 
         TRY(op_project(ctx, *L, p, X, B, P, true));
         TRY(op_forward(ctx, *L, p, W, X, P, eps, seed, nullptr, loss, out_dev, true, 0, mse));
         TRY(finish(3));
-        TRY(op_update(ctx, *L, p.off_upd, W, B, seed, lr, out_dev + 3));
+        if (!B_out) TRY(op_update(ctx, *L, p.off_upd, W, B, seed, lr, out_dev + 3));
         return AGZO_OK;
     }
     // 1. base forward f0 and subspace extraction from the same activations (Alg. 2, part 1)
@@ -679,8 +730,19 @@ int agzo_step(agzo_ctx* ctx, const agzo_layer* L, void* W, const void* X, const 
     }
     // 3. scalar g and the rank-r update
     TRY(finish(one_sided ? 2 : 3));
-    TRY(op_update(ctx, *L, p.off_upd, W, B, seed, lr, out_dev + 3));
+    if (!B_out) TRY(op_update(ctx, *L, p.off_upd, W, B, seed, lr, out_dev + 3));
     return AGZO_OK;
+}
+
+int agzo_step(agzo_ctx* ctx, const agzo_layer* L, void* W, const void* X, const agzo_loss_spec* loss, int32_t K,
+              float eps, float lr, uint64_t seed, int32_t flags, double* out_dev) {
+    return step_impl(ctx, L, W, X, loss, K, eps, lr, seed, flags, out_dev, nullptr);
+}
+
+int agzo_step_no_update(agzo_ctx* ctx, const agzo_layer* L, void* W, const void* X, const agzo_loss_spec* loss,
+                        int32_t K, float eps, uint64_t seed, int32_t flags, double* out_dev, float* B_out) {
+    if (ctx && !B_out) return fail(ctx, AGZO_EINVAL, "B_out is NULL");
+    return step_impl(ctx, L, W, X, loss, K, eps, 0.f, seed, flags, out_dev, B_out);
 }
 
 }  // extern "C"

@@ -167,6 +167,19 @@ hipError_t launch_qr(const float* S, const float* splits, int nsplit, int rp, fl
 size_t update_workspace_bytes(int dtype, int64_t d_out, int64_t d_in, int r);
 hipError_t launch_update(void* W, int dtype, int64_t ldw, int64_t d_out, int64_t d_in, const float* B, int r,
                          uint64_t seed, float lr, const double* g_dev, void* workspace, hipStream_t st);
+// the same for n bf16 matrices that share nk = ceil(r / 16), n <= update_many_max(), in two launches; the workspace
+// holds the sum of their update_workspace_bytes()
+struct UpdateDesc {
+    void* W;
+    const float* B;
+    const double* g_dev;
+    int64_t ldw, d_out, d_in;
+    uint64_t seed;
+    float lr;
+    int r;
+};
+int update_many_max();
+hipError_t launch_update_many(const UpdateDesc* d, int n, int nk, void* workspace, hipStream_t st);
 
 // loss.hip
 // cross-entropy from the GEMM's per-chunk softmax statistics: out[ph] = mean over rows with target >= 0 of

@@ -134,12 +134,10 @@ constexpr int UM_COLS = 256;    // columns of W per workgroup
 // fragment stores (uint4 units):
 //   Gf [row block ib][kc][plane][lane]        lane = (i % 32) + 32 * lh,      k = 16 kc + 8 lh + 0..7
 //   Bf [col block jb][kc][plane][m][lane]     lane = c + 32 * lh, j = 256 jb + 8 c + m, same k
-__global__ __launch_bounds__(256) void update_prep_kernel(uint4* __restrict__ Gf, uint4* __restrict__ Bf,
-                                                          int64_t n_g, int64_t n_b, int nk, int64_t d_out,
-                                                          int64_t d_in, const float* __restrict__ B, int r,
-                                                          uint32_t s_lo, uint32_t s_hi, float lr,
-                                                          const double* __restrict__ g_dev) {
-    const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+__device__ __forceinline__ void prep_fragment(uint4* __restrict__ Gf, uint4* __restrict__ Bf, int64_t n_g, int64_t n_b,
+                                              int nk, int64_t d_out, int64_t d_in, const float* __restrict__ B, int r,
+                                              uint32_t s_lo, uint32_t s_hi, float lr,
+                                              const double* __restrict__ g_dev, int64_t t) {
     float f[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     FragU hi, lo;
     if (t < n_g) {
@@ -180,14 +178,48 @@ __global__ __launch_bounds__(256) void update_prep_kernel(uint4* __restrict__ Gf
     }
 }
 
+__global__ __launch_bounds__(256) void update_prep_kernel(uint4* __restrict__ Gf, uint4* __restrict__ Bf,
+                                                          int64_t n_g, int64_t n_b, int nk, int64_t d_out,
+                                                          int64_t d_in, const float* __restrict__ B, int r,
+                                                          uint32_t s_lo, uint32_t s_hi, float lr,
+                                                          const double* __restrict__ g_dev) {
+    prep_fragment(Gf, Bf, n_g, n_b, nk, d_out, d_in, B, r, s_lo, s_hi, lr, g_dev, (int64_t)blockIdx.x * 256 + threadIdx.x);
+}
+
+// Several matrices in one pair of launches (Alg. 2 updates every layer once the scalar g is known): the table is a
+// kernel argument, a workgroup finds its matrix from the running block counts (uniform, a handful of scalar compares).
+constexpr int UPD_MAX = 16;
+struct UpdItem {
+    bf16_t* W;
+    uint4 *Gf, *Bf;
+    const float* B;
+    const double* g_dev;
+    int64_t ldw, d_out, d_in, n_g, n_b;
+    uint32_t prep_blk0, sweep_blk0;   // first workgroup of this matrix in the two launches
+    uint32_t s_lo, s_hi;
+    float lr;
+    int r, njb, row_iters;
+};
+struct UpdBatch {
+    int n;
+    UpdItem it[UPD_MAX];
+};
+
+__global__ __launch_bounds__(256) void update_prep_many_kernel(const UpdBatch tb, int nk) {
+    int m = 0;
+    while (m + 1 < tb.n && blockIdx.x >= tb.it[m + 1].prep_blk0) ++m;
+    const UpdItem& u = tb.it[m];
+    prep_fragment(u.Gf, u.Bf, u.n_g, u.n_b, nk, u.d_out, u.d_in, u.B, u.r, u.s_lo, u.s_hi, u.lr, u.g_dev,
+                  (int64_t)(blockIdx.x - u.prep_blk0) * 256 + threadIdx.x);
+}
+
 template <int NK>   // NK = rp / 16
-__global__ __launch_bounds__(256, 2) void update_mfma_kernel(bf16_t* __restrict__ W, int64_t ldw, int64_t d_out,
-                                                             int64_t d_in, const uint4* __restrict__ Gf,
-                                                             const uint4* __restrict__ Bf, int row_iters) {
+__device__ __forceinline__ void sweep_columns(bf16_t* __restrict__ W, int64_t ldw, int64_t d_out, int64_t d_in,
+                                              const uint4* __restrict__ Gf, const uint4* __restrict__ Bf, int row_iters,
+                                              int64_t jb, int64_t by) {
     extern __shared__ __align__(16) uint4 um_smem[];   // [NK][2][8][64]
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int c = lane & 31, lh = lane >> 5;
-    const int64_t jb = blockIdx.x;
     {
         const uint4* src = Bf + jb * (NK * 2 * 8 * 64);
 #pragma unroll
@@ -196,18 +228,28 @@ __global__ __launch_bounds__(256, 2) void update_mfma_kernel(bf16_t* __restrict_
     __syncthreads();
     const int64_t jc = jb * UM_COLS + 8 * c;     // this lane's eight consecutive columns
     const bool col_ok = jc < d_in;               // d_in is a multiple of 8: the piece is all in or all out
+    const uint32_t voff = (uint32_t)((4 * lh * ldw + 8 * c) * 2);   // bytes from the tile's corner; ldw < 2^28 (host check)
 
     for (int it = 0; it < row_iters; ++it) {
-        const int64_t ib = ((int64_t)blockIdx.y * row_iters + it) * 4 + wave;
+        const int64_t ib = (by * row_iters + it) * 4 + wave;
         const int64_t i0 = ib * UM_ROWS;
         if (i0 >= d_out) break;                  // wave-uniform
-        // this lane's rows: i0 + 8 (e / 4) + 4 lh + e % 4
+        // this lane's rows: i0 + 8 (e / 4) + 4 lh + e % 4.  Addresses = a wave-uniform row base (scalar registers) plus
+        // one 32-bit lane offset, instead of sixteen 64-bit pointers per lane
+        char* tile;
+        {   // kept in scalar registers: passing the halves through readfirstlane stops the compiler from turning the
+            // sixteen row addresses into per-lane 64-bit induction variables of the row loop
+            const uint64_t a = reinterpret_cast<uint64_t>(W + i0 * ldw + jb * UM_COLS);
+            const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)a), hi = __builtin_amdgcn_readfirstlane((uint32_t)(a >> 32));
+            tile = reinterpret_cast<char*>(((uint64_t)hi << 32) | lo);
+        }
         uint4 wv[16];
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
             const int64_t i = i0 + 8 * (e >> 2) + 4 * lh + (e & 3);
             wv[e] = make_uint4(0, 0, 0, 0);
-            if (col_ok && i < d_out) wv[e] = *reinterpret_cast<const uint4*>(W + i * ldw + jc);
+            if (col_ok && i < d_out)
+                wv[e] = *reinterpret_cast<const uint4*>(tile + (int64_t)(8 * (e >> 2) + (e & 3)) * ldw * 2 + voff);
         }
         floatx16 z[8];
 #pragma unroll
@@ -239,9 +281,25 @@ __global__ __launch_bounds__(256, 2) void update_mfma_kernel(bf16_t* __restrict_
                 const float w0 = __uint_as_float(pw[q] << 16), w1 = __uint_as_float(pw[q] & 0xFFFF0000u);
                 pw[q] = pack_bf16x2(w0 + z[2 * q][e], w1 + z[2 * q + 1][e]);
             }
-            *reinterpret_cast<uint4*>(W + i * ldw + jc) = wv[e];
+            *reinterpret_cast<uint4*>(tile + (int64_t)(8 * (e >> 2) + (e & 3)) * ldw * 2 + voff) = wv[e];
         }
     }
+}
+
+template <int NK>
+__global__ __launch_bounds__(256, 2) void update_mfma_kernel(bf16_t* __restrict__ W, int64_t ldw, int64_t d_out,
+                                                             int64_t d_in, const uint4* __restrict__ Gf,
+                                                             const uint4* __restrict__ Bf, int row_iters) {
+    sweep_columns<NK>(W, ldw, d_out, d_in, Gf, Bf, row_iters, blockIdx.x, blockIdx.y);
+}
+
+template <int NK>
+__global__ __launch_bounds__(256, 2) void update_mfma_many_kernel(const UpdBatch tb) {
+    int m = 0;
+    while (m + 1 < tb.n && blockIdx.x >= tb.it[m + 1].sweep_blk0) ++m;
+    const UpdItem& u = tb.it[m];
+    const uint32_t local = blockIdx.x - u.sweep_blk0, by = local / (uint32_t)u.njb;
+    sweep_columns<NK>(u.W, u.ldw, u.d_out, u.d_in, u.Gf, u.Bf, u.row_iters, local - by * (uint32_t)u.njb, by);
 }
 
 size_t update_workspace_bytes(int dtype, int64_t d_out, int64_t d_in, int r) {
@@ -251,14 +309,19 @@ size_t update_workspace_bytes(int dtype, int64_t d_out, int64_t d_in, int r) {
     return (size_t)(nib * nk * 2 * 64 + njb * nk * 2 * 8 * 64) * sizeof(uint4);
 }
 
+// more rows per workgroup (fewer reloads of the basis fragments) once the grid still covers the chip a few times
+static int sweep_row_iters(int64_t njb, int64_t ngroups) {
+    int row_iters = 1;
+    while (row_iters < 4 && njb * (ngroups / (2 * row_iters)) >= 2048) row_iters *= 2;
+    return row_iters;
+}
+
 template <int NK>
 static hipError_t launch_mfma(bf16_t* W, int64_t ldw, int64_t d_out, int64_t d_in, const uint4* Gf, const uint4* Bf,
                               hipStream_t st) {
     const int64_t njb = (d_in + UM_COLS - 1) / UM_COLS;
     const int64_t ngroups = (d_out + 4 * UM_ROWS - 1) / (4 * UM_ROWS);
-    // more rows per workgroup (fewer reloads of the basis fragments) once the grid still covers the chip a few times
-    int row_iters = 1;
-    while (row_iters < 4 && njb * (ngroups / (2 * row_iters)) >= 2048) row_iters *= 2;
+    const int row_iters = sweep_row_iters(njb, ngroups);
     dim3 grid((unsigned)njb, (unsigned)((ngroups + row_iters - 1) / row_iters));
     const size_t smem = (size_t)NK * 2 * 8 * 64 * sizeof(uint4);
     hipLaunchKernelGGL((update_mfma_kernel<NK>), grid, dim3(256), smem, st, W, ldw, d_out, d_in, Gf, Bf, row_iters);
@@ -296,7 +359,7 @@ hipError_t launch_update(void* W, int dtype, int64_t ldw, int64_t d_out, int64_t
         if (r <= 8) return launch_kc<8>(Wf, ldw, d_out, d_in, B, r, 1, seed, lr, g_dev, st);
         return launch_kc<16>(Wf, ldw, d_out, d_in, B, r, (r + 15) / 16, seed, lr, g_dev, st);
     }
-    if (!workspace) return hipErrorInvalidValue;
+    if (!workspace || ldw >= (1LL << 28)) return hipErrorInvalidValue;   // the sweep's lane offsets are 32-bit
     const int nk = (r + 15) / 16;
     const int64_t nib = (d_out + UM_ROWS - 1) / UM_ROWS, njb = (d_in + UM_COLS - 1) / UM_COLS;
     const int64_t n_g = nib * nk * 64, n_b = njb * nk * 8 * 64;
@@ -315,6 +378,55 @@ hipError_t launch_update(void* W, int dtype, int64_t ldw, int64_t d_out, int64_t
     }
 }
 
+// bf16 matrices of one padded rank (nk = ceil(r / 16) the same for all), at most UPD_MAX of them: one preparation
+// launch and one sweep for the lot.  The workspace holds the fragments of all of them back to back.
+hipError_t launch_update_many(const UpdateDesc* d, int n, int nk, void* workspace, hipStream_t st) {
+    if (n < 1 || n > UPD_MAX || !workspace) return hipErrorInvalidValue;
+    UpdBatch tb;
+    tb.n = 0;
+    uint4* ws = static_cast<uint4*>(workspace);
+    int64_t prep_blocks = 0, sweep_blocks = 0;
+    for (int m = 0; m < n; ++m) {
+        if (d[m].d_out == 0 || d[m].d_in == 0) continue;
+        if (d[m].ldw >= (1LL << 28)) return hipErrorInvalidValue;
+        UpdItem& u = tb.it[tb.n++];
+        const int64_t nib = (d[m].d_out + UM_ROWS - 1) / UM_ROWS, njb = (d[m].d_in + UM_COLS - 1) / UM_COLS;
+        const int64_t ngroups = (d[m].d_out + 4 * UM_ROWS - 1) / (4 * UM_ROWS);
+        u.W = static_cast<bf16_t*>(d[m].W);
+        u.Gf = ws;
+        u.Bf = ws + nib * nk * 2 * 64;
+        ws = u.Bf + njb * nk * 2 * 8 * 64;
+        u.B = d[m].B;
+        u.g_dev = d[m].g_dev;
+        u.ldw = d[m].ldw; u.d_out = d[m].d_out; u.d_in = d[m].d_in;
+        u.n_g = nib * nk * 64; u.n_b = njb * nk * 8 * 64;
+        u.s_lo = (uint32_t)d[m].seed; u.s_hi = (uint32_t)(d[m].seed >> 32);
+        u.lr = d[m].lr; u.r = d[m].r;
+        u.njb = (int)njb;
+        u.row_iters = sweep_row_iters(njb, ngroups);
+        u.prep_blk0 = (uint32_t)prep_blocks;
+        u.sweep_blk0 = (uint32_t)sweep_blocks;
+        prep_blocks += (u.n_g + u.n_b + 255) / 256;
+        sweep_blocks += njb * ((ngroups + u.row_iters - 1) / u.row_iters);
+    }
+    if (tb.n == 0) return hipSuccess;
+    if (prep_blocks > 0x7FFFFFFFLL || sweep_blocks > 0x7FFFFFFFLL) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(update_prep_many_kernel, dim3((unsigned)prep_blocks), dim3(256), 0, st, tb, nk);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const size_t smem = (size_t)nk * 2 * 8 * 64 * sizeof(uint4);
+    const dim3 grid((unsigned)sweep_blocks);
+    switch (nk) {
+        case 1: hipLaunchKernelGGL((update_mfma_many_kernel<1>), grid, dim3(256), smem, st, tb); break;
+        case 2: hipLaunchKernelGGL((update_mfma_many_kernel<2>), grid, dim3(256), smem, st, tb); break;
+        case 3: hipLaunchKernelGGL((update_mfma_many_kernel<3>), grid, dim3(256), smem, st, tb); break;
+        case 4: hipLaunchKernelGGL((update_mfma_many_kernel<4>), grid, dim3(256), smem, st, tb); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+int update_many_max() { return UPD_MAX; }
 
 // Dense Gaussian sweep (Eq. 7, the branch for parameters that are not linear-layer weights; Alg. 2 perturb / restore /
 // update lines): theta[i][j] += coef * z(i, j), z from Philox stream AGZO_TAG_DENSE, coef = scale * (*g_dev or 1).

@@ -42,17 +42,24 @@ def x4096():
     return synth.device_powerlaw_x(101, N, 4096)
 
 
-@pytest.mark.parametrize("name,d_out,target_dtype,R", [("k", 1024, torch.bfloat16, 16), ("k", 1024, torch.float32, 16),
-                                                       ("q", 4096, torch.bfloat16, 16),
-                                                       ("k", 1024, torch.bfloat16, 64)])      # the largest rank
-def test_full_step_against_full_oracle(ctx, x4096, name, d_out, target_dtype, R):
+# batched: the calls bench.py times (the step up to g, then the update through agzo_update_many); otherwise agzo_step
+@pytest.mark.parametrize("name,d_out,target_dtype,R,batched", [("k", 1024, torch.bfloat16, 16, True),
+                                                               ("k", 1024, torch.float32, 16, False),
+                                                               ("q", 4096, torch.bfloat16, 16, True),
+                                                               ("k", 1024, torch.bfloat16, 64, False)])   # the largest rank
+def test_full_step_against_full_oracle(ctx, x4096, name, d_out, target_dtype, R, batched):
     X = x4096
     W, T = synth.device_weights_and_target(7 + d_out, X, d_out, target_dtype=target_dtype)
     W0 = host(W)
     Xh, Th = host(X), host(T)
     out = torch.zeros(4, dtype=torch.float64, device="cuda")
     seed = 4321
-    ctx.step(binding.make_layer(W, X, R), W, X, binding.make_loss(T), K, EPS, LR, seed, 0, out)
+    if batched:
+        B = torch.empty(X.shape[1], R, dtype=torch.float32, device="cuda")
+        ctx.step_no_update(binding.make_layer(W, X, R), W, X, binding.make_loss(T), K, EPS, seed, 0, out, B)
+        ctx.update_many([(W, B, seed, LR, out[3:4])])
+    else:
+        ctx.step(binding.make_layer(W, X, R), W, X, binding.make_loss(T), K, EPS, LR, seed, 0, out)
     ctx.check()
     o = oagzo.agzo_step(W0, Xh, Th, R, K, EPS, LR, seed, storage="bf16")
     got = out.cpu().numpy()
@@ -121,6 +128,40 @@ def test_wide_projections_sampled(ctx, x4096, name, d_in, d_out):
     wrows = np.sort(rng.choice(d_out, size=64, replace=False))
     want = oagzo.round_bf16(W0[wrows] - LR * got[3] * Zg[wrows])
     assert rel(host(W)[wrows], want) < 3e-3
+
+
+def test_layer_set_updated_in_one_call_at_full_size(ctx):
+    """The seven matrices of the benchmark's layer set through agzo_update_many: every matrix bit-identical to its own
+    agzo_update, and sampled rows against the oracle's W - lr g G B^T."""
+    rng = np.random.default_rng(3)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(11)
+    items, checks = [], []
+    for li, (name, d_in, d_out) in enumerate(synth.QWEN3_8B_LAYER):
+        W = (0.02 * torch.randn(d_out, d_in, device="cuda", generator=gen)).to(torch.bfloat16)
+        Bh, _ = np.linalg.qr(rng.standard_normal((d_in, R)))
+        B = torch.from_numpy(Bh.astype(np.float32)).cuda()
+        g = torch.tensor([(-1.0) ** li * (0.3 + li)], dtype=torch.float64, device="cuda")
+        items.append((W, B, 900 + li, 1e-2, g))
+        checks.append((W.clone(), Bh.astype(np.float32).astype(np.float64), g.item()))
+    ctx.update_many(items)
+    ctx.check()
+    for (W, B, seed, lr, g), (W0, Bh, gv) in zip(items, checks):
+        d_out, d_in = W0.shape
+        wrows = np.sort(rng.choice(d_out, size=48, replace=False))
+        idx = torch.from_numpy(wrows).cuda()
+        G = oagzo.gaussian_factor(seed, d_out, R)[wrows]
+        want = oagzo.round_bf16(host(W0[idx]) - np.float64(np.float32(lr)) * gv * (G @ Bh.T))
+        assert rel(host(W[idx]), want) < 3e-3
+        assert rel(host(W[idx]) - host(W0[idx]), want - host(W0[idx])) < 5e-3
+        single = W0                                     # update the untouched copy with the single-matrix call
+        Ls = binding.AgzoLayer()
+        Ls.n_tokens, Ls.d_in, Ls.d_out, Ls.r = 0, d_in, d_out, R
+        Ls.dtype = Ls.y_dtype = binding.BF16
+        Ls.tiling, Ls.ldw, Ls.ldx, Ls.ldy = 0, d_in, d_in, d_out
+        ctx.update(Ls, single, B, seed, lr, g)
+        assert torch.equal(single, W)
+    ctx.check()
 
 
 def test_bench_line_has_the_contract_fields():

@@ -202,6 +202,110 @@ def test_forward_sketch_basis_perturbed_update(ctx, storage, n, d_in, d_out, r, 
     ctx.check()
 
 
+# ---------------------------------------------------------------------------------------------
+# several matrices updated in one call
+# ---------------------------------------------------------------------------------------------
+def _update_set(n_small):
+    """(storage, d_out, d_in, r, row stride or None, g or None): mixed ranks (four padded widths), an fp32 matrix,
+    a matrix inside a wider allocation, ragged row and column tails, and n_small equal small ones to overflow a batch."""
+    base = [("bf16", 264, 200, 8, None, -0.731), ("bf16", 40, 72, 1, None, None), ("bf16", 520, 1024, 16, None, 0.4),
+            ("bf16", 300, 136, 24, None, 1.7), ("bf16", 520, 192, 64, None, -0.2), ("f32", 70, 100, 4, None, 0.9),
+            ("bf16", 130, 264, 40, 272, 0.55), ("bf16", 1, 8, 3, None, -1.0)]
+    return base + [("bf16", 96 + 8 * i, 256 + 8 * i, 16, None, 0.1 * (i + 1)) for i in range(n_small)]
+
+
+def test_update_many_matches_oracle_and_single_updates(ctx):
+    rng = np.random.default_rng(77)
+    items, singles, wants = [], [], []
+    for idx, (storage, d_out, d_in, r, ld, g) in enumerate(_update_set(19)):
+        W = (0.02 * rng.standard_normal((d_out, d_in))).astype(np.float32)
+        if storage == "bf16":
+            W = synth.to_bf16_values(W)
+        B, _ = np.linalg.qr(rng.standard_normal((d_in, r)))
+        B32 = B.astype(np.float32)
+        seed = 1000 + idx
+        if ld is None:
+            Wa, Wb = dev(W, storage), dev(W, storage)
+        else:       # a view with a row stride larger than d_in; the columns beyond d_in must stay as they are
+            Wa = torch.full((d_out, ld), 3.0, dtype=torch.bfloat16, device="cuda")
+            Wa[:, :d_in] = dev(W, storage)
+            Wb = Wa.clone()
+            Wa, Wb = Wa[:, :d_in], Wb[:, :d_in]
+        gd = None if g is None else torch.tensor([g], dtype=torch.float64, device="cuda")
+        Bd = dev(B32)
+        items.append((Wa, Bd, seed, LR, gd))
+        singles.append((Wb, Bd, seed, gd, r))
+        Z, G = oagzo.perturbation(B32.astype(np.float64), seed, d_out)
+        wants.append((storage, oagzo.round_storage(W.astype(np.float64) - LR * (1.0 if g is None else g) * Z, storage), W))
+    ctx.update_many(items)
+    ctx.check()
+    for (Wa, _, _, _, _), (Wb, Bd, seed, gd, r), (storage, want, W) in zip(items, singles, wants):
+        ctx.update(_layer_for(Wb, r), Wb, Bd, seed, LR, gd)
+        assert torch.equal(Wa, Wb), (tuple(Wa.shape), r)                 # same arithmetic: the same bits
+        assert rel(host(Wa), want) < (1e-6 if storage == "f32" else 2e-3)
+        assert rel(host(Wa) - W, want - W) < (1e-4 if storage == "f32" else 0.2)
+        if Wa.stride(0) != Wa.shape[1]:
+            assert (Wa._base[:, Wa.shape[1]:] == 3.0).all()
+    ctx.check()
+
+
+def _layer_for(W, r):
+    L = binding.AgzoLayer()
+    L.n_tokens, L.d_in, L.d_out, L.r = 0, W.shape[1], W.shape[0], r
+    L.dtype = L.y_dtype = binding.F32 if W.dtype == torch.float32 else binding.BF16
+    L.tiling, L.ldw, L.ldx, L.ldy = 0, W.stride(0), W.shape[1], W.shape[0]
+    return L
+
+
+def test_update_many_rejects_bad_lists_and_accepts_an_empty_one(ctx):
+    W = torch.zeros(16, 32, dtype=torch.bfloat16, device="cuda")
+    B = torch.ones(32, 4, dtype=torch.float32, device="cuda")
+    ctx.update_many([])
+    arr = (binding.AgzoUpdateItem * 2)()
+    for it in arr:
+        it.W, it.B, it.g_dev, it.d_out, it.d_in, it.ldw = W.data_ptr(), B.data_ptr(), 0, 16, 32, 32
+        it.r, it.dtype, it.seed, it.lr, it.reserved = 4, binding.BF16, 5, 1.0, 0
+    for n, poke in ((-1, None), (2, ("reserved", 1)), (2, ("r", 65)), (2, ("ldw", 24)), (2, ("dtype", 7)), (2, ("W", 0)),
+                    (2, ("d_in", 36))):
+        saved = None
+        if poke:
+            saved = getattr(arr[1], poke[0])
+            setattr(arr[1], poke[0], poke[1])
+        with pytest.raises(binding.AgzoError) as e:
+            ctx.update_many_raw(arr, n)
+        assert e.value.code == binding.EINVAL
+        if poke:
+            setattr(arr[1], poke[0], saved)
+    with pytest.raises(binding.AgzoError) as e:
+        ctx.update_many_raw(None, 1)
+    assert e.value.code == binding.EINVAL
+    ctx.check()
+    assert (W == 0).all()          # the first, valid item of a rejected list was not touched
+
+
+@pytest.mark.parametrize("storage,n,d_in,d_out,r", [("f32", 512, 256, 256, 4), ("bf16", 600, 1024, 520, 16)])
+@pytest.mark.parametrize("flags", [0, binding.ONE_SIDED, binding.SHARED_FORWARD])
+def test_step_without_update_then_update_many_equals_step(ctx, storage, n, d_in, d_out, r, flags):
+    W, X, T, Wd, Xd, Td = problem(7 + n, n, d_in, d_out, "rmsnorm" if storage == "bf16" else "lowrank", storage)
+    L = binding.make_layer(Wd, Xd, r)
+    loss = binding.make_loss(Td)
+    W1, W2 = Wd.clone(), Wd.clone()
+    out1 = torch.zeros(4, dtype=torch.float64, device="cuda")
+    out2 = torch.zeros(4, dtype=torch.float64, device="cuda")
+    ctx.step(L, W1, Xd, loss, 3, EPS, LR, 99, flags, out1)
+    B = torch.empty(d_in, r, dtype=torch.float32, device="cuda")
+    ctx.step_no_update(L, W2, Xd, loss, 3, EPS, 99, flags, out2, B)
+    ctx.check()
+    assert torch.equal(W2, Wd)                       # untouched so far
+    assert torch.equal(out1, out2)
+    ctx.update_many([(W2, B, 99, LR, out2[3:4])])
+    ctx.check()
+    assert torch.equal(W1, W2)
+    with pytest.raises(binding.AgzoError) as e:
+        ctx.step_no_update(L, W2, Xd, loss, 3, EPS, 99, flags, out2, None)
+    assert e.value.code == binding.EINVAL
+
+
 @pytest.mark.parametrize("storage,n,d_in,d_out,r,kind", [
     ("f32", 512, 256, 256, 4, "lowrank"),
     ("bf16", 515, 136, 300, 8, "lowrank"),
