@@ -366,6 +366,31 @@ def main():
         res["naive_inplace"] = {"value": nsteps / dt2, "unit": "steps/s", "ms_per_step": 1e3 * dt2 / nsteps, "steps": nsteps,
                                 "note": "perturb-in-place / undo comparator (4 extra sweeps of W per step; in bf16 a different "
                                         "computation: the perturbation is rounded into the weights)"}
+        # the dense branch of Eq. 7 applied to the same matrices (the zeroth-order baseline the paper compares with): no
+        # extraction, two plain forwards, four in-place sweeps that regenerate d_out x d_in normals each
+        def dense_step(step):
+            for li, (L, W, X, loss) in enumerate(descs):
+                seed = 1000 * step + li
+                ctx.dense_perturb(W, seed, eps)
+                ctx.layer_forward_sketch(L, W, X, None, binding.SKETCH_NONE, None, seed, None, loss, out[li, 1:2])
+                ctx.dense_perturb(W, seed, -2.0 * eps)
+                ctx.layer_forward_sketch(L, W, X, None, binding.SKETCH_NONE, None, seed, None, loss, out[li, 2:3])
+                ctx.dense_perturb(W, seed, eps)
+                ctx.two_point(out[li], eps)
+                ctx.dense_perturb(W, seed, -lr, out[li, 3:4])
+
+        dense_step(50_000)
+        torch.cuda.synchronize()
+        t5 = time.perf_counter()
+        for s in range(nsteps):
+            dense_step(50_001 + s)
+        torch.cuda.synchronize()
+        dt5 = time.perf_counter() - t5
+        ctx.check()
+        res["dense_gaussian"] = {"value": nsteps / dt5, "unit": "steps/s", "ms_per_step": 1e3 * dt5 / nsteps, "steps": nsteps,
+                                 "agzo_over_dense": (args.steps / dt) / (nsteps / dt5),
+                                 "note": "Eq. 7's dense branch on the same matrices, composed from agzo_dense_perturb, the plain "
+                                         "forward and agzo_two_point: two forwards and four generator-bound sweeps per projection"}
     # the standalone generator fill (the form in which the Gaussian factor is checked bit for bit): 2^28 normals
     gbuf = torch.empty(1 << 24, 16, dtype=torch.float32, device="cuda")
     ctx.fill_normal(gbuf, 1, binding.TAG_G)

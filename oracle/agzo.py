@@ -224,3 +224,25 @@ def agzo_step_inplace(W, X, target, B, eps, lr, seed, loss="mse", storage="f32")
     Wr = apply_rank_r(Wm, B, seed, +eps, storage)          # restore
     W_new = apply_rank_r(Wr, B, seed, -lr * g, storage)    # update
     return {"L0": L0, "Lp": Lp, "Lm": Lm, "g": g, "W_new": W_new, "Wp": Wp, "Wm": Wm}
+
+
+def dense_step(W, X, target, eps, lr, seed, loss="mse", storage="f32", one_sided=False):
+    """Alg. 2 for a parameter block taken through the other branch of Eq. 7 (a dense Gaussian R of the block's
+    own shape instead of G B^T), here the weight of one linear layer: the estimator the paper compares against.
+    There is no factored form, so the schedule is the literal one: every sweep stores the block in its
+    storage type (perturb +eps, evaluate, to the other side -2 eps, evaluate, restore +eps, update -lr g)."""
+    W0 = np.asarray(W, dtype=np.float64)
+    L0 = loss_value(forward(X, W0), loss, target) if one_sided else 0.0
+    Wp = dense_apply(W0, seed, +eps, storage)
+    Lp = loss_value(forward(X, Wp), loss, target)
+    if one_sided:
+        Lm, Wr = 0.0, dense_apply(Wp, seed, -eps, storage)
+        g = (Lp - L0) / eps
+    else:
+        Wm = dense_apply(Wp, seed, -2.0 * eps, storage)
+        Lm = loss_value(forward(X, Wm), loss, target)
+        Wr = dense_apply(Wm, seed, +eps, storage)
+        g = (Lp - Lm) / (2.0 * eps)
+    W_new = dense_apply(Wr, seed, -lr * g, storage)
+    return {"L0": L0, "Lp": Lp, "Lm": Lm, "g": g, "W_restored": Wr, "W_new": W_new}
+

@@ -411,6 +411,46 @@ def test_naive_inplace_comparator_has_its_own_oracle(ctx):
         assert rel(host(Wd), o["W_new"]) < tolW
 
 
+@pytest.mark.parametrize("storage,one_sided", [("f32", False), ("bf16", False), ("bf16", True)])
+def test_dense_gaussian_step_composed_from_the_calls(ctx, storage, one_sided):
+    """Alg. 2 with a linear layer's weight taken through the dense branch of Eq. 7 (the estimator the paper compares
+    with), composed from the library's calls: in-place dense sweeps, plain forwards with the fused loss, the scalar,
+    the update sweep with g read from the device."""
+    W, X, T, Wd, Xd, Td = problem(9, 300, 136, 264, "lowrank", storage)
+    eps, lr, seed = float(np.float32(1e-2)), LR, 57
+    L = binding.make_layer(Wd, Xd, 1)
+    loss = binding.make_loss(Td)
+    out = torch.zeros(4, dtype=torch.float64, device="cuda")
+    flags = binding.ONE_SIDED if one_sided else 0
+
+    def f(slot):
+        ctx.layer_forward_sketch(L, Wd, Xd, None, binding.SKETCH_NONE, None, seed, None, loss, out[slot:slot + 1])
+
+    if one_sided:
+        f(0)
+    ctx.dense_perturb(Wd, seed, +eps)
+    f(1)
+    if one_sided:
+        ctx.dense_perturb(Wd, seed, -eps)
+    else:
+        ctx.dense_perturb(Wd, seed, -2.0 * eps)
+        f(2)
+        ctx.dense_perturb(Wd, seed, +eps)
+    restored = host(Wd)
+    ctx.two_point(out, eps, flags)
+    ctx.dense_perturb(Wd, seed, -lr, out[3:4])
+    ctx.check()
+    o = oagzo.dense_step(W, X, T, eps, lr, seed, storage=storage, one_sided=one_sided)
+    got = out.cpu().numpy()
+    for k, key in ((0, "L0"), (1, "Lp"), (2, "Lm")):
+        assert abs(got[k] - o[key]) <= 1e-4 * o[key], key
+    assert abs(got[3] - o["g"]) < (2e-3 if storage == "f32" else 2e-2) * abs(o["g"]), (got[3], o["g"])
+    ulp = 2.0 ** -(23 if storage == "f32" else 7)
+    assert np.abs(restored - W).max() <= 4 * ulp * np.abs(W).max()
+    assert rel(host(Wd), o["W_new"]) < (1e-5 if storage == "f32" else 3e-3)
+    assert rel(host(Wd) - restored, o["W_new"] - o["W_restored"]) < (3e-3 if storage == "f32" else 0.2)
+
+
 @pytest.mark.parametrize("target_dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("flags", [0, binding.SHARED_FORWARD])
 def test_tile_aligned_shapes_take_the_specialised_loss_epilogues(ctx, target_dtype, flags):

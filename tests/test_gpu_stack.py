@@ -96,8 +96,8 @@ class GpuStack:
             self.run_pass(-1, eps, seeds, out[2:3])
             sweep_gains(+eps)
         self.ctx.two_point(out, eps, flags)
-        for nm in self.names:
-            self.ctx.update(self.L[nm], self.W[nm], self.B[nm], seeds[nm], lr, out[3:4])
+        # every linear layer moves by the one global g: one batched call (the f32-storage stack: matrix by matrix inside it)
+        self.ctx.update_many([(self.W[nm], self.B[nm], seeds[nm], lr, out[3:4]) for nm in self.names])
         sweep_gains(-lr, out[3:4])
         self.ctx.check()
         return out.cpu().numpy()

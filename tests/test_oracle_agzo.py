@@ -274,3 +274,38 @@ def test_dense_two_point_estimator_mean_is_the_gradient():
         acc += g * R
     err = np.linalg.norm(acc / n - (th - a)) / np.linalg.norm(th - a)
     assert err < 4.0 * math.sqrt((th.size + 1.0) / n)
+
+
+def test_dense_step_is_the_two_point_estimator_along_a_dense_direction():
+    # squared error is quadratic in W, so the central difference along R is exactly <grad, R>
+    rng = np.random.default_rng(12)
+    X = rng.standard_normal((40, 12))
+    W = (0.1 * rng.standard_normal((7, 12))).astype(np.float32).astype(np.float64)
+    T = rng.standard_normal((40, 7))
+    eps, lr, seed = 1e-3, 1e-2, 77
+    R = agzo.dense_perturbation(seed, 7, 12)
+    dd = float((agzo.mse_grad(X, W, T) * R).sum())
+    o = agzo.dense_step(W, X, T, eps, lr, seed, storage="f32")
+    assert abs(o["g"] - dd) < 2e-4 * abs(dd)                  # fp32 storage of the perturbed weights: 2^-24 |W| / eps
+    assert np.abs(o["W_restored"] - W).max() <= 2.0 ** -22 * np.abs(W).max()
+    np.testing.assert_allclose(o["W_new"] - o["W_restored"], -lr * o["g"] * R, rtol=0, atol=2.0 ** -23 * np.abs(W).max())
+    # one-sided form: differs from the central one by the curvature term, eps/2 R^T H R
+    o1 = agzo.dense_step(W, X, T, eps, lr, seed, storage="f32", one_sided=True)
+    curv = (eps / 2.0) * 2.0 * float(((X @ R.T) ** 2).sum()) / (40 * 7)
+    assert abs(o1["g"] - (dd + curv)) < 2e-3 * abs(dd)
+    assert o1["Lm"] == 0.0 and o["L0"] == 0.0
+
+
+def test_dense_direction_alignment_with_a_fixed_vector():
+    # Cor. 5.5's baseline: for an isotropic Gaussian direction in n dimensions, E|cos(R, v)| = Gamma(n/2) / (sqrt(pi) Gamma((n+1)/2))
+    v = np.arange(1.0, 17.0).reshape(4, 4)
+    n_trials = 6000
+    cs = np.empty(n_trials)
+    for s in range(n_trials):
+        R = agzo.dense_perturbation(5000 + s, 4, 4)
+        cs[s] = abs(float((R * v).sum())) / (np.linalg.norm(R) * np.linalg.norm(v))
+    beta16 = math.gamma(8.0) / (math.sqrt(math.pi) * math.gamma(8.5))
+    assert abs(beta16 - 0.20261) < 1e-5
+    # var |cos| = 1/n - beta^2
+    assert abs(cs.mean() - beta16) < 4.0 * math.sqrt((1.0 / 16 - beta16 ** 2) / n_trials)
+
