@@ -189,6 +189,40 @@ def test_estimator_mean_is_projected_gradient():
     assert err < 6.0 * math.sqrt((3 * 2 + 2) / n)      # ~ sqrt((D+2)/n) relative noise, D = d_out r
 
 
+def _beta(D):
+    return math.exp(math.lgamma(D / 2.0) - math.lgamma((D + 1) / 2.0)) / math.sqrt(math.pi)
+
+
+def test_expected_cosine_is_beta_times_captured_gradient_energy():
+    """Thm 5.4 (expected cosine of the noiseless estimator): for a fixed orthonormal basis A,
+    E_R |cos(R A^T, grad)| = beta_{d_out r} |grad A|_F / |grad|_F, beta_D = Gamma(D/2) / (sqrt(pi) Gamma((D+1)/2));
+    the paper prints beta_D's bounds sqrt(2/(pi D)) <= beta_D <= sqrt(2/(pi (D-1)))."""
+    W, X, T = _tiny(4, n=10, d_in=8, d_out=3)
+    r = 2
+    B = agzo.subspace_extract(X, r, 3, seed=1)["B"]
+    grad = agzo.mse_grad(X, W, T)
+    D = 3 * r
+    beta = _beta(D)
+    assert math.sqrt(2 / (math.pi * D)) <= beta <= math.sqrt(2 / (math.pi * (D - 1)))
+    ratio = np.linalg.norm(grad @ B) / np.linalg.norm(grad)
+    assert 0.3 < ratio < 1.0                       # the basis captures part of the gradient, not all: the factor matters
+    n = 8000
+    cs = np.empty(n)
+    for s in range(n):
+        Z, _ = agzo.perturbation(B, 20_000 + s, 3)
+        cs[s] = abs(float((Z * grad).sum())) / (np.linalg.norm(Z) * np.linalg.norm(grad))
+    sigma = ratio * math.sqrt(1.0 / D - beta ** 2)
+    assert abs(cs.mean() - beta * ratio) < 4.0 * sigma / math.sqrt(n)
+    # the dense direction on the same layer (Cor. 5.5): beta_{d_out d_in}, smaller
+    cd = np.empty(n)
+    for s in range(n):
+        Rd = agzo.dense_perturbation(20_000 + s, 3, 8)
+        cd[s] = abs(float((Rd * grad).sum())) / (np.linalg.norm(Rd) * np.linalg.norm(grad))
+    b24 = _beta(24)
+    assert abs(cd.mean() - b24) < 4.0 * math.sqrt((1.0 / 24 - b24 ** 2) / n)
+    assert cs.mean() > 1.3 * cd.mean()
+
+
 # --- losses, rounding ---------------------------------------------------------------
 def test_ce_matches_library_with_ignored_rows():
     rng = np.random.default_rng(10)
