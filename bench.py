@@ -366,6 +366,17 @@ def main():
         res["naive_inplace"] = {"value": nsteps / dt2, "unit": "steps/s", "ms_per_step": 1e3 * dt2 / nsteps, "steps": nsteps,
                                 "note": "perturb-in-place / undo comparator (4 extra sweeps of W per step; in bf16 a different "
                                         "computation: the perturbation is rounded into the weights)"}
+        # the literal one-sided form of Eq. 10 / Alg. 2: the base forward and one perturbed forward per projection
+        one_step(35_000, binding.ONE_SIDED)
+        torch.cuda.synchronize()
+        t7 = time.perf_counter()
+        for s in range(nsteps):
+            one_step(35_001 + s, binding.ONE_SIDED)
+        torch.cuda.synchronize()
+        dt7 = time.perf_counter() - t7
+        ctx.check()
+        res["one_sided"] = {"value": nsteps / dt7, "unit": "steps/s", "ms_per_step": 1e3 * dt7 / nsteps, "steps": nsteps,
+                            "note": "g = (f+ - f0) / eps as printed in Eq. 10: two forwards per projection instead of three"}
         # the dense branch of Eq. 7 applied to the same matrices (the zeroth-order baseline the paper compares with): no
         # extraction, two plain forwards, four in-place sweeps that regenerate d_out x d_in normals each
         def dense_step(step):
@@ -389,8 +400,36 @@ def main():
         ctx.check()
         res["dense_gaussian"] = {"value": nsteps / dt5, "unit": "steps/s", "ms_per_step": 1e3 * dt5 / nsteps, "steps": nsteps,
                                  "agzo_over_dense": (args.steps / dt) / (nsteps / dt5),
+                                 "agzo_one_sided_over_dense": (nsteps / dt7) / (nsteps / dt5),
                                  "note": "Eq. 7's dense branch on the same matrices, composed from agzo_dense_perturb, the plain "
                                          "forward and agzo_two_point: two forwards and four generator-bound sweeps per projection"}
+        # the data-independent low-rank estimator of the paper's Sec. 2 on the same kernels: a Gaussian V [d_in][r] in the
+        # place of the activation basis (no extraction, no base forward), the estimate scaled by 1 / r
+        Vs = [torch.empty(W.shape[1], r, dtype=torch.float32, device="cuda") for _, W, _, _ in descs]
+
+        def lowrank_step(step):
+            for li, (L, W, X, loss) in enumerate(descs):
+                seed = 1000 * step + li
+                ctx.fill_normal(Vs[li], seed, binding.TAG_Q0)
+                ctx.perturbed_forward(L, W, X, Vs[li], seed, eps, None, loss, out[li, 1:2])
+                ctx.perturbed_forward(L, W, X, Vs[li], seed, -eps, None, loss, out[li, 2:3])
+                ctx.two_point(out[li], eps)
+            ctx.update_many([(W, Vs[li], 1000 * step + li, lr / r, out[li, 3:4]) for li, (_, W, _, _) in enumerate(descs)])
+
+        lowrank_step(60_000)
+        torch.cuda.synchronize()
+        t6 = time.perf_counter()
+        for s in range(nsteps):
+            lowrank_step(60_001 + s)
+        torch.cuda.synchronize()
+        dt6 = time.perf_counter() - t6
+        ctx.check()
+        res["lowrank_gaussian"] = {"value": nsteps / dt6, "unit": "steps/s", "ms_per_step": 1e3 * dt6 / nsteps, "steps": nsteps,
+                                   "agzo_over_lowrank": (args.steps / dt) / (nsteps / dt6),
+                                   "agzo_one_sided_over_lowrank": (nsteps / dt7) / (nsteps / dt6),
+                                   "note": "perturbation U V^T with Gaussian factors (Sec. 2), two perturbed forwards and the batched "
+                                           "rank-r update; composed from agzo_fill_normal, agzo_perturbed_forward, agzo_two_point, "
+                                           "agzo_update_many"}
     # the standalone generator fill (the form in which the Gaussian factor is checked bit for bit): 2^28 normals
     gbuf = torch.empty(1 << 24, 16, dtype=torch.float32, device="cuda")
     ctx.fill_normal(gbuf, 1, binding.TAG_G)

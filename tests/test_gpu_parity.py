@@ -451,6 +451,32 @@ def test_dense_gaussian_step_composed_from_the_calls(ctx, storage, one_sided):
     assert rel(host(Wd) - restored, o["W_new"] - o["W_restored"]) < (3e-3 if storage == "f32" else 0.2)
 
 
+@pytest.mark.parametrize("storage", ["f32", "bf16"])
+def test_low_rank_gaussian_step_composed_from_the_calls(ctx, storage):
+    """The data-independent low-rank estimator of Sec. 2 (perturbation U V^T with Gaussian factors, estimate scaled by
+    1 / r) on the rank-r kernels: V takes the place of the activation basis, U is the seeded Gaussian factor."""
+    n, d_in, d_out, r, seed = 300, 136, 264, 8, 23
+    W, X, T, Wd, Xd, Td = problem(13, n, d_in, d_out, "lowrank", storage)
+    L = binding.make_layer(Wd, Xd, r)
+    loss = binding.make_loss(Td)
+    out = torch.zeros(4, dtype=torch.float64, device="cuda")
+    V = torch.empty(d_in, r, dtype=torch.float32, device="cuda")
+    ctx.fill_normal(V, seed, binding.TAG_Q0)
+    ctx.perturbed_forward(L, Wd, Xd, V, seed, +EPS, None, loss, out[1:2])
+    ctx.perturbed_forward(L, Wd, Xd, V, seed, -EPS, None, loss, out[2:3])
+    ctx.two_point(out, EPS)
+    ctx.update(L, Wd, V, seed, LR / r, out[3:4])
+    ctx.check()
+    Vo = ophilox.normal(seed, ophilox.TAG_Q0, d_in, r).astype(np.float64)
+    assert np.abs(host(V) - Vo).max() < 2e-6
+    o = oagzo.agzo_step(W, X, T, r, 0, EPS, float(np.float32(LR / r)), seed, storage=storage, B=host(V))
+    got = out.cpu().numpy()
+    assert abs(got[1] - o["Lp"]) < 1e-5 * o["Lp"] and abs(got[2] - o["Lm"]) < 1e-5 * o["Lm"]
+    assert abs(got[3] - o["g"]) < (2e-3 if storage == "f32" else 2e-2) * abs(o["g"]), (got[3], o["g"])
+    assert rel(host(Wd), o["W_new"]) < (1e-6 if storage == "f32" else 3e-3)
+    assert rel(host(Wd) - W, o["W_new"] - W) < (3e-3 if storage == "f32" else 0.2)
+
+
 @pytest.mark.parametrize("target_dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("flags", [0, binding.SHARED_FORWARD])
 def test_tile_aligned_shapes_take_the_specialised_loss_epilogues(ctx, target_dtype, flags):
