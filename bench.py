@@ -175,13 +175,13 @@ def main():
 
     # Alg. 2 at the level of the layer set: every projection runs its step up to its scalar g, then all the
     # updates go out together (one preparation launch and one sweep for the seven matrices)
-    def step_fn(descs_, out_, r_):
+    def step_fn(descs_, out_, r_, c=ctx):
         bases = [torch.empty(W.shape[1], r_, dtype=torch.float32, device="cuda") for _, W, _, _ in descs_]
 
         def run(step, fl):
             for li, (L, W, X, loss) in enumerate(descs_):
-                ctx.step_no_update(L, W, X, loss, K, eps, 1000 * step + li, fl, out_[li], bases[li])
-            ctx.update_many([(W, bases[li], 1000 * step + li, lr, out_[li, 3:4]) for li, (_, W, _, _) in enumerate(descs_)])
+                c.step_no_update(L, W, X, loss, K, eps, 1000 * step + li, fl, out_[li], bases[li])
+            c.update_many([(W, bases[li], 1000 * step + li, lr, out_[li, 3:4]) for li, (_, W, _, _) in enumerate(descs_)])
         return run
 
     run_step = step_fn(descs, out, r)
@@ -493,6 +493,37 @@ def main():
         res["qwen3_0p6b_layer_set"] = {"value": n_small / dt3, "unit": "steps/s", "ms_per_step": 1e3 * dt3 / n_small,
                                        "tokens": 2048, "rank": 8, "steps": n_small, "stage_ms_per_step": st,
                                        "note": "launch- and latency-bound: 7 projections of 1-3 M parameters each"}
+        # the same step recorded once in a HIP graph on a stream of its own and replayed (the calls enqueue kernels only);
+        # the seeds are part of the recorded arguments, so every replay repeats one step's seeds: the work is the same
+        try:
+            side = torch.cuda.Stream()
+            gctx = binding.Context(stream=side)
+            torch.cuda.synchronize()
+            graph_run = step_fn(s_descs, s_out, 8, gctx)
+            with torch.cuda.stream(side):
+                for s_ in range(3):
+                    graph_run(200 + s_, 0)
+                gctx.check()
+                graph = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(graph, stream=side):
+                    graph_run(300, 0)
+            torch.cuda.synchronize()
+            for s_ in range(5):
+                graph.replay()
+            torch.cuda.synchronize()
+            t8 = time.perf_counter()
+            for s_ in range(n_small):
+                graph.replay()
+            torch.cuda.synchronize()
+            dt8 = time.perf_counter() - t8
+            with torch.cuda.stream(side):
+                gctx.check()
+            res["qwen3_0p6b_layer_set"]["graph_replay"] = {"value": n_small / dt8, "unit": "steps/s",
+                                                           "ms_per_step": 1e3 * dt8 / n_small, "steps": n_small}
+            del graph
+            gctx.close()
+        except (binding.AgzoError, RuntimeError) as e:        # an extra: never a reason to lose the measurement
+            res["qwen3_0p6b_layer_set"]["graph_replay"] = {"error": str(e)[:200]}
         del s_layers, s_descs
     # yardstick for the MFMA fraction: a register-only MFMA loop (no LDS, no memory traffic) on this device, with
     # operand bits that never toggle (zeros) and with N(0,1) bf16 operands like the workload's
