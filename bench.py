@@ -246,12 +246,14 @@ def main():
     upd_avg_ms = ms_upd / max(n_upd, 1)
     upd_gbs = upd_bytes_per_launch / (upd_avg_ms * 1e-3) / 1e9
 
-    traffic = None
+    traffic = upd_traffic = None
     tfile = os.path.join(ROOT, "profiles", "gemm_bf16_qwen3_8b_traffic.txt")
-    if os.path.exists(tfile):
+    if os.path.exists(tfile) and args.workload == "qwen3-8b" and N == 16384 and r == 16:
         for line in open(tfile):
             if line.startswith("traffic_bytes_per_launch"):
                 traffic = float(line.split()[1])
+            if line.startswith("update_traffic_bytes_per_launch") and not args.naive:
+                upd_traffic = float(line.split()[1])
 
     res = {
         "metric": "AGZO steps/sec per layer set (Qwen3-8B layer projections)",
@@ -267,7 +269,8 @@ def main():
                      "shader_clock_ghz": gemm_ghz, "clock_note": "mean shader clock over the first workgroup of each of "
                      "these launches (in-kernel cycle counter / constant-rate counter); the peak assumes 2.4 GHz"},
         "roofline_update": {"bound": "hbm", "kernel": "update_prep_many_kernel + update_mfma_many_kernel (the layer set's matrices in one launch pair)", "achieved": upd_gbs, "peak": PEAK_HBM_GBS,
-                            "unit": "GB/s", "frac": upd_gbs / PEAK_HBM_GBS, "launches": n_upd, "avg_ms": upd_avg_ms},
+                            "unit": "GB/s", "frac": upd_gbs / PEAK_HBM_GBS, "traffic": upd_traffic,
+                            "algorithmic_bytes": upd_bytes_per_launch, "launches": n_upd, "avg_ms": upd_avg_ms},
         "stage_ms_per_step": {"gemm": st_gemm, "update": st_upd, "xq": ms_xq, "xtt": ms_xtt, "qr": ms_qr,
                               "note": "from %d extra steps with every kernel class timed" % nstage},
     }
