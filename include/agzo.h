@@ -48,7 +48,8 @@ typedef enum { AGZO_LOSS_NONE = 0, AGZO_LOSS_MSE = 1, AGZO_LOSS_CE = 2 } agzo_lo
 typedef enum {
     AGZO_SKETCH_NONE = 0,
     AGZO_SKETCH_RANGE = 1, /* S = X^T Omega, Omega [n_tokens][r] Gaussian from (seed, tag 1): Alg. 1, first product */
-    AGZO_SKETCH_POWER = 2  /* S = X^T (X Q) for a given Q [d_in][r]: Alg. 1, power step */
+    AGZO_SKETCH_POWER = 2  /* S = X^T (X Q) for a given Q [d_in][r]: Alg. 1, power step; Q == NULL: Q is the Gaussian
+                              [d_in][r] of (seed, tag 2), the start of the AGZO_INIT_FEATURE variant */
 } agzo_sketch;
 
 /* Philox stream tags: which Gaussian matrix a (seed, tag, row, col) element belongs to. */

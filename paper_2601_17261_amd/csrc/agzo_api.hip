@@ -541,7 +541,6 @@ int agzo_layer_forward_sketch(agzo_ctx* ctx, const agzo_layer* L, const void* W,
     if (mode != AGZO_SKETCH_NONE && mode != AGZO_SKETCH_RANGE && mode != AGZO_SKETCH_POWER)
         return fail(ctx, AGZO_EINVAL, "sketch mode %d", mode);
     if (mode != AGZO_SKETCH_NONE && !S) return fail(ctx, AGZO_EINVAL, "S is NULL");
-    if (mode == AGZO_SKETCH_POWER && !Q) return fail(ctx, AGZO_EINVAL, "power sketch needs Q");
     if (gemm) {
         TRY(check_y(ctx, L, Y));
         TRY(check_loss(ctx, L, loss, loss_dev));
@@ -554,6 +553,11 @@ int agzo_layer_forward_sketch(agzo_ctx* ctx, const agzo_layer* L, const void* W,
         TRY(reduce_to_S(ctx, *L, p, S));
     }
     if (mode == AGZO_SKETCH_POWER) {
+        if (!Q) {   // no Q given: the Gaussian feature-space start of the flagged variant, from the seed
+            float* Q0 = wsf(ctx, p.off_Q);
+            HIPCHK(launch_fill_normal(Q0, L->d_in, L->r, seed, AGZO_TAG_Q0, ctx->stream));
+            Q = Q0;
+        }
         if (L->dtype == AGZO_BF16)
             HIPCHK(launch_pack_planes(Q, L->d_in, L->r, p.rp, wsh(ctx, p.off_pack), ctx->stream));
         TRY(sketch_power(ctx, *L, p, X, Q, S));

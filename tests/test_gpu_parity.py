@@ -158,6 +158,11 @@ def test_forward_sketch_basis_perturbed_update(ctx, storage, n, d_in, d_out, r, 
     ctx.layer_forward_sketch(L, None, Xd, None, binding.SKETCH_POWER, dev(Q1), seed, S, None, None)
     assert rel(host(S), oagzo.power_sketch(X64, Q1.astype(np.float64))) < tol
 
+    # power sketch without a Q: the Gaussian start matrix of the feature-space variant, from the seed
+    ctx.layer_forward_sketch(L, None, Xd, None, binding.SKETCH_POWER, None, seed, S, None, None)
+    Q0 = ophilox.normal(seed, ophilox.TAG_Q0, d_in, r).astype(np.float64)
+    assert rel(host(S), oagzo.power_sketch(X64, Q0)) < tol
+
     # basis, with and without a precomputed first sketch
     B = torch.empty(d_in, r, dtype=torch.float32, device="cuda")
     ctx.basis(L, Xd, 3, seed, None, 0, B)
