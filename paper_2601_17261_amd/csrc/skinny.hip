@@ -292,7 +292,12 @@ constexpr int XTT_STEP = 32;
 
 int xtt_num_splits(int64_t M, int64_t K) {
     const int64_t panels = (K + XTT_PANEL - 1) / XTT_PANEL;
-    int64_t want = (256 + panels - 1) / panels;   // about one workgroup per CU; few splits keep the partials small
+    // at least about one workgroup per CU; with many tokens up to eight token ranges even when the panels alone fill
+    // the chip (activations wider than the last-level cache come from HBM and need the bytes in flight: 814 -> 696 us
+    // per extraction at 16384 x 12288); more ranges than that cost more in partial sums than they hide
+    int64_t want = (256 + panels - 1) / panels;
+    const int64_t by_tokens = M / 1024 < 8 ? M / 1024 : 8;
+    if (want < by_tokens) want = by_tokens;
     const int64_t max_splits = (M + 4 * XTT_STEP - 1) / (4 * XTT_STEP);
     if (want > max_splits) want = max_splits;
     if (want < 1) want = 1;
@@ -321,36 +326,54 @@ __global__ __launch_bounds__(256) void xtt_bf16_kernel(const bf16_t* __restrict_
 
     const int64_t dcol = db + lc * 8;
     const bool din = dcol < K;
-    for (int64_t tb = ts + wave * XTT_STEP; tb < te; tb += 4 * XTT_STEP) {
-        uint4 v[8];
+    // one 32-token step: 8 KB of X and the T planes per wave.  The next step's loads are issued before this step's
+    // matrix work (twice the bytes in flight: with one step in flight the sweep ran at memory latency); they are
+    // unconditional, the step after the last one re-reads the last (clamped) and is dropped.
+    auto load_step = [&](int64_t tb, uint4 (&v)[8], Frag (&a)[NB][3]) {
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             const int64_t t = min(tb + lg * 8 + i, M - 1);   // rows past M meet zero planes
             v[i] = din ? *reinterpret_cast<const uint4*>(X + t * ldx + dcol) : make_uint4(0, 0, 0, 0);
         }
-        Frag a[NB][3];
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
             for (int pl = 0; pl < 3; ++pl)
                 a[nb][pl].u = *reinterpret_cast<const uint4*>(TpackT + ((int64_t)(pl * RP + nb * 16 + lc)) * m_pad + tb + lg * 8);
+    };
+    int64_t tb = ts + wave * XTT_STEP;
+    if (tb < te) {
+        uint4 v[8];
+        Frag a[NB][3];
+        load_step(tb, v, a);
+        for (; tb < te; tb += 4 * XTT_STEP) {
+            uint4 vn[8];
+            Frag an[NB][3];
+            load_step(min(tb + 4 * XTT_STEP, te - XTT_STEP), vn, an);
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            // word q of v[i] holds features 2q (low half) and 2q+1 (high half) of token i
-            const uint32_t sel = (j & 1) ? 0x07060302u : 0x05040100u;
-            const int q = j >> 1;
-            Frag b;
-            const uint32_t* w0 = reinterpret_cast<const uint32_t*>(&v[0]);
-            uint32_t o[4];
+            for (int j = 0; j < 8; ++j) {
+                // word q of v[i] holds features 2q (low half) and 2q+1 (high half) of token i
+                const uint32_t sel = (j & 1) ? 0x07060302u : 0x05040100u;
+                const int q = j >> 1;
+                Frag b;
+                const uint32_t* w0 = reinterpret_cast<const uint32_t*>(&v[0]);
+                uint32_t o[4];
 #pragma unroll
-            for (int pp = 0; pp < 4; ++pp)
-                o[pp] = __builtin_amdgcn_perm(w0[(2 * pp + 1) * 4 + q], w0[(2 * pp) * 4 + q], sel);
-            b.u = make_uint4(o[0], o[1], o[2], o[3]);
+                for (int pp = 0; pp < 4; ++pp)
+                    o[pp] = __builtin_amdgcn_perm(w0[(2 * pp + 1) * 4 + q], w0[(2 * pp) * 4 + q], sel);
+                b.u = make_uint4(o[0], o[1], o[2], o[3]);
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                    for (int pl = 0; pl < 3; ++pl)
+                        acc[nb][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[nb][pl].v, b.v, acc[nb][j], 0, 0, 0);
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) v[i] = vn[i];
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-                for (int pl = 0; pl < 3; ++pl)
-                    acc[nb][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[nb][pl].v, b.v, acc[nb][j], 0, 0, 0);
+                for (int pl = 0; pl < 3; ++pl) a[nb][pl] = an[nb][pl];
         }
     }
     // D layout: row (k within block) = 4*(lane/16) + e, col = lane%16 -> feature db + 8*lc + j
