@@ -510,6 +510,26 @@ def test_tile_aligned_shapes_take_the_specialised_loss_epilogues(ctx, target_dty
     assert rel(host(Wd), o["W_new"]) < 3e-3
 
 
+@pytest.mark.parametrize("storage", ["f32", "bf16"])
+def test_all_zero_activations_raise_the_numeric_flag_and_leave_the_context_usable(ctx, storage):
+    """X = 0: every sketch is zero, the first Cholesky pivot is 0, no basis exists.  The step reports AGZO_ENUMERIC at
+    the next check instead of NaNs passing silently, and the context goes on working."""
+    W, X, T, Wd, Xd, Td = problem(3, 300, 136, 264, "lowrank", storage)
+    Xz = torch.zeros_like(Xd)
+    out = torch.zeros(4, dtype=torch.float64, device="cuda")
+    ctx.step(binding.make_layer(Wd, Xz, 4), Wd.clone(), Xz, binding.make_loss(Td), 2, EPS, LR, 5, 0, out)
+    with pytest.raises(binding.AgzoError) as e:
+        ctx.check()
+    assert e.value.code == binding.ENUMERIC
+    ctx.check()                                            # cleared
+    W2 = Wd.clone()
+    ctx.step(binding.make_layer(W2, Xd, 4), W2, Xd, binding.make_loss(Td), 2, EPS, LR, 5, 0, out)
+    ctx.check()
+    o = oagzo.agzo_step(W, X, T, 4, 2, EPS, LR, 5, storage=storage)
+    assert abs(out[3].item() - o["g"]) < 2e-2 * abs(o["g"])
+    assert rel(host(W2), o["W_new"]) < (1e-6 if storage == "f32" else 3e-3)
+
+
 def test_step_is_deterministic(ctx):
     W, X, T, Wd, Xd, Td = problem(3, 600, 1024, 520, "rmsnorm", "bf16")
     L = binding.make_layer(Wd, Xd, 16)
