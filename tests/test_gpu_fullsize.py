@@ -164,6 +164,42 @@ def test_layer_set_updated_in_one_call_at_full_size(ctx):
     ctx.check()
 
 
+@pytest.mark.parametrize("d_out,d_in", [(16384 + 96, 8192), (32768 + 40, 16384)])
+def test_very_large_matrix_update_walks_several_row_groups_per_workgroup(ctx, d_out, d_in):
+    """Matrices large enough that a workgroup of the sweep takes two (first shape) or four (second) groups of 128 rows
+    in turn, with a ragged last group: sampled rows against the oracle, and the batched call against the single one."""
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(d_out)
+    W = (0.02 * torch.randn(d_out, d_in, device="cuda", generator=gen)).to(torch.bfloat16)
+    W0 = W.clone()
+    rng = np.random.default_rng(d_in)
+    Bh, _ = np.linalg.qr(rng.standard_normal((d_in, R)))
+    Bh = Bh.astype(np.float32)
+    B = torch.from_numpy(Bh).cuda()
+    g = torch.tensor([-1.3], dtype=torch.float64, device="cuda")
+    seed, lr = 31, 1e-2
+    L = binding.AgzoLayer()
+    L.n_tokens, L.d_in, L.d_out, L.r = 0, d_in, d_out, R
+    L.dtype = L.y_dtype = binding.BF16
+    L.tiling, L.ldw, L.ldx, L.ldy = 0, d_in, d_in, d_out
+    ctx.update(L, W, B, seed, lr, g)
+    ctx.check()
+    # the first and last rows, the rows around every 128-row group boundary of the first workgroups, and a random sample
+    rows = np.unique(np.concatenate([np.arange(0, 4), np.arange(d_out - 4, d_out), np.arange(124, 132), np.arange(508, 516),
+                                     np.arange(1020, 1028), rng.choice(d_out, size=48, replace=False)]))
+    idx = torch.from_numpy(rows).cuda()
+    G = oagzo.gaussian_factor(seed, d_out, R)[rows]
+    w0 = host(W0[idx])
+    want = oagzo.round_bf16(w0 - np.float64(np.float32(lr)) * (-1.3) * (G @ Bh.astype(np.float64).T))
+    assert rel(host(W[idx]), want) < 3e-3
+    assert rel(host(W[idx]) - w0, want - w0) < 5e-3
+    changed = (W != W0).float().mean().item()
+    assert changed > 0.5                                   # every part of the matrix was swept
+    ctx.update_many([(W0, B, seed, lr, g)])                # the untouched copy through the batched call
+    ctx.check()
+    assert torch.equal(W0, W)
+
+
 def test_bench_line_has_the_contract_fields():
     """bench.py in its default shape (fewer steps, no CPU baseline): one JSON line with the fields the harness reads,
     a roofline whose fraction is achieved / peak, and a finite positive throughput."""
