@@ -262,6 +262,24 @@ def _layer_for(W, r):
     return L
 
 
+@pytest.mark.parametrize("r", [2, 3, 6, 8, 12, 16, 24, 33, 64])
+def test_f32_update_at_every_rank_chunking(ctx, r):
+    """fp32 storage keeps the vector-ALU sweep, compiled per chunk of the rank (1, 2, 4, 8, 16 and multiples of 16)."""
+    rng = np.random.default_rng(r)
+    d_out, d_in = 70 + r, 131
+    W = (0.02 * rng.standard_normal((d_out, d_in))).astype(np.float32)
+    B, _ = np.linalg.qr(rng.standard_normal((d_in, r)))
+    B32 = B.astype(np.float32)
+    Wd = dev(W)
+    g = torch.tensor([0.77], dtype=torch.float64, device="cuda")
+    ctx.update(_layer_for(Wd, r), Wd, dev(B32), 900 + r, LR, g)
+    ctx.check()
+    Z, _ = oagzo.perturbation(B32.astype(np.float64), 900 + r, d_out)
+    want = oagzo.round_storage(W.astype(np.float64) - LR * 0.77 * Z, "f32")
+    assert rel(host(Wd), want) < 1e-6
+    assert rel(host(Wd) - W, want - W) < 1e-4
+
+
 def test_update_many_rejects_bad_lists_and_accepts_an_empty_one(ctx):
     W = torch.zeros(16, 32, dtype=torch.bfloat16, device="cuda")
     B = torch.ones(32, 4, dtype=torch.float32, device="cuda")
