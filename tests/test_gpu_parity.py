@@ -207,6 +207,32 @@ def test_forward_sketch_basis_perturbed_update(ctx, storage, n, d_in, d_out, r, 
     ctx.check()
 
 
+@pytest.mark.parametrize("tiling", TILINGS)
+@pytest.mark.parametrize("n,d_in,d_out,r", [(515, 136, 300, 8), (512, 320, 768, 16)])
+def test_outputs_stored_as_bf16(ctx, n, d_in, d_out, r, tiling):
+    """Y kept in bf16 (the storage type of the bf16 configurations): the fp32 accumulators rounded once to nearest even,
+    ragged and tile-aligned shapes, both tilings, base and perturbed forward."""
+    seed = 77
+    W, X, T, Wd, Xd, Td = problem(n + d_out, n, d_in, d_out, "powerlaw", "bf16")
+    W64, X64 = W.astype(np.float64), X.astype(np.float64)
+    Y = torch.empty(n, d_out, dtype=torch.bfloat16, device="cuda")
+    L = binding.make_layer(Wd, Xd, r, Y=Y)
+    L.tiling = tiling
+    ctx.layer_forward_sketch(L, Wd, Xd, Y, binding.SKETCH_NONE, None, seed, None, None, None)
+    B = oagzo.subspace_extract(X64, r, 2, seed)["B"].astype(np.float32)
+    Z, _ = oagzo.perturbation(B.astype(np.float64), seed, d_out)
+    for eps_signed, Wp in ((0.0, W64), (+EPS, W64 + EPS * Z)):
+        if eps_signed != 0.0:
+            ctx.perturbed_forward(L, Wd, Xd, dev(B), seed, eps_signed, Y, None, None)
+        want = oagzo.round_bf16(oagzo.forward(X64, Wp))
+        got = host(Y)
+        assert rel(got, want) < 1e-3
+        assert (got != want).mean() < 5e-3                    # accumulators a rounding boundary apart in fp32 and fp64
+        # one rounding step apart at most; for outputs near zero the step is smaller than the fp32 accumulation error
+        assert (np.abs(got - want) <= np.abs(want) * 2.0 ** -7 + 2e-5 * np.abs(want).max()).all()
+    ctx.check()
+
+
 # ---------------------------------------------------------------------------------------------
 # several matrices updated in one call
 # ---------------------------------------------------------------------------------------------
