@@ -233,6 +233,49 @@ def test_outputs_stored_as_bf16(ctx, n, d_in, d_out, r, tiling):
     ctx.check()
 
 
+@pytest.mark.parametrize("tiling", TILINGS)
+@pytest.mark.parametrize("n,d_in,d_out,r,tdt", [(515, 136, 300, 8, "f32"), (512, 320, 768, 16, "f32"), (512, 320, 768, 16, "bf16")])
+def test_operands_inside_wider_allocations(ctx, n, d_in, d_out, r, tdt, tiling):
+    """W, X, Y and the target as column ranges of wider buffers (leading dimensions larger than the widths): a whole
+    step, the stored outputs, and nothing written outside the ranges."""
+    seed = 19
+    W, X, T, _, _, _ = problem(n + 1, n, d_in, d_out, "powerlaw", "bf16")
+    if tdt == "bf16":
+        T = synth.to_bf16_values(T)
+
+    def inside(a, storage, pad):
+        big = torch.full((a.shape[0], a.shape[1] + pad), 7.0, dtype=torch.bfloat16 if storage == "bf16" else torch.float32,
+                         device="cuda")
+        big[:, :a.shape[1]] = dev(a, storage)
+        return big, big[:, :a.shape[1]]
+
+    Wb, Wd = inside(W, "bf16", 8)
+    Xb, Xd = inside(X, "bf16", 16)
+    Tb, Td = inside(T, tdt, 8)
+    Yb, Y = inside(np.zeros((n, d_out), dtype=np.float32), "f32", 4)
+    L = binding.make_layer(Wd, Xd, r, Y=Y)
+    L.tiling = tiling
+    assert L.ldw == d_in + 8 and L.ldx == d_in + 16 and L.ldy == d_out + 4
+    sc = torch.zeros(1, dtype=torch.float64, device="cuda")
+    ctx.layer_forward_sketch(L, Wd, Xd, Y, binding.SKETCH_NONE, None, seed, None, binding.make_loss(Td), sc)
+    Y0 = oagzo.forward(X.astype(np.float64), W.astype(np.float64))
+    assert rel(host(Y), Y0) < 2e-5
+    assert abs(sc.item() - oagzo.mse_loss(Y0, T)) < 1e-5 * oagzo.mse_loss(Y0, T)
+    assert (Yb[:, d_out:] == 7.0).all()
+    out = torch.zeros(4, dtype=torch.float64, device="cuda")
+    Ls = binding.make_layer(Wd, Xd, r)
+    Ls.tiling = tiling
+    ctx.step(Ls, Wd, Xd, binding.make_loss(Td), 2, EPS, LR, seed, 0, out)
+    ctx.check()
+    o = oagzo.agzo_step(W, X, T, r, 2, EPS, LR, seed, storage="bf16")
+    got = out.cpu().numpy()
+    for k, key in enumerate(("L0", "Lp", "Lm")):
+        assert abs(got[k] - o[key]) < 1e-5 * o[key]
+    assert abs(got[3] - o["g"]) < 2e-2 * abs(o["g"])
+    assert rel(host(Wd), o["W_new"]) < 3e-3
+    assert (Wb[:, d_in:] == 7.0).all() and (Xb[:, d_in:] == 7.0).all() and (Tb[:, d_out:] == 7.0).all()
+
+
 # ---------------------------------------------------------------------------------------------
 # several matrices updated in one call
 # ---------------------------------------------------------------------------------------------
