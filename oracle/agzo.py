@@ -209,19 +209,25 @@ def apply_rank_r(W, B, seed, coef, storage):
     return round_storage(W + coef * Z, storage)
 
 
-def agzo_step_inplace(W, X, target, B, eps, lr, seed, loss="mse", storage="f32"):
+def agzo_step_inplace(W, X, target, B, eps, lr, seed, loss="mse", storage="f32", one_sided=False):
     """The paper's literal in-place schedule (Alg. 2: perturb in place, evaluate,
     restore and update), extended to the central difference: every sweep stores
     W in the storage type, so in bf16 this is a *different* computation from
-    agzo_step (the perturbation is partly rounded away) and has its own parity."""
+    agzo_step (the perturbation is partly rounded away) and has its own parity.
+    one_sided: exactly Alg. 2 as printed (one perturbed evaluation, g = (L+ - L0) / eps)."""
     W0 = np.asarray(W, dtype=np.float64)
     L0 = loss_value(forward(X, W0), loss, target)
     Wp = apply_rank_r(W0, B, seed, +eps, storage)
     Lp = loss_value(forward(X, Wp), loss, target)
-    Wm = apply_rank_r(Wp, B, seed, -2.0 * eps, storage)
-    Lm = loss_value(forward(X, Wm), loss, target)
-    g = (Lp - Lm) / (2.0 * eps)
-    Wr = apply_rank_r(Wm, B, seed, +eps, storage)          # restore
+    if one_sided:
+        Wm, Lm = None, 0.0
+        g = (Lp - L0) / eps
+        Wr = apply_rank_r(Wp, B, seed, -eps, storage)      # restore
+    else:
+        Wm = apply_rank_r(Wp, B, seed, -2.0 * eps, storage)
+        Lm = loss_value(forward(X, Wm), loss, target)
+        g = (Lp - Lm) / (2.0 * eps)
+        Wr = apply_rank_r(Wm, B, seed, +eps, storage)      # restore
     W_new = apply_rank_r(Wr, B, seed, -lr * g, storage)    # update
     return {"L0": L0, "Lp": Lp, "Lm": Lm, "g": g, "W_new": W_new, "Wp": Wp, "Wm": Wm}
 

@@ -260,6 +260,12 @@ def test_bf16_storage_and_inplace_schedule():
     c = agzo.agzo_step_inplace(W64, X64, T, out["B"], 1e-3, 1e-2, 5, storage="bf16")
     np.testing.assert_array_equal(c["Wp"], agzo.round_bf16(W64 + 1e-3 * out["Z"]))
     assert c["L0"] == out["L0"]
+    # the printed, one-sided form of the same schedule agrees with the factored one-sided step in fp32 storage
+    a1 = agzo.agzo_step(W32, X32, T32, r=4, K=3, eps=1e-3, lr=1e-2, seed=5, storage="f32", one_sided=True)
+    b1 = agzo.agzo_step_inplace(W32, X32, T32, a1["B"], 1e-3, 1e-2, 5, storage="f32", one_sided=True)
+    assert abs(a1["g"] - b1["g"]) < 2e-3 * abs(a1["g"]) and b1["Lm"] == 0.0 and b1["Lp"] == b["Lp"]
+    assert np.linalg.norm(a1["W_new"] - b1["W_new"]) < 1e-6 * np.linalg.norm(a1["W_new"])
+    assert abs(a1["g"] - a["g"]) > 1e-6 * abs(a["g"])          # and is not the central estimate
 
 
 # --- Eq. 7, second branch: dense Gaussian perturbation of other parameters ---------------------
