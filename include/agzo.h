@@ -158,6 +158,19 @@ int agzo_two_point(agzo_ctx* ctx, double* out4_dev, float eps, int32_t flags);
 int agzo_update(agzo_ctx* ctx, const agzo_layer* L, void* W, const float* B, uint64_t seed,
                 float lr, const double* g_dev);
 
+/* agzo_update for callers that cannot allocate device memory: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, same kernels and bit-identical results; the scratch that a bf16
+ * update needs (both factors as bf16 hi/lo matrix-core fragments: 4 r16 (d_out rounded up to 32 + d_in rounded up to
+ * 256) bytes, r16 = r rounded up to 16; 1 MiB for a 12288 x 4096 matrix at r = 16) lives in a static device array of 8 MiB that each GPU the library runs on holds until
+ * the process ends, instead of the context's growable workspace.  The call allocates and frees nothing.  fp32
+ * matrices need no scratch.  Every call on a GPU shares that GPU's array (also across contexts): calls that may
+ * overlap on one GPU (different streams) race and must be ordered by the caller; nothing in the array has to start
+ * at zero, every call rewrites all of what it reads.  The device current at the call must be the one the context was
+ * created on.  Errors: as agzo_update; AGZO_EINVAL when the fragments exceed the 8 MiB or the device differs
+ * (nothing is enqueued then). */
+int agzo_update_noalloc(agzo_ctx* ctx, const agzo_layer* L, void* W, const float* B, uint64_t seed,
+                        float lr, const double* g_dev);
+
 /* The same sweep for n matrices at once (Alg. 2: every layer is updated after the one scalar g is known, so the
  * updates of a model arrive together).  items: host array, read during the call only; per item the arguments of
  * agzo_update: W device [d_out][ldw] of `dtype`, B device fp32 [d_in][r], g_dev device scalar or NULL (= 1), seed of

@@ -26,7 +26,7 @@ PROF_ALL = 63
 
 EXPORTS = ["agzo_create", "agzo_destroy", "agzo_last_error", "agzo_check", "agzo_profile_enable",
            "agzo_profile_read", "agzo_profile_clock", "agzo_probe_mfma", "agzo_philox_words", "agzo_fill_normal",
-           "agzo_layer_forward_sketch", "agzo_qr", "agzo_basis", "agzo_perturbed_forward", "agzo_two_point", "agzo_dense_perturb", "agzo_update",
+           "agzo_layer_forward_sketch", "agzo_qr", "agzo_basis", "agzo_perturbed_forward", "agzo_two_point", "agzo_dense_perturb", "agzo_update", "agzo_update_noalloc",
            "agzo_update_many", "agzo_step", "agzo_step_no_update"]
 
 
@@ -89,6 +89,7 @@ def load():
     lib.agzo_two_point.argtypes = [vp, vp, f32, i32]
     lib.agzo_dense_perturb.argtypes = [vp, vp, i32, i64, i64, i64, u64, f32, vp]
     lib.agzo_update.argtypes = [vp, lp, vp, vp, u64, f32, vp]
+    lib.agzo_update_noalloc.argtypes = [vp, lp, vp, vp, u64, f32, vp]
     lib.agzo_update_many.argtypes = [vp, ctypes.POINTER(AgzoUpdateItem), i32]
     lib.agzo_step.argtypes = [vp, lp, vp, vp, sp, i32, f32, f32, u64, i32, vp]
     lib.agzo_step_no_update.argtypes = [vp, lp, vp, vp, sp, i32, f32, u64, i32, vp, vp]
@@ -240,6 +241,9 @@ class Context:
 
     def update(self, L, W, B, seed, lr, g_dev):
         self._rc(self.lib.agzo_update(self.h, ctypes.byref(L), _ptr(W), _ptr(B), seed, lr, _ptr(g_dev)))
+
+    def update_noalloc(self, L, W, B, seed, lr, g_dev):
+        self._rc(self.lib.agzo_update_noalloc(self.h, ctypes.byref(L), _ptr(W), _ptr(B), seed, lr, _ptr(g_dev)))
 
     def update_many(self, items):
         """items: sequence of (W, B, seed, lr, g_dev) with W a 2-D device tensor (unit stride along d_in), B [d_in][r]."""

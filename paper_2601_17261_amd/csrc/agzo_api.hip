@@ -4,6 +4,7 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -16,8 +17,15 @@ struct ProfClass {
     size_t used = 0;
 };
 
+// Scratch of agzo_update_noalloc: the factor fragments of one bf16 update, for callers that cannot allocate.
+// One copy per GPU, held until the process ends; its device address is resolved once per device (resolve_scratch).
+constexpr size_t kStaticScratchBytes = (size_t)8 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 struct agzo_ctx {
     hipStream_t stream;
+    int device;            // the device that was current at agzo_create
+    char* static_scratch;  // device address of `scratch` on that device
     char err[512];
     char* ws;
     size_t ws_bytes;
@@ -76,6 +84,26 @@ struct ProfScope {
         if (stop) (void)hipEventRecord(stop, c->stream);
     }
 };
+
+// Device address of the static scratch array on the current device.  The array's name is only a host-side handle
+// for the symbol: every use of its memory goes through the address looked up here, once per device.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+char* g_scratch_ptr[kMaxDevices] = {};
+
+hipError_t resolve_scratch(int device, char** out) {
+    if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[device]) {
+        void* ptr = nullptr;
+        hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!ptr) return hipErrorInvalidSymbol;
+        g_scratch_ptr[device] = static_cast<char*>(ptr);
+    }
+    *out = g_scratch_ptr[device];
+    return hipSuccess;
+}
 
 inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 inline int round16(int r) { return (r + 15) / 16 * 16; }
@@ -396,7 +424,11 @@ int agzo_create(agzo_ctx** out, void* hip_stream) {
     ctx->prof = 0;
     ctx->clk = nullptr;
     ctx->clk_used = 0;
-    hipError_t e = hipMalloc(reinterpret_cast<void**>(&ctx->flag), 256);
+    ctx->device = -1;
+    ctx->static_scratch = nullptr;
+    hipError_t e = hipGetDevice(&ctx->device);
+    if (e == hipSuccess) e = resolve_scratch(ctx->device, &ctx->static_scratch);
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&ctx->flag), 256);
     if (e == hipSuccess) e = hipMemset(ctx->flag, 0, 256);
     if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&ctx->clk), kClkBytes);
     if (e == hipSuccess) e = hipMemset(ctx->clk, 0, kClkBytes);
@@ -605,6 +637,25 @@ int agzo_update(agzo_ctx* ctx, const agzo_layer* L, void* W, const float* B, uin
     TRY(check_update(ctx, W, B, L->dtype, L->d_out, L->d_in, L->ldw, L->r));
     TRY(reserve(ctx, update_workspace_bytes(L->dtype, L->d_out, L->d_in, L->r)));
     TRY(op_update(ctx, *L, 0, W, B, seed, lr, g_dev));
+    return AGZO_OK;
+}
+
+int agzo_update_noalloc(agzo_ctx* ctx, const agzo_layer* L, void* W, const float* B, uint64_t seed, float lr,
+                        const double* g_dev) {
+    if (!ctx) return AGZO_EINVAL;
+    if (!L) return fail(ctx, AGZO_EINVAL, "layer descriptor is NULL");
+    if (L->tiling != AGZO_TILING_AUTO && L->tiling != AGZO_TILING_LARGE) return fail(ctx, AGZO_EINVAL, "tiling %d", L->tiling);
+    TRY(check_update(ctx, W, B, L->dtype, L->d_out, L->d_in, L->ldw, L->r));
+    const size_t need = update_workspace_bytes(L->dtype, L->d_out, L->d_in, L->r);
+    if (need > kStaticScratchBytes)
+        return fail(ctx, AGZO_EINVAL, "factor fragments of this update take %zu bytes, the static scratch holds %zu",
+                    need, kStaticScratchBytes);
+    int dev = -1;
+    HIPCHK(hipGetDevice(&dev));
+    if (dev != ctx->device || !ctx->static_scratch)
+        return fail(ctx, AGZO_EINVAL, "current device %d is not the context's device %d", dev, ctx->device);
+    // the preparation launch rewrites every fragment the sweep reads, so nothing left by an earlier call is seen
+    HIPCHK(launch_update(W, L->dtype, L->ldw, L->d_out, L->d_in, B, L->r, seed, lr, g_dev, ctx->static_scratch, ctx->stream));
     return AGZO_OK;
 }
 
