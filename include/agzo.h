@@ -18,7 +18,8 @@
  *     sketches S and the start/iterate Q are [d_in][r] fp32 with leading
  *     dimension r, the projection P is [n_tokens][r] fp32.
  *   - Leading dimensions (ldw, ldx, ldy, ldt) are in elements; for bf16
- *     operands ldw, ldx and d_in must be multiples of 8 (16-byte rows).
+ *     operands ldw, ldx and d_in must be multiples of 8 and below 2^22, and
+ *     W and X must be 16-byte aligned (16-byte rows).
  *   - Calls only enqueue work on the ctx stream (no host synchronisation)
  *     unless stated.  Calls on one ctx must not overlap from several threads.
  *   - Return value: 0 on success, a negative agzo_status otherwise; the text
@@ -60,7 +61,9 @@ enum { AGZO_TILING_AUTO = 0, AGZO_TILING_LARGE = 1 };
 /* agzo_step / agzo_basis flags */
 enum {
     AGZO_ONE_SIDED = 1,    /* g = (L+ - L0)/eps, the literal form of Eq. 10 / Alg. 2; default is (L+ - L-)/(2 eps) */
-    AGZO_NAIVE_INPLACE = 2,/* comparator: perturb W in place, plain forward, undo (Alg. 2's literal schedule) */
+    AGZO_NAIVE_INPLACE = 2,/* comparator: perturb W in place, plain forward, undo (Alg. 2's literal schedule); together
+                              with AGZO_ONE_SIDED, agzo_step runs Alg. 2 exactly as printed, its last line as one sweep
+                              W <- W - (eps + lr g) G B^T over the still-perturbed weights */
     AGZO_INIT_FEATURE = 4, /* start Alg. 1 from a Gaussian Q0 [d_in][r] (tag 2) instead of a token-space Omega */
     AGZO_SHARED_FORWARD = 8/* single layer only: f0, f+ and f- are evaluated from one pass over X and W
                               (Y+- = X W^T +- eps (X B) G^T share the product X W^T); extraction runs first */
@@ -82,7 +85,8 @@ typedef struct {
     int32_t kind;         /* agzo_loss_kind */
     int32_t target_dtype; /* MSE: AGZO_F32 or AGZO_BF16 target values; ignored for CE */
     const void* target;   /* MSE: Y* [n_tokens][d_out], ld = ldt.  CE: int32 ids [n_tokens] in [0, d_out), < 0 = ignored row
-                             (loss = mean over the other rows of -log softmax(Y[row])[id], natural log) */
+                             (loss = mean over the other rows of -log softmax(Y[row])[id], natural log); an id >= d_out
+                             is a caller error that the kernels survive: such a row is skipped like an ignored one */
     int64_t ldt;
 } agzo_loss_spec;
 

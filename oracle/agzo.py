@@ -214,7 +214,10 @@ def agzo_step_inplace(W, X, target, B, eps, lr, seed, loss="mse", storage="f32",
     restore and update), extended to the central difference: every sweep stores
     W in the storage type, so in bf16 this is a *different* computation from
     agzo_step (the perturbation is partly rounded away) and has its own parity.
-    one_sided: exactly Alg. 2 as printed (one perturbed evaluation, g = (L+ - L0) / eps)."""
+    one_sided: exactly Alg. 2 as printed: one perturbed evaluation, g = (L+ - L0) / eps, and the
+    last line as ONE sweep over the still-perturbed weights, W <- W - eps Z - lr g Z (one rounding
+    to storage).  The central form has no printed last line; it restores (+eps from the minus
+    side) and updates in two rounded sweeps."""
     W0 = np.asarray(W, dtype=np.float64)
     L0 = loss_value(forward(X, W0), loss, target)
     Wp = apply_rank_r(W0, B, seed, +eps, storage)
@@ -222,13 +225,13 @@ def agzo_step_inplace(W, X, target, B, eps, lr, seed, loss="mse", storage="f32",
     if one_sided:
         Wm, Lm = None, 0.0
         g = (Lp - L0) / eps
-        Wr = apply_rank_r(Wp, B, seed, -eps, storage)      # restore
+        W_new = apply_rank_r(Wp, B, seed, -(eps + lr * g), storage)   # restore and update, one sweep
     else:
         Wm = apply_rank_r(Wp, B, seed, -2.0 * eps, storage)
         Lm = loss_value(forward(X, Wm), loss, target)
         g = (Lp - Lm) / (2.0 * eps)
         Wr = apply_rank_r(Wm, B, seed, +eps, storage)      # restore
-    W_new = apply_rank_r(Wr, B, seed, -lr * g, storage)    # update
+        W_new = apply_rank_r(Wr, B, seed, -lr * g, storage)    # update
     return {"L0": L0, "Lp": Lp, "Lm": Lm, "g": g, "W_new": W_new, "Wp": Wp, "Wm": Wm}
 
 

@@ -115,6 +115,7 @@ struct Plan {
     int rp, nsplit;
     int64_t m_pad;
     int n_part;
+    size_t part_count;   // doubles in the loss-partials region
 };
 
 Plan make_plan(const agzo_layer& L, bool need_ybuf, bool ce = false, bool shared = false) {
@@ -139,6 +140,7 @@ Plan make_plan(const agzo_layer& L, bool need_ybuf, bool ce = false, bool shared
         size_t part = (size_t)n_gemm * 3;                                          // MSE: one double per tile and phase
         const size_t ce_part = (size_t)2 * L.n_tokens + 6 * ((L.n_tokens + 255) / 256);   // CE: (sum, count) pairs
         if (ce && ce_part > part) part = ce_part;
+        p.part_count = part;
         p.off_part = take(part * 8);
     }
     p.off_ce_ms = take((ce && bf) ? (size_t)3 * gemm_bf16_ce_chunks(L.d_out) * L.n_tokens * 8 : 0);
@@ -182,6 +184,17 @@ int check_layer(agzo_ctx* ctx, const agzo_layer* L, bool need_w) {
         if (L->d_in % 8 || L->ldx % 8 || (need_w && L->ldw % 8))
             return fail(ctx, AGZO_EINVAL, "bf16 layers need d_in, ldx, ldw multiples of 8");
     }
+    return 0;
+}
+
+// bf16 operands travel as 16-byte vectors (direct global -> LDS loads included) and the kernels build 32-bit byte
+// offsets of up to 512 rows from a tile's corner
+int check_operands(agzo_ctx* ctx, const agzo_layer* L, const void* W, const void* X) {
+    if (L->dtype != AGZO_BF16) return 0;
+    if ((reinterpret_cast<uintptr_t>(X) & 15) || (reinterpret_cast<uintptr_t>(W) & 15))
+        return fail(ctx, AGZO_EINVAL, "bf16 X and W must be 16-byte aligned");
+    if (L->ldx >= (1LL << 22) || (W && L->ldw >= (1LL << 22)))
+        return fail(ctx, AGZO_EINVAL, "bf16 layers need ldx and ldw below 2^22 elements");
     return 0;
 }
 
@@ -302,9 +315,20 @@ int op_forward(agzo_ctx* ctx, const agzo_layer& L, const Plan& p, const void* W,
     la.target_dtype = has_loss ? loss->target_dtype : AGZO_F32;
     la.target = has_loss ? loss->target : nullptr;
     la.ldt = has_loss ? loss->ldt : 0;
-    // a step keeps the tile partials of its forwards side by side (slot = 0, 1, 2) and finishes them in one launch
-    la.partials = reinterpret_cast<double*>(ctx->ws + p.off_part) + (size_t)part_slot * p.n_part;
     const bool ce = has_loss && loss->kind == AGZO_LOSS_CE;
+    // squared error: a step keeps the tile partials of its forwards side by side (slot = 0, 1, 2) and finishes them in
+    // one launch.  Cross-entropy: every loss is finished by launches of its own right behind the forward, so all of
+    // them use the region from its start: (sum, count) per token (fp32 storage) or per 256 tokens and phase (bf16).
+    {
+        const size_t at = ce ? 0 : (size_t)part_slot * p.n_part;
+        const size_t nblk = (size_t)((L.n_tokens + 255) / 256);
+        const size_t need = !has_loss ? 0 : ce ? (L.dtype == AGZO_BF16 ? 2 * nblk * (shared ? 3 : 1) : 2 * (size_t)L.n_tokens)
+                                               : (size_t)p.n_part * (shared ? 3 : 1);
+        if (at + need > p.part_count)
+            return fail(ctx, AGZO_EHIP, "internal: loss scratch of %zu doubles at %zu exceeds its region of %zu", need, at,
+                        p.part_count);
+        la.partials = reinterpret_cast<double*>(ctx->ws + p.off_part) + at;
+    }
     const int32_t* ids = ce ? static_cast<const int32_t*>(loss->target) : nullptr;
     if (ce && L.dtype == AGZO_BF16) {
         la.ce_ms = ctx->ws + p.off_ce_ms;
@@ -327,7 +351,7 @@ int op_forward(agzo_ctx* ctx, const agzo_layer& L, const Plan& p, const void* W,
             HIPCHK(launch_gemm_bf16(a, st));
         }
         if (ce)
-            HIPCHK(launch_ce_combine(la.ce_ms, la.ce_tl, ids, L.n_tokens, gemm_bf16_ce_chunks(L.d_out), shared ? 3 : 1,
+            HIPCHK(launch_ce_combine(la.ce_ms, la.ce_tl, ids, L.n_tokens, L.d_out, gemm_bf16_ce_chunks(L.d_out), shared ? 3 : 1,
                                      la.partials, loss_dev, st));
     } else {
         float* Yf = Y ? static_cast<float*>(Y) : wsf(ctx, p.off_Ybuf);
@@ -368,9 +392,9 @@ int check_update(agzo_ctx* ctx, const void* W, const float* B, int dtype, int64_
 }
 
 int op_update(agzo_ctx* ctx, const agzo_layer& L, size_t off_upd, void* W, const float* B, uint64_t seed, float lr,
-              const double* g_dev) {
+              const double* g_dev, float shift = 0.f) {
     ProfScope ps(ctx, AGZO_PROF_UPDATE);
-    HIPCHK(launch_update(W, L.dtype, L.ldw, L.d_out, L.d_in, B, L.r, seed, lr, g_dev, ctx->ws + off_upd, ctx->stream));
+    HIPCHK(launch_update(W, L.dtype, L.ldw, L.d_out, L.d_in, B, L.r, seed, lr, g_dev, ctx->ws + off_upd, ctx->stream, shift));
     return 0;
 }
 
@@ -569,6 +593,7 @@ int agzo_layer_forward_sketch(agzo_ctx* ctx, const agzo_layer* L, const void* W,
     const bool gemm = (W != nullptr);
     TRY(check_layer(ctx, L, gemm));
     if (!X) return fail(ctx, AGZO_EINVAL, "X is NULL");
+    TRY(check_operands(ctx, L, W, X));
     if (!gemm && (Y || (loss && loss->kind != AGZO_LOSS_NONE))) return fail(ctx, AGZO_EINVAL, "Y or loss without W");
     if (mode != AGZO_SKETCH_NONE && mode != AGZO_SKETCH_RANGE && mode != AGZO_SKETCH_POWER)
         return fail(ctx, AGZO_EINVAL, "sketch mode %d", mode);
@@ -610,6 +635,7 @@ int agzo_basis(agzo_ctx* ctx, const agzo_layer* L, const void* X, int32_t K, uin
                int32_t flags, float* B) {
     TRY(check_layer(ctx, L, false));
     if (!X || !B) return fail(ctx, AGZO_EINVAL, "X or B is NULL");
+    TRY(check_operands(ctx, L, nullptr, X));
     if (K < 0 || K > 64) return fail(ctx, AGZO_EINVAL, "K=%d outside 0..64", K);
     const Plan p = make_plan(*L, false);
     TRY(reserve(ctx, p.total));
@@ -620,6 +646,7 @@ int agzo_perturbed_forward(agzo_ctx* ctx, const agzo_layer* L, const void* W, co
                            uint64_t seed, float eps_signed, void* Y, const agzo_loss_spec* loss, double* loss_dev) {
     TRY(check_layer(ctx, L, true));
     if (!W || !X || !B) return fail(ctx, AGZO_EINVAL, "W, X or B is NULL");
+    TRY(check_operands(ctx, L, W, X));
     TRY(check_y(ctx, L, Y));
     TRY(check_loss(ctx, L, loss, loss_dev));
     const Plan p = make_plan(*L, L->dtype == AGZO_F32 && !Y, loss && loss->kind == AGZO_LOSS_CE);
@@ -732,7 +759,7 @@ static int step_impl(agzo_ctx* ctx, const agzo_layer* L, void* W, const void* X,
     TRY(check_loss(ctx, L, loss, out_dev));
     if (K < 0 || K > 64) return fail(ctx, AGZO_EINVAL, "K=%d outside 0..64", K);
     if (!(eps > 0.f)) return fail(ctx, AGZO_EINVAL, "eps must be positive");
-    if (L->dtype == AGZO_BF16 && (reinterpret_cast<uintptr_t>(W) & 15)) return fail(ctx, AGZO_EINVAL, "W misaligned");
+    TRY(check_operands(ctx, L, W, X));
     const Plan p = make_plan(*L, L->dtype == AGZO_F32, loss->kind == AGZO_LOSS_CE,
                              (flags & AGZO_SHARED_FORWARD) && !(flags & AGZO_NAIVE_INPLACE));
     TRY(reserve(ctx, p.total));
@@ -774,8 +801,14 @@ static int step_impl(agzo_ctx* ctx, const agzo_layer* L, void* W, const void* X,
             TRY(op_update(ctx, *L, p.off_upd, W, B, seed, 2.f * eps, nullptr));
             TRY(op_forward(ctx, *L, p, W, X, nullptr, 0.f, seed, nullptr, loss, out_dev + 2, false, 2, mse));
             TRY(op_update(ctx, *L, p.off_upd, W, B, seed, -eps, nullptr));
-        } else {
+        } else if (B_out) {
             TRY(op_update(ctx, *L, p.off_upd, W, B, seed, eps, nullptr));
+        } else {
+            // Alg. 2 as printed: W still holds W + eps Z here, and the last line takes the perturbation out and applies
+            // the update in one sweep, W <- W - (eps + lr g) Z
+            TRY(finish(2));
+            TRY(op_update(ctx, *L, p.off_upd, W, B, seed, lr, out_dev + 3, eps));
+            return AGZO_OK;
         }
     } else {
         float* P = wsf(ctx, p.off_T);

@@ -162,11 +162,12 @@ size_t qr_workspace_bytes(int64_t d, int r);
 hipError_t launch_qr(const float* S, const float* splits, int nsplit, int rp, float* S_out, int64_t d, int r, float* Q,
                      bf16_t* planes, void* workspace, int* numeric_flag, bool refine, hipStream_t st);
 
-// update.hip : W -= lr * g * G B^T in place
+// update.hip : W -= (lr * g + shift) * G B^T in place, g = *g_dev (1 if NULL)
 // workspace: update_workspace_bytes() bytes of device scratch (may be NULL when that is 0)
 size_t update_workspace_bytes(int dtype, int64_t d_out, int64_t d_in, int r);
 hipError_t launch_update(void* W, int dtype, int64_t ldw, int64_t d_out, int64_t d_in, const float* B, int r,
-                         uint64_t seed, float lr, const double* g_dev, void* workspace, hipStream_t st);
+                         uint64_t seed, float lr, const double* g_dev, void* workspace, hipStream_t st,
+                         float shift = 0.f);
 // the same for n bf16 matrices that share nk = ceil(r / 16), n <= update_many_max(), in two launches; the workspace
 // holds the sum of their update_workspace_bytes()
 struct UpdateDesc {
@@ -185,8 +186,8 @@ hipError_t launch_update_many(const UpdateDesc* d, int n, int nk, void* workspac
 // cross-entropy from the GEMM's per-chunk softmax statistics: out[ph] = mean over rows with target >= 0 of
 // log(sum exp) - logit[target];  ms: float2 [nphase][nchunk][M], tl: float [nphase][M]
 int gemm_bf16_ce_chunks(int64_t N);
-hipError_t launch_ce_combine(const void* ms, const float* tl, const int32_t* target, int64_t M, int nchunk, int nphase,
-                             double* scratch, double* out, hipStream_t st);
+hipError_t launch_ce_combine(const void* ms, const float* tl, const int32_t* target, int64_t M, int64_t N, int nchunk,
+                             int nphase, double* scratch, double* out, hipStream_t st);
 // cross-entropy of stored fp32 logits Y [M][N] (fp32-storage path): out[0] as above
 hipError_t launch_ce_rows_f32(const float* Y, int64_t ldy, int64_t M, int64_t N, const int32_t* target, double* scratch,
                               double* out, hipStream_t st);

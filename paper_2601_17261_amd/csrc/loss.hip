@@ -79,14 +79,14 @@ __global__ __launch_bounds__(256) void finish_two_point_kernel(const double* __r
 // one thread per token: merge the chunk statistics, loss_t = log(sum exp) - logit[target]; block sums
 // of (loss, count) go to scratch[2*block], the last stage divides.
 __global__ __launch_bounds__(256) void ce_combine_kernel(const float2* __restrict__ ms, const float* __restrict__ tl,
-                                                         const int32_t* __restrict__ target, int64_t M, int nchunk,
-                                                         double* __restrict__ scratch) {
+                                                         const int32_t* __restrict__ target, int64_t M, int64_t N,
+                                                         int nchunk, double* __restrict__ scratch) {
     __shared__ double rs[256], rc[256];
     const int tid = threadIdx.x;
     const int ph = blockIdx.y;
     const int64_t t = (int64_t)blockIdx.x * 256 + tid;
     double loss = 0.0, cnt = 0.0;
-    if (t < M && target[t] >= 0) {
+    if (t < M && target[t] >= 0 && target[t] < N) {   // an id outside the layer's outputs has no logit: skipped
         const float2* m = ms + (int64_t)ph * nchunk * M + t;
         float mx = -INFINITY;
         for (int c = 0; c < nchunk; ++c) mx = fmaxf(mx, m[(int64_t)c * M].x);
@@ -127,11 +127,11 @@ __global__ __launch_bounds__(256) void ce_finish_kernel(const double* __restrict
     if (tid == 0) out[ph] = rc[0] > 0.0 ? rs[0] / rc[0] : 0.0;
 }
 
-hipError_t launch_ce_combine(const void* ms, const float* tl, const int32_t* target, int64_t M, int nchunk, int nphase,
-                             double* scratch, double* out, hipStream_t st) {
+hipError_t launch_ce_combine(const void* ms, const float* tl, const int32_t* target, int64_t M, int64_t N, int nchunk,
+                             int nphase, double* scratch, double* out, hipStream_t st) {
     const int nblk = (int)((M + 255) / 256);
     hipLaunchKernelGGL(ce_combine_kernel, dim3(nblk, nphase), dim3(256), 0, st, reinterpret_cast<const float2*>(ms), tl,
-                       target, M, nchunk, scratch);
+                       target, M, N, nchunk, scratch);
     hipLaunchKernelGGL(ce_finish_kernel, dim3(nphase), dim3(256), 0, st, scratch, nblk, out);
     return hipGetLastError();
 }
@@ -143,7 +143,7 @@ __global__ __launch_bounds__(256) void ce_rows_f32_kernel(const float* __restric
     const int tid = threadIdx.x;
     const int64_t t = blockIdx.x;
     const int tgt = target[t];
-    if (tgt < 0) {
+    if (tgt < 0 || tgt >= N) {   // ignored row; an id outside the layer's outputs has no logit and is skipped too
         if (tid == 0) { scratch[t * 2] = 0.0; scratch[t * 2 + 1] = 0.0; }
         return;
     }

@@ -301,6 +301,10 @@ static hipError_t launch_apply(dim3 grid, size_t smem, hipStream_t st, const flo
         return hipGetLastError();
     }
     hipLaunchKernelGGL(qr_apply_gram_kernel<RP>, grid, block, smem, st, Sin, d, r, partial1, nblk, Q1, partial2, numeric_flag);
+    {
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
     hipLaunchKernelGGL((qr_apply_final_kernel<RP, double>), grid, block, smem, st, Q1, d, r, partial2, nblk, Q, planes, numeric_flag);
     return hipGetLastError();
 }
@@ -324,6 +328,10 @@ hipError_t launch_qr(const float* S, const float* splits, int nsplit, int rp, fl
         attr_set = true;
     }
     hipLaunchKernelGGL(qr_gram_kernel, grid, block, sm_full, st, S, splits, nsplit, S_out, d, r, rp, partial1);
+    {
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;      // the launches below consume what this one would have written
+    }
     switch (rp) {
         case 16: return launch_apply<16>(grid, sm_full, st, Sin, d, r, partial1, partial2, nblk, Q1, Q, planes, numeric_flag, refine);
         case 32: return launch_apply<32>(grid, sm_full, st, Sin, d, r, partial1, partial2, nblk, Q1, Q, planes, numeric_flag, refine);

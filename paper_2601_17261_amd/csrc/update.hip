@@ -1,5 +1,7 @@
 // In-place rank-r sweep of Alg. 2 (restore / update line, Eq. 10):
-//     W[i][j] -= lr * g * sum_k G[i][k] * B[j][k]
+//     W[i][j] -= (lr * g + shift) * sum_k G[i][k] * B[j][k]
+// (shift = 0 for the update alone; shift = eps makes it the printed last line of Alg. 2, which takes the perturbation
+// out and applies the update in one sweep).
 // W is read and written exactly once (HBM-bound); G is regenerated from the Philox seed (the d_out x d_in
 // direction Z = G B^T never exists in memory); B (d_in x r fp32) is small and stays in L2.  fp32
 // accumulation, one rounding to the storage type on the store.
@@ -15,7 +17,8 @@ constexpr int UP_TR = 8;     // rows per thread
 template <int KC>
 __global__ __launch_bounds__(256) void update_kernel(float* __restrict__ Wf, int64_t ldw, int64_t d_out, int64_t d_in,
                                                      const float* __restrict__ B, int r, int nchunk, uint32_t s_lo,
-                                                     uint32_t s_hi, float lr, const double* __restrict__ g_dev) {
+                                                     uint32_t s_hi, float lr, float shift,
+                                                     const double* __restrict__ g_dev) {
     extern __shared__ __align__(16) float up_smem[];
     const int rp = KC * nchunk;
     float* Gs = up_smem;                 // [UP_TI][rp]
@@ -42,7 +45,7 @@ __global__ __launch_bounds__(256) void update_kernel(float* __restrict__ Wf, int
     }
     __syncthreads();
 
-    const float coef = -lr * (g_dev ? (float)(*g_dev) : 1.0f);
+    const float coef = -fmaf(lr, g_dev ? (float)(*g_dev) : 1.0f, shift);
     const int tx = tid & 31;          // 8 consecutive columns
     const int ty = tid >> 5;          // rows ty + 8*s
     const int64_t jc = j0 + tx * 8;
@@ -136,7 +139,7 @@ constexpr int UM_COLS = 256;    // columns of W per workgroup
 //   Bf [col block jb][kc][plane][m][lane]     lane = c + 32 * lh, j = 256 jb + 8 c + m, same k
 __device__ __forceinline__ void prep_fragment(uint4* __restrict__ Gf, uint4* __restrict__ Bf, int64_t n_g, int64_t n_b,
                                               int nk, int64_t d_out, int64_t d_in, const float* __restrict__ B, int r,
-                                              uint32_t s_lo, uint32_t s_hi, float lr,
+                                              uint32_t s_lo, uint32_t s_hi, float lr, float shift,
                                               const double* __restrict__ g_dev, int64_t t) {
     float f[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     FragU hi, lo;
@@ -146,7 +149,7 @@ __device__ __forceinline__ void prep_fragment(uint4* __restrict__ Gf, uint4* __r
         const int64_t i = ib * UM_ROWS + (lane & 31);
         const int k0 = 16 * kc + 8 * (lane >> 5);
         if (i < d_out && k0 < r) {
-            const float coef = -lr * (g_dev ? (float)(*g_dev) : 1.0f);
+            const float coef = -fmaf(lr, g_dev ? (float)(*g_dev) : 1.0f, shift);
             const float4 z0 = philox_normal4(s_lo, s_hi, AGZO_TAG_G, (uint32_t)i, (uint32_t)(k0 >> 2));
             f[0] = z0.x; f[1] = z0.y; f[2] = z0.z; f[3] = z0.w;
             if (k0 + 4 < r) {
@@ -181,9 +184,9 @@ __device__ __forceinline__ void prep_fragment(uint4* __restrict__ Gf, uint4* __r
 __global__ __launch_bounds__(256) void update_prep_kernel(uint4* __restrict__ Gf, uint4* __restrict__ Bf,
                                                           int64_t n_g, int64_t n_b, int nk, int64_t d_out,
                                                           int64_t d_in, const float* __restrict__ B, int r,
-                                                          uint32_t s_lo, uint32_t s_hi, float lr,
+                                                          uint32_t s_lo, uint32_t s_hi, float lr, float shift,
                                                           const double* __restrict__ g_dev) {
-    prep_fragment(Gf, Bf, n_g, n_b, nk, d_out, d_in, B, r, s_lo, s_hi, lr, g_dev, (int64_t)blockIdx.x * 256 + threadIdx.x);
+    prep_fragment(Gf, Bf, n_g, n_b, nk, d_out, d_in, B, r, s_lo, s_hi, lr, shift, g_dev, (int64_t)blockIdx.x * 256 + threadIdx.x);
 }
 
 // Several matrices in one pair of launches (Alg. 2 updates every layer once the scalar g is known): the table is a
@@ -209,7 +212,7 @@ __global__ __launch_bounds__(256) void update_prep_many_kernel(const UpdBatch tb
     int m = 0;
     while (m + 1 < tb.n && blockIdx.x >= tb.it[m + 1].prep_blk0) ++m;
     const UpdItem& u = tb.it[m];
-    prep_fragment(u.Gf, u.Bf, u.n_g, u.n_b, nk, u.d_out, u.d_in, u.B, u.r, u.s_lo, u.s_hi, u.lr, u.g_dev,
+    prep_fragment(u.Gf, u.Bf, u.n_g, u.n_b, nk, u.d_out, u.d_in, u.B, u.r, u.s_lo, u.s_hi, u.lr, 0.f, u.g_dev,
                   (int64_t)(blockIdx.x - u.prep_blk0) * 256 + threadIdx.x);
 }
 
@@ -330,7 +333,7 @@ static hipError_t launch_mfma(bf16_t* W, int64_t ldw, int64_t d_out, int64_t d_i
 
 template <int KC>
 static hipError_t launch_kc(float* W, int64_t ldw, int64_t d_out, int64_t d_in, const float* B, int r, int nchunk,
-                            uint64_t seed, float lr, const double* g_dev, hipStream_t st) {
+                            uint64_t seed, float lr, float shift, const double* g_dev, hipStream_t st) {
     dim3 grid((unsigned)((d_in + UP_TJ - 1) / UP_TJ), (unsigned)((d_out + UP_TI - 1) / UP_TI));
     const int rp = KC * nchunk;
     const size_t smem = (size_t)(UP_TI + UP_TJ) * rp * sizeof(float);
@@ -343,21 +346,21 @@ static hipError_t launch_kc(float* W, int64_t ldw, int64_t d_out, int64_t d_in, 
         set = true;
     }
     hipLaunchKernelGGL((update_kernel<KC>), grid, dim3(256), smem, st, W, ldw, d_out, d_in, B, r, nchunk, (uint32_t)seed,
-                       (uint32_t)(seed >> 32), lr, g_dev);
+                       (uint32_t)(seed >> 32), lr, shift, g_dev);
     return hipGetLastError();
 }
 
 hipError_t launch_update(void* W, int dtype, int64_t ldw, int64_t d_out, int64_t d_in, const float* B, int r,
-                         uint64_t seed, float lr, const double* g_dev, void* workspace, hipStream_t st) {
+                         uint64_t seed, float lr, const double* g_dev, void* workspace, hipStream_t st, float shift) {
     if (d_out == 0 || d_in == 0) return hipSuccess;
     // fp32 storage keeps exact fp32 products (VALU); bf16 storage takes the matrix-core outer product
     if (dtype != AGZO_BF16) {
         float* Wf = static_cast<float*>(W);
-        if (r <= 1) return launch_kc<1>(Wf, ldw, d_out, d_in, B, r, 1, seed, lr, g_dev, st);
-        if (r <= 2) return launch_kc<2>(Wf, ldw, d_out, d_in, B, r, 1, seed, lr, g_dev, st);
-        if (r <= 4) return launch_kc<4>(Wf, ldw, d_out, d_in, B, r, 1, seed, lr, g_dev, st);
-        if (r <= 8) return launch_kc<8>(Wf, ldw, d_out, d_in, B, r, 1, seed, lr, g_dev, st);
-        return launch_kc<16>(Wf, ldw, d_out, d_in, B, r, (r + 15) / 16, seed, lr, g_dev, st);
+        if (r <= 1) return launch_kc<1>(Wf, ldw, d_out, d_in, B, r, 1, seed, lr, shift, g_dev, st);
+        if (r <= 2) return launch_kc<2>(Wf, ldw, d_out, d_in, B, r, 1, seed, lr, shift, g_dev, st);
+        if (r <= 4) return launch_kc<4>(Wf, ldw, d_out, d_in, B, r, 1, seed, lr, shift, g_dev, st);
+        if (r <= 8) return launch_kc<8>(Wf, ldw, d_out, d_in, B, r, 1, seed, lr, shift, g_dev, st);
+        return launch_kc<16>(Wf, ldw, d_out, d_in, B, r, (r + 15) / 16, seed, lr, shift, g_dev, st);
     }
     if (!workspace || ldw >= (1LL << 28)) return hipErrorInvalidValue;   // the sweep's lane offsets are 32-bit
     const int nk = (r + 15) / 16;
@@ -366,7 +369,7 @@ hipError_t launch_update(void* W, int dtype, int64_t ldw, int64_t d_out, int64_t
     uint4* Gf = static_cast<uint4*>(workspace);
     uint4* Bf = Gf + nib * nk * 2 * 64;
     hipLaunchKernelGGL(update_prep_kernel, dim3((unsigned)((n_g + n_b + 255) / 256)), dim3(256), 0, st, Gf, Bf, n_g, n_b,
-                       nk, d_out, d_in, B, r, (uint32_t)seed, (uint32_t)(seed >> 32), lr, g_dev);
+                       nk, d_out, d_in, B, r, (uint32_t)seed, (uint32_t)(seed >> 32), lr, shift, g_dev);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     bf16_t* Wb = static_cast<bf16_t*>(W);

@@ -44,6 +44,20 @@ def host(t):
     return t.detach().float().cpu().numpy().astype(np.float64)
 
 
+def assert_increment(W_gpu, W, W_oracle, storage, g_tol=2e-2):
+    """The update itself, not the weights it rides on (a no-op update must fail): fp32 storage compares the increments;
+    in bf16 storage most increments round away, so the entries the oracle moved must exist and move identically on the
+    GPU (up to the few whose rounding boundary lies inside g's own tolerance), and the others must stay."""
+    d_gpu, d_or = W_gpu - W, W_oracle - W
+    assert np.count_nonzero(d_or) > 0, "the case has no power: the oracle's update rounds away everywhere"
+    if storage == "f32":
+        assert rel(d_gpu, d_or) < g_tol
+        return
+    moved = d_or != 0
+    assert np.mean(W_gpu[moved] == W_oracle[moved]) > 0.9, np.mean(W_gpu[moved] == W_oracle[moved])
+    assert np.mean(W_gpu[~moved] != W[~moved]) < 0.02
+
+
 def problem(seed, n, d_in, d_out, kind, storage):
     W, X, T = synth.single_layer_problem(seed, n, d_in, d_out, kind=kind, storage=storage)
     return W, X, T, dev(W, storage), dev(X, storage), dev(T)
@@ -427,6 +441,7 @@ def test_step_matches_oracle(ctx, storage, n, d_in, d_out, r, kind, flags, tilin
     assert abs(got[3] - o["g"]) < gtol * abs(o["g"]) + 1e-9, (got[3], o["g"])
     assert rel(host(Wd), o["W_new"]) < (1e-4 if storage == "f32" else 2e-2)
     assert rel(host(Wd), o["W_new"]) < (1e-6 if storage == "f32" else 3e-3)
+    assert_increment(host(Wd), W.astype(np.float64), o["W_new"], storage)
 
 
 @pytest.mark.parametrize("storage,n,d_in,d_out,r", [("f32", 200, 96, 130, 4), ("bf16", 515, 136, 300, 8),
@@ -503,6 +518,7 @@ def test_naive_inplace_comparator_has_its_own_oracle(ctx, one_sided):
         assert abs(got[1] - o["Lp"]) < 1e-4 * o["Lp"]
         assert abs(got[2] - o["Lm"]) <= 1e-4 * o["Lm"]
         assert rel(host(Wd), o["W_new"]) < tolW
+        assert_increment(host(Wd), W.astype(np.float64), o["W_new"], storage)
 
 
 @pytest.mark.parametrize("storage,one_sided", [("f32", False), ("bf16", False), ("bf16", True)])
@@ -657,6 +673,7 @@ def test_qwen3_0p6b_layer_set_one_step(ctx, tiling):
         assert abs(got[0] - o["L0"]) < 1e-5 * o["L0"], name
         assert abs(got[3] - o["g"]) < 2e-2 * abs(o["g"]) + 1e-9, (name, got[3], o["g"])
         assert rel(host(Wd), o["W_new"]) < 3e-3, name
+        assert_increment(host(Wd), W.astype(np.float64), o["W_new"], "bf16")
 
 
 # ---------------------------------------------------------------------------------------------
@@ -695,6 +712,63 @@ def test_invalid_arguments_are_rejected(ctx):
     ctx.dense_perturb(torch.empty(0, dtype=torch.bfloat16, device="cuda"), 1, 1.0)
     ctx.check()
     np.testing.assert_array_equal(Wd.float().cpu().numpy(), W)     # nothing was touched
+
+
+def test_misaligned_or_overlong_bf16_operands_are_rejected(ctx):
+    """bf16 operands travel as 16-byte vectors: a pointer off by a few elements, or a leading dimension beyond what
+    the kernels' 32-bit offsets cover, is refused by every entry point that reads X or W."""
+    W, X, T, Wd, Xd, Td = problem(1, 64, 40, 16, "lowrank", "bf16")
+    Xw = torch.zeros(64, 48, dtype=torch.bfloat16, device="cuda")
+    Xoff = Xw[:, 4:44]                      # 8 bytes off a 16-byte boundary, ld = 48
+    Ww = torch.zeros(16, 48, dtype=torch.bfloat16, device="cuda")
+    Woff = Ww[:, 4:44]
+    out = torch.zeros(4, dtype=torch.float64, device="cuda")
+    B = torch.zeros(40, 4, dtype=torch.float32, device="cuda")
+    S = torch.zeros(40, 4, dtype=torch.float32, device="cuda")
+    loss = binding.make_loss(Td)
+    calls = [
+        lambda X_, W_: ctx.layer_forward_sketch(binding.make_layer(W_, X_, 4), W_, X_, None, binding.SKETCH_RANGE, None, 1, S, loss, out[0:1]),
+        lambda X_, W_: ctx.basis(binding.make_layer(W_, X_, 4), X_, 3, 1, None, 0, B),
+        lambda X_, W_: ctx.perturbed_forward(binding.make_layer(W_, X_, 4), W_, X_, B, 1, EPS, None, loss, out[1:2]),
+        lambda X_, W_: ctx.step(binding.make_layer(W_, X_, 4), W_, X_, loss, 3, EPS, LR, 1, 0, out),
+    ]
+    for i, call in enumerate(calls):
+        with pytest.raises(binding.AgzoError) as e:
+            call(Xoff, Wd)
+        assert e.value.code == binding.EINVAL, i
+        if i != 1:                          # agzo_basis does not read W
+            with pytest.raises(binding.AgzoError) as e:
+                call(Xd, Woff)
+            assert e.value.code == binding.EINVAL, i
+    Lbig = binding.make_layer(Wd, Xd, 4)
+    Lbig.ldx = 1 << 22
+    with pytest.raises(binding.AgzoError) as e:
+        ctx.step(Lbig, Wd, Xd, loss, 3, EPS, LR, 1, 0, out)
+    assert e.value.code == binding.EINVAL
+    ctx.check()
+    assert torch.count_nonzero(Xw).item() == 0 and torch.count_nonzero(Ww).item() == 0
+
+
+@pytest.mark.parametrize("storage,n,d_in,d_out", [("f32", 200, 96, 130), ("bf16", 515, 136, 300)])
+def test_cross_entropy_ids_beyond_the_outputs_are_skipped(ctx, storage, n, d_in, d_out):
+    """An id >= d_out is a caller error; the kernels do not read a logit for it: the row counts as ignored."""
+    W, X, _ = synth.single_layer_problem(5 + n, n, d_in, d_out, kind="lowrank", storage=storage)
+    rng = np.random.default_rng(n)
+    ids = rng.integers(0, d_out, size=n).astype(np.int32)
+    bad = rng.choice(n, size=n // 9, replace=False)
+    ids_bad = ids.copy()
+    ids_bad[bad] = d_out + rng.integers(0, 1000, size=bad.size).astype(np.int32)
+    ids_ref = ids.copy()
+    ids_ref[bad] = -1
+    Wd, Xd = dev(W, storage), dev(X, storage)
+    L = binding.make_layer(Wd, Xd, 4)
+    sc = torch.zeros(1, dtype=torch.float64, device="cuda")
+    ids_dev = torch.from_numpy(ids_bad).cuda()
+    ctx.layer_forward_sketch(L, Wd, Xd, None, binding.SKETCH_NONE, None, 1, None,
+                             binding.make_loss(ids_dev, kind=binding.LOSS_CE), sc)
+    ctx.check()
+    want = oagzo.ce_loss(oagzo.forward(X, W), ids_ref)
+    assert abs(sc.item() - want) < 2e-6 * want
 
 
 # ---------------------------------------------------------------------------------------------
