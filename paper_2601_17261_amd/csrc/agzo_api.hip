@@ -344,7 +344,7 @@ int op_forward(agzo_ctx* ctx, const agzo_layer& L, const Plan& p, const void* W,
         a.loss = la;
         a.shared = shared;
         a.large_tiles = (L.tiling == AGZO_TILING_LARGE);
-        a.ext_ws = (P && !shared) ? ctx->ws + p.off_ext : nullptr;
+        a.ext_ws = P ? ctx->ws + p.off_ext : nullptr;
         if (((ctx->prof >> AGZO_PROF_GEMM) & 1u) && ctx->clk_used < kClkSlots) a.clk = ctx->clk + 4 * ctx->clk_used++;
         {
             ProfScope ps(ctx, AGZO_PROF_GEMM);

@@ -36,12 +36,10 @@ int gemm_bf16_num_workgroups(int64_t M, int64_t N, bool small_ok) {
 
 // WA x WB waves: WA splits the 256 outputs, WB splits the 256 tokens
 // EPI selects the epilogue compiled into the kernel: 0 = general (stores, squared error, any bounds), 1 = cross-entropy
-// statistics, 2 / 3 = squared error only against an fp32 / bf16 target, M and N multiples of the tile, 16-byte accesses
+// statistics.  (Tile-aligned layers with the squared-error loss and no stored Y take the kernel of gemm_bf16_mse.hip.)
 template <int WA, int WB, bool SHARED, int EPI>
 __global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
     constexpr bool CE = (EPI == 1);
-    constexpr bool FAST = (EPI >= 2);
-    constexpr bool T_F32 = (EPI == 2);
     constexpr int NT = 64 * WA * WB;
     constexpr int BA = BT / WA / 32;           // 32-row blocks of W per wave
     constexpr int BB = BT / WB / 32;           // 32-row blocks of X per wave
@@ -226,37 +224,6 @@ __global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
     const bool l_f32 = !CE && p.loss_kind == AGZO_LOSS_MSE && p.target_dtype != AGZO_BF16;
     const bool l_bf16 = !CE && p.loss_kind == AGZO_LOSS_MSE && p.target_dtype == AGZO_BF16;
 
-    // Target staging for the squared-error loss: the 16 values a lane needs per accumulator block are fetched as raw
-    // 16-byte vectors (fp32: four, bf16: two), one token block (BA accumulator blocks) per request group and two groups
-    // in flight, because the epilogue is bound by memory latency, not by bandwidth or arithmetic.
-    uint4 traw[2][BA][4];
-    // token block j of the tile: fp32 values fill traw[j & 1][i][0..3] (two blocks in flight); bf16 values fill
-    // traw[j >> 1][i][2 (j & 1) ..] (the whole tile fits)
-    auto tload = [&](auto J) __attribute__((always_inline)) {
-        constexpr int j = decltype(J)::value;
-        if (!FAST) return;
-        const int64_t row = m0 + wb * (BT / WB) + j * 32 + lr;
-        const int64_t colw = n0 + wa * (BT / WA) + lh * 16;
-        if (T_F32) {
-            const uint4* src = reinterpret_cast<const uint4*>(reinterpret_cast<const float*>(p.target) + row * p.ldt + colw);
-#pragma clang loop unroll(full)
-            for (int i = 0; i < BA; ++i)
-#pragma clang loop unroll(full)
-                for (int q = 0; q < 4; ++q) traw[j & 1][i][q] = src[i * 8 + q];
-        } else {
-            const uint4* src = reinterpret_cast<const uint4*>(reinterpret_cast<const bf16_t*>(p.target) + row * p.ldt + colw);
-#pragma clang loop unroll(full)
-            for (int i = 0; i < BA; ++i)
-#pragma clang loop unroll(full)
-                for (int q = 0; q < 2; ++q) traw[j >> 1][i][2 * (j & 1) + q] = src[i * 4 + q];
-        }
-    };
-    // issued ahead of the last multiply before the evaluation that reads the target: 64 registers' worth (one fp32
-    // token block, two bf16 ones); more would not fit beside the multiply's fragments and spill
-    auto tload_first = [&]() __attribute__((always_inline)) {
-        tload(IC<0>{});
-        if (FAST && !T_F32) tload(IC<1>{});
-    };
     // ---- multiply ---------------------------------------------------------------------------------
     // per-lane LDS byte offsets of this wave's fragments for the four 16-wide sub-steps of a slice; block i of an
     // operand is 32 rows = 4096 bytes further (the swizzle term (row >> 1) & 7 is the same for all blocks)
@@ -361,7 +328,7 @@ __global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
         }
     };
     // the plain slices 0 .. nfull-1 (and ready-made extension slices) through the pipeline above
-    auto run_plain = [&](bool preload) __attribute__((always_inline)) {
+    auto run_plain = [&]() __attribute__((always_inline)) {
         if (npipe == 0) return;
         select_slice(IC<0>{}, 0);
 #pragma unroll
@@ -381,7 +348,6 @@ __global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
             steady(0, npipe - 1);
             __builtin_amdgcn_s_waitcnt(0x0F70);          // the re-fetches
             // last plain slice: sub-step 0 is already in fragment set 0
-            if (preload) tload_first();
             const int cur = (npipe - 1) & 1;
 #pragma unroll
             for (int kk = 0; kk < 4; ++kk) {
@@ -393,17 +359,15 @@ __global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
                 for (int q = 0; q < 16; ++q) mfma1(kk & 1, q);
             }
         } else {
-            if (preload) tload_first();
             multiply_plain(0);
         }
         __syncthreads();
     };
     // slices [it_begin, it_end) that the threads fill themselves (ragged end of d_in, rank-r extension), one at a time
-    auto run_manual = [&](int it_begin, int it_end, int preload_at) __attribute__((always_inline)) {
+    auto run_manual = [&](int it_begin, int it_end) __attribute__((always_inline)) {
         for (int it = it_begin; it < it_end; ++it) {
             fill_manual(it, 0);
             __syncthreads();
-            if (it == preload_at) tload_first();
             multiply_plain(0);
             __syncthreads();
         }
@@ -411,7 +375,6 @@ __global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
     // ---- evaluation point: the accumulators hold Y0 (shared mode, after the d_in slices), or Y with
     // the rank-r term of the current sign.  Lane = one token, 16 consecutive outputs per block.
     // Differences and their squares are taken in fp32, four at a time, and summed in fp64.
-    // The caller has issued tload(0) before the last multiply when the target is read at this evaluation.
     auto evaluate = [&](int phase) __attribute__((always_inline)) {
         double part = 0.0;
         // shared mode: the first evaluation turns the accumulators into the residual Y0 - Y*, so the
@@ -508,63 +471,10 @@ __global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
                 if (SHARED) acc[i][j] = v;
             }
         };
-        // fast path: one of two specialised bodies, no stores, no bounds
-        auto fast_block = [&](auto J, auto F32) __attribute__((always_inline)) {
-            constexpr int j = decltype(J)::value;
-            constexpr bool f32 = decltype(F32)::value != 0;
-#pragma clang loop unroll(full)
-            for (int i = 0; i < BA; ++i) {
-                floatx16 v = acc[i][j];
-#pragma clang loop unroll(full)
-                for (int q = 0; q < 4; ++q) {
-                    float tv[4] = {0.f, 0.f, 0.f, 0.f};
-                    if (!resid) {
-                        if (f32) {
-                            const uint4 t = traw[j & 1][i][q];
-                            tv[0] = __uint_as_float(t.x); tv[1] = __uint_as_float(t.y);
-                            tv[2] = __uint_as_float(t.z); tv[3] = __uint_as_float(t.w);
-                        } else {
-                            const uint4 t = traw[j >> 1][i][2 * (j & 1) + (q >> 1)];
-                            const uint32_t w0 = (q & 1) ? t.z : t.x, w1 = (q & 1) ? t.w : t.y;
-                            tv[0] = __uint_as_float(w0 << 16); tv[1] = __uint_as_float(w0 & 0xFFFF0000u);
-                            tv[2] = __uint_as_float(w1 << 16); tv[3] = __uint_as_float(w1 & 0xFFFF0000u);
-                        }
-                    }
-                    float s4 = 0.f;
-#pragma clang loop unroll(full)
-                    for (int u = 0; u < 4; ++u) {
-                        const float dd = v[4 * q + u] - tv[u];
-                        s4 = fmaf(dd, dd, s4);
-                        if (SHARED) v[4 * q + u] = dd;
-                    }
-                    part += (double)s4;
-                }
-                if (SHARED && !resid) acc[i][j] = v;
-            }
-        };
-        if constexpr (FAST) {
-            if constexpr (T_F32) {
-                // the next token block's values are requested before this one's are used
-                if (!resid) tload(IC<1>{});
-                fast_block(IC<0>{}, IC<1>{});
-                if (!resid) tload(IC<2>{});
-                fast_block(IC<1>{}, IC<1>{});
-                if (!resid) tload(IC<3>{});
-                fast_block(IC<2>{}, IC<1>{});
-                fast_block(IC<3>{}, IC<1>{});
-            } else {
-                if (!resid) { tload(IC<2>{}); tload(IC<3>{}); }
-                fast_block(IC<0>{}, IC<0>{});
-                fast_block(IC<1>{}, IC<0>{});
-                fast_block(IC<2>{}, IC<0>{});
-                fast_block(IC<3>{}, IC<0>{});
-            }
-        } else {
-            eval_block(IC<0>{});
-            eval_block(IC<1>{});
-            eval_block(IC<2>{});
-            eval_block(IC<3>{});
-        }
+        eval_block(IC<0>{});
+        eval_block(IC<1>{});
+        eval_block(IC<2>{});
+        eval_block(IC<3>{});
         if (CE) {
             // a lane holds 16 of the 32 logits of each of its BA blocks for BB tokens; its partner lane
             // (lane ^ 32) holds the other 16.  Online softmax over the wave's columns, per token.
@@ -621,26 +531,23 @@ __global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
             __syncthreads();
         }
     };
-    // the first target values are requested ahead of the last multiply before the evaluation that reads them
     if (SHARED && next > 0) {
-        const int last0 = nd - 1;
-        run_plain(last0 == nfull - 1);
+        run_plain();
         // one copy of the fill / multiply / evaluate code, walked three times: Y0, Y+ (extension with +eps), Y- (-2 eps)
         for (int ph = 0; ph < 3; ++ph) {
             const int it0 = (ph == 0) ? nfull : nd + (ph - 1) * next;
             const int it1 = nd + ph * next;
-            run_manual(it0, it1, (ph == 0) ? last0 : -1);
+            run_manual(it0, it1);
             evaluate(ph);
         }
     } else if (ext_dma) {
         // pipelined: plain slices, then the ready-made extension slices; the ragged end of d_in (if any) last
-        run_plain(ntail == 0);
-        run_manual(nfull, nd, nd - 1);
+        run_plain();
+        run_manual(nfull, nd);
         evaluate(0);
     } else {
-        const int last0 = total - 1;
-        run_plain(last0 == nfull - 1);
-        run_manual(nfull, total, last0);
+        run_plain();
+        run_manual(nfull, total);
         evaluate(0);
     }
     if (p.clk && blockIdx.x == 0 && tid == 0) { p.clk[2] = __builtin_readcyclecounter(); p.clk[3] = wall_clock64(); }
@@ -650,14 +557,17 @@ __global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
 
 // Extension operands for one perturbed forward, written once instead of once per tile: eight columns per thread.
 // Rows 0..M-1 are the X side ([Ph | Ph | Pl | 0], P = X B split hi + lo in bf16), rows M..M+N-1 the W side
-// ([Gh | Gl | Gh | 0], G regenerated from the Philox seed, times the signed eps).
+// ([Gh | Gl | Gh | 0], G regenerated from the Philox seed, times the signed eps); n_w = 2 adds rows M+N..M+2N-1, the
+// W side once more with coef2 (the shared-forward kernel's second pass, -2 eps).
 __global__ __launch_bounds__(256) void gemm_ext_prep_kernel(bf16_t* __restrict__ Xext, bf16_t* __restrict__ Wext, int64_t M,
                                                             int64_t N, int ext_ld, const float* __restrict__ P, int r, int rp,
-                                                            float coef, uint32_t s_lo, uint32_t s_hi) {
+                                                            float coef, float coef2, int n_w, uint32_t s_lo, uint32_t s_hi) {
     const int chunks = ext_ld / 8;
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= (M + N) * chunks) return;
-    const int64_t row = idx / chunks;
+    if (idx >= (M + n_w * N) * chunks) return;
+    int64_t row = idx / chunks;
+    const bool second = row >= M + N;
+    if (second) { row -= N; coef = coef2; }
     const int col0 = (int)(idx % chunks) * 8;
     const int seg = col0 / rp, k0 = col0 % rp;
     uint32_t hi[4] = {0, 0, 0, 0}, lo[4] = {0, 0, 0, 0};
@@ -689,14 +599,14 @@ __global__ __launch_bounds__(256) void gemm_ext_prep_kernel(bf16_t* __restrict__
     // X side: [hi | hi | lo]; W side: [hi | lo | hi]
     const bool use_lo = (row < M) ? (seg == 2) : (seg == 1);
     const uint4 out = use_lo ? make_uint4(lo[0], lo[1], lo[2], lo[3]) : make_uint4(hi[0], hi[1], hi[2], hi[3]);
-    bf16_t* dst = (row < M) ? Xext + row * ext_ld + col0 : Wext + (row - M) * ext_ld + col0;
+    bf16_t* dst = (row < M) ? Xext + row * ext_ld + col0 : Wext + (row - M + (second ? N : 0)) * ext_ld + col0;
     *reinterpret_cast<uint4*>(dst) = out;
 }
 
 size_t gemm_bf16_ext_bytes(int64_t M, int64_t N, int r) {
     const int rp = (r + 15) / 16 * 16;
     const int ext_ld = (3 * rp + BK - 1) / BK * BK;
-    return (size_t)(M + N) * ext_ld * sizeof(bf16_t);
+    return (size_t)(M + 2 * N) * ext_ld * sizeof(bf16_t);   // X side, W side, and the W side of a second pass
 }
 
 template <int WA, int WB, bool SHARED, int EPI>
@@ -735,47 +645,39 @@ hipError_t launch_gemm_bf16(const GemmBf16Args& a, hipStream_t st) {
         vec = vec && (a.loss.ldt % 8 == 0) && ((reinterpret_cast<uintptr_t>(a.loss.target) & 15) == 0);
     p.vec_ok = vec ? 1 : 0;
     p.shared = a.shared ? 1 : 0;
-    p.Xext = nullptr; p.Wext = nullptr; p.ext_ld = 0;
-    if (a.P && !a.shared && a.ext_ws) {
+    p.Xext = nullptr; p.Wext = nullptr; p.Wext2 = nullptr; p.ext_ld = 0;
+    const bool small = small_shape(a.M, a.N) && !a.large_tiles && !a.shared && p.loss_kind != AGZO_LOSS_CE;
+    // the squared-error kernel of gemm_bf16_mse.hip takes tile-aligned layers (also in shared-forward mode)
+    const bool mse = !small && a.loss.kind == AGZO_LOSS_MSE && !a.Y && vec && a.M % BT == 0 && a.N % BT == 0 &&
+                     a.K % BK == 0 && a.K >= 2 * BK && (!a.P || a.ext_ws);
+    if (a.P && a.ext_ws && (!a.shared || mse)) {
         p.ext_ld = (3 * p.rp + BK - 1) / BK * BK;
         bf16_t* xe = static_cast<bf16_t*>(a.ext_ws);
         bf16_t* we = xe + a.M * p.ext_ld;
-        const int64_t items = (a.M + a.N) * (p.ext_ld / 8);
+        const int n_w = a.shared ? 2 : 1;
+        const int64_t items = (a.M + n_w * a.N) * (p.ext_ld / 8);
         hipLaunchKernelGGL(gemm_ext_prep_kernel, dim3((unsigned)((items + 255) / 256)), dim3(256), 0, st, xe, we, a.M, a.N, p.ext_ld,
-                           a.P, a.r, p.rp, a.eps_signed, p.s_lo, p.s_hi);
+                           a.P, a.r, p.rp, a.eps_signed, -2.f * a.eps_signed, n_w, p.s_lo, p.s_hi);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
         p.Xext = xe; p.Wext = we;
+        if (a.shared) p.Wext2 = we + a.N * p.ext_ld;
     }
     p.ce_target = reinterpret_cast<const int32_t*>(a.loss.target);
     p.ce_ms = reinterpret_cast<float2*>(a.loss.ce_ms);
     p.ce_tl = a.loss.ce_tl;
     p.clk = a.clk;
-    if (small_shape(a.M, a.N) && !a.large_tiles && !a.shared && p.loss_kind != AGZO_LOSS_CE) {
+    if (small) {
         // the workspace was sized for this tiling's partials (gemm_bf16_num_workgroups with small_ok)
         if (a.P && !p.Xext) return hipErrorInvalidValue;      // the small tiling takes the rank-r term as operands only
         p.tiles_m = (int)((a.M + BT_SMALL - 1) / BT_SMALL);
         p.tiles_n = (int)((a.N + BT_SMALL - 1) / BT_SMALL);
         return launch_gemm_bf16_small(p, st);
     }
-    int epi = 0;
-    if (p.loss_kind == AGZO_LOSS_CE) epi = 1;
-    else if (p.loss_kind == AGZO_LOSS_MSE && !a.Y && vec && a.M % BT == 0 && a.N % BT == 0)
-        epi = (p.target_dtype == AGZO_BF16) ? 3 : 2;
-    if (p.shared) {
-        switch (epi) {
-            case 1: return launch_variant<2, 2, true, 1>(p, st);
-            case 2: return launch_variant<2, 2, true, 2>(p, st);
-            case 3: return launch_variant<2, 2, true, 3>(p, st);
-            default: return launch_variant<2, 2, true, 0>(p, st);
-        }
-    }
-    switch (epi) {
-        case 1: return launch_variant<2, 2, false, 1>(p, st);
-        case 2: return launch_variant<2, 2, false, 2>(p, st);
-        case 3: return launch_variant<2, 2, false, 3>(p, st);
-        default: return launch_variant<2, 2, false, 0>(p, st);
-    }
+    if (mse) return launch_gemm_bf16_mse(p, st);
+    const bool ce = p.loss_kind == AGZO_LOSS_CE;
+    if (p.shared) return ce ? launch_variant<2, 2, true, 1>(p, st) : launch_variant<2, 2, true, 0>(p, st);
+    return ce ? launch_variant<2, 2, false, 1>(p, st) : launch_variant<2, 2, false, 0>(p, st);
 }
 
 }  // namespace agzo

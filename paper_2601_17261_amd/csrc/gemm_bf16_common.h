@@ -30,7 +30,8 @@ struct GemmParams {
     const float* P; int r; int rp;
     // rank-r extension operands prepared ahead of the launch (NULL: the workgroups build them per tile):
     // Xext [M][ext_ld] = [Ph | Ph | Pl | 0], Wext [N][ext_ld] = [Gh | Gl | Gh | 0] with the signed eps folded into G
-    const bf16_t* Xext; const bf16_t* Wext; int ext_ld;
+    // Wext2: the W side once more with -2 eps folded in (second pass of the shared-forward squared-error kernel)
+    const bf16_t* Xext; const bf16_t* Wext; const bf16_t* Wext2; int ext_ld;
     float eps_signed; uint32_t s_lo, s_hi;
     int loss_kind; int target_dtype; const void* target; int64_t ldt; double* partials;
     int tiles_m, tiles_n;
@@ -48,5 +49,10 @@ struct GemmParams {
 // partials [tiles128_m * tiles128_n]
 constexpr int BT_SMALL = 128;
 hipError_t launch_gemm_bf16_small(const GemmParams& p, hipStream_t st);
+
+// squared-error kernel for tile-aligned layers (gemm_bf16_mse.hip): M, N multiples of 256, d_in a multiple of 64 and
+// >= 128, no stored Y, 16-byte target accesses, the rank-r term as prepared operands; p.shared: f0, f+, f- in one pass
+// (needs Wext2), partials [3][tiles]
+hipError_t launch_gemm_bf16_mse(const GemmParams& p, hipStream_t st);
 
 }  // namespace agzo

@@ -1,0 +1,339 @@
+// Forward GEMM with the squared-error loss for tile-aligned layers, the case the benchmark configuration runs:
+//     f = sum over the tile of (X W^T (+ eps (X B) G^T) - Y*)^2        (f0, f+, f- of Sec. 4.1; Eq. 7 factored)
+// Same tiling, LDS layout, direct global -> LDS operand loads and fixed-order steady state as gemm_bf16.hip (256 x 256
+// tile, four waves of 128 x 128, v_mfma_f32_32x32x16_bf16, 64-wide K slices, two LDS stages), but a kernel of its own
+// with one straight path and nothing else compiled in: M and N multiples of 256, d_in a multiple of 64 and at least
+// 128, no stored Y, 16-byte aligned target rows, the rank-r extension as prepared operands.
+//
+// The accumulators do not start at zero but at minus the target tile: the target is requested before the first
+// operand slice and converted while that slice is on its way, so after the last slice the registers hold the residual
+// Y - Y* and the epilogue is a sum of squares of registers with no memory access.  (Reading the target in the epilogue
+// left the matrix cores idle for 15 - 18 % of a tile: every workgroup asks for its 128 KiB at the same moment and
+// waits out the latency, and the staging registers spilled.)  All evaluations of a step start from the same -Y*, so
+// f+ and f- still share bit-identical accumulators up to the rank-r slices.
+//
+// PHASES = 3 is the shared-forward schedule for a single layer: the d_in slices are multiplied once, f0 is the sum of
+// squares of the accumulators as they stand, the extension slices with +eps make them the residual of f+, the same
+// slices with -2 eps that of f-.  The extension operands of both passes are requested before the evaluation that
+// precedes them, so their latency runs under it.
+#include "gemm_bf16_common.h"
+
+namespace agzo {
+
+// A value moved into an accumulation register by hand: the 256 start values of the accumulators are produced by
+// vector instructions, and left to itself the compiler parks them in ordinary registers (and spills most of them)
+// until the first multiply.
+__device__ __forceinline__ float to_acc(float x) {
+    float r;
+    asm volatile("v_accvgpr_write_b32 %0, %1" : "=a"(r) : "v"(x));
+    return r;
+}
+
+template <bool T_F32, int PHASES>
+__global__ __launch_bounds__(256) void gemm_bf16_mse_kernel(GemmParams p) {
+    constexpr int NT = 256, BA = 4, BB = 4;
+    extern __shared__ __align__(16) char smem[];
+    const int tid = threadIdx.x, lane = tid & 63;
+    if (p.clk && blockIdx.x == 0 && tid == 0) { p.clk[0] = __builtin_readcyclecounter(); p.clk[1] = wall_clock64(); }
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wa = wave >> 1, wb = wave & 1;
+    const int lr = lane & 31, lh = lane >> 5;
+
+    // workgroup -> tile: each XCD (ids are dealt round-robin over the 8 XCDs) owns a contiguous run of tiles, walked in
+    // bands of group_m token tiles per output tile so that its L2 keeps a W tile and a band of X tiles
+    int wg = (int)blockIdx.x;
+    const int nwg = p.tiles_m * p.tiles_n;
+    {
+        const int per = nwg / 8;
+        if (wg < per * 8) wg = (wg % 8) * per + wg / 8;
+    }
+    const int GROUP_M = p.group_m;
+    const int group = wg / (GROUP_M * p.tiles_n);
+    const int first_m = group * GROUP_M;
+    const int gsz = min(GROUP_M, p.tiles_m - first_m);
+    const int in_group = wg - group * GROUP_M * p.tiles_n;
+    const int64_t tm = __builtin_amdgcn_readfirstlane(first_m + in_group % gsz);
+    const int64_t tn = __builtin_amdgcn_readfirstlane(in_group / gsz);
+    const int64_t m0 = tm * BT, n0 = tn * BT;
+
+    // ---- operand sources: X / W slices, then the prepared extension operands ----------------------
+    auto rsrc = [&](const bf16_t* base) {
+        return __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(base), 0, (int)0xFFFFFFFFu, 0x00020000);
+    };
+    const bf16_t* xbase = p.X + m0 * p.ldx;
+    const bf16_t* wbase = p.W + n0 * p.ldw;
+    const bool has_ext = p.Xext != nullptr;
+    const __amdgpu_buffer_rsrc_t rx = rsrc(xbase), rw = rsrc(wbase);
+    const __amdgpu_buffer_rsrc_t rx2 = rsrc(has_ext ? p.Xext + m0 * p.ext_ld : xbase);
+    const __amdgpu_buffer_rsrc_t rw2 = rsrc(has_ext ? p.Wext + n0 * p.ext_ld : wbase);
+    const __amdgpu_buffer_rsrc_t rw3 = rsrc((has_ext && PHASES == 3) ? p.Wext2 + n0 * p.ext_ld : wbase);
+    const int row0 = 8 * wave + (lane >> 3);                 // row of group t = row0 + 32 t (X), 32 t + w_perm(row0) (W)
+    const int chunk0 = (lane & 7) ^ ((row0 >> 1) & 7);       // the swizzle term does not depend on t
+    const int vx = (int)(((int64_t)row0 * p.ldx + chunk0 * 8) * 2), vw = (int)(((int64_t)w_perm(row0) * p.ldw + chunk0 * 8) * 2);
+    const int vx2 = (row0 * p.ext_ld + chunk0 * 8) * 2, vw2 = (w_perm(row0) * p.ext_ld + chunk0 * 8) * 2;
+    const int gsx = (int)(64 * p.ldx), gsw = (int)(64 * p.ldw), gs2 = 64 * p.ext_ld;   // bytes between row groups
+    const int nfull = (int)(p.K / BK);
+    const int next = has_ext ? p.ext_ld / BK : 0;
+    // slices that ride the load pipeline: the d_in slices, and in the one-evaluation kernel the extension behind them
+    const int npipe = nfull + (PHASES == 1 ? next : 0);
+    typedef __attribute__((address_space(3))) void* lptr_t;
+
+    // ---- accumulators <- minus the target tile ----------------------------------------------------
+    // lane = one token (row) and 16 consecutive outputs per 32 x 32 block; the raw 16-byte vectors wait in 128
+    // registers that nothing else needs before the first multiply: a whole bf16 tile, or half an fp32 one
+    floatx16 acc[BA][BB];
+    uint4 traw[2][BA][4];
+    auto tload = [&](auto J) __attribute__((always_inline)) {
+        constexpr int j = decltype(J)::value;
+        const int64_t row = m0 + wb * 128 + j * 32 + lr;
+        const int64_t colw = n0 + wa * 128 + lh * 16;
+        if (T_F32) {
+            const uint4* src = reinterpret_cast<const uint4*>(reinterpret_cast<const float*>(p.target) + row * p.ldt + colw);
+#pragma clang loop unroll(full)
+            for (int i = 0; i < BA; ++i)
+#pragma clang loop unroll(full)
+                for (int q = 0; q < 4; ++q) traw[j & 1][i][q] = src[i * 8 + q];
+        } else {
+            const uint4* src = reinterpret_cast<const uint4*>(reinterpret_cast<const bf16_t*>(p.target) + row * p.ldt + colw);
+#pragma clang loop unroll(full)
+            for (int i = 0; i < BA; ++i)
+#pragma clang loop unroll(full)
+                for (int q = 0; q < 2; ++q) traw[j >> 1][i][2 * (j & 1) + q] = src[i * 4 + q];
+        }
+    };
+    auto tneg = [&](auto J) __attribute__((always_inline)) {
+        constexpr int j = decltype(J)::value;
+#pragma clang loop unroll(full)
+        for (int i = 0; i < BA; ++i) {
+            floatx16 v;
+            if (T_F32) {
+#pragma clang loop unroll(full)
+                for (int q = 0; q < 4; ++q) {
+                    const uint4 t = traw[j & 1][i][q];
+                    v[4 * q] = to_acc(-__uint_as_float(t.x)); v[4 * q + 1] = to_acc(-__uint_as_float(t.y));
+                    v[4 * q + 2] = to_acc(-__uint_as_float(t.z)); v[4 * q + 3] = to_acc(-__uint_as_float(t.w));
+                }
+            } else {
+#pragma clang loop unroll(full)
+                for (int q = 0; q < 2; ++q) {
+                    const uint4 t = traw[j >> 1][i][2 * (j & 1) + q];
+                    const uint32_t w[4] = {t.x, t.y, t.z, t.w};
+#pragma clang loop unroll(full)
+                    for (int u = 0; u < 4; ++u) {     // widened to fp32 with the sign flipped on the raw bits
+                        v[8 * q + 2 * u] = to_acc(__uint_as_float((w[u] << 16) ^ 0x80000000u));
+                        v[8 * q + 2 * u + 1] = to_acc(__uint_as_float((w[u] & 0xFFFF0000u) ^ 0x80000000u));
+                    }
+                }
+            }
+            acc[i][j] = v;
+        }
+    };
+
+    // ---- multiply ---------------------------------------------------------------------------------
+    int aoff[4], boff[4];
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+        aoff[kk] = TILE_BYTES + lds_off(wa * 128 + lr, kk * 2 + lh);
+        boff[kk] = lds_off(wb * 128 + lr, kk * 2 + lh);
+    }
+    bf16x8 a[2][BA], b[2][BB];
+    auto frag1 = [&](int buf, int kk, int s, int q) __attribute__((always_inline)) {
+        const char* base = smem + buf * (2 * TILE_BYTES);
+        if (q < 4) a[s][q] = *reinterpret_cast<const bf16x8*>(base + aoff[kk] + q * 4096);
+        else b[s][q - 4] = *reinterpret_cast<const bf16x8*>(base + boff[kk] + (q - 4) * 4096);
+    };
+    auto mfma1 = [&](int s, int idx) __attribute__((always_inline)) {
+        const int i = idx >> 2, j = idx & 3;
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[s][i], b[s][j], acc[i][j], 0, 0, 0);
+    };
+    // source of a pipelined slice, chosen once per slice with scalar selects (no branches at the load sites)
+    __amdgpu_buffer_rsrc_t src_rsx[2] = {rx, rx}, src_rsw[2] = {rw, rw};
+    int src_vx[2] = {vx, vx}, src_vw[2] = {vw, vw}, src_so[2] = {0, 0}, src_gx[2] = {gsx, gsx}, src_gw[2] = {gsw, gsw};
+    auto select_slice = [&](auto SET, int kt) __attribute__((always_inline)) {
+        constexpr int set = decltype(SET)::value;
+        const bool e = kt >= nfull;
+        src_rsx[set] = e ? rx2 : rx;   src_rsw[set] = e ? rw2 : rw;
+        src_vx[set] = e ? vx2 : vx;    src_vw[set] = e ? vw2 : vw;
+        src_so[set] = (e ? kt - nfull : kt) * (BK * 2);
+        src_gx[set] = e ? gs2 : gsx;   src_gw[set] = e ? gs2 : gsw;
+    };
+    // direct load q (0..15) of the selected slice into buffer buf: even q = X row group q/2, odd q = W row group
+    auto dma1 = [&](auto SET, int buf, int q) __attribute__((always_inline)) {
+        constexpr int set = decltype(SET)::value;
+        const int t = q >> 1;
+        char* dst = smem + buf * (2 * TILE_BYTES) + wave * 1024 + t * 4096 + ((q & 1) ? TILE_BYTES : 0);
+        if (q & 1) __builtin_amdgcn_raw_ptr_buffer_load_lds(src_rsw[set], (lptr_t)dst, 16, src_vw[set] + t * src_gw[set], src_so[set], 0, 0);
+        else __builtin_amdgcn_raw_ptr_buffer_load_lds(src_rsx[set], (lptr_t)dst, 16, src_vx[set] + t * src_gx[set], src_so[set], 0, 0);
+    };
+    // 16 MFMAs of sub-step S_CUR in fixed issue order: even slots carry one fragment read each (for the next block),
+    // odd slots the direct loads D0..D1-1 of the selected slice
+    auto block = [&](auto S_CUR, int rbuf, auto RKK, auto RS, auto SET, int lbuf, auto D0, auto D1) __attribute__((always_inline)) {
+        constexpr int s_cur = decltype(S_CUR)::value, rkk = decltype(RKK)::value, rs = decltype(RS)::value;
+        constexpr int d0 = decltype(D0)::value, d1 = decltype(D1)::value, n = d1 - d0;
+#pragma unroll
+        for (int q = 0; q < 16; ++q) {
+            mfma1(s_cur, q);
+            const int o = q >> 1;
+            if (!(q & 1)) frag1(rbuf, rkk, rs, o);
+            else if (((o + 1) * n) / 8 > (o * n) / 8) dma1(SET, lbuf, d0 + (o * n) / 8);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    constexpr int N3 = 8;      // loads of slice kt+2 issued in the last block of slice kt; the other 8 in the first of kt+1
+    // slices kt0 .. kt1-1; on entry fragment set 0 holds sub-step 0 of slice kt0 and the first N3 loads of slice
+    // kt0+1 are in flight; the same holds for kt1 on exit
+    auto steady = [&](int kt0, int kt1) __attribute__((always_inline)) {
+        for (int kt = kt0; kt < kt1; ++kt) {
+            const int cur = kt & 1;
+            select_slice(IC<0>{}, kt + 1);
+            block(IC<0>{}, cur, IC<1>{}, IC<1>{}, IC<0>{}, cur ^ 1, IC<N3>{}, IC<16>{});
+            block(IC<1>{}, cur, IC<2>{}, IC<0>{}, IC<0>{}, 0, IC<0>{}, IC<0>{});
+            block(IC<0>{}, cur, IC<3>{}, IC<1>{}, IC<0>{}, 0, IC<0>{}, IC<0>{});
+            __builtin_amdgcn_s_waitcnt(0x0070);              // vmcnt(0) lgkmcnt(0): the next slice has landed
+            __builtin_amdgcn_s_barrier();
+            __builtin_amdgcn_sched_barrier(0);
+            const int k2 = min(kt + 2, npipe - 1);           // past the end: a re-fetch into the buffer nobody reads
+            select_slice(IC<1>{}, k2);
+            block(IC<1>{}, cur ^ 1, IC<0>{}, IC<0>{}, IC<1>{}, cur, IC<0>{}, IC<N3>{});
+        }
+    };
+    // a slice whose operands are complete in buffer `buf`; FIRST_READ: fragment set 0 not yet read
+    auto multiply_slice = [&](int buf, bool first_read) __attribute__((always_inline)) {
+        if (first_read) {
+#pragma unroll
+            for (int q = 0; q < 8; ++q) frag1(buf, 0, 0, q);
+        }
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            if (kk + 1 < 4) {
+#pragma unroll
+                for (int q = 0; q < 8; ++q) frag1(buf, kk + 1, (kk + 1) & 1, q);
+            }
+#pragma unroll
+            for (int q = 0; q < 16; ++q) mfma1(kk & 1, q);
+        }
+    };
+
+    // ---- sum of squares of the accumulators (fp32 squares four at a time, summed in fp64, fixed order) ----
+    double* red = reinterpret_cast<double*>(smem + 4 * TILE_BYTES);
+    auto evaluate = [&](int phase) __attribute__((always_inline)) {
+        double part = 0.0;
+#pragma clang loop unroll(full)
+        for (int j = 0; j < BB; ++j)
+#pragma clang loop unroll(full)
+            for (int i = 0; i < BA; ++i) {
+                const floatx16 v = acc[i][j];
+#pragma clang loop unroll(full)
+                for (int q = 0; q < 4; ++q) {
+                    float s4 = 0.f;
+#pragma clang loop unroll(full)
+                    for (int u = 0; u < 4; ++u) s4 = fmaf(v[4 * q + u], v[4 * q + u], s4);
+                    part += (double)s4;
+                }
+            }
+        red[tid] = part;
+        __syncthreads();
+        for (int s = NT / 2; s > 0; s >>= 1) {
+            if (tid < s) red[tid] += red[tid + s];
+            __syncthreads();
+        }
+        if (tid == 0) p.partials[(int64_t)phase * p.tiles_m * p.tiles_n + tm * p.tiles_n + tn] = red[0];
+    };
+
+    // ---- the tile -----------------------------------------------------------------------------------
+    tload(IC<0>{}); tload(IC<1>{});
+    if (!T_F32) { tload(IC<2>{}); tload(IC<3>{}); }
+    select_slice(IC<0>{}, 0);
+#pragma unroll
+    for (int q = 0; q < 16; ++q) dma1(IC<0>{}, 0, q);
+    select_slice(IC<1>{}, 1);
+#pragma unroll
+    for (int q = 0; q < N3; ++q) dma1(IC<1>{}, 1, q);
+    tneg(IC<0>{}); tneg(IC<1>{});
+    if (T_F32) { tload(IC<2>{}); tload(IC<3>{}); }
+    tneg(IC<2>{}); tneg(IC<3>{});
+    if (T_F32) __builtin_amdgcn_s_waitcnt(0x0F70);           // the second half of an fp32 target was requested last
+    else __builtin_amdgcn_s_waitcnt(0x0F70 | N3);            // vmcnt(N3): slice 0 has landed
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < 8; ++q) frag1(0, 0, 0, q);
+    steady(0, npipe - 1);
+    __builtin_amdgcn_s_waitcnt(0x0F70);                      // the re-fetches
+    multiply_slice((npipe - 1) & 1, false);                  // last pipelined slice: sub-step 0 is already in set 0
+    __syncthreads();
+    if constexpr (PHASES == 1) {
+        evaluate(0);
+    } else {
+        // both LDS stages are free: the first extension slice of each perturbed evaluation is requested before the
+        // evaluation that precedes it (stage 0 for +eps, stage 1 for -2 eps); further slices (r > 16) one at a time
+        auto ext_dma = [&](const __amdgpu_buffer_rsrc_t& rws, int e, int buf) __attribute__((always_inline)) {
+#pragma unroll
+            for (int q = 0; q < 16; ++q) {
+                const int t = q >> 1;
+                char* dst = smem + buf * (2 * TILE_BYTES) + wave * 1024 + t * 4096 + ((q & 1) ? TILE_BYTES : 0);
+                if (q & 1) __builtin_amdgcn_raw_ptr_buffer_load_lds(rws, (lptr_t)dst, 16, vw2 + t * gs2, e * (BK * 2), 0, 0);
+                else __builtin_amdgcn_raw_ptr_buffer_load_lds(rx2, (lptr_t)dst, 16, vx2 + t * gs2, e * (BK * 2), 0, 0);
+            }
+        };
+        if (next > 0) ext_dma(rw2, 0, 0);
+        evaluate(0);
+        if (next > 0) {
+            ext_dma(rw3, 0, 1);
+            __builtin_amdgcn_s_waitcnt(0x0F70 | 16);         // the +eps slice has landed (the -2 eps one may be in flight)
+            __syncthreads();
+            multiply_slice(0, true);
+            for (int e = 1; e < next; ++e) {
+                __syncthreads();
+                ext_dma(rw2, e, 0);
+                __builtin_amdgcn_s_waitcnt(0x0F70);
+                __syncthreads();
+                multiply_slice(0, true);
+            }
+        }
+        evaluate(1);
+        if (next > 0) {
+            __builtin_amdgcn_s_waitcnt(0x0F70);
+            __syncthreads();
+            multiply_slice(1, true);
+            for (int e = 1; e < next; ++e) {
+                __syncthreads();
+                ext_dma(rw3, e, 1);
+                __builtin_amdgcn_s_waitcnt(0x0F70);
+                __syncthreads();
+                multiply_slice(1, true);
+            }
+        }
+        evaluate(2);
+    }
+    if (p.clk && blockIdx.x == 0 && tid == 0) { p.clk[2] = __builtin_readcyclecounter(); p.clk[3] = wall_clock64(); }
+}
+
+template <bool T_F32, int PHASES>
+static hipError_t launch_mse_variant(const GemmParams& p, hipStream_t st) {
+    static bool attr_set = false;
+    const int smem = 4 * TILE_BYTES + 256 * (int)sizeof(double);
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_bf16_mse_kernel<T_F32, PHASES>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    dim3 grid((unsigned)((int64_t)p.tiles_m * p.tiles_n));
+    hipLaunchKernelGGL((gemm_bf16_mse_kernel<T_F32, PHASES>), grid, dim3(256), smem, st, p);
+    return hipGetLastError();
+}
+
+bool gemm_bf16_mse_supported(const GemmParams& p) {
+    return p.loss_kind == AGZO_LOSS_MSE && p.Y == nullptr && p.vec_ok && p.M % BT == 0 && p.N % BT == 0 &&
+           p.K % BK == 0 && p.K >= 2 * BK && (p.P == nullptr || p.Xext != nullptr) &&
+           (!p.shared || p.Wext2 != nullptr);
+}
+
+hipError_t launch_gemm_bf16_mse(const GemmParams& p, hipStream_t st) {
+    if (!gemm_bf16_mse_supported(p)) return hipErrorInvalidValue;
+    const bool f32 = p.target_dtype != AGZO_BF16;
+    if (p.shared) return f32 ? launch_mse_variant<true, 3>(p, st) : launch_mse_variant<false, 3>(p, st);
+    return f32 ? launch_mse_variant<true, 1>(p, st) : launch_mse_variant<false, 1>(p, st);
+}
+
+}  // namespace agzo

@@ -588,11 +588,16 @@ def test_low_rank_gaussian_step_composed_from_the_calls(ctx, storage):
 
 
 @pytest.mark.parametrize("target_dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("flags", [0, binding.SHARED_FORWARD])
-def test_tile_aligned_shapes_take_the_specialised_loss_epilogues(ctx, target_dtype, flags):
-    """Tokens and outputs multiples of the 256 x 256 tile: the squared-error kernels without bounds checks,
-    against an fp32 and a bf16 target."""
-    n, d_in, d_out, r = 512, 320, 768, 16
+@pytest.mark.parametrize("flags", [0, binding.SHARED_FORWARD, binding.ONE_SIDED, binding.SHARED_FORWARD | binding.ONE_SIDED])
+@pytest.mark.parametrize("n,d_in,d_out,r", [(512, 320, 768, 16),     # five d_in slices, one extension slice
+                                            (256, 128, 512, 40),     # the shortest pipeline (two slices), two extension slices
+                                            (512, 192, 256, 64),     # three extension slices
+                                            (768, 1088, 256, 8),     # 17 slices: odd count, tiles_n = 1
+                                            (512, 264, 768, 16)])    # d_in not a multiple of 64: the general kernel
+def test_tile_aligned_shapes_take_the_specialised_loss_epilogues(ctx, target_dtype, flags, n, d_in, d_out, r):
+    """Tokens and outputs multiples of the 256 x 256 tile: the squared-error kernel whose accumulators start at minus
+    the target (one evaluation per launch, or f0, f+, f- from one pass in shared-forward mode), against an fp32 and a
+    bf16 target."""
     W, X, T, Wd, Xd, Td = problem(61, n, d_in, d_out, "powerlaw", "bf16")
     if target_dtype == "bf16":
         T = synth.to_bf16_values(T)
@@ -606,13 +611,16 @@ def test_tile_aligned_shapes_take_the_specialised_loss_epilogues(ctx, target_dty
     out = torch.zeros(4, dtype=torch.float64, device="cuda")
     ctx.step(L, Wd, Xd, binding.make_loss(Td), 2, EPS, LR, 17, flags, out)
     ctx.check()
-    o = oagzo.agzo_step(W, X, T, r, 2, EPS, LR, 17, storage="bf16")
+    one_sided = bool(flags & binding.ONE_SIDED)
+    o = oagzo.agzo_step(W, X, T, r, 2, EPS, LR, 17, storage="bf16", one_sided=one_sided)
     got = out.cpu().numpy()
     assert abs(got[0] - o["L0"]) < 1e-5 * o["L0"]
     assert abs(got[1] - o["Lp"]) < 1e-5 * o["Lp"]
-    assert abs(got[2] - o["Lm"]) < 1e-5 * o["Lm"]
+    if not one_sided:
+        assert abs(got[2] - o["Lm"]) < 1e-5 * o["Lm"]
     assert abs(got[3] - o["g"]) < 2e-2 * abs(o["g"]) + 1e-9, (got[3], o["g"])
     assert rel(host(Wd), o["W_new"]) < 3e-3
+    assert_increment(host(Wd), W.astype(np.float64), o["W_new"], "bf16")
 
 
 @pytest.mark.parametrize("storage", ["f32", "bf16"])
