@@ -119,8 +119,9 @@ __global__ __launch_bounds__(256) void gemm_bf16_mse_kernel(GemmParams p) {
                     const uint4 t = traw[j >> 1][i][2 * (j & 1) + q];
                     const uint32_t w[4] = {t.x, t.y, t.z, t.w};
 #pragma clang loop unroll(full)
-                    for (int u = 0; u < 4; ++u) {     // widened to fp32 with the sign flipped on the raw bits
-                        v[8 * q + 2 * u] = to_acc(__uint_as_float((w[u] << 16) ^ 0x80000000u));
+                    for (int u = 0; u < 4; ++u) {     // widened to fp32 with the sign flipped on the raw bits (one
+                        // instruction each: adding 2^31 to the shifted word flips its top bit)
+                        v[8 * q + 2 * u] = to_acc(__uint_as_float((w[u] << 16) + 0x80000000u));
                         v[8 * q + 2 * u + 1] = to_acc(__uint_as_float((w[u] & 0xFFFF0000u) ^ 0x80000000u));
                     }
                 }
@@ -214,7 +215,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_mse_kernel(GemmParams p) {
         }
     };
 
-    // ---- sum of squares of the accumulators (fp32 squares four at a time, summed in fp64, fixed order) ----
+    // ---- sum of squares of the accumulators: fp32 squares four at a time, summed in fp64; lanes, then waves, in a
+    // fixed order ----
     double* red = reinterpret_cast<double*>(smem + 4 * TILE_BYTES);
     auto evaluate = [&](int phase) __attribute__((always_inline)) {
         double part = 0.0;
@@ -231,13 +233,13 @@ __global__ __launch_bounds__(256) void gemm_bf16_mse_kernel(GemmParams p) {
                     part += (double)s4;
                 }
             }
-        red[tid] = part;
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) part += __shfl_xor(part, off);
+        if (lane == 0) red[phase * 4 + wave] = part;
         __syncthreads();
-        for (int s = NT / 2; s > 0; s >>= 1) {
-            if (tid < s) red[tid] += red[tid + s];
-            __syncthreads();
-        }
-        if (tid == 0) p.partials[(int64_t)phase * p.tiles_m * p.tiles_n + tm * p.tiles_n + tn] = red[0];
+        if (tid == 0)
+            p.partials[(int64_t)phase * p.tiles_m * p.tiles_n + tm * p.tiles_n + tn] =
+                (red[phase * 4] + red[phase * 4 + 1]) + (red[phase * 4 + 2] + red[phase * 4 + 3]);
     };
 
     // ---- the tile -----------------------------------------------------------------------------------
