@@ -146,6 +146,22 @@ int agzo_qr(agzo_ctx* ctx, const float* S, int64_t d_in, int32_t r, float* Q);
 int agzo_basis(agzo_ctx* ctx, const agzo_layer* L, const void* X, int32_t K, uint64_t seed,
                const float* S0, int32_t flags, float* B);
 
+/* Alg. 1 for n layers at once (Alg. 2, first loop: the base forward computes every layer's basis; the extractions are
+ * independent of each other).  Per item the arguments of agzo_basis; every stage of the algorithm (test matrix,
+ * sketches, orthonormalisations, power steps) is one launch for up to 16 bf16 layers whose ranks round up to the same
+ * multiple of 16, instead of one per layer, which is what a set of small layers is bound by.  Every B is bit-identical
+ * to what agzo_basis gives for the same item.  items: host array, read during the call only; the B of different items
+ * must not overlap.  n = 0 is a no-op.  Errors: AGZO_EINVAL for n < 0, NULL items, or an item agzo_basis would reject
+ * (nothing is enqueued then). */
+typedef struct {
+    agzo_layer layer;   /* d_out, ldw, ldy, y_dtype are not used */
+    const void* X;
+    uint64_t seed;
+    const float* S0;    /* nullable, as for agzo_basis */
+    float* B;           /* [d_in][r] out */
+} agzo_basis_item;
+int agzo_basis_many(agzo_ctx* ctx, const agzo_basis_item* items, int32_t n, int32_t K, int32_t flags);
+
 /* Perturbed forward (f+ / f- of Sec. 4.1, Eq. 7): Y = X W^T + eps_signed (X B) G^T with G [d_out][r]
  * regenerated from (seed, tag 0); W is not modified.  Loss as above. */
 int agzo_perturbed_forward(agzo_ctx* ctx, const agzo_layer* L, const void* W, const void* X,
@@ -217,6 +233,24 @@ int agzo_step(agzo_ctx* ctx, const agzo_layer* L, void* W, const void* X, const 
  * AGZO_NAIVE_INPLACE W is perturbed and restored inside the call.  Errors as agzo_step, AGZO_EINVAL for NULL B_out. */
 int agzo_step_no_update(agzo_ctx* ctx, const agzo_layer* L, void* W, const void* X, const agzo_loss_spec* loss,
                         int32_t K, float eps, uint64_t seed, int32_t flags, double* out_dev, float* B_out);
+
+/* Alg. 2 for n independent single-layer problems in one call (a layer set whose projections each have their own loss
+ * and their own scalar g): every layer's base forward, all bases together (as agzo_basis_many), all projections X B
+ * in one launch, the perturbed forwards, every scalar, and all updates in one batched sweep (as agzo_update_many).
+ * Per item the arguments of agzo_step; out_dev[4] = {L0, L+, L-, g} per item.  B_out != NULL: that item's basis goes
+ * there and its W is left unchanged (as agzo_step_no_update).  Results per item are bit-identical to agzo_step with the
+ * same arguments.  Flags: AGZO_ONE_SIDED, AGZO_INIT_FEATURE, AGZO_SHARED_FORWARD; AGZO_NAIVE_INPLACE is refused.
+ * Errors: AGZO_EINVAL for a bad list or an item agzo_step would reject (nothing is enqueued then). */
+typedef struct {
+    agzo_layer layer;
+    void* W;
+    const void* X;
+    agzo_loss_spec loss;
+    uint64_t seed;
+    double* out_dev;
+    float* B_out;       /* nullable */
+} agzo_step_item;
+int agzo_step_many(agzo_ctx* ctx, const agzo_step_item* items, int32_t n, int32_t K, float eps, float lr, int32_t flags);
 
 #ifdef __cplusplus
 }

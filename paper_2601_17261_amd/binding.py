@@ -27,7 +27,7 @@ PROF_ALL = 63
 EXPORTS = ["agzo_create", "agzo_destroy", "agzo_last_error", "agzo_check", "agzo_profile_enable",
            "agzo_profile_read", "agzo_profile_clock", "agzo_probe_mfma", "agzo_philox_words", "agzo_fill_normal",
            "agzo_layer_forward_sketch", "agzo_qr", "agzo_basis", "agzo_perturbed_forward", "agzo_two_point", "agzo_dense_perturb", "agzo_update", "agzo_update_noalloc",
-           "agzo_update_many", "agzo_step", "agzo_step_no_update"]
+           "agzo_update_many", "agzo_step", "agzo_step_no_update", "agzo_basis_many", "agzo_step_many"]
 
 
 class AgzoLayer(ctypes.Structure):
@@ -47,6 +47,16 @@ class AgzoUpdateItem(ctypes.Structure):
                 ("d_out", ctypes.c_int64), ("d_in", ctypes.c_int64), ("ldw", ctypes.c_int64),
                 ("r", ctypes.c_int32), ("dtype", ctypes.c_int32), ("seed", ctypes.c_uint64),
                 ("lr", ctypes.c_float), ("reserved", ctypes.c_int32)]
+
+
+class AgzoBasisItem(ctypes.Structure):
+    _fields_ = [("layer", AgzoLayer), ("X", ctypes.c_void_p), ("seed", ctypes.c_uint64), ("S0", ctypes.c_void_p),
+                ("B", ctypes.c_void_p)]
+
+
+class AgzoStepItem(ctypes.Structure):
+    _fields_ = [("layer", AgzoLayer), ("W", ctypes.c_void_p), ("X", ctypes.c_void_p), ("loss", AgzoLossSpec),
+                ("seed", ctypes.c_uint64), ("out_dev", ctypes.c_void_p), ("B_out", ctypes.c_void_p)]
 
 
 class AgzoError(RuntimeError):
@@ -91,6 +101,8 @@ def load():
     lib.agzo_update.argtypes = [vp, lp, vp, vp, u64, f32, vp]
     lib.agzo_update_noalloc.argtypes = [vp, lp, vp, vp, u64, f32, vp]
     lib.agzo_update_many.argtypes = [vp, ctypes.POINTER(AgzoUpdateItem), i32]
+    lib.agzo_basis_many.argtypes = [vp, ctypes.POINTER(AgzoBasisItem), i32, i32, i32]
+    lib.agzo_step_many.argtypes = [vp, ctypes.POINTER(AgzoStepItem), i32, i32, f32, f32, i32]
     lib.agzo_step.argtypes = [vp, lp, vp, vp, sp, i32, f32, f32, u64, i32, vp]
     lib.agzo_step_no_update.argtypes = [vp, lp, vp, vp, sp, i32, f32, u64, i32, vp, vp]
     for name in EXPORTS:
@@ -256,6 +268,29 @@ class Context:
 
     def update_many_raw(self, arr, n):
         self._rc(self.lib.agzo_update_many(self.h, arr, n))
+
+    def basis_many(self, items, K, flags=0):
+        """items: sequence of (L, X, seed, S0 or None, B)."""
+        arr = (AgzoBasisItem * max(len(items), 1))()
+        for it, (L, X, seed, S0, B) in zip(arr, items):
+            it.layer, it.X, it.seed = L, X.data_ptr(), seed
+            it.S0, it.B = (0 if S0 is None else S0.data_ptr()), B.data_ptr()
+        self._rc(self.lib.agzo_basis_many(self.h, arr, len(items), K, flags))
+
+    def make_step_items(self, items):
+        """items: sequence of (L, W, X, loss, seed, out_dev, B_out or None) -> ctypes array for step_many_raw (the seeds
+        can be rewritten in place between steps)."""
+        arr = (AgzoStepItem * max(len(items), 1))()
+        for it, (L, W, X, loss, seed, out_dev, B_out) in zip(arr, items):
+            it.layer, it.W, it.X, it.loss, it.seed = L, W.data_ptr(), X.data_ptr(), loss, seed
+            it.out_dev, it.B_out = out_dev.data_ptr(), (0 if B_out is None else B_out.data_ptr())
+        return arr
+
+    def step_many_raw(self, arr, n, K, eps, lr, flags=0):
+        self._rc(self.lib.agzo_step_many(self.h, arr, n, K, eps, lr, flags))
+
+    def step_many(self, items, K, eps, lr, flags=0):
+        self.step_many_raw(self.make_step_items(items), len(items), K, eps, lr, flags)
 
     def step_no_update(self, L, W, X, loss, K, eps, seed, flags, out_dev, B_out):
         self._rc(self.lib.agzo_step_no_update(self.h, ctypes.byref(L), _ptr(W), _ptr(X), ctypes.byref(loss), K, eps,

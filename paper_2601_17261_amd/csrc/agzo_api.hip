@@ -118,7 +118,8 @@ struct Plan {
     size_t part_count;   // doubles in the loss-partials region
 };
 
-Plan make_plan(const agzo_layer& L, bool need_ybuf, bool ce = false, bool shared = false) {
+// base: where this layer's carve-out starts inside the workspace (several layers side by side in the batched calls)
+Plan make_plan(const agzo_layer& L, bool need_ybuf, bool ce = false, bool shared = false, size_t base = 0) {
     Plan p;
     const bool bf = (L.dtype == AGZO_BF16);
     p.rp = round16(L.r);
@@ -126,7 +127,7 @@ Plan make_plan(const agzo_layer& L, bool need_ybuf, bool ce = false, bool shared
     p.nsplit = bf ? xtt_num_splits(L.n_tokens, L.d_in) : 1;
     const int n_gemm = bf ? gemm_bf16_num_workgroups(L.n_tokens, L.d_out, !ce && !shared && L.tiling != AGZO_TILING_LARGE) : epilogue_f32_num_workgroups(L.n_tokens, L.d_out);
     p.n_part = n_gemm;
-    size_t o = 0;
+    size_t o = align_up(base);
     auto take = [&](size_t bytes) { size_t at = o; o += align_up(bytes); return at; };
     p.off_S = take((size_t)L.d_in * L.r * 4);
     p.off_Q = take((size_t)L.d_in * L.r * 4);
@@ -432,6 +433,161 @@ int op_basis(agzo_ctx* ctx, const agzo_layer& L, const Plan& p, const void* X, i
     return 0;
 }
 
+// ---- several layers at once (Alg. 2: the base forward computes every layer's basis before the perturbed passes; the
+// extractions are independent, so every stage of Alg. 1 is one launch for all layers) ----
+struct LayerJob {
+    agzo_layer L;
+    Plan p;
+    const void* X;
+    uint64_t seed;
+    const float* S0;
+    float* B;          // where the basis goes
+};
+
+// one stage for the bf16 jobs idx[0..n): Omega^T planes + range sketch, or T = X Q planes + power sketch
+int stage_sketch_many(agzo_ctx* ctx, const std::vector<LayerJob>& jobs, const int* idx, int n, bool range) {
+    hipStream_t st = ctx->stream;
+    if (range) {
+        FillPackTArgs f[kBatchMax];
+        for (int i = 0; i < n; ++i) {
+            const LayerJob& j = jobs[idx[i]];
+            f[i] = FillPackTArgs{wsh(ctx, j.p.off_TpackT), j.L.n_tokens, j.p.m_pad, j.L.r, j.p.rp, j.seed, AGZO_TAG_OMEGA};
+        }
+        ProfScope ps(ctx, AGZO_PROF_FILL);
+        HIPCHK(launch_fill_normal_packT_many(f, n, st));
+    } else {
+        XqArgs q[kBatchMax];
+        for (int i = 0; i < n; ++i) {
+            const LayerJob& j = jobs[idx[i]];
+            q[i] = XqArgs{static_cast<const bf16_t*>(j.X), j.L.ldx, j.L.n_tokens, j.L.d_in, wsh(ctx, j.p.off_pack), j.L.r, j.p.rp,
+                          nullptr, wsh(ctx, j.p.off_TpackT), j.p.m_pad, wsf(ctx, j.p.off_xqpart)};
+        }
+        ProfScope ps(ctx, AGZO_PROF_XQ);
+        HIPCHK(launch_xq_bf16_many(q, n, st));
+    }
+    XttArgs t[kBatchMax];
+    for (int i = 0; i < n; ++i) {
+        const LayerJob& j = jobs[idx[i]];
+        t[i] = XttArgs{static_cast<const bf16_t*>(j.X), j.L.ldx, j.L.n_tokens, j.L.d_in, wsh(ctx, j.p.off_TpackT), j.p.m_pad, j.p.rp,
+                       wsf(ctx, j.p.off_xtt), j.p.nsplit};
+    }
+    ProfScope ps(ctx, AGZO_PROF_XTT);
+    HIPCHK(launch_xtt_bf16_many(t, n, st));
+    return 0;
+}
+
+// Alg. 1 for every job.  bf16 jobs that share a padded rank go through the batched kernels, at most kBatchMax per
+// launch; the others one by one.  On return every bf16 job's workspace planes hold its basis.
+int basis_many_impl(agzo_ctx* ctx, const std::vector<LayerJob>& jobs, int K, int flags) {
+    std::vector<char> done(jobs.size(), 0);
+    for (size_t a = 0; a < jobs.size(); ++a) {
+        if (done[a]) continue;
+        const LayerJob& ja = jobs[a];
+        if (ja.L.dtype != AGZO_BF16) {
+            TRY(op_basis(ctx, ja.L, ja.p, ja.X, K, ja.seed, ja.S0, flags, ja.B));
+            done[a] = 1;
+            continue;
+        }
+        int idx[kBatchMax], n = 0;
+        for (size_t b = a; b < jobs.size() && n < kBatchMax; ++b)
+            if (!done[b] && jobs[b].L.dtype == AGZO_BF16 && jobs[b].p.rp == ja.p.rp) { idx[n++] = (int)b; done[b] = 1; }
+        // first sketch: the feature-space start (Q0 from the seed, then a power sketch), a given S0, or the range sketch
+        bool given[kBatchMax];
+        int need_idx[kBatchMax], n_need = 0;
+        for (int i = 0; i < n; ++i) {
+            const LayerJob& j = jobs[idx[i]];
+            given[i] = false;
+            if (flags & AGZO_INIT_FEATURE) {
+                HIPCHK(launch_fill_normal(wsf(ctx, j.p.off_Q), j.L.d_in, j.L.r, j.seed, AGZO_TAG_Q0, ctx->stream));
+                HIPCHK(launch_pack_planes(wsf(ctx, j.p.off_Q), j.L.d_in, j.L.r, j.p.rp, wsh(ctx, j.p.off_pack), ctx->stream));
+                need_idx[n_need++] = idx[i];
+            } else if (j.S0) {
+                given[i] = true;
+            } else {
+                need_idx[n_need++] = idx[i];
+            }
+        }
+        if (n_need) TRY(stage_sketch_many(ctx, jobs, need_idx, n_need, !(flags & AGZO_INIT_FEATURE)));
+        for (int k = 0; k <= K; ++k) {
+            QrArgs q[kBatchMax];
+            for (int i = 0; i < n; ++i) {
+                const LayerJob& j = jobs[idx[i]];
+                float* out = (k == K) ? j.B : wsf(ctx, j.p.off_Q);
+                if (k == 0 && given[i])
+                    q[i] = QrArgs{j.S0, nullptr, 0, j.p.rp, nullptr, j.L.d_in, j.L.r, out, wsh(ctx, j.p.off_pack), ctx->ws + j.p.off_qr};
+                else
+                    q[i] = QrArgs{nullptr, wsf(ctx, j.p.off_xtt), j.p.nsplit, j.p.rp, wsf(ctx, j.p.off_S), j.L.d_in, j.L.r, out,
+                                  wsh(ctx, j.p.off_pack), ctx->ws + j.p.off_qr};
+            }
+            {
+                ProfScope ps(ctx, AGZO_PROF_QR);
+                HIPCHK(launch_qr_many(q, n, ctx->flag, k == K, ctx->stream));
+            }
+            if (k < K) TRY(stage_sketch_many(ctx, jobs, idx, n, false));
+        }
+    }
+    return 0;
+}
+
+// P = X B for every bf16 job whose planes hold its basis (one launch per kBatchMax jobs of a padded rank)
+int project_many(agzo_ctx* ctx, const std::vector<LayerJob>& jobs) {
+    std::vector<char> done(jobs.size(), 0);
+    for (size_t a = 0; a < jobs.size(); ++a) {
+        if (done[a]) continue;
+        const LayerJob& ja = jobs[a];
+        if (ja.L.dtype != AGZO_BF16) {
+            TRY(op_project(ctx, ja.L, ja.p, ja.X, ja.B, wsf(ctx, ja.p.off_T), true));
+            done[a] = 1;
+            continue;
+        }
+        XqArgs q[kBatchMax];
+        int n = 0;
+        for (size_t b = a; b < jobs.size() && n < kBatchMax; ++b) {
+            const LayerJob& j = jobs[b];
+            if (done[b] || j.L.dtype != AGZO_BF16 || j.p.rp != ja.p.rp) continue;
+            q[n++] = XqArgs{static_cast<const bf16_t*>(j.X), j.L.ldx, j.L.n_tokens, j.L.d_in, wsh(ctx, j.p.off_pack), j.L.r, j.p.rp,
+                            wsf(ctx, j.p.off_T), nullptr, j.p.m_pad, wsf(ctx, j.p.off_xqpart)};
+            done[b] = 1;
+        }
+        ProfScope ps(ctx, AGZO_PROF_XQ);
+        HIPCHK(launch_xq_bf16_many(q, n, ctx->stream));
+    }
+    return 0;
+}
+
+// checked items, workspace reserved: the factor fragments of all matrices start at workspace offset `off`.
+// fp32 matrices one by one (no workspace); bf16 matrices by padded rank, update_many_max() to a pair of launches
+int update_many_at(agzo_ctx* ctx, const agzo_update_item* items, int n, size_t off) {
+    for (int nk = 0; nk <= (kMaxRank + 15) / 16; ++nk) {
+        std::vector<UpdateDesc> group;
+        size_t group_bytes = 0;
+        auto flush = [&]() -> int {
+            if (group.empty()) return 0;
+            ProfScope ps(ctx, AGZO_PROF_UPDATE);
+            HIPCHK(launch_update_many(group.data(), (int)group.size(), nk, ctx->ws + off, ctx->stream));
+            off += group_bytes;
+            group.clear();
+            group_bytes = 0;
+            return 0;
+        };
+        for (int m = 0; m < n; ++m) {
+            const agzo_update_item& u = items[m];
+            if (nk == 0) {
+                if (u.dtype != AGZO_F32) continue;
+                ProfScope ps(ctx, AGZO_PROF_UPDATE);
+                HIPCHK(launch_update(u.W, u.dtype, u.ldw, u.d_out, u.d_in, u.B, u.r, u.seed, u.lr, u.g_dev, nullptr, ctx->stream));
+                continue;
+            }
+            if (u.dtype != AGZO_BF16 || (u.r + 15) / 16 != nk) continue;
+            group.push_back(UpdateDesc{u.W, u.B, u.g_dev, u.ldw, u.d_out, u.d_in, u.seed, u.lr, u.r});
+            group_bytes += update_workspace_bytes(u.dtype, u.d_out, u.d_in, u.r);
+            if ((int)group.size() == update_many_max()) TRY(flush());
+        }
+        TRY(flush());
+    }
+    return AGZO_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -697,36 +853,7 @@ int agzo_update_many(agzo_ctx* ctx, const agzo_update_item* items, int32_t n) {
         need += update_workspace_bytes(u.dtype, u.d_out, u.d_in, u.r);
     }
     TRY(reserve(ctx, need));
-    // fp32 matrices one by one (no workspace); bf16 matrices by padded rank, update_many_max() to a pair of launches
-    size_t off = 0;
-    for (int nk = 0; nk <= (kMaxRank + 15) / 16; ++nk) {
-        std::vector<UpdateDesc> group;
-        size_t group_bytes = 0;
-        auto flush = [&]() -> int {
-            if (group.empty()) return 0;
-            ProfScope ps(ctx, AGZO_PROF_UPDATE);
-            HIPCHK(launch_update_many(group.data(), (int)group.size(), nk, ctx->ws + off, ctx->stream));
-            off += group_bytes;
-            group.clear();
-            group_bytes = 0;
-            return 0;
-        };
-        for (int m = 0; m < n; ++m) {
-            const agzo_update_item& u = items[m];
-            if (nk == 0) {
-                if (u.dtype != AGZO_F32) continue;
-                ProfScope ps(ctx, AGZO_PROF_UPDATE);
-                HIPCHK(launch_update(u.W, u.dtype, u.ldw, u.d_out, u.d_in, u.B, u.r, u.seed, u.lr, u.g_dev, nullptr, ctx->stream));
-                continue;
-            }
-            if (u.dtype != AGZO_BF16 || (u.r + 15) / 16 != nk) continue;
-            group.push_back(UpdateDesc{u.W, u.B, u.g_dev, u.ldw, u.d_out, u.d_in, u.seed, u.lr, u.r});
-            group_bytes += update_workspace_bytes(u.dtype, u.d_out, u.d_in, u.r);
-            if ((int)group.size() == update_many_max()) TRY(flush());
-        }
-        TRY(flush());
-    }
-    return AGZO_OK;
+    return update_many_at(ctx, items, n, 0);
 }
 
 int agzo_dense_perturb(agzo_ctx* ctx, void* theta, int32_t dtype, int64_t rows, int64_t cols, int64_t ld, uint64_t seed,
@@ -747,6 +874,104 @@ int agzo_two_point(agzo_ctx* ctx, double* out4_dev, float eps, int32_t flags) {
     if (!(eps > 0.f)) return fail(ctx, AGZO_EINVAL, "eps must be positive");
     HIPCHK(launch_two_point(out4_dev, eps, (flags & AGZO_ONE_SIDED) ? 1 : 0, ctx->stream));
     return AGZO_OK;
+}
+
+int agzo_basis_many(agzo_ctx* ctx, const agzo_basis_item* items, int32_t n, int32_t K, int32_t flags) {
+    if (!ctx) return AGZO_EINVAL;
+    if (n < 0 || (n > 0 && !items)) return fail(ctx, AGZO_EINVAL, "bad item list");
+    if (K < 0 || K > 64) return fail(ctx, AGZO_EINVAL, "K=%d outside 0..64", K);
+    std::vector<LayerJob> jobs((size_t)n);
+    size_t total = 0;
+    for (int m = 0; m < n; ++m) {
+        const agzo_basis_item& it = items[m];
+        TRY(check_layer(ctx, &it.layer, false));
+        if (!it.X || !it.B) return fail(ctx, AGZO_EINVAL, "item %d: X or B is NULL", m);
+        TRY(check_operands(ctx, &it.layer, nullptr, it.X));
+        LayerJob& j = jobs[(size_t)m];
+        j.L = it.layer; j.X = it.X; j.seed = it.seed; j.S0 = it.S0; j.B = it.B;
+        j.p = make_plan(j.L, false, false, false, total);
+        total = j.p.total;
+    }
+    TRY(reserve(ctx, total));
+    return basis_many_impl(ctx, jobs, K, flags);
+}
+
+int agzo_step_many(agzo_ctx* ctx, const agzo_step_item* items, int32_t n, int32_t K, float eps, float lr, int32_t flags) {
+    if (!ctx) return AGZO_EINVAL;
+    if (n < 0 || (n > 0 && !items)) return fail(ctx, AGZO_EINVAL, "bad item list");
+    if (K < 0 || K > 64) return fail(ctx, AGZO_EINVAL, "K=%d outside 0..64", K);
+    if (!(eps > 0.f)) return fail(ctx, AGZO_EINVAL, "eps must be positive");
+    if (flags & AGZO_NAIVE_INPLACE) return fail(ctx, AGZO_EINVAL, "the in-place comparator runs layer by layer (agzo_step)");
+    const bool shared = (flags & AGZO_SHARED_FORWARD) != 0, one_sided = (flags & AGZO_ONE_SIDED) != 0;
+    std::vector<LayerJob> jobs((size_t)n);
+    size_t total = 0;
+    for (int m = 0; m < n; ++m) {
+        const agzo_step_item& it = items[m];
+        TRY(check_layer(ctx, &it.layer, true));
+        if (!it.W || !it.X || !it.out_dev) return fail(ctx, AGZO_EINVAL, "item %d: W, X or out_dev is NULL", m);
+        if (it.loss.kind == AGZO_LOSS_NONE) return fail(ctx, AGZO_EINVAL, "item %d: a step needs a loss", m);
+        TRY(check_loss(ctx, &it.layer, &it.loss, it.out_dev));
+        TRY(check_operands(ctx, &it.layer, it.W, it.X));
+        TRY(check_update(ctx, it.W, reinterpret_cast<const float*>(it.X) /* B is the call's own: any non-NULL */, it.layer.dtype, it.layer.d_out, it.layer.d_in, it.layer.ldw, it.layer.r));
+        LayerJob& j = jobs[(size_t)m];
+        j.L = it.layer; j.X = it.X; j.seed = it.seed; j.S0 = nullptr;
+        j.p = make_plan(j.L, j.L.dtype == AGZO_F32, it.loss.kind == AGZO_LOSS_CE, shared, total);
+        total = j.p.total;
+    }
+    size_t upd_bytes = 0;
+    for (int m = 0; m < n; ++m)
+        if (!items[m].B_out) upd_bytes += update_workspace_bytes(items[m].layer.dtype, items[m].layer.d_out, items[m].layer.d_in, items[m].layer.r);
+    TRY(reserve(ctx, total + upd_bytes));
+    for (int m = 0; m < n; ++m) jobs[(size_t)m].B = items[m].B_out ? items[m].B_out : wsf(ctx, jobs[(size_t)m].p.off_B);
+    hipStream_t st = ctx->stream;
+    auto forward = [&](int m, const float* P, float e, double* dst, bool sh, int slot) -> int {
+        const agzo_step_item& it = items[m];
+        const LayerJob& j = jobs[(size_t)m];
+        return op_forward(ctx, j.L, j.p, it.W, it.X, P, e, it.seed, nullptr, &it.loss, dst, sh, slot, it.loss.kind == AGZO_LOSS_MSE);
+    };
+    // Alg. 2, part 1: the base forward of every layer, and every layer's basis from the same activations
+    if (!shared)
+        for (int m = 0; m < n; ++m) TRY(forward(m, nullptr, 0.f, items[m].out_dev, false, 0));
+    TRY(basis_many_impl(ctx, jobs, K, flags & AGZO_INIT_FEATURE));
+    // parts 2-3: the perturbed evaluations
+    TRY(project_many(ctx, jobs));
+    for (int m = 0; m < n; ++m) {
+        const float* P = wsf(ctx, jobs[(size_t)m].p.off_T);
+        if (shared) {
+            TRY(forward(m, P, eps, items[m].out_dev, true, 0));
+        } else {
+            TRY(forward(m, P, +eps, items[m].out_dev + 1, false, 1));
+            if (!one_sided) TRY(forward(m, P, -eps, items[m].out_dev + 2, false, 2));
+        }
+    }
+    // the scalars, then every update in one batched call
+    std::vector<agzo_update_item> upd;
+    for (int m = 0; m < n; ++m) {
+        const agzo_step_item& it = items[m];
+        const LayerJob& j = jobs[(size_t)m];
+        if (it.loss.kind == AGZO_LOSS_MSE)
+            HIPCHK(launch_finish_two_point(reinterpret_cast<const double*>(ctx->ws + j.p.off_part), j.p.n_part,
+                                           1.0 / ((double)j.L.n_tokens * (double)j.L.d_out), (shared || !one_sided) ? 3 : 2,
+                                           it.out_dev, eps, one_sided ? 1 : 0, st));
+        else
+            HIPCHK(launch_two_point(it.out_dev, eps, one_sided ? 1 : 0, st));
+        if (!it.B_out) {
+            agzo_update_item u;
+            u.W = it.W; u.B = j.B; u.g_dev = it.out_dev + 3;
+            u.d_out = j.L.d_out; u.d_in = j.L.d_in; u.ldw = j.L.ldw; u.r = j.L.r; u.dtype = j.L.dtype;
+            u.seed = it.seed; u.lr = lr; u.reserved = 0;
+            upd.push_back(u);
+        }
+    }
+    if (upd.empty()) return AGZO_OK;
+    // the update's factor fragments go behind the layers' carve-outs, which still hold the bases
+    size_t need = 0;
+    for (const agzo_update_item& u : upd) need += update_workspace_bytes(u.dtype, u.d_out, u.d_in, u.r);
+    if (total + need > ctx->ws_bytes) {
+        // (reserve() would move the workspace and with it the bases: sized up front instead)
+        return fail(ctx, AGZO_EHIP, "internal: update scratch was not reserved");
+    }
+    return update_many_at(ctx, upd.data(), (int)upd.size(), total);
 }
 
 // Alg. 2 for one layer.  B_out == NULL: the basis stays in the workspace and the update runs at the end;

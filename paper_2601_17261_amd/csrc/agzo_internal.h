@@ -84,6 +84,30 @@ __device__ __forceinline__ float4 philox_normal4(uint32_t seed_lo, uint32_t seed
 }
 
 // ---------------------------------------------------------------------------
+// Several independent problems in one launch (the extractions of a model's layers, Alg. 2 first loop): the argument
+// sets travel as a kernel argument, a workgroup finds its problem from the running workgroup counts (uniform: a few
+// scalar compares) and then runs exactly the code of the single-problem kernel, so results are bit-identical.
+// ---------------------------------------------------------------------------
+constexpr int kBatchMax = 16;
+template <typename A>
+struct KBatch {
+    int n;
+    uint32_t first[kBatchMax];   // first workgroup of problem m
+    uint32_t gx[kBatchMax];      // its grid width (workgroups along x); y = local / gx
+    A a[kBatchMax];
+};
+// index of the problem that workgroup blockIdx.x belongs to; bx, by: its coordinates inside that problem's grid
+template <typename A>
+__device__ __forceinline__ int kbatch_find(const KBatch<A>& tb, uint32_t& bx, uint32_t& by) {
+    int m = 0;
+    while (m + 1 < tb.n && blockIdx.x >= tb.first[m + 1]) ++m;
+    const uint32_t local = blockIdx.x - tb.first[m];
+    by = local / tb.gx[m];
+    bx = local - by * tb.gx[m];
+    return m;
+}
+
+// ---------------------------------------------------------------------------
 // host-side launch functions (one per source file); all enqueue on `st`
 // ---------------------------------------------------------------------------
 struct GemmLossArgs {
@@ -103,6 +127,10 @@ hipError_t launch_fill_normal(float* dst, int64_t rows, int cols, uint64_t seed,
 // bf16 [3][rp][n_pad] hi/mid/lo planes of Omega^T (rows of Omega are tokens)
 hipError_t launch_fill_normal_packT(bf16_t* dst, int64_t n, int64_t n_pad, int r, int rp, uint64_t seed,
                                     uint32_t tag, hipStream_t st);
+
+struct FillPackTArgs { bf16_t* dst; int64_t n, n_pad; int r, rp; uint64_t seed; uint32_t tag; };
+// the same for up to kBatchMax matrices in one launch
+hipError_t launch_fill_normal_packT_many(const FillPackTArgs* a, int n, hipStream_t st);
 
 // gemm_bf16.hip : Y = X W^T (+ P' G^T), MFMA, fused loss partials
 struct GemmBf16Args {
@@ -147,10 +175,15 @@ hipError_t launch_epilogue_f32(float* Y, int64_t ldy, int64_t M, int64_t N, cons
 size_t xq_part_bytes(int64_t M, int64_t K, int rp);
 hipError_t launch_xq_bf16(const bf16_t* X, int64_t ldx, int64_t M, int64_t K, const bf16_t* Qpack, int r, int rp,
                           float* T, bf16_t* TpackT, int64_t m_pad, float* part, hipStream_t st);
+struct XqArgs { const bf16_t* X; int64_t ldx, M, K; const bf16_t* Qpack; int r, rp; float* T; bf16_t* TpackT; int64_t m_pad; float* part; };
+// up to kBatchMax products with the same rp in one launch (plus one finishing launch if any of them splits d_in)
+hipError_t launch_xq_bf16_many(const XqArgs* a, int n, hipStream_t st);
 int xtt_num_splits(int64_t M, int64_t K);
 // partial[s][d][rp] = sum over token range s of X[t][d] * T[t][k]
 hipError_t launch_xtt_bf16(const bf16_t* X, int64_t ldx, int64_t M, int64_t K, const bf16_t* TpackT, int64_t m_pad,
                            int rp, float* partial, int nsplit, hipStream_t st);
+struct XttArgs { const bf16_t* X; int64_t ldx, M, K; const bf16_t* TpackT; int64_t m_pad; int rp; float* partial; int nsplit; };
+hipError_t launch_xtt_bf16_many(const XttArgs* a, int n, hipStream_t st);
 hipError_t launch_reduce_splits(const float* partial, int nsplit, int64_t d, int rp, int r, float* S, hipStream_t st);
 // Q fp32 [d][r] -> bf16 planes [3][rp][d]
 hipError_t launch_pack_planes(const float* Q, int64_t d, int r, int rp, bf16_t* pack, hipStream_t st);
@@ -161,6 +194,10 @@ size_t qr_workspace_bytes(int64_t d, int r);
 // planes (nullable) bf16 [3][rp][d]; refine = false: single Cholesky pass (for iterates that are sketched again)
 hipError_t launch_qr(const float* S, const float* splits, int nsplit, int rp, float* S_out, int64_t d, int r, float* Q,
                      bf16_t* planes, void* workspace, int* numeric_flag, bool refine, hipStream_t st);
+
+struct QrArgs { const float* S; const float* splits; int nsplit; int rp; float* S_out; int64_t d; int r; float* Q; bf16_t* planes; void* workspace; };
+// up to kBatchMax factorisations with the same rp, each launch of the sequence serving all of them
+hipError_t launch_qr_many(const QrArgs* a, int n, int* numeric_flag, bool refine, hipStream_t st);
 
 // update.hip : W -= (lr * g + shift) * G B^T in place, g = *g_dev (1 if NULL)
 // workspace: update_workspace_bytes() bytes of device scratch (may be NULL when that is 0)

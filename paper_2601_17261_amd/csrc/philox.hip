@@ -42,11 +42,10 @@ __global__ __launch_bounds__(256) void fill_normal_kernel(float* __restrict__ ds
 
 // Omega^T as three bf16 planes [3][rp][n_pad] (hi, mid, lo of each fp32 normal); columns >= r and
 // tokens >= n are zero.  One thread makes one token's four columns.
-__global__ __launch_bounds__(256) void fill_normal_packT_kernel(bf16_t* __restrict__ dst, int64_t n, int64_t n_pad,
-                                                                int r, int rp, uint32_t s_lo, uint32_t s_hi,
-                                                                uint32_t tag) {
-    int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    int quad = blockIdx.y;
+__device__ __forceinline__ void fill_normal_packT_body(bf16_t* __restrict__ dst, int64_t n, int64_t n_pad, int r, int rp,
+                                                       uint32_t s_lo, uint32_t s_hi, uint32_t tag, uint32_t bx, uint32_t by) {
+    int64_t t = (int64_t)bx * 256 + threadIdx.x;
+    int quad = (int)by;
     if (t >= n_pad) return;
     float v[4] = {0.f, 0.f, 0.f, 0.f};
     if (t < n && quad * 4 < r) {
@@ -63,6 +62,18 @@ __global__ __launch_bounds__(256) void fill_normal_packT_kernel(bf16_t* __restri
         dst[((int64_t)1 * rp + k) * n_pad + t] = mid;
         dst[((int64_t)2 * rp + k) * n_pad + t] = lo;
     }
+}
+
+__global__ __launch_bounds__(256) void fill_normal_packT_kernel(bf16_t* __restrict__ dst, int64_t n, int64_t n_pad,
+                                                                int r, int rp, uint32_t s_lo, uint32_t s_hi,
+                                                                uint32_t tag) {
+    fill_normal_packT_body(dst, n, n_pad, r, rp, s_lo, s_hi, tag, blockIdx.x, blockIdx.y);
+}
+
+__global__ __launch_bounds__(256) void fill_normal_packT_many_kernel(const KBatch<FillPackTArgs> tb) {
+    uint32_t bx, by;
+    const FillPackTArgs& a = tb.a[kbatch_find(tb, bx, by)];
+    fill_normal_packT_body(a.dst, a.n, a.n_pad, a.r, a.rp, (uint32_t)a.seed, (uint32_t)(a.seed >> 32), a.tag, bx, by);
 }
 
 hipError_t launch_philox_words(uint32_t* dst, int64_t rows, int cols, uint64_t seed, uint32_t tag, hipStream_t st) {
@@ -92,6 +103,25 @@ hipError_t launch_fill_normal_packT(bf16_t* dst, int64_t n, int64_t n_pad, int r
     dim3 grid((unsigned)((n_pad + 255) / 256), (unsigned)(rp / 4));
     hipLaunchKernelGGL(fill_normal_packT_kernel, grid, dim3(256), 0, st, dst, n, n_pad, r, rp, (uint32_t)seed,
                        (uint32_t)(seed >> 32), tag);
+    return hipGetLastError();
+}
+
+hipError_t launch_fill_normal_packT_many(const FillPackTArgs* a, int n, hipStream_t st) {
+    if (n < 0 || n > kBatchMax) return hipErrorInvalidValue;
+    KBatch<FillPackTArgs> tb;
+    tb.n = 0;
+    uint64_t blocks = 0;
+    for (int m = 0; m < n; ++m) {
+        if (a[m].n_pad == 0) continue;
+        const uint32_t gx = (uint32_t)((a[m].n_pad + 255) / 256);
+        tb.first[tb.n] = (uint32_t)blocks;
+        tb.gx[tb.n] = gx;
+        tb.a[tb.n++] = a[m];
+        blocks += (uint64_t)gx * (uint32_t)(a[m].rp / 4);
+    }
+    if (tb.n == 0) return hipSuccess;
+    if (blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(fill_normal_packT_many_kernel, dim3((unsigned)blocks), dim3(256), 0, st, tb);
     return hipGetLastError();
 }
 

@@ -66,7 +66,7 @@ __device__ int chol_block(double* G, int r, int rp) {
 
 // Gram partial of the block's rows (fp64 in LDS: Ys[row][ld], zero padded to a multiple of 4 rows and rp
 // columns) with the fp64 matrix cores, written to partial[blockIdx.x][rp][rp].
-__device__ void gram_partial(const double* Ys, int ld, int rows_pad, int rp, double* partial) {
+__device__ void gram_partial(const double* Ys, int ld, int rows_pad, int rp, double* partial, uint32_t bx) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int nb = rp / 16;
     // operand lane layout of the 16x16x4 fp64 MFMA: lane l supplies element (l % 16, k = l / 16) of both A (rows =
@@ -85,7 +85,7 @@ __device__ void gram_partial(const double* Ys, int ld, int rows_pad, int rp, dou
 #pragma unroll
         for (int i = 0; i < 4; ++i) quarter[wave][(4 * i + (lane >> 4)) * 16 + (lane & 15)] = acc[i];
         __syncthreads();
-        partial[(int64_t)blockIdx.x * 256 + tid] = (quarter[0][tid] + quarter[1][tid]) + (quarter[2][tid] + quarter[3][tid]);
+        partial[(int64_t)bx * 256 + tid] = (quarter[0][tid] + quarter[1][tid]) + (quarter[2][tid] + quarter[3][tid]);
         return;
     }
     // block pair (bi, bj) of the Gram matrix per wave, round robin
@@ -99,13 +99,13 @@ __device__ void gram_partial(const double* Ys, int ld, int rows_pad, int rp, dou
         }
 #pragma unroll
         for (int i = 0; i < 4; ++i)
-            partial[((int64_t)blockIdx.x * rp + bi * 16 + 4 * i + (lane >> 4)) * rp + bj * 16 + (lane & 15)] = acc[i];
+            partial[((int64_t)bx * rp + bi * 16 + 4 * i + (lane >> 4)) * rp + bj * 16 + (lane & 15)] = acc[i];
     }
 }
 
 // Every block: Gs <- sum over blocks of partial (block order, up to 32 loads in flight), then the workgroup factors
 // it in place (upper factor, reciprocal diagonal).  Block 0 reports a bad pivot.
-__device__ void reduce_and_factor(const double* partial, int nblk, double* Gs, int r, int rp, int* flag) {
+__device__ void reduce_and_factor(const double* partial, int nblk, double* Gs, int r, int rp, int* flag, uint32_t bx) {
     const int tid = threadIdx.x;
     for (int e = tid; e < rp * rp; e += blockDim.x) {
         double sum = 0.0;
@@ -120,7 +120,7 @@ __device__ void reduce_and_factor(const double* partial, int nblk, double* Gs, i
     }
     __syncthreads();
     const int bad = chol_block(Gs, r, rp);
-    if (bad && tid == 0 && blockIdx.x == 0) *flag = 1;
+    if (bad && tid == 0 && bx == 0) *flag = 1;
 }
 
 // the block's input row of this thread, requested before the reduction and factorisation so that its memory latency
@@ -149,14 +149,14 @@ __device__ __forceinline__ void solve_row_t(const Tin (&y)[RP], const double* Rl
 
 // launch 1.  Input: S fp32 [d][r], or (splits != nullptr) partial sketches [nsplit][d][rp] whose sum is
 // stored to S_out as fp32 and used (in its rounded form) for the factorisation.
-__global__ __launch_bounds__(256) void qr_gram_kernel(const float* __restrict__ S, const float* __restrict__ splits,
-                                                      int nsplit, float* __restrict__ S_out, int64_t d, int r, int rp,
-                                                      double* __restrict__ partial) {
+__device__ __forceinline__ void qr_gram_body(const float* __restrict__ S, const float* __restrict__ splits, int nsplit,
+                                             float* __restrict__ S_out, int64_t d, int r, int rp,
+                                             double* __restrict__ partial, uint32_t bx) {
     extern __shared__ __align__(16) double qr_smem[];
     const int ld = rp + 1;
     double* Ys = qr_smem;                 // [QR_ROWS][ld]
     const int tid = threadIdx.x;
-    const int64_t i0 = (int64_t)blockIdx.x * QR_ROWS;
+    const int64_t i0 = (int64_t)bx * QR_ROWS;
     const int rows = (int)min((int64_t)QR_ROWS, d - i0);
     const int rows_pad = (rows + 3) & ~3;
     if (splits != nullptr) {
@@ -208,55 +208,89 @@ __global__ __launch_bounds__(256) void qr_gram_kernel(const float* __restrict__ 
         }
     }
     __syncthreads();
-    gram_partial(Ys, ld, rows_pad, rp, partial);
+    gram_partial(Ys, ld, rows_pad, rp, partial, bx);
+}
+
+__global__ __launch_bounds__(256) void qr_gram_kernel(const float* __restrict__ S, const float* __restrict__ splits,
+                                                      int nsplit, float* __restrict__ S_out, int64_t d, int r, int rp,
+                                                      double* __restrict__ partial) {
+    qr_gram_body(S, splits, nsplit, S_out, d, r, rp, partial, blockIdx.x);
+}
+
+// several factorisations per launch: per problem, what the three launches of one factorisation need
+struct QrDev {
+    const float* S; const float* splits; int nsplit; float* S_out; const float* Sin;
+    int64_t d; int r; int nblk;
+    double *Q1, *partial1, *partial2;
+    float* Q; bf16_t* planes;
+};
+__global__ __launch_bounds__(256) void qr_gram_many_kernel(const KBatch<QrDev> tb, int rp) {
+    uint32_t bx, by;
+    const QrDev& a = tb.a[kbatch_find(tb, bx, by)];
+    qr_gram_body(a.S, a.splits, a.nsplit, a.S_out, a.d, a.r, rp, a.partial1, bx);
 }
 
 // launch 2: R1 from the partials, Q1 = S R1^-1 for the block's rows (fp64, stored), Gram partials of Q1.
 template <int RP>
-__global__ __launch_bounds__(256) void qr_apply_gram_kernel(const float* __restrict__ S, int64_t d, int r,
-                                                            const double* __restrict__ partial1, int nblk,
-                                                            double* __restrict__ Q1, double* __restrict__ partial2,
-                                                            int* flag) {
+__device__ __forceinline__ void qr_apply_gram_body(const float* __restrict__ S, int64_t d, int r,
+                                                   const double* __restrict__ partial1, int nblk,
+                                                   double* __restrict__ Q1, double* __restrict__ partial2, int* flag,
+                                                   uint32_t bx) {
     extern __shared__ __align__(16) double qr_smem[];
     constexpr int rp = RP;
     const int ld = rp + 1;
     double* Ys = qr_smem;
     double* Gs = qr_smem + QR_ROWS * ld;
     const int tid = threadIdx.x;
-    const int64_t i0 = (int64_t)blockIdx.x * QR_ROWS;
+    const int64_t i0 = (int64_t)bx * QR_ROWS;
     const int rows = (int)min((int64_t)QR_ROWS, d - i0);
     const int rows_pad = (rows + 3) & ~3;
     float y[RP];
     load_row_t<RP>(S + (i0 + min(tid, rows - 1)) * r, r, tid < rows, y);
     for (int e = tid; e < rows_pad * ld; e += 256) Ys[e] = 0.0;
-    reduce_and_factor(partial1, nblk, Gs, r, rp, flag);
+    reduce_and_factor(partial1, nblk, Gs, r, rp, flag, bx);
     if (tid < rows) {
         double* q = Ys + tid * ld;
         solve_row_t<RP>(y, Gs, q);
         for (int c = 0; c < r; ++c) Q1[(i0 + tid) * r + c] = q[c];
     }
     __syncthreads();
-    gram_partial(Ys, ld, rows_pad, rp, partial2);
+    gram_partial(Ys, ld, rows_pad, rp, partial2, bx);
+}
+
+template <int RP>
+__global__ __launch_bounds__(256) void qr_apply_gram_kernel(const float* __restrict__ S, int64_t d, int r,
+                                                            const double* __restrict__ partial1, int nblk,
+                                                            double* __restrict__ Q1, double* __restrict__ partial2,
+                                                            int* flag) {
+    qr_apply_gram_body<RP>(S, d, r, partial1, nblk, Q1, partial2, flag, blockIdx.x);
+}
+
+template <int RP>
+__global__ __launch_bounds__(256) void qr_apply_gram_many_kernel(const KBatch<QrDev> tb, int* flag) {
+    uint32_t bx, by;
+    const QrDev& a = tb.a[kbatch_find(tb, bx, by)];
+    qr_apply_gram_body<RP>(a.Sin, a.d, a.r, a.partial1, a.nblk, a.Q1, a.partial2, flag, bx);
 }
 
 // launch 3: Q = Q1 R2^-1, rounded to fp32; planes (nullable) receive the hi/mid/lo bf16 parts [3][rp][d].
 // With Tin = float the same kernel closes a single-pass factorisation: Q = Y R1^-1 straight from launch 1's partials.
 template <int RP, typename Tin>
-__global__ __launch_bounds__(256) void qr_apply_final_kernel(const Tin* __restrict__ Q1, int64_t d, int r,
-                                                             const double* __restrict__ partial2, int nblk,
-                                                             float* __restrict__ Q, bf16_t* __restrict__ planes,
-                                                             int* flag) {
+__device__ __forceinline__ void qr_apply_final_body(const Tin* __restrict__ Q1, int64_t d, int r,
+                                                    const double* __restrict__ partial2, int nblk,
+                                                    float* __restrict__ Q, bf16_t* __restrict__ planes, int* flag,
+                                                    uint32_t bx) {
     extern __shared__ __align__(16) double qr_smem[];
     constexpr int rp = RP;
     const int ld = rp + 1;
     double* Gs = qr_smem;                 // [rp][rp]
     double* Qs = qr_smem + rp * rp;       // [QR_ROWS][ld]
     const int tid = threadIdx.x;
-    const int64_t i0 = (int64_t)blockIdx.x * QR_ROWS;
+    const int64_t i0 = (int64_t)bx * QR_ROWS;
     const int rows = (int)min((int64_t)QR_ROWS, d - i0);
     Tin y[RP];
     load_row_t<RP>(Q1 + (i0 + min(tid, rows - 1)) * r, r, tid < rows, y);
-    reduce_and_factor(partial2, nblk, Gs, r, rp, flag);
+    reduce_and_factor(partial2, nblk, Gs, r, rp, flag, bx);
     if (tid < rows) {
         double* q = Qs + tid * ld;
         solve_row_t<RP>(y, Gs, q);
@@ -275,6 +309,23 @@ __global__ __launch_bounds__(256) void qr_apply_final_kernel(const Tin* __restri
         planes[((int64_t)1 * rp + c) * d + i0 + i] = mid;
         planes[((int64_t)2 * rp + c) * d + i0 + i] = lo;
     }
+}
+
+template <int RP, typename Tin>
+__global__ __launch_bounds__(256) void qr_apply_final_kernel(const Tin* __restrict__ Q1, int64_t d, int r,
+                                                             const double* __restrict__ partial2, int nblk,
+                                                             float* __restrict__ Q, bf16_t* __restrict__ planes,
+                                                             int* flag) {
+    qr_apply_final_body<RP, Tin>(Q1, d, r, partial2, nblk, Q, planes, flag, blockIdx.x);
+}
+
+// DOUBLE_IN: second pass of CholeskyQR2 (input Q1, partials of Q1); otherwise the single-pass form (input Y)
+template <int RP, bool DOUBLE_IN>
+__global__ __launch_bounds__(256) void qr_apply_final_many_kernel(const KBatch<QrDev> tb, int* flag) {
+    uint32_t bx, by;
+    const QrDev& a = tb.a[kbatch_find(tb, bx, by)];
+    if constexpr (DOUBLE_IN) qr_apply_final_body<RP, double>(a.Q1, a.d, a.r, a.partial2, a.nblk, a.Q, a.planes, flag, bx);
+    else qr_apply_final_body<RP, float>(a.Sin, a.d, a.r, a.partial1, a.nblk, a.Q, a.planes, flag, bx);
 }
 
 // the launches after the first, for one padded rank (the rows' registers are sized by it)
@@ -337,6 +388,80 @@ hipError_t launch_qr(const float* S, const float* splits, int nsplit, int rp, fl
         case 32: return launch_apply<32>(grid, sm_full, st, Sin, d, r, partial1, partial2, nblk, Q1, Q, planes, numeric_flag, refine);
         case 48: return launch_apply<48>(grid, sm_full, st, Sin, d, r, partial1, partial2, nblk, Q1, Q, planes, numeric_flag, refine);
         case 64: return launch_apply<64>(grid, sm_full, st, Sin, d, r, partial1, partial2, nblk, Q1, Q, planes, numeric_flag, refine);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+template <int RP>
+static hipError_t launch_apply_many(const KBatch<QrDev>& tb, unsigned blocks, size_t smem, int* flag, bool refine, hipStream_t st) {
+    static bool attr_set = false;
+    if (!attr_set) {
+        const int big = (QR_ROWS * (kMaxRank + 1) + kMaxRank * kMaxRank) * (int)sizeof(double);
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(qr_apply_gram_many_kernel<RP>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, big);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(qr_apply_final_many_kernel<RP, true>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, big);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(qr_apply_final_many_kernel<RP, false>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, big);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const dim3 grid(blocks), block(256);
+    if (!refine) {
+        hipLaunchKernelGGL((qr_apply_final_many_kernel<RP, false>), grid, block, smem, st, tb, flag);
+        return hipGetLastError();
+    }
+    hipLaunchKernelGGL(qr_apply_gram_many_kernel<RP>, grid, block, smem, st, tb, flag);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((qr_apply_final_many_kernel<RP, true>), grid, block, smem, st, tb, flag);
+    return hipGetLastError();
+}
+
+hipError_t launch_qr_many(const QrArgs* a, int n, int* numeric_flag, bool refine, hipStream_t st) {
+    if (n < 0 || n > kBatchMax) return hipErrorInvalidValue;
+    KBatch<QrDev> tb;
+    tb.n = 0;
+    uint64_t blocks = 0;
+    int rp = 0;
+    for (int m = 0; m < n; ++m) {
+        if (a[m].d == 0) continue;
+        if (rp == 0) rp = a[m].rp;
+        if (a[m].rp != rp) return hipErrorInvalidValue;       // one padded rank per launch
+        QrDev q;
+        q.S = a[m].S; q.splits = a[m].splits; q.nsplit = a[m].nsplit; q.S_out = a[m].S_out;
+        q.Sin = a[m].splits ? a[m].S_out : a[m].S;
+        q.d = a[m].d; q.r = a[m].r; q.nblk = (int)qr_blocks(a[m].d);
+        q.Q1 = reinterpret_cast<double*>(a[m].workspace);
+        q.partial1 = q.Q1 + a[m].d * a[m].r;
+        q.partial2 = q.partial1 + (size_t)q.nblk * rp * rp;
+        q.Q = a[m].Q; q.planes = a[m].planes;
+        tb.first[tb.n] = (uint32_t)blocks; tb.gx[tb.n] = (uint32_t)q.nblk; tb.a[tb.n++] = q;
+        blocks += (uint64_t)q.nblk;
+    }
+    if (tb.n == 0) return hipSuccess;
+    if (blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    const size_t sm_full = ((size_t)QR_ROWS * (rp + 1) + (size_t)rp * rp) * sizeof(double);
+    static bool attr_set = false;
+    if (!attr_set) {
+        const int big = (QR_ROWS * (kMaxRank + 1) + kMaxRank * kMaxRank) * (int)sizeof(double);
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(qr_gram_many_kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, big);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(qr_gram_many_kernel, dim3((unsigned)blocks), dim3(256), sm_full, st, tb, rp);
+    {
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    switch (rp) {
+        case 16: return launch_apply_many<16>(tb, (unsigned)blocks, sm_full, numeric_flag, refine, st);
+        case 32: return launch_apply_many<32>(tb, (unsigned)blocks, sm_full, numeric_flag, refine, st);
+        case 48: return launch_apply_many<48>(tb, (unsigned)blocks, sm_full, numeric_flag, refine, st);
+        case 64: return launch_apply_many<64>(tb, (unsigned)blocks, sm_full, numeric_flag, refine, st);
         default: return hipErrorInvalidValue;
     }
 }

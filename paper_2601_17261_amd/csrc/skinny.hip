@@ -46,10 +46,12 @@ __device__ __forceinline__ void wait_vmcnt_dyn(int n) {
     }
 }
 
+// bx: token block, by / ny: this workgroup's share of d_in (ny = 1: all of it)
 template <int NB>
-__global__ __launch_bounds__(256) void xq_bf16_kernel(const bf16_t* __restrict__ X, int64_t ldx, int64_t M, int64_t K,
-                                                      const bf16_t* __restrict__ Qpack, int r, float* __restrict__ T,
-                                                      bf16_t* __restrict__ TpackT, int64_t m_pad, float* __restrict__ part) {
+__device__ __forceinline__ void xq_bf16_body(const bf16_t* __restrict__ X, int64_t ldx, int64_t M, int64_t K,
+                                             const bf16_t* __restrict__ Qpack, int r, float* __restrict__ T,
+                                             bf16_t* __restrict__ TpackT, int64_t m_pad, float* __restrict__ part,
+                                             uint32_t bx, uint32_t by, uint32_t ny) {
     constexpr int RP = NB * 16;
     constexpr int QROWS = 3 * RP;                          // plane rows: (plane, k)
     constexpr int NGROUP = XQ_TOK / 8 + QROWS / 8;         // 8-row groups per slice: X first, then the planes
@@ -61,7 +63,7 @@ __global__ __launch_bounds__(256) void xq_bf16_kernel(const bf16_t* __restrict__
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lm = lane & 15, lg = lane >> 4;
-    const int64_t t0 = (int64_t)blockIdx.x * XQ_TOK;
+    const int64_t t0 = (int64_t)bx * XQ_TOK;
 
     floatx4 acc[NB];
 #pragma unroll
@@ -81,7 +83,7 @@ __global__ __launch_bounds__(256) void xq_bf16_kernel(const bf16_t* __restrict__
     }
     // few tokens: gridDim.y workgroups share a token block, each taking a contiguous run of d_in slices, and leave
     // partial sums in `part` for xq_finish_kernel (a single workgroup per block would walk d_in alone, bound by latency)
-    const int nsplit = (int)gridDim.y, split = (int)blockIdx.y;
+    const int nsplit = (int)ny, split = (int)by;
     const int nfull_all = (int)(K / XQ_BK);
     const int kbeg = (int)((int64_t)nfull_all * split / nsplit);
     const int nfull = (int)((int64_t)nfull_all * (split + 1) / nsplit) - kbeg;      // this workgroup's slices
@@ -204,11 +206,32 @@ __global__ __launch_bounds__(256) void xq_bf16_kernel(const bf16_t* __restrict__
     }
 }
 
+template <int NB>
+__global__ __launch_bounds__(256) void xq_bf16_kernel(const bf16_t* __restrict__ X, int64_t ldx, int64_t M, int64_t K,
+                                                      const bf16_t* __restrict__ Qpack, int r, float* __restrict__ T,
+                                                      bf16_t* __restrict__ TpackT, int64_t m_pad, float* __restrict__ part) {
+    xq_bf16_body<NB>(X, ldx, M, K, Qpack, r, T, TpackT, m_pad, part, blockIdx.x, blockIdx.y, gridDim.y);
+}
+
+// several products per launch (the layers of a model): what one launch of the kernel above needs, per product
+struct XqDev {
+    const bf16_t* X; int64_t ldx, M, K;
+    const bf16_t* Qpack; int r;
+    float* T; bf16_t* TpackT; int64_t m_pad; float* part;   // part: NULL unless ns > 1
+    int ns; int64_t rows;
+};
+template <int NB>
+__global__ __launch_bounds__(256) void xq_bf16_many_kernel(const KBatch<XqDev> tb) {
+    uint32_t bx, by;
+    const XqDev& a = tb.a[kbatch_find(tb, bx, by)];
+    xq_bf16_body<NB>(a.X, a.ldx, a.M, a.K, a.Qpack, a.r, a.T, a.TpackT, a.m_pad, a.part, bx, by, (uint32_t)a.ns);
+}
+
 // sums the d_in splits of xq in fixed order and writes what the unsplit kernel's epilogue writes; one thread per (t, k)
-__global__ __launch_bounds__(256) void xq_finish_kernel(const float* __restrict__ part, int nsplit, int64_t rows, int64_t M,
-                                                        int64_t m_pad, int r, int rp, float* __restrict__ T,
-                                                        bf16_t* __restrict__ TpackT) {
-    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+__device__ __forceinline__ void xq_finish_body(const float* __restrict__ part, int nsplit, int64_t rows, int64_t M,
+                                               int64_t m_pad, int r, int rp, float* __restrict__ T,
+                                               bf16_t* __restrict__ TpackT, uint32_t bx) {
+    const int64_t idx = (int64_t)bx * 256 + threadIdx.x;
     if (idx >= rows * rp) return;
     const int64_t t = idx / rp;
     const int k = (int)(idx - t * rp);
@@ -223,6 +246,18 @@ __global__ __launch_bounds__(256) void xq_finish_kernel(const float* __restrict_
         TpackT[((int64_t)1 * rp + k) * m_pad + t] = mid;
         TpackT[((int64_t)2 * rp + k) * m_pad + t] = lo;
     }
+}
+
+__global__ __launch_bounds__(256) void xq_finish_kernel(const float* __restrict__ part, int nsplit, int64_t rows, int64_t M,
+                                                        int64_t m_pad, int r, int rp, float* __restrict__ T,
+                                                        bf16_t* __restrict__ TpackT) {
+    xq_finish_body(part, nsplit, rows, M, m_pad, r, rp, T, TpackT, blockIdx.x);
+}
+
+__global__ __launch_bounds__(256) void xq_finish_many_kernel(const KBatch<XqDev> tb, int rp) {
+    uint32_t bx, by;
+    const XqDev& a = tb.a[kbatch_find(tb, bx, by)];
+    xq_finish_body(a.part, a.ns, a.rows, a.M, a.m_pad, a.r, rp, a.T, a.TpackT, bx);
 }
 
 // number of d_in splits for M tokens (1 = the token blocks alone fill the chip, or d_in is too short to share)
@@ -255,6 +290,61 @@ static hipError_t launch_xq_nb(dim3 grid, hipStream_t st, const bf16_t* X, int64
         set = true;
     }
     hipLaunchKernelGGL(xq_bf16_kernel<NB>, grid, dim3(256), smem, st, X, ldx, M, K, Qpack, r, T, TpackT, m_pad, part);
+    return hipGetLastError();
+}
+
+template <int NB>
+static hipError_t launch_xq_many_nb(const KBatch<XqDev>& tb, unsigned blocks, hipStream_t st) {
+    constexpr int stages = (NB == 1) ? 8 : (NB == 2) ? 6 : 4;
+    const int smem = stages * (XQ_TOK + 3 * NB * 16) * 128;
+    static bool set = false;
+    if (!set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(xq_bf16_many_kernel<NB>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+        if (e != hipSuccess) return e;
+        set = true;
+    }
+    hipLaunchKernelGGL(xq_bf16_many_kernel<NB>, dim3(blocks), dim3(256), smem, st, tb);
+    return hipGetLastError();
+}
+
+hipError_t launch_xq_bf16_many(const XqArgs* a, int n, hipStream_t st) {
+    if (n < 0 || n > kBatchMax) return hipErrorInvalidValue;
+    KBatch<XqDev> tb, fin;
+    tb.n = fin.n = 0;
+    uint64_t blocks = 0, fin_blocks = 0;
+    int rp = 0;
+    for (int m = 0; m < n; ++m) {
+        if (a[m].M == 0) continue;
+        if (rp == 0) rp = a[m].rp;
+        if (a[m].rp != rp) return hipErrorInvalidValue;       // one padded rank per launch
+        XqDev d;
+        d.X = a[m].X; d.ldx = a[m].ldx; d.M = a[m].M; d.K = a[m].K; d.Qpack = a[m].Qpack; d.r = a[m].r;
+        d.T = a[m].T; d.TpackT = a[m].TpackT; d.m_pad = a[m].m_pad;
+        d.rows = a[m].TpackT ? a[m].m_pad : a[m].M;
+        d.ns = a[m].part ? xq_splits(a[m].m_pad, a[m].K) : 1;
+        d.part = d.ns > 1 ? a[m].part : nullptr;
+        const uint32_t gx = (uint32_t)((d.rows + XQ_TOK - 1) / XQ_TOK);
+        tb.first[tb.n] = (uint32_t)blocks; tb.gx[tb.n] = gx; tb.a[tb.n++] = d;
+        blocks += (uint64_t)gx * (uint32_t)d.ns;
+        if (d.ns > 1) {
+            const uint32_t fx = (uint32_t)((d.rows * rp + 255) / 256);
+            fin.first[fin.n] = (uint32_t)fin_blocks; fin.gx[fin.n] = fx; fin.a[fin.n++] = d;
+            fin_blocks += fx;
+        }
+    }
+    if (tb.n == 0) return hipSuccess;
+    if (blocks > 0x7FFFFFFFull || fin_blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    hipError_t e;
+    switch (rp / 16) {
+        case 1: e = launch_xq_many_nb<1>(tb, (unsigned)blocks, st); break;
+        case 2: e = launch_xq_many_nb<2>(tb, (unsigned)blocks, st); break;
+        case 3: e = launch_xq_many_nb<3>(tb, (unsigned)blocks, st); break;
+        case 4: e = launch_xq_many_nb<4>(tb, (unsigned)blocks, st); break;
+        default: return hipErrorInvalidValue;
+    }
+    if (e != hipSuccess || fin.n == 0) return e;
+    hipLaunchKernelGGL(xq_finish_many_kernel, dim3((unsigned)fin_blocks), dim3(256), 0, st, fin, rp);
     return hipGetLastError();
 }
 
@@ -305,16 +395,17 @@ int xtt_num_splits(int64_t M, int64_t K) {
     return (int)want;
 }
 
+// bx: panel of features, by: token range
 template <int NB>
-__global__ __launch_bounds__(256) void xtt_bf16_kernel(const bf16_t* __restrict__ X, int64_t ldx, int64_t M, int64_t K,
-                                                       const bf16_t* __restrict__ TpackT, int64_t m_pad,
-                                                       float* __restrict__ partial, int64_t tok_per_split) {
+__device__ __forceinline__ void xtt_bf16_body(const bf16_t* __restrict__ X, int64_t ldx, int64_t M, int64_t K,
+                                              const bf16_t* __restrict__ TpackT, int64_t m_pad,
+                                              float* __restrict__ partial, int64_t tok_per_split, uint32_t bx, uint32_t by) {
     constexpr int RP = NB * 16;
     extern __shared__ __align__(16) float sbuf[];   // [XTT_PANEL][RP]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int lc = lane & 15, lg = lane >> 4;
-    const int64_t db = (int64_t)blockIdx.x * XTT_PANEL;
-    const int split = blockIdx.y;
+    const int64_t db = (int64_t)bx * XTT_PANEL;
+    const int split = (int)by;
     const int64_t ts = (int64_t)split * tok_per_split;
     const int64_t te = min(ts + tok_per_split, m_pad);
 
@@ -397,11 +488,65 @@ __global__ __launch_bounds__(256) void xtt_bf16_kernel(const bf16_t* __restrict_
         if (idx < nvalid) out[idx] = sbuf[idx];
 }
 
+template <int NB>
+__global__ __launch_bounds__(256) void xtt_bf16_kernel(const bf16_t* __restrict__ X, int64_t ldx, int64_t M, int64_t K,
+                                                       const bf16_t* __restrict__ TpackT, int64_t m_pad,
+                                                       float* __restrict__ partial, int64_t tok_per_split) {
+    xtt_bf16_body<NB>(X, ldx, M, K, TpackT, m_pad, partial, tok_per_split, blockIdx.x, blockIdx.y);
+}
+
+struct XttDev {
+    const bf16_t* X; int64_t ldx, M, K;
+    const bf16_t* TpackT; int64_t m_pad;
+    float* partial; int64_t tok_per_split;
+};
+template <int NB>
+__global__ __launch_bounds__(256) void xtt_bf16_many_kernel(const KBatch<XttDev> tb) {
+    uint32_t bx, by;
+    const XttDev& a = tb.a[kbatch_find(tb, bx, by)];
+    xtt_bf16_body<NB>(a.X, a.ldx, a.M, a.K, a.TpackT, a.m_pad, a.partial, a.tok_per_split, bx, by);
+}
+
+static int64_t xtt_tokens_per_split(int64_t m_pad, int nsplit) {
+    const int64_t t = (m_pad + nsplit - 1) / nsplit;
+    return (t + 4 * XTT_STEP - 1) / (4 * XTT_STEP) * (4 * XTT_STEP);
+}
+
+hipError_t launch_xtt_bf16_many(const XttArgs* a, int n, hipStream_t st) {
+    if (n < 0 || n > kBatchMax) return hipErrorInvalidValue;
+    KBatch<XttDev> tb;
+    tb.n = 0;
+    uint64_t blocks = 0;
+    int rp = 0;
+    for (int m = 0; m < n; ++m) {
+        if (a[m].M == 0 || a[m].K == 0) continue;
+        if (rp == 0) rp = a[m].rp;
+        if (a[m].rp != rp || a[m].nsplit < 1) return hipErrorInvalidValue;
+        XttDev d;
+        d.X = a[m].X; d.ldx = a[m].ldx; d.M = a[m].M; d.K = a[m].K; d.TpackT = a[m].TpackT; d.m_pad = a[m].m_pad;
+        d.partial = a[m].partial; d.tok_per_split = xtt_tokens_per_split(a[m].m_pad, a[m].nsplit);
+        const uint32_t gx = (uint32_t)((a[m].K + XTT_PANEL - 1) / XTT_PANEL);
+        tb.first[tb.n] = (uint32_t)blocks; tb.gx[tb.n] = gx; tb.a[tb.n++] = d;
+        blocks += (uint64_t)gx * (uint32_t)a[m].nsplit;
+    }
+    if (tb.n == 0) return hipSuccess;
+    if (blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    const size_t smem = (size_t)XTT_PANEL * rp * sizeof(float);
+    const dim3 grid((unsigned)blocks);
+    switch (rp / 16) {
+        case 1: hipLaunchKernelGGL(xtt_bf16_many_kernel<1>, grid, dim3(256), smem, st, tb); break;
+        case 2: hipLaunchKernelGGL(xtt_bf16_many_kernel<2>, grid, dim3(256), smem, st, tb); break;
+        case 3: hipLaunchKernelGGL(xtt_bf16_many_kernel<3>, grid, dim3(256), smem, st, tb); break;
+        case 4: hipLaunchKernelGGL(xtt_bf16_many_kernel<4>, grid, dim3(256), smem, st, tb); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
 hipError_t launch_xtt_bf16(const bf16_t* X, int64_t ldx, int64_t M, int64_t K, const bf16_t* TpackT, int64_t m_pad,
                            int rp, float* partial, int nsplit, hipStream_t st) {
     if (M == 0 || K == 0) return hipSuccess;
-    int64_t tok_per_split = (m_pad + nsplit - 1) / nsplit;
-    tok_per_split = (tok_per_split + 4 * XTT_STEP - 1) / (4 * XTT_STEP) * (4 * XTT_STEP);
+    const int64_t tok_per_split = xtt_tokens_per_split(m_pad, nsplit);
     dim3 grid((unsigned)((K + XTT_PANEL - 1) / XTT_PANEL), (unsigned)nsplit);
     const size_t smem = (size_t)XTT_PANEL * rp * sizeof(float);
     switch (rp / 16) {

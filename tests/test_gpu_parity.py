@@ -412,6 +412,103 @@ def test_step_without_update_then_update_many_equals_step(ctx, storage, n, d_in,
     assert e.value.code == binding.EINVAL
 
 
+# ---------------------------------------------------------------------------------------------
+# several layers per call: every stage of Alg. 1 (and of the step around it) is one launch for all of them
+# ---------------------------------------------------------------------------------------------
+MANY_LAYERS = [
+    # storage, n, d_in, d_out, r, kind
+    ("bf16", 600, 1024, 520, 16, "rmsnorm"),
+    ("bf16", 300, 200, 264, 8, "lowrank"),       # same padded rank as the first: shares its launches
+    ("bf16", 700, 320, 264, 40, "powerlaw"),     # another padded rank: launches of its own
+    ("bf16", 200, 4136, 72, 16, "rmsnorm"),      # X Q splits d_in here
+    ("bf16", 512, 320, 768, 16, "powerlaw"),     # tile-aligned
+    ("f32", 300, 100, 70, 4, "lowrank"),         # fp32 storage: runs layer by layer inside the call
+]
+
+
+def test_basis_many_is_bit_identical_to_basis(ctx):
+    items, want = [], []
+    for li, (storage, n, d_in, d_out, r, kind) in enumerate(MANY_LAYERS):
+        W, X, T, Wd, Xd, Td = problem(40 + li, n, d_in, d_out, kind, storage)
+        L = binding.make_layer(Wd, Xd, r)
+        S0 = None
+        if li == 1:                                # one item brings its first sketch along
+            S0 = torch.empty(d_in, r, dtype=torch.float32, device="cuda")
+            ctx.layer_forward_sketch(L, None, Xd, None, binding.SKETCH_RANGE, None, 900 + li, S0, None, None)
+        B1 = torch.empty(d_in, r, dtype=torch.float32, device="cuda")
+        ctx.basis(L, Xd, 3, 900 + li, S0, 0, B1)
+        want.append(B1)
+        items.append((L, Xd, 900 + li, S0, torch.zeros(d_in, r, dtype=torch.float32, device="cuda")))
+    ctx.basis_many(items, 3)
+    ctx.check()
+    for li, (it, B1) in enumerate(zip(items, want)):
+        assert torch.equal(it[4], B1), li
+    # the feature-space start, and K = 0
+    for K, flags in ((2, binding.INIT_FEATURE), (0, 0)):
+        for it in items:
+            it[4].zero_()
+        ctx.basis_many([(L, Xd, seed, None, B) for (L, Xd, seed, _, B) in items], K, flags)
+        for li, (L, Xd, seed, _, B) in enumerate(items):
+            B1 = torch.empty_like(B)
+            ctx.basis(L, Xd, K, seed, None, flags, B1)
+            assert torch.equal(B, B1), (K, flags, li)
+    ctx.basis_many([], 3)
+    ctx.check()
+
+
+def test_basis_many_more_layers_than_one_launch_holds(ctx):
+    rng = np.random.default_rng(5)
+    items, want = [], []
+    for li in range(19):
+        n, d_in, r = int(rng.integers(40, 300)), 8 * int(rng.integers(4, 40)), int(rng.integers(1, 17))
+        X = dev(synth.x_rmsnorm_gaussian(rng, n, d_in, storage="bf16"), "bf16")
+        L = binding.make_layer(None, X, r, d_out=8)
+        B1 = torch.empty(d_in, r, dtype=torch.float32, device="cuda")
+        ctx.basis(L, X, 2, 70 + li, None, 0, B1)
+        want.append(B1)
+        items.append((L, X, 70 + li, None, torch.zeros_like(B1)))
+    ctx.basis_many(items, 2)
+    ctx.check()
+    for li, (it, B1) in enumerate(zip(items, want)):
+        assert torch.equal(it[4], B1), li
+
+
+@pytest.mark.parametrize("flags", [0, binding.ONE_SIDED, binding.SHARED_FORWARD, binding.INIT_FEATURE])
+def test_step_many_is_bit_identical_to_steps(ctx, flags):
+    probs = []
+    for li, (storage, n, d_in, d_out, r, kind) in enumerate(MANY_LAYERS):
+        W, X, T, Wd, Xd, Td = problem(60 + li, n, d_in, d_out, kind, storage)
+        if li == 4:
+            Td = dev(synth.to_bf16_values(T), "bf16")      # bf16 target on the tile-aligned layer
+        probs.append((binding.make_layer(Wd, Xd, r), Wd, Xd, Td))
+    outs = torch.zeros(len(probs), 4, dtype=torch.float64, device="cuda")
+    Wm = [Wd.clone() for _, Wd, _, _ in probs]
+    losses = [binding.make_loss(Td) for _, _, _, Td in probs]
+    ctx.step_many([(L, Wm[li], Xd, losses[li], 300 + li, outs[li], None) for li, (L, _, Xd, _) in enumerate(probs)],
+                  3, EPS, LR, flags)
+    ctx.check()
+    for li, (L, Wd, Xd, Td) in enumerate(probs):
+        W1 = Wd.clone()
+        out1 = torch.zeros(4, dtype=torch.float64, device="cuda")
+        ctx.step(L, W1, Xd, losses[li], 3, EPS, LR, 300 + li, flags, out1)
+        ctx.check()
+        assert torch.equal(out1, outs[li]), (li, out1, outs[li])
+        assert torch.equal(W1.view(torch.int16 if W1.dtype == torch.bfloat16 else torch.int32),
+                           Wm[li].view(torch.int16 if W1.dtype == torch.bfloat16 else torch.int32)), li
+        assert not torch.equal(W1, Wd), li
+    # with B_out the item's W stays as it was and its basis is handed out
+    Bo = torch.zeros(probs[0][2].shape[1], probs[0][0].r, dtype=torch.float32, device="cuda")
+    W0 = probs[0][1].clone()
+    ctx.step_many([(probs[0][0], W0, probs[0][2], losses[0], 300, outs[0], Bo)], 3, EPS, LR, flags)
+    B1 = torch.empty_like(Bo)
+    ctx.basis(probs[0][0], probs[0][2], 3, 300, None, flags & binding.INIT_FEATURE, B1)
+    assert torch.equal(W0, probs[0][1]) and torch.equal(Bo, B1)
+    with pytest.raises(binding.AgzoError) as e:
+        ctx.step_many([(probs[0][0], W0, probs[0][2], losses[0], 300, outs[0], None)], 3, EPS, LR, binding.NAIVE_INPLACE)
+    assert e.value.code == binding.EINVAL
+    ctx.check()
+
+
 @pytest.mark.parametrize("storage,n,d_in,d_out,r,kind", [
     ("f32", 512, 256, 256, 4, "lowrank"),
     ("bf16", 515, 136, 300, 8, "lowrank"),
