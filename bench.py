@@ -74,10 +74,120 @@ def cpu_baseline(n_tokens, r, K, eps, lr, shapes, budget_s=25.0):
         del W, X, T
     scale = total_flops / done_flops
     return {"value": 1.0 / (spent * scale), "unit": "steps/s", "cores": int(cores), "kind": "oracle",
-            "sample": "one oracle step each of the projections %s (N=%d, r=%d, K=%d) took %.1f s; %s" % (
+            "sample": "one oracle step each of the projections %s (N=%d, r=%d, K=%d) took %.1f s; %s; inputs of the CPU leg: "
+                      "iid N(0,1) activations rounded to bf16, W ~ N(0, 0.02^2), target = X W^T (every loss is 0: the "
+                      "oracle's time does not depend on the values, so the GPU leg's power-law activations are not "
+                      "regenerated on the host)" % (
                 ",".join(done), n_tokens, r, K, spent,
                 "that is the whole layer set" if len(done) == len(shapes) else
                 "scaled to the whole layer set by forward-flop ratio %.2f" % scale)}
+
+
+class MlpStack:
+    """Alg. 2 over a model: the residual stack of gated-MLP blocks with an LM head (hidden 2048, intermediate 6144,
+    vocabulary 32000), all linear layers perturbed at once, one global g.  Every linear-layer operation is a library
+    call; the glue between layers (embedding lookup, RMS normalisation, SiLU gate, residual sum: not steps of the
+    method) is the library's single-pass kernels (agzo_glue_*: fp32 arithmetic, one rounding to bf16) and a torch
+    gather for the embedding.  The base pass keeps every layer's input (a few GB), so that all 85 extractions run as
+    one batched call."""
+
+    def __init__(self, ctx, params, ids, r, K):
+        self.ctx, self.r, self.K = ctx, r, K
+        self.nb = params["n_blocks"]
+        self.names = []
+        for b in range(self.nb):
+            self.names += [("gate", b), ("up", b), ("down", b)]
+        self.names.append(("head", 0))
+        self.W = {nm: params[nm] for nm in self.names}
+        self.E = params["E"]
+        self.ids = ids.reshape(-1)
+        tgt = torch.full(ids.shape, -1, dtype=torch.int32, device=ids.device)
+        tgt[:, :-1] = ids[:, 1:].to(torch.int32)
+        self.tgt = tgt.reshape(-1).contiguous()
+        self.loss = binding.make_loss(self.tgt, kind=binding.LOSS_CE)
+        n = self.ids.numel()
+        self.Y = {nm: torch.empty(n, self.W[nm].shape[0], dtype=torch.bfloat16, device="cuda") for nm in self.names if nm[0] != "head"}
+        self.B = {nm: torch.empty(self.W[nm].shape[1], r, dtype=torch.float32, device="cuda") for nm in self.names}
+        self.X = {}
+        self.out = torch.zeros(4, dtype=torch.float64, device="cuda")
+        self.flops_fwd = sum(2.0 * n * self.W[nm].shape[0] * self.W[nm].shape[1] for nm in self.names)
+        self.flops_rank = sum(2.0 * n * r * (self.W[nm].shape[0] + self.W[nm].shape[1]) for nm in self.names)
+
+    def rms(self, h):
+        y = torch.empty_like(h)
+        self.ctx.glue_rmsnorm(h, y)
+        return y
+
+    def linear(self, nm, x, sign, eps, seed0, loss_dev):
+        W, Y = self.W[nm], self.Y.get(nm)
+        L = binding.make_layer(W, x, self.r, Y=Y)
+        loss = self.loss if nm[0] == "head" else None
+        seed = seed0 + self.names.index(nm)
+        if sign == 0:
+            self.X[nm] = x
+            self.ctx.layer_forward_sketch(L, W, x, Y, binding.SKETCH_NONE, None, seed, None, loss, loss_dev)
+        else:
+            self.ctx.perturbed_forward(L, W, x, self.B[nm], seed, sign * eps, Y, loss, loss_dev)
+        return Y
+
+    def run_pass(self, sign, eps, seed0, loss_dev):
+        h = self.E[self.ids]
+        for b in range(self.nb):
+            n = self.rms(h)
+            a = self.linear(("gate", b), n, sign, eps, seed0, None)
+            u = self.linear(("up", b), n, sign, eps, seed0, None)
+            m = torch.empty_like(a)
+            self.ctx.glue_swiglu(a, u, m)
+            d = self.linear(("down", b), m, sign, eps, seed0, None)
+            self.ctx.glue_add(h, d)
+        self.linear(("head", 0), self.rms(h), sign, eps, seed0, loss_dev)
+
+    def step(self, step, eps, lr):
+        seed0 = 100_000 * (step + 1)
+        self.run_pass(0, eps, seed0, self.out[0:1])
+        self.ctx.basis_many([(binding.make_layer(self.W[nm], self.X[nm], self.r), self.X[nm], seed0 + i, None, self.B[nm])
+                             for i, nm in enumerate(self.names)], self.K)
+        self.X.clear()
+        self.run_pass(+1, eps, seed0, self.out[1:2])
+        self.run_pass(-1, eps, seed0, self.out[2:3])
+        self.ctx.two_point(self.out, eps)
+        self.ctx.update_many([(self.W[nm], self.B[nm], seed0 + i, lr, self.out[3:4]) for i, nm in enumerate(self.names)])
+
+
+def run_mlp_stack(ctx, steps, warmup, r=16, K=3, n_blocks=28, n_seq=16, seq_len=512):
+    """Steps per second of the MLP-stack workload (28 blocks + LM head, 16 x 512 tokens, token cross-entropy, global g)."""
+    eps, lr = float(np.float32(1e-3)), float(np.float32(1e-4))
+    params, ids = synth.device_mlp_stack(11, n_blocks, 2048, 6144, 32000, n_seq, seq_len)
+    model = MlpStack(ctx, params, ids, r, K)
+    for s in range(warmup):
+        model.step(s, eps, lr)
+    ctx.check()
+    torch.cuda.synchronize()
+    ctx.profile_enable(1 << binding.PROF_GEMM)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    t0 = time.perf_counter()
+    for s in range(steps):
+        ev[s].record()
+        model.step(warmup + s, eps, lr)
+    ev[steps].record()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    n_g, ms_g = ctx.profile_read(binding.PROF_GEMM)
+    ctx.profile_enable(False)
+    ctx.check()
+    losses = model.out.cpu().numpy()
+    if not np.isfinite(losses).all():
+        raise RuntimeError("non-finite loss in the MLP-stack workload")
+    per_step = sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(steps))
+    med = per_step[len(per_step) // 2]
+    flops = 3.0 * model.flops_fwd + 2.0 * model.flops_rank
+    return {"value": 1e3 / med, "unit": "steps/s", "ms_per_step": med, "ms_per_step_mean_wall": 1e3 * dt / steps, "steps": steps,
+            "gemm_launches": n_g, "gemm_ms_per_step": ms_g / steps, "gemm_tflops": flops * steps / (ms_g * 1e-3) / 1e12,
+            "forward_tflop": model.flops_fwd / 1e12, "linear_layers": len(model.names), "tokens": n_seq * seq_len, "rank": r,
+            "power_steps": K, "losses": {"L0": losses[0], "L+": losses[1], "L-": losses[2], "g": losses[3]},
+            "note": "Alg. 2 over %d blocks + LM head: base pass keeping every layer's input, one batched extraction for the "
+                    "%d layers, two perturbed passes (factored, fused cross-entropy on the head), global g, one batched "
+                    "update" % (n_blocks, len(model.names))}
 
 
 def sweep(args):
@@ -147,9 +257,9 @@ def main():
     ap.add_argument("--sweep", action="store_true", help="rank x tokens sweep on Qwen3-4B shapes (text table)")
     ap.add_argument("--no-extras", action="store_true",
                     help="only the timed workload and its stage breakdown (for counter-collection runs of the profiler)")
-    ap.add_argument("--workload", choices=["qwen3-8b", "qwen3-0.6b"], default="qwen3-8b",
+    ap.add_argument("--workload", choices=["qwen3-8b", "qwen3-0.6b", "mlp-stack"], default="qwen3-8b",
                     help="layer set: qwen3-8b is the benchmark configuration; qwen3-0.6b (use --tokens 2048 --rank 8) is the "
-                         "small launch-bound one")
+                         "small launch-bound one; mlp-stack is the 28-block residual stack with LM head and global g")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives are part of it); use --gpus 1",
@@ -162,6 +272,19 @@ def main():
     if args.sweep:
         sweep(args)
         return
+    if args.workload == "mlp-stack":
+        ctx = binding.Context()
+        st = run_mlp_stack(ctx, max(args.steps // 4, 3), max(args.warmup // 2, 1), r=args.rank)
+        res = {"metric": "AGZO steps/sec (MLP stack with LM head)", "value": st["value"], "unit": "steps/s", "n_gpus": 1,
+               "steps": st["steps"], "warmup": max(args.warmup // 2, 1), "ms_per_step": st["ms_per_step"],
+               "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+               "config": {"workload": "28 SwiGLU-MLP blocks (hidden 2048, intermediate 6144, RMSNorm) + 2048x32000 LM head, "
+                                      "16x512 tokens, next-token cross-entropy, r=%d, K=3, global g" % args.rank},
+               "roofline": {"bound": "mfma", "kernel": "gemm_bf16_kernel", "achieved": st["gemm_tflops"], "peak": PEAK_BF16_TFLOPS,
+                            "unit": "TFLOP/s", "frac": st["gemm_tflops"] / PEAK_BF16_TFLOPS, "traffic": None},
+               "detail": st}
+        print(json.dumps(res))
+        return
     N, r, K = args.tokens, args.rank, 3
     eps, lr = float(np.float32(1e-3)), float(np.float32(1e-4))
     shapes = synth.QWEN3_8B_LAYER if args.workload == "qwen3-8b" else synth.QWEN3_0P6B_LAYER
@@ -173,15 +296,23 @@ def main():
     out = torch.zeros(len(layers), 4, dtype=torch.float64, device="cuda")
     flags = binding.NAIVE_INPLACE if args.naive else 0
 
-    # Alg. 2 at the level of the layer set: every projection runs its step up to its scalar g, then all the
-    # updates go out together (one preparation launch and one sweep for the seven matrices)
+    # Alg. 2 at the level of the layer set (agzo_step_many): every projection's base forward, all bases together (each
+    # stage of Alg. 1 one launch for the seven layers), all projections X B in one launch, the perturbed forwards, the
+    # scalars, and all updates in one batched sweep.  The in-place comparator runs layer by layer (agzo_step_no_update
+    # + one batched update).
     def step_fn(descs_, out_, r_, c=ctx):
         bases = [torch.empty(W.shape[1], r_, dtype=torch.float32, device="cuda") for _, W, _, _ in descs_]
+        arr = c.make_step_items([(L, W, X, loss, 0, out_[li], None) for li, (L, W, X, loss) in enumerate(descs_)])
 
         def run(step, fl):
-            for li, (L, W, X, loss) in enumerate(descs_):
-                c.step_no_update(L, W, X, loss, K, eps, 1000 * step + li, fl, out_[li], bases[li])
-            c.update_many([(W, bases[li], 1000 * step + li, lr, out_[li, 3:4]) for li, (_, W, _, _) in enumerate(descs_)])
+            if fl & binding.NAIVE_INPLACE:
+                for li, (L, W, X, loss) in enumerate(descs_):
+                    c.step_no_update(L, W, X, loss, K, eps, 1000 * step + li, fl, out_[li], bases[li])
+                c.update_many([(W, bases[li], 1000 * step + li, lr, out_[li, 3:4]) for li, (_, W, _, _) in enumerate(descs_)])
+                return
+            for li in range(len(descs_)):
+                arr[li].seed = 1000 * step + li
+            c.step_many_raw(arr, len(descs_), K, eps, lr, fl)
         return run
 
     run_step = step_fn(descs, out, r)
@@ -202,11 +333,17 @@ def main():
     # the timed region carries HIP events only around the two kernels whose rooflines are reported (forward GEMM,
     # update); every event costs stream time, so the other stages are timed in a pass of their own below
     ctx.profile_enable((1 << binding.PROF_GEMM) | (1 << binding.PROF_UPDATE))
+    # per-step times from events on the library's stream (= torch's current stream), no host synchronisation inside
+    step_ev = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     t0 = time.perf_counter()
     for s in range(args.steps):
+        step_ev[s].record()
         one_step(args.warmup + s)
+    step_ev[args.steps].record()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    per_step_ms = sorted(step_ev[i].elapsed_time(step_ev[i + 1]) for i in range(args.steps))
+    median_ms = per_step_ms[len(per_step_ms) // 2]
     n_gemm, ms_gemm = ctx.profile_read(binding.PROF_GEMM)
     n_upd, ms_upd = ctx.profile_read(binding.PROF_UPDATE)
     try:
@@ -257,14 +394,17 @@ def main():
 
     res = {
         "metric": "AGZO steps/sec per layer set (Qwen3-8B layer projections)",
-        "value": args.steps / dt, "unit": "steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": 1e3 * dt / args.steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "value": 1e3 / median_ms, "unit": "steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": median_ms, "ms_per_step_mean_wall": 1e3 * dt / args.steps,
+        "ms_per_step_min_max": [per_step_ms[0], per_step_ms[-1]], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": args.workload + " layer projections (q,k,v,o,gate,up,down), N=%d tokens, r=%d, K=%d, "
                                "bf16 weights/activations/targets, MSE loss, %s" % (N, r, K, "naive in-place comparator" if args.naive else "factored perturbed forward"),
                    "tokens": N, "rank": r, "power_steps": K, "eps": eps, "lr": lr},
         "roofline": {"bound": "mfma", "kernel": "gemm_bf16_kernel", "achieved": gemm_tflops, "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": gemm_tflops / PEAK_BF16_TFLOPS, "traffic": traffic,
+                     "traffic_source": "profiles/gemm_bf16_qwen3_8b_traffic.txt (two rocprofv3 --pmc runs of this command, scaled by a "
+                                       "plain copy; counters cannot be read from inside this process)",
                      "launches": n_gemm, "avg_ms": gemm_avg_ms,
                      "shader_clock_ghz": gemm_ghz, "clock_note": "mean shader clock over the first workgroup of each of "
                      "these launches (in-kernel cycle counter / constant-rate counter); the peak assumes 2.4 GHz"},
@@ -402,7 +542,7 @@ def main():
         dt5 = time.perf_counter() - t5
         ctx.check()
         res["dense_gaussian"] = {"value": nsteps / dt5, "unit": "steps/s", "ms_per_step": 1e3 * dt5 / nsteps, "steps": nsteps,
-                                 "agzo_over_dense": (args.steps / dt) / (nsteps / dt5),
+                                 "agzo_over_dense": (1e3 / median_ms) / (nsteps / dt5),
                                  "agzo_one_sided_over_dense": (nsteps / dt7) / (nsteps / dt5),
                                  "note": "Eq. 7's dense branch on the same matrices, composed from agzo_dense_perturb, the plain "
                                          "forward and agzo_two_point: two forwards and four generator-bound sweeps per projection"}
@@ -428,7 +568,7 @@ def main():
         dt6 = time.perf_counter() - t6
         ctx.check()
         res["lowrank_gaussian"] = {"value": nsteps / dt6, "unit": "steps/s", "ms_per_step": 1e3 * dt6 / nsteps, "steps": nsteps,
-                                   "agzo_over_lowrank": (args.steps / dt) / (nsteps / dt6),
+                                   "agzo_over_lowrank": (1e3 / median_ms) / (nsteps / dt6),
                                    "agzo_one_sided_over_lowrank": (nsteps / dt7) / (nsteps / dt6),
                                    "note": "perturbation U V^T with Gaussian factors (Sec. 2), two perturbed forwards and the batched "
                                            "rank-r update; composed from agzo_fill_normal, agzo_perturbed_forward, agzo_two_point, "
@@ -528,6 +668,36 @@ def main():
         except (binding.AgzoError, RuntimeError) as e:        # an extra: never a reason to lose the measurement
             res["qwen3_0p6b_layer_set"]["graph_replay"] = {"error": str(e)[:200]}
         del s_layers, s_descs
+    # ceilings of this machine that the HBM figures can be read against: a plain device copy and a read-only sweep of 1 GiB
+    # (torch's elementwise copy and reduction kernels, 10 launches each, HIP events on the current stream)
+    try:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        def timed_ms(fn, reps=10):
+            fn()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(reps):
+                fn()
+            b.record()
+            torch.cuda.synchronize()
+            return a.elapsed_time(b) / reps
+        gib = float(1 << 30)
+        res["box_ceilings"] = {"copy_GBps": 2.0 * gib / (timed_ms(lambda: dst.copy_(src)) * 1e-3) / 1e9,
+                               "read_only_GBps": gib / (timed_ms(lambda: src.sum()) * 1e-3) / 1e9,
+                               "note": "1 GiB fp32: copy counts bytes read + written, the read-only sweep is a sum reduction"}
+        del src, dst
+    except RuntimeError as e:
+        res["box_ceilings"] = {"error": str(e)[:200]}
+    if args.workload == "qwen3-8b" and not args.naive and not args.no_extras:
+        # Alg. 2 over a model: the 28-block MLP stack with LM head at its full size (a workload of its own with
+        # --workload mlp-stack)
+        try:
+            torch.cuda.empty_cache()
+            res["mlp_stack"] = run_mlp_stack(ctx, 3, 1)
+        except (binding.AgzoError, RuntimeError) as e:
+            res["mlp_stack"] = {"error": str(e)[:300]}
+        torch.cuda.empty_cache()
     # yardstick for the MFMA fraction: a register-only MFMA loop (no LDS, no memory traffic) on this device, with
     # operand bits that never toggle (zeros) and with N(0,1) bf16 operands like the workload's
     gen = torch.Generator(device="cuda")

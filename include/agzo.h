@@ -234,6 +234,19 @@ int agzo_step(agzo_ctx* ctx, const agzo_layer* L, void* W, const void* X, const 
 int agzo_step_no_update(agzo_ctx* ctx, const agzo_layer* L, void* W, const void* X, const agzo_loss_spec* loss,
                         int32_t K, float eps, uint64_t seed, int32_t flags, double* out_dev, float* B_out);
 
+/* The model around the linear layers of a gated-MLP stack (not steps of the method; a whole-model step of Alg. 2 runs
+ * them once per block and pass, so they are single-pass kernels): bf16 device tensors of n rows of d values (d a
+ * multiple of 8, 16-byte aligned rows, leading dimensions in elements), fp32 arithmetic, one rounding to bf16.
+ *   rmsnorm: y[t] = gain * x[t] / sqrt(mean(x[t]^2) + eps)   (gain: device fp32 [d], NULL = 1; y may alias x)
+ *   swiglu : m = silu(a) * u, silu(z) = z / (1 + exp(-z))     (m may alias a or u)
+ *   add    : h += delta in place
+ * Errors: AGZO_EINVAL for NULL or misaligned tensors, d % 8 != 0, leading dimensions below d. */
+int agzo_glue_rmsnorm(agzo_ctx* ctx, const void* x, int64_t ldx, void* y, int64_t ldy, const float* gain, int64_t n, int64_t d,
+                      float eps);
+int agzo_glue_swiglu(agzo_ctx* ctx, const void* a, int64_t lda, const void* u, int64_t ldu, void* m, int64_t ldm, int64_t n,
+                     int64_t d);
+int agzo_glue_add(agzo_ctx* ctx, void* h, int64_t ldh, const void* delta, int64_t ldd, int64_t n, int64_t d);
+
 /* Alg. 2 for n independent single-layer problems in one call (a layer set whose projections each have their own loss
  * and their own scalar g): every layer's base forward, all bases together (as agzo_basis_many), all projections X B
  * in one launch, the perturbed forwards, every scalar, and all updates in one batched sweep (as agzo_update_many).

@@ -27,7 +27,8 @@ PROF_ALL = 63
 EXPORTS = ["agzo_create", "agzo_destroy", "agzo_last_error", "agzo_check", "agzo_profile_enable",
            "agzo_profile_read", "agzo_profile_clock", "agzo_probe_mfma", "agzo_philox_words", "agzo_fill_normal",
            "agzo_layer_forward_sketch", "agzo_qr", "agzo_basis", "agzo_perturbed_forward", "agzo_two_point", "agzo_dense_perturb", "agzo_update", "agzo_update_noalloc",
-           "agzo_update_many", "agzo_step", "agzo_step_no_update", "agzo_basis_many", "agzo_step_many"]
+           "agzo_update_many", "agzo_step", "agzo_step_no_update", "agzo_basis_many", "agzo_step_many",
+           "agzo_glue_rmsnorm", "agzo_glue_swiglu", "agzo_glue_add"]
 
 
 class AgzoLayer(ctypes.Structure):
@@ -103,6 +104,9 @@ def load():
     lib.agzo_update_many.argtypes = [vp, ctypes.POINTER(AgzoUpdateItem), i32]
     lib.agzo_basis_many.argtypes = [vp, ctypes.POINTER(AgzoBasisItem), i32, i32, i32]
     lib.agzo_step_many.argtypes = [vp, ctypes.POINTER(AgzoStepItem), i32, i32, f32, f32, i32]
+    lib.agzo_glue_rmsnorm.argtypes = [vp, vp, i64, vp, i64, vp, i64, i64, f32]
+    lib.agzo_glue_swiglu.argtypes = [vp, vp, i64, vp, i64, vp, i64, i64, i64]
+    lib.agzo_glue_add.argtypes = [vp, vp, i64, vp, i64, i64, i64]
     lib.agzo_step.argtypes = [vp, lp, vp, vp, sp, i32, f32, f32, u64, i32, vp]
     lib.agzo_step_no_update.argtypes = [vp, lp, vp, vp, sp, i32, f32, u64, i32, vp, vp]
     for name in EXPORTS:
@@ -291,6 +295,18 @@ class Context:
 
     def step_many(self, items, K, eps, lr, flags=0):
         self.step_many_raw(self.make_step_items(items), len(items), K, eps, lr, flags)
+
+    def glue_rmsnorm(self, x, y, gain=None, eps=1e-6):
+        n, d = x.shape
+        self._rc(self.lib.agzo_glue_rmsnorm(self.h, _ptr(x), x.stride(0), _ptr(y), y.stride(0), _ptr(gain), n, d, eps))
+
+    def glue_swiglu(self, a, u, m):
+        n, d = a.shape
+        self._rc(self.lib.agzo_glue_swiglu(self.h, _ptr(a), a.stride(0), _ptr(u), u.stride(0), _ptr(m), m.stride(0), n, d))
+
+    def glue_add(self, h, delta):
+        n, d = h.shape
+        self._rc(self.lib.agzo_glue_add(self.h, _ptr(h), h.stride(0), _ptr(delta), delta.stride(0), n, d))
 
     def step_no_update(self, L, W, X, loss, K, eps, seed, flags, out_dev, B_out):
         self._rc(self.lib.agzo_step_no_update(self.h, ctypes.byref(L), _ptr(W), _ptr(X), ctypes.byref(loss), K, eps,

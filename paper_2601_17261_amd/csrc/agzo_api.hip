@@ -4,6 +4,7 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <initializer_list>
 #include <mutex>
 #include <new>
 #include <vector>
@@ -972,6 +973,40 @@ int agzo_step_many(agzo_ctx* ctx, const agzo_step_item* items, int32_t n, int32_
         return fail(ctx, AGZO_EHIP, "internal: update scratch was not reserved");
     }
     return update_many_at(ctx, upd.data(), (int)upd.size(), total);
+}
+
+namespace {
+int check_glue(agzo_ctx* ctx, int64_t n, int64_t d, std::initializer_list<const void*> ptrs, std::initializer_list<int64_t> lds) {
+    if (!ctx) return AGZO_EINVAL;
+    if (n < 0 || d < 0 || d % 8) return fail(ctx, AGZO_EINVAL, "rows of %lld values: need a non-negative multiple of 8", (long long)d);
+    for (const void* p : ptrs)
+        if ((!p && n * d > 0) || (reinterpret_cast<uintptr_t>(p) & 15)) return fail(ctx, AGZO_EINVAL, "NULL or misaligned tensor");
+    for (int64_t ld : lds)
+        if (ld < d || ld % 8) return fail(ctx, AGZO_EINVAL, "leading dimension %lld below the row length or not a multiple of 8", (long long)ld);
+    if (n > 0x7FFFFFFFLL) return fail(ctx, AGZO_EINVAL, "too many rows");
+    return 0;
+}
+}  // namespace
+
+int agzo_glue_rmsnorm(agzo_ctx* ctx, const void* x, int64_t ldx, void* y, int64_t ldy, const float* gain, int64_t n, int64_t d,
+                      float eps) {
+    TRY(check_glue(ctx, n, d, {x, y}, {ldx, ldy}));
+    HIPCHK(launch_glue_rmsnorm(static_cast<const bf16_t*>(x), ldx, static_cast<bf16_t*>(y), ldy, gain, n, d, eps, ctx->stream));
+    return AGZO_OK;
+}
+
+int agzo_glue_swiglu(agzo_ctx* ctx, const void* a, int64_t lda, const void* u, int64_t ldu, void* m, int64_t ldm, int64_t n,
+                     int64_t d) {
+    TRY(check_glue(ctx, n, d, {a, u, m}, {lda, ldu, ldm}));
+    HIPCHK(launch_glue_swiglu(static_cast<const bf16_t*>(a), lda, static_cast<const bf16_t*>(u), ldu, static_cast<bf16_t*>(m), ldm,
+                              n, d, ctx->stream));
+    return AGZO_OK;
+}
+
+int agzo_glue_add(agzo_ctx* ctx, void* h, int64_t ldh, const void* delta, int64_t ldd, int64_t n, int64_t d) {
+    TRY(check_glue(ctx, n, d, {h, delta}, {ldh, ldd}));
+    HIPCHK(launch_glue_add(static_cast<bf16_t*>(h), ldh, static_cast<const bf16_t*>(delta), ldd, n, d, ctx->stream));
+    return AGZO_OK;
 }
 
 // Alg. 2 for one layer.  B_out == NULL: the basis stays in the workspace and the update runs at the end;

@@ -239,6 +239,13 @@ hipError_t launch_finish_two_point(const double* partials, int n, double scale, 
 hipError_t launch_dense_axpy(void* theta, int dtype, int64_t rows, int64_t cols, int64_t ld, uint64_t seed, float scale,
                              const double* g_dev, hipStream_t st);
 
+// glue.hip : the model around the linear layers of the MLP-stack workload (bf16 rows of d, d % 8 == 0, 16-byte aligned)
+hipError_t launch_glue_rmsnorm(const bf16_t* x, int64_t ldx, bf16_t* y, int64_t ldy, const float* gain, int64_t n, int64_t d,
+                               float eps, hipStream_t st);
+hipError_t launch_glue_swiglu(const bf16_t* a, int64_t lda, const bf16_t* u, int64_t ldu, bf16_t* m, int64_t ldm, int64_t n,
+                              int64_t d, hipStream_t st);
+hipError_t launch_glue_add(bf16_t* h, int64_t ldh, const bf16_t* dl, int64_t ldd, int64_t n, int64_t d, hipStream_t st);
+
 // probe.hip : register-only MFMA loop for measuring the sustained matrix rate and shader clock of the device;
 // clk4: four 64-bit words for the counters plus 1 KiB that the kernel may (never does) write behind them
 hipError_t launch_probe_mfma(const void* operands, int duty, int iters, unsigned long long* clk4, hipStream_t st);

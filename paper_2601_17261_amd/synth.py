@@ -163,3 +163,22 @@ def mlp_stack_problem(seed, n_blocks, hidden, inter, vocab, n_seq, seq_len, emb_
         for nm in [("norm", b) for b in range(n_blocks)] + [("norm_f", 0)]:
             params[nm] = (1.0 + 0.1 * rng.standard_normal(hidden)).astype(np.float32)
     return params, ids
+
+
+def device_mlp_stack(seed, n_blocks, hidden, inter, vocab, n_seq, seq_len, emb_rank=16, device="cuda"):
+    """The MLP-stack workload at any size, generated on the device (same recipe as mlp_stack_problem, without gains):
+    bf16 tensors "E", ("gate", b), ("up", b), ("down", b), ("head", 0) and int64 ids [n_seq][seq_len]."""
+    gen = torch.Generator(device=device)
+    gen.manual_seed(int(seed))
+    f32 = dict(device=device, dtype=torch.float32, generator=gen)
+    A = torch.randn(vocab, emb_rank, **f32) * torch.logspace(0.0, -1.0, emb_rank, device=device)[None, :]
+    E = A @ torch.randn(emb_rank, hidden, **f32) + 0.3 * torch.randn(vocab, hidden, **f32)
+    E /= E.square().mean().sqrt()
+    params = {"n_blocks": n_blocks, "E": E.to(torch.bfloat16)}
+    for b in range(n_blocks):
+        params[("gate", b)] = (torch.randn(inter, hidden, **f32) * 0.02).to(torch.bfloat16)
+        params[("up", b)] = (torch.randn(inter, hidden, **f32) * 0.02).to(torch.bfloat16)
+        params[("down", b)] = (torch.randn(hidden, inter, **f32) * 0.02).to(torch.bfloat16)
+    params[("head", 0)] = (torch.randn(vocab, hidden, **f32) * 0.02).to(torch.bfloat16)
+    ids = torch.randint(0, vocab, (n_seq, seq_len), device=device, generator=gen)
+    return params, ids

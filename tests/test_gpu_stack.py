@@ -177,3 +177,48 @@ def test_reduced_mlp_stack_step_matches_oracle(ctx, reduced_stack, storage, eps,
             diff = np.abs(Wg - want)
             assert (diff <= bound).all(), (nm, float((diff / bound).max()))
             assert (diff > 0).mean() < 0.05, (nm, (diff > 0).mean())
+
+
+def test_glue_kernels_match_the_oracle_model(ctx):
+    """RMS normalisation, SiLU gate and residual sum between the linear layers: the library's single-pass kernels
+    against the oracle's fp64 functions rounded once to bf16.  fp32 arithmetic can land on the other side of a bf16
+    rounding boundary: isolated one-ulp differences only."""
+    rng = np.random.default_rng(8)
+    n, d = 70, 264
+
+    def bf(a):
+        return torch.from_numpy(synth.to_bf16_values(a)).to("cuda", torch.bfloat16)
+
+    def check(got, want64):
+        got = got.double().cpu().numpy()
+        want = oagzo.round_bf16(want64)
+        ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(want), 1e-30))) - 7)
+        assert (np.abs(got - want) <= ulp * 1.0001).all()
+        assert (got != want).mean() < 0.01
+
+    x = 3.0 * rng.standard_normal((n, d))
+    gain = (1.0 + 0.1 * rng.standard_normal(d)).astype(np.float32)
+    xd = bf(x)
+    x64 = xd.double().cpu().numpy()
+    y = torch.empty_like(xd)
+    ctx.glue_rmsnorm(xd, y)
+    check(y, ostack.rmsnorm(x64))
+    ctx.glue_rmsnorm(xd, y, torch.from_numpy(gain).cuda())
+    check(y, ostack.rmsnorm(x64, gain))
+    a, u = bf(2.0 * rng.standard_normal((n, d))), bf(rng.standard_normal((n, d)))
+    m = torch.empty_like(a)
+    ctx.glue_swiglu(a, u, m)
+    check(m, ostack.silu(a.double().cpu().numpy()) * u.double().cpu().numpy())
+    h = xd.clone()
+    ctx.glue_add(h, a)
+    check(h, x64 + a.double().cpu().numpy())
+    # rows inside wider allocations, an empty tensor, and a row length that is not a multiple of 8
+    wide = torch.zeros(n, d + 24, dtype=torch.bfloat16, device="cuda")
+    ctx.glue_rmsnorm(xd, wide[:, 8:8 + d])
+    check(wide[:, 8:8 + d], ostack.rmsnorm(x64))
+    assert torch.count_nonzero(wide[:, :8]).item() == 0 and torch.count_nonzero(wide[:, 8 + d:]).item() == 0
+    ctx.glue_add(torch.empty(0, 8, dtype=torch.bfloat16, device="cuda"), torch.empty(0, 8, dtype=torch.bfloat16, device="cuda"))
+    with pytest.raises(binding.AgzoError) as e:
+        ctx.glue_add(torch.zeros(4, 12, dtype=torch.bfloat16, device="cuda"), torch.zeros(4, 12, dtype=torch.bfloat16, device="cuda"))
+    assert e.value.code == binding.EINVAL
+    ctx.check()
