@@ -190,6 +190,51 @@ def run_mlp_stack(ctx, steps, warmup, r=16, K=3, n_blocks=28, n_seq=16, seq_len=
                     "update" % (n_blocks, len(model.names))}
 
 
+def gemm_shapes(args):
+    """The forward GEMM alone on each distinct projection shape of the Qwen3-8B layer (for counter-collection runs: with
+    --shape every GEMM dispatch of the process has that one shape).  Prints one JSON line per shape and variant."""
+    ctx = binding.Context()
+    N, r = args.tokens, args.rank
+    eps = float(np.float32(1e-3))
+    shapes = [("q", 4096, 4096), ("k", 4096, 1024), ("gate", 4096, 12288), ("down", 12288, 4096)]
+    if args.calibrate_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)            # 1 GiB read + 1 GiB written by one elementwise kernel: scale for the traffic counters
+        torch.cuda.synchronize()
+        del src, dst
+    xs = {}
+    for name, d_in, d_out in shapes:
+        if args.shape and name != args.shape:
+            continue
+        if d_in not in xs:
+            xs[d_in] = synth.device_powerlaw_x(100 + d_in, N, d_in)
+        X = xs[d_in]
+        W, T = synth.device_weights_and_target(3 + d_out, X, d_out)
+        L, loss = binding.make_layer(W, X, r), binding.make_loss(T)
+        sc = torch.zeros(4, dtype=torch.float64, device="cuda")
+        B = torch.empty(d_in, r, device="cuda")
+        ctx.basis(L, X, 1, 5, None, 0, B)
+        ctx.check()
+        variants = {"base_forward_loss": lambda: ctx.layer_forward_sketch(L, W, X, None, 0, None, 1, None, loss, sc[0:1]),
+                    "perturbed_forward_loss": lambda: ctx.perturbed_forward(L, W, X, B, 5, eps, None, loss, sc[1:2])}
+        for vname, fn in variants.items():
+            for _ in range(3):
+                fn()
+            torch.cuda.synchronize()
+            ctx.profile_enable(1 << binding.PROF_GEMM)
+            for _ in range(args.steps):
+                fn()
+            n, ms = ctx.profile_read(binding.PROF_GEMM)
+            _, ghz = ctx.profile_clock()
+            ctx.profile_enable(False)
+            flops = 2.0 * N * d_in * d_out + (2.0 * N * r * (d_in + d_out) if vname.startswith("pert") else 0.0)
+            print(json.dumps({"shape": "%s %d->%d" % (name, d_in, d_out), "tokens": N, "variant": vname, "launches": n,
+                              "avg_us": 1e3 * ms / n, "tflops": flops / (ms / n * 1e-3) / 1e12, "shader_clock_ghz": ghz,
+                              "algorithmic_bytes": 2.0 * N * d_in + 2.0 * d_in * d_out + 2.0 * N * d_out}), flush=True)
+        del W, T
+
+
 def sweep(args):
     """Qwen3-4B shapes, r in {1,4,16,64} x N in {512,4096,16384,65536}: per kernel the achieved rate, the
     algorithmic intensity and which roofline (HBM or MFMA) bounds it.  Prints one text table."""
@@ -198,6 +243,7 @@ def sweep(args):
     projs = [p for p in synth.QWEN3_4B_LAYER if p[0] in ("q", "k", "gate", "down")]
     print("# kernel rates on Qwen3-4B-shaped projections, bf16; bound = larger of flops/2500 TFLOP/s and bytes/8000 GB/s")
     print("# %-5s %6s %3s | %-9s %9s %9s %8s %7s %6s" % ("proj", "N", "r", "kernel", "us", "TFLOP/s", "GB/s", "flop/B", "bound"))
+    table = {}
     for N in (512, 4096, 16384, 65536):
         xs = {}
         for name, d_in, d_out in projs:
@@ -238,9 +284,24 @@ def sweep(args):
                     bound = "mfma" if fl / 2.5e15 > by / 8e12 else "hbm"
                     print("  %-5s %6d %3d | %-9s %9.1f %9.1f %8.0f %7.1f %6s" %
                           (name, N, r, kname, us, fl / us / 1e6, by / us / 1e3, fl / by, bound), flush=True)
+                    table.setdefault((name, kname, r), []).append((N, fl / us / 1e6, by / us / 1e3))
             del W, T
         del xs
         torch.cuda.empty_cache()
+    # where the measured rates bend: a kernel is taken as bound by memory while its byte rate is the larger fraction of
+    # its peak, and by the matrix cores once its flop rate is; the crossover is read from the measured rates, not
+    # from the intensities
+    print("# measured regime per kernel: fraction of 8000 GB/s / fraction of 2500 TFLOP/s at N = 512, 4096, 16384, 65536; "
+          "crossover = first N where the flop fraction is the larger one")
+    for (name, kname, r), rows in sorted(table.items()):
+        cells, cross = [], None
+        for N, tf, gb in rows:
+            fb, ff = gb / PEAK_HBM_GBS, tf / PEAK_BF16_TFLOPS
+            cells.append("%.2f/%.2f" % (fb, ff))
+            if cross is None and ff > fb:
+                cross = N
+        print("#  %-5s %-9s r=%-2d  %s   crossover: %s" % (name, kname, r, "  ".join(cells),
+              ("N = %d" % cross) if cross else "stays memory-bound up to N = 65536"))
 
 
 def main():
@@ -255,6 +316,9 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (known traffic) so counter runs can be scaled")
     ap.add_argument("--sweep", action="store_true", help="rank x tokens sweep on Qwen3-4B shapes (text table)")
+    ap.add_argument("--gemm-shapes", action="store_true",
+                    help="time the forward GEMM alone on each distinct Qwen3-8B projection shape (one JSON line each)")
+    ap.add_argument("--shape", choices=["q", "k", "gate", "down"], default=None, help="with --gemm-shapes: only this shape")
     ap.add_argument("--no-extras", action="store_true",
                     help="only the timed workload and its stage breakdown (for counter-collection runs of the profiler)")
     ap.add_argument("--workload", choices=["qwen3-8b", "qwen3-0.6b", "mlp-stack"], default="qwen3-8b",
@@ -271,6 +335,9 @@ def main():
 
     if args.sweep:
         sweep(args)
+        return
+    if args.gemm_shapes:
+        gemm_shapes(args)
         return
     if args.workload == "mlp-stack":
         ctx = binding.Context()
