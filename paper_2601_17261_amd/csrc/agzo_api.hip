@@ -490,8 +490,12 @@ int basis_many_impl(agzo_ctx* ctx, const std::vector<LayerJob>& jobs, int K, int
             continue;
         }
         int idx[kBatchMax], n = 0;
+        // (single columns are normalised rather than factored: launches of their own)
         for (size_t b = a; b < jobs.size() && n < kBatchMax; ++b)
-            if (!done[b] && jobs[b].L.dtype == AGZO_BF16 && jobs[b].p.rp == ja.p.rp) { idx[n++] = (int)b; done[b] = 1; }
+            if (!done[b] && jobs[b].L.dtype == AGZO_BF16 && jobs[b].p.rp == ja.p.rp && (jobs[b].L.r == 1) == (ja.L.r == 1)) {
+                idx[n++] = (int)b;
+                done[b] = 1;
+            }
         // first sketch: the feature-space start (Q0 from the seed, then a power sketch), a given S0, or the range sketch
         bool given[kBatchMax];
         int need_idx[kBatchMax], n_need = 0;
@@ -557,7 +561,8 @@ int project_many(agzo_ctx* ctx, const std::vector<LayerJob>& jobs) {
 }
 
 // checked items, workspace reserved: the factor fragments of all matrices start at workspace offset `off`.
-// fp32 matrices one by one (no workspace); bf16 matrices by padded rank, update_many_max() to a pair of launches
+// fp32 matrices and rank-1 sweeps one by one (no workspace); other bf16 matrices by padded rank, update_many_max() to a
+// pair of launches
 int update_many_at(agzo_ctx* ctx, const agzo_update_item* items, int n, size_t off) {
     for (int nk = 0; nk <= (kMaxRank + 15) / 16; ++nk) {
         std::vector<UpdateDesc> group;
@@ -573,13 +578,14 @@ int update_many_at(agzo_ctx* ctx, const agzo_update_item* items, int n, size_t o
         };
         for (int m = 0; m < n; ++m) {
             const agzo_update_item& u = items[m];
+            const bool single = (u.dtype == AGZO_F32) || u.r == 1;   // fp32 matrices and rank-1 sweeps: one launch each, no scratch
             if (nk == 0) {
-                if (u.dtype != AGZO_F32) continue;
+                if (!single) continue;
                 ProfScope ps(ctx, AGZO_PROF_UPDATE);
                 HIPCHK(launch_update(u.W, u.dtype, u.ldw, u.d_out, u.d_in, u.B, u.r, u.seed, u.lr, u.g_dev, nullptr, ctx->stream));
                 continue;
             }
-            if (u.dtype != AGZO_BF16 || (u.r + 15) / 16 != nk) continue;
+            if (single || (u.r + 15) / 16 != nk) continue;
             group.push_back(UpdateDesc{u.W, u.B, u.g_dev, u.ldw, u.d_out, u.d_in, u.seed, u.lr, u.r});
             group_bytes += update_workspace_bytes(u.dtype, u.d_out, u.d_in, u.r);
             if ((int)group.size() == update_many_max()) TRY(flush());

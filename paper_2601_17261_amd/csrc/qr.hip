@@ -328,6 +328,95 @@ __global__ __launch_bounds__(256) void qr_apply_final_many_kernel(const KBatch<Q
     else qr_apply_final_body<RP, float>(a.Sin, a.d, a.r, a.partial1, a.nblk, a.Q, a.planes, flag, bx);
 }
 
+// ---- r = 1 (the paper's operating point): the thin QR of a single column with a positive diagonal is the column
+// divided by its norm, so the orthonormalisation is a sum of squares and a scaling: two small launches, no Gram
+// matrix, no factorisation, and nothing for a second pass to refine.
+constexpr int QR1_ROWS = 1024;   // rows per workgroup (4 per thread)
+
+// launch 1: y_i = the column (or the fp64 sum of its partial sketches in split order, rounded to fp32 and stored to
+// S_out like the general path does), partial[b] = sum of y_i^2 over the block's rows (fp64, fixed order)
+__device__ __forceinline__ void qr1_sumsq_body(const float* __restrict__ S, const float* __restrict__ splits, int nsplit, int rp,
+                                               float* __restrict__ S_out, int64_t d, double* __restrict__ partial, uint32_t bx) {
+    __shared__ double red[4];
+    const int tid = threadIdx.x;
+    double ss = 0.0;
+#pragma unroll
+    for (int u = 0; u < QR1_ROWS / 256; ++u) {
+        const int64_t i = (int64_t)bx * QR1_ROWS + u * 256 + tid;
+        if (i >= d) continue;
+        float y;
+        if (splits != nullptr) {
+            double acc = 0.0;
+            for (int sp = 0; sp < nsplit; ++sp) acc += (double)splits[((int64_t)sp * d + i) * rp];
+            y = (float)acc;
+            S_out[i] = y;
+        } else {
+            y = S[i];
+        }
+        ss = fma((double)y, (double)y, ss);
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off);
+    if ((tid & 63) == 0) red[tid >> 6] = ss;
+    __syncthreads();
+    if (tid == 0) partial[bx] = (red[0] + red[1]) + (red[2] + red[3]);
+}
+
+// launch 2: q = y / sqrt(sum of the partials) -> Q fp32 [d][1] and, if asked, the bf16 planes [3][rp][d] (rows of the
+// padding columns zero).  A sum that is not positive (an all-zero sketch) raises the numeric flag.
+__device__ __forceinline__ void qr1_scale_body(const float* __restrict__ Y, int64_t d, int rp, const double* __restrict__ partial,
+                                               int nblk, float* __restrict__ Q, bf16_t* __restrict__ planes, int* flag,
+                                               uint32_t bx) {
+    const int tid = threadIdx.x;
+    double sum = 0.0;
+    for (int b = 0; b < nblk; ++b) sum += partial[b];          // uniform: every thread adds the same few values
+    if (!(sum > 0.0)) {
+        if (tid == 0 && bx == 0) *flag = 1;
+        sum = 1.0;
+    }
+    const double inv = 1.0 / sqrt(sum);
+#pragma unroll
+    for (int u = 0; u < QR1_ROWS / 256; ++u) {
+        const int64_t i = (int64_t)bx * QR1_ROWS + u * 256 + tid;
+        if (i >= d) continue;
+        const float q = (float)((double)Y[i] * inv);
+        Q[i] = q;
+        if (planes != nullptr) {
+            bf16_t hi, mid, lo;
+            split3_bf16(q, hi, mid, lo);
+            planes[((int64_t)0 * rp) * d + i] = hi;
+            planes[((int64_t)1 * rp) * d + i] = mid;
+            planes[((int64_t)2 * rp) * d + i] = lo;
+            for (int c = 1; c < rp; ++c) {
+                planes[((int64_t)0 * rp + c) * d + i] = 0;
+                planes[((int64_t)1 * rp + c) * d + i] = 0;
+                planes[((int64_t)2 * rp + c) * d + i] = 0;
+            }
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void qr1_sumsq_kernel(const float* __restrict__ S, const float* __restrict__ splits, int nsplit,
+                                                        int rp, float* __restrict__ S_out, int64_t d, double* __restrict__ partial) {
+    qr1_sumsq_body(S, splits, nsplit, rp, S_out, d, partial, blockIdx.x);
+}
+__global__ __launch_bounds__(256) void qr1_scale_kernel(const float* __restrict__ Y, int64_t d, int rp,
+                                                        const double* __restrict__ partial, int nblk, float* __restrict__ Q,
+                                                        bf16_t* __restrict__ planes, int* flag) {
+    qr1_scale_body(Y, d, rp, partial, nblk, Q, planes, flag, blockIdx.x);
+}
+__global__ __launch_bounds__(256) void qr1_sumsq_many_kernel(const KBatch<QrDev> tb, int rp) {
+    uint32_t bx, by;
+    const QrDev& a = tb.a[kbatch_find(tb, bx, by)];
+    qr1_sumsq_body(a.S, a.splits, a.nsplit, rp, a.S_out, a.d, a.partial1, bx);
+}
+__global__ __launch_bounds__(256) void qr1_scale_many_kernel(const KBatch<QrDev> tb, int rp, int* flag) {
+    uint32_t bx, by;
+    const QrDev& a = tb.a[kbatch_find(tb, bx, by)];
+    qr1_scale_body(a.Sin, a.d, rp, a.partial1, a.nblk, a.Q, a.planes, flag, bx);
+}
+static inline int64_t qr1_blocks(int64_t d) { return (d + QR1_ROWS - 1) / QR1_ROWS; }
+
 // the launches after the first, for one padded rank (the rows' registers are sized by it)
 template <int RP>
 static hipError_t launch_apply(dim3 grid, size_t smem, hipStream_t st, const float* Sin, int64_t d, int r, const double* partial1,
@@ -363,6 +452,16 @@ static hipError_t launch_apply(dim3 grid, size_t smem, hipStream_t st, const flo
 hipError_t launch_qr(const float* S, const float* splits, int nsplit, int rp, float* S_out, int64_t d, int r, float* Q,
                      bf16_t* planes, void* workspace, int* numeric_flag, bool refine, hipStream_t st) {
     if (d == 0) return hipSuccess;
+    if (r == 1) {
+        const int nb1 = (int)qr1_blocks(d);
+        double* part = reinterpret_cast<double*>(workspace);          // nb1 <= the d doubles reserved for Q1
+        const float* Y = splits ? S_out : S;
+        hipLaunchKernelGGL(qr1_sumsq_kernel, dim3((unsigned)nb1), dim3(256), 0, st, S, splits, nsplit, rp, S_out, d, part);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(qr1_scale_kernel, dim3((unsigned)nb1), dim3(256), 0, st, Y, d, rp, part, nb1, Q, planes, numeric_flag);
+        return hipGetLastError();
+    }
     const int nblk = (int)qr_blocks(d);
     double* Q1 = reinterpret_cast<double*>(workspace);
     double* partial1 = Q1 + d * r;
@@ -425,11 +524,13 @@ hipError_t launch_qr_many(const QrArgs* a, int n, int* numeric_flag, bool refine
     KBatch<QrDev> tb;
     tb.n = 0;
     uint64_t blocks = 0;
-    int rp = 0;
+    int rp = 0, rank1 = -1;
     for (int m = 0; m < n; ++m) {
         if (a[m].d == 0) continue;
         if (rp == 0) rp = a[m].rp;
-        if (a[m].rp != rp) return hipErrorInvalidValue;       // one padded rank per launch
+        if (rank1 < 0) rank1 = (a[m].r == 1);
+        // one padded rank per launch, and single columns (normalised, not factored) apart from the others
+        if (a[m].rp != rp || (a[m].r == 1) != (rank1 == 1)) return hipErrorInvalidValue;
         QrDev q;
         q.S = a[m].S; q.splits = a[m].splits; q.nsplit = a[m].nsplit; q.S_out = a[m].S_out;
         q.Sin = a[m].splits ? a[m].S_out : a[m].S;
@@ -438,11 +539,19 @@ hipError_t launch_qr_many(const QrArgs* a, int n, int* numeric_flag, bool refine
         q.partial1 = q.Q1 + a[m].d * a[m].r;
         q.partial2 = q.partial1 + (size_t)q.nblk * rp * rp;
         q.Q = a[m].Q; q.planes = a[m].planes;
+        if (rank1 == 1) { q.nblk = (int)qr1_blocks(a[m].d); q.partial1 = q.Q1; }
         tb.first[tb.n] = (uint32_t)blocks; tb.gx[tb.n] = (uint32_t)q.nblk; tb.a[tb.n++] = q;
         blocks += (uint64_t)q.nblk;
     }
     if (tb.n == 0) return hipSuccess;
     if (blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    if (rank1 == 1) {
+        hipLaunchKernelGGL(qr1_sumsq_many_kernel, dim3((unsigned)blocks), dim3(256), 0, st, tb, rp);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(qr1_scale_many_kernel, dim3((unsigned)blocks), dim3(256), 0, st, tb, rp, numeric_flag);
+        return hipGetLastError();
+    }
     const size_t sm_full = ((size_t)QR_ROWS * (rp + 1) + (size_t)rp * rp) * sizeof(double);
     static bool attr_set = false;
     if (!attr_set) {

@@ -305,6 +305,50 @@ __global__ __launch_bounds__(256, 2) void update_mfma_many_kernel(const UpdBatch
     sweep_columns<NK>(u.W, u.ldw, u.d_out, u.d_in, u.Gf, u.Bf, u.row_iters, local - by * (uint32_t)u.njb, by);
 }
 
+// ---------------------------------------------------------------------------
+// bf16 storage, r = 1 (the paper's operating point): the perturbation is an outer product g b^T of two vectors, so the
+// sweep is one read-multiply-add-write of W on the vector units with nothing prepared beforehand: a wave owns 16 rows
+// x 512 columns, lane l < 16 regenerates the Gaussian value of row l once and the wave passes it around; a lane keeps
+// its eight basis values in registers and has all 16 row pieces in flight before the first store.  Exact fp32
+// products, one rounding to bf16.
+// ---------------------------------------------------------------------------
+constexpr int U1_ROWS = 16;     // rows per wave
+constexpr int U1_COLS = 512;    // columns per wave (8 per lane)
+
+__global__ __launch_bounds__(256) void update_rank1_bf16_kernel(bf16_t* __restrict__ W, int64_t ldw, int64_t d_out, int64_t d_in,
+                                                                const float* __restrict__ B, uint32_t s_lo, uint32_t s_hi,
+                                                                float lr, float shift, const double* __restrict__ g_dev) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t i0 = ((int64_t)blockIdx.y * 4 + wave) * U1_ROWS;
+    const int64_t jc = (int64_t)blockIdx.x * U1_COLS + 8 * lane;
+    if (i0 >= d_out) return;                               // wave-uniform
+    const float coef = -fmaf(lr, g_dev ? (float)(*g_dev) : 1.0f, shift);
+    float gmine = 0.f;
+    if (lane < U1_ROWS && i0 + lane < d_out) gmine = coef * philox_normal4(s_lo, s_hi, AGZO_TAG_G, (uint32_t)(i0 + lane), 0u).x;
+    const bool col_ok = jc < d_in;                          // d_in is a multiple of 8: the piece is all in or all out
+    float b[8];
+#pragma unroll
+    for (int c = 0; c < 8; ++c) b[c] = col_ok ? B[jc + c] : 0.f;
+    uint4 wv[U1_ROWS];
+#pragma unroll
+    for (int e = 0; e < U1_ROWS; ++e) {
+        wv[e] = make_uint4(0, 0, 0, 0);
+        if (col_ok && i0 + e < d_out) wv[e] = *reinterpret_cast<const uint4*>(W + (i0 + e) * ldw + jc);
+    }
+#pragma unroll
+    for (int e = 0; e < U1_ROWS; ++e) {
+        const float g = __shfl(gmine, e);
+        if (!(col_ok && i0 + e < d_out)) continue;
+        uint32_t* pw = reinterpret_cast<uint32_t*>(&wv[e]);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const float w0 = __uint_as_float(pw[q] << 16), w1 = __uint_as_float(pw[q] & 0xFFFF0000u);
+            pw[q] = pack_bf16x2(w0 + g * b[2 * q], w1 + g * b[2 * q + 1]);
+        }
+        *reinterpret_cast<uint4*>(W + (i0 + e) * ldw + jc) = wv[e];
+    }
+}
+
 size_t update_workspace_bytes(int dtype, int64_t d_out, int64_t d_in, int r) {
     if (dtype != AGZO_BF16) return 0;
     const int64_t nk = (r + 15) / 16;
@@ -361,6 +405,12 @@ hipError_t launch_update(void* W, int dtype, int64_t ldw, int64_t d_out, int64_t
         if (r <= 4) return launch_kc<4>(Wf, ldw, d_out, d_in, B, r, 1, seed, lr, shift, g_dev, st);
         if (r <= 8) return launch_kc<8>(Wf, ldw, d_out, d_in, B, r, 1, seed, lr, shift, g_dev, st);
         return launch_kc<16>(Wf, ldw, d_out, d_in, B, r, (r + 15) / 16, seed, lr, shift, g_dev, st);
+    }
+    if (r == 1) {
+        const dim3 grid((unsigned)((d_in + U1_COLS - 1) / U1_COLS), (unsigned)((d_out + 4 * U1_ROWS - 1) / (4 * U1_ROWS)));
+        hipLaunchKernelGGL(update_rank1_bf16_kernel, grid, dim3(256), 0, st, static_cast<bf16_t*>(W), ldw, d_out, d_in, B,
+                           (uint32_t)seed, (uint32_t)(seed >> 32), lr, shift, g_dev);
+        return hipGetLastError();
     }
     if (!workspace || ldw >= (1LL << 28)) return hipErrorInvalidValue;   // the sweep's lane offsets are 32-bit
     const int nk = (r + 15) / 16;

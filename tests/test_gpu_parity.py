@@ -130,6 +130,7 @@ CASES = [
     ("bf16", 300, 200, 264, 8, "lowrank", 2e-5),
     ("bf16", 600, 1024, 520, 16, "rmsnorm", 2e-5),
     ("bf16", 257, 72, 40, 1, "lowrank", 2e-5),
+    ("bf16", 300, 1096, 1000, 1, "lowrank", 2e-5),      # r = 1 paths: normalisation, rank-1 sweep over three column blocks
     ("bf16", 515, 136, 300, 24, "powerlaw", 2e-5),
     ("bf16", 700, 320, 264, 40, "powerlaw", 2e-5),      # three 16-column blocks in every rank-r kernel
     ("bf16", 450, 192, 520, 64, "rmsnorm", 2e-5),       # the largest rank
@@ -423,6 +424,8 @@ MANY_LAYERS = [
     ("bf16", 200, 4136, 72, 16, "rmsnorm"),      # X Q splits d_in here
     ("bf16", 512, 320, 768, 16, "powerlaw"),     # tile-aligned
     ("f32", 300, 100, 70, 4, "lowrank"),         # fp32 storage: runs layer by layer inside the call
+    ("bf16", 300, 264, 136, 1, "lowrank"),       # a single column: normalised, not factored; rank-1 update sweep
+    ("bf16", 400, 520, 264, 1, "rmsnorm"),
 ]
 
 
