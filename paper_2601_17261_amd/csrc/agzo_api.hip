@@ -561,34 +561,39 @@ int project_many(agzo_ctx* ctx, const std::vector<LayerJob>& jobs) {
 }
 
 // checked items, workspace reserved: the factor fragments of all matrices start at workspace offset `off`.
-// fp32 matrices and rank-1 sweeps one by one (no workspace); other bf16 matrices by padded rank, update_many_max() to a
-// pair of launches
+// fp32 matrices one by one (no workspace); bf16 matrices with r = 1 in rank-1 sweeps of up to kBatchMax per launch (no
+// workspace); the other bf16 matrices by padded rank, update_many_max() to a pair of launches
 int update_many_at(agzo_ctx* ctx, const agzo_update_item* items, int n, size_t off) {
-    for (int nk = 0; nk <= (kMaxRank + 15) / 16; ++nk) {
+    for (int nk = -1; nk <= (kMaxRank + 15) / 16; ++nk) {
         std::vector<UpdateDesc> group;
         size_t group_bytes = 0;
+        const int cap = (nk == 0) ? kBatchMax : update_many_max();
         auto flush = [&]() -> int {
             if (group.empty()) return 0;
             ProfScope ps(ctx, AGZO_PROF_UPDATE);
-            HIPCHK(launch_update_many(group.data(), (int)group.size(), nk, ctx->ws + off, ctx->stream));
-            off += group_bytes;
+            if (nk == 0) {
+                HIPCHK(launch_update_rank1_many(group.data(), (int)group.size(), ctx->stream));
+            } else {
+                HIPCHK(launch_update_many(group.data(), (int)group.size(), nk, ctx->ws + off, ctx->stream));
+                off += group_bytes;
+            }
             group.clear();
             group_bytes = 0;
             return 0;
         };
         for (int m = 0; m < n; ++m) {
             const agzo_update_item& u = items[m];
-            const bool single = (u.dtype == AGZO_F32) || u.r == 1;   // fp32 matrices and rank-1 sweeps: one launch each, no scratch
-            if (nk == 0) {
-                if (!single) continue;
+            if (nk < 0) {
+                if (u.dtype != AGZO_F32) continue;
                 ProfScope ps(ctx, AGZO_PROF_UPDATE);
                 HIPCHK(launch_update(u.W, u.dtype, u.ldw, u.d_out, u.d_in, u.B, u.r, u.seed, u.lr, u.g_dev, nullptr, ctx->stream));
                 continue;
             }
-            if (single || (u.r + 15) / 16 != nk) continue;
+            if (u.dtype != AGZO_BF16) continue;
+            if (nk == 0 ? u.r != 1 : (u.r == 1 || (u.r + 15) / 16 != nk)) continue;
             group.push_back(UpdateDesc{u.W, u.B, u.g_dev, u.ldw, u.d_out, u.d_in, u.seed, u.lr, u.r});
-            group_bytes += update_workspace_bytes(u.dtype, u.d_out, u.d_in, u.r);
-            if ((int)group.size() == update_many_max()) TRY(flush());
+            if (nk > 0) group_bytes += update_workspace_bytes(u.dtype, u.d_out, u.d_in, u.r);
+            if ((int)group.size() == cap) TRY(flush());
         }
         TRY(flush());
     }

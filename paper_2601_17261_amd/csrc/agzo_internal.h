@@ -217,6 +217,8 @@ struct UpdateDesc {
     int r;
 };
 int update_many_max();
+// bf16 matrices with r = 1 (at most kBatchMax): one launch, no scratch
+hipError_t launch_update_rank1_many(const UpdateDesc* d, int n, hipStream_t st);
 hipError_t launch_update_many(const UpdateDesc* d, int n, int nk, void* workspace, hipStream_t st);
 
 // loss.hip

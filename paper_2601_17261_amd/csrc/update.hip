@@ -315,12 +315,12 @@ __global__ __launch_bounds__(256, 2) void update_mfma_many_kernel(const UpdBatch
 constexpr int U1_ROWS = 16;     // rows per wave
 constexpr int U1_COLS = 512;    // columns per wave (8 per lane)
 
-__global__ __launch_bounds__(256) void update_rank1_bf16_kernel(bf16_t* __restrict__ W, int64_t ldw, int64_t d_out, int64_t d_in,
-                                                                const float* __restrict__ B, uint32_t s_lo, uint32_t s_hi,
-                                                                float lr, float shift, const double* __restrict__ g_dev) {
+__device__ __forceinline__ void update_rank1_bf16_body(bf16_t* __restrict__ W, int64_t ldw, int64_t d_out, int64_t d_in,
+                                                       const float* __restrict__ B, uint32_t s_lo, uint32_t s_hi, float lr,
+                                                       float shift, const double* __restrict__ g_dev, uint32_t bx, uint32_t by) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int64_t i0 = ((int64_t)blockIdx.y * 4 + wave) * U1_ROWS;
-    const int64_t jc = (int64_t)blockIdx.x * U1_COLS + 8 * lane;
+    const int64_t i0 = ((int64_t)by * 4 + wave) * U1_ROWS;
+    const int64_t jc = (int64_t)bx * U1_COLS + 8 * lane;
     if (i0 >= d_out) return;                               // wave-uniform
     const float coef = -fmaf(lr, g_dev ? (float)(*g_dev) : 1.0f, shift);
     float gmine = 0.f;
@@ -347,6 +347,23 @@ __global__ __launch_bounds__(256) void update_rank1_bf16_kernel(bf16_t* __restri
         }
         *reinterpret_cast<uint4*>(W + (i0 + e) * ldw + jc) = wv[e];
     }
+}
+
+__global__ __launch_bounds__(256) void update_rank1_bf16_kernel(bf16_t* __restrict__ W, int64_t ldw, int64_t d_out, int64_t d_in,
+                                                                const float* __restrict__ B, uint32_t s_lo, uint32_t s_hi,
+                                                                float lr, float shift, const double* __restrict__ g_dev) {
+    update_rank1_bf16_body(W, ldw, d_out, d_in, B, s_lo, s_hi, lr, shift, g_dev, blockIdx.x, blockIdx.y);
+}
+
+struct U1Dev {
+    bf16_t* W; int64_t ldw, d_out, d_in;
+    const float* B; const double* g_dev;
+    uint32_t s_lo, s_hi; float lr;
+};
+__global__ __launch_bounds__(256) void update_rank1_bf16_many_kernel(const KBatch<U1Dev> tb) {
+    uint32_t bx, by;
+    const U1Dev& a = tb.a[kbatch_find(tb, bx, by)];
+    update_rank1_bf16_body(a.W, a.ldw, a.d_out, a.d_in, a.B, a.s_lo, a.s_hi, a.lr, 0.f, a.g_dev, bx, by);
 }
 
 size_t update_workspace_bytes(int dtype, int64_t d_out, int64_t d_in, int r) {
@@ -433,6 +450,28 @@ hipError_t launch_update(void* W, int dtype, int64_t ldw, int64_t d_out, int64_t
 
 // bf16 matrices of one padded rank (nk = ceil(r / 16) the same for all), at most UPD_MAX of them: one preparation
 // launch and one sweep for the lot.  The workspace holds the fragments of all of them back to back.
+// bf16 matrices with r = 1, at most kBatchMax: one launch of the rank-1 sweep for all of them (no scratch)
+hipError_t launch_update_rank1_many(const UpdateDesc* d, int n, hipStream_t st) {
+    if (n < 0 || n > kBatchMax) return hipErrorInvalidValue;
+    KBatch<U1Dev> tb;
+    tb.n = 0;
+    uint64_t blocks = 0;
+    for (int m = 0; m < n; ++m) {
+        if (d[m].d_out == 0 || d[m].d_in == 0) continue;
+        if (d[m].r != 1) return hipErrorInvalidValue;
+        const uint32_t gx = (uint32_t)((d[m].d_in + U1_COLS - 1) / U1_COLS);
+        const uint64_t gy = (uint64_t)((d[m].d_out + 4 * U1_ROWS - 1) / (4 * U1_ROWS));
+        tb.first[tb.n] = (uint32_t)blocks; tb.gx[tb.n] = gx;
+        tb.a[tb.n++] = U1Dev{static_cast<bf16_t*>(d[m].W), d[m].ldw, d[m].d_out, d[m].d_in, d[m].B, d[m].g_dev,
+                             (uint32_t)d[m].seed, (uint32_t)(d[m].seed >> 32), d[m].lr};
+        blocks += gx * gy;
+    }
+    if (tb.n == 0) return hipSuccess;
+    if (blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(update_rank1_bf16_many_kernel, dim3((unsigned)blocks), dim3(256), 0, st, tb);
+    return hipGetLastError();
+}
+
 hipError_t launch_update_many(const UpdateDesc* d, int n, int nk, void* workspace, hipStream_t st) {
     if (n < 1 || n > UPD_MAX || !workspace) return hipErrorInvalidValue;
     UpdBatch tb;

@@ -299,7 +299,8 @@ def _update_set(n_small):
     a matrix inside a wider allocation, ragged row and column tails, and n_small equal small ones to overflow a batch."""
     base = [("bf16", 264, 200, 8, None, -0.731), ("bf16", 40, 72, 1, None, None), ("bf16", 520, 1024, 16, None, 0.4),
             ("bf16", 300, 136, 24, None, 1.7), ("bf16", 520, 192, 64, None, -0.2), ("f32", 70, 100, 4, None, 0.9),
-            ("bf16", 130, 264, 40, 272, 0.55), ("bf16", 1, 8, 3, None, -1.0)]
+            ("bf16", 130, 264, 40, 272, 0.55), ("bf16", 1, 8, 3, None, -1.0),
+            ("bf16", 1000, 1096, 1, 1104, 0.3)]        # rank-1 sweeps share a launch of their own
     return base + [("bf16", 96 + 8 * i, 256 + 8 * i, 16, None, 0.1 * (i + 1)) for i in range(n_small)]
 
 
