@@ -47,7 +47,13 @@ __device__ __forceinline__ void wait_vmcnt_dyn(int n) {
 }
 
 // bx: token block, by / ny: this workgroup's share of d_in (ny = 1: all of it)
-template <int NB>
+// ring depth: DEEP = one workgroup per CU with as many slices in flight as LDS holds; otherwise a shallower ring that
+// lets two workgroups share a CU, for launches with at least two workgroups per CU (several layers at once): while one
+// waits at its barrier or on its fragment reads the other multiplies
+template <int NB, bool DEEP>
+struct XqRing { static constexpr int STAGES = DEEP ? ((NB == 1) ? 8 : (NB == 2) ? 6 : 4) : ((NB == 1) ? 5 : (NB == 2) ? 3 : 4); };
+
+template <int NB, bool DEEP>
 __device__ __forceinline__ void xq_bf16_body(const bf16_t* __restrict__ X, int64_t ldx, int64_t M, int64_t K,
                                              const bf16_t* __restrict__ Qpack, int r, float* __restrict__ T,
                                              bf16_t* __restrict__ TpackT, int64_t m_pad, float* __restrict__ part,
@@ -56,7 +62,7 @@ __device__ __forceinline__ void xq_bf16_body(const bf16_t* __restrict__ X, int64
     constexpr int QROWS = 3 * RP;                          // plane rows: (plane, k)
     constexpr int NGROUP = XQ_TOK / 8 + QROWS / 8;         // 8-row groups per slice: X first, then the planes
     constexpr int SLOT = (XQ_TOK + QROWS) * 128;           // bytes per ring slot
-    constexpr int STAGES = (NB == 1) ? 8 : (NB == 2) ? 6 : 4;
+    constexpr int STAGES = XqRing<NB, DEEP>::STAGES;
     extern __shared__ __align__(16) char xq_smem[];
     typedef __attribute__((address_space(3))) void* lptr_t;
     typedef const __attribute__((address_space(1))) void* gptr_t;
@@ -210,7 +216,7 @@ template <int NB>
 __global__ __launch_bounds__(256) void xq_bf16_kernel(const bf16_t* __restrict__ X, int64_t ldx, int64_t M, int64_t K,
                                                       const bf16_t* __restrict__ Qpack, int r, float* __restrict__ T,
                                                       bf16_t* __restrict__ TpackT, int64_t m_pad, float* __restrict__ part) {
-    xq_bf16_body<NB>(X, ldx, M, K, Qpack, r, T, TpackT, m_pad, part, blockIdx.x, blockIdx.y, gridDim.y);
+    xq_bf16_body<NB, true>(X, ldx, M, K, Qpack, r, T, TpackT, m_pad, part, blockIdx.x, blockIdx.y, gridDim.y);
 }
 
 // several products per launch (the layers of a model): what one launch of the kernel above needs, per product
@@ -220,11 +226,11 @@ struct XqDev {
     float* T; bf16_t* TpackT; int64_t m_pad; float* part;   // part: NULL unless ns > 1
     int ns; int64_t rows;
 };
-template <int NB>
+template <int NB, bool DEEP>
 __global__ __launch_bounds__(256) void xq_bf16_many_kernel(const KBatch<XqDev> tb) {
     uint32_t bx, by;
     const XqDev& a = tb.a[kbatch_find(tb, bx, by)];
-    xq_bf16_body<NB>(a.X, a.ldx, a.M, a.K, a.Qpack, a.r, a.T, a.TpackT, a.m_pad, a.part, bx, by, (uint32_t)a.ns);
+    xq_bf16_body<NB, DEEP>(a.X, a.ldx, a.M, a.K, a.Qpack, a.r, a.T, a.TpackT, a.m_pad, a.part, bx, by, (uint32_t)a.ns);
 }
 
 // sums the d_in splits of xq in fixed order and writes what the unsplit kernel's epilogue writes; one thread per (t, k)
@@ -293,19 +299,24 @@ static hipError_t launch_xq_nb(dim3 grid, hipStream_t st, const bf16_t* X, int64
     return hipGetLastError();
 }
 
-template <int NB>
-static hipError_t launch_xq_many_nb(const KBatch<XqDev>& tb, unsigned blocks, hipStream_t st) {
-    constexpr int stages = (NB == 1) ? 8 : (NB == 2) ? 6 : 4;
-    const int smem = stages * (XQ_TOK + 3 * NB * 16) * 128;
+template <int NB, bool DEEP>
+static hipError_t launch_xq_many_ring(const KBatch<XqDev>& tb, unsigned blocks, hipStream_t st) {
+    const int smem = XqRing<NB, DEEP>::STAGES * (XQ_TOK + 3 * NB * 16) * 128;
     static bool set = false;
     if (!set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(xq_bf16_many_kernel<NB>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(xq_bf16_many_kernel<NB, DEEP>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, smem);
         if (e != hipSuccess) return e;
         set = true;
     }
-    hipLaunchKernelGGL(xq_bf16_many_kernel<NB>, dim3(blocks), dim3(256), smem, st, tb);
+    hipLaunchKernelGGL((xq_bf16_many_kernel<NB, DEEP>), dim3(blocks), dim3(256), smem, st, tb);
     return hipGetLastError();
+}
+template <int NB>
+static hipError_t launch_xq_many_nb(const KBatch<XqDev>& tb, unsigned blocks, hipStream_t st) {
+    // (the result does not depend on the ring's depth: same slices, same order)
+    if (NB <= 2 && blocks >= 512) return launch_xq_many_ring<NB, false>(tb, blocks, st);
+    return launch_xq_many_ring<NB, true>(tb, blocks, st);
 }
 
 hipError_t launch_xq_bf16_many(const XqArgs* a, int n, hipStream_t st) {

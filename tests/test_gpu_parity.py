@@ -477,6 +477,29 @@ def test_basis_many_more_layers_than_one_launch_holds(ctx):
         assert torch.equal(it[4], B1), li
 
 
+@pytest.mark.parametrize("r", [8, 24])
+def test_basis_many_with_two_workgroups_per_cu(ctx, r):
+    """Enough token blocks in one launch (>= 512) for the shallower load ring that lets two workgroups share a CU: the
+    same slices in the same order, so still the per-layer call's bits."""
+    rng = np.random.default_rng(9)
+    X = dev(synth.x_rmsnorm_gaussian(rng, 2048, 264, storage="bf16"), "bf16")
+    items, want = [], []
+    for li in range(16):
+        L = binding.make_layer(None, X, r, d_out=8)
+        B1 = torch.empty(264, r, dtype=torch.float32, device="cuda")
+        if li < 3:
+            ctx.basis(L, X, 2, 500 + li, None, 0, B1)
+            want.append(B1)
+        items.append((L, X, 500 + li, None, torch.zeros_like(B1)))
+    ctx.basis_many(items, 2)
+    ctx.check()
+    for li, B1 in enumerate(want):
+        assert torch.equal(items[li][4], B1), li
+    Bo = oagzo.subspace_extract(host(X), r, 2, 515)["B"]
+    Bg = host(items[15][4])
+    assert np.linalg.norm(Bg @ Bg.T - Bo @ Bo.T) / np.sqrt(r) < 2e-3
+
+
 @pytest.mark.parametrize("flags", [0, binding.ONE_SIDED, binding.SHARED_FORWARD, binding.INIT_FEATURE])
 def test_step_many_is_bit_identical_to_steps(ctx, flags):
     probs = []
