@@ -9,7 +9,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(ROOT, "_build")
 LIB = os.path.join(PKG, "libagzo.so")
-SOURCES = ["philox.hip", "gemm_f32.hip", "gemm_bf16.hip", "gemm_bf16_mse.hip", "gemm_bf16_small.hip", "skinny.hip", "qr.hip", "update.hip", "loss.hip", "glue.hip",
+SOURCES = ["philox.hip", "gemm_f32.hip", "gemm_bf16.hip", "gemm_bf16_aligned.hip", "gemm_bf16_small.hip", "skinny.hip", "qr.hip", "update.hip", "loss.hip", "glue.hip",
            "probe.hip", "agzo_api.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # packed-fp32 VALU forms are switched off for every device compile (some forms have misbehaved

@@ -36,7 +36,8 @@ int gemm_bf16_num_workgroups(int64_t M, int64_t N, bool small_ok) {
 
 // WA x WB waves: WA splits the 256 outputs, WB splits the 256 tokens
 // EPI selects the epilogue compiled into the kernel: 0 = general (stores, squared error, any bounds), 1 = cross-entropy
-// statistics.  (Tile-aligned layers with the squared-error loss and no stored Y take the kernel of gemm_bf16_mse.hip.)
+// statistics.  (Tile-aligned layers with the squared-error loss and no stored Y, or a stored bf16 Y and no loss, take the kernel of
+// gemm_bf16_aligned.hip.)
 template <int WA, int WB, bool SHARED, int EPI>
 __global__ __launch_bounds__(64 * WA * WB) void gemm_bf16_kernel(GemmParams p) {
     constexpr bool CE = (EPI == 1);
@@ -647,9 +648,11 @@ hipError_t launch_gemm_bf16(const GemmBf16Args& a, hipStream_t st) {
     p.shared = a.shared ? 1 : 0;
     p.Xext = nullptr; p.Wext = nullptr; p.Wext2 = nullptr; p.ext_ld = 0;
     const bool small = small_shape(a.M, a.N) && !a.large_tiles && !a.shared && p.loss_kind != AGZO_LOSS_CE;
-    // the squared-error kernel of gemm_bf16_mse.hip takes tile-aligned layers (also in shared-forward mode)
-    const bool mse = !small && a.loss.kind == AGZO_LOSS_MSE && !a.Y && vec && a.M % BT == 0 && a.N % BT == 0 &&
-                     a.K % BK == 0 && a.K >= 2 * BK && (!a.P || a.ext_ws);
+    // the kernel of gemm_bf16_aligned.hip takes tile-aligned layers: squared error without a stored Y (also in
+    // shared-forward mode), or a stored bf16 Y without a loss
+    const bool aligned_shape = !small && vec && a.M % BT == 0 && a.N % BT == 0 && a.K % BK == 0 && a.K >= 2 * BK && (!a.P || a.ext_ws);
+    const bool mse = aligned_shape && ((a.loss.kind == AGZO_LOSS_MSE && !a.Y) ||
+                                       (a.loss.kind == AGZO_LOSS_NONE && a.Y && a.y_dtype == AGZO_BF16 && !a.shared));
     if (a.P && a.ext_ws && (!a.shared || mse)) {
         p.ext_ld = (3 * p.rp + BK - 1) / BK * BK;
         bf16_t* xe = static_cast<bf16_t*>(a.ext_ws);
@@ -674,7 +677,7 @@ hipError_t launch_gemm_bf16(const GemmBf16Args& a, hipStream_t st) {
         p.tiles_n = (int)((a.N + BT_SMALL - 1) / BT_SMALL);
         return launch_gemm_bf16_small(p, st);
     }
-    if (mse) return launch_gemm_bf16_mse(p, st);
+    if (mse) return launch_gemm_bf16_aligned(p, st);
     const bool ce = p.loss_kind == AGZO_LOSS_CE;
     if (p.shared) return ce ? launch_variant<2, 2, true, 1>(p, st) : launch_variant<2, 2, true, 0>(p, st);
     return ce ? launch_variant<2, 2, false, 1>(p, st) : launch_variant<2, 2, false, 0>(p, st);

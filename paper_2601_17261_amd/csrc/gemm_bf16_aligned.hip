@@ -1,10 +1,12 @@
-// Forward GEMM with the squared-error loss for tile-aligned layers, the case the benchmark configuration runs:
-//     f = sum over the tile of (X W^T (+ eps (X B) G^T) - Y*)^2        (f0, f+, f- of Sec. 4.1; Eq. 7 factored)
+// Forward GEMM for tile-aligned layers, the case the benchmark configurations run:
+//     OUT = 0:  f = sum over the tile of (X W^T (+ eps (X B) G^T) - Y*)^2     (f0, f+, f- of Sec. 4.1; Eq. 7 factored)
+//     OUT = 1:  Y = X W^T (+ eps (X B) G^T) stored as bf16                     (a layer inside a model, Alg. 2)
 // Same tiling, LDS layout, direct global -> LDS operand loads and fixed-order steady state as gemm_bf16.hip (256 x 256
 // tile, four waves of 128 x 128, v_mfma_f32_32x32x16_bf16, 64-wide K slices, two LDS stages), but a kernel of its own
 // with one straight path and nothing else compiled in: M and N multiples of 256, d_in a multiple of 64 and at least
-// 128, no stored Y, 16-byte aligned target rows, the rank-r extension as prepared operands.
+// 128, 16-byte aligned target / output rows, the rank-r extension as prepared operands.
 //
+// Squared error (OUT = 0).
 // The accumulators do not start at zero but at minus the target tile: the target is requested before the first
 // operand slice and converted while that slice is on its way, so after the last slice the registers hold the residual
 // Y - Y* and the epilogue is a sum of squares of registers with no memory access.  (Reading the target in the epilogue
@@ -29,8 +31,9 @@ __device__ __forceinline__ float to_acc(float x) {
     return r;
 }
 
-template <bool T_F32, int PHASES>
-__global__ __launch_bounds__(256) void gemm_bf16_mse_kernel(GemmParams p) {
+template <int OUT, bool T_F32, int PHASES>
+__global__ __launch_bounds__(256) void gemm_bf16_aligned_kernel(GemmParams p) {
+    static_assert(OUT == 0 || (PHASES == 1 && !T_F32), "the storing kernel has one evaluation and no target");
     constexpr int NT = 256, BA = 4, BB = 4;
     extern __shared__ __align__(16) char smem[];
     const int tid = threadIdx.x, lane = tid & 63;
@@ -243,19 +246,30 @@ __global__ __launch_bounds__(256) void gemm_bf16_mse_kernel(GemmParams p) {
     };
 
     // ---- the tile -----------------------------------------------------------------------------------
-    tload(IC<0>{}); tload(IC<1>{});
-    if (!T_F32) { tload(IC<2>{}); tload(IC<3>{}); }
+    if constexpr (OUT == 0) {
+        tload(IC<0>{}); tload(IC<1>{});
+        if (!T_F32) { tload(IC<2>{}); tload(IC<3>{}); }
+    }
     select_slice(IC<0>{}, 0);
 #pragma unroll
     for (int q = 0; q < 16; ++q) dma1(IC<0>{}, 0, q);
     select_slice(IC<1>{}, 1);
 #pragma unroll
     for (int q = 0; q < N3; ++q) dma1(IC<1>{}, 1, q);
-    tneg(IC<0>{}); tneg(IC<1>{});
-    if (T_F32) { tload(IC<2>{}); tload(IC<3>{}); }
-    tneg(IC<2>{}); tneg(IC<3>{});
-    if (T_F32) __builtin_amdgcn_s_waitcnt(0x0F70);           // the second half of an fp32 target was requested last
-    else __builtin_amdgcn_s_waitcnt(0x0F70 | N3);            // vmcnt(N3): slice 0 has landed
+    if constexpr (OUT == 0) {
+        tneg(IC<0>{}); tneg(IC<1>{});
+        if (T_F32) { tload(IC<2>{}); tload(IC<3>{}); }
+        tneg(IC<2>{}); tneg(IC<3>{});
+    } else {
+#pragma unroll
+        for (int i = 0; i < BA; ++i)
+#pragma unroll
+            for (int j = 0; j < BB; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+    }
+    if (OUT == 0 && T_F32) __builtin_amdgcn_s_waitcnt(0x0F70);   // the second half of an fp32 target was requested last
+    else __builtin_amdgcn_s_waitcnt(0x0F70 | N3);                // vmcnt(N3): slice 0 has landed
     __syncthreads();
 #pragma unroll
     for (int q = 0; q < 8; ++q) frag1(0, 0, 0, q);
@@ -263,7 +277,23 @@ __global__ __launch_bounds__(256) void gemm_bf16_mse_kernel(GemmParams p) {
     __builtin_amdgcn_s_waitcnt(0x0F70);                      // the re-fetches
     multiply_slice((npipe - 1) & 1, false);                  // last pipelined slice: sub-step 0 is already in set 0
     __syncthreads();
-    if constexpr (PHASES == 1) {
+    if constexpr (OUT == 1) {
+        // lane = one token, 16 consecutive outputs per block: two 16-byte stores each
+#pragma clang loop unroll(full)
+        for (int j = 0; j < BB; ++j) {
+            bf16_t* yrow = reinterpret_cast<bf16_t*>(p.Y) + (m0 + wb * 128 + j * 32 + lr) * p.ldy + n0 + wa * 128 + lh * 16;
+#pragma clang loop unroll(full)
+            for (int i = 0; i < BA; ++i) {
+                const floatx16 v = acc[i][j];
+                uint32_t w[8];
+#pragma clang loop unroll(full)
+                for (int q = 0; q < 8; ++q) w[q] = pack_bf16x2(v[2 * q], v[2 * q + 1]);
+                uint4* dst = reinterpret_cast<uint4*>(yrow + i * 32);
+                dst[0] = make_uint4(w[0], w[1], w[2], w[3]);
+                dst[1] = make_uint4(w[4], w[5], w[6], w[7]);
+            }
+        }
+    } else if constexpr (PHASES == 1) {
         evaluate(0);
     } else {
         // both LDS stages are free: the first extension slice of each perturbed evaluation is requested before the
@@ -310,32 +340,33 @@ __global__ __launch_bounds__(256) void gemm_bf16_mse_kernel(GemmParams p) {
     if (p.clk && blockIdx.x == 0 && tid == 0) { p.clk[2] = __builtin_readcyclecounter(); p.clk[3] = wall_clock64(); }
 }
 
-template <bool T_F32, int PHASES>
-static hipError_t launch_mse_variant(const GemmParams& p, hipStream_t st) {
+template <int OUT, bool T_F32, int PHASES>
+static hipError_t launch_aligned_variant(const GemmParams& p, hipStream_t st) {
     static bool attr_set = false;
     const int smem = 4 * TILE_BYTES + 256 * (int)sizeof(double);
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_bf16_mse_kernel<T_F32, PHASES>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_bf16_aligned_kernel<OUT, T_F32, PHASES>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, smem);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     dim3 grid((unsigned)((int64_t)p.tiles_m * p.tiles_n));
-    hipLaunchKernelGGL((gemm_bf16_mse_kernel<T_F32, PHASES>), grid, dim3(256), smem, st, p);
+    hipLaunchKernelGGL((gemm_bf16_aligned_kernel<OUT, T_F32, PHASES>), grid, dim3(256), smem, st, p);
     return hipGetLastError();
 }
 
-bool gemm_bf16_mse_supported(const GemmParams& p) {
-    return p.loss_kind == AGZO_LOSS_MSE && p.Y == nullptr && p.vec_ok && p.M % BT == 0 && p.N % BT == 0 &&
-           p.K % BK == 0 && p.K >= 2 * BK && (p.P == nullptr || p.Xext != nullptr) &&
-           (!p.shared || p.Wext2 != nullptr);
-}
-
-hipError_t launch_gemm_bf16_mse(const GemmParams& p, hipStream_t st) {
-    if (!gemm_bf16_mse_supported(p)) return hipErrorInvalidValue;
+hipError_t launch_gemm_bf16_aligned(const GemmParams& p, hipStream_t st) {
+    const bool shape_ok = p.vec_ok && p.M % BT == 0 && p.N % BT == 0 && p.K % BK == 0 && p.K >= 2 * BK &&
+                          (p.P == nullptr || p.Xext != nullptr);
+    if (!shape_ok) return hipErrorInvalidValue;
+    if (p.Y != nullptr) {       // stored output, no loss
+        if (p.loss_kind != AGZO_LOSS_NONE || p.y_dtype != AGZO_BF16 || p.shared) return hipErrorInvalidValue;
+        return launch_aligned_variant<1, false, 1>(p, st);
+    }
+    if (p.loss_kind != AGZO_LOSS_MSE || (p.shared && p.Wext2 == nullptr)) return hipErrorInvalidValue;
     const bool f32 = p.target_dtype != AGZO_BF16;
-    if (p.shared) return f32 ? launch_mse_variant<true, 3>(p, st) : launch_mse_variant<false, 3>(p, st);
-    return f32 ? launch_mse_variant<true, 1>(p, st) : launch_mse_variant<false, 1>(p, st);
+    if (p.shared) return f32 ? launch_aligned_variant<0, true, 3>(p, st) : launch_aligned_variant<0, false, 3>(p, st);
+    return f32 ? launch_aligned_variant<0, true, 1>(p, st) : launch_aligned_variant<0, false, 1>(p, st);
 }
 
 }  // namespace agzo

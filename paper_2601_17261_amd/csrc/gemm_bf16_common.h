@@ -50,9 +50,9 @@ struct GemmParams {
 constexpr int BT_SMALL = 128;
 hipError_t launch_gemm_bf16_small(const GemmParams& p, hipStream_t st);
 
-// squared-error kernel for tile-aligned layers (gemm_bf16_mse.hip): M, N multiples of 256, d_in a multiple of 64 and
-// >= 128, no stored Y, 16-byte target accesses, the rank-r term as prepared operands; p.shared: f0, f+, f- in one pass
-// (needs Wext2), partials [3][tiles]
-hipError_t launch_gemm_bf16_mse(const GemmParams& p, hipStream_t st);
+// kernel for tile-aligned layers (gemm_bf16_aligned.hip): M, N multiples of 256, d_in a multiple of 64 and >= 128,
+// 16-byte target / output accesses, the rank-r term as prepared operands; either the squared-error loss without a
+// stored Y (p.shared: f0, f+, f- in one pass, needs Wext2, partials [3][tiles]) or a bf16 Y without a loss
+hipError_t launch_gemm_bf16_aligned(const GemmParams& p, hipStream_t st);
 
 }  // namespace agzo
