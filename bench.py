@@ -653,8 +653,8 @@ def main():
     res["roofline_generator"] = {"bound": "hbm", "kernel": "fill_normal_kernel", "achieved": fill_gbs, "peak": PEAK_HBM_GBS,
                                  "unit": "GB/s", "frac": fill_gbs / PEAK_HBM_GBS, "launches": n_fill,
                                  "normals_per_s": fill_gbs * 1e9 / 4.0,
-                                 "note": "4 bytes written per value; about 60 VALU issue slots per value (Philox4x32-10 "
-                                         "+ Box-Muller), so the ALU bound is of the same order as the write bound"}
+                                 "note": "4 bytes written per value; 68 vector instructions per value (Philox4x32-10 + "
+                                         "Box-Muller; profiles/generator_valu_instructions.txt): bound by its arithmetic"}
     # the dense Gaussian sweep of Eq. 7's other branch on a bf16 block of the same size (read + write 2 bytes each)
     theta = gbuf.view(torch.bfloat16)[:, :16]
     theta.zero_()
