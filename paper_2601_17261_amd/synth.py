@@ -182,3 +182,48 @@ def device_mlp_stack(seed, n_blocks, hidden, inter, vocab, n_seq, seq_len, emb_r
     params[("head", 0)] = (torch.randn(vocab, hidden, **f32) * 0.02).to(torch.bfloat16)
     ids = torch.randint(0, vocab, (n_seq, seq_len), device=device, generator=gen)
     return params, ids
+
+
+DECODER_PROJECTIONS = ("q", "k", "v", "o", "gate", "up", "down")
+
+
+def decoder_shapes(hidden, n_heads, n_kv_heads, inter, head_dim=128):
+    """(d_out, d_in) of the seven projections of one decoder layer."""
+    return {"q": (n_heads * head_dim, hidden), "k": (n_kv_heads * head_dim, hidden), "v": (n_kv_heads * head_dim, hidden),
+            "o": (hidden, n_heads * head_dim), "gate": (inter, hidden), "up": (inter, hidden), "down": (hidden, inter)}
+
+
+def decoder_problem(seed, n_layers, hidden, n_heads, n_kv_heads, inter, vocab, n_seq, seq_len, emb_rank=16):
+    """Weights and token ids of a small decoder-style transformer (grouped-query attention with 128-wide heads, gated
+    MLP, LM head): bf16-exact values, W ~ N(0, 0.02^2), embedding as in mlp_stack_problem."""
+    rng = np.random.default_rng(seed)
+    A = rng.standard_normal((vocab, emb_rank))
+    C = rng.standard_normal((emb_rank, hidden))
+    E = (A * np.logspace(0.0, -1.0, emb_rank)[None, :]) @ C + 0.3 * rng.standard_normal((vocab, hidden))
+    E /= np.sqrt(np.mean(E * E))
+    params = {"n_layers": n_layers, "n_heads": n_heads, "n_kv_heads": n_kv_heads, "E": to_bf16_values(E)}
+    shapes = decoder_shapes(hidden, n_heads, n_kv_heads, inter)
+    for l in range(n_layers):
+        for p in DECODER_PROJECTIONS:
+            params[(p, l)] = weights(rng, shapes[p][0], shapes[p][1], storage="bf16")
+    params[("head", 0)] = weights(rng, vocab, hidden, storage="bf16")
+    ids = rng.integers(0, vocab, size=(n_seq, seq_len), dtype=np.int64)
+    return params, ids
+
+
+def device_decoder(seed, n_layers, hidden, n_heads, n_kv_heads, inter, vocab, n_seq, seq_len, emb_rank=16, device="cuda"):
+    """The decoder workload at any size, generated on the device (same recipe as decoder_problem)."""
+    gen = torch.Generator(device=device)
+    gen.manual_seed(int(seed))
+    f32 = dict(device=device, dtype=torch.float32, generator=gen)
+    A = torch.randn(vocab, emb_rank, **f32) * torch.logspace(0.0, -1.0, emb_rank, device=device)[None, :]
+    E = A @ torch.randn(emb_rank, hidden, **f32) + 0.3 * torch.randn(vocab, hidden, **f32)
+    E /= E.square().mean().sqrt()
+    params = {"n_layers": n_layers, "n_heads": n_heads, "n_kv_heads": n_kv_heads, "E": E.to(torch.bfloat16)}
+    shapes = decoder_shapes(hidden, n_heads, n_kv_heads, inter)
+    for l in range(n_layers):
+        for p in DECODER_PROJECTIONS:
+            params[(p, l)] = (torch.randn(shapes[p][0], shapes[p][1], **f32) * 0.02).to(torch.bfloat16)
+    params[("head", 0)] = (torch.randn(vocab, hidden, **f32) * 0.02).to(torch.bfloat16)
+    ids = torch.randint(0, vocab, (n_seq, seq_len), device=device, generator=gen)
+    return params, ids
