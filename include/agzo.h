@@ -240,7 +240,16 @@ int agzo_step_no_update(agzo_ctx* ctx, const agzo_layer* L, void* W, const void*
  *   rmsnorm: y[t] = gain * x[t] / sqrt(mean(x[t]^2) + eps)   (gain: device fp32 [d], NULL = 1; y may alias x)
  *   swiglu : m = silu(a) * u, silu(z) = z / (1 + exp(-z))     (m may alias a or u)
  *   add    : h += delta in place
- * Errors: AGZO_EINVAL for NULL or misaligned tensors, d % 8 != 0, leading dimensions below d. */
+ *   attention: the core of a decoder layer between its q / k / v projections and its o projection: grouped-query causal
+ *            attention with 128-wide heads, queries and keys RMS-normalised per head (gain 1, eps 1e-6) and rotated by
+ *            the rotary embedding (pairs (i, i + 64) of a head by the angle t rope_theta^(-2i/128), t the position inside
+ *            the sequence), scores scaled by 1/sqrt(128), softmax in fp32, probabilities rounded to bf16 for the second
+ *            product.  q [N][n_heads 128], k and v [N][n_kv_heads 128], out [N][n_heads 128], N = n_seq seq_len tokens,
+ *            the sequences back to back; n_heads a multiple of n_kv_heads.  Uses (and may grow) the context's workspace.
+ * Errors: AGZO_EINVAL for NULL or misaligned tensors, d % 8 != 0, leading dimensions below d, a bad attention shape. */
+int agzo_glue_attention(agzo_ctx* ctx, const void* q, int64_t ldq, const void* k, int64_t ldk, const void* v, int64_t ldv,
+                        void* out, int64_t ldo, int32_t n_seq, int32_t seq_len, int32_t n_heads, int32_t n_kv_heads,
+                        float rope_theta);
 int agzo_glue_rmsnorm(agzo_ctx* ctx, const void* x, int64_t ldx, void* y, int64_t ldy, const float* gain, int64_t n, int64_t d,
                       float eps);
 int agzo_glue_swiglu(agzo_ctx* ctx, const void* a, int64_t lda, const void* u, int64_t ldu, void* m, int64_t ldm, int64_t n,

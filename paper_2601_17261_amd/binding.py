@@ -28,7 +28,7 @@ EXPORTS = ["agzo_create", "agzo_destroy", "agzo_last_error", "agzo_check", "agzo
            "agzo_profile_read", "agzo_profile_clock", "agzo_probe_mfma", "agzo_philox_words", "agzo_fill_normal",
            "agzo_layer_forward_sketch", "agzo_qr", "agzo_basis", "agzo_perturbed_forward", "agzo_two_point", "agzo_dense_perturb", "agzo_update", "agzo_update_noalloc",
            "agzo_update_many", "agzo_step", "agzo_step_no_update", "agzo_basis_many", "agzo_step_many",
-           "agzo_glue_rmsnorm", "agzo_glue_swiglu", "agzo_glue_add"]
+           "agzo_glue_rmsnorm", "agzo_glue_swiglu", "agzo_glue_add", "agzo_glue_attention"]
 
 
 class AgzoLayer(ctypes.Structure):
@@ -107,6 +107,7 @@ def load():
     lib.agzo_glue_rmsnorm.argtypes = [vp, vp, i64, vp, i64, vp, i64, i64, f32]
     lib.agzo_glue_swiglu.argtypes = [vp, vp, i64, vp, i64, vp, i64, i64, i64]
     lib.agzo_glue_add.argtypes = [vp, vp, i64, vp, i64, i64, i64]
+    lib.agzo_glue_attention.argtypes = [vp, vp, i64, vp, i64, vp, i64, vp, i64, i32, i32, i32, i32, f32]
     lib.agzo_step.argtypes = [vp, lp, vp, vp, sp, i32, f32, f32, u64, i32, vp]
     lib.agzo_step_no_update.argtypes = [vp, lp, vp, vp, sp, i32, f32, u64, i32, vp, vp]
     for name in EXPORTS:
@@ -307,6 +308,11 @@ class Context:
     def glue_add(self, h, delta):
         n, d = h.shape
         self._rc(self.lib.agzo_glue_add(self.h, _ptr(h), h.stride(0), _ptr(delta), delta.stride(0), n, d))
+
+    def glue_attention(self, q, k, v, out, n_seq, seq_len, rope_theta=1.0e6):
+        n_heads, n_kv = q.shape[1] // 128, k.shape[1] // 128
+        self._rc(self.lib.agzo_glue_attention(self.h, _ptr(q), q.stride(0), _ptr(k), k.stride(0), _ptr(v), v.stride(0),
+                                              _ptr(out), out.stride(0), n_seq, seq_len, n_heads, n_kv, rope_theta))
 
     def step_no_update(self, L, W, X, loss, K, eps, seed, flags, out_dev, B_out):
         self._rc(self.lib.agzo_step_no_update(self.h, ctypes.byref(L), _ptr(W), _ptr(X), ctypes.byref(loss), K, eps,

@@ -1014,6 +1014,24 @@ int agzo_glue_swiglu(agzo_ctx* ctx, const void* a, int64_t lda, const void* u, i
     return AGZO_OK;
 }
 
+int agzo_glue_attention(agzo_ctx* ctx, const void* q, int64_t ldq, const void* k, int64_t ldk, const void* v, int64_t ldv,
+                        void* out, int64_t ldo, int32_t n_seq, int32_t seq_len, int32_t n_heads, int32_t n_kv_heads,
+                        float rope_theta) {
+    if (!ctx) return AGZO_EINVAL;
+    if (n_seq < 0 || seq_len < 0 || n_heads < 1 || n_kv_heads < 1 || n_heads % n_kv_heads || n_heads > 65535 || n_seq > 65535)
+        return fail(ctx, AGZO_EINVAL, "bad attention shape: %d sequences of %d tokens, %d heads on %d kv heads", n_seq, seq_len, n_heads,
+                    n_kv_heads);
+    if (!(rope_theta > 1.f)) return fail(ctx, AGZO_EINVAL, "rope_theta must exceed 1");
+    const int64_t n = (int64_t)n_seq * seq_len, dq = (int64_t)n_heads * 128, dkv = (int64_t)n_kv_heads * 128;
+    TRY(check_glue(ctx, n, dq, {q, out}, {ldq, ldo}));
+    TRY(check_glue(ctx, n, dkv, {k, v}, {ldk, ldv}));
+    if (n == 0) return AGZO_OK;
+    TRY(reserve(ctx, glue_attention_workspace_bytes(n_seq, seq_len, n_heads, n_kv_heads)));
+    HIPCHK(launch_glue_attention(static_cast<const bf16_t*>(q), ldq, static_cast<const bf16_t*>(k), ldk, static_cast<const bf16_t*>(v), ldv,
+                                 static_cast<bf16_t*>(out), ldo, n_seq, seq_len, n_heads, n_kv_heads, rope_theta, ctx->ws, ctx->stream));
+    return AGZO_OK;
+}
+
 int agzo_glue_add(agzo_ctx* ctx, void* h, int64_t ldh, const void* delta, int64_t ldd, int64_t n, int64_t d) {
     TRY(check_glue(ctx, n, d, {h, delta}, {ldh, ldd}));
     HIPCHK(launch_glue_add(static_cast<bf16_t*>(h), ldh, static_cast<const bf16_t*>(delta), ldd, n, d, ctx->stream));

@@ -248,6 +248,13 @@ hipError_t launch_glue_swiglu(const bf16_t* a, int64_t lda, const bf16_t* u, int
                               int64_t d, hipStream_t st);
 hipError_t launch_glue_add(bf16_t* h, int64_t ldh, const bf16_t* dl, int64_t ldd, int64_t n, int64_t d, hipStream_t st);
 
+// attention core of a decoder layer (128-wide heads): q [N][n_heads 128], k, v [N][n_kv 128] bf16, N = n_seq seq_len tokens,
+// sequences back to back -> out [N][n_heads 128]; workspace: glue_attention_workspace_bytes() of device scratch
+size_t glue_attention_workspace_bytes(int n_seq, int seq_len, int n_heads, int n_kv);
+hipError_t launch_glue_attention(const bf16_t* q, int64_t ldq, const bf16_t* k, int64_t ldk, const bf16_t* v, int64_t ldv,
+                                 bf16_t* out, int64_t ldo, int n_seq, int seq_len, int n_heads, int n_kv, float rope_theta,
+                                 void* workspace, hipStream_t st);
+
 // probe.hip : register-only MFMA loop for measuring the sustained matrix rate and shader clock of the device;
 // clk4: four 64-bit words for the counters plus 1 KiB that the kernel may (never does) write behind them
 hipError_t launch_probe_mfma(const void* operands, int duty, int iters, unsigned long long* clk4, hipStream_t st);
