@@ -154,11 +154,84 @@ class MlpStack:
         self.ctx.update_many([(self.W[nm], self.B[nm], seed0 + i, lr, self.out[3:4]) for i, nm in enumerate(self.names)])
 
 
-def run_mlp_stack(ctx, steps, warmup, r=16, K=3, n_blocks=28, n_seq=16, seq_len=512):
-    """Steps per second of the MLP-stack workload (28 blocks + LM head, 16 x 512 tokens, token cross-entropy, global g)."""
+class Decoder(MlpStack):
+    """Alg. 2 over full decoder layers (grouped-query attention with 128-wide heads, per-head normalisation, rotary
+    embedding, gated MLP) with an LM head: eight linear layers per decoder layer all perturbed at once, one global g.
+    share_bases: layers that read the same activations (q / k / v, gate / up) carry one basis (the paper extracts per
+    layer; their Gaussian factors stay their own)."""
+
+    def __init__(self, ctx, params, ids, r, K, share_bases):
+        self.ctx, self.r, self.K = ctx, r, K
+        self.nl = params["n_layers"]
+        self.n_seq, self.T = ids.shape
+        self.names = []
+        for l in range(self.nl):
+            self.names += [(p, l) for p in synth.DECODER_PROJECTIONS]
+        self.names.append(("head", 0))
+        self.index = {nm: i for i, nm in enumerate(self.names)}
+        self.W = {nm: params[nm] for nm in self.names}
+        self.E = params["E"]
+        self.ids = ids.reshape(-1)
+        tgt = torch.full(ids.shape, -1, dtype=torch.int32, device=ids.device)
+        tgt[:, :-1] = ids[:, 1:].to(torch.int32)
+        self.tgt = tgt.reshape(-1).contiguous()
+        self.loss = binding.make_loss(self.tgt, kind=binding.LOSS_CE)
+        n = self.ids.numel()
+        self.Y = {nm: torch.empty(n, self.W[nm].shape[0], dtype=torch.bfloat16, device="cuda") for nm in self.names if nm[0] != "head"}
+        self.share = {}
+        if share_bases:
+            for l in range(self.nl):
+                self.share.update({("k", l): ("q", l), ("v", l): ("q", l), ("up", l): ("gate", l)})
+        self.B = {nm: torch.empty(self.W[nm].shape[1], r, dtype=torch.float32, device="cuda") for nm in self.names if nm not in self.share}
+        for nm, src in self.share.items():
+            self.B[nm] = self.B[src]
+        self.X = {}
+        self.out = torch.zeros(4, dtype=torch.float64, device="cuda")
+        self.flops_fwd = sum(2.0 * n * self.W[nm].shape[0] * self.W[nm].shape[1] for nm in self.names)
+        self.flops_rank = sum(2.0 * n * r * (self.W[nm].shape[0] + self.W[nm].shape[1]) for nm in self.names)
+
+    def linear(self, nm, x, sign, eps, seed0, loss_dev):
+        W, Y = self.W[nm], self.Y.get(nm)
+        L = binding.make_layer(W, x, self.r, Y=Y)
+        loss = self.loss if nm[0] == "head" else None
+        seed = seed0 + self.index[nm]
+        if sign == 0:
+            self.X[nm] = x
+            self.ctx.layer_forward_sketch(L, W, x, Y, binding.SKETCH_NONE, None, seed, None, loss, loss_dev)
+        else:
+            self.ctx.perturbed_forward(L, W, x, self.B[nm], seed, sign * eps, Y, loss, loss_dev)
+        return Y
+
+    def run_pass(self, sign, eps, seed0, loss_dev):
+        h = self.E[self.ids]
+        for l in range(self.nl):
+            n = self.rms(h)
+            q, k, v = (self.linear((p, l), n, sign, eps, seed0, None) for p in ("q", "k", "v"))
+            a = torch.empty_like(q)
+            self.ctx.glue_attention(q, k, v, a, self.n_seq, self.T)
+            self.ctx.glue_add(h, self.linear(("o", l), a, sign, eps, seed0, None))
+            n = self.rms(h)
+            g, u = self.linear(("gate", l), n, sign, eps, seed0, None), self.linear(("up", l), n, sign, eps, seed0, None)
+            m = torch.empty_like(g)
+            self.ctx.glue_swiglu(g, u, m)
+            self.ctx.glue_add(h, self.linear(("down", l), m, sign, eps, seed0, None))
+        self.linear(("head", 0), self.rms(h), sign, eps, seed0, loss_dev)
+
+    def step(self, step, eps, lr):
+        seed0 = 100_000 * (step + 1)
+        self.run_pass(0, eps, seed0, self.out[0:1])
+        own = [nm for nm in self.names if nm not in self.share]
+        self.ctx.basis_many([(binding.make_layer(self.W[nm], self.X[nm], self.r), self.X[nm], seed0 + self.index[nm], None, self.B[nm])
+                             for nm in own], self.K)
+        self.X.clear()
+        self.run_pass(+1, eps, seed0, self.out[1:2])
+        self.run_pass(-1, eps, seed0, self.out[2:3])
+        self.ctx.two_point(self.out, eps)
+        self.ctx.update_many([(self.W[nm], self.B[nm], seed0 + self.index[nm], lr, self.out[3:4]) for nm in self.names])
+
+
+def run_model(ctx, model, steps, warmup, note):
     eps, lr = float(np.float32(1e-3)), float(np.float32(1e-4))
-    params, ids = synth.device_mlp_stack(11, n_blocks, 2048, 6144, 32000, n_seq, seq_len)
-    model = MlpStack(ctx, params, ids, r, K)
     for s in range(warmup):
         model.step(s, eps, lr)
     ctx.check()
@@ -177,17 +250,37 @@ def run_mlp_stack(ctx, steps, warmup, r=16, K=3, n_blocks=28, n_seq=16, seq_len=
     ctx.check()
     losses = model.out.cpu().numpy()
     if not np.isfinite(losses).all():
-        raise RuntimeError("non-finite loss in the MLP-stack workload")
+        raise RuntimeError("non-finite loss in the model workload")
     per_step = sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(steps))
     med = per_step[len(per_step) // 2]
     flops = 3.0 * model.flops_fwd + 2.0 * model.flops_rank
     return {"value": 1e3 / med, "unit": "steps/s", "ms_per_step": med, "ms_per_step_mean_wall": 1e3 * dt / steps, "steps": steps,
             "gemm_launches": n_g, "gemm_ms_per_step": ms_g / steps, "gemm_tflops": flops * steps / (ms_g * 1e-3) / 1e12,
-            "forward_tflop": model.flops_fwd / 1e12, "linear_layers": len(model.names), "tokens": n_seq * seq_len, "rank": r,
-            "power_steps": K, "losses": {"L0": losses[0], "L+": losses[1], "L-": losses[2], "g": losses[3]},
-            "note": "Alg. 2 over %d blocks + LM head: base pass keeping every layer's input, one batched extraction for the "
-                    "%d layers, two perturbed passes (factored, fused cross-entropy on the head), global g, one batched "
-                    "update" % (n_blocks, len(model.names))}
+            "forward_tflop": model.flops_fwd / 1e12, "linear_layers": len(model.names), "tokens": int(model.ids.numel()),
+            "rank": model.r, "power_steps": model.K, "losses": {"L0": losses[0], "L+": losses[1], "L-": losses[2], "g": losses[3]},
+            "note": note}
+
+
+def run_decoder(ctx, steps, warmup, r=16, K=3, n_layers=28, n_seq=16, seq_len=512, share_bases=False):
+    """Steps per second of Alg. 2 over a Qwen3-1.7B-shaped decoder (hidden 2048, 16 query heads on 8 kv heads of 128,
+    intermediate 6144, 28 layers, vocabulary 32000), 16 x 512 tokens, token cross-entropy, global g."""
+    params, ids = synth.device_decoder(13, n_layers, 2048, 16, 8, 6144, 32000, n_seq, seq_len)
+    model = Decoder(ctx, params, ids, r, K, share_bases)
+    return run_model(ctx, model, steps, warmup,
+                     "Alg. 2 over %d decoder layers + LM head (%d linear layers): base pass keeping every layer's input, one batched "
+                     "extraction (%s), two perturbed passes, global g, one batched update; attention, normalisations, gate and "
+                     "residual sums are the library's glue kernels" % (n_layers, len(model.names),
+                                                                       "one basis per distinct input" if share_bases else "one basis per layer"))
+
+
+def run_mlp_stack(ctx, steps, warmup, r=16, K=3, n_blocks=28, n_seq=16, seq_len=512):
+    """Steps per second of the MLP-stack workload (28 blocks + LM head, 16 x 512 tokens, token cross-entropy, global g)."""
+    params, ids = synth.device_mlp_stack(11, n_blocks, 2048, 6144, 32000, n_seq, seq_len)
+    model = MlpStack(ctx, params, ids, r, K)
+    return run_model(ctx, model, steps, warmup,
+                     "Alg. 2 over %d blocks + LM head: base pass keeping every layer's input, one batched extraction for the "
+                     "%d layers, two perturbed passes (factored, fused cross-entropy on the head), global g, one batched "
+                     "update" % (n_blocks, len(model.names)))
 
 
 def gemm_shapes(args):
@@ -321,9 +414,11 @@ def main():
     ap.add_argument("--shape", choices=["q", "k", "gate", "down"], default=None, help="with --gemm-shapes: only this shape")
     ap.add_argument("--no-extras", action="store_true",
                     help="only the timed workload and its stage breakdown (for counter-collection runs of the profiler)")
-    ap.add_argument("--workload", choices=["qwen3-8b", "qwen3-0.6b", "mlp-stack"], default="qwen3-8b",
+    ap.add_argument("--workload", choices=["qwen3-8b", "qwen3-0.6b", "mlp-stack", "decoder"], default="qwen3-8b",
                     help="layer set: qwen3-8b is the benchmark configuration; qwen3-0.6b (use --tokens 2048 --rank 8) is the "
-                         "small launch-bound one; mlp-stack is the 28-block residual stack with LM head and global g")
+                         "small launch-bound one; mlp-stack is the 28-block residual stack with LM head and global g; decoder the "
+                         "same with full decoder layers (attention)")
+    ap.add_argument("--share-bases", action="store_true", help="decoder workload: one basis per distinct input")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives are part of it); use --gpus 1",
@@ -338,6 +433,20 @@ def main():
         return
     if args.gemm_shapes:
         gemm_shapes(args)
+        return
+    if args.workload == "decoder":
+        ctx = binding.Context()
+        st = run_decoder(ctx, max(args.steps // 4, 3), max(args.warmup // 2, 1), r=args.rank, share_bases=args.share_bases)
+        res = {"metric": "AGZO steps/sec (decoder stack with LM head)", "value": st["value"], "unit": "steps/s", "n_gpus": 1,
+               "steps": st["steps"], "warmup": max(args.warmup // 2, 1), "ms_per_step": st["ms_per_step"],
+               "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+               "config": {"workload": "28 Qwen3-1.7B-shaped decoder layers (hidden 2048, 16 heads on 8 kv heads, intermediate 6144) + "
+                                      "2048x32000 LM head, 16x512 tokens, next-token cross-entropy, r=%d, K=3, global g, %s"
+                                      % (args.rank, "shared bases" if args.share_bases else "per-layer bases")},
+               "roofline": {"bound": "mfma", "kernel": "gemm_bf16_kernel", "achieved": st["gemm_tflops"], "peak": PEAK_BF16_TFLOPS,
+                            "unit": "TFLOP/s", "frac": st["gemm_tflops"] / PEAK_BF16_TFLOPS, "traffic": None},
+               "detail": st}
+        print(json.dumps(res))
         return
     if args.workload == "mlp-stack":
         ctx = binding.Context()
@@ -764,6 +873,13 @@ def main():
             res["mlp_stack"] = run_mlp_stack(ctx, 3, 1)
         except (binding.AgzoError, RuntimeError) as e:
             res["mlp_stack"] = {"error": str(e)[:300]}
+        try:
+            torch.cuda.empty_cache()
+            res["decoder"] = run_decoder(ctx, 3, 1)
+            torch.cuda.empty_cache()
+            res["decoder_shared_bases"] = run_decoder(ctx, 3, 1, share_bases=True)
+        except (binding.AgzoError, RuntimeError) as e:
+            res["decoder"] = {"error": str(e)[:300]}
         torch.cuda.empty_cache()
     # yardstick for the MFMA fraction: a register-only MFMA loop (no LDS, no memory traffic) on this device, with
     # operand bits that never toggle (zeros) and with N(0,1) bf16 operands like the workload's

@@ -84,7 +84,7 @@ __global__ __launch_bounds__(256) void glue_add_kernel(bf16_t* __restrict__ h, i
 //
 // prep: q, k <- rope(rmsnorm_per_head(.)), head-major [seq][head][t][128]; v transposed to [seq][kv head][128][t_pad]
 //       (t_pad = seq_len rounded up to 32, the padding zero) so that the second product reads keys contiguously.
-// attention: one wave = 16 queries of one head.  Scores are computed transposed, S^T = K Q^T (keys x queries), with
+// attention: one wave = 32 queries of one head (two groups of 16).  Scores are computed transposed, S^T = K Q^T (keys x queries), with
 //       v_mfma_f32_16x16x32_bf16: a lane then holds, for ONE query (column lane % 16), the scores of keys 4 g + e of each
 //       16-key block (g = lane / 16), so the softmax's running maximum and sum are per-lane scalars up to a reduction
 //       over the four g, and the rescaling of the output accumulators (out^T = V^T P^T, same column = query) is a
@@ -149,86 +149,124 @@ __global__ __launch_bounds__(256) void glue_v_transpose_kernel(const bf16_t* __r
     for (int i = 0; i < 8; ++i) dst[(int64_t)i * t_pad] = (bf16_t)((i & 1) ? (w[i >> 1] >> 16) : (w[i >> 1] & 0xFFFFu));
 }
 
+// QG 16-query groups per wave: every K and V^T fragment a wave loads serves QG matrix instructions
+constexpr int ATT_QG = 2;
+constexpr int ATT_WAVE_Q = 16 * ATT_QG;     // queries per wave
+constexpr int ATT_WG_Q = 4 * ATT_WAVE_Q;    // queries per workgroup
+
 __global__ __launch_bounds__(256) void glue_attention_kernel(const bf16_t* __restrict__ Qr, const bf16_t* __restrict__ Kr,
                                                              const bf16_t* __restrict__ Vt, bf16_t* __restrict__ out, int64_t ldo,
                                                              int seq_len, int t_pad, int n_heads, int n_kv) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int n = lane & 15, g = lane >> 4;
     const int head = blockIdx.y, seq = blockIdx.z, kvh = head / (n_heads / n_kv);
-    const int q0 = (blockIdx.x * 4 + wave) * 16;
+    // heavy tiles first: the last queries of a sequence see the most keys
+    const int q0 = ((int)(gridDim.x - 1 - blockIdx.x) * 4 + wave) * ATT_WAVE_Q;
     if (q0 >= seq_len) return;                                         // wave-uniform
-    const int qi = min(q0 + n, seq_len - 1);                           // rows past the end repeat the last query, unstored
     const bf16_t* Qh = Qr + ((int64_t)seq * n_heads + head) * seq_len * HEAD_DIM;
     const bf16_t* Kh = Kr + ((int64_t)seq * n_kv + kvh) * seq_len * HEAD_DIM;
     const bf16_t* Vh = Vt + ((int64_t)seq * n_kv + kvh) * HEAD_DIM * t_pad;
     union Frag { uint4 u; bf16x8_t v; };
-    Frag qf[4];
+    int qi[ATT_QG];                                                    // rows past the end repeat the last query, unstored
+    Frag qf[ATT_QG][4];
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) qf[ks].u = *reinterpret_cast<const uint4*>(Qh + (int64_t)qi * HEAD_DIM + 32 * ks + 8 * g);
-    floatx4_t acc[8];
+    for (int qg = 0; qg < ATT_QG; ++qg) {
+        qi[qg] = min(q0 + 16 * qg + n, seq_len - 1);
 #pragma unroll
-    for (int db = 0; db < 8; ++db) acc[db] = floatx4_t{0.f, 0.f, 0.f, 0.f};
-    float m_run = -INFINITY, l_run = 0.f;
+        for (int ks = 0; ks < 4; ++ks) qf[qg][ks].u = *reinterpret_cast<const uint4*>(Qh + (int64_t)qi[qg] * HEAD_DIM + 32 * ks + 8 * g);
+    }
+    floatx4_t acc[ATT_QG][8];
+#pragma unroll
+    for (int qg = 0; qg < ATT_QG; ++qg)
+#pragma unroll
+        for (int db = 0; db < 8; ++db) acc[qg][db] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+    float m_run[ATT_QG], l_run[ATT_QG];
+#pragma unroll
+    for (int qg = 0; qg < ATT_QG; ++qg) { m_run[qg] = -INFINITY; l_run[qg] = 0.f; }
     const float sc = 1.44269504088896341f * 0.08838834764831845f;      // log2(e) / sqrt(128)
-    const int k_end = min(q0 + 15, seq_len - 1);                       // last key any query of this wave may see
-    for (int kb = 0; kb <= k_end; kb += 32) {
-        floatx4_t s[2];
+    const int k_end = min(q0 + ATT_WAVE_Q - 1, seq_len - 1);           // last key any query of this wave may see
+    // K operand of a 32-key step: this lane's rows are keys kb + 16 blk + n (clamped), its columns 32 ks + 8 g ..
+    auto load_k = [&](int kb, Frag (&kf)[2][4]) __attribute__((always_inline)) {
 #pragma unroll
         for (int blk = 0; blk < 2; ++blk) {
-            const int krow = min(kb + 16 * blk + n, seq_len - 1);      // this lane's row of the K operand (key index = lane % 16)
-            s[blk] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+            const int krow = min(kb + 16 * blk + n, seq_len - 1);
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks) {
-                Frag kf;
-                kf.u = *reinterpret_cast<const uint4*>(Kh + (int64_t)krow * HEAD_DIM + 32 * ks + 8 * g);
-                s[blk] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf.v, qf[ks].v, s[blk], 0, 0, 0);
-            }
+            for (int ks = 0; ks < 4; ++ks) kf[blk][ks].u = *reinterpret_cast<const uint4*>(Kh + (int64_t)krow * HEAD_DIM + 32 * ks + 8 * g);
         }
-        // lane: query qi (column n), keys kb + 16 blk + 4 g + e
-        float p[8], mx = m_run;
-#pragma unroll
-        for (int blk = 0; blk < 2; ++blk)
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int key = kb + 16 * blk + 4 * g + e;
-                const float v = (key <= qi && key < seq_len) ? s[blk][e] * sc : -INFINITY;
-                p[4 * blk + e] = v;
-                mx = fmaxf(mx, v);
-            }
-        mx = fmaxf(mx, __shfl_xor(mx, 16));
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float alpha = exp2f(m_run - mx);                          // 0 on the first step (m_run = -inf, mx finite: key 0 is visible)
-        float psum = 0.f;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            p[i] = exp2f(p[i] - mx);
-            psum += p[i];
-        }
-        l_run = l_run * alpha + psum;
-        m_run = mx;
-        Frag pf;
-        pf.u = make_uint4(pack_bf16x2(p[0], p[1]), pack_bf16x2(p[2], p[3]), pack_bf16x2(p[4], p[5]), pack_bf16x2(p[6], p[7]));
+    };
+    Frag kf[2][4];
+    load_k(0, kf);
+    for (int kb = 0; kb <= k_end; kb += 32) {
+        // V^T operands of this step: row = dim 16 db + n, the keys in the order the probabilities are held (4 g .. 4 g + 3
+        // of both 16-key blocks); requested before the scores so that they arrive under the first product and the softmax
+        Frag vf[8];
 #pragma unroll
         for (int db = 0; db < 8; ++db) {
-            // V^T operand: row = dim 16 db + n, the keys in the order this step's probabilities are held
             const bf16_t* vrow = Vh + (int64_t)(16 * db + n) * t_pad + kb + 4 * g;
             const uint2 v0 = *reinterpret_cast<const uint2*>(vrow), v1 = *reinterpret_cast<const uint2*>(vrow + 16);
-            Frag vf;
-            vf.u = make_uint4(v0.x, v0.y, v1.x, v1.y);
+            vf[db].u = make_uint4(v0.x, v0.y, v1.x, v1.y);
+        }
+        floatx4_t s[ATT_QG][2];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) acc[db][e] *= alpha;
-            acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf.v, pf.v, acc[db], 0, 0, 0);
+        for (int qg = 0; qg < ATT_QG; ++qg)
+#pragma unroll
+            for (int blk = 0; blk < 2; ++blk) {
+                s[qg][blk] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks)
+                    s[qg][blk] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[blk][ks].v, qf[qg][ks].v, s[qg][blk], 0, 0, 0);
+            }
+        // the next step's K operands (the step after the last one re-reads clamped rows and is dropped)
+        load_k(kb + 32, kf);
+#pragma unroll
+        for (int qg = 0; qg < ATT_QG; ++qg) {
+            // lane: query qi[qg] (column n), keys kb + 16 blk + 4 g + e
+            float p[8], mx = m_run[qg];
+#pragma unroll
+            for (int blk = 0; blk < 2; ++blk)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int key = kb + 16 * blk + 4 * g + e;
+                    const float v = (key <= qi[qg] && key < seq_len) ? s[qg][blk][e] * sc : -INFINITY;
+                    p[4 * blk + e] = v;
+                    mx = fmaxf(mx, v);
+                }
+            mx = fmaxf(mx, __shfl_xor(mx, 16));
+            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            // a group of queries that sees none of this step's keys (its rows all lie before kb) keeps its state:
+            // mx = m_run, alpha = 1, every p = 0.  On a group's first step m_run = -inf and mx is finite (key 0 is visible).
+            const float alpha = exp2f(m_run[qg] - mx);
+            float psum = 0.f;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                p[i] = exp2f(p[i] - mx);
+                psum += p[i];
+            }
+            l_run[qg] = l_run[qg] * alpha + psum;
+            m_run[qg] = mx;
+            Frag pf;
+            pf.u = make_uint4(pack_bf16x2(p[0], p[1]), pack_bf16x2(p[2], p[3]), pack_bf16x2(p[4], p[5]), pack_bf16x2(p[6], p[7]));
+#pragma unroll
+            for (int db = 0; db < 8; ++db) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) acc[qg][db][e] *= alpha;
+                acc[qg][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[db].v, pf.v, acc[qg][db], 0, 0, 0);
+            }
         }
     }
-    l_run += __shfl_xor(l_run, 16);
-    l_run += __shfl_xor(l_run, 32);
-    if (q0 + n >= seq_len) return;
-    const float inv = 1.f / l_run;
-    bf16_t* orow = out + ((int64_t)seq * seq_len + q0 + n) * ldo + head * HEAD_DIM + 4 * g;    // dims 16 db + 4 g + e
 #pragma unroll
-    for (int db = 0; db < 8; ++db)
-        *reinterpret_cast<uint2*>(orow + 16 * db) = make_uint2(pack_bf16x2(acc[db][0] * inv, acc[db][1] * inv),
-                                                               pack_bf16x2(acc[db][2] * inv, acc[db][3] * inv));
+    for (int qg = 0; qg < ATT_QG; ++qg) {
+        float l = l_run[qg];
+        l += __shfl_xor(l, 16);
+        l += __shfl_xor(l, 32);
+        if (q0 + 16 * qg + n >= seq_len) continue;
+        const float inv = 1.f / l;
+        bf16_t* orow = out + ((int64_t)seq * seq_len + q0 + 16 * qg + n) * ldo + head * HEAD_DIM + 4 * g;    // dims 16 db + 4 g + e
+#pragma unroll
+        for (int db = 0; db < 8; ++db)
+            *reinterpret_cast<uint2*>(orow + 16 * db) = make_uint2(pack_bf16x2(acc[qg][db][0] * inv, acc[qg][db][1] * inv),
+                                                                   pack_bf16x2(acc[qg][db][2] * inv, acc[qg][db][3] * inv));
+    }
 }
 
 size_t glue_attention_workspace_bytes(int n_seq, int seq_len, int n_heads, int n_kv) {
@@ -253,7 +291,7 @@ hipError_t launch_glue_attention(const bf16_t* q, int64_t ldq, const bf16_t* k, 
                        dim3(256), 0, st, v, ldv, Vt, n_seq, seq_len, t_pad, n_kv);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(glue_attention_kernel, dim3((unsigned)((seq_len + 63) / 64), (unsigned)n_heads, (unsigned)n_seq), dim3(256), 0, st,
+    hipLaunchKernelGGL(glue_attention_kernel, dim3((unsigned)((seq_len + ATT_WG_Q - 1) / ATT_WG_Q), (unsigned)n_heads, (unsigned)n_seq), dim3(256), 0, st,
                        Qr, Kr, Vt, out, ldo, seq_len, t_pad, n_heads, n_kv);
     return hipGetLastError();
 }
