@@ -49,8 +49,13 @@ typedef enum { AGZO_LOSS_NONE = 0, AGZO_LOSS_MSE = 1, AGZO_LOSS_CE = 2 } agzo_lo
 typedef enum {
     AGZO_SKETCH_NONE = 0,
     AGZO_SKETCH_RANGE = 1, /* S = X^T Omega, Omega [n_tokens][r] Gaussian from (seed, tag 1): Alg. 1, first product */
-    AGZO_SKETCH_POWER = 2  /* S = X^T (X Q) for a given Q [d_in][r]: Alg. 1, power step; Q == NULL: Q is the Gaussian
+    AGZO_SKETCH_POWER = 2, /* S = X^T (X Q) for a given Q [d_in][r]: Alg. 1, power step; Q == NULL: Q is the Gaussian
                               [d_in][r] of (seed, tag 2), the start of the AGZO_INIT_FEATURE variant */
+    AGZO_SKETCH_RANGE_FUSED = 3 /* the S of AGZO_SKETCH_RANGE (same Omega; sums in another order), emitted by the forward
+                              GEMM itself from the X tiles it stages in LDS instead of by a sweep of its own over X
+                              (Sec. 4.1: the f0 pass also yields the subspace information).  Only for bf16 layers whose
+                              forward runs in the 128 x 128 tiling (fewer than 160 tiles of 256 x 256, tiling AUTO, W
+                              given, squared-error loss or none), r <= 16, n_tokens <= 8192: otherwise AGZO_EINVAL */
 } agzo_sketch;
 
 /* Philox stream tags: which Gaussian matrix a (seed, tag, row, col) element belongs to. */

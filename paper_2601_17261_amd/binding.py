@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libagzo.so")
 
 F32, BF16 = 0, 1
 LOSS_NONE, LOSS_MSE, LOSS_CE = 0, 1, 2
-SKETCH_NONE, SKETCH_RANGE, SKETCH_POWER = 0, 1, 2
+SKETCH_NONE, SKETCH_RANGE, SKETCH_POWER, SKETCH_RANGE_FUSED = 0, 1, 2, 3
 TAG_G, TAG_OMEGA, TAG_Q0, TAG_DENSE = 0, 1, 2, 3
 ONE_SIDED, NAIVE_INPLACE, INIT_FEATURE, SHARED_FORWARD = 1, 2, 4, 8
 OK, EINVAL, ENOMEM, ENUMERIC, EHIP = 0, -1, -2, -3, -4

@@ -120,12 +120,13 @@ struct Plan {
 };
 
 // base: where this layer's carve-out starts inside the workspace (several layers side by side in the batched calls)
-Plan make_plan(const agzo_layer& L, bool need_ybuf, bool ce = false, bool shared = false, size_t base = 0) {
+// fused_sketch: the range sketch comes out of the forward GEMM, one partial sum per 128-token tile
+Plan make_plan(const agzo_layer& L, bool need_ybuf, bool ce = false, bool shared = false, size_t base = 0, bool fused_sketch = false) {
     Plan p;
     const bool bf = (L.dtype == AGZO_BF16);
     p.rp = round16(L.r);
-    p.m_pad = round32(L.n_tokens);
-    p.nsplit = bf ? xtt_num_splits(L.n_tokens, L.d_in) : 1;
+    p.m_pad = fused_sketch ? gemm_bf16_sketch_mpad(L.n_tokens) : round32(L.n_tokens);
+    p.nsplit = !bf ? 1 : fused_sketch ? gemm_bf16_sketch_splits(L.n_tokens) : xtt_num_splits(L.n_tokens, L.d_in);
     const int n_gemm = bf ? gemm_bf16_num_workgroups(L.n_tokens, L.d_out, !ce && !shared && L.tiling != AGZO_TILING_LARGE) : epilogue_f32_num_workgroups(L.n_tokens, L.d_out);
     p.n_part = n_gemm;
     size_t o = align_up(base);
@@ -309,7 +310,7 @@ int op_project(agzo_ctx* ctx, const agzo_layer& L, const Plan& p, const void* X,
 // shared = true: one pass over X and W evaluates the loss at W, W + eps Z, W - eps Z -> loss_dev[0..2]
 int op_forward(agzo_ctx* ctx, const agzo_layer& L, const Plan& p, const void* W, const void* X, const float* P,
                float eps_signed, uint64_t seed, void* Y, const agzo_loss_spec* loss, double* loss_dev,
-               bool shared = false, int part_slot = 0, bool defer_finish = false) {
+               bool shared = false, int part_slot = 0, bool defer_finish = false, bool fused_sketch = false) {
     hipStream_t st = ctx->stream;
     GemmLossArgs la;
     const bool has_loss = loss && loss->kind != AGZO_LOSS_NONE;
@@ -347,6 +348,7 @@ int op_forward(agzo_ctx* ctx, const agzo_layer& L, const Plan& p, const void* W,
         a.shared = shared;
         a.large_tiles = (L.tiling == AGZO_TILING_LARGE);
         a.ext_ws = P ? ctx->ws + p.off_ext : nullptr;
+        if (fused_sketch) { a.sk_T = wsh(ctx, p.off_TpackT); a.sk_mpad = p.m_pad; a.sk_partial = wsf(ctx, p.off_xtt); }
         if (((ctx->prof >> AGZO_PROF_GEMM) & 1u) && ctx->clk_used < kClkSlots) a.clk = ctx->clk + 4 * ctx->clk_used++;
         {
             ProfScope ps(ctx, AGZO_PROF_GEMM);
@@ -763,15 +765,31 @@ int agzo_layer_forward_sketch(agzo_ctx* ctx, const agzo_layer* L, const void* W,
     if (!X) return fail(ctx, AGZO_EINVAL, "X is NULL");
     TRY(check_operands(ctx, L, W, X));
     if (!gemm && (Y || (loss && loss->kind != AGZO_LOSS_NONE))) return fail(ctx, AGZO_EINVAL, "Y or loss without W");
-    if (mode != AGZO_SKETCH_NONE && mode != AGZO_SKETCH_RANGE && mode != AGZO_SKETCH_POWER)
+    if (mode != AGZO_SKETCH_NONE && mode != AGZO_SKETCH_RANGE && mode != AGZO_SKETCH_POWER && mode != AGZO_SKETCH_RANGE_FUSED)
         return fail(ctx, AGZO_EINVAL, "sketch mode %d", mode);
+    const bool fused = (mode == AGZO_SKETCH_RANGE_FUSED);
+    if (fused) {
+        const bool ce = loss && loss->kind == AGZO_LOSS_CE;
+        if (!gemm || L->dtype != AGZO_BF16 || ce || !gemm_bf16_fuses_sketch(L->n_tokens, L->d_out, L->r, L->tiling == AGZO_TILING_LARGE))
+            return fail(ctx, AGZO_EINVAL, "the fused range sketch needs a bf16 forward in the 128 x 128 tiling (few 256 x 256 tiles, "
+                                          "no cross-entropy, tiling AUTO), r <= 16 and at most 8192 tokens");
+    }
     if (mode != AGZO_SKETCH_NONE && !S) return fail(ctx, AGZO_EINVAL, "S is NULL");
     if (gemm) {
         TRY(check_y(ctx, L, Y));
         TRY(check_loss(ctx, L, loss, loss_dev));
     }
-    const Plan p = make_plan(*L, gemm && L->dtype == AGZO_F32 && !Y, loss && loss->kind == AGZO_LOSS_CE);
+    const Plan p = make_plan(*L, gemm && L->dtype == AGZO_F32 && !Y, loss && loss->kind == AGZO_LOSS_CE, false, 0, fused);
     TRY(reserve(ctx, p.total));
+    if (fused) {
+        {
+            ProfScope ps(ctx, AGZO_PROF_FILL);
+            HIPCHK(launch_fill_normal_packT(wsh(ctx, p.off_TpackT), L->n_tokens, p.m_pad, L->r, p.rp, seed, AGZO_TAG_OMEGA, ctx->stream));
+        }
+        TRY(op_forward(ctx, *L, p, W, X, nullptr, 0.f, seed, Y, loss, loss_dev, false, 0, false, true));
+        TRY(reduce_to_S(ctx, *L, p, S));
+        return AGZO_OK;
+    }
     if (gemm) TRY(op_forward(ctx, *L, p, W, X, nullptr, 0.f, seed, Y, loss, loss_dev));
     if (mode == AGZO_SKETCH_RANGE) {
         TRY(sketch_range(ctx, *L, p, X, seed, S));

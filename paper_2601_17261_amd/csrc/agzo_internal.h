@@ -150,6 +150,10 @@ struct GemmBf16Args {
     // gemm_bf16_ext_bytes() bytes of device scratch for the rank-r extension operands of a perturbed forward
     // (NULL: every tile builds them itself)
     void* ext_ws = nullptr;
+    // fused range sketch S = X^T Omega (NULL: none; only where gemm_bf16_fuses_sketch() says so): Omega^T as bf16
+    // planes [3][16][sk_mpad], sk_mpad = gemm_bf16_sketch_mpad(M); sk_partial receives gemm_bf16_sketch_splits(M)
+    // partial sums [split][K][16], one per 128-token tile
+    const bf16_t* sk_T = nullptr; int64_t sk_mpad = 0; float* sk_partial = nullptr;
     // telemetry (NULL: none): four 64-bit device words that workgroup 0 fills with the shader-clock counter and the
     // constant-rate counter at kernel entry and exit
     unsigned long long* clk = nullptr;
@@ -158,6 +162,11 @@ struct GemmBf16Args {
 // mode, no cross-entropy), which is then used for shapes with few 256 x 256 tiles
 int gemm_bf16_num_workgroups(int64_t M, int64_t N, bool small_ok);
 size_t gemm_bf16_ext_bytes(int64_t M, int64_t N, int r);
+// true: a plain forward of this shape (no rank-r term, no shared-forward mode, no cross-entropy) runs in the 128 x 128
+// tiling, whose kernel can emit the range sketch from its LDS-staged X tiles (r <= 16, at most 64 token tiles)
+bool gemm_bf16_fuses_sketch(int64_t M, int64_t N, int r, bool large_tiles);
+inline int64_t gemm_bf16_sketch_mpad(int64_t M) { return (M + 127) / 128 * 128; }
+inline int gemm_bf16_sketch_splits(int64_t M) { return (int)((M + 127) / 128); }
 hipError_t launch_gemm_bf16(const GemmBf16Args& a, hipStream_t st);
 
 // gemm_f32.hip : generic strided fp32 GEMM with fp64 accumulation, and the fp32 epilogue

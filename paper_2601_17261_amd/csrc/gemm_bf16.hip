@@ -27,6 +27,10 @@ static bool small_shape(int64_t M, int64_t N) {
     return ((M + BT - 1) / BT) * ((N + BT - 1) / BT) < 160;
 }
 
+bool gemm_bf16_fuses_sketch(int64_t M, int64_t N, int r, bool large_tiles) {
+    return !large_tiles && small_shape(M, N) && r <= 16 && gemm_bf16_sketch_splits(M) <= 64;
+}
+
 int gemm_bf16_ce_chunks(int64_t N) { return (int)((N + BT - 1) / BT) * 2; }   // 128-column chunks (2 per tile)
 
 int gemm_bf16_num_workgroups(int64_t M, int64_t N, bool small_ok) {
@@ -670,6 +674,11 @@ hipError_t launch_gemm_bf16(const GemmBf16Args& a, hipStream_t st) {
     p.ce_ms = reinterpret_cast<float2*>(a.loss.ce_ms);
     p.ce_tl = a.loss.ce_tl;
     p.clk = a.clk;
+    p.sk_T = nullptr; p.sk_mpad = 0; p.sk_partial = nullptr;
+    if (a.sk_T) {
+        if (!small || a.P || !gemm_bf16_fuses_sketch(a.M, a.N, a.r, a.large_tiles)) return hipErrorInvalidValue;
+        p.sk_T = a.sk_T; p.sk_mpad = a.sk_mpad; p.sk_partial = a.sk_partial;
+    }
     if (small) {
         // the workspace was sized for this tiling's partials (gemm_bf16_num_workgroups with small_ok)
         if (a.P && !p.Xext) return hipErrorInvalidValue;      // the small tiling takes the rank-r term as operands only

@@ -40,6 +40,9 @@ struct GemmParams {
     int shared;                 // one pass evaluates f0, f+ and f- (three loss partials per tile)
     // cross-entropy: per (128-column chunk, token) running max and sum of exponentials, and the target's logit
     const int32_t* ce_target; float2* ce_ms; float* ce_tl;
+    // fused range sketch (128 x 128 tiling only; NULL: none): Omega^T planes [3][16][sk_mpad] (sk_mpad a multiple of
+    // 128 that covers every token tile, zero past the last token) and the per-token-tile partial sums [tiles_m][K][16]
+    const bf16_t* sk_T; int64_t sk_mpad; float* sk_partial;
     // optional telemetry: workgroup 0 leaves {shader clock, constant-rate clock} at entry and at exit
     unsigned long long* clk;
 };

@@ -10,6 +10,17 @@
 // again ends up with one token and 16 consecutive outputs per block.  The rank-r term comes as extra K slices from
 // the extension operands that gemm_ext_prep_kernel wrote ([Ph|Ph|Pl] against [Gh|Gl|Gh], eps folded in), appended
 // after the d_in slices so that both signs share bit-identical X W^T accumulators.
+//
+// SK = true also emits the range sketch of Alg. 1 (first product, Y <- H Omega; here S = X^T Omega) from the X tiles
+// that the forward stages in LDS anyway (Sec. 4.1: the pass that evaluates f0 also yields the layer's basis): tile
+// (tm, tn) contracts its 128 tokens against Omega for the d_in slices tn, tn + tiles_n, ..., so that every slice of
+// every token tile is sketched exactly once over the grid, and writes S's partial sum for that token tile
+// (sk_partial[tm][d_in][16]; whoever consumes the sketch adds the token tiles in a fixed order).  Omega^T comes as the
+// three bf16 planes of its fp32 values, token-contiguous, and is kept in LDS for the whole tile; the contraction runs
+// over tokens while the X tile holds a token's features side by side, so a lane fetches one 32-bit word (two
+// features) of eight tokens and a byte permute puts one feature's eight tokens side by side: wave w takes word w of
+// every 16-byte chunk, lanes 0-7 of a 16-lane group its low half and lanes 8-15 its high half, which makes one
+// 16 x 16 x 32 matrix instruction cover the wave's 16 features of the slice without idle columns.
 #include "gemm_bf16_common.h"
 
 namespace agzo {
@@ -17,10 +28,15 @@ namespace agzo {
 constexpr int ST = BT_SMALL;                    // tile edge
 constexpr int STILE_BYTES = ST * BK * 2;        // one operand tile: 16 KiB
 constexpr int SMALL_SMEM = 4 * STILE_BYTES;      // 64 KiB: two operand tiles x two stages (the loss reduction reuses them)
+constexpr int SK_RP = 16;                        // sketch columns of the fused range sketch (r <= 16)
+constexpr int SK_ROW = ST * 2 + 16;              // bytes per row of the Omega^T planes in LDS (padded against bank conflicts)
+constexpr int SK_SMEM = 3 * SK_RP * SK_ROW;      // 12.75 KiB: two workgroups still share a compute unit
 
 // (LDS allows two workgroups per compute unit = two waves per SIMD, so each wave may use half the register file)
+template <bool SK>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void gemm_bf16_small_kernel(GemmParams p) {
     extern __shared__ __align__(16) char smem[];
+    char* const Ts = smem + SMALL_SMEM;                       // SK: Omega^T planes [3][16][128 tokens] of this token tile
     auto Xs = [&](int buf) -> char* { return smem + buf * (2 * STILE_BYTES); };
     auto Ws = [&](int buf) -> char* { return smem + buf * (2 * STILE_BYTES) + STILE_BYTES; };
     double* red = reinterpret_cast<double*>(smem);           // used after the slice loop, when the operand buffers are idle
@@ -112,6 +128,43 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         }
     };
 
+    // ---- fused range sketch (SK) ----
+    int sk_next = (int)tn;                                   // next slice this tile sketches
+    if (SK) {
+        // planes [pl][k][m0 .. m0 + 127] -> LDS: 768 16-byte chunks (sk_mpad covers whole 128-token tiles)
+        for (int idx = tid; idx < 3 * SK_RP * (ST / 8); idx += 256) {
+            const int row = idx / (ST / 8), ch = idx % (ST / 8);
+            *reinterpret_cast<uint4*>(Ts + row * SK_ROW + ch * 16) =
+                *reinterpret_cast<const uint4*>(p.sk_T + (int64_t)row * p.sk_mpad + m0 + ch * 8);
+        }
+    }
+    auto sketch = [&](int buf, int it) __attribute__((always_inline)) {
+        typedef float f32x4 __attribute__((ext_vector_type(4)));
+        // (lane roles are recomputed here and the token chunks are not unrolled: the slice loop has no registers to spare)
+        const int sk_n = lane & 15, sk_g = lane >> 4, sk_c = sk_n & 7;
+        const uint32_t sk_sel = (sk_n >> 3) ? 0x07060302u : 0x05040100u;
+        f32x4 sacc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 1
+        for (int tc = 0; tc < 4; ++tc) {
+            uint32_t wv[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                wv[i] = *reinterpret_cast<const uint32_t*>(Xs(buf) + lds_off(32 * tc + 8 * sk_g + i, sk_c) + 4 * wave);
+            union { uint4 u; bf16x8 v; } b, a;
+            b.u = make_uint4(__builtin_amdgcn_perm(wv[1], wv[0], sk_sel), __builtin_amdgcn_perm(wv[3], wv[2], sk_sel),
+                             __builtin_amdgcn_perm(wv[5], wv[4], sk_sel), __builtin_amdgcn_perm(wv[7], wv[6], sk_sel));
+#pragma unroll
+            for (int pl = 0; pl < 3; ++pl) {
+                a.u = *reinterpret_cast<const uint4*>(Ts + (pl * SK_RP + sk_n) * SK_ROW + (32 * tc + 8 * sk_g) * 2);
+                sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, b.v, sacc, 0, 0, 0);
+            }
+        }
+        // lane: feature = column sk_n of the block, sketch columns 4 sk_g .. 4 sk_g + 3
+        const int64_t f = (int64_t)it * BK + 8 * sk_c + 2 * wave + (sk_n >> 3);
+        if (f < p.K)
+            *reinterpret_cast<float4*>(p.sk_partial + ((int64_t)tm * p.K + f) * SK_RP + 4 * sk_g) = make_float4(sacc[0], sacc[1], sacc[2], sacc[3]);
+    };
+
     // Slice j travels through register set j % DEPTH: requested DEPTH iterations before it is multiplied (a single
     // slice in flight leaves the loop bound by memory latency: a 128 x 128 slice multiplies in a quarter of a
     // microsecond), written to LDS buffer j % 2 one iteration before.  The loop is unrolled by DEPTH so that the set
@@ -121,6 +174,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         if (it + DEPTH < total) gload(IC<u>{}, it + DEPTH);  // set u held slice `it`, which is in LDS already
         multiply(it & 1);
         if (it + 1 < total) sstore(IC<(u + 1) % DEPTH>{}, (it + 1) & 1);    // the buffer that slice it-1 was read from
+        if (SK && it == sk_next && it < nd) { sketch(it & 1, it); sk_next += p.tiles_n; }
         __syncthreads();
     };
     // the same without the tests, for the steady state: with nothing conditional between a request and its use the
@@ -130,6 +184,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         gload(IC<u>{}, it + DEPTH);
         multiply(it & 1);
         sstore(IC<(u + 1) % DEPTH>{}, (it + 1) & 1);
+        if (SK && it == sk_next && it < nd) { sketch(it & 1, it); sk_next += p.tiles_n; }
         __syncthreads();
     };
     if (total > 0) {
@@ -255,7 +310,20 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 // p.tiles_m / p.tiles_n count 128 x 128 tiles here
 hipError_t launch_gemm_bf16_small(const GemmParams& p, hipStream_t st) {
     dim3 grid((unsigned)((int64_t)p.tiles_m * p.tiles_n));
-    hipLaunchKernelGGL(gemm_bf16_small_kernel, grid, dim3(256), SMALL_SMEM, st, p);
+    if (p.sk_T) {
+        // the sketch is taken from the d_in slices (at least one), for r <= 16
+        if (!p.sk_partial || p.K < 1 || p.sk_mpad < (int64_t)p.tiles_m * ST) return hipErrorInvalidValue;
+        static bool attr_set = false;
+        if (!attr_set) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_bf16_small_kernel<true>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, SMALL_SMEM + SK_SMEM);
+            if (e != hipSuccess) return e;
+            attr_set = true;
+        }
+        hipLaunchKernelGGL(gemm_bf16_small_kernel<true>, grid, dim3(256), SMALL_SMEM + SK_SMEM, st, p);
+    } else {
+        hipLaunchKernelGGL(gemm_bf16_small_kernel<false>, grid, dim3(256), SMALL_SMEM, st, p);
+    }
     return hipGetLastError();
 }
 

@@ -415,6 +415,84 @@ def test_step_without_update_then_update_many_equals_step(ctx, storage, n, d_in,
 
 
 # ---------------------------------------------------------------------------------------------
+# range sketch emitted by the forward GEMM itself (Sec. 4.1: the f0 pass also yields the subspace information)
+# ---------------------------------------------------------------------------------------------
+FUSED_SKETCH = [
+    # n, d_in, d_out, r, kind
+    (600, 1024, 520, 16, "rmsnorm"),         # 5 token tiles x 5 output tiles, 16 slices: every tile sketches 3-4 of them
+    (300, 200, 264, 8, "lowrank"),           # ragged everywhere: last slice 8 wide, last token tile 44 rows
+    (2048, 1024, 1024, 16, "rmsnorm"),       # a Qwen3-0.6B projection at that workload's token count
+    (130, 72, 1100, 1, "lowrank"),           # more output tiles (9) than slices (2): most tiles sketch nothing
+    (128, 64, 128, 3, "powerlaw"),           # a single tile, a single slice
+    (1000, 3080, 136, 13, "powerlaw"),       # deep d_in against two output tiles: every tile sketches half the slices
+]
+
+
+@pytest.mark.parametrize("n,d_in,d_out,r,kind", FUSED_SKETCH)
+@pytest.mark.parametrize("with_y,with_loss", [(True, True), (False, True), (True, False)])
+def test_range_sketch_fused_into_the_forward(ctx, n, d_in, d_out, r, kind, with_y, with_loss):
+    seed = 77 + n
+    W, X, T, Wd, Xd, Td = problem(n + d_out, n, d_in, d_out, kind, "bf16")
+    X64 = X.astype(np.float64)
+    loss = binding.make_loss(Td) if with_loss else None
+    scal = torch.zeros(2, dtype=torch.float64, device="cuda")
+    Y1 = torch.full((n, d_out), 3.0, dtype=torch.bfloat16, device="cuda") if with_y else None
+    Y2 = torch.full((n, d_out), 5.0, dtype=torch.bfloat16, device="cuda") if with_y else None
+    S1 = torch.full((d_in, r), 9.0, dtype=torch.float32, device="cuda")
+    S2 = torch.full((d_in, r), 8.0, dtype=torch.float32, device="cuda")
+    L1 = binding.make_layer(Wd, Xd, r, Y=Y1)
+    ctx.layer_forward_sketch(L1, Wd, Xd, Y1, binding.SKETCH_RANGE, None, seed, S1, loss, scal[0:1] if with_loss else None)
+    L2 = binding.make_layer(Wd, Xd, r, Y=Y2)
+    ctx.layer_forward_sketch(L2, Wd, Xd, Y2, binding.SKETCH_RANGE_FUSED, None, seed, S2, loss, scal[1:2] if with_loss else None)
+    ctx.check()
+    # the forward itself is the same arithmetic in the same order
+    if with_y:
+        assert torch.equal(Y1, Y2)
+    if with_loss:
+        assert scal[0].item() == scal[1].item()
+    # the sketch against the definition (fp32 Omega is exact as three bf16 planes; fp32 sums)
+    S0 = oagzo.range_sketch(X64, r, seed)
+    assert rel(host(S2), S0) < 2e-5
+    assert rel(host(S2), host(S1)) < 2e-5
+    assert np.abs(host(S2) - S0).max() < 2e-5 * np.abs(S0).max() * np.sqrt(n)
+    # and it is a sketch the extraction accepts as its first one: same basis as from the separate sweep
+    B1 = torch.empty(d_in, r, dtype=torch.float32, device="cuda")
+    B2 = torch.empty(d_in, r, dtype=torch.float32, device="cuda")
+    ctx.basis(L1, Xd, 2, seed, S1, 0, B1)
+    ctx.basis(L2, Xd, 2, seed, S2, 0, B2)
+    ctx.check()
+    Bg, Bh = host(B1), host(B2)
+    assert np.linalg.norm(Bh @ Bh.T - Bg @ Bg.T) / np.sqrt(r) < 2e-3
+
+
+def test_fused_range_sketch_is_refused_where_the_forward_cannot_emit_it(ctx):
+    W, X, T, Wd, Xd, Td = problem(3, 300, 200, 264, "lowrank", "bf16")
+    S = torch.zeros(200, 24, dtype=torch.float32, device="cuda")
+    def call(L, W_, loss=None, out=None):
+        with pytest.raises(binding.AgzoError) as e:
+            ctx.layer_forward_sketch(L, W_, Xd, None, binding.SKETCH_RANGE_FUSED, None, 1, S, loss, out)
+        assert e.value.code == binding.EINVAL
+    call(binding.make_layer(Wd, Xd, 24), Wd)                      # r above 16
+    call(binding.make_layer(Wd, Xd, 8), None)                     # no forward to ride on
+    Ll = binding.make_layer(Wd, Xd, 8)
+    Ll.tiling = binding.TILING_LARGE
+    call(Ll, Wd)                                                   # the 256 x 256 tiling does not emit it
+    ids = torch.zeros(300, dtype=torch.int32, device="cuda")
+    call(binding.make_layer(Wd, Xd, 8), Wd, binding.make_loss(ids, kind=binding.LOSS_CE), torch.zeros(1, dtype=torch.float64, device="cuda"))
+    # fp32 storage
+    Wf, Xf = Wd.float(), Xd.float()
+    with pytest.raises(binding.AgzoError) as e:
+        ctx.layer_forward_sketch(binding.make_layer(Wf, Xf, 8), Wf, Xf, None, binding.SKETCH_RANGE_FUSED, None, 1, S, None, None)
+    assert e.value.code == binding.EINVAL
+    # a shape with many 256 x 256 tiles
+    Wb = torch.zeros(4096, 64, dtype=torch.bfloat16, device="cuda")
+    Xb = torch.zeros(4096, 64, dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(binding.AgzoError) as e:
+        ctx.layer_forward_sketch(binding.make_layer(Wb, Xb, 8), Wb, Xb, None, binding.SKETCH_RANGE_FUSED, None, 1, S, None, None)
+    assert e.value.code == binding.EINVAL
+
+
+# ---------------------------------------------------------------------------------------------
 # several layers per call: every stage of Alg. 1 (and of the step around it) is one launch for all of them
 # ---------------------------------------------------------------------------------------------
 MANY_LAYERS = [
