@@ -328,6 +328,48 @@ def gemm_shapes(args):
         del W, T
 
 
+def sketch_fusion(args):
+    """Range sketch of Alg. 1 taken by a sweep of its own over X against the same sketch emitted by the forward GEMM
+    (AGZO_SKETCH_RANGE_FUSED), on the projection shapes of the Qwen3-0.6B layer set (the shapes whose forward runs in
+    the 128 x 128 tiling).  Per shape: torch-event time of the forward alone, forward + separate sketch, fused forward.
+    One JSON line per shape and a summary line."""
+    ctx = binding.Context()
+    N, r = args.tokens, args.rank
+    rows, tot = [], {"forward": 0.0, "separate": 0.0, "fused": 0.0}
+    xs = {}
+    for name, d_in, d_out in synth.QWEN3_0P6B_LAYER:
+        if d_in not in xs:
+            xs[d_in] = synth.device_powerlaw_x(100 + d_in, N, d_in)
+        X = xs[d_in]
+        W, T = synth.device_weights_and_target(3 + d_out, X, d_out)
+        L, loss = binding.make_layer(W, X, r), binding.make_loss(T)
+        sc = torch.zeros(1, dtype=torch.float64, device="cuda")
+        S = torch.empty(d_in, r, dtype=torch.float32, device="cuda")
+        variants = {"forward": lambda: ctx.layer_forward_sketch(L, W, X, None, binding.SKETCH_NONE, None, 1, None, loss, sc),
+                    "separate": lambda: ctx.layer_forward_sketch(L, W, X, None, binding.SKETCH_RANGE, None, 1, S, loss, sc),
+                    "fused": lambda: ctx.layer_forward_sketch(L, W, X, None, binding.SKETCH_RANGE_FUSED, None, 1, S, loss, sc)}
+        res = {"shape": "%s %d->%d" % (name, d_in, d_out), "tokens": N, "rank": r}
+        for vname, fn in variants.items():
+            for _ in range(5):
+                fn()
+            ctx.check()
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+            ev[0].record()
+            for i in range(args.steps):
+                fn()
+                ev[i + 1].record()
+            torch.cuda.synchronize()
+            us = sorted(1e3 * ev[i].elapsed_time(ev[i + 1]) for i in range(args.steps))
+            res[vname + "_us"] = us[len(us) // 2]
+            tot[vname] += us[len(us) // 2]
+        res["sketch_bytes"] = 2.0 * N * d_in
+        rows.append(res)
+        print(json.dumps(res), flush=True)
+        del W, T
+    print(json.dumps({"summary": "sum over the seven projections, us", **tot,
+                      "separate_minus_forward": tot["separate"] - tot["forward"], "fused_minus_forward": tot["fused"] - tot["forward"]}))
+
+
 def sweep(args):
     """Qwen3-4B shapes, r in {1,4,16,64} x N in {512,4096,16384,65536}: per kernel the achieved rate, the
     algorithmic intensity and which roofline (HBM or MFMA) bounds it.  Prints one text table."""
@@ -411,6 +453,9 @@ def main():
     ap.add_argument("--sweep", action="store_true", help="rank x tokens sweep on Qwen3-4B shapes (text table)")
     ap.add_argument("--gemm-shapes", action="store_true",
                     help="time the forward GEMM alone on each distinct Qwen3-8B projection shape (one JSON line each)")
+    ap.add_argument("--sketch-fusion", action="store_true",
+                    help="time the range sketch as a sweep of its own against the one the forward GEMM emits, on the Qwen3-0.6B "
+                         "projection shapes (use --tokens 2048)")
     ap.add_argument("--shape", choices=["q", "k", "gate", "down"], default=None, help="with --gemm-shapes: only this shape")
     ap.add_argument("--no-extras", action="store_true",
                     help="only the timed workload and its stage breakdown (for counter-collection runs of the profiler)")
@@ -433,6 +478,9 @@ def main():
         return
     if args.gemm_shapes:
         gemm_shapes(args)
+        return
+    if args.sketch_fusion:
+        sketch_fusion(args)
         return
     if args.workload == "decoder":
         ctx = binding.Context()
