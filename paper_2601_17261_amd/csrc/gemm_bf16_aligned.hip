@@ -14,6 +14,18 @@
 // waits out the latency, and the staging registers spilled.)  All evaluations of a step start from the same -Y*, so
 // f+ and f- still share bit-identical accumulators up to the rank-r slices.
 //
+// Persistent workgroups.
+// One workgroup per compute unit walks through a list of tiles (its LDS and accumulators leave no room for a second one,
+// so a workgroup per tile paid the launch of a workgroup, the latency of the first operand slices and of the target, and
+// an unpipelined last slice once per tile, with the matrix cores idle: about an eighth of a tile's time).  The slice
+// loop runs across tile boundaries: every slice, the last one of a tile included, is a steady iteration whose loads
+// fetch the slice after next - at the end of a tile the first two slices of the next tile - so when a tile's last
+// matrix instruction has issued, the next tile's first slice is in LDS and its first fragments are in registers.
+// Between two tiles only the accumulators change hands: the next target is requested, the finished tile is evaluated
+// (or stored) while it travels, and the accumulators restart from minus the new target.  The tile list keeps the
+// order that makes an XCD's 32 workgroups share operand slices in its L2: XCD x (workgroup id mod 8) owns a contiguous
+// run of tiles, and its workgroups take them 32 at a time.
+//
 // PHASES = 3 is the shared-forward schedule for a single layer: the d_in slices are multiplied once, f0 is the sum of
 // squares of the accumulators as they stand, the extension slices with +eps make them the residual of f+, the same
 // slices with -2 eps that of f-.  The extension operands of both passes are requested before the evaluation that
@@ -31,6 +43,20 @@ __device__ __forceinline__ float to_acc(float x) {
     return r;
 }
 
+// buffer descriptor over everything from `base` on (no range check: the kernel only takes tiles that lie inside)
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t rsrc(const bf16_t* base) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(base), 0, (int)0xFFFFFFFFu, 0x00020000);
+}
+
+// ... and read back by hand, one value at a time in program order: left to itself the compiler copies all 256
+// accumulators into ordinary registers at once before it sums their squares, and whatever else is live at that moment
+// (the next tile's target) goes to scratch memory
+__device__ __forceinline__ float from_acc(float x) {
+    float r;
+    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(r) : "a"(x));
+    return r;
+}
+
 template <int OUT, bool T_F32, int PHASES>
 __global__ __launch_bounds__(256) void gemm_bf16_aligned_kernel(GemmParams p) {
     static_assert(OUT == 0 || (PHASES == 1 && !T_F32), "the storing kernel has one evaluation and no target");
@@ -42,34 +68,55 @@ __global__ __launch_bounds__(256) void gemm_bf16_aligned_kernel(GemmParams p) {
     const int wa = wave >> 1, wb = wave & 1;
     const int lr = lane & 31, lh = lane >> 5;
 
-    // workgroup -> tile: each XCD (ids are dealt round-robin over the 8 XCDs) owns a contiguous run of tiles, walked in
-    // bands of group_m token tiles per output tile so that its L2 keeps a W tile and a band of X tiles
-    int wg = (int)blockIdx.x;
+    // ---- this workgroup's tiles ---------------------------------------------------------------------
+    // XCD x = id mod 8 (ids are dealt round-robin over the XCDs) owns the run of tiles [x per, (x + 1) per), walked by
+    // its S workgroups S at a time; the up to 7 tiles left over go to the last workgroup of the first XCDs.  Inside a
+    // run, tiles are ordered in bands of group_m token tiles per output tile, so that the tiles an XCD works on at any
+    // moment share a few W tiles and a band of X tiles.
     const int nwg = p.tiles_m * p.tiles_n;
-    {
-        const int per = nwg / 8;
-        if (wg < per * 8) wg = (wg % 8) * per + wg / 8;
-    }
+    const int G = (int)gridDim.x;
+    const bool by_xcd = (G % 8 == 0);
+    const int S = by_xcd ? G / 8 : G;
+    const int xcd = by_xcd ? (int)blockIdx.x % 8 : 0, slot = by_xcd ? (int)blockIdx.x / 8 : (int)blockIdx.x;
+    const int per = by_xcd ? nwg / 8 : nwg;
+    const int n_run = slot < per ? (per - slot + S - 1) / S : 0;
+    const int n_tiles = __builtin_amdgcn_readfirstlane(n_run + ((by_xcd && slot == S - 1 && xcd < nwg - 8 * per) ? 1 : 0));
     const int GROUP_M = p.group_m;
-    const int group = wg / (GROUP_M * p.tiles_n);
-    const int first_m = group * GROUP_M;
-    const int gsz = min(GROUP_M, p.tiles_m - first_m);
-    const int in_group = wg - group * GROUP_M * p.tiles_n;
-    const int64_t tm = __builtin_amdgcn_readfirstlane(first_m + in_group % gsz);
-    const int64_t tn = __builtin_amdgcn_readfirstlane(in_group / gsz);
-    const int64_t m0 = tm * BT, n0 = tn * BT;
+    int64_t tm = 0, tn = 0;
+    auto tile_at = [&](int i, int64_t& tm_, int64_t& tn_) __attribute__((always_inline)) {
+        const int lin = (i < n_run) ? xcd * per + slot + i * S : 8 * per + xcd;
+        const int group = lin / (GROUP_M * p.tiles_n);
+        const int first_m = group * GROUP_M;
+        const int gsz = min(GROUP_M, p.tiles_m - first_m);
+        const int in_group = lin - group * GROUP_M * p.tiles_n;
+        tm_ = __builtin_amdgcn_readfirstlane(first_m + in_group % gsz);
+        tn_ = __builtin_amdgcn_readfirstlane(in_group / gsz);
+    };
+    if (n_tiles == 0) return;
+    tile_at(0, tm, tn);
+    int64_t m0 = tm * BT, n0 = tn * BT;
 
     // ---- operand sources: X / W slices, then the prepared extension operands ----------------------
-    auto rsrc = [&](const bf16_t* base) {
-        return __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(base), 0, (int)0xFFFFFFFFu, 0x00020000);
-    };
-    const bf16_t* xbase = p.X + m0 * p.ldx;
-    const bf16_t* wbase = p.W + n0 * p.ldw;
     const bool has_ext = p.Xext != nullptr;
-    const __amdgpu_buffer_rsrc_t rx = rsrc(xbase), rw = rsrc(wbase);
-    const __amdgpu_buffer_rsrc_t rx2 = rsrc(has_ext ? p.Xext + m0 * p.ext_ld : xbase);
-    const __amdgpu_buffer_rsrc_t rw2 = rsrc(has_ext ? p.Wext + n0 * p.ext_ld : wbase);
-    const __amdgpu_buffer_rsrc_t rw3 = rsrc((has_ext && PHASES == 3) ? p.Wext2 + n0 * p.ext_ld : wbase);
+    // operand bases of the current tile (d_in slices, extension slices) and of the next tile's d_in slices
+    const bf16_t *xb, *wb_, *xb2, *wb2, *wb3, *xbn, *wbn;
+    auto tile_sources = [&]() __attribute__((always_inline)) {
+        xb = p.X + m0 * p.ldx;
+        wb_ = p.W + n0 * p.ldw;
+        xb2 = has_ext ? p.Xext + m0 * p.ext_ld : xb;
+        wb2 = has_ext ? p.Wext + n0 * p.ext_ld : wb_;
+        wb3 = (has_ext && PHASES == 3) ? p.Wext2 + n0 * p.ext_ld : wb_;
+    };
+    // i: index of the tile after the current one; past the list: the current tile once more (its first slices are
+    // fetched again into the stage nobody reads)
+    auto next_sources = [&](int i) __attribute__((always_inline)) {
+        int64_t tmn = tm, tnn = tn;
+        if (i < n_tiles) tile_at(i, tmn, tnn);
+        xbn = p.X + tmn * BT * p.ldx;
+        wbn = p.W + tnn * BT * p.ldw;
+    };
+    tile_sources();
+    next_sources(1);
     const int row0 = 8 * wave + (lane >> 3);                 // row of group t = row0 + 32 t (X), 32 t + w_perm(row0) (W)
     const int chunk0 = (lane & 7) ^ ((row0 >> 1) & 7);       // the swizzle term does not depend on t
     const int vx = (int)(((int64_t)row0 * p.ldx + chunk0 * 8) * 2), vw = (int)(((int64_t)w_perm(row0) * p.ldw + chunk0 * 8) * 2);
@@ -78,6 +125,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_aligned_kernel(GemmParams p) {
     const int nfull = (int)(p.K / BK);
     const int next = has_ext ? p.ext_ld / BK : 0;
     // slices that ride the load pipeline: the d_in slices, and in the one-evaluation kernel the extension behind them
+    // (at least two: the first two slices of a tile are always d_in slices)
     const int npipe = nfull + (PHASES == 1 ? next : 0);
     typedef __attribute__((address_space(3))) void* lptr_t;
 
@@ -151,15 +199,30 @@ __global__ __launch_bounds__(256) void gemm_bf16_aligned_kernel(GemmParams p) {
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[s][i], b[s][j], acc[i][j], 0, 0, 0);
     };
     // source of a pipelined slice, chosen once per slice with scalar selects (no branches at the load sites)
-    __amdgpu_buffer_rsrc_t src_rsx[2] = {rx, rx}, src_rsw[2] = {rw, rw};
+    __amdgpu_buffer_rsrc_t src_rsx[2] = {rsrc(xb), rsrc(xb)}, src_rsw[2] = {rsrc(wb_), rsrc(wb_)};
     int src_vx[2] = {vx, vx}, src_vw[2] = {vw, vw}, src_so[2] = {0, 0}, src_gx[2] = {gsx, gsx}, src_gw[2] = {gsw, gsw};
+    // kt counts from the current tile's first slice; npipe and npipe + 1 are the first two slices of the next tile.
+    // Two rounds of selects, each on one condition, between values (a select between captured references becomes a
+    // computed address into the closure, which then stays in memory with everything it points to; and selects on
+    // mixed conditions cost four scalar instructions each instead of one)
     auto select_slice = [&](auto SET, int kt) __attribute__((always_inline)) {
         constexpr int set = decltype(SET)::value;
-        const bool e = kt >= nfull;
-        src_rsx[set] = e ? rx2 : rx;   src_rsw[set] = e ? rw2 : rw;
-        src_vx[set] = e ? vx2 : vx;    src_vw[set] = e ? vw2 : vw;
-        src_so[set] = (e ? kt - nfull : kt) * (BK * 2);
-        src_gx[set] = e ? gs2 : gsx;   src_gw[set] = e ? gs2 : gsw;
+        // (copies first: the selects then see values, not addresses of captured variables)
+        const bf16_t *cxb = xb, *cwb = wb_, *cxb2 = xb2, *cwb2 = wb2, *cxbn = xbn, *cwbn = wbn;
+        const int cvx = vx, cvw = vw, cvx2 = vx2, cvw2 = vw2, cgsx = gsx, cgsw = gsw, cgs2 = gs2;
+        const bool e = kt >= nfull;                          // extension operands (or, past npipe, the next tile)
+        const bf16_t* xs = e ? cxb2 : cxb;
+        const bf16_t* ws = e ? cwb2 : cwb;
+        int svx = e ? cvx2 : cvx, svw = e ? cvw2 : cvw, sgx = e ? cgs2 : cgsx, sgw = e ? cgs2 : cgsw;
+        int so = e ? kt - nfull : kt;
+        const bool nxt = kt >= npipe;
+        xs = nxt ? cxbn : xs;
+        ws = nxt ? cwbn : ws;
+        svx = nxt ? cvx : svx;   svw = nxt ? cvw : svw;   sgx = nxt ? cgsx : sgx;   sgw = nxt ? cgsw : sgw;
+        so = nxt ? kt - npipe : so;
+        src_rsx[set] = rsrc(xs);   src_rsw[set] = rsrc(ws);
+        src_vx[set] = svx;   src_vw[set] = svw;   src_gx[set] = sgx;   src_gw[set] = sgw;
+        src_so[set] = so * (BK * 2);
     };
     // direct load q (0..15) of the selected slice into buffer buf: even q = X row group q/2, odd q = W row group
     auto dma1 = [&](auto SET, int buf, int q) __attribute__((always_inline)) {
@@ -179,28 +242,14 @@ __global__ __launch_bounds__(256) void gemm_bf16_aligned_kernel(GemmParams p) {
             mfma1(s_cur, q);
             const int o = q >> 1;
             if (!(q & 1)) frag1(rbuf, rkk, rs, o);
-            else if (((o + 1) * n) / 8 > (o * n) / 8) dma1(SET, lbuf, d0 + (o * n) / 8);
+            else {
+#pragma unroll
+                for (int d = (o * n) / 8; d < ((o + 1) * n) / 8; ++d) dma1(SET, lbuf, d0 + d);
+            }
             __builtin_amdgcn_sched_barrier(0);
         }
     };
     constexpr int N3 = 8;      // loads of slice kt+2 issued in the last block of slice kt; the other 8 in the first of kt+1
-    // slices kt0 .. kt1-1; on entry fragment set 0 holds sub-step 0 of slice kt0 and the first N3 loads of slice
-    // kt0+1 are in flight; the same holds for kt1 on exit
-    auto steady = [&](int kt0, int kt1) __attribute__((always_inline)) {
-        for (int kt = kt0; kt < kt1; ++kt) {
-            const int cur = kt & 1;
-            select_slice(IC<0>{}, kt + 1);
-            block(IC<0>{}, cur, IC<1>{}, IC<1>{}, IC<0>{}, cur ^ 1, IC<N3>{}, IC<16>{});
-            block(IC<1>{}, cur, IC<2>{}, IC<0>{}, IC<0>{}, 0, IC<0>{}, IC<0>{});
-            block(IC<0>{}, cur, IC<3>{}, IC<1>{}, IC<0>{}, 0, IC<0>{}, IC<0>{});
-            __builtin_amdgcn_s_waitcnt(0x0070);              // vmcnt(0) lgkmcnt(0): the next slice has landed
-            __builtin_amdgcn_s_barrier();
-            __builtin_amdgcn_sched_barrier(0);
-            const int k2 = min(kt + 2, npipe - 1);           // past the end: a re-fetch into the buffer nobody reads
-            select_slice(IC<1>{}, k2);
-            block(IC<1>{}, cur ^ 1, IC<0>{}, IC<0>{}, IC<1>{}, cur, IC<0>{}, IC<N3>{});
-        }
-    };
     // a slice whose operands are complete in buffer `buf`; FIRST_READ: fragment set 0 not yet read
     auto multiply_slice = [&](int buf, bool first_read) __attribute__((always_inline)) {
         if (first_read) {
@@ -221,7 +270,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_aligned_kernel(GemmParams p) {
     // ---- sum of squares of the accumulators: fp32 squares four at a time, summed in fp64; lanes, then waves, in a
     // fixed order ----
     double* red = reinterpret_cast<double*>(smem + 4 * TILE_BYTES);
-    auto evaluate = [&](int phase) __attribute__((always_inline)) {
+    auto evaluate = [&](int phase, int64_t tm_, int64_t tn_) __attribute__((always_inline)) {
         double part = 0.0;
 #pragma clang loop unroll(full)
         for (int j = 0; j < BB; ++j)
@@ -232,7 +281,11 @@ __global__ __launch_bounds__(256) void gemm_bf16_aligned_kernel(GemmParams p) {
                 for (int q = 0; q < 4; ++q) {
                     float s4 = 0.f;
 #pragma clang loop unroll(full)
-                    for (int u = 0; u < 4; ++u) s4 = fmaf(v[4 * q + u], v[4 * q + u], s4);
+                    for (int u = 0; u < 4; ++u) {
+                        // (the shared-forward schedule multiplies on after an evaluation and nothing else is live there)
+                        const float x = (PHASES == 1) ? from_acc(v[4 * q + u]) : v[4 * q + u];
+                        s4 = fmaf(x, x, s4);
+                    }
                     part += (double)s4;
                 }
             }
@@ -241,102 +294,152 @@ __global__ __launch_bounds__(256) void gemm_bf16_aligned_kernel(GemmParams p) {
         if (lane == 0) red[phase * 4 + wave] = part;
         __syncthreads();
         if (tid == 0)
-            p.partials[(int64_t)phase * p.tiles_m * p.tiles_n + tm * p.tiles_n + tn] =
+            p.partials[(int64_t)phase * p.tiles_m * p.tiles_n + tm_ * p.tiles_n + tn_] =
                 (red[phase * 4] + red[phase * 4 + 1]) + (red[phase * 4 + 2] + red[phase * 4 + 3]);
     };
 
-    // ---- the tile -----------------------------------------------------------------------------------
-    if constexpr (OUT == 0) {
-        tload(IC<0>{}); tload(IC<1>{});
-        if (!T_F32) { tload(IC<2>{}); tload(IC<3>{}); }
-    }
+    // accumulators <- minus the target tile (squared error) or zero (stored output)
+    auto start_tile = [&]() __attribute__((always_inline)) {
+        if constexpr (OUT == 0) {
+            tneg(IC<0>{}); tneg(IC<1>{});
+            if (T_F32) { tload(IC<2>{}); tload(IC<3>{}); }
+            tneg(IC<2>{}); tneg(IC<3>{});
+        } else {
+#pragma unroll
+            for (int i = 0; i < BA; ++i)
+#pragma unroll
+                for (int j = 0; j < BB; ++j)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+        }
+    };
+    auto request_target = [&]() __attribute__((always_inline)) {
+        if constexpr (OUT == 0) {
+            tload(IC<0>{}); tload(IC<1>{});
+            if (!T_F32) { tload(IC<2>{}); tload(IC<3>{}); }
+        }
+    };
+
+    // ---- first tile: target, the first slice and the head of the second ------------------------------
+    request_target();
     select_slice(IC<0>{}, 0);
 #pragma unroll
     for (int q = 0; q < 16; ++q) dma1(IC<0>{}, 0, q);
     select_slice(IC<1>{}, 1);
 #pragma unroll
     for (int q = 0; q < N3; ++q) dma1(IC<1>{}, 1, q);
-    if constexpr (OUT == 0) {
-        tneg(IC<0>{}); tneg(IC<1>{});
-        if (T_F32) { tload(IC<2>{}); tload(IC<3>{}); }
-        tneg(IC<2>{}); tneg(IC<3>{});
-    } else {
-#pragma unroll
-        for (int i = 0; i < BA; ++i)
-#pragma unroll
-            for (int j = 0; j < BB; ++j)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
-    }
-    if (OUT == 0 && T_F32) __builtin_amdgcn_s_waitcnt(0x0F70);   // the second half of an fp32 target was requested last
-    else __builtin_amdgcn_s_waitcnt(0x0F70 | N3);                // vmcnt(N3): slice 0 has landed
-    __syncthreads();
-#pragma unroll
-    for (int q = 0; q < 8; ++q) frag1(0, 0, 0, q);
-    steady(0, npipe - 1);
-    __builtin_amdgcn_s_waitcnt(0x0F70);                      // the re-fetches
-    multiply_slice((npipe - 1) & 1, false);                  // last pipelined slice: sub-step 0 is already in set 0
-    __syncthreads();
-    if constexpr (OUT == 1) {
-        // lane = one token, 16 consecutive outputs per block: two 16-byte stores each
-#pragma clang loop unroll(full)
-        for (int j = 0; j < BB; ++j) {
-            bf16_t* yrow = reinterpret_cast<bf16_t*>(p.Y) + (m0 + wb * 128 + j * 32 + lr) * p.ldy + n0 + wa * 128 + lh * 16;
-#pragma clang loop unroll(full)
-            for (int i = 0; i < BA; ++i) {
-                const floatx16 v = acc[i][j];
-                uint32_t w[8];
-#pragma clang loop unroll(full)
-                for (int q = 0; q < 8; ++q) w[q] = pack_bf16x2(v[2 * q], v[2 * q + 1]);
-                uint4* dst = reinterpret_cast<uint4*>(yrow + i * 32);
-                dst[0] = make_uint4(w[0], w[1], w[2], w[3]);
-                dst[1] = make_uint4(w[4], w[5], w[6], w[7]);
-            }
-        }
-    } else if constexpr (PHASES == 1) {
-        evaluate(0);
-    } else {
-        // both LDS stages are free: the first extension slice of each perturbed evaluation is requested before the
-        // evaluation that precedes it (stage 0 for +eps, stage 1 for -2 eps); further slices (r > 16) one at a time
-        auto ext_dma = [&](const __amdgpu_buffer_rsrc_t& rws, int e, int buf) __attribute__((always_inline)) {
-#pragma unroll
-            for (int q = 0; q < 16; ++q) {
-                const int t = q >> 1;
-                char* dst = smem + buf * (2 * TILE_BYTES) + wave * 1024 + t * 4096 + ((q & 1) ? TILE_BYTES : 0);
-                if (q & 1) __builtin_amdgcn_raw_ptr_buffer_load_lds(rws, (lptr_t)dst, 16, vw2 + t * gs2, e * (BK * 2), 0, 0);
-                else __builtin_amdgcn_raw_ptr_buffer_load_lds(rx2, (lptr_t)dst, 16, vx2 + t * gs2, e * (BK * 2), 0, 0);
-            }
-        };
-        if (next > 0) ext_dma(rw2, 0, 0);
-        evaluate(0);
-        if (next > 0) {
-            ext_dma(rw3, 0, 1);
-            __builtin_amdgcn_s_waitcnt(0x0F70 | 16);         // the +eps slice has landed (the -2 eps one may be in flight)
+
+    int g = 0;                                               // slices multiplied so far: slice g sits in LDS stage g & 1
+    for (int it = 0;; ++it) {
+        // the accumulators are written here and nowhere else, and are dead at the end of the loop body: carried around
+        // the loop they would pass through a join, which the compiler answers by spilling them
+        start_tile();
+        if (it == 0) {
+            __builtin_amdgcn_s_waitcnt(0x0F70 | N3);         // vmcnt(N3): slice 0 has landed
             __syncthreads();
-            multiply_slice(0, true);
-            for (int e = 1; e < next; ++e) {
-                __syncthreads();
-                ext_dma(rw2, e, 0);
-                __builtin_amdgcn_s_waitcnt(0x0F70);
-                __syncthreads();
-                multiply_slice(0, true);
-            }
+#pragma unroll
+            for (int q = 0; q < 8; ++q) frag1(0, 0, 0, q);
         }
-        evaluate(1);
-        if (next > 0) {
+        // every slice of the tile, the last one included, in LDS stage cur = g & 1: on entry fragment set 0 holds its
+        // sub-step 0 and the first N3 loads of the next slice are in flight into the other stage; the same holds for the
+        // next slice on exit
+        for (int kt = 0; kt < npipe; ++kt, ++g) {
+            const int cur = g & 1;
+            select_slice(IC<0>{}, kt + 1);
+            block(IC<0>{}, cur, IC<1>{}, IC<1>{}, IC<0>{}, cur ^ 1, IC<N3>{}, IC<16>{});
+            block(IC<1>{}, cur, IC<2>{}, IC<0>{}, IC<0>{}, 0, IC<0>{}, IC<0>{});
+            block(IC<0>{}, cur, IC<3>{}, IC<1>{}, IC<0>{}, 0, IC<0>{}, IC<0>{});
+            __builtin_amdgcn_s_waitcnt(0x0070);              // vmcnt(0) lgkmcnt(0): the next slice has landed
+            __builtin_amdgcn_s_barrier();
+            __builtin_amdgcn_sched_barrier(0);
+            select_slice(IC<1>{}, kt + 2);
+            block(IC<1>{}, cur ^ 1, IC<0>{}, IC<0>{}, IC<1>{}, cur, IC<0>{}, IC<N3>{});
+        }
+        // the tile's last matrix instruction has issued; stage g & 1 holds the next tile's first slice, fragment set 0 its
+        // sub-step 0, and the head of its second slice is in flight
+        const bool more = it + 1 < n_tiles;
+        if constexpr (OUT == 1) {
+            // lane = one token, 16 consecutive outputs per block: two 16-byte stores each
+#pragma clang loop unroll(full)
+            for (int j = 0; j < BB; ++j) {
+                bf16_t* yrow = reinterpret_cast<bf16_t*>(p.Y) + (m0 + wb * 128 + j * 32 + lr) * p.ldy + n0 + wa * 128 + lh * 16;
+#pragma clang loop unroll(full)
+                for (int i = 0; i < BA; ++i) {
+                    const floatx16 v = acc[i][j];
+                    uint32_t w[8];
+#pragma clang loop unroll(full)
+                    for (int q = 0; q < 8; ++q) w[q] = pack_bf16x2(v[2 * q], v[2 * q + 1]);
+                    uint4* dst = reinterpret_cast<uint4*>(yrow + i * 32);
+                    dst[0] = make_uint4(w[0], w[1], w[2], w[3]);
+                    dst[1] = make_uint4(w[4], w[5], w[6], w[7]);
+                }
+            }
+            if (!more) break;
+        } else if constexpr (PHASES == 1) {
+            const int64_t tm_done = tm, tn_done = tn;
+            if (more) {
+                tile_at(it + 1, tm, tn);
+                m0 = tm * BT; n0 = tn * BT;
+                request_target();                            // travels while the finished tile is evaluated
+            }
+            evaluate(0, tm_done, tn_done);
+            if (!more) break;
+        } else {
+            // shared forward: one tile per workgroup.  Both LDS stages are free once the re-fetched slices have landed: the
+            // first extension slice of each perturbed evaluation is requested before the evaluation that precedes it (stage
+            // 0 for +eps, stage 1 for -2 eps); further slices (r > 16) one at a time
             __builtin_amdgcn_s_waitcnt(0x0F70);
             __syncthreads();
-            multiply_slice(1, true);
-            for (int e = 1; e < next; ++e) {
+            const __amdgpu_buffer_rsrc_t rx2 = rsrc(xb2), rw2 = rsrc(wb2), rw3 = rsrc(wb3);
+            auto ext_dma = [&](const __amdgpu_buffer_rsrc_t& rws, int e, int buf) __attribute__((always_inline)) {
+#pragma unroll
+                for (int q = 0; q < 16; ++q) {
+                    const int t = q >> 1;
+                    char* dst = smem + buf * (2 * TILE_BYTES) + wave * 1024 + t * 4096 + ((q & 1) ? TILE_BYTES : 0);
+                    if (q & 1) __builtin_amdgcn_raw_ptr_buffer_load_lds(rws, (lptr_t)dst, 16, vw2 + t * gs2, e * (BK * 2), 0, 0);
+                    else __builtin_amdgcn_raw_ptr_buffer_load_lds(rx2, (lptr_t)dst, 16, vx2 + t * gs2, e * (BK * 2), 0, 0);
+                }
+            };
+            if (next > 0) ext_dma(rw2, 0, 0);
+            evaluate(0, tm, tn);
+            if (next > 0) {
+                ext_dma(rw3, 0, 1);
+                __builtin_amdgcn_s_waitcnt(0x0F70 | 16);     // the +eps slice has landed (the -2 eps one may be in flight)
                 __syncthreads();
-                ext_dma(rw3, e, 1);
+                multiply_slice(0, true);
+                for (int e = 1; e < next; ++e) {
+                    __syncthreads();
+                    ext_dma(rw2, e, 0);
+                    __builtin_amdgcn_s_waitcnt(0x0F70);
+                    __syncthreads();
+                    multiply_slice(0, true);
+                }
+            }
+            evaluate(1, tm, tn);
+            if (next > 0) {
                 __builtin_amdgcn_s_waitcnt(0x0F70);
                 __syncthreads();
                 multiply_slice(1, true);
+                for (int e = 1; e < next; ++e) {
+                    __syncthreads();
+                    ext_dma(rw3, e, 1);
+                    __builtin_amdgcn_s_waitcnt(0x0F70);
+                    __syncthreads();
+                    multiply_slice(1, true);
+                }
             }
+            evaluate(2, tm, tn);
+            break;
         }
-        evaluate(2);
+        // ---- hand the accumulators to the next tile ----
+        if constexpr (OUT == 1) {
+            tile_at(it + 1, tm, tn);
+            m0 = tm * BT; n0 = tn * BT;
+        }
+        tile_sources();
+        next_sources(it + 2);
     }
+    __builtin_amdgcn_s_waitcnt(0x0F70);                      // the slices fetched past the end of the list
     if (p.clk && blockIdx.x == 0 && tid == 0) { p.clk[2] = __builtin_readcyclecounter(); p.clk[3] = wall_clock64(); }
 }
 
@@ -350,7 +453,19 @@ static hipError_t launch_aligned_variant(const GemmParams& p, hipStream_t st) {
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    dim3 grid((unsigned)((int64_t)p.tiles_m * p.tiles_n));
+    // one workgroup per compute unit, each with a list of tiles (a multiple of 8 workgroups: one share per XCD); the
+    // shared-forward schedule needs both LDS stages between its evaluations and takes one tile per workgroup
+    int64_t G = (int64_t)p.tiles_m * p.tiles_n;
+    if (PHASES == 1) {
+        int dev = 0, cus = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e != hipSuccess) return e;
+        if (cus < 1) return hipErrorInvalidDevice;
+        if (G > cus) G = cus;
+        if (G >= 8) G -= G % 8;
+    }
+    dim3 grid((unsigned)G);
     hipLaunchKernelGGL((gemm_bf16_aligned_kernel<OUT, T_F32, PHASES>), grid, dim3(256), smem, st, p);
     return hipGetLastError();
 }

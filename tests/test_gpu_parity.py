@@ -825,6 +825,44 @@ def test_tile_aligned_shapes_take_the_specialised_loss_epilogues(ctx, target_dty
     assert_increment(host(Wd), W.astype(np.float64), o["W_new"], "bf16")
 
 
+@pytest.mark.parametrize("n,d_in,d_out", [(4352, 128, 4352),    # 289 tiles: 36 per XCD, one left over; the shortest pipeline
+                                          (4096, 192, 4352),    # 272 tiles: 34 per XCD, so two workgroups per XCD take two
+                                          (2048, 320, 16640)])  # 520 tiles: every workgroup takes two, eight take three
+def test_more_tiles_than_compute_units_walks_tile_lists(ctx, n, d_in, d_out):
+    """The tile-aligned kernel runs one workgroup per compute unit, each walking a list of tiles with the next tile's first
+    slices fetched under the last slices of the current one: losses (plain and perturbed, bf16 and fp32 targets) and the
+    stored bf16 output against the oracle where some workgroups take one tile more than others."""
+    r, seed = 16, 91
+    W, X, T, Wd, Xd, Td = problem(7, n, d_in, d_out, "powerlaw", "bf16")
+    X64, W64 = X.astype(np.float64), W.astype(np.float64)
+    Y0 = oagzo.forward(X64, W64)
+    L = binding.make_layer(Wd, Xd, r)
+    B = torch.empty(d_in, r, dtype=torch.float32, device="cuda")
+    ctx.basis(L, Xd, 1, seed, None, 0, B)
+    Z, _ = oagzo.perturbation(host(B), seed, d_out)
+    Yp = oagzo.forward(X64, W64 + EPS * Z)
+    for tdt in ("bf16", "f32"):
+        Tt = synth.to_bf16_values(T) if tdt == "bf16" else T
+        Ttd = dev(Tt, tdt)
+        sc = torch.zeros(2, dtype=torch.float64, device="cuda")
+        ctx.layer_forward_sketch(L, Wd, Xd, None, binding.SKETCH_NONE, None, 1, None, binding.make_loss(Ttd), sc[0:1])
+        ctx.perturbed_forward(L, Wd, Xd, B, seed, EPS, None, binding.make_loss(Ttd), sc[1:2])
+        ctx.check()
+        l0, lp = oagzo.mse_loss(Y0, Tt), oagzo.mse_loss(Yp, Tt)
+        assert abs(sc[0].item() - l0) < 1e-5 * l0, tdt
+        assert abs(sc[1].item() - lp) < 1e-5 * lp, tdt
+    # stored output: every tile of every workgroup's list
+    Y = torch.full((n, d_out), 7.0, dtype=torch.bfloat16, device="cuda")
+    Ly = binding.make_layer(Wd, Xd, r, Y=Y)
+    ctx.perturbed_forward(Ly, Wd, Xd, B, seed, EPS, Y, None, None)
+    ctx.check()
+    got = host(Y)
+    assert np.abs(got - Yp).max() <= 2.0 ** -8 * np.abs(Yp).max() + 1e-6
+    assert rel(got, Yp) < 3e-3
+    tiles = np.abs(got - Yp).reshape(n // 256, 256, d_out // 256, 256).max(axis=(1, 3)) / np.abs(Yp).max()
+    assert tiles.max() < 2.0 ** -8, np.unravel_index(tiles.argmax(), tiles.shape)
+
+
 @pytest.mark.parametrize("storage", ["f32", "bf16"])
 def test_all_zero_activations_raise_the_numeric_flag_and_leave_the_context_usable(ctx, storage):
     """X = 0: every sketch is zero, the first Cholesky pivot is 0, no basis exists.  The step reports AGZO_ENUMERIC at
