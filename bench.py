@@ -325,7 +325,21 @@ def gemm_shapes(args):
             print(json.dumps({"shape": "%s %d->%d" % (name, d_in, d_out), "tokens": N, "variant": vname, "launches": n,
                               "avg_us": 1e3 * ms / n, "tflops": flops / (ms / n * 1e-3) / 1e12, "shader_clock_ghz": ghz,
                               "algorithmic_bytes": 2.0 * N * d_in + 2.0 * d_in * d_out + 2.0 * N * d_out}), flush=True)
-        del W, T
+        # yardstick: the vendor library's plain bf16 GEMM (torch.matmul -> hipBLASLt / rocBLAS) on the same operands in the same
+        # process: no loss, stores the N x d_out output; what this box's power budget lets a tuned kernel of that shape reach
+        Yl = X @ W.t()
+        for _ in range(3):
+            torch.matmul(X, W.t(), out=Yl)
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+        ev[0].record()
+        for i in range(args.steps):
+            torch.matmul(X, W.t(), out=Yl)
+            ev[i + 1].record()
+        torch.cuda.synchronize()
+        us = sorted(1e3 * ev[i].elapsed_time(ev[i + 1]) for i in range(args.steps))
+        print(json.dumps({"shape": "%s %d->%d" % (name, d_in, d_out), "tokens": N, "variant": "library_gemm_stores_output_no_loss", "launches": args.steps,
+                          "avg_us": sum(us) / len(us), "median_us": us[len(us) // 2], "tflops": 2.0 * N * d_in * d_out / (sum(us) / len(us) * 1e-6) / 1e12}), flush=True)
+        del W, T, Yl
 
 
 def sketch_fusion(args):

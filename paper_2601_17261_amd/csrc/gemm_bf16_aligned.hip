@@ -191,8 +191,10 @@ __global__ __launch_bounds__(256) void gemm_bf16_aligned_kernel(GemmParams p) {
     bf16x8 a[2][BA], b[2][BB];
     auto frag1 = [&](int buf, int kk, int s, int q) __attribute__((always_inline)) {
         const char* base = smem + buf * (2 * TILE_BYTES);
-        if (q < 4) a[s][q] = *reinterpret_cast<const bf16x8*>(base + aoff[kk] + q * 4096);
-        else b[s][q - 4] = *reinterpret_cast<const bf16x8*>(base + boff[kk] + (q - 4) * 4096);
+        // X fragments first: all four are needed by the first four matrix instructions of the block that uses them, a W
+        // fragment only from the fourth instruction of its row on
+        if (q < 4) b[s][q] = *reinterpret_cast<const bf16x8*>(base + boff[kk] + q * 4096);
+        else a[s][q - 4] = *reinterpret_cast<const bf16x8*>(base + aoff[kk] + (q - 4) * 4096);
     };
     auto mfma1 = [&](int s, int idx) __attribute__((always_inline)) {
         const int i = idx >> 2, j = idx & 3;
@@ -345,14 +347,20 @@ __global__ __launch_bounds__(256) void gemm_bf16_aligned_kernel(GemmParams p) {
         // next slice on exit
         for (int kt = 0; kt < npipe; ++kt, ++g) {
             const int cur = g & 1;
-            select_slice(IC<0>{}, kt + 1);
+            // while the two slices ahead are d_in slices of this tile only the K offset moves; the general choice
+            // (extension operands, next tile: some 60 scalar instructions in front of a matrix instruction, 5 % of a
+            // slice's time) is left to the last slices of a tile, behind a branch that is rarely taken
+            const bool tail = kt + 2 >= nfull;
+            if (__builtin_expect(tail, 0)) select_slice(IC<0>{}, kt + 1);
+            else src_so[0] = (kt + 1) * (BK * 2);
             block(IC<0>{}, cur, IC<1>{}, IC<1>{}, IC<0>{}, cur ^ 1, IC<N3>{}, IC<16>{});
             block(IC<1>{}, cur, IC<2>{}, IC<0>{}, IC<0>{}, 0, IC<0>{}, IC<0>{});
             block(IC<0>{}, cur, IC<3>{}, IC<1>{}, IC<0>{}, 0, IC<0>{}, IC<0>{});
             __builtin_amdgcn_s_waitcnt(0x0070);              // vmcnt(0) lgkmcnt(0): the next slice has landed
             __builtin_amdgcn_s_barrier();
             __builtin_amdgcn_sched_barrier(0);
-            select_slice(IC<1>{}, kt + 2);
+            if (__builtin_expect(tail, 0)) select_slice(IC<1>{}, kt + 2);
+            else src_so[1] = (kt + 2) * (BK * 2);
             block(IC<1>{}, cur ^ 1, IC<0>{}, IC<0>{}, IC<1>{}, cur, IC<0>{}, IC<N3>{});
         }
         // the tile's last matrix instruction has issued; stage g & 1 holds the next tile's first slice, fragment set 0 its
