@@ -37,7 +37,9 @@ def bf(a):
     return torch.from_numpy(synth.to_bf16_values(np.asarray(a, dtype=np.float32))).to("cuda", BF)
 
 
-@pytest.mark.parametrize("n_seq,T,H,Hkv", [(2, 13, 2, 1), (3, 100, 4, 2), (1, 200, 8, 8), (2, 64, 2, 2), (1, 1, 2, 1)])
+@pytest.mark.parametrize("n_seq,T,H,Hkv", [(2, 13, 2, 1), (3, 100, 4, 2), (1, 200, 8, 8), (2, 64, 2, 2), (1, 1, 2, 1),
+                                           (2, 512, 16, 8),      # the decoder workload's sequence length and heads
+                                           (1, 129, 4, 1)])      # one query past a workgroup's 128, four query heads per kv head
 def test_attention_core_matches_oracle(ctx, n_seq, T, H, Hkv):
     rng = np.random.default_rng(100 * T + H)
     N = n_seq * T
