@@ -505,7 +505,8 @@ def main():
                "config": {"workload": "28 Qwen3-1.7B-shaped decoder layers (hidden 2048, 16 heads on 8 kv heads, intermediate 6144) + "
                                       "2048x32000 LM head, 16x512 tokens, next-token cross-entropy, r=%d, K=3, global g, %s"
                                       % (args.rank, "shared bases" if args.share_bases else "per-layer bases")},
-               "roofline": {"bound": "mfma", "kernel": "gemm_bf16_kernel", "achieved": st["gemm_tflops"], "peak": PEAK_BF16_TFLOPS,
+               "roofline": {"bound": "mfma", "kernel": "forward GEMMs of the step (gemm_bf16_aligned_kernel<1, false, 1>, gemm_bf16_small_kernel, LM head)",
+                            "achieved": st["gemm_tflops"], "peak": PEAK_BF16_TFLOPS,
                             "unit": "TFLOP/s", "frac": st["gemm_tflops"] / PEAK_BF16_TFLOPS, "traffic": None},
                "detail": st}
         print(json.dumps(res))
@@ -518,7 +519,8 @@ def main():
                "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
                "config": {"workload": "28 SwiGLU-MLP blocks (hidden 2048, intermediate 6144, RMSNorm) + 2048x32000 LM head, "
                                       "16x512 tokens, next-token cross-entropy, r=%d, K=3, global g" % args.rank},
-               "roofline": {"bound": "mfma", "kernel": "gemm_bf16_kernel", "achieved": st["gemm_tflops"], "peak": PEAK_BF16_TFLOPS,
+               "roofline": {"bound": "mfma", "kernel": "forward GEMMs of the step (gemm_bf16_aligned_kernel<1, false, 1>, gemm_bf16_small_kernel, LM head)",
+                            "achieved": st["gemm_tflops"], "peak": PEAK_BF16_TFLOPS,
                             "unit": "TFLOP/s", "frac": st["gemm_tflops"] / PEAK_BF16_TFLOPS, "traffic": None},
                "detail": st}
         print(json.dumps(res))
@@ -639,7 +641,9 @@ def main():
         "config": {"workload": args.workload + " layer projections (q,k,v,o,gate,up,down), N=%d tokens, r=%d, K=%d, "
                                "bf16 weights/activations/targets, MSE loss, %s" % (N, r, K, "naive in-place comparator" if args.naive else "factored perturbed forward"),
                    "tokens": N, "rank": r, "power_steps": K, "eps": eps, "lr": lr},
-        "roofline": {"bound": "mfma", "kernel": "gemm_bf16_kernel", "achieved": gemm_tflops, "peak": PEAK_BF16_TFLOPS,
+        "roofline": {"bound": "mfma", "kernel": ("gemm_bf16_aligned_kernel<0, false, 1>" if args.workload == "qwen3-8b" and N % 256 == 0 and not args.naive
+                                                  else "forward GEMM (gemm_bf16_aligned / gemm_bf16_small / gemm_bf16 kernels, by shape)"),
+                     "achieved": gemm_tflops, "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": gemm_tflops / PEAK_BF16_TFLOPS, "traffic": traffic,
                      "traffic_source": "profiles/gemm_bf16_qwen3_8b_traffic.txt (two rocprofv3 --pmc runs of this command, scaled by a "
                                        "plain copy; counters cannot be read from inside this process)",
