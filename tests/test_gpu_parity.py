@@ -538,6 +538,28 @@ def test_basis_many_is_bit_identical_to_basis(ctx):
     ctx.check()
 
 
+@pytest.mark.parametrize("n,d_in", [(700, 320), (2100, 1096), (64, 4136), (5000, 136)])
+def test_basis_many_with_layers_that_read_the_same_activations(ctx, n, d_in):
+    """q / k / v (and gate / up) of a layer read one tensor: several layers of a batched call point at the same activations,
+    with their own seeds and ranks; bit-identical to the single calls."""
+    rng = np.random.default_rng(n)
+    Xa = dev(synth.to_bf16_values(rng.standard_normal((n, d_in)) * (1.0 / np.arange(1, d_in + 1)) ** 0.5), "bf16")
+    Xb = dev(synth.to_bf16_values(rng.standard_normal((n, d_in))), "bf16")
+    items, want = [], []
+    for li, (X, r) in enumerate([(Xa, 16), (Xa, 9), (Xa, 16), (Xb, 16), (Xa, 12), (Xa, 16), (Xb, 3), (Xb, 3)]):
+        L = binding.make_layer(None, X, r, d_out=8)
+        B1 = torch.empty(d_in, r, dtype=torch.float32, device="cuda")
+        ctx.basis(L, X, 3, 500 + li, None, 0, B1)
+        want.append(B1)
+        items.append((L, X, 500 + li, None, torch.zeros(d_in, r, dtype=torch.float32, device="cuda")))
+    ctx.basis_many(items, 3)
+    ctx.check()
+    for li, (it, B1) in enumerate(zip(items, want)):
+        assert torch.equal(it[4], B1), li
+        Bh = host(B1)
+        assert np.linalg.norm(Bh.T @ Bh - np.eye(Bh.shape[1])) < 1e-4
+
+
 def test_basis_many_more_layers_than_one_launch_holds(ctx):
     rng = np.random.default_rng(5)
     items, want = [], []
