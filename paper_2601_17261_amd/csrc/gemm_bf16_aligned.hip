@@ -202,7 +202,17 @@ __global__ __launch_bounds__(256) void gemm_bf16_aligned_kernel(GemmParams p) {
     };
     // source of a pipelined slice, chosen once per slice with scalar selects (no branches at the load sites)
     __amdgpu_buffer_rsrc_t src_rsx[2] = {rsrc(xb), rsrc(xb)}, src_rsw[2] = {rsrc(wb_), rsrc(wb_)};
-    int src_vx[2] = {vx, vx}, src_vw[2] = {vw, vw}, src_so[2] = {0, 0}, src_gx[2] = {gsx, gsx}, src_gw[2] = {gsw, gsw};
+    int src_so[2] = {0, 0};
+    // vector offsets of a lane's eight row groups per operand, kept in registers: worked out in front of each load they
+    // put an add and its latency between a matrix instruction and the load behind it
+    int src_vxt[2][8], src_vwt[2][8];
+    auto set_offsets = [&](auto SET, int v0x, int gx, int v0w, int gw) __attribute__((always_inline)) {
+        constexpr int set = decltype(SET)::value;
+#pragma unroll
+        for (int t = 0; t < 8; ++t) { src_vxt[set][t] = v0x + t * gx; src_vwt[set][t] = v0w + t * gw; }
+    };
+    set_offsets(IC<0>{}, vx, gsx, vw, gsw);
+    set_offsets(IC<1>{}, vx, gsx, vw, gsw);
     // kt counts from the current tile's first slice; npipe and npipe + 1 are the first two slices of the next tile.
     // Two rounds of selects, each on one condition, between values (a select between captured references becomes a
     // computed address into the closure, which then stays in memory with everything it points to; and selects on
@@ -223,7 +233,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_aligned_kernel(GemmParams p) {
         svx = nxt ? cvx : svx;   svw = nxt ? cvw : svw;   sgx = nxt ? cgsx : sgx;   sgw = nxt ? cgsw : sgw;
         so = nxt ? kt - npipe : so;
         src_rsx[set] = rsrc(xs);   src_rsw[set] = rsrc(ws);
-        src_vx[set] = svx;   src_vw[set] = svw;   src_gx[set] = sgx;   src_gw[set] = sgw;
+        set_offsets(SET, svx, sgx, svw, sgw);
         src_so[set] = so * (BK * 2);
     };
     // direct load q (0..15) of the selected slice into buffer buf: even q = X row group q/2, odd q = W row group
@@ -231,8 +241,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_aligned_kernel(GemmParams p) {
         constexpr int set = decltype(SET)::value;
         const int t = q >> 1;
         char* dst = smem + buf * (2 * TILE_BYTES) + wave * 1024 + t * 4096 + ((q & 1) ? TILE_BYTES : 0);
-        if (q & 1) __builtin_amdgcn_raw_ptr_buffer_load_lds(src_rsw[set], (lptr_t)dst, 16, src_vw[set] + t * src_gw[set], src_so[set], 0, 0);
-        else __builtin_amdgcn_raw_ptr_buffer_load_lds(src_rsx[set], (lptr_t)dst, 16, src_vx[set] + t * src_gx[set], src_so[set], 0, 0);
+        if (q & 1) __builtin_amdgcn_raw_ptr_buffer_load_lds(src_rsw[set], (lptr_t)dst, 16, src_vwt[set][t], src_so[set], 0, 0);
+        else __builtin_amdgcn_raw_ptr_buffer_load_lds(src_rsx[set], (lptr_t)dst, 16, src_vxt[set][t], src_so[set], 0, 0);
     };
     // 16 MFMAs of sub-step S_CUR in fixed issue order: even slots carry one fragment read each (for the next block),
     // odd slots the direct loads D0..D1-1 of the selected slice
