@@ -17,7 +17,7 @@
 // Persistent workgroups.
 // One workgroup per compute unit walks through a list of tiles (its LDS and accumulators leave no room for a second one,
 // so a workgroup per tile paid the launch of a workgroup, the latency of the first operand slices and of the target, and
-// an unpipelined last slice once per tile, with the matrix cores idle: about an eighth of a tile's time).  The slice
+// an unpipelined last slice once per tile, with the matrix cores idle; walking tile lists instead measured 1 - 3 % faster).  The slice
 // loop runs across tile boundaries: every slice, the last one of a tile included, is a steady iteration whose loads
 // fetch the slice after next - at the end of a tile the first two slices of the next tile - so when a tile's last
 // matrix instruction has issued, the next tile's first slice is in LDS and its first fragments are in registers.
@@ -34,6 +34,11 @@
 
 namespace agzo {
 
+// buffer descriptor over everything from `base` on (no range check: the kernel only takes tiles that lie inside)
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t rsrc(const bf16_t* base) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(base), 0, (int)0xFFFFFFFFu, 0x00020000);
+}
+
 // A value moved into an accumulation register by hand: the 256 start values of the accumulators are produced by
 // vector instructions, and left to itself the compiler parks them in ordinary registers (and spills most of them)
 // until the first multiply.
@@ -43,14 +48,10 @@ __device__ __forceinline__ float to_acc(float x) {
     return r;
 }
 
-// buffer descriptor over everything from `base` on (no range check: the kernel only takes tiles that lie inside)
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t rsrc(const bf16_t* base) {
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(base), 0, (int)0xFFFFFFFFu, 0x00020000);
-}
-
 // ... and read back by hand, one value at a time in program order: left to itself the compiler copies all 256
 // accumulators into ordinary registers at once before it sums their squares, and whatever else is live at that moment
-// (the next tile's target) goes to scratch memory
+// (the next tile's target) goes to scratch memory.  The compiler's hazard bookkeeping does not look inside the asm:
+// the caller keeps the 11 wait states that an 8-pass matrix instruction needs before its result may be read.
 __device__ __forceinline__ float from_acc(float x) {
     float r;
     asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(r) : "a"(x));
@@ -284,6 +285,10 @@ __global__ __launch_bounds__(256) void gemm_bf16_aligned_kernel(GemmParams p) {
     double* red = reinterpret_cast<double*>(smem + 4 * TILE_BYTES);
     auto evaluate = [&](int phase, int64_t tm_, int64_t tn_) __attribute__((always_inline)) {
         double part = 0.0;
+        // 16 wait states between the last matrix instruction and from_acc's first read.  (As the code stands the first
+        // block read was written 16 matrix instructions before the end of the slice loop and the last four blocks
+        // written are read some 150 instructions later; this keeps the distance whatever order either side takes.)
+        if constexpr (PHASES == 1) asm volatile("s_nop 7\n\ts_nop 7");
 #pragma clang loop unroll(full)
         for (int j = 0; j < BB; ++j)
 #pragma clang loop unroll(full)
