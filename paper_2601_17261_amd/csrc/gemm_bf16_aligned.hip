@@ -1,10 +1,22 @@
 // Forward GEMM for tile-aligned layers, the case the benchmark configurations run:
 //     OUT = 0:  f = sum over the tile of (X W^T (+ eps (X B) G^T) - Y*)^2     (f0, f+, f- of Sec. 4.1; Eq. 7 factored)
 //     OUT = 1:  Y = X W^T (+ eps (X B) G^T) stored as bf16                     (a layer inside a model, Alg. 2)
-// Same tiling, LDS layout, direct global -> LDS operand loads and fixed-order steady state as gemm_bf16.hip (256 x 256
-// tile, four waves of 128 x 128, v_mfma_f32_32x32x16_bf16, 64-wide K slices, two LDS stages), but a kernel of its own
-// with one straight path and nothing else compiled in: M and N multiples of 256, d_in a multiple of 64 and at least
-// 128, 16-byte aligned target / output rows, the rank-r extension as prepared operands.
+// Same tiling, tile layout in LDS and direct global -> LDS operand loads as gemm_bf16.hip (256 x 256 tile, four waves of
+// 128 x 128, v_mfma_f32_32x32x16_bf16, 64-wide K slices), but a kernel of its own with one straight path and nothing
+// else compiled in: M and N multiples of 256, d_in a multiple of 64 and at least 128, 16-byte aligned target / output
+// rows, the rank-r extension as prepared operands.
+//
+// LDS stages.
+// A 64-wide slice is 32 KiB per operand and the compute unit has 160 KiB: three stages for W and two for X.  A stage
+// can be filled again once every wave has read its last fragment, which the one barrier of a slice establishes (after
+// the third of its four blocks of matrix instructions: fragments are read one block ahead).  With two stages per
+// operand everything for the slice after next had to be requested behind that barrier and to land before the next
+// one, the later half of it within two blocks: the barrier waited for the slowest line, 250 - 450 cycles per slice on
+// the wide layers.  With the third W stage the W half of the slice after next is requested a block before the barrier,
+// into the stage the previous slice left, and has six blocks to land; behind the barrier only the X half is
+// requested, at once, and has three.  The wait in front of the barrier is for all but the eight youngest loads (loads
+// return in the order issued).  Cycles per launch fell by 15 % on the wide layers; the clock, which the power limit
+// sets, gave a third of that back.
 //
 // Squared error (OUT = 0).
 // The accumulators do not start at zero but at minus the target tile: the target is requested before the first
@@ -51,7 +63,7 @@ __device__ __forceinline__ float to_acc(float x) {
 // ... and read back by hand, one value at a time in program order: left to itself the compiler copies all 256
 // accumulators into ordinary registers at once before it sums their squares, and whatever else is live at that moment
 // (the next tile's target) goes to scratch memory.  The compiler's hazard bookkeeping does not look inside the asm:
-// the caller keeps the 11 wait states that an 8-pass matrix instruction needs before its result may be read.
+// the caller keeps the wait states that a matrix instruction needs before its result may be read (19 for the longest).
 __device__ __forceinline__ float from_acc(float x) {
     float r;
     asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(r) : "a"(x));
@@ -62,6 +74,7 @@ template <int OUT, bool T_F32, int PHASES>
 __global__ __launch_bounds__(256) void gemm_bf16_aligned_kernel(GemmParams p) {
     static_assert(OUT == 0 || (PHASES == 1 && !T_F32), "the storing kernel has one evaluation and no target");
     constexpr int NT = 256, BA = 4, BB = 4;
+    constexpr int W_BASE = 0, X_BASE = 3 * TILE_BYTES;       // LDS: three W stages, then two X stages (all 160 KiB)
     extern __shared__ __align__(16) char smem[];
     const int tid = threadIdx.x, lane = tid & 63;
     if (p.clk && blockIdx.x == 0 && tid == 0) { p.clk[0] = __builtin_readcyclecounter(); p.clk[1] = wall_clock64(); }
@@ -186,40 +199,36 @@ __global__ __launch_bounds__(256) void gemm_bf16_aligned_kernel(GemmParams p) {
     int aoff[4], boff[4];
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
-        aoff[kk] = TILE_BYTES + lds_off(wa * 128 + lr, kk * 2 + lh);
-        boff[kk] = lds_off(wb * 128 + lr, kk * 2 + lh);
+        aoff[kk] = W_BASE + lds_off(wa * 128 + lr, kk * 2 + lh);
+        boff[kk] = X_BASE + lds_off(wb * 128 + lr, kk * 2 + lh);
     }
     bf16x8 a[2][BA], b[2][BB];
-    auto frag1 = [&](int buf, int kk, int s, int q) __attribute__((always_inline)) {
-        const char* base = smem + buf * (2 * TILE_BYTES);
+    auto frag1 = [&](int xbuf, int wbuf, int kk, int s, int q) __attribute__((always_inline)) {
         // X fragments first: all four are needed by the first four matrix instructions of the block that uses them, a W
         // fragment only from the fourth instruction of its row on
-        if (q < 4) b[s][q] = *reinterpret_cast<const bf16x8*>(base + boff[kk] + q * 4096);
-        else a[s][q - 4] = *reinterpret_cast<const bf16x8*>(base + aoff[kk] + (q - 4) * 4096);
+        if (q < 4) b[s][q] = *reinterpret_cast<const bf16x8*>(smem + xbuf * TILE_BYTES + boff[kk] + q * 4096);
+        else a[s][q - 4] = *reinterpret_cast<const bf16x8*>(smem + wbuf * TILE_BYTES + aoff[kk] + (q - 4) * 4096);
     };
     auto mfma1 = [&](int s, int idx) __attribute__((always_inline)) {
         const int i = idx >> 2, j = idx & 3;
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[s][i], b[s][j], acc[i][j], 0, 0, 0);
     };
     // source of a pipelined slice, chosen once per slice with scalar selects (no branches at the load sites)
-    __amdgpu_buffer_rsrc_t src_rsx[2] = {rsrc(xb), rsrc(xb)}, src_rsw[2] = {rsrc(wb_), rsrc(wb_)};
-    int src_so[2] = {0, 0};
+    __amdgpu_buffer_rsrc_t src_rsx = rsrc(xb), src_rsw = rsrc(wb_);
+    int src_so = 0;
     // vector offsets of a lane's eight row groups per operand, kept in registers: worked out in front of each load they
     // put an add and its latency between a matrix instruction and the load behind it
-    int src_vxt[2][8], src_vwt[2][8];
-    auto set_offsets = [&](auto SET, int v0x, int gx, int v0w, int gw) __attribute__((always_inline)) {
-        constexpr int set = decltype(SET)::value;
+    int src_vxt[8], src_vwt[8];
+    auto set_offsets = [&](int v0x, int gx, int v0w, int gw) __attribute__((always_inline)) {
 #pragma unroll
-        for (int t = 0; t < 8; ++t) { src_vxt[set][t] = v0x + t * gx; src_vwt[set][t] = v0w + t * gw; }
+        for (int t = 0; t < 8; ++t) { src_vxt[t] = v0x + t * gx; src_vwt[t] = v0w + t * gw; }
     };
-    set_offsets(IC<0>{}, vx, gsx, vw, gsw);
-    set_offsets(IC<1>{}, vx, gsx, vw, gsw);
+    set_offsets(vx, gsx, vw, gsw);
     // kt counts from the current tile's first slice; npipe and npipe + 1 are the first two slices of the next tile.
     // Two rounds of selects, each on one condition, between values (a select between captured references becomes a
     // computed address into the closure, which then stays in memory with everything it points to; and selects on
     // mixed conditions cost four scalar instructions each instead of one)
-    auto select_slice = [&](auto SET, int kt) __attribute__((always_inline)) {
-        constexpr int set = decltype(SET)::value;
+    auto select_slice = [&](int kt) __attribute__((always_inline)) {
         // (copies first: the selects then see values, not addresses of captured variables)
         const bf16_t *cxb = xb, *cwb = wb_, *cxb2 = xb2, *cwb2 = wb2, *cxbn = xbn, *cwbn = wbn;
         const int cvx = vx, cvw = vw, cvx2 = vx2, cvw2 = vw2, cgsx = gsx, cgsw = gsw, cgs2 = gs2;
@@ -233,47 +242,45 @@ __global__ __launch_bounds__(256) void gemm_bf16_aligned_kernel(GemmParams p) {
         ws = nxt ? cwbn : ws;
         svx = nxt ? cvx : svx;   svw = nxt ? cvw : svw;   sgx = nxt ? cgsx : sgx;   sgw = nxt ? cgsw : sgw;
         so = nxt ? kt - npipe : so;
-        src_rsx[set] = rsrc(xs);   src_rsw[set] = rsrc(ws);
-        set_offsets(SET, svx, sgx, svw, sgw);
-        src_so[set] = so * (BK * 2);
+        src_rsx = rsrc(xs);   src_rsw = rsrc(ws);
+        set_offsets(svx, sgx, svw, sgw);
+        src_so = so * (BK * 2);
     };
-    // direct load q (0..15) of the selected slice into buffer buf: even q = X row group q/2, odd q = W row group
-    auto dma1 = [&](auto SET, int buf, int q) __attribute__((always_inline)) {
-        constexpr int set = decltype(SET)::value;
-        const int t = q >> 1;
-        char* dst = smem + buf * (2 * TILE_BYTES) + wave * 1024 + t * 4096 + ((q & 1) ? TILE_BYTES : 0);
-        if (q & 1) __builtin_amdgcn_raw_ptr_buffer_load_lds(src_rsw[set], (lptr_t)dst, 16, src_vwt[set][t], src_so[set], 0, 0);
-        else __builtin_amdgcn_raw_ptr_buffer_load_lds(src_rsx[set], (lptr_t)dst, 16, src_vxt[set][t], src_so[set], 0, 0);
+    // direct load of row group t (0..7) of the selected slice: X into X stage buf (0..1), W into W stage buf (0..2)
+    auto dma_x = [&](int buf, int t) __attribute__((always_inline)) {
+        char* dst = smem + X_BASE + buf * TILE_BYTES + wave * 1024 + t * 4096;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(src_rsx, (lptr_t)dst, 16, src_vxt[t], src_so, 0, 0);
+    };
+    auto dma_w = [&](int buf, int t) __attribute__((always_inline)) {
+        char* dst = smem + W_BASE + buf * TILE_BYTES + wave * 1024 + t * 4096;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(src_rsw, (lptr_t)dst, 16, src_vwt[t], src_so, 0, 0);
     };
     // 16 MFMAs of sub-step S_CUR in fixed issue order: even slots carry one fragment read each (for the next block),
-    // odd slots the direct loads D0..D1-1 of the selected slice
-    auto block = [&](auto S_CUR, int rbuf, auto RKK, auto RS, auto SET, int lbuf, auto D0, auto D1) __attribute__((always_inline)) {
+    // odd slots the eight direct loads of one operand of the selected slice (LOADS: 0 none, 1 W, 2 X)
+    auto block = [&](auto S_CUR, int rxbuf, int rwbuf, auto RKK, auto RS, auto LOADS, int lbuf) __attribute__((always_inline)) {
         constexpr int s_cur = decltype(S_CUR)::value, rkk = decltype(RKK)::value, rs = decltype(RS)::value;
-        constexpr int d0 = decltype(D0)::value, d1 = decltype(D1)::value, n = d1 - d0;
+        constexpr int loads = decltype(LOADS)::value;
 #pragma unroll
         for (int q = 0; q < 16; ++q) {
             mfma1(s_cur, q);
             const int o = q >> 1;
-            if (!(q & 1)) frag1(rbuf, rkk, rs, o);
-            else {
-#pragma unroll
-                for (int d = (o * n) / 8; d < ((o + 1) * n) / 8; ++d) dma1(SET, lbuf, d0 + d);
-            }
+            if (!(q & 1)) frag1(rxbuf, rwbuf, rkk, rs, o);
+            else if (loads == 1) dma_w(lbuf, o);
+            else if (loads == 2) dma_x(lbuf, o);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
-    constexpr int N3 = 8;      // loads of slice kt+2 issued in the last block of slice kt; the other 8 in the first of kt+1
     // a slice whose operands are complete in buffer `buf`; FIRST_READ: fragment set 0 not yet read
     auto multiply_slice = [&](int buf, bool first_read) __attribute__((always_inline)) {
         if (first_read) {
 #pragma unroll
-            for (int q = 0; q < 8; ++q) frag1(buf, 0, 0, q);
+            for (int q = 0; q < 8; ++q) frag1(buf, buf, 0, 0, q);
         }
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
             if (kk + 1 < 4) {
 #pragma unroll
-                for (int q = 0; q < 8; ++q) frag1(buf, kk + 1, (kk + 1) & 1, q);
+                for (int q = 0; q < 8; ++q) frag1(buf, buf, kk + 1, (kk + 1) & 1, q);
             }
 #pragma unroll
             for (int q = 0; q < 16; ++q) mfma1(kk & 1, q);
@@ -282,13 +289,14 @@ __global__ __launch_bounds__(256) void gemm_bf16_aligned_kernel(GemmParams p) {
 
     // ---- sum of squares of the accumulators: fp32 squares four at a time, summed in fp64; lanes, then waves, in a
     // fixed order ----
-    double* red = reinterpret_cast<double*>(smem + 4 * TILE_BYTES);
-    auto evaluate = [&](int phase, int64_t tm_, int64_t tn_) __attribute__((always_inline)) {
+    // The four waves' sums meet in LDS, in `red`: the head of a W stage that nothing reads or fills at that moment
+    // (the operand stages take all of the LDS)
+    auto evaluate = [&](int phase, int64_t tm_, int64_t tn_, double* red) __attribute__((always_inline)) {
         double part = 0.0;
-        // 16 wait states between the last matrix instruction and from_acc's first read.  (As the code stands the first
+        // 24 wait states between the last matrix instruction and from_acc's first read.  (As the code stands the first
         // block read was written 16 matrix instructions before the end of the slice loop and the last four blocks
         // written are read some 150 instructions later; this keeps the distance whatever order either side takes.)
-        if constexpr (PHASES == 1) asm volatile("s_nop 7\n\ts_nop 7");
+        if constexpr (PHASES == 1) asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7");
 #pragma clang loop unroll(full)
         for (int j = 0; j < BB; ++j)
 #pragma clang loop unroll(full)
@@ -313,6 +321,9 @@ __global__ __launch_bounds__(256) void gemm_bf16_aligned_kernel(GemmParams p) {
         if (tid == 0)
             p.partials[(int64_t)phase * p.tiles_m * p.tiles_n + tm_ * p.tiles_n + tn_] =
                 (red[phase * 4] + red[phase * 4 + 1]) + (red[phase * 4 + 2] + red[phase * 4 + 3]);
+        // (one-evaluation kernel: the next slice's loads go into this stage, and no wave may issue them before the sums
+        // have been read)
+        if constexpr (PHASES == 1) __syncthreads();
     };
 
     // accumulators <- minus the target tile (squared error) or zero (stored output)
@@ -337,49 +348,55 @@ __global__ __launch_bounds__(256) void gemm_bf16_aligned_kernel(GemmParams p) {
         }
     };
 
-    // ---- first tile: target, the first slice and the head of the second ------------------------------
+    // ---- first tile: target and the first two slices ------------------------------------------------
     request_target();
-    select_slice(IC<0>{}, 0);
+    select_slice(0);
 #pragma unroll
-    for (int q = 0; q < 16; ++q) dma1(IC<0>{}, 0, q);
-    select_slice(IC<1>{}, 1);
+    for (int t = 0; t < 8; ++t) { dma_x(0, t); dma_w(0, t); }
+    select_slice(1);
 #pragma unroll
-    for (int q = 0; q < N3; ++q) dma1(IC<1>{}, 1, q);
+    for (int t = 0; t < 8; ++t) { dma_x(1, t); dma_w(1, t); }
 
-    int g = 0;                                               // slices multiplied so far: slice g sits in LDS stage g & 1
+    int g = 0;                                   // slices multiplied so far: slice g sits in W stage g mod 3, X stage g & 1
+    int wst = 0;                                  // g mod 3
     for (int it = 0;; ++it) {
         // the accumulators are written here and nowhere else, and are dead at the end of the loop body: carried around
         // the loop they would pass through a join, which the compiler answers by spilling them
         start_tile();
         if (it == 0) {
-            __builtin_amdgcn_s_waitcnt(0x0F70 | N3);         // vmcnt(N3): slice 0 has landed
+            __builtin_amdgcn_s_waitcnt(0x4F70);              // vmcnt(16): slice 0 has landed
             __syncthreads();
 #pragma unroll
-            for (int q = 0; q < 8; ++q) frag1(0, 0, 0, q);
+            for (int q = 0; q < 8; ++q) frag1(0, 0, 0, 0, q);
         }
-        // every slice of the tile, the last one included, in LDS stage cur = g & 1: on entry fragment set 0 holds its
-        // sub-step 0 and the first N3 loads of the next slice are in flight into the other stage; the same holds for the
-        // next slice on exit
+        // every slice of the tile, the last one included, with its W in stage wst and its X in stage cur: on entry
+        // fragment set 0 holds its sub-step 0, the next slice's W has landed or is in flight and its X is in flight;
+        // the same holds for the next slice on exit
         for (int kt = 0; kt < npipe; ++kt, ++g) {
             const int cur = g & 1;
-            // while the two slices ahead are d_in slices of this tile only the K offset moves; the general choice
-            // (extension operands, next tile: some 60 scalar instructions in front of a matrix instruction, 5 % of a
-            // slice's time) is left to the last slices of a tile, behind a branch that is rarely taken
+            const int wst1 = (wst == 2) ? 0 : wst + 1, wst2 = (wst == 0) ? 2 : wst - 1;      // stages of slices g + 1, g + 2
+            // while the slice after next is a d_in slice of this tile only the K offset moves; the general choice
+            // (extension operands, next tile: some 60 scalar instructions in front of a matrix instruction) is left to
+            // the last slices of a tile, behind a branch that is rarely taken
             const bool tail = kt + 2 >= nfull;
-            if (__builtin_expect(tail, 0)) select_slice(IC<0>{}, kt + 1);
-            else src_so[0] = (kt + 1) * (BK * 2);
-            block(IC<0>{}, cur, IC<1>{}, IC<1>{}, IC<0>{}, cur ^ 1, IC<N3>{}, IC<16>{});
-            block(IC<1>{}, cur, IC<2>{}, IC<0>{}, IC<0>{}, 0, IC<0>{}, IC<0>{});
-            block(IC<0>{}, cur, IC<3>{}, IC<1>{}, IC<0>{}, 0, IC<0>{}, IC<0>{});
-            __builtin_amdgcn_s_waitcnt(0x0070);              // vmcnt(0) lgkmcnt(0): the next slice has landed
+            if (__builtin_expect(tail, 0)) select_slice(kt + 2);
+            else src_so = (kt + 2) * (BK * 2);
+            // W of slice g + 2 goes into the stage that slice g - 1 left at the previous barrier, six blocks before its
+            // first fragment is read (issued in the second block: the first still sees the X loads of the block before it)
+            block(IC<0>{}, cur, wst, IC<1>{}, IC<1>{}, IC<0>{}, 0);
+            block(IC<1>{}, cur, wst, IC<2>{}, IC<0>{}, IC<1>{}, wst2);
+            block(IC<0>{}, cur, wst, IC<3>{}, IC<1>{}, IC<0>{}, 0);
+            // vmcnt(8) lgkmcnt(0): all but the eight W loads of this slice have landed (loads return in the order
+            // issued), which is the whole of the next slice
+            __builtin_amdgcn_s_waitcnt(0x0078);
             __builtin_amdgcn_s_barrier();
             __builtin_amdgcn_sched_barrier(0);
-            if (__builtin_expect(tail, 0)) select_slice(IC<1>{}, kt + 2);
-            else src_so[1] = (kt + 2) * (BK * 2);
-            block(IC<1>{}, cur ^ 1, IC<0>{}, IC<0>{}, IC<1>{}, cur, IC<0>{}, IC<N3>{});
+            // every wave has read this slice's X: X of slice g + 2 goes into its stage, three blocks ahead
+            block(IC<1>{}, cur ^ 1, wst1, IC<0>{}, IC<0>{}, IC<2>{}, cur);
+            wst = wst1;
         }
-        // the tile's last matrix instruction has issued; stage g & 1 holds the next tile's first slice, fragment set 0 its
-        // sub-step 0, and the head of its second slice is in flight
+        // the tile's last matrix instruction has issued; the stages of slice g hold the next tile's first slice, fragment
+        // set 0 its sub-step 0, and its second slice is in flight; W stage wst - 1 is idle until the next W loads
         const bool more = it + 1 < n_tiles;
         if constexpr (OUT == 1) {
             // lane = one token, 16 consecutive outputs per block: two 16-byte stores each
@@ -405,12 +422,12 @@ __global__ __launch_bounds__(256) void gemm_bf16_aligned_kernel(GemmParams p) {
                 m0 = tm * BT; n0 = tn * BT;
                 request_target();                            // travels while the finished tile is evaluated
             }
-            evaluate(0, tm_done, tn_done);
+            evaluate(0, tm_done, tn_done, reinterpret_cast<double*>(smem + W_BASE + ((wst == 0) ? 2 : wst - 1) * TILE_BYTES));
             if (!more) break;
         } else {
-            // shared forward: one tile per workgroup.  Both LDS stages are free once the re-fetched slices have landed: the
-            // first extension slice of each perturbed evaluation is requested before the evaluation that precedes it (stage
-            // 0 for +eps, stage 1 for -2 eps); further slices (r > 16) one at a time
+            // shared forward: one tile per workgroup.  All LDS stages are free once the re-fetched slices have landed: the
+            // first extension slice of each perturbed evaluation is requested before the evaluation that precedes it (X and
+            // W stages 0 for +eps, 1 for -2 eps); further slices (r > 16) one at a time; the sums meet in W stage 2
             __builtin_amdgcn_s_waitcnt(0x0F70);
             __syncthreads();
             const __amdgpu_buffer_rsrc_t rx2 = rsrc(xb2), rw2 = rsrc(wb2), rw3 = rsrc(wb3);
@@ -418,13 +435,14 @@ __global__ __launch_bounds__(256) void gemm_bf16_aligned_kernel(GemmParams p) {
 #pragma unroll
                 for (int q = 0; q < 16; ++q) {
                     const int t = q >> 1;
-                    char* dst = smem + buf * (2 * TILE_BYTES) + wave * 1024 + t * 4096 + ((q & 1) ? TILE_BYTES : 0);
+                    char* dst = smem + buf * TILE_BYTES + wave * 1024 + t * 4096 + ((q & 1) ? W_BASE : X_BASE);
                     if (q & 1) __builtin_amdgcn_raw_ptr_buffer_load_lds(rws, (lptr_t)dst, 16, vw2 + t * gs2, e * (BK * 2), 0, 0);
                     else __builtin_amdgcn_raw_ptr_buffer_load_lds(rx2, (lptr_t)dst, 16, vx2 + t * gs2, e * (BK * 2), 0, 0);
                 }
             };
             if (next > 0) ext_dma(rw2, 0, 0);
-            evaluate(0, tm, tn);
+            double* red = reinterpret_cast<double*>(smem + W_BASE + 2 * TILE_BYTES);
+            evaluate(0, tm, tn, red);
             if (next > 0) {
                 ext_dma(rw3, 0, 1);
                 __builtin_amdgcn_s_waitcnt(0x0F70 | 16);     // the +eps slice has landed (the -2 eps one may be in flight)
@@ -438,7 +456,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_aligned_kernel(GemmParams p) {
                     multiply_slice(0, true);
                 }
             }
-            evaluate(1, tm, tn);
+            evaluate(1, tm, tn, red);
             if (next > 0) {
                 __builtin_amdgcn_s_waitcnt(0x0F70);
                 __syncthreads();
@@ -451,7 +469,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_aligned_kernel(GemmParams p) {
                     multiply_slice(1, true);
                 }
             }
-            evaluate(2, tm, tn);
+            evaluate(2, tm, tn, red);
             break;
         }
         // ---- hand the accumulators to the next tile ----
@@ -469,7 +487,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_aligned_kernel(GemmParams p) {
 template <int OUT, bool T_F32, int PHASES>
 static hipError_t launch_aligned_variant(const GemmParams& p, hipStream_t st) {
     static bool attr_set = false;
-    const int smem = 4 * TILE_BYTES + 256 * (int)sizeof(double);
+    const int smem = 5 * TILE_BYTES;           // three W stages and two X stages: all 160 KiB of a compute unit's LDS
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_bf16_aligned_kernel<OUT, T_F32, PHASES>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, smem);
