@@ -958,6 +958,10 @@ def main():
             for _ in range(6):                      # a few launches so that the clock settles (about 6 ms each)
                 tf, ghz = ctx.probe_mfma(ops, 8, 3000)
             probes[name] = {"tflops": tf, "clock_ghz": ghz}
+            if name == "randn_operands":            # the same flop count from 16x16x32 instructions
+                for _ in range(6):
+                    tf, ghz = ctx.probe_mfma(ops, 9, 3000)
+                probes["randn_operands_16x16x32"] = {"tflops": tf, "clock_ghz": ghz}
         res["roofline"]["sustained_mfma"] = dict(probes, note="register-only v_mfma_f32_32x32x16_bf16 loop, 4 waves per CU, "
                                                  "issued back to back: the rate this device holds under its power limit")
         res["roofline"]["frac_of_sustained"] = gemm_tflops / probes["randn_operands"]["tflops"]

@@ -207,7 +207,8 @@ class Context:
         return n.value, ghz.value
 
     def probe_mfma(self, operands, duty, iters):
-        """operands: 32 KiB device tensor of bf16 bit patterns.  Returns (TFLOP/s, shader clock in GHz)."""
+        """operands: 32 KiB device tensor of bf16 bit patterns; duty 1..8 of 8 groups of 32x32x16 instructions, or 9 for
+        the flop count of all 8 from 16x16x32 instructions.  Returns (TFLOP/s, shader clock in GHz)."""
         if operands.numel() * operands.element_size() < 32768 or not operands.is_contiguous():
             raise ValueError("operands must be a contiguous device tensor of at least 32 KiB")
         tf, ghz = ctypes.c_double(0.0), ctypes.c_double(0.0)

@@ -705,7 +705,7 @@ int agzo_profile_clock(agzo_ctx* ctx, int64_t* launches, double* mean_ghz) {
 int agzo_probe_mfma(agzo_ctx* ctx, const void* operands, int32_t duty, int32_t iters, double* tflops, double* clock_ghz) {
     if (!ctx) return AGZO_EINVAL;
     if (!operands || !tflops || !clock_ghz) return fail(ctx, AGZO_EINVAL, "NULL argument");
-    if (duty < 1 || duty > 8 || iters < 1 || iters > (1 << 20)) return fail(ctx, AGZO_EINVAL, "need 1 <= duty <= 8 and 1 <= iters <= 2^20");
+    if (duty < 1 || duty > 9 || iters < 1 || iters > (1 << 20)) return fail(ctx, AGZO_EINVAL, "need 1 <= duty <= 9 and 1 <= iters <= 2^20");
     double hz = 0.0;
     TRY(wall_rate(ctx, &hz));
     int dev = 0, cus = 0;
@@ -719,7 +719,8 @@ int agzo_probe_mfma(agzo_ctx* ctx, const void* operands, int32_t duty, int32_t i
     const double seconds = (double)(h[3] - h[1]) / hz;
     if (seconds <= 0.0) return fail(ctx, AGZO_EHIP, "probe returned no time");
     // 16 MFMAs of 32x32x16 per issued group, 4 waves per workgroup, one workgroup per CU
-    const double flops = 2.0 * 32 * 32 * 16 * 16.0 * duty * (double)iters * 4.0 * cus;
+    // (duty 9: the flop count of 8 groups from 256 instructions of 16x16x32)
+    const double flops = 2.0 * 32 * 32 * 16 * 16.0 * (duty == 9 ? 8 : duty) * (double)iters * 4.0 * cus;
     *tflops = flops / seconds * 1e-12;
     *clock_ghz = (double)(h[2] - h[0]) / seconds * 1e-9;
     return AGZO_OK;

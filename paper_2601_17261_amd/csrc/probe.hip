@@ -12,7 +12,8 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 // One workgroup of 4 waves per CU.  Each lane keeps four A and four B fragments (8 bf16 each) taken from `operands`
 // and sixteen 32x32 fp32 accumulators; an iteration is 8 groups of 16 MFMAs that cycle through the 16 fragment pairs.
 // DUTY of the 8 groups are issued; the others are replaced by a sleep of about the same length.  (A compile-time
-// DUTY: a run-time test per group costs about a tenth of the issue rate.)
+// DUTY: a run-time test per group costs about a tenth of the issue rate.)  DUTY = 9 issues the flop count of all 8
+// groups as 16x16x32 instructions.
 template <int DUTY>
 __global__ __launch_bounds__(256) void probe_mfma_kernel(const uint4* __restrict__ operands, int iters,
                                                           unsigned long long* clk4, float* sink) {
@@ -28,6 +29,29 @@ __global__ __launch_bounds__(256) void probe_mfma_kernel(const uint4* __restrict
         b[i] = __builtin_bit_cast(bf16x8, operands[(4 + i) * 256 + threadIdx.x]);
     }
     if (blockIdx.x == 0 && threadIdx.x == 0) { clk4[0] = __builtin_readcyclecounter(); clk4[1] = wall_clock64(); }
+    if constexpr (DUTY == 9) {
+        // the same flop count per iteration from 16x16x32 instructions: 64 accumulators of four registers (a wave's
+        // 128 x 128 tile), eight A and eight B fragments, every pair once per round, four rounds
+        typedef float floatx4 __attribute__((ext_vector_type(4)));
+        floatx4 c[64];
+#pragma unroll
+        for (int i = 0; i < 64; ++i) c[i] = floatx4{0.f, 0.f, 0.f, 0.f};
+        bf16x8 a2[8], b2[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            a2[i] = __builtin_bit_cast(bf16x8, operands[((2 * i) & 7) * 256 + threadIdx.x]);
+            b2[i] = __builtin_bit_cast(bf16x8, operands[((2 * i + 1) & 7) * 256 + threadIdx.x]);
+        }
+        for (int it = 0; it < iters; ++it) {
+#pragma unroll
+            for (int g = 0; g < 4; ++g)
+#pragma unroll
+                for (int i = 0; i < 64; ++i)
+                    c[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a2[((i >> 3) + g) & 7], b2[((i & 7) + g) & 7], c[i], 0, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < 64; ++i) acc[i & 15][i >> 4] += c[i][0] + c[i][1] + c[i][2] + c[i][3];
+    } else
     for (int it = 0; it < iters; ++it) {
 #pragma unroll
         for (int g = 0; g < 8; ++g) {
@@ -67,6 +91,7 @@ hipError_t launch_probe_mfma(const void* operands, int duty, int iters, unsigned
         case 6: hipLaunchKernelGGL(probe_mfma_kernel<6>, grid, block, 0, st, ops, iters, clk4, sink); break;
         case 7: hipLaunchKernelGGL(probe_mfma_kernel<7>, grid, block, 0, st, ops, iters, clk4, sink); break;
         case 8: hipLaunchKernelGGL(probe_mfma_kernel<8>, grid, block, 0, st, ops, iters, clk4, sink); break;
+        case 9: hipLaunchKernelGGL(probe_mfma_kernel<9>, grid, block, 0, st, ops, iters, clk4, sink); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
