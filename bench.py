@@ -309,8 +309,14 @@ def gemm_shapes(args):
         B = torch.empty(d_in, r, device="cuda")
         ctx.basis(L, X, 1, 5, None, 0, B)
         ctx.check()
+        Ys = torch.empty(N, d_out, dtype=torch.bfloat16, device="cuda")
+        Ls = binding.make_layer(W, X, r, Y=Ys)
         variants = {"base_forward_loss": lambda: ctx.layer_forward_sketch(L, W, X, None, 0, None, 1, None, loss, sc[0:1]),
-                    "perturbed_forward_loss": lambda: ctx.perturbed_forward(L, W, X, B, 5, eps, None, loss, sc[1:2])}
+                    "perturbed_forward_loss": lambda: ctx.perturbed_forward(L, W, X, B, 5, eps, None, loss, sc[1:2]),
+                    # what the vendor's GEMM below does: bf16 output stored, no loss (the kernel a layer inside a model takes)
+                    "base_forward_stores_output": lambda: ctx.layer_forward_sketch(Ls, W, X, Ys, 0, None, 1, None, None, None)}
+        if not args.store_variant:
+            del variants["base_forward_stores_output"]
         for vname, fn in variants.items():
             for _ in range(3):
                 fn()
@@ -339,7 +345,7 @@ def gemm_shapes(args):
         us = sorted(1e3 * ev[i].elapsed_time(ev[i + 1]) for i in range(args.steps))
         print(json.dumps({"shape": "%s %d->%d" % (name, d_in, d_out), "tokens": N, "variant": "library_gemm_stores_output_no_loss", "launches": args.steps,
                           "avg_us": sum(us) / len(us), "median_us": us[len(us) // 2], "tflops": 2.0 * N * d_in * d_out / (sum(us) / len(us) * 1e-6) / 1e12}), flush=True)
-        del W, T, Yl
+        del W, T, Yl, Ys
 
 
 def sketch_fusion(args):
@@ -471,6 +477,7 @@ def main():
                     help="time the range sketch as a sweep of its own against the one the forward GEMM emits, on the Qwen3-0.6B "
                          "projection shapes (use --tokens 2048)")
     ap.add_argument("--shape", choices=["q", "k", "gate", "down"], default=None, help="with --gemm-shapes: only this shape")
+    ap.add_argument("--store-variant", action="store_true", help="with --gemm-shapes: also time the forward that stores a bf16 output and has no loss")
     ap.add_argument("--no-extras", action="store_true",
                     help="only the timed workload and its stage breakdown (for counter-collection runs of the profiler)")
     ap.add_argument("--workload", choices=["qwen3-8b", "qwen3-0.6b", "mlp-stack", "decoder"], default="qwen3-8b",
