@@ -399,21 +399,33 @@ __global__ __launch_bounds__(256) void gemm_bf16_aligned_kernel(GemmParams p) {
         // set 0 its sub-step 0, and its second slice is in flight; W stage wst - 1 is idle until the next W loads
         const bool more = it + 1 < n_tiles;
         if constexpr (OUT == 1) {
-            // lane = one token, 16 consecutive outputs per block: two 16-byte stores each
+            // A lane holds 16 consecutive outputs of one token per block, so stored from the registers every store touches
+            // 32 rows (8 k cycles of the address unit per tile).  Instead each wave passes its 128 x 128 block through LDS,
+            // 32 tokens at a time, in its quarter of the W stage that is idle between two tiles: written as held (16-byte
+            // chunk c of row t at c ^ (t mod 16): the lanes of one write spread over all banks), read back 16 lanes to a
+            // 256-byte row, and stored four whole rows to an instruction.
+            char* stg = smem + W_BASE + ((wst == 0) ? 2 : wst - 1) * TILE_BYTES + wave * 8192;
 #pragma clang loop unroll(full)
             for (int j = 0; j < BB; ++j) {
-                bf16_t* yrow = reinterpret_cast<bf16_t*>(p.Y) + (m0 + wb * 128 + j * 32 + lr) * p.ldy + n0 + wa * 128 + lh * 16;
 #pragma clang loop unroll(full)
                 for (int i = 0; i < BA; ++i) {
                     const floatx16 v = acc[i][j];
                     uint32_t w[8];
 #pragma clang loop unroll(full)
                     for (int q = 0; q < 8; ++q) w[q] = pack_bf16x2(v[2 * q], v[2 * q + 1]);
-                    uint4* dst = reinterpret_cast<uint4*>(yrow + i * 32);
-                    dst[0] = make_uint4(w[0], w[1], w[2], w[3]);
-                    dst[1] = make_uint4(w[4], w[5], w[6], w[7]);
+                    const int c0 = i * 4 + lh * 2;
+                    *reinterpret_cast<uint4*>(stg + lr * 256 + ((c0 ^ (lr & 15)) << 4)) = make_uint4(w[0], w[1], w[2], w[3]);
+                    *reinterpret_cast<uint4*>(stg + lr * 256 + (((c0 + 1) ^ (lr & 15)) << 4)) = make_uint4(w[4], w[5], w[6], w[7]);
+                }
+                const int cc = lane & 15;
+#pragma clang loop unroll(full)
+                for (int n = 0; n < 8; ++n) {
+                    const int t = 4 * n + (lane >> 4);
+                    const uint4 v = *reinterpret_cast<const uint4*>(stg + t * 256 + ((cc ^ (t & 15)) << 4));
+                    *reinterpret_cast<uint4*>(reinterpret_cast<bf16_t*>(p.Y) + (m0 + wb * 128 + j * 32 + t) * p.ldy + n0 + wa * 128 + cc * 8) = v;
                 }
             }
+            __syncthreads();                                 // the next W loads go into that stage
             if (!more) break;
         } else if constexpr (PHASES == 1) {
             const int64_t tm_done = tm, tn_done = tn;
