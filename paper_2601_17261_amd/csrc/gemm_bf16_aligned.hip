@@ -291,7 +291,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_aligned_kernel(GemmParams p) {
     // fixed order ----
     // The four waves' sums meet in LDS, in `red`: the head of a W stage that nothing reads or fills at that moment
     // (the operand stages take all of the LDS)
-    auto evaluate = [&](int phase, int64_t tm_, int64_t tn_, double* red) __attribute__((always_inline)) {
+    auto eval_sum = [&]() __attribute__((always_inline)) {
         double part = 0.0;
         // 24 wait states between the last matrix instruction and from_acc's first read.  (As the code stands the first
         // block read was written 16 matrix instructions before the end of the slice loop and the last four blocks
@@ -314,6 +314,9 @@ __global__ __launch_bounds__(256) void gemm_bf16_aligned_kernel(GemmParams p) {
                     part += (double)s4;
                 }
             }
+        return part;
+    };
+    auto eval_finish = [&](double part, int phase, int64_t tm_, int64_t tn_, double* red) __attribute__((always_inline)) {
 #pragma unroll
         for (int off = 32; off > 0; off >>= 1) part += __shfl_xor(part, off);
         if (lane == 0) red[phase * 4 + wave] = part;
@@ -324,6 +327,9 @@ __global__ __launch_bounds__(256) void gemm_bf16_aligned_kernel(GemmParams p) {
         // (one-evaluation kernel: the next slice's loads go into this stage, and no wave may issue them before the sums
         // have been read)
         if constexpr (PHASES == 1) __syncthreads();
+    };
+    auto evaluate = [&](int phase, int64_t tm_, int64_t tn_, double* red) __attribute__((always_inline)) {
+        eval_finish(eval_sum(), phase, tm_, tn_, red);
     };
 
     // accumulators <- minus the target tile (squared error) or zero (stored output)
@@ -429,12 +435,20 @@ __global__ __launch_bounds__(256) void gemm_bf16_aligned_kernel(GemmParams p) {
             if (!more) break;
         } else if constexpr (PHASES == 1) {
             const int64_t tm_done = tm, tn_done = tn;
+            double part;
             if (more) {
                 tile_at(it + 1, tm, tn);
                 m0 = tm * BT; n0 = tn * BT;
-                request_target();                            // travels while the finished tile is evaluated
+                // The next tile's target is requested and the finished tile summed, in one order by two of the waves and in
+                // the other by the other two: a request keeps its wave's issue port for as long as the address unit takes
+                // over its 64 rows, and the address unit is the compute unit's one, so four waves requesting at once wait
+                // for each other while nobody sums
+                if (wave < 2) { request_target(); part = eval_sum(); }
+                else { part = eval_sum(); request_target(); }
+            } else {
+                part = eval_sum();
             }
-            evaluate(0, tm_done, tn_done, reinterpret_cast<double*>(smem + W_BASE + ((wst == 0) ? 2 : wst - 1) * TILE_BYTES));
+            eval_finish(part, 0, tm_done, tn_done, reinterpret_cast<double*>(smem + W_BASE + ((wst == 0) ? 2 : wst - 1) * TILE_BYTES));
             if (!more) break;
         } else {
             // shared forward: one tile per workgroup.  All LDS stages are free once the re-fetched slices have landed: the
