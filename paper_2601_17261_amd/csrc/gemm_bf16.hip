@@ -653,9 +653,10 @@ hipError_t launch_gemm_bf16(const GemmBf16Args& a, hipStream_t st) {
     p.Xext = nullptr; p.Wext = nullptr; p.Wext2 = nullptr; p.ext_ld = 0;
     const bool small = small_shape(a.M, a.N) && !a.large_tiles && !a.shared && p.loss_kind != AGZO_LOSS_CE;
     // the kernel of gemm_bf16_aligned.hip takes tile-aligned layers: squared error without a stored Y (also in
-    // shared-forward mode), or a stored bf16 Y without a loss
+    // shared-forward mode), the cross-entropy statistics without a stored Y, or a stored bf16 Y without a loss
     const bool aligned_shape = !small && vec && a.M % BT == 0 && a.N % BT == 0 && a.K % BK == 0 && a.K >= 2 * BK && (!a.P || a.ext_ws);
     const bool mse = aligned_shape && ((a.loss.kind == AGZO_LOSS_MSE && !a.Y) ||
+                                       (a.loss.kind == AGZO_LOSS_CE && !a.Y && !a.shared) ||
                                        (a.loss.kind == AGZO_LOSS_NONE && a.Y && a.y_dtype == AGZO_BF16 && !a.shared));
     if (a.P && a.ext_ws && (!a.shared || mse)) {
         p.ext_ld = (3 * p.rp + BK - 1) / BK * BK;

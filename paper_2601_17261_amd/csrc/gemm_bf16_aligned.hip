@@ -1,6 +1,8 @@
 // Forward GEMM for tile-aligned layers, the case the benchmark configurations run:
 //     OUT = 0:  f = sum over the tile of (X W^T (+ eps (X B) G^T) - Y*)^2     (f0, f+, f- of Sec. 4.1; Eq. 7 factored)
 //     OUT = 1:  Y = X W^T (+ eps (X B) G^T) stored as bf16                     (a layer inside a model, Alg. 2)
+//     OUT = 2:  the same logits never stored: per token and 128-column chunk their maximum and the sum of exponentials
+//               around it, and the target's logit (token cross-entropy of a model's last layer; loss.hip combines them)
 // Same tiling, tile layout in LDS and direct global -> LDS operand loads as gemm_bf16.hip (256 x 256 tile, four waves of
 // 128 x 128, v_mfma_f32_32x32x16_bf16, 64-wide K slices), but a kernel of its own with one straight path and nothing
 // else compiled in: M and N multiples of 256, d_in a multiple of 64 and at least 128, 16-byte aligned target / output
@@ -72,7 +74,7 @@ __device__ __forceinline__ float from_acc(float x) {
 
 template <int OUT, bool T_F32, int PHASES>
 __global__ __launch_bounds__(256) void gemm_bf16_aligned_kernel(GemmParams p) {
-    static_assert(OUT == 0 || (PHASES == 1 && !T_F32), "the storing kernel has one evaluation and no target");
+    static_assert(OUT == 0 || (PHASES == 1 && !T_F32), "the kernels without a squared-error target have one evaluation");
     constexpr int NT = 256, BA = 4, BB = 4;
     constexpr int W_BASE = 0, X_BASE = 3 * TILE_BYTES;       // LDS: three W stages, then two X stages (all 160 KiB)
     extern __shared__ __align__(16) char smem[];
@@ -433,6 +435,39 @@ __global__ __launch_bounds__(256) void gemm_bf16_aligned_kernel(GemmParams p) {
             }
             __syncthreads();                                 // the next W loads go into that stage
             if (!more) break;
+        } else if constexpr (OUT == 2) {
+            // a lane holds 16 of the 32 logits of each of its four blocks for four tokens; its partner lane (lane ^ 32)
+            // holds the other 16.  Online softmax over the wave's 128 columns, per token
+#pragma clang loop unroll(full)
+            for (int j = 0; j < BB; ++j) {
+                const int64_t row = m0 + wb * 128 + j * 32 + lr;
+                const int tgt = p.ce_target[row];
+                float mx = -INFINITY, tl = 0.f;
+                bool has_tl = false;
+#pragma clang loop unroll(full)
+                for (int i = 0; i < BA; ++i) {
+                    const int trel = (tgt >= 0) ? (int)((int64_t)tgt - (n0 + wa * 128 + i * 32 + lh * 16)) : -1;
+#pragma clang loop unroll(full)
+                    for (int e = 0; e < 16; ++e) {
+                        const float y = acc[i][j][e];
+                        mx = fmaxf(mx, y);
+                        if (e == trel) { tl = y; has_tl = true; }
+                    }
+                }
+                mx = fmaxf(mx, __shfl_xor(mx, 32));
+                // exp(y - mx) as 2^((y - mx) log2 e) on the hardware exponential: the difference is exact enough in fp32
+                // (one rounding), the terms that matter have small exponents, and the far tail underflows to 0
+                float sm = 0.f;
+#pragma clang loop unroll(full)
+                for (int i = 0; i < BA; ++i)
+#pragma clang loop unroll(full)
+                    for (int e = 0; e < 16; ++e) sm += __builtin_amdgcn_exp2f((acc[i][j][e] - mx) * 1.44269504088896341f);
+                sm += __shfl_xor(sm, 32);
+                const int64_t chunk = tn * 2 + wa;           // of tiles_n x 2 chunks per token
+                if (lh == 0) p.ce_ms[chunk * p.M + row] = make_float2(mx, sm);
+                if (has_tl) p.ce_tl[row] = tl;
+            }
+            if (!more) break;
         } else if constexpr (PHASES == 1) {
             const int64_t tm_done = tm, tn_done = tn;
             double part;
@@ -499,7 +534,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_aligned_kernel(GemmParams p) {
             break;
         }
         // ---- hand the accumulators to the next tile ----
-        if constexpr (OUT == 1) {
+        if constexpr (OUT != 0) {
             tile_at(it + 1, tm, tn);
             m0 = tm * BT; n0 = tn * BT;
         }
@@ -544,6 +579,10 @@ hipError_t launch_gemm_bf16_aligned(const GemmParams& p, hipStream_t st) {
     if (p.Y != nullptr) {       // stored output, no loss
         if (p.loss_kind != AGZO_LOSS_NONE || p.y_dtype != AGZO_BF16 || p.shared) return hipErrorInvalidValue;
         return launch_aligned_variant<1, false, 1>(p, st);
+    }
+    if (p.loss_kind == AGZO_LOSS_CE) {
+        if (p.shared || !p.ce_target || !p.ce_ms || !p.ce_tl) return hipErrorInvalidValue;
+        return launch_aligned_variant<2, false, 1>(p, st);
     }
     if (p.loss_kind != AGZO_LOSS_MSE || (p.shared && p.Wext2 == nullptr)) return hipErrorInvalidValue;
     const bool f32 = p.target_dtype != AGZO_BF16;

@@ -669,7 +669,9 @@ def test_step_matches_oracle(ctx, storage, n, d_in, d_out, r, kind, flags, tilin
 
 
 @pytest.mark.parametrize("storage,n,d_in,d_out,r", [("f32", 200, 96, 130, 4), ("bf16", 515, 136, 300, 8),
-                                                      ("bf16", 512, 256, 1000, 16)])
+                                                      ("bf16", 512, 256, 1000, 16),
+                                                      ("bf16", 512, 256, 768, 16),     # tile-aligned: six tiles of the persistent kernel
+                                                      ("bf16", 2304, 128, 8192, 8)])   # 288 tiles: tile lists, the shortest pipeline
 @pytest.mark.parametrize("flags", [0, binding.SHARED_FORWARD])
 def test_cross_entropy_step_matches_oracle(ctx, storage, n, d_in, d_out, r, flags):
     """Token cross-entropy on the layer's outputs as logits (LM-head shape: d_out = vocabulary), with
@@ -1019,7 +1021,7 @@ def test_misaligned_or_overlong_bf16_operands_are_rejected(ctx):
     assert torch.count_nonzero(Xw).item() == 0 and torch.count_nonzero(Ww).item() == 0
 
 
-@pytest.mark.parametrize("storage,n,d_in,d_out", [("f32", 200, 96, 130), ("bf16", 515, 136, 300)])
+@pytest.mark.parametrize("storage,n,d_in,d_out", [("f32", 200, 96, 130), ("bf16", 515, 136, 300), ("bf16", 512, 128, 512)])
 def test_cross_entropy_ids_beyond_the_outputs_are_skipped(ctx, storage, n, d_in, d_out):
     """An id >= d_out is a caller error; the kernels do not read a logit for it: the row counts as ignored."""
     W, X, _ = synth.single_layer_problem(5 + n, n, d_in, d_out, kind="lowrank", storage=storage)
