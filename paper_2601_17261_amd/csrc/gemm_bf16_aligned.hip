@@ -48,6 +48,13 @@
 
 namespace agzo {
 
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+// LDS row m' of a 64-row group of the W tile holds W row perm64(m'): block t = m' / 16 of the group, output register e
+// of lane group g = (m' / 4) mod 4 of a 16 x 16 block is row 4 g + e of the block, which this makes output column
+// 16 g + 4 t + e of the group: a lane's 4 x 4 values over four neighbouring blocks are 16 consecutive outputs.
+__device__ __forceinline__ int w_perm64(int m) { return ((m >> 2) & 3) * 16 + (m >> 4) * 4 + (m & 3); }
+
 // buffer descriptor over everything from `base` on (no range check: the kernel only takes tiles that lie inside)
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t rsrc(const bf16_t* base) {
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(base), 0, (int)0xFFFFFFFFu, 0x00020000);
@@ -82,7 +89,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_aligned_kernel(GemmParams p) {
     if (p.clk && blockIdx.x == 0 && tid == 0) { p.clk[0] = __builtin_readcyclecounter(); p.clk[1] = wall_clock64(); }
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wa = wave >> 1, wb = wave & 1;
-    const int lr = lane & 31, lh = lane >> 5;
+    const int lc = lane & 15, lg = lane >> 4;      // matrix instruction 16x16x32: column (token) / row of a fragment, k group
 
     // ---- this workgroup's tiles ---------------------------------------------------------------------
     // XCD x = id mod 8 (ids are dealt round-robin over the XCDs) owns the run of tiles [x per, (x + 1) per), walked by
@@ -133,10 +140,12 @@ __global__ __launch_bounds__(256) void gemm_bf16_aligned_kernel(GemmParams p) {
     };
     tile_sources();
     next_sources(1);
-    const int row0 = 8 * wave + (lane >> 3);                 // row of group t = row0 + 32 t (X), 32 t + w_perm(row0) (W)
+    // LDS row 32 t + row0 of a tile: X row 32 t + row0; W row 64 (t / 2) + 8 (t mod 2) + perm64(row0) (perm64 of a row 32
+    // further on is 8 more)
+    const int row0 = 8 * wave + (lane >> 3);
     const int chunk0 = (lane & 7) ^ ((row0 >> 1) & 7);       // the swizzle term does not depend on t
-    const int vx = (int)(((int64_t)row0 * p.ldx + chunk0 * 8) * 2), vw = (int)(((int64_t)w_perm(row0) * p.ldw + chunk0 * 8) * 2);
-    const int vx2 = (row0 * p.ext_ld + chunk0 * 8) * 2, vw2 = (w_perm(row0) * p.ext_ld + chunk0 * 8) * 2;
+    const int vx = (int)(((int64_t)row0 * p.ldx + chunk0 * 8) * 2), vw = (int)(((int64_t)w_perm64(row0) * p.ldw + chunk0 * 8) * 2);
+    const int vx2 = (row0 * p.ext_ld + chunk0 * 8) * 2, vw2 = (w_perm64(row0) * p.ext_ld + chunk0 * 8) * 2;
     const int gsx = (int)(64 * p.ldx), gsw = (int)(64 * p.ldw), gs2 = 64 * p.ext_ld;   // bytes between row groups
     const int nfull = (int)(p.K / BK);
     const int next = has_ext ? p.ext_ld / BK : 0;
@@ -146,74 +155,87 @@ __global__ __launch_bounds__(256) void gemm_bf16_aligned_kernel(GemmParams p) {
     typedef __attribute__((address_space(3))) void* lptr_t;
 
     // ---- accumulators <- minus the target tile ----------------------------------------------------
-    // lane = one token (row) and 16 consecutive outputs per 32 x 32 block; the raw 16-byte vectors wait in 128
-    // registers that nothing else needs before the first multiply: a whole bf16 tile, or half an fp32 one
-    floatx16 acc[BA][BB];
-    uint4 traw[2][BA][4];
-    auto tload = [&](auto J) __attribute__((always_inline)) {
-        constexpr int j = decltype(J)::value;
-        const int64_t row = m0 + wb * 128 + j * 32 + lr;
-        const int64_t colw = n0 + wa * 128 + lh * 16;
+    // 8 x 8 blocks of 16 x 16 per wave.  Lane (lc, lg) holds token 16 J + lc of token block J and, over the four output
+    // blocks 4 I4 .. 4 I4 + 3, the 16 consecutive outputs 64 I4 + 16 lg + [0, 16): value 4 t + e is register e of block
+    // 4 I4 + t.  The raw 16-byte vectors of the target wait in 128 registers that nothing else needs before the first
+    // multiply: a whole bf16 tile, or half an fp32 one (token blocks 0..3, then 4..7)
+    floatx4 acc[8][8];
+    uint4 traw[32];
+    auto tload = [&](auto JJ) __attribute__((always_inline)) {
+        constexpr int J = decltype(JJ)::value;
+        const int64_t row = m0 + wb * 128 + J * 16 + lc;
+        const int64_t colw = n0 + wa * 128 + lg * 16;
         if (T_F32) {
             const uint4* src = reinterpret_cast<const uint4*>(reinterpret_cast<const float*>(p.target) + row * p.ldt + colw);
 #pragma clang loop unroll(full)
-            for (int i = 0; i < BA; ++i)
+            for (int i4 = 0; i4 < 2; ++i4)
 #pragma clang loop unroll(full)
-                for (int q = 0; q < 4; ++q) traw[j & 1][i][q] = src[i * 8 + q];
+                for (int q = 0; q < 4; ++q) traw[(J & 3) * 8 + i4 * 4 + q] = src[i4 * 16 + q];
         } else {
             const uint4* src = reinterpret_cast<const uint4*>(reinterpret_cast<const bf16_t*>(p.target) + row * p.ldt + colw);
 #pragma clang loop unroll(full)
-            for (int i = 0; i < BA; ++i)
+            for (int i4 = 0; i4 < 2; ++i4)
 #pragma clang loop unroll(full)
-                for (int q = 0; q < 2; ++q) traw[j >> 1][i][2 * (j & 1) + q] = src[i * 4 + q];
+                for (int q = 0; q < 2; ++q) traw[J * 4 + i4 * 2 + q] = src[i4 * 8 + q];
         }
     };
-    auto tneg = [&](auto J) __attribute__((always_inline)) {
-        constexpr int j = decltype(J)::value;
+    auto tneg = [&](auto JJ) __attribute__((always_inline)) {
+        constexpr int J = decltype(JJ)::value;
 #pragma clang loop unroll(full)
-        for (int i = 0; i < BA; ++i) {
-            floatx16 v;
+        for (int i4 = 0; i4 < 2; ++i4) {
+            float v[16];
             if (T_F32) {
 #pragma clang loop unroll(full)
                 for (int q = 0; q < 4; ++q) {
-                    const uint4 t = traw[j & 1][i][q];
-                    v[4 * q] = to_acc(-__uint_as_float(t.x)); v[4 * q + 1] = to_acc(-__uint_as_float(t.y));
-                    v[4 * q + 2] = to_acc(-__uint_as_float(t.z)); v[4 * q + 3] = to_acc(-__uint_as_float(t.w));
+                    const uint4 t = traw[(J & 3) * 8 + i4 * 4 + q];
+                    v[4 * q] = -__uint_as_float(t.x); v[4 * q + 1] = -__uint_as_float(t.y);
+                    v[4 * q + 2] = -__uint_as_float(t.z); v[4 * q + 3] = -__uint_as_float(t.w);
                 }
             } else {
 #pragma clang loop unroll(full)
                 for (int q = 0; q < 2; ++q) {
-                    const uint4 t = traw[j >> 1][i][2 * (j & 1) + q];
+                    const uint4 t = traw[J * 4 + i4 * 2 + q];
                     const uint32_t w[4] = {t.x, t.y, t.z, t.w};
 #pragma clang loop unroll(full)
                     for (int u = 0; u < 4; ++u) {     // widened to fp32 with the sign flipped on the raw bits (one
                         // instruction each: adding 2^31 to the shifted word flips its top bit)
-                        v[8 * q + 2 * u] = to_acc(__uint_as_float((w[u] << 16) + 0x80000000u));
-                        v[8 * q + 2 * u + 1] = to_acc(__uint_as_float((w[u] & 0xFFFF0000u) ^ 0x80000000u));
+                        v[8 * q + 2 * u] = __uint_as_float((w[u] << 16) + 0x80000000u);
+                        v[8 * q + 2 * u + 1] = __uint_as_float((w[u] & 0xFFFF0000u) ^ 0x80000000u);
                     }
                 }
             }
-            acc[i][j] = v;
+#pragma clang loop unroll(full)
+            for (int t = 0; t < 4; ++t) {
+                floatx4 o;
+#pragma clang loop unroll(full)
+                for (int e = 0; e < 4; ++e) o[e] = to_acc(v[4 * t + e]);
+                acc[i4 * 4 + t][J] = o;
+            }
         }
     };
 
     // ---- multiply ---------------------------------------------------------------------------------
-    int aoff[4], boff[4];
+    // v_mfma_f32_16x16x32_bf16: two k steps of 32 per slice.  Fragment of block row I (W) or token block J (X), k step s:
+    // lane (lc, lg) reads 16-byte chunk 4 s + lg of tile row 16 I + lc.  (The same flop count from this instruction
+    // draws less power than from the 32x32x16 one: under the device's power limit the register-only probe holds
+    // 2.2 PFLOP/s with it against 1.9.)
+    int aoff[2], boff[2];
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-        aoff[kk] = W_BASE + lds_off(wa * 128 + lr, kk * 2 + lh);
-        boff[kk] = X_BASE + lds_off(wb * 128 + lr, kk * 2 + lh);
+    for (int ks = 0; ks < 2; ++ks) {
+        aoff[ks] = W_BASE + lds_off(wa * 128 + lc, ks * 4 + lg);
+        boff[ks] = X_BASE + lds_off(wb * 128 + lc, ks * 4 + lg);
     }
-    bf16x8 a[2][BA], b[2][BB];
-    auto frag1 = [&](int xbuf, int wbuf, int kk, int s, int q) __attribute__((always_inline)) {
-        // X fragments first: all four are needed by the first four matrix instructions of the block that uses them, a W
-        // fragment only from the fourth instruction of its row on
-        if (q < 4) b[s][q] = *reinterpret_cast<const bf16x8*>(smem + xbuf * TILE_BYTES + boff[kk] + q * 4096);
-        else a[s][q - 4] = *reinterpret_cast<const bf16x8*>(smem + wbuf * TILE_BYTES + aoff[kk] + (q - 4) * 4096);
+    bf16x8 aw[2][4], bx[8];                      // W fragments of four block rows, two sets; X fragments of the eight token blocks
+    auto read_w = [&](int wbuf, int ks, int set, int i) __attribute__((always_inline)) {      // block row 4 set + i
+        aw[set][i] = *reinterpret_cast<const bf16x8*>(smem + wbuf * TILE_BYTES + aoff[ks] + (set * 4 + i) * 2048);
     };
-    auto mfma1 = [&](int s, int idx) __attribute__((always_inline)) {
-        const int i = idx >> 2, j = idx & 3;
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[s][i], b[s][j], acc[i][j], 0, 0, 0);
+    auto read_x = [&](int xbuf, int ks, int J) __attribute__((always_inline)) {
+        bx[J] = *reinterpret_cast<const bf16x8*>(smem + xbuf * TILE_BYTES + boff[ks] + J * 2048);
+    };
+    auto mfma1 = [&](int set, int i, int J) __attribute__((always_inline)) {
+        // (written out, with the accumulator tied to one register tuple: through the builtin the compiler rotated a dozen
+        // tuples per slice through vector registers)
+        asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[set * 4 + i][J]) : "v"(aw[set][i]), "v"(bx[J]));
     };
     // source of a pipelined slice, chosen once per slice with scalar selects (no branches at the load sites)
     __amdgpu_buffer_rsrc_t src_rsx = rsrc(xb), src_rsw = rsrc(wb_);
@@ -223,7 +245,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_aligned_kernel(GemmParams p) {
     int src_vxt[8], src_vwt[8];
     auto set_offsets = [&](int v0x, int gx, int v0w, int gw) __attribute__((always_inline)) {
 #pragma unroll
-        for (int t = 0; t < 8; ++t) { src_vxt[t] = v0x + t * gx; src_vwt[t] = v0w + t * gw; }
+        for (int t = 0; t < 8; ++t) { src_vxt[t] = v0x + t * gx; src_vwt[t] = v0w + (t >> 1) * (2 * gw) + (t & 1) * (gw >> 2); }
     };
     set_offsets(vx, gsx, vw, gsw);
     // kt counts from the current tile's first slice; npipe and npipe + 1 are the first two slices of the next tile.
@@ -257,39 +279,47 @@ __global__ __launch_bounds__(256) void gemm_bf16_aligned_kernel(GemmParams p) {
         char* dst = smem + W_BASE + buf * TILE_BYTES + wave * 1024 + t * 4096;
         __builtin_amdgcn_raw_ptr_buffer_load_lds(src_rsw, (lptr_t)dst, 16, src_vwt[t], src_so, 0, 0);
     };
-    // 16 MFMAs of sub-step S_CUR in fixed issue order: even slots carry one fragment read each (for the next block),
-    // odd slots the eight direct loads of one operand of the selected slice (LOADS: 0 none, 1 W, 2 X)
-    auto block = [&](auto S_CUR, int rxbuf, int rwbuf, auto RKK, auto RS, auto LOADS, int lbuf) __attribute__((always_inline)) {
-        constexpr int s_cur = decltype(S_CUR)::value, rkk = decltype(RKK)::value, rs = decltype(RS)::value;
-        constexpr int loads = decltype(LOADS)::value;
+    // 32 MFMAs in fixed issue order: the block rows 4 SET .. 4 SET + 3 against the eight token blocks, token block by token
+    // block, with the fragments in registers.  Rides along: the W fragments of the other set for the block after this one
+    // (k step RKS of W stage rwbuf), one after the third instruction of every other token block; with REFILL, the X fragment
+    // of token block J for the next k step (RKS of X stage rxbuf) as soon as the block's last instruction on it has issued;
+    // the eight direct loads of one operand of the selected slice, one behind the first instruction of each token block
+    // (LOADS: 0 none, 1 W, 2 X)
+    auto block = [&](auto SET, auto RKS, auto REFILL, int rxbuf, int rwbuf, auto LOADS, int lbuf) __attribute__((always_inline)) {
+        constexpr int set = decltype(SET)::value, rks = decltype(RKS)::value, loads = decltype(LOADS)::value;
+        constexpr bool refill = decltype(REFILL)::value != 0;
 #pragma unroll
-        for (int q = 0; q < 16; ++q) {
-            mfma1(s_cur, q);
-            const int o = q >> 1;
-            if (!(q & 1)) frag1(rxbuf, rwbuf, rkk, rs, o);
-            else if (loads == 1) dma_w(lbuf, o);
-            else if (loads == 2) dma_x(lbuf, o);
-            __builtin_amdgcn_sched_barrier(0);
+        for (int J = 0; J < 8; ++J) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                mfma1(set, i, J);
+                if (i == 0 && loads == 1) dma_w(lbuf, J);
+                if (i == 0 && loads == 2) dma_x(lbuf, J);
+                if (i == 2 && !(J & 1)) read_w(rwbuf, rks, set ^ 1, J >> 1);
+                if (i == 3 && refill) read_x(rxbuf, rks, J);
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
     };
-    // a slice whose operands are complete in buffer `buf`; FIRST_READ: fragment set 0 not yet read
-    auto multiply_slice = [&](int buf, bool first_read) __attribute__((always_inline)) {
-        if (first_read) {
+    // a slice whose operands are complete in buffer `buf`, unpipelined
+    auto multiply_slice = [&](int buf, bool) __attribute__((always_inline)) {
 #pragma unroll
-            for (int q = 0; q < 8; ++q) frag1(buf, buf, 0, 0, q);
-        }
+        for (int ks = 0; ks < 2; ++ks) {
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            if (kk + 1 < 4) {
+            for (int J = 0; J < 8; ++J) read_x(buf, ks, J);
 #pragma unroll
-                for (int q = 0; q < 8; ++q) frag1(buf, buf, kk + 1, (kk + 1) & 1, q);
+            for (int set = 0; set < 2; ++set) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) read_w(buf, ks, set, i);
+#pragma unroll
+                for (int J = 0; J < 8; ++J)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) mfma1(set, i, J);
             }
-#pragma unroll
-            for (int q = 0; q < 16; ++q) mfma1(kk & 1, q);
         }
     };
 
-    // ---- sum of squares of the accumulators: fp32 squares four at a time, summed in fp64; lanes, then waves, in a
+    // ---- sum of squares of the accumulators    // ---- sum of squares of the accumulators: fp32 squares four at a time, summed in fp64; lanes, then waves, in a
     // fixed order ----
     // The four waves' sums meet in LDS, in `red`: the head of a W stage that nothing reads or fills at that moment
     // (the operand stages take all of the LDS)
@@ -298,23 +328,20 @@ __global__ __launch_bounds__(256) void gemm_bf16_aligned_kernel(GemmParams p) {
         // 24 wait states between the last matrix instruction and from_acc's first read.  (As the code stands the first
         // block read was written 16 matrix instructions before the end of the slice loop and the last four blocks
         // written are read some 150 instructions later; this keeps the distance whatever order either side takes.)
-        if constexpr (PHASES == 1) asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7");
+        asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7");
 #pragma clang loop unroll(full)
-        for (int j = 0; j < BB; ++j)
+        for (int J = 0; J < 8; ++J)
 #pragma clang loop unroll(full)
-            for (int i = 0; i < BA; ++i) {
-                const floatx16 v = acc[i][j];
+            for (int I = 0; I < 8; ++I) {
+                const floatx4 v = acc[I][J];
+                float s4 = 0.f;
 #pragma clang loop unroll(full)
-                for (int q = 0; q < 4; ++q) {
-                    float s4 = 0.f;
-#pragma clang loop unroll(full)
-                    for (int u = 0; u < 4; ++u) {
-                        // (the shared-forward schedule multiplies on after an evaluation and nothing else is live there)
-                        const float x = (PHASES == 1) ? from_acc(v[4 * q + u]) : v[4 * q + u];
-                        s4 = fmaf(x, x, s4);
-                    }
-                    part += (double)s4;
+                for (int u = 0; u < 4; ++u) {
+                    // (the shared-forward schedule multiplies on after an evaluation and nothing else is live there)
+                    const float x = (PHASES == 1) ? from_acc(v[u]) : v[u];
+                    s4 = fmaf(x, x, s4);
                 }
+                part += (double)s4;
             }
         return part;
     };
@@ -337,22 +364,22 @@ __global__ __launch_bounds__(256) void gemm_bf16_aligned_kernel(GemmParams p) {
     // accumulators <- minus the target tile (squared error) or zero (stored output)
     auto start_tile = [&]() __attribute__((always_inline)) {
         if constexpr (OUT == 0) {
-            tneg(IC<0>{}); tneg(IC<1>{});
-            if (T_F32) { tload(IC<2>{}); tload(IC<3>{}); }
-            tneg(IC<2>{}); tneg(IC<3>{});
+            tneg(IC<0>{}); tneg(IC<1>{}); tneg(IC<2>{}); tneg(IC<3>{});
+            if (T_F32) { tload(IC<4>{}); tload(IC<5>{}); tload(IC<6>{}); tload(IC<7>{}); }
+            tneg(IC<4>{}); tneg(IC<5>{}); tneg(IC<6>{}); tneg(IC<7>{});
         } else {
 #pragma unroll
-            for (int i = 0; i < BA; ++i)
+            for (int I = 0; I < 8; ++I)
 #pragma unroll
-                for (int j = 0; j < BB; ++j)
+                for (int J = 0; J < 8; ++J)
 #pragma unroll
-                    for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+                    for (int e = 0; e < 4; ++e) acc[I][J][e] = 0.f;
         }
     };
     auto request_target = [&]() __attribute__((always_inline)) {
         if constexpr (OUT == 0) {
-            tload(IC<0>{}); tload(IC<1>{});
-            if (!T_F32) { tload(IC<2>{}); tload(IC<3>{}); }
+            tload(IC<0>{}); tload(IC<1>{}); tload(IC<2>{}); tload(IC<3>{});
+            if (!T_F32) { tload(IC<4>{}); tload(IC<5>{}); tload(IC<6>{}); tload(IC<7>{}); }
         }
     };
 
@@ -375,11 +402,13 @@ __global__ __launch_bounds__(256) void gemm_bf16_aligned_kernel(GemmParams p) {
             __builtin_amdgcn_s_waitcnt(0x4F70);              // vmcnt(16): slice 0 has landed
             __syncthreads();
 #pragma unroll
-            for (int q = 0; q < 8; ++q) frag1(0, 0, 0, 0, q);
+            for (int J = 0; J < 8; ++J) read_x(0, 0, J);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) read_w(0, 0, 0, i);
         }
-        // every slice of the tile, the last one included, with its W in stage wst and its X in stage cur: on entry
-        // fragment set 0 holds its sub-step 0, the next slice's W has landed or is in flight and its X is in flight;
-        // the same holds for the next slice on exit
+        // every slice of the tile, the last one included, with its W in stage wst and its X in stage cur: on entry the X
+        // fragments and W fragment set 0 hold its first k step, the next slice's W has landed or is in flight and its X is
+        // in flight; the same holds for the next slice on exit
         for (int kt = 0; kt < npipe; ++kt, ++g) {
             const int cur = g & 1;
             const int wst1 = (wst == 2) ? 0 : wst + 1, wst2 = (wst == 0) ? 2 : wst - 1;      // stages of slices g + 1, g + 2
@@ -391,80 +420,93 @@ __global__ __launch_bounds__(256) void gemm_bf16_aligned_kernel(GemmParams p) {
             else src_so = (kt + 2) * (BK * 2);
             // W of slice g + 2 goes into the stage that slice g - 1 left at the previous barrier, six blocks before its
             // first fragment is read (issued in the second block: the first still sees the X loads of the block before it)
-            block(IC<0>{}, cur, wst, IC<1>{}, IC<1>{}, IC<0>{}, 0);
-            block(IC<1>{}, cur, wst, IC<2>{}, IC<0>{}, IC<1>{}, wst2);
-            block(IC<0>{}, cur, wst, IC<3>{}, IC<1>{}, IC<0>{}, 0);
+            block(IC<0>{}, IC<0>{}, IC<0>{}, cur, wst, IC<0>{}, 0);
+            block(IC<1>{}, IC<1>{}, IC<1>{}, cur, wst, IC<1>{}, wst2);
+            block(IC<0>{}, IC<1>{}, IC<0>{}, cur, wst, IC<0>{}, 0);
             // vmcnt(8) lgkmcnt(0): all but the eight W loads of this slice have landed (loads return in the order
             // issued), which is the whole of the next slice
             __builtin_amdgcn_s_waitcnt(0x0078);
             __builtin_amdgcn_s_barrier();
             __builtin_amdgcn_sched_barrier(0);
             // every wave has read this slice's X: X of slice g + 2 goes into its stage, three blocks ahead
-            block(IC<1>{}, cur ^ 1, wst1, IC<0>{}, IC<0>{}, IC<2>{}, cur);
+            block(IC<1>{}, IC<0>{}, IC<1>{}, cur ^ 1, wst1, IC<2>{}, cur);
             wst = wst1;
         }
         // the tile's last matrix instruction has issued; the stages of slice g hold the next tile's first slice, fragment
         // set 0 its sub-step 0, and its second slice is in flight; W stage wst - 1 is idle until the next W loads
         const bool more = it + 1 < n_tiles;
         if constexpr (OUT == 1) {
-            // A lane holds 16 consecutive outputs of one token per block, so stored from the registers every store touches
-            // 32 rows (8 k cycles of the address unit per tile).  Instead each wave passes its 128 x 128 block through LDS,
-            // 32 tokens at a time, in its quarter of the W stage that is idle between two tiles: written as held (16-byte
-            // chunk c of row t at c ^ (t mod 16): the lanes of one write spread over all banks), read back 16 lanes to a
-            // 256-byte row, and stored four whole rows to an instruction.
+            // A lane holds 16 consecutive outputs of one token per group of four blocks, so stored from the registers every
+            // store touches 16 rows.  Instead each wave passes its 128 x 128 block through LDS, 32 tokens at a time, in its
+            // quarter of the W stage that is idle between two tiles: written as held (16-byte chunk c of row t at
+            // c ^ (t mod 16): the lanes of one write spread over all banks), read back 16 lanes to a 256-byte row, and
+            // stored four whole rows to an instruction.
+            asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7");     // (the matrix instructions are written out: their results' wait states too)
             char* stg = smem + W_BASE + ((wst == 0) ? 2 : wst - 1) * TILE_BYTES + wave * 8192;
 #pragma clang loop unroll(full)
-            for (int j = 0; j < BB; ++j) {
+            for (int r2 = 0; r2 < 4; ++r2) {
 #pragma clang loop unroll(full)
-                for (int i = 0; i < BA; ++i) {
-                    const floatx16 v = acc[i][j];
-                    uint32_t w[8];
+                for (int jj = 0; jj < 2; ++jj) {
+                    const int J = 2 * r2 + jj, trow = jj * 16 + lc;
 #pragma clang loop unroll(full)
-                    for (int q = 0; q < 8; ++q) w[q] = pack_bf16x2(v[2 * q], v[2 * q + 1]);
-                    const int c0 = i * 4 + lh * 2;
-                    *reinterpret_cast<uint4*>(stg + lr * 256 + ((c0 ^ (lr & 15)) << 4)) = make_uint4(w[0], w[1], w[2], w[3]);
-                    *reinterpret_cast<uint4*>(stg + lr * 256 + (((c0 + 1) ^ (lr & 15)) << 4)) = make_uint4(w[4], w[5], w[6], w[7]);
+                    for (int i4 = 0; i4 < 2; ++i4) {
+                        uint32_t w[8];
+#pragma clang loop unroll(full)
+                        for (int t = 0; t < 4; ++t) {
+                            const floatx4 v = acc[i4 * 4 + t][J];
+                            w[2 * t] = pack_bf16x2(v[0], v[1]);
+                            w[2 * t + 1] = pack_bf16x2(v[2], v[3]);
+                        }
+                        const int c0 = i4 * 8 + lg * 2;
+                        *reinterpret_cast<uint4*>(stg + trow * 256 + ((c0 ^ (trow & 15)) << 4)) = make_uint4(w[0], w[1], w[2], w[3]);
+                        *reinterpret_cast<uint4*>(stg + trow * 256 + (((c0 + 1) ^ (trow & 15)) << 4)) = make_uint4(w[4], w[5], w[6], w[7]);
+                    }
                 }
                 const int cc = lane & 15;
 #pragma clang loop unroll(full)
                 for (int n = 0; n < 8; ++n) {
                     const int t = 4 * n + (lane >> 4);
                     const uint4 v = *reinterpret_cast<const uint4*>(stg + t * 256 + ((cc ^ (t & 15)) << 4));
-                    *reinterpret_cast<uint4*>(reinterpret_cast<bf16_t*>(p.Y) + (m0 + wb * 128 + j * 32 + t) * p.ldy + n0 + wa * 128 + cc * 8) = v;
+                    *reinterpret_cast<uint4*>(reinterpret_cast<bf16_t*>(p.Y) + (m0 + wb * 128 + r2 * 32 + t) * p.ldy + n0 + wa * 128 + cc * 8) = v;
                 }
             }
             __syncthreads();                                 // the next W loads go into that stage
             if (!more) break;
         } else if constexpr (OUT == 2) {
-            // a lane holds 16 of the 32 logits of each of its four blocks for four tokens; its partner lane (lane ^ 32)
-            // holds the other 16.  Online softmax over the wave's 128 columns, per token
+            // a lane holds 32 of the 128 logits of the wave's columns for each of eight tokens; the lanes lane ^ 16, ^ 32, ^ 48
+            // hold the others.  Online softmax over the wave's 128 columns, per token
+            asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7");
 #pragma clang loop unroll(full)
-            for (int j = 0; j < BB; ++j) {
-                const int64_t row = m0 + wb * 128 + j * 32 + lr;
+            for (int J = 0; J < 8; ++J) {
+                const int64_t row = m0 + wb * 128 + J * 16 + lc;
                 const int tgt = p.ce_target[row];
                 float mx = -INFINITY, tl = 0.f;
                 bool has_tl = false;
 #pragma clang loop unroll(full)
-                for (int i = 0; i < BA; ++i) {
-                    const int trel = (tgt >= 0) ? (int)((int64_t)tgt - (n0 + wa * 128 + i * 32 + lh * 16)) : -1;
+                for (int i4 = 0; i4 < 2; ++i4) {
+                    const int trel = (tgt >= 0) ? (int)((int64_t)tgt - (n0 + wa * 128 + i4 * 64 + lg * 16)) : -1;
 #pragma clang loop unroll(full)
-                    for (int e = 0; e < 16; ++e) {
-                        const float y = acc[i][j][e];
-                        mx = fmaxf(mx, y);
-                        if (e == trel) { tl = y; has_tl = true; }
-                    }
+                    for (int t = 0; t < 4; ++t)
+#pragma clang loop unroll(full)
+                        for (int e = 0; e < 4; ++e) {
+                            const float y = acc[i4 * 4 + t][J][e];
+                            mx = fmaxf(mx, y);
+                            if (4 * t + e == trel) { tl = y; has_tl = true; }
+                        }
                 }
+                mx = fmaxf(mx, __shfl_xor(mx, 16));
                 mx = fmaxf(mx, __shfl_xor(mx, 32));
                 // exp(y - mx) as 2^((y - mx) log2 e) on the hardware exponential: the difference is exact enough in fp32
                 // (one rounding), the terms that matter have small exponents, and the far tail underflows to 0
                 float sm = 0.f;
 #pragma clang loop unroll(full)
-                for (int i = 0; i < BA; ++i)
+                for (int I = 0; I < 8; ++I)
 #pragma clang loop unroll(full)
-                    for (int e = 0; e < 16; ++e) sm += __builtin_amdgcn_exp2f((acc[i][j][e] - mx) * 1.44269504088896341f);
+                    for (int e = 0; e < 4; ++e) sm += __builtin_amdgcn_exp2f((acc[I][J][e] - mx) * 1.44269504088896341f);
+                sm += __shfl_xor(sm, 16);
                 sm += __shfl_xor(sm, 32);
                 const int64_t chunk = tn * 2 + wa;           // of tiles_n x 2 chunks per token
-                if (lh == 0) p.ce_ms[chunk * p.M + row] = make_float2(mx, sm);
+                if (lg == 0) p.ce_ms[chunk * p.M + row] = make_float2(mx, sm);
                 if (has_tl) p.ce_tl[row] = tl;
             }
             if (!more) break;
@@ -497,7 +539,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_aligned_kernel(GemmParams p) {
                 for (int q = 0; q < 16; ++q) {
                     const int t = q >> 1;
                     char* dst = smem + buf * TILE_BYTES + wave * 1024 + t * 4096 + ((q & 1) ? W_BASE : X_BASE);
-                    if (q & 1) __builtin_amdgcn_raw_ptr_buffer_load_lds(rws, (lptr_t)dst, 16, vw2 + t * gs2, e * (BK * 2), 0, 0);
+                    if (q & 1) __builtin_amdgcn_raw_ptr_buffer_load_lds(rws, (lptr_t)dst, 16, vw2 + (t >> 1) * (2 * gs2) + (t & 1) * (gs2 >> 2), e * (BK * 2), 0, 0);
                     else __builtin_amdgcn_raw_ptr_buffer_load_lds(rx2, (lptr_t)dst, 16, vx2 + t * gs2, e * (BK * 2), 0, 0);
                 }
             };
