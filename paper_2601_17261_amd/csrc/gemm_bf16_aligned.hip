@@ -295,7 +295,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_aligned_kernel(GemmParams p) {
                 mfma1(set, i, J);
                 if (i == 0 && loads == 1) dma_w(lbuf, J);
                 if (i == 0 && loads == 2) dma_x(lbuf, J);
-                if (i == 2 && !(J & 1)) read_w(rwbuf, rks, set ^ 1, J >> 1);
+                if (i == 2 && J < 4) read_w(rwbuf, rks, set ^ 1, J);
                 if (i == 3 && refill) read_x(rxbuf, rks, J);
                 __builtin_amdgcn_sched_barrier(0);
             }
