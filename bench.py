@@ -969,9 +969,9 @@ def main():
                 for _ in range(6):
                     tf, ghz = ctx.probe_mfma(ops, 9, 3000)
                 probes["randn_operands_16x16x32"] = {"tflops": tf, "clock_ghz": ghz}
-        res["roofline"]["sustained_mfma"] = dict(probes, note="register-only v_mfma_f32_32x32x16_bf16 loop, 4 waves per CU, "
-                                                 "issued back to back: the rate this device holds under its power limit")
-        res["roofline"]["frac_of_sustained"] = gemm_tflops / probes["randn_operands"]["tflops"]
+        res["roofline"]["sustained_mfma"] = dict(probes, note="register-only matrix-instruction loop, 4 waves per CU, issued back to back: the rate this "
+                                                 "device holds under its power limit (v_mfma_f32_32x32x16_bf16; _16x16x32: the instruction the GEMM uses)")
+        res["roofline"]["frac_of_sustained"] = gemm_tflops / probes["randn_operands_16x16x32"]["tflops"]
     except binding.AgzoError as e:                  # a yardstick, not part of the measurement
         res["roofline"]["sustained_mfma"] = {"error": str(e)}
     if not args.no_cpu_baseline:

@@ -121,7 +121,7 @@ int agzo_profile_clock(agzo_ctx* ctx, int64_t* launches, double* mean_ghz);
  * four waves per compute unit runs `iters` iterations of 8 groups of 16 v_mfma_f32_32x32x16_bf16 on register
  * operands only (no LDS, no memory traffic inside the loop); `duty` (1..8) of every 8 groups are issued, the rest
  * replaced by a sleep of similar length; duty = 9 issues the flop count of all 8 groups as 256
- * v_mfma_f32_16x16x32_bf16 over 64 accumulators of four registers.  operands: device, 32 KiB of bf16 bit patterns, read as 8 x 256 16-byte
+ * v_mfma_f32_16x16x32_bf16 over 64 accumulators of four accumulation registers.  operands: device, 32 KiB of bf16 bit patterns, read as 8 x 256 16-byte
  * vectors (vector i*256 + t feeds lane t: i < 4 A fragments, i >= 4 B fragments); how often these bits toggle decides
  * the power drawn and with it the clock the device holds.  Synchronous: enqueues on the ctx stream, waits, and
  * returns the matrix rate over workgroup 0's lifetime in *tflops and the mean shader clock in *clock_ghz (host

@@ -47,7 +47,10 @@ __global__ __launch_bounds__(256) void probe_mfma_kernel(const uint4* __restrict
             for (int g = 0; g < 4; ++g)
 #pragma unroll
                 for (int i = 0; i < 64; ++i)
-                    c[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a2[((i >> 3) + g) & 7], b2[((i & 7) + g) & 7], c[i], 0, 0, 0);
+                    // (written out with the accumulator in the accumulation registers, as the GEMM has it: through the
+                    // builtin these accumulators land in the ordinary registers, where the instruction issues at 0.81 of
+                    // its rate)
+                    asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(c[i]) : "v"(a2[((i >> 3) + g) & 7]), "v"(b2[((i & 7) + g) & 7]));
         }
 #pragma unroll
         for (int i = 0; i < 64; ++i) acc[i & 15][i >> 4] += c[i][0] + c[i][1] + c[i][2] + c[i][3];
