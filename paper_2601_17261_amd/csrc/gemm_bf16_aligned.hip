@@ -3,15 +3,25 @@
 //     OUT = 1:  Y = X W^T (+ eps (X B) G^T) stored as bf16                     (a layer inside a model, Alg. 2)
 //     OUT = 2:  the same logits never stored: per token and 128-column chunk their maximum and the sum of exponentials
 //               around it, and the target's logit (token cross-entropy of a model's last layer; loss.hip combines them)
-// Same tiling, tile layout in LDS and direct global -> LDS operand loads as gemm_bf16.hip (256 x 256 tile, four waves of
-// 128 x 128, v_mfma_f32_32x32x16_bf16, 64-wide K slices), but a kernel of its own with one straight path and nothing
-// else compiled in: M and N multiples of 256, d_in a multiple of 64 and at least 128, 16-byte aligned target / output
-// rows, the rank-r extension as prepared operands.
+// Same tile, tile layout in LDS and direct global -> LDS operand loads as gemm_bf16.hip (256 x 256 tile, four waves of
+// 128 x 128, 64-wide K slices), but a kernel of its own with one straight path and nothing else compiled in: M and N
+// multiples of 256, d_in a multiple of 64 and at least 128, 16-byte aligned target / output rows, the rank-r extension
+// as prepared operands.
+//
+// Matrix instruction.
+// v_mfma_f32_16x16x32_bf16, 8 x 8 blocks per wave, two k steps of 32 per slice, where gemm_bf16.hip has 4 x 4 blocks of
+// v_mfma_f32_32x32x16_bf16 and four k steps.  Both give the published rate at the top clock; under the device's power
+// limit, on random operands, a register-only loop of the first holds 2.2 PFLOP/s at 2.1 GHz and one of the second
+// 1.9 at 1.8, and this kernel spends 80 - 90 % of its time in these instructions.  A slice is four blocks of 32
+// instructions (block rows 0..3 / 4..7 of k step 0, then of k step 1), each walked token block by token block with the
+// four W fragments of its block rows and the eight X fragments of the k step in registers; the W fragments of the next
+// block are read in the first half of a block, and in the second block of a k step each X fragment is replaced by the
+// next k step's as soon as its last instruction has issued.
 //
 // LDS stages.
 // A 64-wide slice is 32 KiB per operand and the compute unit has 160 KiB: three stages for W and two for X.  A stage
 // can be filled again once every wave has read its last fragment, which the one barrier of a slice establishes (after
-// the third of its four blocks of matrix instructions: fragments are read one block ahead).  With two stages per
+// the third of its four blocks of matrix instructions: fragments are read a block ahead).  With two stages per
 // operand everything for the slice after next had to be requested behind that barrier and to land before the next
 // one, the later half of it within two blocks: the barrier waited for the slowest line, 250 - 450 cycles per slice on
 // the wide layers.  With the third W stage the W half of the slice after next is requested a block before the barrier,
@@ -325,9 +335,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_aligned_kernel(GemmParams p) {
     // (the operand stages take all of the LDS)
     auto eval_sum = [&]() __attribute__((always_inline)) {
         double part = 0.0;
-        // 24 wait states between the last matrix instruction and from_acc's first read.  (As the code stands the first
-        // block read was written 16 matrix instructions before the end of the slice loop and the last four blocks
-        // written are read some 150 instructions later; this keeps the distance whatever order either side takes.)
+        // 24 wait states between the last matrix instruction and the first read of a result: the matrix instructions are
+        // written out, so the compiler does not know of them and keeps no distance itself
         asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7");
 #pragma clang loop unroll(full)
         for (int J = 0; J < 8; ++J)
